@@ -1,0 +1,61 @@
+/*
+ * slicer_ref.h -- CPU oracle of the SLICER intermediate-feature codec.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This is the slow, plain, obviously-correct
+ * statement of what the codec computes, written from the paper
+ * (arXiv 2511.11608, Sec. 3: ATKF, MS, ABQ, Eq. "dequnt").  It shares no code,
+ * header, table or constant generator with the HIP library; only tests, the
+ * smoke check and the benchmark's cpu_baseline leg may call it.
+ *
+ * All pointers are HOST pointers.  Layout of `stream` and `meta` is the wire
+ * format (version 1) described at the top of slicer_ref.c.
+ */
+#ifndef SLICER_REF_H
+#define SLICER_REF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { SLICER_REF_F32 = 0, SLICER_REF_BF16 = 1 };
+
+/* Worst-case buffer sizes (every block at max(bit_set)).  Returns 0 or <0. */
+int slicer_ref_sizes(int dtype, int64_t rows, int64_t row_len, double keep_ratio,
+                     int n_blocks, uint32_t bit_set,
+                     size_t* stream_capacity_bytes, size_t* meta_bytes);
+
+/* Encode rows*row_len elements (row-major) into stream + meta.
+ * n_threads <= 1: serial; > 1: OpenMP over rows (rows are independent).
+ * Returns 0 or <0 (invalid argument). */
+int slicer_ref_encode(const void* x, int dtype, int64_t rows, int64_t row_len,
+                      double keep_ratio, int n_blocks, uint32_t bit_set,
+                      double distortion_budget, void* stream, void* meta,
+                      int n_threads);
+
+/* Decode into dense y (same dtype and shape as the encoded tensor). */
+int slicer_ref_decode(const void* stream, const void* meta, void* y, int n_threads);
+
+/* Per-element view of ONE row, before packing (for stage-by-stage checks):
+ *   block_of[i] = -1 if element i is not transmitted, else its block number in
+ *                 [0, 2*n_blocks): positive class first, block 0 = largest
+ *                 magnitudes;
+ *   code_of[i]  = integer code of element i at its block's chosen bitwidth;
+ *   vmin/vmax/qb = per-block range and chosen bitwidth (bit 7 of qb = no
+ *                 bitwidth met the budget), arrays of 2*n_blocks;
+ *   s_int[b*17+q] = integer residual energy S_b(q) for q in 1..16 (0 if q not in
+ *                 bit_set), e_int[b] = integer block energy, e_exp[b] = exponent e.
+ * Any output pointer may be NULL. */
+int slicer_ref_analyze_row(const void* x_row, int dtype, int64_t row_len,
+                           double keep_ratio, int n_blocks, uint32_t bit_set,
+                           double distortion_budget,
+                           int32_t* block_of, uint32_t* code_of,
+                           float* vmin, float* vmax, uint8_t* qb,
+                           uint64_t* s_int, uint64_t* e_int, int32_t* e_exp);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

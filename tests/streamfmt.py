@@ -1,0 +1,68 @@
+"""Independent reader of the codec's wire format (version 1), in plain Python.
+
+Written from the format description alone; it calls neither the oracle nor the HIP
+library, so tests can use it to look inside a (stream, meta) pair produced by
+either side: kept indices per block, integer codes, block sizes, bit counts.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+MAGIC = 0x52434C53
+
+
+def header(meta: np.ndarray) -> dict:
+    m = np.ascontiguousarray(meta, np.uint8)
+    u32 = lambda o: int(m[o:o + 4].view(np.uint32)[0])
+    u64 = lambda o: int(m[o:o + 8].view(np.uint64)[0])
+    return dict(magic=u32(0), version=u32(4), dtype=u32(8), M=u32(12), rows=u64(16), row_len=u64(24),
+                k=u64(32), bit_set=u32(40), w=u32(44), total_words=u64(48), reserved=u64(56))
+
+
+def arrays(meta: np.ndarray) -> dict:
+    h = header(meta)
+    R, M = h["rows"], h["M"]
+    m = np.ascontiguousarray(meta, np.uint8)
+    o = 64
+    row_off = m[o:o + 8 * R].view(np.uint64); o += 8 * R
+    n_pos = m[o:o + 4 * R].view(np.uint32); o += 4 * R
+    n_neg = m[o:o + 4 * R].view(np.uint32); o += 4 * R
+    vmin = m[o:o + 8 * R * M].view(np.float32).reshape(R, 2 * M); o += 8 * R * M
+    vmax = m[o:o + 8 * R * M].view(np.float32).reshape(R, 2 * M); o += 8 * R * M
+    q = m[o:o + 2 * R * M].reshape(R, 2 * M); o += 2 * R * M
+    size = (o + 7) // 8 * 8
+    return dict(row_off=row_off, n_pos=n_pos, n_neg=n_neg, vmin=vmin, vmax=vmax, q=q, size=size)
+
+
+def block_sizes(n_cls: int, M: int) -> list[int]:
+    """Equal-cardinality sizes of one sign class: K, ..., K, K + remainder."""
+    K = n_cls // M
+    return [K] * (M - 1) + [n_cls - K * (M - 1)]
+
+
+def _bits(words: np.ndarray, pos: int, n: int) -> int:
+    v = 0
+    for i in range(n):
+        p = pos + i
+        v |= ((int(words[p >> 5]) >> (p & 31)) & 1) << i
+    return v
+
+
+def parse_row(stream: np.ndarray, meta: np.ndarray, r: int) -> dict:
+    """Blocks of row r: list (2M entries) of (indices, codes), plus bit accounting."""
+    h = header(meta)
+    a = arrays(meta)
+    M, w = h["M"], h["w"]
+    sizes = block_sizes(int(a["n_pos"][r]), M) + block_sizes(int(a["n_neg"][r]), M)
+    n = sum(sizes)
+    words = np.ascontiguousarray(stream, np.uint32)[int(a["row_off"][r]):]
+    ipos, cpos = 0, n * w
+    blocks = []
+    for b, cnt in enumerate(sizes):
+        q = int(a["q"][r, b]) & 0x7F
+        idx = [_bits(words, ipos + j * w, w) for j in range(cnt)]
+        cod = [_bits(words, cpos + j * q, q) for j in range(cnt)]
+        ipos += cnt * w
+        cpos += cnt * q
+        blocks.append((idx, cod))
+    return dict(blocks=blocks, sizes=sizes, bits=cpos, words=(cpos + 31) // 32)

@@ -1,0 +1,414 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix.
+
+None of these tests touches the HIP library.  They hold the oracle to:
+hand-worked examples (tests/golden), a full sort for the top-K set, closed forms
+for block sizes / packed size, an exhaustive search in true fp64 error for the ABQ
+bitwidth, the distortion bound itself, and exact special cases of the quantiser.
+"""
+import json
+import os
+
+import numpy as np
+import pytest
+
+from paper_2511_11608_amd import synth
+from tests import streamfmt
+
+GOLD = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "worked_examples.json")))
+B28 = synth.BITS_2_TO_8
+
+
+def bits_of(qs):
+    return sum(1 << q for q in qs)
+
+
+def f32(workload_or_x, dtype):
+    return workload_or_x if dtype == "f32" else synth.bf16_bits_to_f32(workload_or_x)
+
+
+# ----------------------------------------------------------------------------
+# hand-worked examples
+# ----------------------------------------------------------------------------
+
+def test_golden_select_pack(oracle):
+    g = GOLD["select_pack"]
+    x = np.array([g["x"]], np.float32)
+    bs = bits_of(g["bits"])
+    s, m = oracle.encode(x, "f32", g["keep_ratio"], g["n_blocks"], bs, g["budget"])
+    assert [int(v) for v in s] == [int(v, 16) for v in g["words"]]
+    h = streamfmt.header(m)
+    assert (h["w"], h["k"], h["total_words"]) == (g["w"], 6, 2)
+    a = oracle.analyze_row(x[0], "f32", g["keep_ratio"], g["n_blocks"], bs, g["budget"])
+    assert a["block_of"].tolist() == g["block_of"]
+    assert sorted(np.nonzero(a["block_of"] >= 0)[0].tolist()) == g["kept"]
+    assert a["qb"].tolist() == g["q"]
+    assert oracle.decode(s, m)[0].tolist() == g["decoded"]
+
+
+def test_golden_aiq_abq(oracle):
+    g = GOLD["aiq_abq"]
+    a = np.array(g["a"], np.float32)
+    for qs, want in (([2], g["codes_q2"]), ([3], g["codes_q3"])):
+        r = oracle.analyze_row(a, "f32", 1.0, 1, bits_of(qs), g["budget"])
+        assert r["code_of"].tolist() == want
+    r = oracle.analyze_row(a, "f32", 1.0, 1, bits_of(g["bits"]), g["budget"])
+    assert int(r["qb"][0]) == g["q"]
+    # the printed relative errors, from the decoded values in fp64
+    for q, want in g["rel_err"].items():
+        s, m = oracle.encode(a[None, :], "f32", 1.0, 1, 1 << int(q), g["budget"])
+        y = oracle.decode(s, m)[0].astype(np.float64)
+        rel = np.sum((a.astype(np.float64) - y) ** 2) / np.sum(a.astype(np.float64) ** 2)
+        assert rel == pytest.approx(want, rel=2e-3)
+
+
+def test_golden_grid_exact(oracle):
+    g = GOLD["grid_exact"]
+    a = np.array(g["a"], np.float32)
+    r = oracle.analyze_row(a, "f32", 1.0, 1, bits_of(g["bits"]), g["budget"])
+    assert int(r["qb"][0]) == g["q"] and r["code_of"].tolist() == g["codes"]
+    s, m = oracle.encode(a[None, :], "f32", 1.0, 1, bits_of(g["bits"]), g["budget"])
+    assert oracle.decode(s, m)[0].tolist() == g["a"]
+
+
+# ----------------------------------------------------------------------------
+# ATKF: the kept set is the head of a full sort, ties to the lower index
+# ----------------------------------------------------------------------------
+
+def topk_by_sort(xf: np.ndarray, k: int) -> np.ndarray:
+    mag = np.abs(xf.astype(np.float64))
+    order = np.lexsort((np.arange(xf.size), -mag))      # magnitude desc, index asc
+    head = order[:k]
+    return np.sort(head[xf[head] != 0])                 # exact zeros are never sent
+
+
+def rows_for_select(dtype):
+    rng = np.random.default_rng(7)
+    out = []
+    for N in (1, 2, 5, 16, 63, 64, 65, 257, 1000):
+        out.append(rng.standard_normal(N).astype(np.float32))
+        out.append((rng.integers(-4, 5, N) * 0.5).astype(np.float32))      # heavy ties and zeros
+        z = rng.standard_normal(N).astype(np.float32); z[rng.random(N) < 0.7] = 0; out.append(z)
+    if dtype == "bf16":
+        out = [synth.f32_to_bf16_bits(r) for r in out]
+    return out
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_topk_equals_full_sort(oracle, dtype):
+    for row in rows_for_select(dtype):
+        N = row.size
+        xf = f32(row, dtype)
+        for keep in (0.0, 0.1, 0.34, 0.5, 0.99, 1.0):
+            a = oracle.analyze_row(row, dtype, keep, 3, B28, 1e-3)
+            k = int(np.floor(keep * N))
+            got = np.nonzero(a["block_of"] >= 0)[0]
+            assert np.array_equal(got, topk_by_sort(xf, k)), (dtype, N, keep)
+            assert got.size == min(k, np.count_nonzero(xf))
+
+
+def test_topk_bruteforce_all_tie_patterns(oracle):
+    # every assignment of N=6 magnitudes from {0,1,2} with signs: exhaustive ties
+    import itertools
+    for vals in itertools.product((-2.0, -1.0, 0.0, 1.0, 2.0), repeat=5):
+        row = np.array(vals + (1.0,), np.float32)
+        for k in range(0, 7):
+            keep = k / 6 + 1e-9 if k < 6 else 1.0
+            a = oracle.analyze_row(row, "f32", keep, 2, B28, 1e-3)
+            assert np.array_equal(np.nonzero(a["block_of"] >= 0)[0], topk_by_sort(row, k))
+
+
+# ----------------------------------------------------------------------------
+# MS: equal cardinality, magnitude order, membership by rank
+# ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("M", [1, 2, 4, 7])
+def test_ms_blocks(oracle, dtype, M):
+    rng = np.random.default_rng(11)
+    for N in (9, 64, 300, 1025):
+        row = rng.standard_normal(N).astype(np.float32)
+        row[rng.random(N) < 0.2] = 0
+        if dtype == "bf16":
+            row = synth.f32_to_bf16_bits(row)
+        xf = f32(row, dtype)
+        for keep in (0.25, 0.8, 1.0):
+            a = oracle.analyze_row(row, dtype, keep, M, B28, 1e-3)
+            blk = a["block_of"]
+            kept = np.nonzero(blk >= 0)[0]
+            for s, sel in ((0, kept[xf[kept] > 0]), (1, kept[xf[kept] < 0])):
+                n = sel.size
+                sizes = [np.count_nonzero(blk[sel] == s * M + m) for m in range(M)]
+                assert sizes == streamfmt.block_sizes(n, M)              # closed form
+                assert np.all((blk[sel] >= s * M) & (blk[sel] < (s + 1) * M))
+                mag = np.abs(xf[sel]).astype(np.float64)
+                # membership = rank // K in the (magnitude desc, index asc) order
+                order = np.lexsort((sel, -mag))
+                K = n // M
+                want = np.minimum(np.arange(n) // K, M - 1) if K > 0 else np.full(n, M - 1)
+                assert np.array_equal(blk[sel[order]] - s * M, want)
+                # blocks are ordered by magnitude
+                for m in range(M - 1):
+                    hi, lo = mag[blk[sel] == s * M + m], mag[blk[sel] > s * M + m]
+                    if hi.size and lo.size:
+                        assert hi.min() >= lo.max()
+
+
+# ----------------------------------------------------------------------------
+# AIQ: exact special cases of the quantiser
+# ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("q", [1, 2, 5, 8, 12, 16])
+def test_aiq_endpoints_grid_and_halfstep(oracle, q):
+    rng = np.random.default_rng(q)
+    L = (1 << q) - 1
+    # (a) a block whose values sit on the 2^q-level grid of a power-of-two step is lossless
+    step = np.float32(2.0 ** -6)
+    codes = np.unique(np.concatenate(([0, L], rng.integers(0, L + 1, 40))))
+    a = (np.float32(3.0) + codes.astype(np.float32) * step * np.float32(1.0)).astype(np.float32)
+    if (L & (L + 1)) == 0 and q in (1,):       # L = 1: grid is {vmin, vmax}
+        pass
+    r = oracle.analyze_row(a, "f32", 1.0, 1, 1 << q, 0.0)
+    # range = L*step exactly, so o = step and inv = 1/step are exact
+    assert np.array_equal(r["code_of"], codes.astype(np.uint32))
+    s, m = oracle.encode(a[None, :], "f32", 1.0, 1, 1 << q, 0.0)
+    assert np.array_equal(oracle.decode(s, m)[0], a)
+    assert int(r["qb"][0]) == q                 # zero distortion: feasible, flag clear
+    # (b) generic block: min -> 0, max -> L, codes monotone, error <= half a step
+    a = np.sort(rng.uniform(0.5, 7.0, 200).astype(np.float32))
+    r = oracle.analyze_row(a, "f32", 1.0, 1, 1 << q, 1.0)
+    c = r["code_of"].astype(np.int64)
+    assert c[0] == 0 and c[-1] == L and np.all(np.diff(c) >= 0)
+    s, m = oracle.encode(a[None, :], "f32", 1.0, 1, 1 << q, 1.0)
+    y = oracle.decode(s, m)[0].astype(np.float64)
+    o = (float(a[-1]) - float(a[0])) / L
+    assert np.max(np.abs(y - a.astype(np.float64))) <= 0.5 * o * (1 + 2.0 ** -10) + 2.0 ** -20
+
+
+def test_aiq_round_half_even(oracle):
+    # positions k + 0.5 exactly: vmin=0 is impossible (zeros are not sent), use vmin=1, step 1/4
+    a = np.array([1.0, 1.125, 1.375, 1.625, 1.75], np.float32)   # q=2: L=3, inv=4: y=0,.5,1.5,2.5,3
+    r = oracle.analyze_row(a, "f32", 1.0, 1, 1 << 2, 1.0)
+    assert r["code_of"].tolist() == [0, 0, 2, 2, 3]
+
+
+def test_degenerate_blocks(oracle):
+    # all-equal block: range 0 -> smallest bitwidth, codes 0, exact reconstruction
+    a = np.full(10, 2.5, np.float32)
+    r = oracle.analyze_row(a, "f32", 1.0, 1, bits_of([3, 4]), 0.0)
+    assert int(r["qb"][0]) == 3 and not r["code_of"].any()
+    s, m = oracle.encode(a[None, :], "f32", 1.0, 1, bits_of([3, 4]), 0.0)
+    assert np.array_equal(oracle.decode(s, m)[0], a)
+    # empty class: its blocks carry q = min(bit_set), range 0
+    assert int(r["qb"][1]) == 3 and r["vmin"][1] == 0 and r["vmax"][1] == 0
+    # denormal-width block collapses to its minimum (documented reading)
+    a = np.array([1e-41, 2e-41, 3e-41], np.float32)
+    r = oracle.analyze_row(a, "f32", 1.0, 1, bits_of([2, 8]), 0.0)
+    assert int(r["qb"][0]) == 2 and not r["code_of"].any()
+
+
+# ----------------------------------------------------------------------------
+# ABQ: chosen bitwidth = exhaustive search in true fp64 error; budget is met
+# ----------------------------------------------------------------------------
+
+def per_block_true_error(oracle, row, dtype, keep, M, q, budget):
+    """Relative squared error per block, in fp64, with every block forced to q bits."""
+    s, m = oracle.encode(row[None, :], dtype, keep, M, 1 << q, budget)
+    y = f32(oracle.decode(s, m)[0], dtype).astype(np.float64)
+    a = oracle.analyze_row(row, dtype, keep, M, 1 << q, budget)
+    xf = f32(row, dtype).astype(np.float64)
+    err = np.zeros(2 * M); en = np.zeros(2 * M)
+    for b in range(2 * M):
+        sel = a["block_of"] == b
+        err[b] = np.sum((xf[sel] - y[sel]) ** 2)
+        en[b] = np.sum(xf[sel] ** 2)
+    return err, en
+
+
+@pytest.mark.parametrize("dtype,cfg", [("f32", 3), ("bf16", 4), ("f32", 2)])
+def test_abq_is_exhaustive_minimum_and_meets_budget(oracle, dtype, cfg):
+    if cfg == 3:
+        wl = synth.vit_tokens(seed=3, rows=6)
+    elif cfg == 4:
+        wl = synth.llm_prefill(seed=4, rows=4)
+    else:
+        wl = synth.resnet_stage3(seed=2, rows=1, channels=16, hw=196)
+    qs = list(range(2, 9))
+    slack = 2.0 ** -9   # integer metric vs true fp64 error (bf16 output rounding included below)
+    for r in range(wl.rows):
+        row = wl.x[r]
+        for budget in (wl.budget, 10 * wl.budget, 1e-5):
+            a = oracle.analyze_row(row, dtype, wl.keep_ratio, wl.n_blocks, wl.bit_set, budget)
+            errs = {q: per_block_true_error(oracle, row, dtype, wl.keep_ratio, wl.n_blocks, q, budget) for q in qs}
+            out_round = (2.0 ** -8) ** 2 if dtype == "bf16" else 0.0     # bf16 RNE of the output
+            for b in range(2 * wl.n_blocks):
+                if not np.any(a["block_of"] == b):
+                    assert int(a["qb"][b]) == 2
+                    continue
+                qb = int(a["qb"][b]) & 0x7F
+                flagged = bool(int(a["qb"][b]) & 0x80)
+                rel = {q: errs[q][0][b] / errs[q][1][b] for q in qs}
+                if flagged:
+                    assert qb == 8 and all(rel[q] > budget * (1 - slack) - out_round for q in qs)
+                    continue
+                assert rel[qb] <= budget * (1 + slack) + out_round, (r, b, qb, rel[qb])
+                for q in qs:
+                    if q < qb:       # every smaller bitwidth misses the budget
+                        assert rel[q] >= budget * (1 - slack) - out_round, (r, b, q, rel[q])
+
+
+def test_abq_monotone_in_budget(oracle):
+    wl = synth.vit_tokens(seed=5, rows=3)
+    for r in range(wl.rows):
+        prev = None
+        for budget in (0.0, 1e-6, 1e-4, 1e-3, 1e-2, 1e-1, 1.0):
+            q = oracle.analyze_row(wl.x[r], "f32", wl.keep_ratio, wl.n_blocks, wl.bit_set, budget)["qb"] & 0x7F
+            if prev is not None:
+                assert np.all(q <= prev)
+            prev = q
+        assert np.all(prev == 2)     # budget 1.0: the coarsest quantiser always qualifies
+
+
+def test_integer_metric_tracks_fp64_error(oracle):
+    wl = synth.llm_prefill(seed=9, rows=3)
+    for r in range(wl.rows):
+        a = oracle.analyze_row(wl.x[r], "bf16", wl.keep_ratio, wl.n_blocks, wl.bit_set, wl.budget)
+        xf = synth.bf16_bits_to_f32(wl.x[r]).astype(np.float64)
+        for b in range(2 * wl.n_blocks):
+            sel = a["block_of"] == b
+            if not sel.any():
+                continue
+            # energy grid: E * 2^(2e-40) ~ sum a^2
+            e = int(a["e_exp"][b])
+            en = float(a["e_int"][b]) * 2.0 ** (2 * e - 40)
+            assert en == pytest.approx(np.sum(xf[sel] ** 2), rel=2.0 ** -17)
+            assert e == int(np.floor(np.log2(np.abs(xf[sel]).max()))) + 1
+            # residual grid at q=4: o^2 * S / 2^30 ~ sum (a - (vmin + c*o))^2
+            q = 4
+            L = (1 << q) - 1
+            vmin, vmax = float(a["vmin"][b]), float(a["vmax"][b])
+            if vmax == vmin:
+                continue
+            o = (vmax - vmin) / L
+            mag = np.abs(xf[sel])
+            c = np.clip(np.rint((mag - vmin) / o), 0, L)
+            true = np.sum((mag - (vmin + c * o)) ** 2)
+            approx = o * o * float(a["s_int"][b, q]) / 2.0 ** 30
+            assert approx == pytest.approx(true, rel=2.0 ** -10, abs=1e-12 * en)
+
+
+# ----------------------------------------------------------------------------
+# packing: closed-form size, exclusive scan, upper bound, parse-back, decode
+# ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_pack_closed_form_and_roundtrip(oracle, cfg):
+    wl = {1: lambda: synth.cnn_map(seed=0, row_len=64 * 14 * 14),
+          2: lambda: synth.resnet_stage3(seed=0, rows=2, channels=32, hw=196),
+          3: lambda: synth.vit_tokens(seed=0, rows=24),
+          4: lambda: synth.llm_prefill(seed=0, rows=12),
+          5: lambda: synth.ar_decode_step(seed=0, step=3, rows=6)}[cfg]()
+    s, m = oracle.encode(wl.x, wl.dtype, wl.keep_ratio, wl.n_blocks, wl.bit_set, wl.budget)
+    h, a = streamfmt.header(m), streamfmt.arrays(m)
+    N, M = wl.row_len, wl.n_blocks
+    assert (h["magic"], h["version"], h["rows"], h["row_len"], h["M"]) == (streamfmt.MAGIC, 1, wl.rows, N, M)
+    assert h["dtype"] == (0 if wl.dtype == "f32" else 1) and h["bit_set"] == wl.bit_set and h["reserved"] == 0
+    assert h["k"] == int(np.floor(wl.keep_ratio * N))
+    assert h["w"] == max(1, int(np.ceil(np.log2(N)))) and m.size == a["size"]
+    sizes_cap, meta_bytes = oracle.sizes(wl.dtype, wl.rows, N, wl.keep_ratio, M, wl.bit_set)
+    assert meta_bytes == m.size and 4 * h["total_words"] <= sizes_cap
+    xf = wl.as_float32()
+    y = f32(oracle.decode(s, m), wl.dtype)
+    off = 0
+    for r in range(wl.rows):
+        p = streamfmt.parse_row(s, m, r)
+        ar = oracle.analyze_row(wl.x[r], wl.dtype, wl.keep_ratio, M, wl.bit_set, wl.budget)
+        n = int(a["n_pos"][r]) + int(a["n_neg"][r])
+        assert n == min(h["k"], np.count_nonzero(xf[r]))
+        # closed-form size: n*w + sum n_b*q_b bits, padded to a word; offsets = exclusive scan
+        bits = n * h["w"] + sum(cnt * (int(a["q"][r, b]) & 0x7F) for b, cnt in enumerate(p["sizes"]))
+        assert p["bits"] == bits and int(a["row_off"][r]) == off
+        off += (bits + 31) // 32
+        # the paper's upper bound with every block at q_bit = max(bit_set) (Sec. 3.3)
+        assert bits <= n * (h["w"] + 8)
+        for b, (idx, cod) in enumerate(p["blocks"]):
+            assert idx == sorted(idx) and len(set(idx)) == len(idx)          # CSR order
+            assert np.array_equal(np.nonzero(ar["block_of"] == b)[0], np.array(idx, np.int64))
+            assert ar["code_of"][idx].tolist() == cod
+            assert np.all((xf[r][idx] < 0) == (b >= M))                      # sign classes
+            assert np.float32(a["vmin"][r, b]) == ar["vmin"][b] and np.float32(a["vmax"][r, b]) == ar["vmax"][b]
+            if idx:
+                assert ar["vmin"][b] == np.abs(xf[r][idx]).min() and ar["vmax"][b] == np.abs(xf[r][idx]).max()
+        # decode: support = kept set, signs preserved, zeros elsewhere
+        kept = ar["block_of"] >= 0
+        assert np.array_equal(y[r] != 0, kept)
+        assert np.all(np.sign(y[r][kept]) == np.sign(xf[r][kept]))
+        # reconstruction meets the budget per block unless flagged
+        for b in range(2 * M):
+            sel = ar["block_of"] == b
+            if sel.any() and not (int(ar["qb"][b]) & 0x80):
+                e = np.sum((xf[r][sel].astype(np.float64) - y[r][sel]) ** 2)
+                en = np.sum(xf[r][sel].astype(np.float64) ** 2)
+                tol = (2.0 ** -8) ** 2 if wl.dtype == "bf16" else 0.0
+                assert e <= (wl.budget * (1 + 2.0 ** -9) + tol) * en
+    assert off == h["total_words"] == s.size
+
+
+def test_adversarial_rows_roundtrip(oracle):
+    for dtype in ("f32", "bf16"):
+        for N in (1, 7, 64, 333):
+            x = synth.adversarial_rows(dtype, N, seed=N)
+            for keep, M in ((0.0, 1), (0.3, 2), (1.0, 5)):
+                s, m = oracle.encode(x, dtype, keep, M, B28, 1e-3)
+                y = f32(oracle.decode(s, m), dtype)
+                xf = f32(x, dtype)
+                k = int(np.floor(keep * N))
+                for r in range(x.shape[0]):
+                    kept = topk_by_sort(xf[r], k)
+                    assert np.array_equal(np.nonzero(y[r])[0], kept[y[r][kept] != 0])
+                    # anything kept and decoded non-zero keeps its sign; dropped entries are zero
+                    assert np.all(np.sign(y[r][kept])[y[r][kept] != 0] == np.sign(xf[r][kept])[y[r][kept] != 0])
+                    mask = np.ones(N, bool); mask[kept] = False
+                    assert not y[r][mask].any()
+
+
+def test_threads_do_not_change_bytes(oracle):
+    wl = synth.vit_tokens(seed=1, rows=40)
+    s1, m1 = oracle.encode(wl.x, "f32", wl.keep_ratio, wl.n_blocks, wl.bit_set, wl.budget, n_threads=1)
+    s4, m4 = oracle.encode(wl.x, "f32", wl.keep_ratio, wl.n_blocks, wl.bit_set, wl.budget, n_threads=4)
+    assert np.array_equal(s1, s4) and np.array_equal(m1, m4)
+    assert np.array_equal(oracle.decode(s1, m1, 1), oracle.decode(s1, m1, 4))
+
+
+def test_rejects_bad_arguments(oracle):
+    x = np.ones((1, 8), np.float32)
+    for kw in (dict(keep_ratio=-0.1), dict(keep_ratio=1.5), dict(n_blocks=0), dict(bit_set=0),
+               dict(bit_set=1), dict(bit_set=1 << 17), dict(budget=-1.0), dict(budget=float("nan"))):
+        args = dict(keep_ratio=0.5, n_blocks=2, bit_set=B28, budget=1e-3); args.update(kw)
+        with pytest.raises(ValueError):
+            oracle.encode(x, "f32", args["keep_ratio"], args["n_blocks"], args["bit_set"], args["budget"])
+
+
+def test_decode_is_two_fp32_roundings(oracle):
+    """Eq. dequnt with the zero-point folded in: a~ = RN(vmin + RN(c * o)), o = RN(RN(vmax - vmin) / L).
+    Expected values come from fp64 arithmetic on the stored fields (exact products and sums of
+    fp32 operands fit in fp64), then one rounding to fp32 per step."""
+    wl = synth.vit_tokens(seed=21, rows=40)
+    s, m = oracle.encode(wl.x, "f32", wl.keep_ratio, wl.n_blocks, wl.bit_set, wl.budget)
+    y = oracle.decode(s, m)
+    a = streamfmt.arrays(m)
+    n_diff_fma = 0
+    for r in range(wl.rows):
+        p = streamfmt.parse_row(s, m, r)
+        for b, (idx, cod) in enumerate(p["blocks"]):
+            if not idx:
+                continue
+            L = (1 << (int(a["q"][r, b]) & 0x7F)) - 1
+            vmin, vmax = np.float64(a["vmin"][r, b]), np.float64(a["vmax"][r, b])
+            o = np.float32(np.float64(np.float32(vmax - vmin)) / L)
+            prod = np.float32(np.float64(o) * np.array(cod, np.float64))
+            want = np.float32(vmin + prod.astype(np.float64))
+            fused = np.float32(vmin + np.float64(o) * np.array(cod, np.float64))
+            n_diff_fma += int(np.count_nonzero(want != fused))
+            sign = -1.0 if b >= wl.n_blocks else 1.0
+            assert np.array_equal(y[r][idx], (sign * want).astype(np.float32))
+    assert n_diff_fma > 0      # the sample does tell a fused multiply-add apart
