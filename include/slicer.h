@@ -1,0 +1,126 @@
+/*
+ * slicer.h -- C ABI of the MI355X (gfx950) implementation of the SLICER
+ * intermediate-feature (IF) codec (arXiv 2511.11608, Sec. 3).
+ *
+ * The codec treats every row of a [rows, row_len] tensor as one instance of the
+ * paper's pipeline (the paper flattens an IF to one vector, Sec. 3.2 footnote):
+ *
+ *   ATKF  (Sec. 3.1, Eq. "split_filter", lambda = 0): keep the
+ *         k = floor(keep_ratio * row_len) entries of largest magnitude; ties at
+ *         the threshold go to the lower index; exact zeros are never sent;
+ *   MS    (Sec. 3.2): split by sign, order each sign class by magnitude, cut it
+ *         into n_blocks equal-cardinality blocks (K = floor(n / n_blocks), the
+ *         last block takes the remainder), store each block CSR-style as an
+ *         index list and a value list;
+ *   ABQ   (Sec. 3.2.1): per block, asymmetric min/max integer quantisation at the
+ *         smallest bitwidth of bit_set whose squared error stays within
+ *         distortion_budget times the block's energy;
+ *   decode (Eq. "dequnt"): scatter vmin + code * step, with the class sign, into
+ *         a zero tensor.
+ *
+ * Every pointer named x, y, stream, meta or workspace is a DEVICE pointer owned by
+ * the caller; the library neither allocates nor frees device memory, and keeps no
+ * state between calls.  Kernels are enqueued on `hip_stream` (a hipStream_t cast
+ * to void*, NULL = the default stream); unless stated otherwise a call returns
+ * without waiting for them.  Calls return SLICER_OK (0) or a negative code.
+ *
+ * Wire format, version 1, little-endian:
+ *   stream  32-bit words; row r starts at word row_word_off[r].  A row holds, for
+ *           its blocks in the order (+0..+M-1, -0..-M-1; block 0 = largest
+ *           magnitudes) and ascending index inside a block, first every index
+ *           (w = max(1, ceil(log2 row_len)) bits each), then every code (q_b bits
+ *           each), least-significant bit first, padded with zeros to a word.
+ *   meta    0 u32 magic 0x52434C53   4 u32 version   8 u32 dtype   12 u32 M
+ *           16 u64 rows   24 u64 row_len   32 u64 k   40 u32 bit_set   44 u32 w
+ *           48 u64 total_words   56 u64 0
+ *           then  u64 row_word_off[R], u32 n_pos[R], u32 n_neg[R],
+ *                 f32 vmin[R][2M], f32 vmax[R][2M], u8 q[R][2M] (bit 7: no bitwidth
+ *                 met the budget, the largest was used), padded to 8 bytes.
+ */
+#ifndef SLICER_H
+#define SLICER_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { SLICER_F32 = 0, SLICER_BF16 = 1 } slicer_dtype;
+
+enum {
+    SLICER_OK = 0,
+    SLICER_EINVAL = -1,       /* null pointer or argument out of range */
+    SLICER_EUNSUPPORTED = -2, /* unknown dtype */
+    SLICER_EHIP = -3,         /* a HIP call failed; see slicer_last_hip_error() */
+    SLICER_EFORMAT = -4       /* meta header is not a version-1 header */
+};
+
+#define SLICER_MAX_BLOCKS 64  /* n_blocks (per sign class) accepted by the library */
+
+/*
+ * Buffer sizes for one encode call (Sec. 3.3 upper bound: every block at
+ * q_bit = max(bit_set)).  Host-only, no GPU work.
+ *   stream_capacity_bytes  rows * ceil(k * (w + q_bit) / 32) * 4
+ *   meta_bytes             64 + 16 rows + 18 rows n_blocks, rounded up to 8
+ *   workspace_bytes        scratch the encoder needs (contents are undefined
+ *                          before and after a call)
+ * Any output pointer may be NULL.  Errors: SLICER_EINVAL for rows <= 0,
+ * row_len <= 0 or >= 2^31, keep_ratio outside [0,1] or NaN, n_blocks outside
+ * [1, SLICER_MAX_BLOCKS], bit_set empty or with bits outside 1..16;
+ * SLICER_EUNSUPPORTED for an unknown dtype.
+ */
+int slicer_sizes(slicer_dtype dt, int64_t rows, int64_t row_len, double keep_ratio,
+                 int n_blocks, uint32_t bit_set,
+                 size_t* stream_capacity_bytes, size_t* meta_bytes, size_t* workspace_bytes);
+
+/*
+ * Encode (Sec. 3.1-3.2.1: ATKF -> MS -> ABQ -> packing).
+ *   x          [rows][row_len], row-major contiguous, fp32 or bf16 (dt); finite values
+ *   keep_ratio 1 - s of Sec. 3.1, in [0, 1]
+ *   n_blocks   M, applied to each sign class (M(+) = M(-))
+ *   bit_set    bit q set <=> bitwidth q allowed, 1 <= q <= 16
+ *   distortion_budget  beta >= 0: per block, sum (a - a~)^2 <= beta * sum a^2
+ *   stream, meta, workspace  at least the sizes slicer_sizes reports; 256-byte aligned
+ * Asynchronous.  The number of stream words actually used is meta.total_words
+ * (slicer_stream_words).  Errors as slicer_sizes, plus SLICER_EINVAL for a null
+ * pointer or a negative / NaN budget, SLICER_EHIP if a launch fails.
+ */
+int slicer_encode(const void* x, slicer_dtype dt, int64_t rows, int64_t row_len,
+                  double keep_ratio, int n_blocks, uint32_t bit_set,
+                  double distortion_budget,
+                  void* stream, void* meta, void* workspace, void* hip_stream);
+
+/*
+ * Decode (Eq. "dequnt": de-quantise every block and scatter it into a zero
+ * tensor).  y receives [rows][row_len] in the dtype recorded in meta; every
+ * element is written.  This call first copies the 64-byte header to the host and
+ * waits for `hip_stream`, validates it (SLICER_EFORMAT), then enqueues the decode
+ * kernel.
+ */
+int slicer_decode(const void* stream, const void* meta, void* y, void* hip_stream);
+
+/*
+ * Same decode for callers that already hold the shape on the host: no header
+ * read, no wait.  dt, rows, row_len and n_blocks must be the values passed to
+ * slicer_encode; the header in meta is not consulted.
+ */
+int slicer_decode_as(const void* stream, const void* meta, void* y, slicer_dtype dt,
+                     int64_t rows, int64_t row_len, int n_blocks, void* hip_stream);
+
+/* Reads meta.total_words (the packed size of Sec. 3.3's payload, in 32-bit words)
+ * to the host.  Waits for `hip_stream`. */
+int slicer_stream_words(const void* meta, uint64_t* words, void* hip_stream);
+
+/* hipError_t of the most recent failed HIP call made by this library on the
+ * calling thread (0 if none). */
+int slicer_last_hip_error(void);
+
+/* Static, human-readable text for a return code. */
+const char* slicer_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SLICER_H */

@@ -1,0 +1,125 @@
+"""Thin Python binding of libslicer.so (include/slicer.h): argument marshalling only.
+
+Every step of the codec runs in the HIP kernels; PyTorch supplies device memory and
+the current HIP stream.  There is no CPU fallback: if the library has not been built
+(``python -m paper_2511_11608_amd.build``) loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libslicer.so")
+
+SLICER_F32, SLICER_BF16 = 0, 1
+_TORCH_DT = {torch.float32: SLICER_F32, torch.bfloat16: SLICER_BF16}
+
+_lib = None
+
+
+class SlicerError(RuntimeError):
+    def __init__(self, fn: str, code: int):
+        L = load()
+        msg = L.slicer_strerror(code).decode()
+        extra = f" (hipError {L.slicer_last_hip_error()})" if code == -3 else ""
+        super().__init__(f"{fn}: {msg}{extra} [{code}]")
+        self.code = code
+
+
+def load() -> C.CDLL:
+    """Load libslicer.so; fails loudly when it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2511_11608_amd.build`")
+        L = C.CDLL(LIB_PATH)
+        vp, i64, dbl, u32, cint = C.c_void_p, C.c_int64, C.c_double, C.c_uint32, C.c_int
+        szp = C.POINTER(C.c_size_t)
+        L.slicer_sizes.restype = cint
+        L.slicer_sizes.argtypes = [cint, i64, i64, dbl, cint, u32, szp, szp, szp]
+        L.slicer_encode.restype = cint
+        L.slicer_encode.argtypes = [vp, cint, i64, i64, dbl, cint, u32, dbl, vp, vp, vp, vp]
+        L.slicer_decode.restype = cint
+        L.slicer_decode.argtypes = [vp, vp, vp, vp]
+        L.slicer_decode_as.restype = cint
+        L.slicer_decode_as.argtypes = [vp, vp, vp, cint, i64, i64, cint, vp]
+        L.slicer_stream_words.restype = cint
+        L.slicer_stream_words.argtypes = [vp, C.POINTER(C.c_uint64), vp]
+        L.slicer_last_hip_error.restype = cint
+        L.slicer_last_hip_error.argtypes = []
+        L.slicer_strerror.restype = C.c_char_p
+        L.slicer_strerror.argtypes = [cint]
+        _lib = L
+    return _lib
+
+
+def _check(fn: str, rc: int) -> None:
+    if rc != 0:
+        raise SlicerError(fn, rc)
+
+
+def _stream_handle(stream) -> int:
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return s.cuda_stream
+
+
+def _dt_of(x: torch.Tensor) -> int:
+    if x.dtype not in _TORCH_DT:
+        raise TypeError(f"unsupported tensor dtype {x.dtype}")
+    return _TORCH_DT[x.dtype]
+
+
+def slicer_sizes(dt: int, rows: int, row_len: int, keep_ratio: float, n_blocks: int, bit_set: int):
+    """(stream_capacity_bytes, meta_bytes, workspace_bytes) for one encode call."""
+    a, b, c = C.c_size_t(0), C.c_size_t(0), C.c_size_t(0)
+    _check("slicer_sizes", load().slicer_sizes(dt, rows, row_len, keep_ratio, n_blocks, bit_set,
+                                               C.byref(a), C.byref(b), C.byref(c)))
+    return a.value, b.value, c.value
+
+
+def alloc_buffers(x: torch.Tensor, keep_ratio: float, n_blocks: int, bit_set: int):
+    """Device buffers (stream int32, meta uint8, workspace uint8) sized for x [rows,row_len]."""
+    rows, row_len = x.shape
+    cap, mb, wb = slicer_sizes(_dt_of(x), rows, row_len, keep_ratio, n_blocks, bit_set)
+    dev = x.device
+    return (torch.empty(max(cap // 4, 1), dtype=torch.int32, device=dev),
+            torch.empty(mb, dtype=torch.uint8, device=dev),
+            torch.empty(max(wb, 256), dtype=torch.uint8, device=dev))
+
+
+def slicer_encode(x: torch.Tensor, keep_ratio: float, n_blocks: int, bit_set: int, distortion_budget: float,
+                  stream_buf: torch.Tensor, meta: torch.Tensor, workspace: torch.Tensor, stream=None) -> None:
+    """Enqueue the encode of x [rows,row_len] (fp32 or bf16, contiguous, on the GPU)."""
+    if not x.is_cuda or not x.is_contiguous() or x.dim() != 2:
+        raise ValueError("x must be a contiguous 2-D tensor on the GPU")
+    rows, row_len = x.shape
+    _check("slicer_encode", load().slicer_encode(
+        x.data_ptr(), _dt_of(x), rows, row_len, keep_ratio, n_blocks, bit_set, distortion_budget,
+        stream_buf.data_ptr(), meta.data_ptr(), workspace.data_ptr(), _stream_handle(stream)))
+
+
+def slicer_decode(stream_buf: torch.Tensor, meta: torch.Tensor, y: torch.Tensor, stream=None) -> None:
+    """Decode into y using the header stored in meta (reads it to the host, waits for the stream)."""
+    _check("slicer_decode", load().slicer_decode(stream_buf.data_ptr(), meta.data_ptr(), y.data_ptr(),
+                                                 _stream_handle(stream)))
+
+
+def slicer_decode_as(stream_buf: torch.Tensor, meta: torch.Tensor, y: torch.Tensor, n_blocks: int,
+                     stream=None) -> None:
+    """Decode into y [rows,row_len] with the shape taken from y; asynchronous."""
+    if not y.is_cuda or not y.is_contiguous() or y.dim() != 2:
+        raise ValueError("y must be a contiguous 2-D tensor on the GPU")
+    rows, row_len = y.shape
+    _check("slicer_decode_as", load().slicer_decode_as(stream_buf.data_ptr(), meta.data_ptr(), y.data_ptr(),
+                                                       _dt_of(y), rows, row_len, n_blocks,
+                                                       _stream_handle(stream)))
+
+
+def slicer_stream_words(meta: torch.Tensor, stream=None) -> int:
+    """Number of 32-bit stream words the last encode into `meta` produced (waits for the stream)."""
+    w = C.c_uint64(0)
+    _check("slicer_stream_words", load().slicer_stream_words(meta.data_ptr(), C.byref(w), _stream_handle(stream)))
+    return w.value

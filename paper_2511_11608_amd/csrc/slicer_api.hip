@@ -1,0 +1,241 @@
+// C ABI of the SLICER IF codec for MI355X (see include/slicer.h): argument
+// checks, workspace carving and kernel launches.  No device memory is allocated.
+#include "../../include/slicer.h"
+
+#include <hip/hip_runtime.h>
+#include <cmath>
+
+#include "slicer_common.hpp"
+#include "slicer_encode_generic.hpp"
+#include "slicer_decode.hpp"
+
+using namespace slicer;
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+inline int hip_fail(hipError_t e)
+{
+    g_last_hip_error = (int)e;
+    return SLICER_EHIP;
+}
+
+#define SLICER_HIP(call)                                   \
+    do {                                                   \
+        hipError_t e_ = (call);                            \
+        if (e_ != hipSuccess) return hip_fail(e_);         \
+    } while (0)
+
+int check_shape(int dt, int64_t rows, int64_t row_len, int n_blocks)
+{
+    if (dt != SLICER_F32 && dt != SLICER_BF16) return SLICER_EUNSUPPORTED;
+    if (rows <= 0 || row_len <= 0 || row_len >= ((int64_t)1 << 31)) return SLICER_EINVAL;
+    if (n_blocks < 1 || n_blocks > SLICER_MAX_BLOCKS) return SLICER_EINVAL;
+    return SLICER_OK;
+}
+
+int check_args(int dt, int64_t rows, int64_t row_len, double keep_ratio, int n_blocks, uint32_t bit_set)
+{
+    int rc = check_shape(dt, rows, row_len, n_blocks);
+    if (rc) return rc;
+    if (!(keep_ratio >= 0.0 && keep_ratio <= 1.0)) return SLICER_EINVAL;
+    if (bit_set == 0 || (bit_set & ~0x1FFFEu)) return SLICER_EINVAL;
+    return SLICER_OK;
+}
+
+int index_bits(int64_t N)
+{
+    int w = 1;
+    while (((int64_t)1 << w) < N) ++w;
+    return w;
+}
+
+struct Plan {
+    int64_t k;
+    int w, qmax;
+    u64 cap_words;          // per row
+    size_t off_row_words, off_slots, off_kept, off_bo_idx, off_bo_val, total;
+};
+
+inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+Plan make_plan(int64_t rows, int64_t row_len, double keep_ratio, uint32_t bit_set)
+{
+    Plan p;
+    p.k = (int64_t)std::floor(keep_ratio * (double)row_len);   // ATKF: k = floor((1-s) N)
+    p.w = index_bits(row_len);
+    p.qmax = 16;
+    while (!((bit_set >> p.qmax) & 1u)) --p.qmax;
+    p.cap_words = ((u64)p.k * (u64)(p.w + p.qmax) + 31) / 32;
+    size_t o = 0;
+    p.off_row_words = o; o = align256(o + 8 * (size_t)rows);
+    p.off_slots = o;     o = align256(o + 4 * (size_t)rows * (size_t)p.cap_words);
+    p.off_kept = o;      o = align256(o + 8 * (size_t)rows * (size_t)p.k);
+    p.off_bo_idx = o;    o = align256(o + 4 * (size_t)rows * (size_t)p.k);
+    p.off_bo_val = o;    o = align256(o + 4 * (size_t)rows * (size_t)p.k);
+    p.total = o ? o : 256;
+    return p;
+}
+
+template <int DT>
+int launch_encode(const EncArgs& ea, hipStream_t st)
+{
+    if (ea.N >= 32768)
+        hipLaunchKernelGGL((enc_generic_kernel<DT, 1024>), dim3((unsigned)ea.R), dim3(1024), 0, st, ea);
+    else
+        hipLaunchKernelGGL((enc_generic_kernel<DT, 256>), dim3((unsigned)ea.R), dim3(256), 0, st, ea);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? SLICER_OK : hip_fail(e);
+}
+
+int launch_decode(const void* stream, const void* meta, void* y, int dt, int64_t rows, int64_t row_len,
+                  int n_blocks, hipStream_t st)
+{
+    DecArgs da;
+    da.stream = (const u32*)stream;
+    da.y = y;
+    da.R = rows; da.N = row_len; da.M = n_blocks; da.w = index_bits(row_len);
+    da.chunks_per_row = (int)((row_len + kDecChunk - 1) / kDecChunk);
+    da.mv = meta_view(const_cast<void*>(meta), rows, n_blocks);
+    const u64 grid = (u64)rows * (u64)da.chunks_per_row;
+    if (grid >= (1ull << 31)) return SLICER_EINVAL;
+    if (dt == SLICER_F32)
+        hipLaunchKernelGGL((dec_kernel<0, 256>), dim3((unsigned)grid), dim3(256), 0, st, da);
+    else
+        hipLaunchKernelGGL((dec_kernel<1, 256>), dim3((unsigned)grid), dim3(256), 0, st, da);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? SLICER_OK : hip_fail(e);
+}
+
+}  // namespace
+
+extern "C" {
+
+int slicer_sizes(slicer_dtype dt, int64_t rows, int64_t row_len, double keep_ratio, int n_blocks,
+                 uint32_t bit_set, size_t* stream_capacity_bytes, size_t* meta_bytes_out,
+                 size_t* workspace_bytes)
+{
+    int rc = check_args((int)dt, rows, row_len, keep_ratio, n_blocks, bit_set);
+    if (rc) return rc;
+    Plan p = make_plan(rows, row_len, keep_ratio, bit_set);
+    if (stream_capacity_bytes) *stream_capacity_bytes = (size_t)(p.cap_words * 4ull * (u64)rows);
+    if (meta_bytes_out) *meta_bytes_out = meta_bytes(rows, n_blocks);
+    if (workspace_bytes) *workspace_bytes = p.total;
+    return SLICER_OK;
+}
+
+int slicer_encode(const void* x, slicer_dtype dt, int64_t rows, int64_t row_len, double keep_ratio,
+                  int n_blocks, uint32_t bit_set, double distortion_budget, void* stream, void* meta,
+                  void* workspace, void* hip_stream)
+{
+    int rc = check_args((int)dt, rows, row_len, keep_ratio, n_blocks, bit_set);
+    if (rc) return rc;
+    if (!x || !stream || !meta || !workspace) return SLICER_EINVAL;
+    if (!(distortion_budget >= 0.0)) return SLICER_EINVAL;
+    if (rows >= ((int64_t)1 << 31)) return SLICER_EINVAL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    Plan p = make_plan(rows, row_len, keep_ratio, bit_set);
+    char* ws = (char*)workspace;
+
+    EncArgs ea;
+    ea.x = x;
+    ea.R = rows; ea.N = row_len; ea.k = p.k;
+    ea.M = n_blocks; ea.w = p.w;
+    ea.nq = 0;
+    for (int q = 1; q <= 16; ++q)
+        if ((bit_set >> q) & 1u) ea.qlist[ea.nq++] = q;
+    for (int t = ea.nq; t < kMaxQ; ++t) ea.qlist[t] = 0;
+    ea.beta = distortion_budget;
+    ea.cap_words = p.cap_words;
+    ea.row_words = (u64*)(ws + p.off_row_words);
+    ea.slots = (u32*)(ws + p.off_slots);
+    ea.kept = (u64*)(ws + p.off_kept);
+    ea.bo_idx = (u32*)(ws + p.off_bo_idx);
+    ea.bo_val = (u32*)(ws + p.off_bo_val);
+    ea.mv = meta_view(meta, rows, n_blocks);
+
+    rc = dt == SLICER_F32 ? launch_encode<0>(ea, st) : launch_encode<1>(ea, st);
+    if (rc) return rc;
+
+    FinishArgs fa;
+    fa.R = rows; fa.N = row_len; fa.k = p.k;
+    fa.M = n_blocks; fa.w = p.w; fa.dt = (int)dt;
+    fa.bit_set = bit_set;
+    fa.row_words = ea.row_words;
+    fa.meta = meta;
+    fa.mv = ea.mv;
+    hipLaunchKernelGGL((enc_offsets_kernel<1024>), dim3(1), dim3(1024), 0, st, fa);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e);
+
+    if (p.cap_words > 0) {
+        const int chunks = (int)((p.cap_words + 4095) / 4096);
+        const u64 grid = (u64)rows * (u64)chunks;
+        if (grid >= (1ull << 31)) return SLICER_EINVAL;
+        hipLaunchKernelGGL(enc_compact_kernel, dim3((unsigned)grid), dim3(256), 0, st, ea.slots, p.cap_words,
+                           ea.row_words, ea.mv.row_off, (u32*)stream, chunks);
+        e = hipGetLastError();
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    return SLICER_OK;
+}
+
+int slicer_decode_as(const void* stream, const void* meta, void* y, slicer_dtype dt, int64_t rows,
+                     int64_t row_len, int n_blocks, void* hip_stream)
+{
+    int rc = check_shape((int)dt, rows, row_len, n_blocks);
+    if (rc) return rc;
+    if (!stream || !meta || !y) return SLICER_EINVAL;
+    return launch_decode(stream, meta, y, (int)dt, rows, row_len, n_blocks, (hipStream_t)hip_stream);
+}
+
+static int read_header(const void* meta, hipStream_t st, uint32_t* h32)
+{
+    SLICER_HIP(hipMemcpyAsync(h32, meta, kHeaderBytes, hipMemcpyDeviceToHost, st));
+    SLICER_HIP(hipStreamSynchronize(st));
+    if (h32[0] != kMagic || h32[1] != kVersion) return SLICER_EFORMAT;
+    return SLICER_OK;
+}
+
+int slicer_decode(const void* stream, const void* meta, void* y, void* hip_stream)
+{
+    if (!stream || !meta || !y) return SLICER_EINVAL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    alignas(8) uint32_t h32[kHeaderBytes / 4];
+    int rc = read_header(meta, st, h32);
+    if (rc) return rc;
+    const uint64_t* h64 = (const uint64_t*)h32;
+    const int dt = (int)h32[2], M = (int)h32[3];
+    const int64_t rows = (int64_t)h64[2], row_len = (int64_t)h64[3];
+    rc = check_shape(dt, rows, row_len, M);
+    if (rc) return SLICER_EFORMAT;
+    if ((int)h32[11] != index_bits(row_len)) return SLICER_EFORMAT;
+    return launch_decode(stream, meta, y, dt, rows, row_len, M, st);
+}
+
+int slicer_stream_words(const void* meta, uint64_t* words, void* hip_stream)
+{
+    if (!meta || !words) return SLICER_EINVAL;
+    alignas(8) uint32_t h32[kHeaderBytes / 4];
+    int rc = read_header(meta, (hipStream_t)hip_stream, h32);
+    if (rc) return rc;
+    *words = ((const uint64_t*)h32)[6];
+    return SLICER_OK;
+}
+
+int slicer_last_hip_error(void) { return g_last_hip_error; }
+
+const char* slicer_strerror(int code)
+{
+    switch (code) {
+        case SLICER_OK: return "ok";
+        case SLICER_EINVAL: return "invalid argument";
+        case SLICER_EUNSUPPORTED: return "unsupported dtype";
+        case SLICER_EHIP: return "HIP call failed (see slicer_last_hip_error)";
+        case SLICER_EFORMAT: return "meta header is not a version-1 SLICER header";
+        default: return "unknown error";
+    }
+}
+
+}  // extern "C"

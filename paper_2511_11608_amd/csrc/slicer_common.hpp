@@ -1,0 +1,165 @@
+// Device-side helpers shared by the encode and decode kernels (gfx950, wave64).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace slicer {
+
+typedef unsigned long long u64;
+typedef uint32_t u32;
+
+constexpr int kWave = 64;
+constexpr u32 kMagic = 0x52434C53u;
+constexpr u32 kVersion = 1u;
+constexpr int kHeaderBytes = 64;
+constexpr int kMaxBlocks = 64;          // per sign class
+constexpr int kMaxB2 = 2 * kMaxBlocks;  // blocks per row
+constexpr int kMaxQ = 16;
+
+// ---- meta layout ---------------------------------------------------------
+
+struct MetaView {
+    u64* row_off;
+    u32* n_pos;
+    u32* n_neg;
+    float* vmin;
+    float* vmax;
+    uint8_t* q;
+};
+
+__host__ __device__ inline size_t meta_bytes(int64_t R, int M)
+{
+    size_t s = kHeaderBytes + 16 * (size_t)R + 18 * (size_t)R * (size_t)M;
+    return (s + 7) & ~(size_t)7;
+}
+
+__host__ __device__ inline MetaView meta_view(void* meta, int64_t R, int M)
+{
+    uint8_t* p = (uint8_t*)meta + kHeaderBytes;
+    MetaView v;
+    v.row_off = (u64*)p;              p += 8 * (size_t)R;
+    v.n_pos = (u32*)p;                p += 4 * (size_t)R;
+    v.n_neg = (u32*)p;                p += 4 * (size_t)R;
+    v.vmin = (float*)p;               p += 8 * (size_t)R * M;
+    v.vmax = (float*)p;               p += 8 * (size_t)R * M;
+    v.q = p;
+    return v;
+}
+
+// ---- element types ---------------------------------------------------------
+// Magnitude key: the bit pattern with the sign cleared orders finite values by
+// |x| (ATKF, Sec. 3.1).  bf16 keys are kept as 15-bit integers.
+
+template <int DT> struct Elem;
+
+template <> struct Elem<0> {  // fp32
+    typedef u32 raw_t;
+    static constexpr int kKeyBits = 31;
+    __device__ static inline u32 key(raw_t r) { return r & 0x7FFFFFFFu; }
+    __device__ static inline u32 neg(raw_t r) { return r >> 31; }
+    __device__ static inline u32 value_bits(u32 key) { return key; }  // |x| as fp32 bits
+};
+
+template <> struct Elem<1> {  // bf16
+    typedef uint16_t raw_t;
+    static constexpr int kKeyBits = 15;
+    __device__ static inline u32 key(raw_t r) { return (u32)r & 0x7FFFu; }
+    __device__ static inline u32 neg(raw_t r) { return (u32)r >> 15; }
+    __device__ static inline u32 value_bits(u32 key) { return key << 16; }  // exact widening
+};
+
+__device__ inline u32 f32_to_bf16_rne(float f)
+{
+    u32 u = __float_as_uint(f);
+    u32 lsb = (u >> 16) & 1u;
+    return (u + 0x7FFFu + lsb) >> 16;
+}
+
+// ---- wave / block primitives -------------------------------------------------
+
+__device__ inline u32 lane_id() { return __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u)); }
+
+// number of set bits of `mask` strictly below the calling lane
+__device__ inline u32 mask_rank(u64 mask)
+{
+    return __builtin_amdgcn_mbcnt_hi((u32)(mask >> 32), __builtin_amdgcn_mbcnt_lo((u32)mask, 0u));
+}
+
+__device__ inline u32 wave_incl_scan(u32 v)
+{
+    const u32 lane = lane_id();
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        u32 t = __shfl_up(v, d);
+        if (lane >= (u32)d) v += t;
+    }
+    return v;
+}
+
+__device__ inline u32 wave_sum(u32 v)
+{
+#pragma unroll
+    for (int d = kWave / 2; d > 0; d >>= 1) v += __shfl_xor(v, d);
+    return v;
+}
+
+// Exclusive prefix sum over the threads of a block (thread order); `total`
+// receives the block sum.  `scratch` holds BLOCK/64 + 1 words.  Two barriers.
+template <int BLOCK>
+__device__ inline u32 block_excl_scan(u32 v, u32* scratch, u32* total)
+{
+    constexpr int NW = BLOCK / kWave;
+    const u32 lane = lane_id(), wid = threadIdx.x / kWave;
+    u32 inc = wave_incl_scan(v);
+    if (lane == kWave - 1) scratch[wid] = inc;
+    __syncthreads();
+    u32 base = 0, tot = 0;
+#pragma unroll
+    for (int i = 0; i < NW; ++i) {
+        u32 s = scratch[i];
+        if ((u32)i < wid) base += s;
+        tot += s;
+    }
+    __syncthreads();
+    *total = tot;
+    return base + inc - v;
+}
+
+// ilogb of a positive finite fp32 given by its bit pattern (subnormals included)
+__device__ inline int ilogb_bits(u32 bits)
+{
+    int ex = (int)(bits >> 23);
+    if (ex) return ex - 127;
+    return (31 - __clz((int)bits)) - 149;
+}
+
+// rint(a * 2^(20-e)) for a positive finite fp32 `bits` with ilogb(a) < e: the
+// 20-bit energy grid of ABQ, computed on the significand with round-half-even.
+__device__ inline u32 energy_grid(u32 bits, int e)
+{
+    int ex = (int)(bits >> 23);
+    u32 m = bits & 0x7FFFFFu;
+    int ea;
+    if (ex) { m |= 0x800000u; ea = ex - 127; } else { ea = -126; }
+    int s = 3 + e - ea;                 // a * 2^(20-e) = m / 2^s, s >= 4
+    if (s > 25) return 0u;
+    u32 q = m >> s;
+    u32 rem = m & ((1u << s) - 1u);
+    u32 half = 1u << (s - 1);
+    if (rem > half || (rem == half && (q & 1u))) ++q;
+    return q;
+}
+
+// ---- bit fields in a word stream (LSB first) -------------------------------------
+
+__device__ inline u32 read_bits(const u32* __restrict__ words, u64 bitpos, int nbits)
+{
+    u64 wi = bitpos >> 5;
+    u32 sh = (u32)bitpos & 31u;
+    u64 lo = words[wi];
+    if (sh + (u32)nbits > 32u) lo |= (u64)words[wi + 1] << 32;
+    return (u32)(lo >> sh) & ((nbits >= 32) ? 0xFFFFFFFFu : ((1u << nbits) - 1u));
+}
+
+}  // namespace slicer

@@ -1,0 +1,129 @@
+// Decoder (Eq. "dequnt"): de-quantise every block and scatter it into a zero tensor.
+// A workgroup owns a contiguous chunk of one output row: it builds the chunk in
+// LDS (zeros, then the decoded entries whose index falls in the chunk) and writes
+// it out once, coalesced, so every output byte goes to HBM exactly once.
+#pragma once
+
+#include "slicer_common.hpp"
+
+namespace slicer {
+
+constexpr int kDecChunk = 8192;   // output elements per workgroup
+
+struct DecArgs {
+    const u32* stream;
+    void* y;
+    int64_t R, N;
+    int M, w;
+    int chunks_per_row;
+    MetaView mv;
+};
+
+template <int DT, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void dec_kernel(DecArgs a)
+{
+    typedef typename Elem<DT>::raw_t raw_t;
+    __shared__ raw_t tile[kDecChunk];
+    __shared__ float vminf[kMaxB2], stepf[kMaxB2];
+    __shared__ int qv[kMaxB2];
+    __shared__ u32 istart[kMaxB2 + 1];     // first element of the block in stream order
+    __shared__ u64 cstart[kMaxB2 + 1];     // first code bit of the block
+    __shared__ u32 act_lo[kMaxB2];         // first element of the block that lands in this chunk
+    __shared__ u32 pre[kMaxB2 + 1];        // prefix of per-block counts landing in this chunk
+
+    const int tid = threadIdx.x;
+    const int64_t r = blockIdx.x / a.chunks_per_row;
+    const int64_t c0 = (int64_t)(blockIdx.x % a.chunks_per_row) * kDecChunk;
+    const int64_t c1 = c0 + kDecChunk < a.N ? c0 + kDecChunk : a.N;
+    const int len = (int)(c1 - c0);
+    const int M = a.M, B2 = 2 * a.M, w = a.w;
+    const u32* __restrict__ rw = a.stream + a.mv.row_off[r];
+    u32 n_cls[2] = { a.mv.n_pos[r], a.mv.n_neg[r] };
+    if ((u64)n_cls[0] + n_cls[1] > (u64)a.N) n_cls[0] = n_cls[1] = 0;   // not a valid row: write zeros
+    const u64 n = (u64)n_cls[0] + n_cls[1];
+
+    for (int b = tid; b < B2; b += BLOCK) {
+        size_t mi = (size_t)r * (size_t)B2 + (size_t)b;
+        int q = a.mv.q[mi] & 0x7F;
+        float vmin = a.mv.vmin[mi], vmax = a.mv.vmax[mi];
+        float L = (float)((1u << q) - 1u);
+        qv[b] = q;
+        vminf[b] = vmin;
+        stepf[b] = (vmax - vmin) / L;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        u32 ia = 0;
+        u64 ca = n * (u64)w;
+        for (int s = 0; s < 2; ++s) {
+            u32 K = n_cls[s] / (u32)M;
+            for (int m = 0; m < M; ++m) {
+                int b = s * M + m;
+                u32 cnt = (m < M - 1) ? K : n_cls[s] - K * (u32)(M - 1);
+                istart[b] = ia; cstart[b] = ca;
+                ia += cnt; ca += (u64)cnt * (u64)qv[b];
+            }
+        }
+        istart[B2] = ia; cstart[B2] = ca;
+    }
+    for (int i = tid; i < len; i += BLOCK) tile[i] = 0;
+    __syncthreads();
+
+    // entries of each block that land in [c0, c1): indices ascend inside a block
+    for (int b = tid; b < B2; b += BLOCK) {
+        u32 first = istart[b], cnt = istart[b + 1] - first;
+        u32 lo = 0, hi = cnt;
+        if (a.chunks_per_row > 1) {
+            u32 l = 0, h = cnt;                    // first j with idx >= c0
+            while (l < h) { u32 m = (l + h) >> 1; if ((int64_t)read_bits(rw, (u64)(first + m) * w, w) < c0) l = m + 1; else h = m; }
+            lo = l; h = cnt;                       // first j with idx >= c1
+            while (l < h) { u32 m = (l + h) >> 1; if ((int64_t)read_bits(rw, (u64)(first + m) * w, w) < c1) l = m + 1; else h = m; }
+            hi = l;
+        }
+        act_lo[b] = lo;
+        pre[b + 1] = hi - lo;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        u32 acc = 0;
+        pre[0] = 0;
+        for (int b = 0; b < B2; ++b) { acc += pre[b + 1]; pre[b + 1] = acc; }
+    }
+    __syncthreads();
+
+    const u32 total = pre[B2];
+    for (u32 t = tid; t < total; t += BLOCK) {
+        int lo = 0, hi = B2 - 1;                   // block b with pre[b] <= t < pre[b+1]
+        while (lo < hi) { int mid = (lo + hi) >> 1; if (pre[mid + 1] <= t) lo = mid + 1; else hi = mid; }
+        const int b = lo;
+        const u32 j = act_lo[b] + (t - pre[b]);
+        const int q = qv[b];
+        const u32 idx = read_bits(rw, (u64)(istart[b] + j) * w, w);
+        const u32 c = read_bits(rw, cstart[b] + (u64)j * (u64)q, q);
+        float val = __fadd_rn(vminf[b], __fmul_rn((float)c, stepf[b]));   // two roundings, never fused
+        if (b >= M) val = -val;
+        const int64_t rel = (int64_t)idx - c0;
+        if (rel >= 0 && rel < len) {
+            if (DT == 0) tile[rel] = (raw_t)__float_as_uint(val);
+            else tile[rel] = (raw_t)f32_to_bf16_rne(val);
+        }
+    }
+    __syncthreads();
+
+    const size_t g0 = (size_t)r * (size_t)a.N + (size_t)c0;
+    if (DT == 0) {
+        u32* __restrict__ out = (u32*)a.y + g0;
+        for (int i = tid; i < len; i += BLOCK) out[i] = (u32)tile[i];
+    } else {
+        uint16_t* __restrict__ out = (uint16_t*)a.y + g0;
+        const int head = (int)(g0 & 1);
+        if (head && tid == 0) out[0] = (uint16_t)tile[0];
+        const int npair = (len - head) >> 1;
+        u32* __restrict__ out2 = (u32*)(out + head);
+        for (int t = tid; t < npair; t += BLOCK)
+            out2[t] = (u32)tile[head + 2 * t] | ((u32)tile[head + 2 * t + 1] << 16);
+        if (((len - head) & 1) && tid == 0) out[len - 1] = (uint16_t)tile[len - 1];
+    }
+}
+
+}  // namespace slicer

@@ -1,0 +1,54 @@
+"""Helpers for the GPU parity tests: run a workload through the HIP library via its
+C ABI and bring stream / meta / decoded tensor back as numpy arrays."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from paper_2511_11608_amd import binding
+
+
+def to_device(x: np.ndarray, dtype: str) -> torch.Tensor:
+    if dtype == "f32":
+        return torch.from_numpy(np.ascontiguousarray(x)).cuda()
+    return torch.from_numpy(np.ascontiguousarray(x).view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def to_host(y: torch.Tensor) -> np.ndarray:
+    if y.dtype == torch.bfloat16:
+        return y.view(torch.int16).cpu().numpy().view(np.uint16)
+    return y.cpu().numpy()
+
+
+def gpu_encode(x: np.ndarray, dtype: str, keep_ratio, n_blocks, bit_set, budget):
+    xd = to_device(x, dtype)
+    sb, meta, ws = binding.alloc_buffers(xd, keep_ratio, n_blocks, bit_set)
+    ws.fill_(0xA5)          # the encoder must not rely on workspace contents
+    sb.fill_(-1)
+    meta.fill_(0xFF)
+    binding.slicer_encode(xd, keep_ratio, n_blocks, bit_set, budget, sb, meta, ws)
+    words = binding.slicer_stream_words(meta)
+    return sb, meta, words
+
+
+def gpu_decode(sb, meta, shape, dtype, n_blocks, use_header=True) -> np.ndarray:
+    y = torch.full(shape, 7.0, dtype=torch.float32 if dtype == "f32" else torch.bfloat16, device="cuda")
+    if use_header:
+        binding.slicer_decode(sb, meta, y)
+    else:
+        binding.slicer_decode_as(sb, meta, y, n_blocks)
+    torch.cuda.synchronize()
+    return to_host(y)
+
+
+def gpu_roundtrip(x: np.ndarray, dtype: str, keep_ratio, n_blocks, bit_set, budget, use_header=True):
+    """(stream uint32[words], meta uint8[], y) from the HIP path."""
+    sb, meta, words = gpu_encode(x, dtype, keep_ratio, n_blocks, bit_set, budget)
+    y = torch.full(x.shape, 7.0, dtype=torch.float32 if dtype == "f32" else torch.bfloat16, device="cuda")
+    if use_header:
+        binding.slicer_decode(sb, meta, y)
+    else:
+        binding.slicer_decode_as(sb, meta, y, n_blocks)
+    torch.cuda.synchronize()
+    s = sb[:words].cpu().numpy().view(np.uint32)
+    return s, meta.cpu().numpy(), to_host(y)

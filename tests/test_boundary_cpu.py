@@ -1,0 +1,62 @@
+"""The C-ABI library loads without a GPU and exports every symbol include/slicer.h
+declares; host-only entry points (sizes, error strings, argument checks) behave."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2511_11608_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2511_11608_amd import build
+        build.build()
+    return binding.load()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "slicer.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(slicer_[a-z_]+)\s*\(", text)))
+
+
+def test_exports_every_declared_symbol(lib):
+    names = declared_symbols()
+    assert {"slicer_sizes", "slicer_encode", "slicer_decode", "slicer_decode_as", "slicer_stream_words",
+            "slicer_last_hip_error", "slicer_strerror"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_sizes_closed_form(lib):
+    from paper_2511_11608_amd import binding, synth
+    # workload 4: k = floor(0.1*4096) = 409, w = 12, q_bit = 8 -> ceil(409*20/32) = 256 words per row
+    cap, mb, wb = binding.slicer_sizes(binding.SLICER_BF16, 16384, 4096, 0.10, 8, synth.BITS_2_TO_8)
+    assert cap == 16384 * 256 * 4
+    assert mb == 64 + 16 * 16384 + 18 * 16384 * 8
+    assert wb >= cap
+    # workload 2: k = 80281, w = 19
+    cap, mb, _ = binding.slicer_sizes(binding.SLICER_F32, 32, 401408, 0.20, 16, synth.BITS_2_TO_8)
+    assert cap == 32 * ((80281 * 27 + 31) // 32) * 4 and mb == 64 + 16 * 32 + 18 * 32 * 16
+
+
+def test_argument_errors_and_strings(lib):
+    from paper_2511_11608_amd import binding
+    good = dict(dt=0, rows=2, row_len=8, keep_ratio=0.5, n_blocks=2, bit_set=0b111100)
+    for kw, code in ((dict(dt=7), -2), (dict(rows=0), -1), (dict(row_len=0), -1), (dict(row_len=1 << 31), -1),
+                     (dict(keep_ratio=-0.1), -1), (dict(keep_ratio=float("nan")), -1), (dict(n_blocks=0), -1),
+                     (dict(n_blocks=65), -1), (dict(bit_set=0), -1), (dict(bit_set=1), -1), (dict(bit_set=1 << 17), -1)):
+        a = dict(good); a.update(kw)
+        with pytest.raises(binding.SlicerError) as ei:
+            binding.slicer_sizes(a["dt"], a["rows"], a["row_len"], a["keep_ratio"], a["n_blocks"], a["bit_set"])
+        assert ei.value.code == code
+    assert lib.slicer_strerror(0) == b"ok"
+    for code in (-1, -2, -3, -4, -99):
+        assert len(lib.slicer_strerror(code)) > 0
+    # null pointers are rejected before anything is launched
+    assert lib.slicer_encode(None, 0, 1, 8, 0.5, 1, 0b100, 1e-3, None, None, None, None) == -1
+    assert lib.slicer_decode_as(None, None, None, 0, 1, 8, 1, None) == -1

@@ -1,0 +1,117 @@
+"""GPU parity: the HIP path, through the C ABI, against the CPU oracle.
+
+Bit-exact on stream and meta (kept set, block membership, bitwidths, codes, ranges,
+offsets) and on the decoded tensor, on seeded synthetic inputs shaped like the five
+workloads (shrunk so the oracle finishes in seconds) plus the degenerate rows.
+"""
+import numpy as np
+import pytest
+
+from paper_2511_11608_amd import synth
+from tests import streamfmt
+
+pytestmark = pytest.mark.gpu
+
+B28 = synth.BITS_2_TO_8
+
+
+def explain_mismatch(s_ref, m_ref, s_gpu, m_gpu, rows):
+    """First differing row and what differs there (for the assertion message)."""
+    a, b = streamfmt.arrays(m_ref), streamfmt.arrays(m_gpu)
+    for name in ("n_pos", "n_neg", "q", "vmin", "vmax", "row_off"):
+        if not np.array_equal(a[name], b[name]):
+            r = int(np.nonzero(np.atleast_1d((a[name] != b[name]).reshape(rows, -1).any(axis=1)))[0][0])
+            return f"meta field {name} differs first at row {r}: ref {a[name][r]} gpu {b[name][r]}"
+    if s_ref.size != s_gpu.size:
+        return f"stream sizes differ: {s_ref.size} vs {s_gpu.size}"
+    d = np.nonzero(s_ref != s_gpu)[0]
+    if d.size:
+        r = int(np.searchsorted(a["row_off"], d[0], side="right") - 1)
+        pr, pg = streamfmt.parse_row(s_ref, m_ref, r), streamfmt.parse_row(s_gpu, m_gpu, r)
+        for bi, (x, y) in enumerate(zip(pr["blocks"], pg["blocks"])):
+            if x != y:
+                return f"stream word {d[0]} (row {r}) differs; first differing block {bi}: ref {x} gpu {y}"
+        return f"stream word {d[0]} (row {r}) differs"
+    return "identical"
+
+
+def check(oracle, wl_x, dtype, keep, M, bits, budget, use_header=True):
+    from tests.gpu_util import gpu_encode, gpu_decode
+    s_ref, m_ref = oracle.encode(wl_x, dtype, keep, M, bits, budget, n_threads=8)
+    y_ref = oracle.decode(s_ref, m_ref, n_threads=8)
+    sb, meta, words = gpu_encode(wl_x, dtype, keep, M, bits, budget)
+    m_gpu = meta.cpu().numpy()
+    # compare before decoding: the decoder is only ever fed a stream known to be well-formed
+    assert np.array_equal(m_ref[:64], m_gpu[:64]), (streamfmt.header(m_ref), streamfmt.header(m_gpu))
+    s_gpu = sb[:words].cpu().numpy().view(np.uint32)
+    ok = np.array_equal(m_ref, m_gpu) and np.array_equal(s_ref, s_gpu)
+    assert ok, explain_mismatch(s_ref, m_ref, s_gpu, m_gpu, wl_x.shape[0])
+    y_gpu = gpu_decode(sb, meta, wl_x.shape, dtype, M, use_header)
+    # decode: bit-identical (stronger than the 1e-6 relative bar)
+    assert np.array_equal(y_ref.view(np.uint32 if dtype == "f32" else np.uint16),
+                          y_gpu.view(np.uint32 if dtype == "f32" else np.uint16))
+
+
+CASES = {
+    "cnn_map": lambda: synth.cnn_map(seed=0),                                        # config 1, full size
+    "cnn_map_ragged": lambda: synth.cnn_map(seed=1, rows=3, row_len=50_001),
+    "resnet_2rows": lambda: synth.resnet_stage3(seed=0, rows=2),                      # config 2, real row length
+    "vit": lambda: synth.vit_tokens(seed=0, rows=700),                               # config 3
+    "llm": lambda: synth.llm_prefill(seed=0, rows=300),                              # config 4
+    "ar_step": lambda: synth.ar_decode_step(seed=0, step=5, rows=64),                 # config 5
+}
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_workload_parity(oracle, name):
+    wl = CASES[name]()
+    check(oracle, wl.x, wl.dtype, wl.keep_ratio, wl.n_blocks, wl.bit_set, wl.budget)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("N", [1, 2, 63, 64, 65, 257, 1000, 4097, 16385, 40000])
+def test_adversarial_rows(oracle, dtype, N):
+    x = synth.adversarial_rows(dtype, N, seed=N)
+    for keep, M, bits, budget in ((0.0, 1, B28, 1e-3), (0.3, 2, B28, 1e-3), (1.0, 5, B28, 0.0),
+                                  (0.11, 64, (1 << 1) | (1 << 16), 1e-6), (0.5, 3, 1 << 5, 1e-2)):
+        check(oracle, x, dtype, keep, M, bits, budget, use_header=(M != 2))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_random_parameters(oracle, dtype):
+    rng = np.random.default_rng(123)
+    for _ in range(12):
+        rows = int(rng.integers(1, 9))
+        N = int(rng.integers(1, 3000))
+        x = rng.standard_normal((rows, N)).astype(np.float32) * np.float32(10.0 ** rng.integers(-3, 4))
+        x[rng.random((rows, N)) < rng.random()] = 0
+        if dtype == "bf16":
+            x = synth.f32_to_bf16_bits(x)
+        keep = float(rng.random())
+        M = int(rng.integers(1, 20))
+        bits = int(rng.integers(1, 1 << 16)) << 1
+        budget = float(10.0 ** rng.uniform(-6, -1))
+        check(oracle, x, dtype, keep, M, bits, budget)
+
+
+def test_encode_is_deterministic():
+    from tests.gpu_util import gpu_roundtrip
+    wl = synth.llm_prefill(seed=3, rows=64)
+    a = gpu_roundtrip(wl.x, wl.dtype, wl.keep_ratio, wl.n_blocks, wl.bit_set, wl.budget)
+    b = gpu_roundtrip(wl.x, wl.dtype, wl.keep_ratio, wl.n_blocks, wl.bit_set, wl.budget)
+    assert all(np.array_equal(u, v) for u, v in zip(a, b))
+
+
+def test_error_codes():
+    import torch
+    from paper_2511_11608_amd import binding
+    x = torch.zeros(4, 16, device="cuda")
+    sb, meta, ws = binding.alloc_buffers(x, 0.5, 2, B28)
+    for kw in (dict(keep_ratio=1.5), dict(n_blocks=0), dict(n_blocks=65), dict(bit_set=1), dict(budget=-1.0)):
+        args = dict(keep_ratio=0.5, n_blocks=2, bit_set=B28, budget=1e-3); args.update(kw)
+        with pytest.raises(binding.SlicerError):
+            binding.slicer_encode(x, args["keep_ratio"], args["n_blocks"], args["bit_set"], args["budget"], sb, meta, ws)
+    meta.zero_()
+    with pytest.raises(binding.SlicerError) as ei:
+        binding.slicer_decode(sb, meta, x)
+    assert ei.value.code == -4
