@@ -1,0 +1,229 @@
+#!/usr/bin/env python3
+"""Benchmark of the SLICER IF codec hot path on one MI355X.
+
+A step = one encode (ATKF -> MS -> ABQ -> packing) followed by one decode of one
+batch of synthetic intermediate features, inputs already resident in HBM.  The
+default workload is the LLM-prefill configuration (bf16 [16384, 4096], the largest
+of the five); input buffers rotate over > 256 MB of distinct device memory so that
+the Infinity Cache does not stand in for HBM.
+
+Prints ONE JSON line: whole-step throughput in GB/s of input IF, the roofline
+record of the dominant kernel (the per-row encode kernel; its duration is read with
+HIP events recorded around that kernel on its stream), and the CPU oracle timed on
+a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
+
+
+class HipEvents:
+    """Raw hipEvent_t handles through libamdhip64 (torch's Event does not expose a
+    handle that can be passed across the C ABI before it has been recorded)."""
+
+    def __init__(self):
+        self.hip = C.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+        self.hip.hipEventSynchronize.argtypes = [C.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [C.c_void_p]
+
+    def create(self) -> int:
+        e = C.c_void_p()
+        rc = self.hip.hipEventCreate(C.byref(e))
+        if rc:
+            raise RuntimeError(f"hipEventCreate: {rc}")
+        return e.value
+
+    def elapsed_ms(self, a: int, b: int) -> float:
+        self.hip.hipEventSynchronize(b)
+        ms = C.c_float(0)
+        rc = self.hip.hipEventElapsedTime(C.byref(ms), a, b)
+        if rc:
+            raise RuntimeError(f"hipEventElapsedTime: {rc}")
+        return ms.value
+
+
+def make_workload(which: int):
+    from paper_2511_11608_amd import synth
+    if which == 5:
+        steps = [synth.ar_decode_step(seed=0, step=s) for s in range(64)]
+        return steps[0], [s.x for s in steps]
+    wl = synth.make_config(which)
+    return wl, [wl.x]
+
+
+def cpu_baseline(wl, threads: int) -> dict:
+    """The oracle as it stands (encode + decode) on a bounded sample of the rows."""
+    from oracle import ref
+    ref.lib()
+    rows = wl.rows
+    probe = max(1, min(rows, 64 if wl.row_len < 100_000 else 2))
+    t0 = time.perf_counter()
+    s, m = ref.encode(wl.x[:probe], wl.dtype, wl.keep_ratio, wl.n_blocks, wl.bit_set, wl.budget, n_threads=threads)
+    ref.decode(s, m, n_threads=threads)
+    per_row = (time.perf_counter() - t0) / probe * min(threads, probe)      # core-seconds per row
+    take = int(max(probe, min(rows, 15.0 / max(per_row, 1e-9))))
+    x = wl.x[:take]
+    t0 = time.perf_counter()
+    s, m = ref.encode(x, wl.dtype, wl.keep_ratio, wl.n_blocks, wl.bit_set, wl.budget, n_threads=threads)
+    t1 = time.perf_counter()
+    ref.decode(s, m, n_threads=threads)
+    t2 = time.perf_counter()
+    nbytes = x.nbytes
+    return {"value": nbytes / (t2 - t0) / 1e9, "unit": "GB/s of input IF (encode+decode)",
+            "cores": int(min(threads, take)), "kind": "oracle",
+            "sample": f"first {take} of {rows} rows of the same workload, OpenMP over rows",
+            "encode_GBps": nbytes / (t1 - t0) / 1e9, "decode_GBps": nbytes / (t2 - t1) / 1e9}
+
+
+def load_traffic(workload: str, kernel: str):
+    """HBM bytes per launch from committed rocprofv3 --pmc summaries, if present."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        table = json.load(open(path))
+        return table[workload][kernel]
+    except Exception:
+        return None
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", type=int, default=4, help="1..5 (default 4: LLM prefill, the headline config)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this codec build runs on ONE GPU (rows are independent; sharding is by rows, "
+              "see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2511_11608_amd import binding
+    from tests.gpu_util import to_device     # numpy -> device tensor (plumbing only)
+
+    binding.load()
+    wl, xs = make_workload(args.workload)
+    M, bits, keep, beta = wl.n_blocks, wl.bit_set, wl.keep_ratio, wl.budget
+    in_bytes = wl.nbytes
+
+    # distinct input buffers: > 256 MB in flight so that reads come from HBM
+    x0 = [to_device(x, wl.dtype) for x in xs]
+    n_buf = max(len(x0), int(np.ceil(320e6 / in_bytes)) + 1)
+    n_buf = min(n_buf, 512)
+    xd = list(x0)
+    shift = 1
+    while len(xd) < n_buf:
+        xd.append(torch.roll(x0[len(xd) % len(x0)], shifts=shift, dims=0).contiguous())
+        shift += 1
+    n_out = min(n_buf, 4)
+    bufs = [binding.alloc_buffers(xd[0], keep, M, bits) for _ in range(n_out)]
+    ys = [torch.empty_like(xd[0]) for _ in range(n_out)]
+
+    ev = HipEvents()
+    K, W = args.steps, args.warmup
+    e_enc = [(ev.create(), ev.create()) for _ in range(K)]
+    e_dec = [(ev.create(), ev.create()) for _ in range(K)]
+
+    def step(i: int, timed_idx: int | None):
+        x = xd[i % n_buf]
+        sb, meta, ws = bufs[i % n_out]
+        if timed_idx is not None:
+            binding.slicer_profile_events(*e_enc[timed_idx])
+        binding.slicer_encode(x, keep, M, bits, beta, sb, meta, ws)
+        if timed_idx is not None:
+            binding.slicer_profile_events(*e_dec[timed_idx])
+        binding.slicer_decode_as(sb, meta, ys[i % n_out], M)
+
+    for i in range(W):
+        step(i, None)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        step(W + i, i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    binding.slicer_profile_events(None, None)
+    ms_per_step = (t1 - t0) * 1e3 / K
+
+    enc_ms = float(np.mean([ev.elapsed_ms(a, b) for a, b in e_enc]))
+    dec_ms = float(np.mean([ev.elapsed_ms(a, b) for a, b in e_dec]))
+
+    # encode-only and decode-only loops (whole call, all kernels), HIP events on the stream
+    def timed_loop(fn):
+        a, b = ev.create(), ev.create()
+        st = torch.cuda.current_stream().cuda_stream
+        ev.hip.hipEventRecord.argtypes = [C.c_void_p, C.c_void_p]
+        ev.hip.hipEventRecord(a, st)
+        for i in range(K):
+            fn(i)
+        ev.hip.hipEventRecord(b, st)
+        return ev.elapsed_ms(a, b) / K
+
+    enc_call_ms = timed_loop(lambda i: binding.slicer_encode(xd[i % n_buf], keep, M, bits, beta, *bufs[i % n_out]))
+    dec_call_ms = timed_loop(lambda i: binding.slicer_decode_as(bufs[i % n_out][0], bufs[i % n_out][1],
+                                                                  ys[i % n_out], M))
+
+    # compressed size of the last batch encoded into bufs[0]
+    binding.slicer_encode(xd[0], keep, M, bits, beta, *bufs[0])
+    words = binding.slicer_stream_words(bufs[0][1])
+    _, meta_bytes, _ = binding.slicer_sizes(binding.SLICER_F32 if wl.dtype == "f32" else binding.SLICER_BF16,
+                                            wl.rows, wl.row_len, keep, M, bits)
+    n_el = wl.rows * wl.row_len
+    out_bytes = 4 * words + meta_bytes
+    bpe = 8.0 * out_bytes / n_el
+
+    enc_kernel = "enc_generic_kernel"
+    enc_alg_bytes = in_bytes + out_bytes                 # read x once, write stream + meta
+    dec_alg_bytes = out_bytes + in_bytes                 # read stream + meta, write y once
+    achieved = enc_alg_bytes / (enc_ms * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": enc_kernel, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBS, "traffic": load_traffic(wl.name, enc_kernel),
+                "algorithmic_bytes_per_launch": enc_alg_bytes, "kernel_ms": enc_ms,
+                "decode_kernel": {"kernel": "dec_kernel", "kernel_ms": dec_ms,
+                                  "achieved": dec_alg_bytes / (dec_ms * 1e-3) / 1e9,
+                                  "frac": dec_alg_bytes / (dec_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                  "traffic": load_traffic(wl.name, "dec_kernel")}}
+
+    threads = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)))
+    cpu = None if args.no_cpu else cpu_baseline(wl, threads)
+
+    out = {
+        "metric": "codec encode+decode throughput, GB/s of input IF",
+        "value": in_bytes / (ms_per_step * 1e-3) / 1e9,
+        "unit": "GB/s",
+        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": f"{wl.name} [{wl.rows}x{wl.row_len}] keep={keep} M={M} bits=2..8 budget={beta}",
+                   "input_bytes": in_bytes, "distinct_input_buffers": n_buf},
+        "encode": {"GBps": in_bytes / (enc_call_ms * 1e-3) / 1e9, "ms": enc_call_ms,
+                   "elements_per_s": n_el / (enc_call_ms * 1e-3),
+                   "frac_hbm_peak": in_bytes / (enc_call_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        "decode": {"GBps": in_bytes / (dec_call_ms * 1e-3) / 1e9, "ms": dec_call_ms,
+                   "elements_per_s": n_el / (dec_call_ms * 1e-3),
+                   "frac_hbm_peak": in_bytes / (dec_call_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        "bits_per_element": bpe, "stream_words": words, "meta_bytes": meta_bytes,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

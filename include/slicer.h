@@ -113,6 +113,16 @@ int slicer_decode_as(const void* stream, const void* meta, void* y, slicer_dtype
  * to the host.  Waits for `hip_stream`. */
 int slicer_stream_words(const void* meta, uint64_t* words, void* hip_stream);
 
+/*
+ * Timing hook for benchmarks.  While both events are non-NULL (hipEvent_t cast to
+ * void*), every slicer_encode / slicer_decode / slicer_decode_as issued by the
+ * calling thread records `start` immediately before and `stop` immediately after
+ * its dominant kernel (the per-row encode kernel, or the decode kernel) on the
+ * call's stream, so that the kernel's own duration can be read with
+ * hipEventElapsedTime.  Pass NULL, NULL to switch it off (the default).
+ */
+int slicer_profile_events(void* start_event, void* stop_event);
+
 /* hipError_t of the most recent failed HIP call made by this library on the
  * calling thread (0 if none). */
 int slicer_last_hip_error(void);

@@ -48,6 +48,8 @@ def load() -> C.CDLL:
         L.slicer_decode_as.argtypes = [vp, vp, vp, cint, i64, i64, cint, vp]
         L.slicer_stream_words.restype = cint
         L.slicer_stream_words.argtypes = [vp, C.POINTER(C.c_uint64), vp]
+        L.slicer_profile_events.restype = cint
+        L.slicer_profile_events.argtypes = [vp, vp]
         L.slicer_last_hip_error.restype = cint
         L.slicer_last_hip_error.argtypes = []
         L.slicer_strerror.restype = C.c_char_p
@@ -123,3 +125,8 @@ def slicer_stream_words(meta: torch.Tensor, stream=None) -> int:
     w = C.c_uint64(0)
     _check("slicer_stream_words", load().slicer_stream_words(meta.data_ptr(), C.byref(w), _stream_handle(stream)))
     return w.value
+
+
+def slicer_profile_events(start_event, stop_event) -> None:
+    """Raw hipEvent_t handles (ints) or None, None: see include/slicer.h."""
+    _check("slicer_profile_events", load().slicer_profile_events(start_event, stop_event))

@@ -14,6 +14,7 @@ using namespace slicer;
 namespace {
 
 thread_local int g_last_hip_error = 0;
+thread_local hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
 
 inline int hip_fail(hipError_t e)
 {
@@ -81,12 +82,16 @@ Plan make_plan(int64_t rows, int64_t row_len, double keep_ratio, uint32_t bit_se
 template <int DT>
 int launch_encode(const EncArgs& ea, hipStream_t st)
 {
+    const bool timed = g_ev_start && g_ev_stop;
+    if (timed) SLICER_HIP(hipEventRecord(g_ev_start, st));
     if (ea.N >= 32768)
         hipLaunchKernelGGL((enc_generic_kernel<DT, 1024>), dim3((unsigned)ea.R), dim3(1024), 0, st, ea);
     else
         hipLaunchKernelGGL((enc_generic_kernel<DT, 256>), dim3((unsigned)ea.R), dim3(256), 0, st, ea);
     hipError_t e = hipGetLastError();
-    return e == hipSuccess ? SLICER_OK : hip_fail(e);
+    if (e != hipSuccess) return hip_fail(e);
+    if (timed) SLICER_HIP(hipEventRecord(g_ev_stop, st));
+    return SLICER_OK;
 }
 
 int launch_decode(const void* stream, const void* meta, void* y, int dt, int64_t rows, int64_t row_len,
@@ -100,12 +105,16 @@ int launch_decode(const void* stream, const void* meta, void* y, int dt, int64_t
     da.mv = meta_view(const_cast<void*>(meta), rows, n_blocks);
     const u64 grid = (u64)rows * (u64)da.chunks_per_row;
     if (grid >= (1ull << 31)) return SLICER_EINVAL;
+    const bool timed = g_ev_start && g_ev_stop;
+    if (timed) SLICER_HIP(hipEventRecord(g_ev_start, st));
     if (dt == SLICER_F32)
         hipLaunchKernelGGL((dec_kernel<0, 256>), dim3((unsigned)grid), dim3(256), 0, st, da);
     else
         hipLaunchKernelGGL((dec_kernel<1, 256>), dim3((unsigned)grid), dim3(256), 0, st, da);
     hipError_t e = hipGetLastError();
-    return e == hipSuccess ? SLICER_OK : hip_fail(e);
+    if (e != hipSuccess) return hip_fail(e);
+    if (timed) SLICER_HIP(hipEventRecord(g_ev_stop, st));
+    return SLICER_OK;
 }
 
 }  // namespace
@@ -221,6 +230,14 @@ int slicer_stream_words(const void* meta, uint64_t* words, void* hip_stream)
     int rc = read_header(meta, (hipStream_t)hip_stream, h32);
     if (rc) return rc;
     *words = ((const uint64_t*)h32)[6];
+    return SLICER_OK;
+}
+
+int slicer_profile_events(void* start_event, void* stop_event)
+{
+    if ((start_event == nullptr) != (stop_event == nullptr)) return SLICER_EINVAL;
+    g_ev_start = (hipEvent_t)start_event;
+    g_ev_stop = (hipEvent_t)stop_event;
     return SLICER_OK;
 }
 

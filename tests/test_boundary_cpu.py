@@ -27,7 +27,7 @@ def declared_symbols():
 def test_exports_every_declared_symbol(lib):
     names = declared_symbols()
     assert {"slicer_sizes", "slicer_encode", "slicer_decode", "slicer_decode_as", "slicer_stream_words",
-            "slicer_last_hip_error", "slicer_strerror"} <= set(names)
+            "slicer_profile_events", "slicer_last_hip_error", "slicer_strerror"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
