@@ -3,10 +3,12 @@
 #include "../../include/slicer.h"
 
 #include <hip/hip_runtime.h>
+#include <algorithm>
 #include <cmath>
 
 #include "slicer_common.hpp"
 #include "slicer_encode_generic.hpp"
+#include "slicer_encode_small.hpp"
 #include "slicer_decode.hpp"
 
 using namespace slicer;
@@ -56,12 +58,14 @@ struct Plan {
     int64_t k;
     int w, qmax;
     u64 cap_words;          // per row
-    size_t off_row_words, off_slots, off_kept, off_bo_idx, off_bo_val, total;
+    size_t off_row_words, off_slots, off_kept, off_bo_idx, off_bo_val, off_fallback, total;
+    // row-resident fast path (0 = not eligible)
+    int small_epl, small_cap, small_region0, small_lds_bytes;
 };
 
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
-Plan make_plan(int64_t rows, int64_t row_len, double keep_ratio, uint32_t bit_set)
+Plan make_plan(int dt, int64_t rows, int64_t row_len, double keep_ratio, int n_blocks, uint32_t bit_set)
 {
     Plan p;
     p.k = (int64_t)std::floor(keep_ratio * (double)row_len);   // ATKF: k = floor((1-s) N)
@@ -75,14 +79,54 @@ Plan make_plan(int64_t rows, int64_t row_len, double keep_ratio, uint32_t bit_se
     p.off_kept = o;      o = align256(o + 8 * (size_t)rows * (size_t)p.k);
     p.off_bo_idx = o;    o = align256(o + 4 * (size_t)rows * (size_t)p.k);
     p.off_bo_val = o;    o = align256(o + 4 * (size_t)rows * (size_t)p.k);
+    p.off_fallback = o;  o = align256(o + 4 * (size_t)rows);
     p.total = o ? o : 256;
+
+    // The one-wave-per-row kernel holds the row in registers (64 * EPL elements) and
+    // its lists in LDS; it needs whole 16-byte chunks, 16-bit indices, one lane per
+    // block and a list capacity below 1024 entries.
+    p.small_epl = 0; p.small_cap = 0; p.small_region0 = 0; p.small_lds_bytes = 0;
+    const int epc = dt == SLICER_F32 ? 4 : 8;
+    const int64_t max_n = dt == SLICER_F32 ? 2048 : 8192;
+    int nq = 0;
+    for (int q = 1; q <= 16; ++q) nq += (bit_set >> q) & 1u;
+    if (row_len % epc == 0 && row_len <= max_n && 2 * n_blocks <= kWave) {
+        const int64_t margin = std::max<int64_t>(64, row_len / (dt == SLICER_F32 ? 8 : 16));
+        int64_t cap = std::min<int64_t>(960, (p.k + margin + 63) / 64 * 64);
+        int epl = epc;
+        while ((int64_t)epl * kWave < row_len) epl *= 2;
+        const int64_t region0 = std::max<int64_t>(kFineBins, p.k + (p.k + 1) / 2 + (int64_t)p.cap_words);
+        const int64_t lds = 4 * (int64_t)small_lds_words((int)cap, (int)region0, 2 * n_blocks, nq);
+        if (p.k + 64 <= cap && lds <= 64 * 1024) {
+            p.small_epl = epl; p.small_cap = (int)cap; p.small_region0 = (int)region0; p.small_lds_bytes = (int)lds;
+        }
+    }
     return p;
+}
+
+template <int DT, int EPL>
+void launch_small_epl(const SmallArgs& sa, int lds_bytes, hipStream_t st)
+{
+    hipLaunchKernelGGL((enc_small_kernel<DT, EPL>), dim3((unsigned)sa.R), dim3(kWave), (size_t)lds_bytes, st, sa);
+}
+
+template <int DT>
+int launch_small(const SmallArgs& sa, const Plan& p, hipStream_t st)
+{
+    constexpr int E0 = DT == 0 ? 4 : 16;      // smallest instantiated elements-per-lane
+    const int lds = p.small_lds_bytes;
+    if (p.small_epl <= E0) launch_small_epl<DT, E0>(sa, lds, st);
+    else if (p.small_epl == E0 * 2) launch_small_epl<DT, E0 * 2>(sa, lds, st);
+    else if (p.small_epl == E0 * 4) launch_small_epl<DT, E0 * 4>(sa, lds, st);
+    else launch_small_epl<DT, E0 * 8>(sa, lds, st);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? SLICER_OK : hip_fail(e);
 }
 
 template <int DT>
 int launch_encode(const EncArgs& ea, hipStream_t st)
 {
-    const bool timed = g_ev_start && g_ev_stop;
+    const bool timed = g_ev_start && g_ev_stop && !ea.only_flagged;
     if (timed) SLICER_HIP(hipEventRecord(g_ev_start, st));
     if (ea.N >= 32768)
         hipLaunchKernelGGL((enc_generic_kernel<DT, 1024>), dim3((unsigned)ea.R), dim3(1024), 0, st, ea);
@@ -127,7 +171,7 @@ int slicer_sizes(slicer_dtype dt, int64_t rows, int64_t row_len, double keep_rat
 {
     int rc = check_args((int)dt, rows, row_len, keep_ratio, n_blocks, bit_set);
     if (rc) return rc;
-    Plan p = make_plan(rows, row_len, keep_ratio, bit_set);
+    Plan p = make_plan((int)dt, rows, row_len, keep_ratio, n_blocks, bit_set);
     if (stream_capacity_bytes) *stream_capacity_bytes = (size_t)(p.cap_words * 4ull * (u64)rows);
     if (meta_bytes_out) *meta_bytes_out = meta_bytes(rows, n_blocks);
     if (workspace_bytes) *workspace_bytes = p.total;
@@ -144,7 +188,7 @@ int slicer_encode(const void* x, slicer_dtype dt, int64_t rows, int64_t row_len,
     if (!(distortion_budget >= 0.0)) return SLICER_EINVAL;
     if (rows >= ((int64_t)1 << 31)) return SLICER_EINVAL;
     hipStream_t st = (hipStream_t)hip_stream;
-    Plan p = make_plan(rows, row_len, keep_ratio, bit_set);
+    Plan p = make_plan((int)dt, rows, row_len, keep_ratio, n_blocks, bit_set);
     char* ws = (char*)workspace;
 
     EncArgs ea;
@@ -163,7 +207,27 @@ int slicer_encode(const void* x, slicer_dtype dt, int64_t rows, int64_t row_len,
     ea.bo_idx = (u32*)(ws + p.off_bo_idx);
     ea.bo_val = (u32*)(ws + p.off_bo_val);
     ea.mv = meta_view(meta, rows, n_blocks);
+    ea.only_flagged = nullptr;
 
+    if (p.small_epl && ((uintptr_t)x & 15) == 0) {
+        // fast path; rows it cannot hold are flagged and redone by the generic kernel
+        SmallArgs sa;
+        sa.x = x; sa.R = rows; sa.N = row_len; sa.k = p.k;
+        sa.M = n_blocks; sa.w = p.w; sa.nq = ea.nq;
+        for (int t = 0; t < kMaxQ; ++t) sa.qlist[t] = ea.qlist[t];
+        sa.beta = distortion_budget;
+        sa.cap_words = p.cap_words;
+        sa.row_words = ea.row_words; sa.slots = ea.slots;
+        sa.fallback = (u32*)(ws + p.off_fallback);
+        sa.mv = ea.mv;
+        sa.cap = p.small_cap; sa.region0_words = p.small_region0;
+        const bool timed = g_ev_start && g_ev_stop;
+        if (timed) SLICER_HIP(hipEventRecord(g_ev_start, st));
+        rc = dt == SLICER_F32 ? launch_small<0>(sa, p, st) : launch_small<1>(sa, p, st);
+        if (rc) return rc;
+        if (timed) SLICER_HIP(hipEventRecord(g_ev_stop, st));
+        ea.only_flagged = sa.fallback;
+    }
     rc = dt == SLICER_F32 ? launch_encode<0>(ea, st) : launch_encode<1>(ea, st);
     if (rc) return rc;
 

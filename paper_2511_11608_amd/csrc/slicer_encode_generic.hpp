@@ -29,6 +29,7 @@ struct EncArgs {
     u64* kept;              // [R][k]   class<<63 | key<<32 | idx, ascending idx
     u32* bo_idx;            // [R][k]   block-ordered indices
     u32* bo_val;            // [R][k]   block-ordered |x| (fp32 bits)
+    const u32* only_flagged;// if set: rows with a zero flag are skipped (already encoded)
     // meta
     MetaView mv;
 };
@@ -127,6 +128,7 @@ __global__ __launch_bounds__(BLOCK) void enc_generic_kernel(EncArgs a)
     const u32 lane = lane_id();
     const int wid = tid / kWave;
     const int64_t r = blockIdx.x;
+    if (a.only_flagged && !a.only_flagged[r]) return;
     const int64_t N = a.N;
     const int M = a.M, w = a.w, B2 = 2 * a.M;
     const raw_t* __restrict__ xr = (const raw_t*)a.x + (size_t)r * (size_t)N;
