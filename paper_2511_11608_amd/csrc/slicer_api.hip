@@ -95,7 +95,7 @@ Plan make_plan(int dt, int64_t rows, int64_t row_len, double keep_ratio, int n_b
         int64_t cap = std::min<int64_t>(960, (p.k + margin + 63) / 64 * 64);
         int epl = epc;
         while ((int64_t)epl * kWave < row_len) epl *= 2;
-        const int64_t region0 = std::max<int64_t>(kFineBins, p.k + (p.k + 1) / 2 + (int64_t)p.cap_words);
+        const int64_t region0 = (std::max<int64_t>(kFineBins, (p.k + 1) / 2 + (int64_t)p.cap_words) + 1) & ~(int64_t)1;
         const int64_t lds = 4 * (int64_t)small_lds_words((int)cap, (int)region0, 2 * n_blocks, nq);
         if (p.k + 64 <= cap && lds <= 64 * 1024) {
             p.small_epl = epl; p.small_cap = (int)cap; p.small_region0 = (int)region0; p.small_lds_bytes = (int)lds;
@@ -107,7 +107,10 @@ Plan make_plan(int dt, int64_t rows, int64_t row_len, double keep_ratio, int n_b
 template <int DT, int EPL>
 void launch_small_epl(const SmallArgs& sa, int lds_bytes, hipStream_t st)
 {
-    hipLaunchKernelGGL((enc_small_kernel<DT, EPL>), dim3((unsigned)sa.R), dim3(kWave), (size_t)lds_bytes, st, sa);
+    if (sa.nq == 7)     // the paper's bitwidth ladders are short; 7 = {2..8} is the benchmarked one
+        hipLaunchKernelGGL((enc_small_kernel<DT, EPL, 7>), dim3((unsigned)sa.R), dim3(kWave), (size_t)lds_bytes, st, sa);
+    else
+        hipLaunchKernelGGL((enc_small_kernel<DT, EPL, 0>), dim3((unsigned)sa.R), dim3(kWave), (size_t)lds_bytes, st, sa);
 }
 
 template <int DT>

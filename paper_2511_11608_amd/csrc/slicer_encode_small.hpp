@@ -1,25 +1,27 @@
 // Row-resident encoder for short rows: ONE WAVEFRONT PER ROW, the row held in
 // registers, every list in LDS, no workgroup barrier anywhere.
 //
-//   1. load the row (16-byte coalesced loads), 10-bit histogram of the magnitude
-//      key's top bits in LDS, scan from the top -> the bin that holds rank k-1;
-//   2. ordered compaction of everything at or above that bin into a short list L
-//      (ascending index; it contains the kept set plus the undecided bin);
-//   3. L is bucket-sorted: 1024 fine bins, linear in the key from the list's lower
+//   1. load the row (16-byte coalesced loads); 10-bit histogram of the magnitude
+//      key's top bits in LDS; scan from the top -> the bin B1 that holds rank k-1;
+//   2. ordered compaction of everything at or above B1 into a short list L
+//      (ascending index: the kept set plus the undecided bin);
+//   3. L is bucketed into 1024 fine bins, linear in the key from the list's lower
 //      bound, both sign classes counted in one packed table; an exclusive scan from
-//      the top gives every bin's first rank, and an all-pairs comparison among the
-//      few members of a bin gives every entry its exact rank in the order
-//      "magnitude descending, lower index first" -- overall (top-K, Sec. 3.1) and
-//      within its sign class (MS, Sec. 3.2);
-//   4. block = rank / K; a stable split by block id (wave ballots) restores
-//      ascending index inside each block; the elements of rank m*K and (m+1)*K-1
-//      are the block's max and min;
+//      the top gives every bin's first rank, overall and per class.  Order
+//      statistics (rank k-1 overall for the top-K cut of Sec. 3.1; ranks j*K-1 per
+//      class for the block boundaries of Sec. 3.2) are located by binary search over
+//      the bins, one lane per boundary, and resolved inside their bin by comparing
+//      the bin's few members pairwise on "key, then lower index";
+//   4. an entry's block is the number of boundaries above it; a stable split by block
+//      id (wave ballots) restores ascending index inside each block;
 //   5. ABQ sums on integer grids, bitwidth choice, bit offsets, packing through an
 //      LDS image of the row's stream segment.
 //
 // Rows the list cannot hold (heavy ties around the threshold, more zeros than
 // dropped elements, ...) are flagged and redone by the generic kernel.
 #pragma once
+
+#include <type_traits>
 
 #include "slicer_common.hpp"
 
@@ -50,29 +52,69 @@ __device__ inline void wave_sync()
 
 __device__ inline u32 bcast(u32 v, int src) { return (u32)__builtin_amdgcn_readlane((int)v, src); }
 
-// LDS carve-up of one wave (word offsets); must match small_lds_words() on the host
+template <int CTRL, int ROW_MASK, int BANK_MASK>
+__device__ inline u32 dpp_get(u32 v)
+{
+    return (u32)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, BANK_MASK, false);
+}
+
+// Inclusive prefix sum over the 64 lanes with data-parallel-primitive moves:
+// shifts inside each row of 16 lanes, then the row totals carried across rows.
+__device__ inline u32 wave_scan_dpp(u32 v)
+{
+    u32 r = v + dpp_get<0x111, 0xf, 0xf>(v);     // row_shr:1
+    r += dpp_get<0x112, 0xf, 0xf>(v);            // row_shr:2
+    r += dpp_get<0x113, 0xf, 0xf>(v);            // row_shr:3
+    r += dpp_get<0x114, 0xf, 0xe>(r);            // row_shr:4, lanes 4..15 of a row
+    r += dpp_get<0x118, 0xf, 0xc>(r);            // row_shr:8, lanes 8..15 of a row
+    r += dpp_get<0x142, 0xa, 0xf>(r);            // lane 15 of rows 0,2 -> rows 1,3
+    r += dpp_get<0x143, 0xc, 0xf>(r);            // lane 31 -> rows 2,3
+    return r;
+}
+
+// Maximum over the 64 lanes (unsigned), same data movement as the scan.
+__device__ inline u32 wave_max_dpp(u32 v)
+{
+    u32 r = max(v, dpp_get<0x111, 0xf, 0xf>(v));
+    r = max(r, dpp_get<0x112, 0xf, 0xf>(v));
+    r = max(r, dpp_get<0x113, 0xf, 0xf>(v));
+    r = max(r, dpp_get<0x114, 0xf, 0xe>(r));
+    r = max(r, dpp_get<0x118, 0xf, 0xc>(r));
+    r = max(r, dpp_get<0x142, 0xa, 0xf>(r));
+    r = max(r, dpp_get<0x143, 0xc, 0xf>(r));
+    return bcast(r, kWave - 1);
+}
+
+// x / d for x < 2^16 and 1 <= d < 2^16 (float estimate with a +-1 repair)
+__device__ inline u32 udiv16(u32 x, u32 d)
+{
+    u32 q = (u32)((float)x * (1.0f / (float)d));
+    if (q * d > x) --q;
+    if ((q + 1) * d <= x) ++q;
+    return q;
+}
+
+// LDS carve-up of one wave (word offsets); small_lds_words() on the host must match
 struct SmallLds {
-    u32* hist;      // [region0]   coarse / fine histogram; later bo_val, bo_idx, stage
-    u32* Lraw;      // [cap]       raw element bits of the list, ascending index
-    u32* S;         // [cap]       list entries arranged by fine bin: inbin_comp << 1 | class
-    uint16_t* Lidx; // [cap]
-    uint16_t* Lr;   // [cap]       class rank of a kept entry, 0xFFFF otherwise
+    u32* hist;      // [region0]   coarse / fine histogram; later bo_val, bo_idx, stream image
+    u32* Lent;      // [cap]       list entries, ascending index: bf16 raw << 16 | idx; fp32 raw
+    u32* S;         // [cap]       entries arranged by fine bin: in-bin comp << 1 | class
+    uint16_t* Lidx; // [cap]       fp32 only: index of the entry
+    u64* thr;       // [B2]        block boundaries per class (full comps, 32-bit for bf16), [cls * M + j - 1]
+    u32* tg;        // [5][64]     boundary work table: bin, base, count, rank in bin, pair prefix
     u32* blk_start; // [B2 + 1]
     u32* vminb;     // [B2] key of the block's smallest / largest element
     u32* vmaxb;     // [B2]
     u32* run;       // [B2]
-    u32* qsel;      // [B2]
-    u32* code_off;  // [B2 + 1]
-    int* e_tab;     // [B2]
-    int* degen;     // [B2]
-    float* inv_tab; // [B2][nq]
     u64* sums;      // [B2][nq + 1]
 };
 
 __host__ __device__ inline int small_lds_words(int cap, int region0, int B2, int nq)
 {
-    int wds = region0 + cap + cap + cap / 2 + cap / 2;
-    wds += (B2 + 1) + B2 * 4 + (B2 + 1) + B2 * 2 + B2 * nq;
+    int wds = region0 + cap + cap + cap / 2;
+    wds += 2 * B2;                       // thr (u64)
+    wds += 5 * 64;                       // tg
+    wds += (B2 + 1) + B2 * 3;
     wds = (wds + 1) & ~1;
     wds += 2 * B2 * (nq + 1);
     return wds;
@@ -82,29 +124,30 @@ __device__ inline SmallLds small_carve(u32* base, int cap, int region0, int B2, 
 {
     SmallLds L;
     u32* p = base;
-    L.hist = p;            p += region0;
-    L.Lraw = p;            p += cap;
+    L.hist = p;            p += region0;           // region0 is even
+    L.Lent = p;            p += cap;
     L.S = p;               p += cap;
     L.Lidx = (uint16_t*)p; p += cap / 2;
-    L.Lr = (uint16_t*)p;   p += cap / 2;
+    L.thr = (u64*)p;       p += 2 * B2;            // cap is a multiple of 64: still 8-byte aligned
+    L.tg = p;              p += 5 * 64;
     L.blk_start = p;       p += B2 + 1;
     L.vminb = p;           p += B2;
     L.vmaxb = p;           p += B2;
     L.run = p;             p += B2;
-    L.qsel = p;            p += B2;
-    L.code_off = p;        p += B2 + 1;
-    L.e_tab = (int*)p;     p += B2;
-    L.degen = (int*)p;     p += B2;
-    L.inv_tab = (float*)p; p += B2 * nq;
     if ((p - base) & 1) ++p;
     L.sums = (u64*)p;
     return L;
 }
 
-template <int DT, int EPL>
+// NQ > 0: the number of allowed bitwidths is known at compile time (loops over the
+// candidate bitwidths unroll without predicates); NQ == 0: any number up to 16.
+template <int DT, int EPL, int NQ>
 __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
 {
     typedef Elem<DT> E;
+    typedef typename E::raw_t raw_t;
+    typedef typename std::conditional<DT == 0, u64, u32>::type comp_t;   // bf16: key + index fit 32 bits
+    constexpr int QN = NQ ? NQ : kMaxQ;
     constexpr int EPC = DT == 0 ? 4 : 8;            // elements per 16-byte chunk
     constexpr int NCH = EPL / EPC;                  // chunks per lane
     constexpr int KS = E::kKeyBits - 10;            // coarse digit = key >> KS
@@ -112,12 +155,16 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
 
     const u32 lane = lane_id();
     const int64_t r = blockIdx.x;
-    const int N = (int)a.N, M = a.M, w = a.w, B2 = 2 * a.M, nq = a.nq, cap = a.cap;
+    const int N = (int)a.N, M = a.M, w = a.w, B2 = 2 * a.M, nq = NQ ? NQ : a.nq, cap = a.cap;
     const int k = (int)a.k;
     const u32 idxmask = (1u << w) - 1u;
     SmallLds L = small_carve(smem, cap, a.region0_words, B2, nq);
 
-    // ---- 1. load the row -------------------------------------------------------
+    // entry accessors: raw bits (sign + key) and index of list entry p
+    auto ent_raw = [&](u32 p) -> u32 { const u32 e = L.Lent[p]; return DT == 0 ? e : e >> 16; };
+    auto ent_idx = [&](u32 p) -> u32 { return DT == 0 ? (u32)L.Lidx[p] : (L.Lent[p] & 0xFFFFu); };
+
+    // ---- 1. load the row, coarse histogram ------------------------------------------
     const uint4* __restrict__ xr = (const uint4*)((const char*)a.x + (size_t)r * (size_t)N * (DT == 0 ? 4 : 2));
     uint4 v[NCH];
 #pragma unroll
@@ -125,338 +172,454 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
         const int base = (c * kWave + (int)lane) * EPC;
         v[c] = base < N ? xr[c * kWave + lane] : make_uint4(0, 0, 0, 0);
     }
-    auto raw_of = [&](int c, int e) -> u32 {       // raw bits of element e of chunk c
-        const u32 wd = (DT == 0) ? (&v[c].x)[e] : (&v[c].x)[e >> 1];
-        return (DT == 0) ? wd : ((e & 1) ? wd >> 16 : wd & 0xFFFFu);
-    };
+    auto word_of = [&](int c, int d) -> u32 { return d == 0 ? v[c].x : d == 1 ? v[c].y : d == 2 ? v[c].z : v[c].w; };
 
-    for (int i = lane; i < kFineBins; i += kWave) L.hist[i] = 0;
+    {
+        uint4* h4 = (uint4*)L.hist;
+#pragma unroll
+        for (int i = 0; i < kFineBins / 4 / kWave; ++i) h4[i * kWave + lane] = make_uint4(0, 0, 0, 0);
+    }
     wave_sync();
-
-    // coarse histogram over the top 10 bits of the key
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
         if ((c * kWave + (int)lane) * EPC < N) {
 #pragma unroll
-            for (int e = 0; e < EPC; ++e) atomicAdd(&L.hist[E::key((typename E::raw_t)raw_of(c, e)) >> KS], 1u);
+            for (int d = 0; d < 4; ++d) {
+                const u32 wd = word_of(c, d);
+                if (DT == 0) {
+                    atomicAdd(&L.hist[(wd & 0x7FFFFFFFu) >> KS], 1u);
+                } else {
+                    atomicAdd(&L.hist[(wd >> KS) & 0x3FFu], 1u);
+                    atomicAdd(&L.hist[(wd >> (16 + KS)) & 0x3FFu], 1u);
+                }
+            }
         }
     }
     wave_sync();
 
-    // scan from the top: bin of rank k-1, count above it, highest occupied bin
-    u32 B1 = 0, c_gt = 0, cnt1 = 0, top_bin = 0;
+    // scan from the top: the bin of rank k-1 and the count above it
+    u32 B1 = 0, c_gt = 0, cnt1 = 0;
     {
         const int hi = kFineBins - (int)lane * 16;
         u32 cs[16];
+        const uint4* h4 = (const uint4*)(L.hist + hi - 16);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint4 t = h4[3 - j];
+            cs[4 * j + 0] = t.w; cs[4 * j + 1] = t.z; cs[4 * j + 2] = t.y; cs[4 * j + 3] = t.x;
+        }
         u32 local = 0;
 #pragma unroll
-        for (int j = 0; j < 16; ++j) { cs[j] = L.hist[hi - 1 - j]; local += cs[j]; }
-        const u32 incl = wave_incl_scan(local), excl = incl - local;
+        for (int j = 0; j < 16; ++j) local += cs[j];          // cs[j] = hist[hi - 1 - j]
+        const u32 incl = wave_scan_dpp(local), excl = incl - local;
         const u32 rem = k > 0 ? (u32)(k - 1) : 0u;
-        const bool mine = local > 0 && excl <= rem && rem < incl;
-        u32 b = 0, ab = 0, cn = 0, tb = 0;
-        {
-            u32 acc = excl;
-            bool found = false, seen = false;
+        // bins of this lane (from its top) that end at or before rank rem, and their total
+        u32 acc = excl, nb = 0, ab = excl;
 #pragma unroll
-            for (int j = 0; j < 16; ++j) {
-                if (!seen && cs[j]) { seen = true; tb = (u32)(hi - 1 - j); }
-                if (!found && rem < acc + cs[j]) { found = true; b = (u32)(hi - 1 - j); ab = acc; cn = cs[j]; }
-                acc += cs[j];
-            }
+        for (int j = 0; j < 16; ++j) {
+            acc += cs[j];
+            const bool below = acc <= rem;
+            nb += below ? 1u : 0u;
+            ab = below ? acc : ab;
         }
-        const u64 mm = __ballot(mine);
-        const u64 occ = __ballot(local > 0);
-        if (mm) { const int src = (int)__builtin_ctzll(mm); B1 = bcast(b, src); c_gt = bcast(ab, src); cnt1 = bcast(cn, src); }
-        if (occ) top_bin = bcast(tb, (int)__builtin_ctzll(occ));
+        const u64 mm = __ballot(local > 0 && excl <= rem && rem < incl);
+        if (mm) {
+            const int src = (int)__builtin_ctzll(mm);
+            B1 = (u32)(kFineBins - src * 16 - 1) - bcast(nb, src);
+            c_gt = bcast(ab, src);
+            cnt1 = L.hist[B1];
+        }
     }
     wave_sync();
 
-    // the list must hold everything from bin B1 up; fine bins must leave room for
-    // the in-bin key bits, the index and the class bit in one 32-bit word
-    const u32 t_lo = B1 << KS;                                   // smallest key of bin B1
-    const u32 range = (((top_bin + 1u) << KS) - 1u) - t_lo;      // largest possible key - t_lo
-    const int sh = range < (u32)kFineBins ? 0 : (32 - __clz((int)range)) - 10;
-    const bool hard = (k > 0) && ((int)(c_gt + cnt1) > cap || sh + w > 31);
-    if (hard) {
+    // the list must hold everything from bin B1 up
+    const u32 t_lo = (B1 << KS) > 1u ? (B1 << KS) : 1u;          // smallest non-zero key of bin B1
+    if (k > 0 && (int)(c_gt + cnt1) > cap) {
         if (lane == 0) a.fallback[r] = 1u;
         return;
     }
 
-    // ---- 2. ordered compaction into L ----------------------------------------------
+    // ---- 2. ordered compaction into L -------------------------------------------------
     u32 nL = 0;
     if (k > 0) {
+        u32 cntc[NCH];
+        const u32 C16 = (0x8000u - t_lo) * 0x10001u;            // bf16: bit 15 / 31 of (key + C16) <=> key >= t_lo
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
-            u32 cntl = 0;
+            u32 n1 = 0;
 #pragma unroll
-            for (int e = 0; e < EPC; ++e) {
-                const u32 key = E::key((typename E::raw_t)raw_of(c, e));
-                cntl += (key >= t_lo && key != 0u) ? 1u : 0u;
+            for (int d = 0; d < 4; ++d) {
+                const u32 wd = word_of(c, d);
+                if (DT == 0) n1 += ((wd & 0x7FFFFFFFu) >= t_lo) ? 1u : 0u;
+                else n1 += (u32)__popc(((wd & 0x7FFF7FFFu) + C16) & 0x80008000u);
             }
-            const u32 incl = wave_incl_scan(cntl);
-            u32 pos = nL + incl - cntl;
-            const int base = (c * kWave + (int)lane) * EPC;
+            cntc[c] = n1;
+        }
+        // exclusive positions: three chunk counts share one scan (10-bit fields, totals <= 512)
+        u32 basec[NCH];
 #pragma unroll
-            for (int e = 0; e < EPC; ++e) {
-                const u32 raw = raw_of(c, e);
-                const u32 key = E::key((typename E::raw_t)raw);
-                if (key >= t_lo && key != 0u) {
-                    if (pos < (u32)cap) { L.Lraw[pos] = raw; L.Lidx[pos] = (uint16_t)(base + e); }
-                    ++pos;
+        for (int g = 0; g < (NCH + 2) / 3; ++g) {
+            u32 pk = cntc[3 * g];
+            if (3 * g + 1 < NCH) pk |= cntc[3 * g + 1] << 10;
+            if (3 * g + 2 < NCH) pk |= cntc[3 * g + 2] << 20;
+            const u32 incl = wave_scan_dpp(pk);
+            const u32 tot = bcast(incl, kWave - 1);
+            const u32 ex = incl - pk;
+#pragma unroll
+            for (int j = 0; j < 3; ++j) {
+                if (3 * g + j < NCH) {
+                    basec[3 * g + j] = nL + ((ex >> (10 * j)) & 0x3FFu);
+                    nL += (tot >> (10 * j)) & 0x3FFu;
                 }
             }
-            nL += bcast(incl, kWave - 1);
         }
-        if (nL > (u32)cap) nL = (u32)cap;      // cannot happen: nL <= c_gt + cnt1 <= cap
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            u32 pos = basec[c];
+            const u32 idx0 = (u32)((c * kWave + (int)lane) * EPC);
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                const u32 wd = word_of(c, d);
+                if (DT == 0) {
+                    if ((wd & 0x7FFFFFFFu) >= t_lo) { L.Lent[pos] = wd; L.Lidx[pos] = (uint16_t)(idx0 + d); ++pos; }
+                } else {
+                    const u32 f = ((wd & 0x7FFF7FFFu) + C16) & 0x80008000u;
+                    if (f & 0x8000u) { L.Lent[pos] = (wd << 16) | (idx0 + 2 * d); ++pos; }
+                    if (f & 0x80000000u) { L.Lent[pos] = (wd & 0xFFFF0000u) | (idx0 + 2 * d + 1); ++pos; }
+                }
+            }
+        }
     }
-    for (int i = lane; i < kFineBins; i += kWave) L.hist[i] = 0;
+    {
+        uint4* h4 = (uint4*)L.hist;
+#pragma unroll
+        for (int i = 0; i < kFineBins / 4 / kWave; ++i) h4[i * kWave + lane] = make_uint4(0, 0, 0, 0);
+    }
     wave_sync();
 
-    // ---- 3. fine bins, ranks ----------------------------------------------------------
+    // ---- 3. fine bins ---------------------------------------------------------------------
+    // 1024 bins, linear in (key - t_lo) >> sh with sh from the largest key of the list; a full
+    // comp (fine bin, in-bin key bits, index) and an S entry (in-bin bits, index, class) must
+    // fit their words
     const int nslots = (int)((nL + kWave - 1) / kWave);
+    u32 kmax = t_lo;
+    for (int s = 0; s < nslots; ++s) {
+        const u32 p = s * kWave + lane;
+        if (p < nL) kmax = max(kmax, E::key((raw_t)ent_raw(p)));
+    }
+    kmax = wave_max_dpp(kmax);
+    const u32 range = kmax - t_lo;
+    const int sh = range < (u32)kFineBins ? 0 : (32 - __clz((int)range)) - 10;
+    if (sh + w > 31 || (DT != 0 && 10 + sh + w > 32)) {
+        if (lane == 0) a.fallback[r] = 1u;
+        return;
+    }
     for (int s = 0; s < nslots; ++s) {
         const u32 p = s * kWave + lane;
         if (p < nL) {
-            const u32 raw = L.Lraw[p];
-            const u32 d = (E::key((typename E::raw_t)raw) - t_lo) >> sh;
-            atomicAdd(&L.hist[d], E::neg((typename E::raw_t)raw) ? 0x10000u : 1u);
+            const u32 raw = ent_raw(p);
+            atomicAdd(&L.hist[(E::key((raw_t)raw) - t_lo) >> sh], E::neg((raw_t)raw) ? 0x10000u : 1u);
         }
     }
     wave_sync();
+    u32 n_pos, n_neg;
     {   // exclusive prefix from the top, per class; repack as pos | neg << 11 | fill << 22
         const int hi = kFineBins - (int)lane * 16;
         u32 cs[16];
+        uint4* h4 = (uint4*)(L.hist + hi - 16);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint4 t = h4[3 - j];
+            cs[4 * j + 0] = t.w; cs[4 * j + 1] = t.z; cs[4 * j + 2] = t.y; cs[4 * j + 3] = t.x;
+        }
         u32 local = 0;
 #pragma unroll
-        for (int j = 0; j < 16; ++j) { cs[j] = L.hist[hi - 1 - j]; local += cs[j]; }
-        u32 acc = wave_incl_scan(local) - local;
+        for (int j = 0; j < 16; ++j) local += cs[j];
+        const u32 incl = wave_scan_dpp(local);
+        const u32 tot = bcast(incl, kWave - 1);
+        n_pos = tot & 0xFFFFu; n_neg = tot >> 16;       // class sizes of L (of the kept set once cut)
+        u32 acc = incl - local;
+        u32 o[16];
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
-            L.hist[hi - 1 - j] = (acc & 0xFFFFu) | ((acc >> 16) << 11);
+            o[j] = (acc & 0xFFFFu) | ((acc >> 16) << 11);
             acc += cs[j];
         }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) h4[3 - j] = make_uint4(o[4 * j + 3], o[4 * j + 2], o[4 * j + 1], o[4 * j + 0]);
     }
     wave_sync();
     const u32 inmask = (1u << sh) - 1u;
     for (int s = 0; s < nslots; ++s) {
         const u32 p = s * kWave + lane;
         if (p < nL) {
-            const u32 raw = L.Lraw[p];
-            const u32 rel = E::key((typename E::raw_t)raw) - t_lo;
+            const u32 raw = ent_raw(p);
+            const u32 rel = E::key((raw_t)raw) - t_lo;
             const u32 old = atomicAdd(&L.hist[rel >> sh], 1u << 22);
             const u32 at = (old & 0x7FFu) + ((old >> 11) & 0x7FFu) + (old >> 22);
-            const u32 comp = ((rel & inmask) << w) | (idxmask - (u32)L.Lidx[p]);
-            L.S[at] = (comp << 1) | E::neg((typename E::raw_t)raw);
+            L.S[at] = ((((rel & inmask) << w) | (idxmask - ent_idx(p))) << 1) | E::neg((raw_t)raw);
         }
     }
     wave_sync();
-    u32 n_pos = 0, n_neg = 0;
-    for (int s = 0; s < nslots; ++s) {
-        const u32 p = s * kWave + lane;
-        bool kept = false;
-        u32 neg = 0;
-        if (p < nL) {
-            const u32 raw = L.Lraw[p];
-            neg = E::neg((typename E::raw_t)raw);
-            const u32 rel = E::key((typename E::raw_t)raw) - t_lo;
-            const u32 wd = L.hist[rel >> sh];
-            const u32 pe = wd & 0x7FFu, ne = (wd >> 11) & 0x7FFu, cnt = wd >> 22;
-            const u32 comp = ((rel & inmask) << w) | (idxmask - (u32)L.Lidx[p]);
-            u32 gt_all = 0, gt_same = 0;
-            if (cnt > 1) {
-                const u32 base = pe + ne;
-                for (u32 j = 0; j < cnt; ++j) {
-                    const u32 o = L.S[base + j];
-                    const u32 g = (o >> 1) > comp ? 1u : 0u;
-                    gt_all += g;
-                    gt_same += g & ((o & 1u) == neg ? 1u : 0u);
-                }
-            }
-            kept = (pe + ne + gt_all) < (u32)k;               // overall rank < k (ATKF)
-            L.Lr[p] = kept ? (uint16_t)((neg ? ne : pe) + gt_same) : (uint16_t)0xFFFFu;
+
+    // ---- top-K cut: the comp of overall rank k-1 (ATKF) -----------------------------------------
+    // full comp of an entry: fine bin, in-bin key bits, inverted index
+    const int cshift = sh + w;
+    comp_t thrK = 0;                                // every entry of L is kept when nL <= k
+    if (nL > (u32)k) {
+        int lo = 0, hi = kFineBins - 1;             // smallest bin whose first overall rank is <= k-1
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            const u32 wd = L.hist[mid];
+            if ((wd & 0x7FFu) + ((wd >> 11) & 0x7FFu) <= (u32)(k - 1)) hi = mid; else lo = mid + 1;
         }
-        n_pos += (u32)__popcll(__ballot(kept && !neg));
-        n_neg += (u32)__popcll(__ballot(kept && neg));
+        const u32 wd = L.hist[lo];
+        const u32 pe = wd & 0x7FFu, ne = (wd >> 11) & 0x7FFu, cnt = wd >> 22, base = pe + ne;
+        const u32 rem = (u32)(k - 1) - base;
+        u32 kp = 0, kn = 0, tin = 0;
+        for (u32 g = 0; g < cnt; g += kWave) {       // members in groups of 64, one per lane
+            const u32 i = g + lane;
+            u32 me = 0, gt = 0;
+            if (i < cnt) {
+                me = L.S[base + i];
+                for (u32 j = 0; j < cnt; ++j) gt += (L.S[base + j] >> 1) > (me >> 1) ? 1u : 0u;
+            }
+            const bool in = i < cnt && gt <= rem;
+            kp += (u32)__popcll(__ballot(in && !(me & 1u)));
+            kn += (u32)__popcll(__ballot(in && (me & 1u)));
+            const u64 hit = __ballot(i < cnt && gt == rem);
+            if (hit) tin = bcast(me >> 1, (int)__builtin_ctzll(hit));
+        }
+        thrK = ((comp_t)lo << cshift) | (comp_t)tin;
+        n_pos = pe + kp; n_neg = ne + kn;
     }
     const u32 n = n_pos + n_neg;
     const u32 n_cls[2] = { n_pos, n_neg };
     const u32 Kc[2] = { n_pos / (u32)M, n_neg / (u32)M };
+
+    // ---- block boundaries: comps of class ranks j*K-1, one lane per boundary ------------------------
+    const int nt0 = Kc[0] ? M - 1 : 0, nt1 = Kc[1] ? M - 1 : 0, ntg = nt0 + nt1;
+    u32* tg_bin = L.tg; u32* tg_base = L.tg + 64; u32* tg_cnt = L.tg + 128; u32* tg_rem = L.tg + 192; u32* tg_pre = L.tg + 256;
+    {
+        const bool act = (int)lane < ntg;
+        const int cls = (int)lane >= nt0 ? 1 : 0;
+        const int j = (cls ? (int)lane - nt0 : (int)lane) + 1;
+        const u32 R = act ? (u32)j * Kc[cls] - 1u : 0u;
+        int lo = 0, hi = kFineBins - 1;             // smallest bin whose first class rank is <= R
+        for (int it = 0; it < 10; ++it) {
+            const int mid = (lo + hi) >> 1;
+            const u32 wd = L.hist[mid];
+            const u32 pc = cls ? (wd >> 11) & 0x7FFu : wd & 0x7FFu;
+            if (pc <= R) hi = mid; else lo = mid + 1;
+        }
+        const u32 wd = L.hist[lo];
+        const u32 pe = wd & 0x7FFu, ne = (wd >> 11) & 0x7FFu;
+        const u32 cnt = act ? wd >> 22 : 0u;
+        const u32 incl = wave_scan_dpp(cnt);
+        tg_bin[lane] = (u32)lo; tg_base[lane] = pe + ne; tg_cnt[lane] = cnt;
+        tg_rem[lane] = R - (cls ? ne : pe);
+        tg_pre[lane] = incl - cnt;
+        const u32 npairs = bcast(incl, kWave - 1);
+        wave_sync();
+        // one lane per (boundary, member of its bin): the member of the boundary's class
+        // with exactly `rem` class-mates above it is the boundary element
+        for (u32 g = 0; g < npairs; g += kWave) {
+            const u32 pr = g + lane;
+            if (pr < npairs) {
+                int tl = 0, th = ntg - 1;           // boundary t with tg_pre[t] <= pr < tg_pre[t] + tg_cnt[t]
+                while (tl < th) {
+                    const int mid = (tl + th + 1) >> 1;
+                    if (tg_pre[mid] <= pr) tl = mid; else th = mid - 1;
+                }
+                const int t = tl;
+                const u32 tc = (u32)(t >= nt0 ? 1 : 0);
+                const u32 bs = tg_base[t], cn = tg_cnt[t];
+                const u32 me = L.S[bs + (pr - tg_pre[t])];
+                if ((me & 1u) == tc) {
+                    u32 gt = 0;
+                    for (u32 jj = 0; jj < cn; ++jj) {
+                        const u32 o = L.S[bs + jj];
+                        gt += ((o & 1u) == tc && (o >> 1) > (me >> 1)) ? 1u : 0u;
+                    }
+                    if (gt == tg_rem[t]) {
+                        const int jb = tc ? t - nt0 : t;
+                        ((comp_t*)L.thr)[tc * (u32)M + (u32)jb] = ((comp_t)tg_bin[t] << cshift) | (comp_t)(me >> 1);
+                    }
+                }
+            }
+        }
+    }
 
     // block starts in closed form (K, ..., K, K + remainder per class)
     if ((int)lane < B2) {
         const int s = (int)lane >= M ? 1 : 0, m = (int)lane - s * M;
         L.blk_start[lane] = (s ? n_pos : 0u) + (u32)m * Kc[s];
         L.run[lane] = 0;
-        L.vminb[lane] = 0; L.vmaxb[lane] = 0;
+        L.vminb[lane] = 0xFFFFFFFFu; L.vmaxb[lane] = 0;
     }
     if (lane == 0) L.blk_start[B2] = n;
     wave_sync();
 
-    // ---- 4. blocks, stable split by block, block-ordered arrays ---------------------------
-    // (the histogram region is free now: it becomes bo_val | bo_idx | stream image)
-    u32* bo_val = L.hist;
-    uint16_t* bo_idx = (uint16_t*)(L.hist + k);
-    u32* stage = L.hist + k + (k + 1) / 2;
+    // ---- 4. blocks, stable split by block, block-ordered arrays -----------------------------------
+    // S and the fine bins are dead (boundaries are resolved): S's storage takes the
+    // block-ordered values, the histogram region the indices and the stream image
+    u32* bo_val = L.S;
+    uint16_t* bo_idx = (uint16_t*)(L.hist);
+    u32* stage = L.hist + (k + 1) / 2;
+    const comp_t* thr = (const comp_t*)L.thr;
     int nbits = 0;
     while ((1 << nbits) < B2) ++nbits;
+    int msteps = 0;
+    while ((1 << msteps) < M) ++msteps;
     for (int s = 0; s < nslots; ++s) {
         const u32 p = s * kWave + lane;
         bool kept = false;
-        u32 b = 0, raw = 0, idx = 0;
+        u32 b = 0, key = 0, idx = 0;
         if (p < nL) {
-            const u32 rr = L.Lr[p];
-            if (rr != 0xFFFFu) {
+            const u32 raw = ent_raw(p);
+            key = E::key((raw_t)raw);
+            idx = ent_idx(p);
+            const u32 rel = key - t_lo;
+            const comp_t comp = ((comp_t)(rel >> sh) << cshift) | (comp_t)(((rel & inmask) << w) | (idxmask - idx));
+            if (comp >= thrK) {
                 kept = true;
-                raw = L.Lraw[p];
-                idx = L.Lidx[p];
-                const int cls = (int)E::neg((typename E::raw_t)raw);
-                const u32 K = Kc[cls];
+                const u32 cls = E::neg((raw_t)raw);
                 u32 m = (u32)(M - 1);
-                if (K) {
-                    u32 qd = (u32)((float)rr * (1.0f / (float)K));       // rr / K with a +-1 repair
-                    if (qd * K > rr) --qd;
-                    if ((qd + 1) * K <= rr) ++qd;
-                    m = qd < (u32)(M - 1) ? qd : (u32)(M - 1);
+                if (Kc[cls]) {                      // block = number of boundaries above this entry
+                    int lo = 0, hi = M - 1;
+                    for (int it = 0; it < msteps; ++it) {
+                        const int mid = (lo + hi) >> 1;
+                        if (lo < hi) { if (thr[cls * (u32)M + (u32)mid] > comp) lo = mid + 1; else hi = mid; }
+                    }
+                    m = (u32)lo;
                 }
-                b = (u32)cls * (u32)M + m;
-                const u32 last = (m < (u32)(M - 1)) ? (m + 1) * K - 1 : n_cls[cls] - 1;
-                if (rr == m * K) L.vmaxb[b] = E::key((typename E::raw_t)raw);
-                if (rr == last) L.vminb[b] = E::key((typename E::raw_t)raw);
+                b = cls * (u32)M + m;
+                atomicMin(&L.vminb[b], key);
+                atomicMax(&L.vmaxb[b], key);
             }
         }
-        u64 peers = __ballot(kept);
+        // lanes of this slot in the same block: one ballot per bit of the block id
+        const u64 km = __ballot(kept);
+        u32 plo = (u32)km, phi = (u32)(km >> 32);
         for (int bit = 0; bit < nbits; ++bit) {
-            const bool on = (b >> bit) & 1u;
-            const u64 bal = __ballot(kept && on);
-            peers &= on ? bal : ~bal;
+            const u64 bal = __ballot(kept && ((b >> bit) & 1u));
+            const u32 onm = (u32)__builtin_amdgcn_sbfe((int)b, (u32)bit, 1u);   // all ones if the bit is set
+            plo &= ~((u32)bal ^ onm);
+            phi &= ~((u32)(bal >> 32) ^ onm);
         }
-        const u32 before = mask_rank(peers);
+        const u32 before = __builtin_amdgcn_mbcnt_hi(phi, __builtin_amdgcn_mbcnt_lo(plo, 0u));
         u32 basep = 0;
         if (kept) basep = L.run[b];
         wave_sync();
         if (kept) {
-            if (before == 0) L.run[b] = basep + (u32)__popcll(peers);
+            if (before == 0) L.run[b] = basep + (u32)__popc(plo) + (u32)__popc(phi);
             const u32 pos = L.blk_start[b] + basep + before;
-            if (pos < (u32)k) { bo_val[pos] = E::value_bits(E::key((typename E::raw_t)raw)); bo_idx[pos] = (uint16_t)idx; }
+            bo_val[pos] = E::value_bits(key);
+            bo_idx[pos] = (uint16_t)idx;
         }
         wave_sync();
     }
 
-    // ---- 5. ABQ tables --------------------------------------------------------------------------
-    if ((int)lane < B2) {
-        const u32 cnt = L.blk_start[lane + 1] - L.blk_start[lane];
-        int dg = 1, e = 0;
-        float rng = 0.f;
+    // ---- 5. ABQ -----------------------------------------------------------------------------------
+    // Each block is walked by kWave / B2 lanes, each lane a contiguous run of the block-ordered
+    // list, so a lane's quantiser constants and partial sums live in registers.
+    const u32 lpb = (u32)kWave / (u32)B2;
+    const u32 myb = udiv16(lane, lpb), sub = lane - myb * lpb;
+    const bool lane_on = myb < (u32)B2;
+    u32 r0 = 0, r1 = 0, bs0 = 0;
+    float vmin = 0.f, rng = 0.f;
+    int e = 0, dg = 1;
+    u32 vmaxbits = 0;
+    if (lane_on) {
+        bs0 = L.blk_start[myb];
+        const u32 be = L.blk_start[myb + 1], cnt = be - bs0;
+        const u32 perb = udiv16(cnt + lpb - 1, lpb);
+        r0 = bs0 + sub * perb; r0 = r0 < be ? r0 : be;
+        r1 = r0 + perb < be ? r0 + perb : be;
         if (cnt) {
-            const u32 lo = E::value_bits(L.vminb[lane]), hi = E::value_bits(L.vmaxb[lane]);
-            rng = __uint_as_float(hi) - __uint_as_float(lo);
+            const u32 lo = E::value_bits(L.vminb[myb]);
+            vmaxbits = E::value_bits(L.vmaxb[myb]);
+            vmin = __uint_as_float(lo);
+            rng = __uint_as_float(vmaxbits) - vmin;
             dg = !(rng >= 0x1p-100f);
-            e = ilogb_bits(hi) + 1;
+            e = ilogb_bits(vmaxbits) + 1;
         }
-        L.degen[lane] = dg; L.e_tab[lane] = e;
-        for (int t = 0; t < nq; ++t) {
-            const float Lq = (float)((1u << a.qlist[t]) - 1u);
-            L.inv_tab[lane * nq + t] = dg ? 0.f : Lq / rng;
-            L.sums[lane * (nq + 1) + t] = 0;
-        }
-        L.sums[lane * (nq + 1) + nq] = 0;
+    }
+    // longest run of any lane: the largest block holds K + (n mod M) entries
+    const u32 mc0 = n_pos - Kc[0] * (u32)(M - 1), mc1 = n_neg - Kc[1] * (u32)(M - 1);
+    const u32 T = udiv16((mc0 > mc1 ? mc0 : mc1) + lpb - 1, lpb);
+    float Lq[QN], inv[QN];
+#pragma unroll
+    for (int t = 0; t < QN; ++t) {
+        Lq[t] = (NQ || t < nq) ? (float)((1u << a.qlist[t]) - 1u) : 1.f;
+        inv[t] = dg ? 0.f : Lq[t] / rng;
+    }
+    if (lane_on && sub == 0) {
+        for (int t = 0; t <= nq; ++t) L.sums[myb * (nq + 1) + t] = 0;
     }
     wave_sync();
-
-    // integer residual / energy sums; each lane walks a contiguous run of the
-    // block-ordered list, so its partial sums stay in registers across a block
-    const u32 per = (n + kWave - 1) / kWave;
     {
-        const u32 p0 = lane * per, p1 = (p0 + per < n) ? p0 + per : n;
-        int cur = -1;
-        u32 acc[kMaxQ];
         u64 accE = 0;
+        for (u32 i0 = 0; i0 < T; i0 += 8) {             // u32 partial sums hold 8 residuals of 2^28
+            u32 acc[QN];
 #pragma unroll
-        for (int t = 0; t < kMaxQ; ++t) acc[t] = 0;
-        float vmin = 0.f;
-        int e = 0, dg = 1;
-        u32 held = 0;
-        auto flush = [&]() {
-            if (cur < 0) return;
+            for (int t = 0; t < QN; ++t) acc[t] = 0;
+            const u32 i1 = i0 + 8 < T ? i0 + 8 : T;
+            for (u32 i = i0; i < i1; ++i) {
+                const u32 p = r0 + i;
+                if (p < r1) {
+                    const float av = __uint_as_float(bo_val[p]);
+                    const u64 A = (u64)(u32)rintf(ldexpf(av, 20 - e));   // 20-bit energy grid scaled to vmax
+                    accE += A * A;
+                    const float d = av - vmin;
 #pragma unroll
-            for (int t = 0; t < kMaxQ; ++t)
-                if (t < nq && acc[t]) { atomicAdd(&L.sums[cur * (nq + 1) + t], (u64)acc[t]); acc[t] = 0; }
-            if (accE) { atomicAdd(&L.sums[cur * (nq + 1) + nq], accE); accE = 0; }
-            held = 0;
-        };
-        for (u32 p = p0; p < p1; ++p) {
-            int b = cur < 0 ? 0 : cur;
-            while (b < B2 - 1 && p >= L.blk_start[b + 1]) ++b;
-            if (b != cur || held >= 8) {
-                flush();
-                cur = b;
-                vmin = __uint_as_float(E::value_bits(L.vminb[b]));
-                e = L.e_tab[b]; dg = L.degen[b];
-            }
-            const u32 abits = bo_val[p];
-            const u64 A = energy_grid(abits, e);
-            accE += A * A;
-            ++held;
-            if (!dg) {
-                const float d = __uint_as_float(abits) - vmin;
-#pragma unroll
-                for (int t = 0; t < kMaxQ; ++t) {
-                    if (t < nq) {
-                        const float Lq = (float)((1u << a.qlist[t]) - 1u);
-                        const float y = d * L.inv_tab[b * nq + t];
-                        const float c = fminf(fmaxf(rintf(y), 0.f), Lq);
-                        const int rho = (int)rintf((y - c) * 32768.0f);
-                        acc[t] += (u32)(rho * rho);
+                    for (int t = 0; t < QN; ++t) {
+                        if (NQ || t < nq) {
+                            const float y = d * inv[t];
+                            const float c = fminf(rintf(y), Lq[t]);          // y >= 0: no lower clamp needed
+                            const int rho = (int)rintf((y - c) * 32768.0f);
+                            acc[t] += (u32)(rho * rho);
+                        }
                     }
                 }
             }
+#pragma unroll
+            for (int t = 0; t < QN; ++t)
+                if ((NQ || t < nq) && acc[t]) atomicAdd(&L.sums[myb * (nq + 1) + t], (u64)acc[t]);
         }
-        flush();
+        if (accE) atomicAdd(&L.sums[myb * (nq + 1) + nq], accE);
     }
     wave_sync();
 
-    // smallest feasible bitwidth per block; meta; bit offsets
-    u32 myq = 0, mybits = 0;
+    // smallest feasible bitwidth per block (every lane of the block evaluates it); meta
+    u32 myq = (u32)a.qlist[0], flag = 0;
     float my_inv = 0.f;
-    if ((int)lane < B2) {
-        const u32 cnt = L.blk_start[lane + 1] - L.blk_start[lane];
-        float vmin = 0.f, vmax = 0.f;
-        int q = a.qlist[0], tsel = 0;
-        u32 flag = 0;
-        if (cnt) {
-            vmin = __uint_as_float(E::value_bits(L.vminb[lane]));
-            vmax = __uint_as_float(E::value_bits(L.vmaxb[lane]));
-            if (!L.degen[lane]) {
-                const float rng = vmax - vmin;
-                const int e = L.e_tab[lane];
-                const double rhs = a.beta * ldexp((double)L.sums[lane * (nq + 1) + nq], 2 * e - 40);
-                int chosen = -1;
-                for (int t = 0; t < nq && chosen < 0; ++t) {
-                    const float Lq = (float)((1u << a.qlist[t]) - 1u);
-                    const float o = rng / Lq;
-                    const double lhs = ((double)o * (double)o) * (double)L.sums[lane * (nq + 1) + t] * 0x1p-30;
-                    if (lhs <= rhs) chosen = t;
-                }
-                if (chosen < 0) { chosen = nq - 1; flag = 0x80u; }
-                tsel = chosen; q = a.qlist[chosen];
+    const u32 mycnt = lane_on ? L.blk_start[myb + 1] - bs0 : 0u;
+    if (lane_on && mycnt && !dg) {
+        const double rhs = a.beta * ldexp((double)L.sums[myb * (nq + 1) + nq], 2 * e - 40);
+        flag = 0x80u;                                   // cleared by the first feasible bitwidth
+#pragma unroll
+        for (int t = 0; t < QN; ++t) {
+            if ((NQ || t < nq) && flag) {
+                const float o = rng / Lq[t];
+                const double lhs = ((double)o * (double)o) * (double)L.sums[myb * (nq + 1) + t] * 0x1p-30;
+                myq = (u32)a.qlist[t]; my_inv = inv[t];   // stays at the largest if none is feasible
+                if (lhs <= rhs) flag = 0;
             }
-            my_inv = L.inv_tab[lane * nq + tsel];
         }
-        myq = (u32)q; mybits = cnt * (u32)q;
-        const size_t mi = (size_t)r * (size_t)B2 + lane;
-        a.mv.vmin[mi] = vmin;
-        a.mv.vmax[mi] = vmax;
-        a.mv.q[mi] = (uint8_t)((u32)q | flag);
     }
-    const u32 incl_bits = wave_incl_scan(mybits);
+    if (lane_on && sub == 0) {
+        const size_t mi = (size_t)r * (size_t)B2 + myb;
+        a.mv.vmin[mi] = mycnt ? vmin : 0.f;
+        a.mv.vmax[mi] = mycnt ? __uint_as_float(vmaxbits) : 0.f;
+        a.mv.q[mi] = (uint8_t)(myq | flag);
+    }
+    // bit offsets of the blocks' code sections: scan over one lane per block
+    const u32 mybits = (lane_on && sub == 0) ? mycnt * myq : 0u;
+    const u32 incl_bits = wave_scan_dpp(mybits);
     const u32 code_bits = bcast(incl_bits, kWave - 1);
-    wave_sync();                      // inv_tab reads above are done: reuse its first B2 words
-    if ((int)lane < B2) {
-        L.qsel[lane] = myq;
-        L.code_off[lane] = incl_bits - mybits;
-        L.inv_tab[lane] = my_inv;     // inverse step at the chosen bitwidth
-    }
+    const u32 my_off = incl_bits - mybits;              // valid in the block's first lane ...
+    const u32 coff = (u32)__shfl((int)my_off, (int)(myb * lpb));   // ... fetched by its other lanes
     const u32 idx_bits = n * (u32)w;
     const u32 row_bits = idx_bits + code_bits;
     u32 row_words = (row_bits + 31u) >> 5;
@@ -466,27 +629,25 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
 
     // ---- packing ----------------------------------------------------------------------------------
     {
-        const u32 p0 = lane * per, p1 = (p0 + per < n) ? p0 + per : n;
-        int b = 0;
-        for (u32 p = p0; p < p1; ++p) {
-            while (b < B2 - 1 && p >= L.blk_start[b + 1]) ++b;
-            const u32 q = L.qsel[b];
-            u32 c = 0;
-            if (!L.degen[b]) {
-                const float Lq = (float)((1u << q) - 1u);
-                const float vmin = __uint_as_float(E::value_bits(L.vminb[b]));
-                const float y = (__uint_as_float(bo_val[p]) - vmin) * L.inv_tab[b];
-                c = (u32)fminf(fmaxf(rintf(y), 0.f), Lq);
-            }
-            {   // index field
-                const u32 P = p * (u32)w, wi = P >> 5, sft = P & 31u, val = bo_idx[p];
-                atomicOr(&stage[wi], val << sft);
-                if (sft + (u32)w > 32u) atomicOr(&stage[wi + 1], val >> (32u - sft));
-            }
-            {   // code field
-                const u32 P = idx_bits + L.code_off[b] + (p - L.blk_start[b]) * q, wi = P >> 5, sft = P & 31u;
-                atomicOr(&stage[wi], c << sft);
-                if (sft + q > 32u) atomicOr(&stage[wi + 1], c >> (32u - sft));
+        const float Lsel = (float)((1u << myq) - 1u);
+        for (u32 i = 0; i < T; ++i) {
+            const u32 p = r0 + i;
+            if (p < r1) {
+                u32 c = 0;
+                if (!dg) {
+                    const float y = (__uint_as_float(bo_val[p]) - vmin) * my_inv;
+                    c = (u32)fminf(rintf(y), Lsel);
+                }
+                {   // index field
+                    const u32 P = p * (u32)w, wi = P >> 5, sft = P & 31u, val = bo_idx[p];
+                    atomicOr(&stage[wi], val << sft);
+                    if (sft + (u32)w > 32u) atomicOr(&stage[wi + 1], val >> (32u - sft));
+                }
+                {   // code field
+                    const u32 P = idx_bits + coff + (p - bs0) * myq, wi = P >> 5, sft = P & 31u;
+                    atomicOr(&stage[wi], c << sft);
+                    if (sft + myq > 32u) atomicOr(&stage[wi + 1], c >> (32u - sft));
+                }
             }
         }
     }
