@@ -58,7 +58,7 @@ struct Plan {
     int64_t k;
     int w, qmax;
     u64 cap_words;          // per row
-    size_t off_row_words, off_slots, off_kept, off_bo_idx, off_bo_val, off_fallback, total;
+    size_t off_row_words, off_slots, off_kept, off_bo_idx, off_bo_val, off_fallback, off_row_local, off_chunk_tot, total;
     // row-resident fast path (0 = not eligible)
     int small_epl, small_cap, small_region0, small_lds_bytes;
 };
@@ -80,6 +80,8 @@ Plan make_plan(int dt, int64_t rows, int64_t row_len, double keep_ratio, int n_b
     p.off_bo_idx = o;    o = align256(o + 4 * (size_t)rows * (size_t)p.k);
     p.off_bo_val = o;    o = align256(o + 4 * (size_t)rows * (size_t)p.k);
     p.off_fallback = o;  o = align256(o + 4 * (size_t)rows);
+    p.off_row_local = o; o = align256(o + 8 * (size_t)rows);
+    p.off_chunk_tot = o; o = align256(o + 8 * (size_t)((rows + kScanRows - 1) / kScanRows));
     p.total = o ? o : 256;
 
     // The one-wave-per-row kernel holds the row in registers (64 * EPL elements) and
@@ -92,7 +94,7 @@ Plan make_plan(int dt, int64_t rows, int64_t row_len, double keep_ratio, int n_b
     for (int q = 1; q <= 16; ++q) nq += (bit_set >> q) & 1u;
     if (row_len % epc == 0 && row_len <= max_n && 2 * n_blocks <= kWave) {
         const int64_t margin = std::max<int64_t>(64, row_len / (dt == SLICER_F32 ? 8 : 16));
-        int64_t cap = std::min<int64_t>(960, (p.k + margin + 63) / 64 * 64);
+        int64_t cap = std::min<int64_t>(1984, (p.k + margin + 63) / 64 * 64);   // ranks are 11-bit fields
         int epl = epc;
         while ((int64_t)epl * kWave < row_len) epl *= 2;
         const int64_t region0 = (std::max<int64_t>(kFineBins, (p.k + 1) / 2 + (int64_t)p.cap_words) + 1) & ~(int64_t)1;
@@ -239,21 +241,22 @@ int slicer_encode(const void* x, slicer_dtype dt, int64_t rows, int64_t row_len,
     fa.M = n_blocks; fa.w = p.w; fa.dt = (int)dt;
     fa.bit_set = bit_set;
     fa.row_words = ea.row_words;
+    fa.row_off_local = (u64*)(ws + p.off_row_local);
+    fa.chunk_tot = (u64*)(ws + p.off_chunk_tot);
+    fa.slots = ea.slots;
+    fa.cap_words = p.cap_words;
+    fa.chunks_per_row = (int)std::max<u64>(1, (p.cap_words + 4095) / 4096);
+    fa.stream = (u32*)stream;
     fa.meta = meta;
     fa.mv = ea.mv;
-    hipLaunchKernelGGL((enc_offsets_kernel<1024>), dim3(1), dim3(1024), 0, st, fa);
+    const u64 grid = (u64)rows * (u64)fa.chunks_per_row;
+    if (grid >= (1ull << 31)) return SLICER_EINVAL;
+    hipLaunchKernelGGL(enc_rowscan_kernel, dim3((unsigned)((rows + kScanRows - 1) / kScanRows)), dim3(kScanRows), 0, st, fa);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e);
-
-    if (p.cap_words > 0) {
-        const int chunks = (int)((p.cap_words + 4095) / 4096);
-        const u64 grid = (u64)rows * (u64)chunks;
-        if (grid >= (1ull << 31)) return SLICER_EINVAL;
-        hipLaunchKernelGGL(enc_compact_kernel, dim3((unsigned)grid), dim3(256), 0, st, ea.slots, p.cap_words,
-                           ea.row_words, ea.mv.row_off, (u32*)stream, chunks);
-        e = hipGetLastError();
-        if (e != hipSuccess) return hip_fail(e);
-    }
+    hipLaunchKernelGGL(enc_gather_kernel, dim3((unsigned)grid), dim3(256), 0, st, fa);
+    e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e);
     return SLICER_OK;
 }
 
@@ -307,6 +310,17 @@ int slicer_profile_events(void* start_event, void* stop_event)
     g_ev_stop = (hipEvent_t)stop_event;
     return SLICER_OK;
 }
+
+#ifdef SLICER_PHASE_TIMING
+// development builds only: read and clear the per-phase cycle table of the row-resident encoder
+int slicer_debug_phase_cycles(unsigned long long* out16)
+{
+    unsigned long long zero[16] = {0};
+    SLICER_HIP(hipMemcpyFromSymbol(out16, HIP_SYMBOL(g_phase_cycles), sizeof(zero)));
+    SLICER_HIP(hipMemcpyToSymbol(HIP_SYMBOL(g_phase_cycles), zero, sizeof(zero)));
+    return SLICER_OK;
+}
+#endif
 
 int slicer_last_hip_error(void) { return g_last_hip_error; }
 

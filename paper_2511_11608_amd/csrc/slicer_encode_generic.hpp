@@ -513,78 +513,105 @@ __global__ __launch_bounds__(BLOCK) void enc_generic_kernel(EncArgs a)
     }
 }
 
-// ---- row offsets (exclusive scan of the row word counts) and header ----------------
+// ---- row offsets (exclusive scan of the row word counts), header, gather ------------------
+// Two launches: (1) every workgroup scans the word counts of 1024 consecutive rows and
+// leaves the rows' offsets relative to its chunk plus the chunk total; (2) the gather
+// kernel adds the totals of the preceding chunks, writes the final offsets and the header
+// and copies each row's slot to its place in the contiguous stream.
+
+constexpr int kScanRows = 1024;
 
 struct FinishArgs {
     int64_t R, N, k;
     int M, w, dt;
     u32 bit_set;
-    const u64* row_words;
+    const u64* row_words;   // [R]
+    u64* row_off_local;     // [R]  offset of the row inside its chunk of kScanRows rows
+    u64* chunk_tot;         // [ceil(R / kScanRows)]
+    const u32* slots;
+    u64 cap_words;
+    int chunks_per_row;     // gather workgroups per row (4096 words each)
+    u32* stream;
     void* meta;
     MetaView mv;
 };
 
-template <int BLOCK>
-__global__ __launch_bounds__(BLOCK) void enc_offsets_kernel(FinishArgs a)
+__global__ __launch_bounds__(kScanRows) void enc_rowscan_kernel(FinishArgs a)
 {
-    __shared__ u64 s_part[BLOCK / kWave];
-    __shared__ u64 s_carry;
+    __shared__ u64 s_part[kScanRows / kWave];
     const int tid = threadIdx.x;
     const u32 lane = lane_id();
     const int wid = tid / kWave;
-    if (tid == 0) s_carry = 0;
-    __syncthreads();
-    for (int64_t base = 0; base < a.R; base += BLOCK) {
-        const int64_t i = base + tid;
-        u64 v = i < a.R ? a.row_words[i] : 0ull;
-        u64 inc = v;
+    const int64_t i = (int64_t)blockIdx.x * kScanRows + tid;
+    const u64 v = i < a.R ? a.row_words[i] : 0ull;
+    u64 inc = v;
 #pragma unroll
-        for (int d = 1; d < kWave; d <<= 1) {
-            u64 t = __shfl_up(inc, d);
-            if (lane >= (u32)d) inc += t;
-        }
-        if (lane == kWave - 1) s_part[wid] = inc;
-        __syncthreads();
-        u64 wbase = 0, tot = 0;
-        for (int v2 = 0; v2 < BLOCK / kWave; ++v2) {
-            u64 s = s_part[v2];
-            if (v2 < wid) wbase += s;
-            tot += s;
-        }
-        const u64 carry = s_carry;
-        if (i < a.R) a.mv.row_off[i] = carry + wbase + inc - v;
-        __syncthreads();
-        if (tid == 0) s_carry = carry + tot;
-        __syncthreads();
+    for (int d = 1; d < kWave; d <<= 1) {
+        u64 t = __shfl_up(inc, d);
+        if (lane >= (u32)d) inc += t;
     }
-    if (tid == 0) {
+    if (lane == kWave - 1) s_part[wid] = inc;
+    __syncthreads();
+    u64 wbase = 0, tot = 0;
+    for (int v2 = 0; v2 < kScanRows / kWave; ++v2) {
+        const u64 sp = s_part[v2];
+        if (v2 < wid) wbase += sp;
+        tot += sp;
+    }
+    if (i < a.R) a.row_off_local[i] = wbase + inc - v;
+    if (tid == 0) a.chunk_tot[blockIdx.x] = tot;
+}
+
+__global__ __launch_bounds__(256) void enc_gather_kernel(FinishArgs a)
+{
+    __shared__ u64 s_red[256 / kWave];
+    const int tid = threadIdx.x;
+    const int64_t r = blockIdx.x / a.chunks_per_row;
+    const u64 c = blockIdx.x % a.chunks_per_row;
+    const int64_t my_chunk = r / kScanRows;
+    const int64_t n_chunks = (a.R + kScanRows - 1) / kScanRows;
+    // words before this row's chunk (and, for the header, in the whole tensor)
+    const bool want_total = blockIdx.x == 0;
+    const int64_t upto = want_total ? n_chunks : my_chunk;
+    u64 part = 0, part_before = 0;
+    for (int64_t j = tid; j < upto; j += 256) {
+        const u64 t = a.chunk_tot[j];
+        part += t;
+        if (j < my_chunk) part_before += t;
+    }
+    // block sums of both partials (part_before differs from part only in workgroup 0)
+    u64 sum_all = part, sum_before = part_before;
+#pragma unroll
+    for (int d = kWave / 2; d > 0; d >>= 1) { sum_all += __shfl_xor(sum_all, d); sum_before += __shfl_xor(sum_before, d); }
+    if ((tid & (kWave - 1)) == 0) s_red[tid / kWave] = sum_all;
+    __syncthreads();
+    u64 total = 0;
+    for (int v2 = 0; v2 < 256 / kWave; ++v2) total += s_red[v2];
+    __syncthreads();
+    if ((tid & (kWave - 1)) == 0) s_red[tid / kWave] = sum_before;
+    __syncthreads();
+    u64 before = 0;
+    for (int v2 = 0; v2 < 256 / kWave; ++v2) before += s_red[v2];
+
+    const u64 off = before + a.row_off_local[r];
+    if (c == 0 && tid == 0) a.mv.row_off[r] = off;
+    if (want_total && tid == 0) {
         u32* h32 = (u32*)a.meta;
         u64* h64 = (u64*)a.meta;
         h32[0] = kMagic; h32[1] = kVersion; h32[2] = (u32)a.dt; h32[3] = (u32)a.M;
         h64[2] = (u64)a.R; h64[3] = (u64)a.N; h64[4] = (u64)a.k;
         h32[10] = a.bit_set; h32[11] = (u32)a.w;
-        h64[6] = s_carry; h64[7] = 0;
+        h64[6] = total; h64[7] = 0;
         uint8_t* m8 = (uint8_t*)a.meta;     // zero the padding after the last array
         for (size_t o = kHeaderBytes + 16 * (size_t)a.R + 18 * (size_t)a.R * a.M; o < meta_bytes(a.R, a.M); ++o) m8[o] = 0;
     }
-}
-
-// ---- gather of the per-row slots into the contiguous stream ----------------------
-
-__global__ __launch_bounds__(256) void enc_compact_kernel(const u32* __restrict__ slots, u64 cap_words,
-                                                          const u64* __restrict__ row_words,
-                                                          const u64* __restrict__ row_off,
-                                                          u32* __restrict__ stream, int chunks_per_row)
-{
-    const int64_t r = blockIdx.x / chunks_per_row;
-    const u64 c = blockIdx.x % chunks_per_row;
-    const u64 nw = row_words[r];
+    const u64 nw = a.row_words[r];
     const u64 j0 = c * 4096ull;
     if (j0 >= nw) return;
     const u64 j1 = j0 + 4096ull < nw ? j0 + 4096ull : nw;
-    const u32* __restrict__ src = slots + (size_t)r * cap_words;
-    u32* __restrict__ dst = stream + row_off[r];
-    for (u64 j = j0 + threadIdx.x; j < j1; j += 256) dst[j] = src[j];
+    const u32* __restrict__ src = a.slots + (size_t)r * a.cap_words;
+    u32* __restrict__ dst = a.stream + off;
+    for (u64 j = j0 + tid; j < j1; j += 256) dst[j] = src[j];
 }
 
 }  // namespace slicer

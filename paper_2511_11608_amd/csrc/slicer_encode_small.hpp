@@ -38,11 +38,25 @@ struct SmallArgs {
     u32* slots;         // [R][cap_words]
     u32* fallback;      // [R] 1 = redo this row with the generic kernel
     MetaView mv;
-    int cap;            // list capacity, multiple of 64, <= 1023
+    int cap;            // list capacity, multiple of 64, < 2048
     int region0_words;  // histogram region, later block-ordered arrays + stream image
 };
 
 constexpr int kFineBins = 1024;
+
+// Optional per-phase cycle accounting (development builds only, -DSLICER_PHASE_TIMING):
+// lane 0 of every wave adds the cycles since the previous mark to a global table.
+#ifdef SLICER_PHASE_TIMING
+__device__ unsigned long long g_phase_cycles[16];
+#define SLICER_PT(i)                                                              \
+    do {                                                                          \
+        const long long t_now_ = clock64();                                       \
+        if (lane == 0) atomicAdd(&g_phase_cycles[i], (unsigned long long)(t_now_ - t_prev_)); \
+        t_prev_ = clock64();                                                      \
+    } while (0)
+#else
+#define SLICER_PT(i) do { } while (0)
+#endif
 
 __device__ inline void wave_sync()
 {
@@ -100,7 +114,7 @@ struct SmallLds {
     u32* Lent;      // [cap]       list entries, ascending index: bf16 raw << 16 | idx; fp32 raw
     u32* S;         // [cap]       entries arranged by fine bin: in-bin comp << 1 | class
     uint16_t* Lidx; // [cap]       fp32 only: index of the entry
-    u64* thr;       // [B2]        block boundaries per class (full comps, 32-bit for bf16), [cls * M + j - 1]
+    u64* thr;       // [B2]        block boundaries (full comps with the class on top; 32-bit for bf16), positive class first
     u32* tg;        // [5][64]     boundary work table: bin, base, count, rank in bin, pair prefix
     u32* blk_start; // [B2 + 1]
     u32* vminb;     // [B2] key of the block's smallest / largest element
@@ -146,7 +160,9 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
 {
     typedef Elem<DT> E;
     typedef typename E::raw_t raw_t;
-    typedef typename std::conditional<DT == 0, u64, u32>::type comp_t;   // bf16: key + index fit 32 bits
+    typedef typename std::conditional<DT == 0, u64, u32>::type comp_t;   // bf16: key + index fit 31 bits
+    constexpr comp_t kClsBit = (comp_t)1 << (8 * sizeof(comp_t) - 1);       // set for the positive class
+    constexpr int kRegThr = 14;                                              // boundaries held in registers
     constexpr int QN = NQ ? NQ : kMaxQ;
     constexpr int EPC = DT == 0 ? 4 : 8;            // elements per 16-byte chunk
     constexpr int NCH = EPL / EPC;                  // chunks per lane
@@ -154,6 +170,9 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
     extern __shared__ u32 smem[];
 
     const u32 lane = lane_id();
+#ifdef SLICER_PHASE_TIMING
+    long long t_prev_ = clock64();
+#endif
     const int64_t r = blockIdx.x;
     const int N = (int)a.N, M = a.M, w = a.w, B2 = 2 * a.M, nq = NQ ? NQ : a.nq, cap = a.cap;
     const int k = (int)a.k;
@@ -239,6 +258,7 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
         return;
     }
 
+    SLICER_PT(0);
     // ---- 2. ordered compaction into L -------------------------------------------------
     u32 nL = 0;
     if (k > 0) {
@@ -297,6 +317,7 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
     }
     wave_sync();
 
+    SLICER_PT(1);
     // ---- 3. fine bins ---------------------------------------------------------------------
     // 1024 bins, linear in (key - t_lo) >> sh with sh from the largest key of the list; a full
     // comp (fine bin, in-bin key bits, index) and an S entry (in-bin bits, index, class) must
@@ -310,7 +331,7 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
     kmax = wave_max_dpp(kmax);
     const u32 range = kmax - t_lo;
     const int sh = range < (u32)kFineBins ? 0 : (32 - __clz((int)range)) - 10;
-    if (sh + w > 31 || (DT != 0 && 10 + sh + w > 32)) {
+    if (sh + w > 31 || (DT != 0 && 10 + sh + w > 31)) {
         if (lane == 0) a.fallback[r] = 1u;
         return;
     }
@@ -332,9 +353,13 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
             const uint4 t = h4[3 - j];
             cs[4 * j + 0] = t.w; cs[4 * j + 1] = t.z; cs[4 * j + 2] = t.y; cs[4 * j + 3] = t.x;
         }
-        u32 local = 0;
+        u32 local = 0, big = 0;
 #pragma unroll
-        for (int j = 0; j < 16; ++j) local += cs[j];
+        for (int j = 0; j < 16; ++j) { local += cs[j]; big |= ((cs[j] & 0xFFFFu) + (cs[j] >> 16)) >> 10; }
+        if (__ballot(big != 0u)) {                      // a fine bin with 1024+ members overflows its fill field
+            if (lane == 0) a.fallback[r] = 1u;
+            return;
+        }
         const u32 incl = wave_scan_dpp(local);
         const u32 tot = bcast(incl, kWave - 1);
         n_pos = tot & 0xFFFFu; n_neg = tot >> 16;       // class sizes of L (of the kept set once cut)
@@ -362,6 +387,7 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
     }
     wave_sync();
 
+    SLICER_PT(2);
     // ---- top-K cut: the comp of overall rank k-1 (ATKF) -----------------------------------------
     // full comp of an entry: fine bin, in-bin key bits, inverted index
     const int cshift = sh + w;
@@ -397,6 +423,7 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
     const u32 n_cls[2] = { n_pos, n_neg };
     const u32 Kc[2] = { n_pos / (u32)M, n_neg / (u32)M };
 
+    SLICER_PT(3);
     // ---- block boundaries: comps of class ranks j*K-1, one lane per boundary ------------------------
     const int nt0 = Kc[0] ? M - 1 : 0, nt1 = Kc[1] ? M - 1 : 0, ntg = nt0 + nt1;
     u32* tg_bin = L.tg; u32* tg_base = L.tg + 64; u32* tg_cnt = L.tg + 128; u32* tg_rem = L.tg + 192; u32* tg_pre = L.tg + 256;
@@ -442,8 +469,7 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
                         gt += ((o & 1u) == tc && (o >> 1) > (me >> 1)) ? 1u : 0u;
                     }
                     if (gt == tg_rem[t]) {
-                        const int jb = tc ? t - nt0 : t;
-                        ((comp_t*)L.thr)[tc * (u32)M + (u32)jb] = ((comp_t)tg_bin[t] << cshift) | (comp_t)(me >> 1);
+                        ((comp_t*)L.thr)[t] = (tc ? (comp_t)0 : kClsBit) | ((comp_t)tg_bin[t] << cshift) | (comp_t)(me >> 1);
                     }
                 }
             }
@@ -460,6 +486,7 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
     if (lane == 0) L.blk_start[B2] = n;
     wave_sync();
 
+    SLICER_PT(4);
     // ---- 4. blocks, stable split by block, block-ordered arrays -----------------------------------
     // S and the fine bins are dead (boundaries are resolved): S's storage takes the
     // block-ordered values, the histogram region the indices and the stream image
@@ -469,8 +496,13 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
     const comp_t* thr = (const comp_t*)L.thr;
     int nbits = 0;
     while ((1 << nbits) < B2) ++nbits;
-    int msteps = 0;
-    while ((1 << msteps) < M) ++msteps;
+    // An entry's block = number of boundaries of its class above it.  With the class as the
+    // top bit of the comp (positive class on top) one count over ALL boundaries serves both
+    // classes: a positive entry is above every negative boundary, a negative entry below
+    // every positive one.  Up to kRegThr boundaries are held in registers.
+    comp_t tx[kRegThr];
+#pragma unroll
+    for (int j = 0; j < kRegThr; ++j) tx[j] = j < ntg ? thr[j] : (comp_t)0;
     for (int s = 0; s < nslots; ++s) {
         const u32 p = s * kWave + lane;
         bool kept = false;
@@ -484,26 +516,24 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
             if (comp >= thrK) {
                 kept = true;
                 const u32 cls = E::neg((raw_t)raw);
-                u32 m = (u32)(M - 1);
-                if (Kc[cls]) {                      // block = number of boundaries above this entry
-                    int lo = 0, hi = M - 1;
-                    for (int it = 0; it < msteps; ++it) {
-                        const int mid = (lo + hi) >> 1;
-                        if (lo < hi) { if (thr[cls * (u32)M + (u32)mid] > comp) lo = mid + 1; else hi = mid; }
-                    }
-                    m = (u32)lo;
-                }
+                const comp_t cx = comp | (cls ? (comp_t)0 : kClsBit);
+                u32 above = 0;
+#pragma unroll
+                for (int j = 0; j < kRegThr; ++j) above += tx[j] > cx ? 1u : 0u;
+                for (int j = kRegThr; j < ntg; ++j) above += thr[j] > cx ? 1u : 0u;
+                const u32 m = Kc[cls] ? above - (cls ? (u32)nt0 : 0u) : (u32)(M - 1);
                 b = cls * (u32)M + m;
                 atomicMin(&L.vminb[b], key);
                 atomicMax(&L.vmaxb[b], key);
             }
         }
         // lanes of this slot in the same block: one ballot per bit of the block id
+        // (lanes that are not kept drop out through the first mask)
         const u64 km = __ballot(kept);
         u32 plo = (u32)km, phi = (u32)(km >> 32);
         for (int bit = 0; bit < nbits; ++bit) {
-            const u64 bal = __ballot(kept && ((b >> bit) & 1u));
             const u32 onm = (u32)__builtin_amdgcn_sbfe((int)b, (u32)bit, 1u);   // all ones if the bit is set
+            const u64 bal = __ballot(onm != 0u);
             plo &= ~((u32)bal ^ onm);
             phi &= ~((u32)(bal >> 32) ^ onm);
         }
@@ -520,6 +550,7 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
         wave_sync();
     }
 
+    SLICER_PT(5);
     // ---- 5. ABQ -----------------------------------------------------------------------------------
     // Each block is walked by kWave / B2 lanes, each lane a contiguous run of the block-ordered
     // list, so a lane's quantiser constants and partial sums live in registers.
@@ -575,10 +606,15 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
 #pragma unroll
                     for (int t = 0; t < QN; ++t) {
                         if (NQ || t < nq) {
+                            // 0 <= y <= Lq (d <= rng and the roundings of Lq / rng, d * inv keep the
+                            // product at or below Lq): the clamp of the definition never acts
                             const float y = d * inv[t];
-                            const float c = fminf(rintf(y), Lq[t]);          // y >= 0: no lower clamp needed
-                            const int rho = (int)rintf((y - c) * 32768.0f);
-                            acc[t] += (u32)(rho * rho);
+                            const float c = rintf(y);
+                            // rint((y - c) * 2^15): the product is exact, so one fused rounding onto the
+                            // integer grid of 1.5 * 2^23 is the same round-half-even
+                            const float tq = __fmaf_rn(y - c, 32768.0f, 12582912.0f);
+                            const int rho = (int)__float_as_uint(tq) - 0x4B400000;
+                            acc[t] += (u32)__mul24(rho, rho);
                         }
                     }
                 }
@@ -627,16 +663,16 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
     for (u32 i = lane; i < row_words; i += kWave) stage[i] = 0;
     wave_sync();
 
+    SLICER_PT(6);
     // ---- packing ----------------------------------------------------------------------------------
     {
-        const float Lsel = (float)((1u << myq) - 1u);
         for (u32 i = 0; i < T; ++i) {
             const u32 p = r0 + i;
             if (p < r1) {
                 u32 c = 0;
                 if (!dg) {
                     const float y = (__uint_as_float(bo_val[p]) - vmin) * my_inv;
-                    c = (u32)fminf(rintf(y), Lsel);
+                    c = (u32)rintf(y);                    // already within [0, 2^q - 1]
                 }
                 {   // index field
                     const u32 P = p * (u32)w, wi = P >> 5, sft = P & 31u, val = bo_idx[p];
@@ -652,6 +688,7 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
         }
     }
     wave_sync();
+    SLICER_PT(7);
     u32* __restrict__ slot = a.slots + (size_t)r * (size_t)a.cap_words;
     for (u32 i = lane; i < row_words; i += kWave) slot[i] = stage[i];
     if (lane == 0) {
