@@ -133,10 +133,11 @@ int launch_encode(const EncArgs& ea, hipStream_t st)
 {
     const bool timed = g_ev_start && g_ev_stop && !ea.only_flagged;
     if (timed) SLICER_HIP(hipEventRecord(g_ev_start, st));
+    const unsigned grid = (unsigned)((ea.R + ea.rows_per_wg - 1) / ea.rows_per_wg);
     if (ea.N >= 32768)
-        hipLaunchKernelGGL((enc_generic_kernel<DT, 1024>), dim3((unsigned)ea.R), dim3(1024), 0, st, ea);
+        hipLaunchKernelGGL((enc_generic_kernel<DT, 1024>), dim3(grid), dim3(1024), 0, st, ea);
     else
-        hipLaunchKernelGGL((enc_generic_kernel<DT, 256>), dim3((unsigned)ea.R), dim3(256), 0, st, ea);
+        hipLaunchKernelGGL((enc_generic_kernel<DT, 256>), dim3(grid), dim3(256), 0, st, ea);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e);
     if (timed) SLICER_HIP(hipEventRecord(g_ev_stop, st));
@@ -156,7 +157,15 @@ int launch_decode(const void* stream, const void* meta, void* y, int dt, int64_t
     if (grid >= (1ull << 31)) return SLICER_EINVAL;
     const bool timed = g_ev_start && g_ev_stop;
     if (timed) SLICER_HIP(hipEventRecord(g_ev_start, st));
-    if (dt == SLICER_F32)
+    // short rows: one wavefront per row, the row assembled in LDS (16 KB per wave at most)
+    const int64_t row_bytes = row_len * (dt == SLICER_F32 ? 4 : 2);
+    if (row_bytes % 16 == 0 && row_bytes <= 16 * 1024 && 2 * n_blocks <= kWave && ((uintptr_t)y & 15) == 0) {
+        const unsigned g4 = (unsigned)((rows + 3) / 4);
+        if (dt == SLICER_F32)
+            hipLaunchKernelGGL((dec_small_kernel<0>), dim3(g4), dim3(256), (size_t)(4 * row_bytes), st, da);
+        else
+            hipLaunchKernelGGL((dec_small_kernel<1>), dim3(g4), dim3(256), (size_t)(4 * row_bytes), st, da);
+    } else if (dt == SLICER_F32)
         hipLaunchKernelGGL((dec_kernel<0, 256>), dim3((unsigned)grid), dim3(256), 0, st, da);
     else
         hipLaunchKernelGGL((dec_kernel<1, 256>), dim3((unsigned)grid), dim3(256), 0, st, da);
@@ -213,6 +222,7 @@ int slicer_encode(const void* x, slicer_dtype dt, int64_t rows, int64_t row_len,
     ea.bo_val = (u32*)(ws + p.off_bo_val);
     ea.mv = meta_view(meta, rows, n_blocks);
     ea.only_flagged = nullptr;
+    ea.rows_per_wg = 1;
 
     if (p.small_epl && ((uintptr_t)x & 15) == 0) {
         // fast path; rows it cannot hold are flagged and redone by the generic kernel
@@ -232,6 +242,7 @@ int slicer_encode(const void* x, slicer_dtype dt, int64_t rows, int64_t row_len,
         if (rc) return rc;
         if (timed) SLICER_HIP(hipEventRecord(g_ev_stop, st));
         ea.only_flagged = sa.fallback;
+        ea.rows_per_wg = (rows + 1023) / 1024;     // few workgroups: flagged rows are rare
     }
     rc = dt == SLICER_F32 ? launch_encode<0>(ea, st) : launch_encode<1>(ea, st);
     if (rc) return rc;
@@ -249,7 +260,7 @@ int slicer_encode(const void* x, slicer_dtype dt, int64_t rows, int64_t row_len,
     fa.stream = (u32*)stream;
     fa.meta = meta;
     fa.mv = ea.mv;
-    const u64 grid = (u64)rows * (u64)fa.chunks_per_row;
+    const u64 grid = ((u64)rows * (u64)fa.chunks_per_row + 3) / 4;     // four wavefronts per workgroup
     if (grid >= (1ull << 31)) return SLICER_EINVAL;
     hipLaunchKernelGGL(enc_rowscan_kernel, dim3((unsigned)((rows + kScanRows - 1) / kScanRows)), dim3(kScanRows), 0, st, fa);
     hipError_t e = hipGetLastError();

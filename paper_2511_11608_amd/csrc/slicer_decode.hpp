@@ -126,4 +126,76 @@ __global__ __launch_bounds__(BLOCK) void dec_kernel(DecArgs a)
     }
 }
 
+// ---- short rows: one wavefront per row, no workgroup barrier ---------------------------
+// Lane b * lpb + sub (lpb = 64 / 2M lanes per block) decodes entries sub, sub + lpb, ... of
+// block b, so neighbouring lanes read neighbouring bit fields; block offsets come from one
+// scan across the lanes.  The row is assembled in LDS and written with 16-byte stores.
+
+__device__ inline u32 dec_scan_add(u32 v)     // inclusive prefix sum over the 64 lanes
+{
+    const u32 lane = lane_id();
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        const u32 t = __shfl_up(v, d);
+        if (lane >= (u32)d) v += t;
+    }
+    return v;
+}
+
+template <int DT>
+__global__ __launch_bounds__(256) void dec_small_kernel(DecArgs a)
+{
+    typedef typename Elem<DT>::raw_t raw_t;
+    constexpr int ESZ = DT == 0 ? 4 : 2;
+    extern __shared__ uint4 dec_smem[];
+    const u32 lane = lane_id();
+    const int wid = threadIdx.x / kWave;
+    const int64_t r = (int64_t)blockIdx.x * (256 / kWave) + wid;
+    if (r >= a.R) return;
+    const int N = (int)a.N, M = a.M, B2 = 2 * a.M, w = a.w;
+    const int row_bytes = N * ESZ;                       // multiple of 16
+    uint4* tile4 = dec_smem + (size_t)wid * (row_bytes / 16);
+    raw_t* tile = (raw_t*)tile4;
+
+    for (int i = lane; i < row_bytes / 16; i += kWave) tile4[i] = make_uint4(0, 0, 0, 0);
+
+    const u32 n_pos = a.mv.n_pos[r], n_neg = a.mv.n_neg[r];
+    const u32* __restrict__ rw = a.stream + a.mv.row_off[r];
+    const u32 lpb = (u32)kWave / (u32)B2;
+    const u32 myb = lane / lpb, sub = lane - myb * lpb;
+    u32 cnt = 0, q = 0;
+    float vmin = 0.f, step = 0.f;
+    if (myb < (u32)B2 && (u64)n_pos + n_neg <= (u64)N) {
+        const u32 cls = myb >= (u32)M ? 1u : 0u, m = myb - cls * (u32)M;
+        const u32 nc = cls ? n_neg : n_pos, K = nc / (u32)M;
+        cnt = (m < (u32)(M - 1)) ? K : nc - K * (u32)(M - 1);
+        const size_t mi = (size_t)r * (size_t)B2 + myb;
+        q = a.mv.q[mi] & 0x7Fu;
+        vmin = a.mv.vmin[mi];
+        step = (a.mv.vmax[mi] - vmin) / (float)((1u << q) - 1u);
+    }
+    // first entry and first code bit of my block: scans over one lane per block
+    const bool head = sub == 0;
+    const u32 ie = dec_scan_add(head ? cnt : 0u) - (head ? cnt : 0u);
+    const u32 ce = dec_scan_add(head ? cnt * q : 0u) - (head ? cnt * q : 0u);
+    const u32 n = n_pos + n_neg;
+    const u32 istart = (u32)__shfl((int)ie, (int)(myb * lpb));
+    const u32 cstart = n * (u32)w + (u32)__shfl((int)ce, (int)(myb * lpb));
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+
+    for (u32 j = sub; j < cnt; j += lpb) {
+        const u32 idx = read_bits(rw, (u64)(istart + j) * (u32)w, w);
+        const u32 c = read_bits(rw, (u64)cstart + (u64)j * q, (int)q);
+        float val = __fadd_rn(vmin, __fmul_rn((float)c, step));      // two roundings, never fused
+        if (myb >= (u32)M) val = -val;
+        if (idx < (u32)N) tile[idx] = DT == 0 ? (raw_t)__float_as_uint(val) : (raw_t)f32_to_bf16_rne(val);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+
+    uint4* __restrict__ out = (uint4*)((char*)a.y + (size_t)r * (size_t)row_bytes);
+    for (int i = lane; i < row_bytes / 16; i += kWave) out[i] = tile4[i];
+}
+
 }  // namespace slicer

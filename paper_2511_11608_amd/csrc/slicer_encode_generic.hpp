@@ -30,6 +30,7 @@ struct EncArgs {
     u32* bo_idx;            // [R][k]   block-ordered indices
     u32* bo_val;            // [R][k]   block-ordered |x| (fp32 bits)
     const u32* only_flagged;// if set: rows with a zero flag are skipped (already encoded)
+    int64_t rows_per_wg;    // consecutive rows a workgroup walks (1 unless only_flagged is set)
     // meta
     MetaView mv;
 };
@@ -127,8 +128,14 @@ __global__ __launch_bounds__(BLOCK) void enc_generic_kernel(EncArgs a)
     const int tid = threadIdx.x;
     const u32 lane = lane_id();
     const int wid = tid / kWave;
-    const int64_t r = blockIdx.x;
-    if (a.only_flagged && !a.only_flagged[r]) return;
+    const int64_t r_end = ((int64_t)blockIdx.x + 1) * a.rows_per_wg < a.R ? ((int64_t)blockIdx.x + 1) * a.rows_per_wg : a.R;
+    if (a.only_flagged) {       // one coalesced look at this workgroup's flags: usually none is set
+        int any = 0;
+        for (int64_t r = (int64_t)blockIdx.x * a.rows_per_wg + tid; r < r_end; r += BLOCK) any |= (int)a.only_flagged[r];
+        if (!__syncthreads_or(any)) return;
+    }
+    for (int64_t r = (int64_t)blockIdx.x * a.rows_per_wg; r < r_end; ++r) {
+    if (a.only_flagged && !a.only_flagged[r]) continue;      // uniform: the whole workgroup skips
     const int64_t N = a.N;
     const int M = a.M, w = a.w, B2 = 2 * a.M;
     const raw_t* __restrict__ xr = (const raw_t*)a.x + (size_t)r * (size_t)N;
@@ -511,6 +518,8 @@ __global__ __launch_bounds__(BLOCK) void enc_generic_kernel(EncArgs a)
         for (int i = tid; i < (int)cw; i += BLOCK) slot[c0 + i] = sA[i];
         __syncthreads();
     }
+    __syncthreads();
+    }   // rows of this workgroup
 }
 
 // ---- row offsets (exclusive scan of the row word counts), header, gather ------------------
@@ -564,38 +573,28 @@ __global__ __launch_bounds__(kScanRows) void enc_rowscan_kernel(FinishArgs a)
 
 __global__ __launch_bounds__(256) void enc_gather_kernel(FinishArgs a)
 {
-    __shared__ u64 s_red[256 / kWave];
-    const int tid = threadIdx.x;
-    const int64_t r = blockIdx.x / a.chunks_per_row;
-    const u64 c = blockIdx.x % a.chunks_per_row;
+    // one wavefront per (row, 4096-word chunk of its slot); no workgroup barrier
+    const u32 lane = lane_id();
+    const int64_t item = (int64_t)blockIdx.x * (256 / kWave) + threadIdx.x / kWave;
+    const int64_t r = item / a.chunks_per_row;
+    const u64 c = (u64)(item % a.chunks_per_row);
+    if (r >= a.R) return;
     const int64_t my_chunk = r / kScanRows;
     const int64_t n_chunks = (a.R + kScanRows - 1) / kScanRows;
-    // words before this row's chunk (and, for the header, in the whole tensor)
-    const bool want_total = blockIdx.x == 0;
+    const bool want_total = item == 0;               // this wave also writes the header
     const int64_t upto = want_total ? n_chunks : my_chunk;
-    u64 part = 0, part_before = 0;
-    for (int64_t j = tid; j < upto; j += 256) {
+    u64 before = 0, total = 0;
+    for (int64_t j = lane; j < upto; j += kWave) {
         const u64 t = a.chunk_tot[j];
-        part += t;
-        if (j < my_chunk) part_before += t;
+        total += t;
+        if (j < my_chunk) before += t;
     }
-    // block sums of both partials (part_before differs from part only in workgroup 0)
-    u64 sum_all = part, sum_before = part_before;
 #pragma unroll
-    for (int d = kWave / 2; d > 0; d >>= 1) { sum_all += __shfl_xor(sum_all, d); sum_before += __shfl_xor(sum_before, d); }
-    if ((tid & (kWave - 1)) == 0) s_red[tid / kWave] = sum_all;
-    __syncthreads();
-    u64 total = 0;
-    for (int v2 = 0; v2 < 256 / kWave; ++v2) total += s_red[v2];
-    __syncthreads();
-    if ((tid & (kWave - 1)) == 0) s_red[tid / kWave] = sum_before;
-    __syncthreads();
-    u64 before = 0;
-    for (int v2 = 0; v2 < 256 / kWave; ++v2) before += s_red[v2];
+    for (int d = kWave / 2; d > 0; d >>= 1) { before += __shfl_xor(before, d); total += __shfl_xor(total, d); }
 
     const u64 off = before + a.row_off_local[r];
-    if (c == 0 && tid == 0) a.mv.row_off[r] = off;
-    if (want_total && tid == 0) {
+    if (c == 0 && lane == 0) a.mv.row_off[r] = off;
+    if (want_total && lane == 0) {
         u32* h32 = (u32*)a.meta;
         u64* h64 = (u64*)a.meta;
         h32[0] = kMagic; h32[1] = kVersion; h32[2] = (u32)a.dt; h32[3] = (u32)a.M;
@@ -611,7 +610,7 @@ __global__ __launch_bounds__(256) void enc_gather_kernel(FinishArgs a)
     const u64 j1 = j0 + 4096ull < nw ? j0 + 4096ull : nw;
     const u32* __restrict__ src = a.slots + (size_t)r * a.cap_words;
     u32* __restrict__ dst = a.stream + off;
-    for (u64 j = j0 + tid; j < j1; j += 256) dst[j] = src[j];
+    for (u64 j = j0 + lane; j < j1; j += kWave) dst[j] = src[j];
 }
 
 }  // namespace slicer
