@@ -123,33 +123,37 @@ struct SmallLds {
     u64* sums;      // [B2][nq + 1]
 };
 
-__host__ __device__ inline int small_lds_words(int cap, int region0, int B2, int nq)
+// (the boundary work table and the ABQ sums are never live together: they share storage;
+//  bf16 entries carry their index, so only fp32 rows get the separate index list)
+__host__ __device__ inline int small_lds_words(int dt, int cap, int region0, int B2, int nq)
 {
-    int wds = region0 + cap + cap + cap / 2;
+    int wds = region0 + cap + cap + (dt == 0 ? cap / 2 : 0);
     wds += 2 * B2;                       // thr (u64)
-    wds += 5 * 64;                       // tg
+    const int sums = 2 * B2 * (nq + 1), tg = 5 * 64;
+    wds += sums > tg ? sums : tg;
     wds += (B2 + 1) + B2 * 3;
-    wds = (wds + 1) & ~1;
-    wds += 2 * B2 * (nq + 1);
     return wds;
 }
 
-__device__ inline SmallLds small_carve(u32* base, int cap, int region0, int B2, int nq)
+__device__ inline SmallLds small_carve(u32* base, int dt, int cap, int region0, int B2, int nq)
 {
     SmallLds L;
     u32* p = base;
     L.hist = p;            p += region0;           // region0 is even
     L.Lent = p;            p += cap;
     L.S = p;               p += cap;
-    L.Lidx = (uint16_t*)p; p += cap / 2;
+    L.Lidx = (uint16_t*)p; p += dt == 0 ? cap / 2 : 0;
     L.thr = (u64*)p;       p += 2 * B2;            // cap is a multiple of 64: still 8-byte aligned
-    L.tg = p;              p += 5 * 64;
+    L.sums = (u64*)p;
+    L.tg = p;
+    {
+        const int sums = 2 * B2 * (nq + 1), tg = 5 * 64;
+        p += sums > tg ? sums : tg;
+    }
     L.blk_start = p;       p += B2 + 1;
     L.vminb = p;           p += B2;
     L.vmaxb = p;           p += B2;
     L.run = p;             p += B2;
-    if ((p - base) & 1) ++p;
-    L.sums = (u64*)p;
     return L;
 }
 
@@ -177,7 +181,7 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
     const int N = (int)a.N, M = a.M, w = a.w, B2 = 2 * a.M, nq = NQ ? NQ : a.nq, cap = a.cap;
     const int k = (int)a.k;
     const u32 idxmask = (1u << w) - 1u;
-    SmallLds L = small_carve(smem, cap, a.region0_words, B2, nq);
+    SmallLds L = small_carve(smem, DT, cap, a.region0_words, B2, nq);
 
     // entry accessors: raw bits (sign + key) and index of list entry p
     auto ent_raw = [&](u32 p) -> u32 { const u32 e = L.Lent[p]; return DT == 0 ? e : e >> 16; };
