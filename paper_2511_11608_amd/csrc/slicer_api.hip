@@ -9,6 +9,7 @@
 #include "slicer_common.hpp"
 #include "slicer_encode_generic.hpp"
 #include "slicer_encode_small.hpp"
+#include "slicer_encode_large.hpp"
 #include "slicer_decode.hpp"
 
 using namespace slicer;
@@ -61,6 +62,11 @@ struct Plan {
     size_t off_row_words, off_slots, off_kept, off_bo_idx, off_bo_val, off_fallback, off_row_local, off_chunk_tot, total;
     // row-resident fast path (0 = not eligible)
     int small_epl, small_cap, small_region0, small_lds_bytes;
+    // long-row path (large_C == 0: not eligible)
+    int large_C, large_LC;
+    u32 large_capL;
+    size_t lo_ch_cum, lo_ch_off, lo_L, lo_Lblk, lo_fine_pos, lo_fine_neg, lo_rowst, lo_thr, lo_blk_start,
+           lo_blkcnt, lo_vminb, lo_vmaxb, lo_sums, lo_qsel, lo_inv_sel, lo_code_off;
 };
 
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
@@ -82,6 +88,35 @@ Plan make_plan(int dt, int64_t rows, int64_t row_len, double keep_ratio, int n_b
     p.off_fallback = o;  o = align256(o + 4 * (size_t)rows);
     p.off_row_local = o; o = align256(o + 8 * (size_t)rows);
     p.off_chunk_tot = o; o = align256(o + 8 * (size_t)((rows + kScanRows - 1) / kScanRows));
+    // Long rows: every pass is spread over many workgroups (slicer_encode_large.hpp).
+    p.large_C = 0; p.large_LC = 0; p.large_capL = 0;
+    {
+        const int epc_l = dt == SLICER_F32 ? 4 : 8;
+        const int64_t C = (row_len + kLCH - 1) / kLCH;
+        const int64_t capL = p.k + std::max<int64_t>(4096, row_len / 16);
+        int nq_l = 0;
+        for (int q = 1; q <= 16; ++q) nq_l += (bit_set >> q) & 1u;
+        if (row_len >= 32768 && row_len % epc_l == 0 && C <= 1024 && rows <= 65535 && capL < ((int64_t)1 << 27)) {
+            const size_t R = (size_t)rows, B2 = 2 * (size_t)n_blocks;
+            p.large_C = (int)C; p.large_capL = (u32)capL; p.large_LC = (int)((capL + kLCE - 1) / kLCE);
+            p.lo_ch_cum = o;    o = align256(o + 4 * R * (size_t)C * kLBins);
+            p.lo_ch_off = o;    o = align256(o + 4 * R * (size_t)C);
+            p.lo_L = o;         o = align256(o + 8 * R * (size_t)capL);
+            p.lo_Lblk = o;      o = align256(o + R * (size_t)capL);
+            p.lo_fine_pos = o;  o = align256(o + 4 * R * kFB);
+            p.lo_fine_neg = o;  o = align256(o + 4 * R * kFB);
+            p.lo_rowst = o;     o = align256(o + 4 * R * 16);
+            p.lo_thr = o;       o = align256(o + 8 * R * (1 + kMaxB2));
+            p.lo_blk_start = o; o = align256(o + 4 * R * (B2 + 1));
+            p.lo_blkcnt = o;    o = align256(o + 4 * R * (size_t)p.large_LC * B2);
+            p.lo_vminb = o;     o = align256(o + 4 * R * B2);
+            p.lo_vmaxb = o;     o = align256(o + 4 * R * B2);
+            p.lo_sums = o;      o = align256(o + 8 * R * B2 * (size_t)(nq_l + 1));
+            p.lo_qsel = o;      o = align256(o + 4 * R * B2);
+            p.lo_inv_sel = o;   o = align256(o + 4 * R * B2);
+            p.lo_code_off = o;  o = align256(o + 8 * R * (B2 + 1));
+        }
+    }
     p.total = o ? o : 256;
 
     // The one-wave-per-row kernel holds the row in registers (64 * EPL elements) and
@@ -124,6 +159,25 @@ int launch_small(const SmallArgs& sa, const Plan& p, hipStream_t st)
     else if (p.small_epl == E0 * 2) launch_small_epl<DT, E0 * 2>(sa, lds, st);
     else if (p.small_epl == E0 * 4) launch_small_epl<DT, E0 * 4>(sa, lds, st);
     else launch_small_epl<DT, E0 * 8>(sa, lds, st);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? SLICER_OK : hip_fail(e);
+}
+
+template <int DT>
+int launch_large(const LargeArgs& la, const Plan& p, hipStream_t st)
+{
+    const dim3 gC((unsigned)la.C, (unsigned)la.R), gL((unsigned)la.LC, (unsigned)la.R), gR((unsigned)la.R);
+    const dim3 gP((unsigned)std::max<int64_t>(1, (la.k + kPCH - 1) / kPCH), (unsigned)la.R);
+    const dim3 gW((unsigned)std::max<u64>(1, (p.cap_words + kStageWords - 1) / kStageWords), (unsigned)la.R);
+    hipLaunchKernelGGL((lr_hist_kernel<DT>), gC, dim3(256), 0, st, la);
+    hipLaunchKernelGGL((lr_select_kernel<DT>), gR, dim3(1024), 0, st, la);
+    hipLaunchKernelGGL((lr_compact_kernel<DT>), gC, dim3(256), 0, st, la);
+    hipLaunchKernelGGL(lr_bounds_kernel, gR, dim3(1024), 0, st, la);
+    hipLaunchKernelGGL(lr_blockcount_kernel, gL, dim3(256), 0, st, la);
+    hipLaunchKernelGGL((lr_scatter_kernel<DT>), gL, dim3(256), 0, st, la);
+    hipLaunchKernelGGL((lr_abq_kernel<DT>), gP, dim3(256), 0, st, la);
+    hipLaunchKernelGGL((lr_choose_kernel<DT>), gR, dim3(128), 0, st, la);
+    hipLaunchKernelGGL((lr_pack_kernel<DT>), gW, dim3(256), 0, st, la);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? SLICER_OK : hip_fail(e);
 }
@@ -243,6 +297,34 @@ int slicer_encode(const void* x, slicer_dtype dt, int64_t rows, int64_t row_len,
         if (timed) SLICER_HIP(hipEventRecord(g_ev_stop, st));
         ea.only_flagged = sa.fallback;
         ea.rows_per_wg = (rows + 1023) / 1024;     // few workgroups: flagged rows are rare
+    }
+    if (!ea.only_flagged && p.large_C && ((uintptr_t)x & 15) == 0) {
+        // long rows: multi-workgroup stages; rows they cannot hold are flagged for the generic kernel
+        LargeArgs la;
+        la.x = x; la.R = rows; la.N = row_len; la.k = p.k;
+        la.M = n_blocks; la.w = p.w; la.nq = ea.nq;
+        for (int t = 0; t < kMaxQ; ++t) la.qlist[t] = ea.qlist[t];
+        la.beta = distortion_budget; la.cap_words = p.cap_words;
+        la.C = p.large_C; la.LC = p.large_LC; la.capL = p.large_capL;
+        la.ch_cum = (u32*)(ws + p.lo_ch_cum);     la.ch_off = (u32*)(ws + p.lo_ch_off);
+        la.L = (u64*)(ws + p.lo_L);               la.Lblk = (uint8_t*)(ws + p.lo_Lblk);
+        la.fine_pos = (u32*)(ws + p.lo_fine_pos); la.fine_neg = (u32*)(ws + p.lo_fine_neg);
+        la.rowst = (u32*)(ws + p.lo_rowst);       la.thr = (u64*)(ws + p.lo_thr);
+        la.blk_start = (u32*)(ws + p.lo_blk_start); la.blkcnt = (u32*)(ws + p.lo_blkcnt);
+        la.vminb = (u32*)(ws + p.lo_vminb);       la.vmaxb = (u32*)(ws + p.lo_vmaxb);
+        la.sums = (u64*)(ws + p.lo_sums);         la.qsel = (u32*)(ws + p.lo_qsel);
+        la.inv_sel = (float*)(ws + p.lo_inv_sel); la.code_off = (u64*)(ws + p.lo_code_off);
+        la.bo_idx = ea.bo_idx; la.bo_val = ea.bo_val;
+        la.row_words = ea.row_words; la.slots = ea.slots;
+        la.fallback = (u32*)(ws + p.off_fallback);
+        la.mv = ea.mv;
+        const bool timed = g_ev_start && g_ev_stop;
+        if (timed) SLICER_HIP(hipEventRecord(g_ev_start, st));
+        rc = dt == SLICER_F32 ? launch_large<0>(la, p, st) : launch_large<1>(la, p, st);
+        if (rc) return rc;
+        if (timed) SLICER_HIP(hipEventRecord(g_ev_stop, st));
+        ea.only_flagged = la.fallback;
+        ea.rows_per_wg = 1;
     }
     rc = dt == SLICER_F32 ? launch_encode<0>(ea, st) : launch_encode<1>(ea, st);
     if (rc) return rc;

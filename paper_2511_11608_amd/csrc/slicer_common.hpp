@@ -151,6 +151,58 @@ __device__ inline u32 energy_grid(u32 bits, int e)
     return q;
 }
 
+// ---- wave-level primitives without LDS traffic -------------------------------------
+
+__device__ inline void wave_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+__device__ inline u32 bcast(u32 v, int src) { return (u32)__builtin_amdgcn_readlane((int)v, src); }
+
+template <int CTRL, int ROW_MASK, int BANK_MASK>
+__device__ inline u32 dpp_get(u32 v)
+{
+    return (u32)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, BANK_MASK, false);
+}
+
+// Inclusive prefix sum over the 64 lanes with data-parallel-primitive moves:
+// shifts inside each row of 16 lanes, then the row totals carried across rows.
+__device__ inline u32 wave_scan_dpp(u32 v)
+{
+    u32 r = v + dpp_get<0x111, 0xf, 0xf>(v);     // row_shr:1
+    r += dpp_get<0x112, 0xf, 0xf>(v);            // row_shr:2
+    r += dpp_get<0x113, 0xf, 0xf>(v);            // row_shr:3
+    r += dpp_get<0x114, 0xf, 0xe>(r);            // row_shr:4, lanes 4..15 of a row
+    r += dpp_get<0x118, 0xf, 0xc>(r);            // row_shr:8, lanes 8..15 of a row
+    r += dpp_get<0x142, 0xa, 0xf>(r);            // lane 15 of rows 0,2 -> rows 1,3
+    r += dpp_get<0x143, 0xc, 0xf>(r);            // lane 31 -> rows 2,3
+    return r;
+}
+
+// Maximum over the 64 lanes (unsigned), same data movement as the scan.
+__device__ inline u32 wave_max_dpp(u32 v)
+{
+    u32 r = max(v, dpp_get<0x111, 0xf, 0xf>(v));
+    r = max(r, dpp_get<0x112, 0xf, 0xf>(v));
+    r = max(r, dpp_get<0x113, 0xf, 0xf>(v));
+    r = max(r, dpp_get<0x114, 0xf, 0xe>(r));
+    r = max(r, dpp_get<0x118, 0xf, 0xc>(r));
+    r = max(r, dpp_get<0x142, 0xa, 0xf>(r));
+    r = max(r, dpp_get<0x143, 0xc, 0xf>(r));
+    return bcast(r, kWave - 1);
+}
+
+// x / d for x < 2^16 and 1 <= d < 2^16 (float estimate with a +-1 repair)
+__device__ inline u32 udiv16(u32 x, u32 d)
+{
+    u32 q = (u32)((float)x * (1.0f / (float)d));
+    if (q * d > x) --q;
+    if ((q + 1) * d <= x) ++q;
+    return q;
+}
+
 // ---- bit fields in a word stream (LSB first) -------------------------------------
 
 __device__ inline u32 read_bits(const u32* __restrict__ words, u64 bitpos, int nbits)

@@ -1,0 +1,686 @@
+// Encoder for long rows (tens of thousands of elements and more): every pass over a
+// row is spread over many workgroups, the per-row state lives in the workspace, and
+// the stages are separate launches on the caller's stream:
+//
+//   hist      per 8192-element chunk: 2048-bin histogram of the key's top 11 bits, stored
+//             as "elements at or above the bin" (so sums over chunks are cumulative too)
+//   select    per row: the bin B1 that holds overall rank k-1, the list offsets of the chunks
+//   compact   per chunk: ordered compaction of everything at or above B1 into the row's
+//             list L (ascending index) + a 16384-bin fine histogram per sign class
+//   bounds    per row: ranks of the fine bins; the comp of overall rank k-1 (ATKF cut,
+//             Sec. 3.1) and of class ranks j*K-1 (block boundaries, Sec. 3.2), each resolved
+//             inside its bin by pairwise comparison of the bin's members
+//   blockcount / scatter   per 2048 list entries: block id, per-block counts, block min/max;
+//             then a stable split by block id (ascending index inside a block)
+//   abq / choose / pack    integer ABQ sums (Sec. 3.2.1) with 64-bit atomics, per-block
+//             bitwidth, bit offsets, and the row's stream image 4096 words at a time
+//
+// comp = key << w | (2^w - 1 - index): larger comp = larger magnitude, then lower index.
+// Rows that do not fit the lists (heavy ties, more zeros than dropped elements) are
+// flagged and redone by the generic kernel.
+#pragma once
+
+#include "slicer_common.hpp"
+#include "slicer_encode_generic.hpp"
+
+namespace slicer {
+
+constexpr int kLCH = 8192;          // elements per hist / compact workgroup
+constexpr int kLBins = 2048;        // coarse bins: top 11 bits of the key
+constexpr int kFB = 16384;          // fine bins per sign class
+constexpr int kLCE = 2048;          // list entries per blockcount / scatter workgroup
+constexpr int kPCH = 4096;          // block-ordered positions per abq workgroup
+constexpr int kCutCap = 4096;       // members of the top-K cut bin (= kMaxB2 * kTgtCap: the two lists share storage)
+constexpr int kTgtCap = 32;         // members of one boundary bin (per class)
+constexpr u64 kTop = 1ull << 63;
+
+struct LargeArgs {
+    const void* x;
+    int64_t R, N, k;
+    int M, w, nq;
+    int qlist[kMaxQ];
+    double beta;
+    u64 cap_words;
+    int C, LC;              // chunks per row, list chunks per row
+    u32 capL;               // list capacity per row
+    u32* ch_cum;            // [R][C][kLBins]  elements of the chunk at or above the bin
+    u32* ch_off;            // [R][C]
+    u64* L;                 // [R][capL]       class << 63 | key << 32 | index
+    uint8_t* Lblk;          // [R][capL]       block of the entry, 255 = not kept
+    u32* fine_pos;          // [R][kFB]        counts, then first class rank of the bin
+    u32* fine_neg;
+    u32* rowst;             // [R][16]  0 t_lo 1 sh 2 nL 3 n_pos 4 n_neg 5 K0 6 K1 7 ntg 8 nt0
+    u64* thr;               // [R][1 + kMaxB2] thr[0] = cut comp, then boundaries (class on top)
+    u32* blk_start;         // [R][B2 + 1]
+    u32* blkcnt;            // [R][LC][B2]
+    u32* vminb;             // [R][B2]  keys
+    u32* vmaxb;
+    u64* sums;              // [R][B2][nq + 1]
+    u32* qsel;              // [R][B2]
+    float* inv_sel;         // [R][B2]
+    u64* code_off;          // [R][B2 + 1]
+    u32* bo_idx;            // [R][k]
+    u32* bo_val;            // [R][k]
+    u64* row_words;
+    u32* slots;
+    u32* fallback;
+    MetaView mv;
+};
+
+template <int DT>
+__global__ __launch_bounds__(256) void lr_hist_kernel(LargeArgs a)
+{
+    typedef Elem<DT> E;
+    typedef typename E::raw_t raw_t;
+    constexpr int KS = E::kKeyBits - 11;
+    __shared__ u32 h[kLBins];
+    __shared__ u32 scr[256 / kWave + 1];
+    const int tid = threadIdx.x, c = blockIdx.x;
+    const int64_t r = blockIdx.y;
+    const int B2 = 2 * a.M;
+    for (int i = tid; i < kLBins; i += 256) h[i] = 0;
+    // this launch also clears what later stages accumulate into
+    for (int i = c * 256 + tid; i < kFB; i += a.C * 256) {
+        a.fine_pos[(size_t)r * kFB + i] = 0;
+        a.fine_neg[(size_t)r * kFB + i] = 0;
+    }
+    if (c == 0) {
+        for (int b = tid; b < B2; b += 256) { a.vminb[r * B2 + b] = 0xFFFFFFFFu; a.vmaxb[r * B2 + b] = 0; }
+        for (int i = tid; i < B2 * (a.nq + 1); i += 256) a.sums[(size_t)r * B2 * (a.nq + 1) + i] = 0;
+    }
+    __syncthreads();
+    const raw_t* __restrict__ xr = (const raw_t*)a.x + (size_t)r * (size_t)a.N;
+    const int64_t i0 = (int64_t)c * kLCH, i1 = i0 + kLCH < a.N ? i0 + kLCH : a.N;
+    for (int64_t i = i0 + tid; i < i1; i += 256) atomicAdd(&h[E::key(xr[i]) >> KS], 1u);
+    __syncthreads();
+    // "at or above": running sum from the top bin down; thread t owns the 8 bins below 2048 - 8t
+    const int hi = kLBins - tid * 8;
+    u32 local = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) local += h[hi - 1 - j];
+    u32 tot;
+    u32 acc = block_excl_scan<256>(local, scr, &tot);
+    u32* __restrict__ out = a.ch_cum + ((size_t)r * a.C + c) * kLBins;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { acc += h[hi - 1 - j]; out[hi - 1 - j] = acc; }
+}
+
+template <int DT>
+__global__ __launch_bounds__(1024) void lr_select_kernel(LargeArgs a)
+{
+    constexpr int KS = Elem<DT>::kKeyBits - 11;
+    __shared__ u32 rc[kLBins + 1];
+    __shared__ u32 scr[1024 / kWave + 1];
+    __shared__ u32 res[2];
+    const int tid = threadIdx.x;
+    const int64_t r = blockIdx.x;
+    for (int bin = tid; bin < kLBins; bin += 1024) {
+        u32 s = 0;
+        for (int c = 0; c < a.C; ++c) s += a.ch_cum[((size_t)r * a.C + c) * kLBins + bin];
+        rc[bin] = s;
+    }
+    if (tid == 0) { rc[kLBins] = 0; res[0] = 0; res[1] = 0; }
+    __syncthreads();
+    const u32 km1 = a.k > 0 ? (u32)(a.k - 1) : 0u;
+    for (int bin = tid; bin < kLBins; bin += 1024) {
+        if (rc[bin] > km1 && rc[bin + 1] <= km1) res[0] = (u32)bin;       // holds rank k-1
+        if (rc[bin] > 0 && rc[bin + 1] == 0) res[1] = (u32)bin;           // highest occupied
+    }
+    __syncthreads();
+    const u32 B1 = res[0], top = res[1];
+    const u32 nL = rc[B1];
+    const u32 t_lo = B1 << KS;
+    const u32 range = (((top + 1u) << KS) - 1u) - t_lo;
+    const int sh = range < (u32)kFB ? 0 : (32 - __clz((int)range)) - 14;
+    // bin 0 holds the exact zeros, which are never sent: such rows go to the generic kernel
+    const bool bad = a.k > 0 && (B1 == 0 || nL > a.capL);
+    const bool live = a.k > 0 && !bad;
+    u32 v = 0;
+    if (live && tid < a.C) v = a.ch_cum[((size_t)r * a.C + tid) * kLBins + B1];
+    u32 tot;
+    const u32 ex = block_excl_scan<1024>(v, scr, &tot);
+    if (tid < a.C) a.ch_off[(size_t)r * a.C + tid] = ex;
+    if (tid == 0) {
+        u32* st = a.rowst + (size_t)r * 16;
+        st[0] = t_lo; st[1] = (u32)sh; st[2] = live ? nL : 0u;
+        a.fallback[r] = bad ? 1u : 0u;
+    }
+}
+
+template <int DT>
+__global__ __launch_bounds__(256) void lr_compact_kernel(LargeArgs a)
+{
+    typedef Elem<DT> E;
+    constexpr int EPC = DT == 0 ? 4 : 8;
+    constexpr int NJ = kLCH / 4 / (kWave * EPC);          // 16-byte loads per lane
+    __shared__ u32 wtot[4];
+    const int tid = threadIdx.x, c = blockIdx.x, wid = tid / kWave;
+    const u32 lane = lane_id();
+    const int64_t r = blockIdx.y;
+    if (a.fallback[r]) return;
+    const u32* st = a.rowst + (size_t)r * 16;
+    const u32 t_lo = st[0], nL = st[2];
+    const int sh = (int)st[1];
+    if (nL == 0) return;
+    const int64_t seg0 = (int64_t)c * kLCH + (int64_t)wid * (kLCH / 4);
+    const uint4* __restrict__ xr4 = (const uint4*)((const char*)a.x + ((size_t)r * (size_t)a.N + (size_t)seg0) * (DT == 0 ? 4 : 2));
+    uint4 v[NJ];
+    u32 cntj[NJ];
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+        const int64_t e0 = seg0 + (int64_t)(j * kWave + (int)lane) * EPC;
+        v[j] = e0 < a.N ? xr4[j * kWave + lane] : make_uint4(0, 0, 0, 0);
+    }
+    auto raw_of = [&](int j, int e) -> u32 {
+        const u32 wd = (DT == 0) ? (e == 0 ? v[j].x : e == 1 ? v[j].y : e == 2 ? v[j].z : v[j].w)
+                                 : ((e >> 1) == 0 ? v[j].x : (e >> 1) == 1 ? v[j].y : (e >> 1) == 2 ? v[j].z : v[j].w);
+        return (DT == 0) ? wd : ((e & 1) ? wd >> 16 : wd & 0xFFFFu);
+    };
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+        u32 n1 = 0;
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) n1 += E::key((typename E::raw_t)raw_of(j, e)) >= t_lo ? 1u : 0u;   // t_lo > 0: zeros drop out
+        cntj[j] = n1;
+    }
+    u32 basej[NJ];
+    u32 wsum = 0;
+#pragma unroll
+    for (int g = 0; g < (NJ + 2) / 3; ++g) {              // three counts per scan, 10-bit fields
+        u32 pk = cntj[3 * g];
+        if (3 * g + 1 < NJ) pk |= cntj[3 * g + 1] << 10;
+        if (3 * g + 2 < NJ) pk |= cntj[3 * g + 2] << 20;
+        const u32 incl = wave_scan_dpp(pk);
+        const u32 tot = bcast(incl, kWave - 1);
+        const u32 ex = incl - pk;
+#pragma unroll
+        for (int jj = 0; jj < 3; ++jj) {
+            if (3 * g + jj < NJ) {
+                basej[3 * g + jj] = wsum + ((ex >> (10 * jj)) & 0x3FFu);
+                wsum += (tot >> (10 * jj)) & 0x3FFu;
+            }
+        }
+    }
+    if (lane == 0) wtot[wid] = wsum;
+    __syncthreads();
+    u32 wbase = a.ch_off[(size_t)r * a.C + c];
+    for (int v2 = 0; v2 < wid; ++v2) wbase += wtot[v2];
+    u64* __restrict__ L = a.L + (size_t)r * a.capL;
+    u32* __restrict__ fp = a.fine_pos + (size_t)r * kFB;
+    u32* __restrict__ fn = a.fine_neg + (size_t)r * kFB;
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+        u32 pos = wbase + basej[j];
+        const u32 idx0 = (u32)(seg0 + (int64_t)(j * kWave + (int)lane) * EPC);
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) {
+            const u32 raw = raw_of(j, e);
+            const u32 key = E::key((typename E::raw_t)raw);
+            if (key >= t_lo) {
+                const u32 neg = E::neg((typename E::raw_t)raw);
+                if (pos < a.capL) L[pos] = ((u64)neg << 63) | ((u64)key << 32) | (u64)(idx0 + e);
+                atomicAdd(neg ? &fn[(key - t_lo) >> sh] : &fp[(key - t_lo) >> sh], 1u);
+                ++pos;
+            }
+        }
+    }
+}
+
+__device__ inline u64 lr_comp(u64 e, int w)       // key << w | inverted index
+{
+    return (((e >> 32) & 0x7FFFFFFFull) << w) | (((1ull << w) - 1ull) - (e & 0xFFFFFFFFull));
+}
+
+__global__ __launch_bounds__(1024) void lr_bounds_kernel(LargeArgs a)
+{
+    __shared__ u64 mem[kCutCap];                 // cut-bin members, later kMaxB2 x kTgtCap boundary members
+    __shared__ u32 bitmap[kFB / 32];
+    __shared__ u32 scr[1024 / kWave + 1];
+    __shared__ u32 tgbin[kMaxB2], tgrem[kMaxB2], tcnt[kMaxB2];
+    __shared__ u32 s_cut[3], s_n[4];
+    __shared__ u64 s_thrK;
+    const int tid = threadIdx.x;
+    const int64_t r = blockIdx.x;
+    if (a.fallback[r]) return;
+    const int M = a.M, B2 = 2 * a.M, w = a.w;
+    u32* st = a.rowst + (size_t)r * 16;
+    const u32 t_lo = st[0], nL = st[2];
+    const int sh = (int)st[1];
+    const u64* __restrict__ L = a.L + (size_t)r * a.capL;
+    u32* __restrict__ fp = a.fine_pos + (size_t)r * kFB;
+    u32* __restrict__ fn = a.fine_neg + (size_t)r * kFB;
+    const u32 k = (u32)a.k;
+
+    for (int i = tid; i < kFB / 32; i += 1024) bitmap[i] = 0;
+    if (tid < kMaxB2) tcnt[tid] = 0;
+    if (tid == 0) { s_cut[0] = 0xFFFFFFFFu; s_n[0] = 0; s_n[1] = 0; s_n[2] = 0; s_n[3] = 0; s_thrK = 0; }
+
+    // (a) first rank of every fine bin, per class, counted from the top; the cut bin
+    const int hi = kFB - tid * 16;
+    u32 cp[16], cn[16];
+    u32 lp = 0, ln = 0;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) { cp[j] = fp[hi - 1 - j]; cn[j] = fn[hi - 1 - j]; lp += cp[j]; ln += cn[j]; }
+    u32 tp, tn;
+    u32 ap = block_excl_scan<1024>(lp, scr, &tp);
+    u32 an = block_excl_scan<1024>(ln, scr, &tn);
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+        fp[hi - 1 - j] = ap; fn[hi - 1 - j] = an;
+        const u32 cnt = cp[j] + cn[j];
+        if (nL > k && cnt && ap + an <= k - 1 && k - 1 < ap + an + cnt) { s_cut[0] = (u32)(hi - 1 - j); s_cut[1] = ap; s_cut[2] = an; }
+        ap += cp[j]; an += cn[j];
+    }
+    __syncthreads();
+
+    // (b) ATKF cut: the comp of overall rank k-1 inside the cut bin
+    u32 n_pos = tp, n_neg = tn;
+    u64 thrK = 0;
+    if (nL > k) {
+        const u32 cut = s_cut[0];
+        for (u32 p = tid; p < nL; p += 1024) {
+            const u64 e = L[p];
+            if ((((u32)(e >> 32) & 0x7FFFFFFFu) - t_lo) >> sh == cut) {
+                const u32 slot = atomicAdd(&s_n[0], 1u);
+                if (slot < (u32)kCutCap) mem[slot] = (e & kTop) | lr_comp(e, w);
+            }
+        }
+        __syncthreads();
+        const u32 nm = s_n[0];
+        if (nm > (u32)kCutCap) { if (tid == 0) a.fallback[r] = 1u; return; }
+        const u32 rem = (k - 1) - (s_cut[1] + s_cut[2]);
+        for (u32 i = tid; i < nm; i += 1024) {
+            const u64 me = mem[i] & ~kTop;
+            u32 gt = 0;
+            for (u32 j = 0; j < nm; ++j) gt += (mem[j] & ~kTop) > me ? 1u : 0u;
+            if (gt == rem) s_thrK = me;
+            if (gt <= rem) atomicAdd((mem[i] & kTop) ? &s_n[2] : &s_n[1], 1u);
+        }
+        __syncthreads();
+        thrK = s_thrK;
+        n_pos = s_cut[1] + s_n[1];
+        n_neg = s_cut[2] + s_n[2];
+    }
+    __syncthreads();
+
+    // (c) block boundaries: class ranks j*K-1, one thread per boundary
+    const u32 Kc0 = n_pos / (u32)M, Kc1 = n_neg / (u32)M;
+    const int nt0 = Kc0 ? M - 1 : 0, nt1 = Kc1 ? M - 1 : 0, ntg = nt0 + nt1;
+    if (tid < ntg) {
+        const int cls = tid >= nt0 ? 1 : 0;
+        const int j = (cls ? tid - nt0 : tid) + 1;
+        const u32 Rk = (u32)j * (cls ? Kc1 : Kc0) - 1u;
+        const u32* pre = cls ? fn : fp;
+        int lo = 0, hi2 = kFB - 1;                   // smallest bin whose first class rank is <= Rk
+        while (lo < hi2) {
+            const int mid = (lo + hi2) >> 1;
+            if (pre[mid] <= Rk) hi2 = mid; else lo = mid + 1;
+        }
+        tgbin[tid] = (u32)lo;
+        tgrem[tid] = Rk - pre[lo];
+        atomicOr(&bitmap[lo >> 5], 1u << (lo & 31));
+    }
+    __syncthreads();
+    u64* tmem = mem;                                 // [ntg][kTgtCap]
+    for (u32 p = tid; p < nL; p += 1024) {
+        const u64 e = L[p];
+        const u32 d = (((u32)(e >> 32) & 0x7FFFFFFFu) - t_lo) >> sh;
+        if ((bitmap[d >> 5] >> (d & 31)) & 1u) {
+            const int cls = (int)(e >> 63);
+            const int t0 = cls ? nt0 : 0, t1 = cls ? ntg : nt0;
+            for (int t = t0; t < t1; ++t) {
+                if (tgbin[t] == d) {
+                    const u32 slot = atomicAdd(&tcnt[t], 1u);
+                    if (slot < (u32)kTgtCap) tmem[t * kTgtCap + slot] = lr_comp(e, w);
+                }
+            }
+        }
+    }
+    __syncthreads();
+    int over = 0;
+    if (tid < ntg && tcnt[tid] > (u32)kTgtCap) over = 1;
+    if (__syncthreads_or(over)) { if (tid == 0) a.fallback[r] = 1u; return; }
+    u64* __restrict__ thr = a.thr + (size_t)r * (1 + kMaxB2);
+    for (int t = tid / kTgtCap; t < ntg; t += 1024 / kTgtCap) {
+        const u32 i = (u32)tid % kTgtCap, cnt = tcnt[t];
+        if (i < cnt) {
+            const u64 me = tmem[t * kTgtCap + i];
+            u32 gt = 0;
+            for (u32 j = 0; j < cnt; ++j) gt += tmem[t * kTgtCap + j] > me ? 1u : 0u;
+            if (gt == tgrem[t]) thr[1 + t] = me | (t >= nt0 ? 0ull : kTop);
+        }
+    }
+    if (tid == 0) {
+        thr[0] = thrK;
+        st[3] = n_pos; st[4] = n_neg; st[5] = Kc0; st[6] = Kc1; st[7] = (u32)ntg; st[8] = (u32)nt0;
+    }
+    for (int b = tid; b <= B2; b += 1024) {          // K, ..., K, K + remainder per class
+        u32 v;
+        if (b == B2) v = n_pos + n_neg;
+        else { const int s = b >= M ? 1 : 0, m = b - s * M; v = (s ? n_pos : 0u) + (u32)m * (s ? Kc1 : Kc0); }
+        a.blk_start[(size_t)r * (B2 + 1) + b] = v;
+    }
+}
+
+__global__ __launch_bounds__(256) void lr_blockcount_kernel(LargeArgs a)
+{
+    __shared__ u64 thr_s[1 + kMaxB2];
+    __shared__ u32 cnt[kMaxB2], kmin[kMaxB2], kmax[kMaxB2];
+    const int tid = threadIdx.x, lc = blockIdx.x;
+    const int64_t r = blockIdx.y;
+    if (a.fallback[r]) return;
+    const int M = a.M, B2 = 2 * a.M, w = a.w;
+    const u32* st = a.rowst + (size_t)r * 16;
+    const u32 nL = st[2];
+    const u32 Kc[2] = { st[5], st[6] };
+    const int ntg = (int)st[7], nt0 = (int)st[8];
+    for (int i = tid; i <= ntg; i += 256) thr_s[i] = a.thr[(size_t)r * (1 + kMaxB2) + i];
+    for (int b = tid; b < B2; b += 256) { cnt[b] = 0; kmin[b] = 0xFFFFFFFFu; kmax[b] = 0; }
+    __syncthreads();
+    const u64 thrK = thr_s[0];
+    const u64* __restrict__ L = a.L + (size_t)r * a.capL;
+    uint8_t* __restrict__ Lblk = a.Lblk + (size_t)r * a.capL;
+    const u32 p0 = (u32)lc * kLCE, p1 = p0 + kLCE < nL ? p0 + kLCE : nL;
+    for (u32 p = p0 + tid; p < p1; p += 256) {
+        const u64 e = L[p];
+        const u64 comp = lr_comp(e, w);
+        u32 b = 255u;
+        if (comp >= thrK) {
+            const u32 cls = (u32)(e >> 63);
+            const u64 cx = comp | (cls ? 0ull : kTop);
+            int lo = 0, hi = ntg;                   // boundaries above cx (they are sorted, largest first)
+            while (lo < hi) { const int mid = (lo + hi) >> 1; if (thr_s[1 + mid] > cx) lo = mid + 1; else hi = mid; }
+            const u32 m = Kc[cls] ? (u32)lo - (cls ? (u32)nt0 : 0u) : (u32)(M - 1);
+            b = cls * (u32)M + m;
+            const u32 key = (u32)(e >> 32) & 0x7FFFFFFFu;
+            atomicAdd(&cnt[b], 1u);
+            atomicMin(&kmin[b], key);
+            atomicMax(&kmax[b], key);
+        }
+        Lblk[p] = (uint8_t)b;
+    }
+    __syncthreads();
+    for (int b = tid; b < B2; b += 256) {
+        a.blkcnt[((size_t)r * a.LC + lc) * B2 + b] = cnt[b];
+        if (cnt[b]) { atomicMin(&a.vminb[r * B2 + b], kmin[b]); atomicMax(&a.vmaxb[r * B2 + b], kmax[b]); }
+    }
+}
+
+template <int DT>
+__global__ __launch_bounds__(256) void lr_scatter_kernel(LargeArgs a)
+{
+    typedef Elem<DT> E;
+    __shared__ u32 base[kMaxB2];
+    __shared__ u32 cw[4][kMaxB2];
+    const int tid = threadIdx.x, lc = blockIdx.x, wid = tid / kWave;
+    const u32 lane = lane_id();
+    const int64_t r = blockIdx.y;
+    if (a.fallback[r]) return;
+    const int B2 = 2 * a.M;
+    const u32 nL = a.rowst[(size_t)r * 16 + 2];
+    if ((u32)lc * kLCE >= nL) return;
+    for (int b = tid; b < B2; b += 256) {
+        u32 s = a.blk_start[(size_t)r * (B2 + 1) + b];
+        for (int l2 = 0; l2 < lc; ++l2) s += a.blkcnt[((size_t)r * a.LC + l2) * B2 + b];
+        base[b] = s;
+        for (int v2 = 0; v2 < 4; ++v2) cw[v2][b] = 0;
+    }
+    __syncthreads();
+    int nbits = 0;
+    while ((1 << nbits) < B2) ++nbits;
+    const u64* __restrict__ L = a.L + (size_t)r * a.capL;
+    const uint8_t* __restrict__ Lblk = a.Lblk + (size_t)r * a.capL;
+    u32* __restrict__ bo_idx = a.bo_idx + (size_t)r * (size_t)a.k;
+    u32* __restrict__ bo_val = a.bo_val + (size_t)r * (size_t)a.k;
+    for (int j = 0; j < kLCE / 256; ++j) {
+        const u32 p = (u32)lc * kLCE + (u32)j * 256 + (u32)tid;
+        u32 b = 0;
+        bool kept = false;
+        u64 e = 0;
+        if (p < nL) { b = Lblk[p]; kept = b != 255u; if (kept) e = L[p]; else b = 0; }
+        const u64 km = __ballot(kept);
+        u32 plo = (u32)km, phi = (u32)(km >> 32);
+        for (int bit = 0; bit < nbits; ++bit) {
+            const u32 onm = (u32)__builtin_amdgcn_sbfe((int)b, (u32)bit, 1u);
+            const u64 bal = __ballot(onm != 0u);
+            plo &= ~((u32)bal ^ onm);
+            phi &= ~((u32)(bal >> 32) ^ onm);
+        }
+        const u32 before = __builtin_amdgcn_mbcnt_hi(phi, __builtin_amdgcn_mbcnt_lo(plo, 0u));
+        if (kept && before == 0) cw[wid][b] = (u32)__popc(plo) + (u32)__popc(phi);
+        __syncthreads();
+        if (kept) {
+            u32 pos = base[b] + before;
+            for (int v2 = 0; v2 < wid; ++v2) pos += cw[v2][b];
+            if ((int64_t)pos < a.k) {
+                bo_idx[pos] = (u32)e;
+                bo_val[pos] = DT == 0 ? ((u32)(e >> 32) & 0x7FFFFFFFu) : (((u32)(e >> 32) & 0x7FFFu) << 16);
+            }
+        }
+        __syncthreads();
+        for (int bb = tid; bb < B2; bb += 256) {
+            u32 s = 0;
+            for (int v2 = 0; v2 < 4; ++v2) { s += cw[v2][bb]; cw[v2][bb] = 0; }
+            base[bb] += s;
+        }
+        __syncthreads();
+    }
+}
+
+template <int DT>
+__global__ __launch_bounds__(256) void lr_abq_kernel(LargeArgs a)
+{
+    typedef Elem<DT> E;
+    __shared__ u32 bs[kMaxB2 + 1];
+    __shared__ float vminf[kMaxB2];
+    __shared__ int e_tab[kMaxB2], degen[kMaxB2];
+    __shared__ float inv_tab[kMaxB2][kMaxQ];
+    __shared__ u64 sums[kMaxB2][kMaxQ + 1];
+    const int tid = threadIdx.x, pc = blockIdx.x;
+    const int64_t r = blockIdx.y;
+    if (a.fallback[r]) return;
+    const int B2 = 2 * a.M, nq = a.nq;
+    const u32* st = a.rowst + (size_t)r * 16;
+    const u32 n = st[3] + st[4];
+    const u32 p0 = (u32)pc * kPCH, p1 = p0 + kPCH < n ? p0 + kPCH : n;
+    if (p0 >= n) return;
+    for (int b = tid; b <= B2; b += 256) bs[b] = a.blk_start[(size_t)r * (B2 + 1) + b];
+    __syncthreads();
+    for (int b = tid; b < B2; b += 256) {
+        const u32 cnt = bs[b + 1] - bs[b];
+        int dg = 1, e = 0;
+        float rng = 0.f, vmin = 0.f;
+        if (cnt) {
+            const u32 lo = E::value_bits(a.vminb[r * B2 + b]), hi = E::value_bits(a.vmaxb[r * B2 + b]);
+            vmin = __uint_as_float(lo);
+            rng = __uint_as_float(hi) - vmin;
+            dg = !(rng >= 0x1p-100f);
+            e = ilogb_bits(hi) + 1;
+        }
+        vminf[b] = vmin; degen[b] = dg; e_tab[b] = e;
+        for (int t = 0; t < nq; ++t) {
+            inv_tab[b][t] = dg ? 0.f : (float)((1u << a.qlist[t]) - 1u) / rng;
+            sums[b][t] = 0;
+        }
+        sums[b][kMaxQ] = 0;
+    }
+    __syncthreads();
+    {
+        const u32* __restrict__ bo_val = a.bo_val + (size_t)r * (size_t)a.k;
+        int cur = -1;
+        u64 acc[kMaxQ];
+        u64 accE = 0;
+#pragma unroll
+        for (int t = 0; t < kMaxQ; ++t) acc[t] = 0;
+        float vmin = 0.f;
+        int e = 0, dg = 1;
+        auto flush = [&]() {
+            if (cur < 0) return;
+#pragma unroll
+            for (int t = 0; t < kMaxQ; ++t)
+                if (t < nq && acc[t]) { atomicAdd(&sums[cur][t], acc[t]); acc[t] = 0; }
+            if (accE) { atomicAdd(&sums[cur][kMaxQ], accE); accE = 0; }
+        };
+        for (u32 p = p0 + tid; p < p1; p += 256) {
+            int b = cur < 0 ? 0 : cur;
+            while (b < B2 - 1 && p >= bs[b + 1]) ++b;
+            if (b != cur) { flush(); cur = b; vmin = vminf[b]; e = e_tab[b]; dg = degen[b]; }
+            const float av = __uint_as_float(bo_val[p]);
+            const u64 A = (u64)(u32)rintf(ldexpf(av, 20 - e));
+            accE += A * A;
+            if (!dg) {
+                const float d = av - vmin;
+#pragma unroll
+                for (int t = 0; t < kMaxQ; ++t) {
+                    if (t < nq) {
+                        const float y = d * inv_tab[b][t];
+                        const float c = fminf(fmaxf(rintf(y), 0.f), (float)((1u << a.qlist[t]) - 1u));
+                        const int rho = (int)rintf((y - c) * 32768.0f);
+                        acc[t] += (u64)(u32)(rho * rho);
+                    }
+                }
+            }
+        }
+        flush();
+    }
+    __syncthreads();
+    for (int i = tid; i < B2 * (nq + 1); i += 256) {
+        const int b = i / (nq + 1), t = i - b * (nq + 1);
+        const u64 v = sums[b][t == nq ? kMaxQ : t];
+        if (v) atomicAdd(&a.sums[((size_t)r * B2 + b) * (nq + 1) + t], v);
+    }
+}
+
+template <int DT>
+__global__ __launch_bounds__(128) void lr_choose_kernel(LargeArgs a)
+{
+    typedef Elem<DT> E;
+    __shared__ u32 bits_s[kMaxB2];
+    const int b = threadIdx.x;
+    const int64_t r = blockIdx.x;
+    if (a.fallback[r]) return;
+    const int B2 = 2 * a.M, nq = a.nq;
+    const u32* st = a.rowst + (size_t)r * 16;
+    const u32 n = st[3] + st[4];
+    if (b < B2) {
+        const u32 cnt = a.blk_start[(size_t)r * (B2 + 1) + b + 1] - a.blk_start[(size_t)r * (B2 + 1) + b];
+        float vmin = 0.f, vmax = 0.f, inv = 0.f;
+        int q = a.qlist[0];
+        u32 flag = 0;
+        if (cnt) {
+            const u32 hi = E::value_bits(a.vmaxb[r * B2 + b]);
+            vmin = __uint_as_float(E::value_bits(a.vminb[r * B2 + b]));
+            vmax = __uint_as_float(hi);
+            const float rng = vmax - vmin;
+            if (rng >= 0x1p-100f) {
+                const int e = ilogb_bits(hi) + 1;
+                const u64* sm = a.sums + ((size_t)r * B2 + b) * (nq + 1);
+                const double rhs = a.beta * ldexp((double)sm[nq], 2 * e - 40);
+                flag = 0x80u;
+                for (int t = 0; t < nq && flag; ++t) {
+                    const float Lq = (float)((1u << a.qlist[t]) - 1u);
+                    const float o = rng / Lq;
+                    const double lhs = ((double)o * (double)o) * (double)sm[t] * 0x1p-30;
+                    q = a.qlist[t]; inv = Lq / rng;
+                    if (lhs <= rhs) flag = 0;
+                }
+            }
+        }
+        a.qsel[r * B2 + b] = (u32)q;
+        a.inv_sel[r * B2 + b] = inv;
+        bits_s[b] = cnt * (u32)q;             // < 2^31 * 16 would overflow: the list capacity keeps cnt small
+        const size_t mi = (size_t)r * (size_t)B2 + b;
+        a.mv.vmin[mi] = vmin; a.mv.vmax[mi] = vmax; a.mv.q[mi] = (uint8_t)((u32)q | flag);
+    }
+    __syncthreads();
+    if (b == 0) {
+        u64 acc = 0;
+        u64* co = a.code_off + (size_t)r * (B2 + 1);
+        for (int i = 0; i < B2; ++i) { co[i] = acc; acc += bits_s[i]; }
+        co[B2] = acc;
+        const u64 bits = (u64)n * (u64)a.w + acc;
+        u64 words = (bits + 31) >> 5;
+        if (words > a.cap_words) words = a.cap_words;
+        a.row_words[r] = words;
+        a.mv.n_pos[r] = st[3];
+        a.mv.n_neg[r] = st[4];
+    }
+}
+
+template <int DT>
+__global__ __launch_bounds__(256) void lr_pack_kernel(LargeArgs a)
+{
+    typedef Elem<DT> E;
+    __shared__ u32 sA[kStageWords];
+    __shared__ u32 bs[kMaxB2 + 1], qsel[kMaxB2];
+    __shared__ u64 coff[kMaxB2 + 1];
+    __shared__ float vminf[kMaxB2], invs[kMaxB2];
+    __shared__ u32 s_range[2];
+    const int tid = threadIdx.x;
+    const int64_t r = blockIdx.y;
+    if (a.fallback[r]) return;
+    const int B2 = 2 * a.M, w = a.w;
+    const u64 row_words = a.row_words[r];
+    const u64 c0 = (u64)blockIdx.x * kStageWords;
+    if (c0 >= row_words) return;
+    const u32* st = a.rowst + (size_t)r * 16;
+    const u32 n = st[3] + st[4];
+    for (int b = tid; b <= B2; b += 256) {
+        bs[b] = a.blk_start[(size_t)r * (B2 + 1) + b];
+        coff[b] = a.code_off[(size_t)r * (B2 + 1) + b];
+        if (b < B2) {
+            qsel[b] = a.qsel[r * B2 + b];
+            invs[b] = a.inv_sel[r * B2 + b];
+            vminf[b] = __uint_as_float(E::value_bits(a.vminb[r * B2 + b]));
+        }
+    }
+    const u64 cw = row_words - c0 < (u64)kStageWords ? row_words - c0 : (u64)kStageWords;
+    const u64 lo = c0 << 5, hi = (c0 + cw) << 5;
+    const u64 idx_bits = (u64)n * (u64)w;
+    for (int i = tid; i < (int)cw; i += 256) sA[i] = 0;
+    __syncthreads();
+    if (tid == 0) {     // entries whose code field meets [lo, hi)
+        u32 plo = n, phi = 0;
+        for (int b = 0; b < B2; ++b) {
+            const u32 cnt = bs[b + 1] - bs[b];
+            if (!cnt) continue;
+            const u64 cs = idx_bits + coff[b], ce = idx_bits + coff[b + 1];
+            if (ce <= lo || cs >= hi) continue;
+            const u64 q = (u64)qsel[b];
+            const u64 jlo = ((lo > cs ? lo : cs) - cs) / q;
+            const u64 jhi = ((hi < ce ? hi : ce) - cs + q - 1) / q;
+            const u32 a0 = bs[b] + (u32)jlo, a1 = bs[b] + (u32)jhi;
+            plo = a0 < plo ? a0 : plo;
+            phi = a1 > phi ? a1 : phi;
+        }
+        s_range[0] = plo; s_range[1] = phi;
+    }
+    __syncthreads();
+    const u32* __restrict__ bo_idx = a.bo_idx + (size_t)r * (size_t)a.k;
+    const u32* __restrict__ bo_val = a.bo_val + (size_t)r * (size_t)a.k;
+    if (lo < idx_bits) {
+        const u64 q0 = lo / (u64)w;
+        u64 q1 = (hi + (u64)w - 1) / (u64)w;
+        if (q1 > n) q1 = n;
+        for (u64 p = q0 + tid; p < q1; p += 256) stage_or_bits(sA, lo, hi, p * (u64)w, bo_idx[p], w);
+    }
+    {
+        const u32 q0 = s_range[0], q1 = s_range[1];
+        int b = 0;
+        for (u32 p = q0 + tid; p < q1; p += 256) {
+            while (b < B2 - 1 && p >= bs[b + 1]) ++b;
+            const int q = (int)qsel[b];
+            u32 c = 0;
+            if (invs[b] != 0.f) {
+                const float y = (__uint_as_float(bo_val[p]) - vminf[b]) * invs[b];
+                c = (u32)fminf(fmaxf(rintf(y), 0.f), (float)((1u << q) - 1u));
+            }
+            stage_or_bits(sA, lo, hi, idx_bits + coff[b] + (u64)(p - bs[b]) * (u64)q, c, q);
+        }
+    }
+    __syncthreads();
+    u32* __restrict__ slot = a.slots + (size_t)r * (size_t)a.cap_words;
+    for (int i = tid; i < (int)cw; i += 256) slot[c0 + i] = sA[i];
+}
+
+}  // namespace slicer
