@@ -65,7 +65,7 @@ struct Plan {
     // long-row path (large_C == 0: not eligible)
     int large_C, large_LC;
     u32 large_capL;
-    size_t lo_ch_cum, lo_ch_off, lo_L, lo_Lblk, lo_fine_pos, lo_fine_neg, lo_rowst, lo_thr, lo_blk_start,
+    size_t lo_ch_cum, lo_ch_off, lo_L, lo_Lblk, lo_rowst, lo_thr, lo_blk_start,
            lo_blkcnt, lo_vminb, lo_vmaxb, lo_sums, lo_qsel, lo_inv_sel, lo_code_off;
 };
 
@@ -103,8 +103,6 @@ Plan make_plan(int dt, int64_t rows, int64_t row_len, double keep_ratio, int n_b
             p.lo_ch_off = o;    o = align256(o + 4 * R * (size_t)C);
             p.lo_L = o;         o = align256(o + 8 * R * (size_t)capL);
             p.lo_Lblk = o;      o = align256(o + R * (size_t)capL);
-            p.lo_fine_pos = o;  o = align256(o + 4 * R * kFB);
-            p.lo_fine_neg = o;  o = align256(o + 4 * R * kFB);
             p.lo_rowst = o;     o = align256(o + 4 * R * 16);
             p.lo_thr = o;       o = align256(o + 8 * R * (1 + kMaxB2));
             p.lo_blk_start = o; o = align256(o + 4 * R * (B2 + 1));
@@ -168,7 +166,7 @@ int launch_large(const LargeArgs& la, const Plan& p, hipStream_t st)
 {
     const dim3 gC((unsigned)la.C, (unsigned)la.R), gL((unsigned)la.LC, (unsigned)la.R), gR((unsigned)la.R);
     const dim3 gP((unsigned)std::max<int64_t>(1, (la.k + kPCH - 1) / kPCH), (unsigned)la.R);
-    const dim3 gW((unsigned)std::max<u64>(1, (p.cap_words + kStageWords - 1) / kStageWords), (unsigned)la.R);
+    const dim3 gW((unsigned)std::max<u64>(1, (p.cap_words + kPackWords - 1) / kPackWords), (unsigned)la.R);
     hipLaunchKernelGGL((lr_hist_kernel<DT>), gC, dim3(256), 0, st, la);
     hipLaunchKernelGGL((lr_select_kernel<DT>), gR, dim3(1024), 0, st, la);
     hipLaunchKernelGGL((lr_compact_kernel<DT>), gC, dim3(256), 0, st, la);
@@ -308,7 +306,6 @@ int slicer_encode(const void* x, slicer_dtype dt, int64_t rows, int64_t row_len,
         la.C = p.large_C; la.LC = p.large_LC; la.capL = p.large_capL;
         la.ch_cum = (u32*)(ws + p.lo_ch_cum);     la.ch_off = (u32*)(ws + p.lo_ch_off);
         la.L = (u64*)(ws + p.lo_L);               la.Lblk = (uint8_t*)(ws + p.lo_Lblk);
-        la.fine_pos = (u32*)(ws + p.lo_fine_pos); la.fine_neg = (u32*)(ws + p.lo_fine_neg);
         la.rowst = (u32*)(ws + p.lo_rowst);       la.thr = (u64*)(ws + p.lo_thr);
         la.blk_start = (u32*)(ws + p.lo_blk_start); la.blkcnt = (u32*)(ws + p.lo_blkcnt);
         la.vminb = (u32*)(ws + p.lo_vminb);       la.vmaxb = (u32*)(ws + p.lo_vmaxb);

@@ -6,8 +6,8 @@
 //             as "elements at or above the bin" (so sums over chunks are cumulative too)
 //   select    per row: the bin B1 that holds overall rank k-1, the list offsets of the chunks
 //   compact   per chunk: ordered compaction of everything at or above B1 into the row's
-//             list L (ascending index) + a 16384-bin fine histogram per sign class
-//   bounds    per row: ranks of the fine bins; the comp of overall rank k-1 (ATKF cut,
+//             list L (ascending index)
+//   bounds    per row: 8192-bin fine histogram of the list in LDS, ranks of the bins; the comp of overall rank k-1 (ATKF cut,
 //             Sec. 3.1) and of class ranks j*K-1 (block boundaries, Sec. 3.2), each resolved
 //             inside its bin by pairwise comparison of the bin's members
 //   blockcount / scatter   per 2048 list entries: block id, per-block counts, block min/max;
@@ -27,11 +27,11 @@ namespace slicer {
 
 constexpr int kLCH = 8192;          // elements per hist / compact workgroup
 constexpr int kLBins = 2048;        // coarse bins: top 11 bits of the key
-constexpr int kFB = 16384;          // fine bins per sign class
+constexpr int kFB = 8192;           // fine bins of the list (kept in LDS by the bounds stage)
 constexpr int kLCE = 2048;          // list entries per blockcount / scatter workgroup
 constexpr int kPCH = 4096;          // block-ordered positions per abq workgroup
-constexpr int kCutCap = 4096;       // members of the top-K cut bin (= kMaxB2 * kTgtCap: the two lists share storage)
-constexpr int kTgtCap = 32;         // members of one boundary bin (per class)
+constexpr int kCutCap = 2048;       // members of the top-K cut bin
+constexpr int kPackWords = 1024;    // stream words per pack workgroup
 constexpr u64 kTop = 1ull << 63;
 
 struct LargeArgs {
@@ -47,8 +47,6 @@ struct LargeArgs {
     u32* ch_off;            // [R][C]
     u64* L;                 // [R][capL]       class << 63 | key << 32 | index
     uint8_t* Lblk;          // [R][capL]       block of the entry, 255 = not kept
-    u32* fine_pos;          // [R][kFB]        counts, then first class rank of the bin
-    u32* fine_neg;
     u32* rowst;             // [R][16]  0 t_lo 1 sh 2 nL 3 n_pos 4 n_neg 5 K0 6 K1 7 ntg 8 nt0
     u64* thr;               // [R][1 + kMaxB2] thr[0] = cut comp, then boundaries (class on top)
     u32* blk_start;         // [R][B2 + 1]
@@ -80,18 +78,36 @@ __global__ __launch_bounds__(256) void lr_hist_kernel(LargeArgs a)
     const int B2 = 2 * a.M;
     for (int i = tid; i < kLBins; i += 256) h[i] = 0;
     // this launch also clears what later stages accumulate into
-    for (int i = c * 256 + tid; i < kFB; i += a.C * 256) {
-        a.fine_pos[(size_t)r * kFB + i] = 0;
-        a.fine_neg[(size_t)r * kFB + i] = 0;
-    }
     if (c == 0) {
         for (int b = tid; b < B2; b += 256) { a.vminb[r * B2 + b] = 0xFFFFFFFFu; a.vmaxb[r * B2 + b] = 0; }
         for (int i = tid; i < B2 * (a.nq + 1); i += 256) a.sums[(size_t)r * B2 * (a.nq + 1) + i] = 0;
     }
     __syncthreads();
-    const raw_t* __restrict__ xr = (const raw_t*)a.x + (size_t)r * (size_t)a.N;
-    const int64_t i0 = (int64_t)c * kLCH, i1 = i0 + kLCH < a.N ? i0 + kLCH : a.N;
-    for (int64_t i = i0 + tid; i < i1; i += 256) atomicAdd(&h[E::key(xr[i]) >> KS], 1u);
+    // 16-byte loads (the row length is a multiple of a 16-byte chunk); exact zeros are not
+    // counted: they are never sent, and skipping them keeps the hot bin of post-ReLU
+    // features out of the LDS atomics (a row whose cut falls among them is redone generically)
+    constexpr int EPC = DT == 0 ? 4 : 8;
+    const int64_t i0 = (int64_t)c * kLCH;
+    const uint4* __restrict__ x4 = (const uint4*)((const char*)a.x + ((size_t)r * (size_t)a.N + (size_t)i0) * sizeof(raw_t));
+#pragma unroll
+    for (int j = 0; j < kLCH / (256 * EPC); ++j) {
+        const int q = j * 256 + tid;
+        if (i0 + (int64_t)q * EPC < a.N) {
+            const uint4 v = x4[q];
+            const u32 wd[4] = { v.x, v.y, v.z, v.w };
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                if (DT == 0) {
+                    const u32 key = wd[d] & 0x7FFFFFFFu;
+                    if (key) atomicAdd(&h[key >> KS], 1u);
+                } else {
+                    const u32 k0 = wd[d] & 0x7FFFu, k1 = (wd[d] >> 16) & 0x7FFFu;
+                    if (k0) atomicAdd(&h[k0 >> KS], 1u);
+                    if (k1) atomicAdd(&h[k1 >> KS], 1u);
+                }
+            }
+        }
+    }
     __syncthreads();
     // "at or above": running sum from the top bin down; thread t owns the 8 bins below 2048 - 8t
     const int hi = kLBins - tid * 8;
@@ -131,7 +147,7 @@ __global__ __launch_bounds__(1024) void lr_select_kernel(LargeArgs a)
     const u32 nL = rc[B1];
     const u32 t_lo = B1 << KS;
     const u32 range = (((top + 1u) << KS) - 1u) - t_lo;
-    const int sh = range < (u32)kFB ? 0 : (32 - __clz((int)range)) - 14;
+    const int sh = range < (u32)kFB ? 0 : (32 - __clz((int)range)) - 13;   // 13 = log2(kFB)
     // bin 0 holds the exact zeros, which are never sent: such rows go to the generic kernel
     const bool bad = a.k > 0 && (B1 == 0 || nL > a.capL);
     const bool live = a.k > 0 && !bad;
@@ -160,7 +176,6 @@ __global__ __launch_bounds__(256) void lr_compact_kernel(LargeArgs a)
     if (a.fallback[r]) return;
     const u32* st = a.rowst + (size_t)r * 16;
     const u32 t_lo = st[0], nL = st[2];
-    const int sh = (int)st[1];
     if (nL == 0) return;
     const int64_t seg0 = (int64_t)c * kLCH + (int64_t)wid * (kLCH / 4);
     const uint4* __restrict__ xr4 = (const uint4*)((const char*)a.x + ((size_t)r * (size_t)a.N + (size_t)seg0) * (DT == 0 ? 4 : 2));
@@ -206,8 +221,6 @@ __global__ __launch_bounds__(256) void lr_compact_kernel(LargeArgs a)
     u32 wbase = a.ch_off[(size_t)r * a.C + c];
     for (int v2 = 0; v2 < wid; ++v2) wbase += wtot[v2];
     u64* __restrict__ L = a.L + (size_t)r * a.capL;
-    u32* __restrict__ fp = a.fine_pos + (size_t)r * kFB;
-    u32* __restrict__ fn = a.fine_neg + (size_t)r * kFB;
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
         u32 pos = wbase + basej[j];
@@ -219,7 +232,6 @@ __global__ __launch_bounds__(256) void lr_compact_kernel(LargeArgs a)
             if (key >= t_lo) {
                 const u32 neg = E::neg((typename E::raw_t)raw);
                 if (pos < a.capL) L[pos] = ((u64)neg << 63) | ((u64)key << 32) | (u64)(idx0 + e);
-                atomicAdd(neg ? &fn[(key - t_lo) >> sh] : &fp[(key - t_lo) >> sh], 1u);
                 ++pos;
             }
         }
@@ -231,14 +243,35 @@ __device__ inline u64 lr_comp(u64 e, int w)       // key << w | inverted index
     return (((e >> 32) & 0x7FFFFFFFull) << w) | (((1ull << w) - 1ull) - (e & 0xFFFFFFFFull));
 }
 
+// fine bin of a list entry: linear in the key from the list's lower bound
+__device__ inline u32 lr_fine(u64 e, u32 t_lo, int sh) { return (((u32)(e >> 32) & 0x7FFFFFFFu) - t_lo) >> sh; }
+
+// Visit every entry of the row's list with eight independent loads in flight per thread.
+template <typename F>
+__device__ inline void lr_for_each(const u64* __restrict__ L, u32 nL, F f)
+{
+    for (u32 p0 = 0; p0 < nL; p0 += 8 * 1024) {
+        u64 e8[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) { const u32 p = p0 + u * 1024 + threadIdx.x; e8[u] = p < nL ? L[p] : 0ull; }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (p0 + u * 1024 + threadIdx.x < nL) f(e8[u]);
+    }
+}
+
 __global__ __launch_bounds__(1024) void lr_bounds_kernel(LargeArgs a)
 {
-    __shared__ u64 mem[kCutCap];                 // cut-bin members, later kMaxB2 x kTgtCap boundary members
+    // fine histogram of the list in LDS: kFB bins, positive count | negative count << 16
+    __shared__ u32 fh[kFB];                      // later: members of the boundary bins
+    __shared__ u64 cutmem[kCutCap];              // members of the cut bin
+    __shared__ u32 tpre_p[1024], tpre_n[1024];   // first class rank of each thread's group of bins
     __shared__ u32 bitmap[kFB / 32];
     __shared__ u32 scr[1024 / kWave + 1];
     __shared__ u32 tgbin[kMaxB2], tgrem[kMaxB2], tcnt[kMaxB2];
     __shared__ u32 s_cut[3], s_n[4];
     __shared__ u64 s_thrK;
+    constexpr int BPT = kFB / 1024;              // bins per thread
     const int tid = threadIdx.x;
     const int64_t r = blockIdx.x;
     if (a.fallback[r]) return;
@@ -247,29 +280,36 @@ __global__ __launch_bounds__(1024) void lr_bounds_kernel(LargeArgs a)
     const u32 t_lo = st[0], nL = st[2];
     const int sh = (int)st[1];
     const u64* __restrict__ L = a.L + (size_t)r * a.capL;
-    u32* __restrict__ fp = a.fine_pos + (size_t)r * kFB;
-    u32* __restrict__ fn = a.fine_neg + (size_t)r * kFB;
     const u32 k = (u32)a.k;
 
+    for (int i = tid; i < kFB; i += 1024) fh[i] = 0;
     for (int i = tid; i < kFB / 32; i += 1024) bitmap[i] = 0;
     if (tid < kMaxB2) tcnt[tid] = 0;
     if (tid == 0) { s_cut[0] = 0xFFFFFFFFu; s_n[0] = 0; s_n[1] = 0; s_n[2] = 0; s_n[3] = 0; s_thrK = 0; }
+    __syncthreads();
+    lr_for_each(L, nL, [&](u64 e) { atomicAdd(&fh[lr_fine(e, t_lo, sh)], (e >> 63) ? 0x10000u : 1u); });
+    __syncthreads();
 
-    // (a) first rank of every fine bin, per class, counted from the top; the cut bin
-    const int hi = kFB - tid * 16;
-    u32 cp[16], cn[16];
+    // (a) class ranks from the top: thread t owns the BPT bins below kFB - BPT * t
+    const int hi = kFB - tid * BPT;
+    u32 cp[BPT], cn[BPT];
     u32 lp = 0, ln = 0;
 #pragma unroll
-    for (int j = 0; j < 16; ++j) { cp[j] = fp[hi - 1 - j]; cn[j] = fn[hi - 1 - j]; lp += cp[j]; ln += cn[j]; }
+    for (int j = 0; j < BPT; ++j) { const u32 c = fh[hi - 1 - j]; cp[j] = c & 0xFFFFu; cn[j] = c >> 16; lp += cp[j]; ln += cn[j]; }
     u32 tp, tn;
-    u32 ap = block_excl_scan<1024>(lp, scr, &tp);
-    u32 an = block_excl_scan<1024>(ln, scr, &tn);
+    const u32 ep = block_excl_scan<1024>(lp, scr, &tp);
+    const u32 en = block_excl_scan<1024>(ln, scr, &tn);
+    tpre_p[tid] = ep; tpre_n[tid] = en;
+    // a 16-bit count that wrapped shows up as a wrong total: such rows are redone generically
+    if (tp + tn != nL) { if (tid == 0) a.fallback[r] = 1u; return; }
+    {
+        u32 ap = ep, an = en;
 #pragma unroll
-    for (int j = 0; j < 16; ++j) {
-        fp[hi - 1 - j] = ap; fn[hi - 1 - j] = an;
-        const u32 cnt = cp[j] + cn[j];
-        if (nL > k && cnt && ap + an <= k - 1 && k - 1 < ap + an + cnt) { s_cut[0] = (u32)(hi - 1 - j); s_cut[1] = ap; s_cut[2] = an; }
-        ap += cp[j]; an += cn[j];
+        for (int j = 0; j < BPT; ++j) {
+            const u32 cnt = cp[j] + cn[j];
+            if (nL > k && cnt && ap + an <= k - 1 && k - 1 < ap + an + cnt) { s_cut[0] = (u32)(hi - 1 - j); s_cut[1] = ap; s_cut[2] = an; }
+            ap += cp[j]; an += cn[j];
+        }
     }
     __syncthreads();
 
@@ -278,75 +318,83 @@ __global__ __launch_bounds__(1024) void lr_bounds_kernel(LargeArgs a)
     u64 thrK = 0;
     if (nL > k) {
         const u32 cut = s_cut[0];
-        for (u32 p = tid; p < nL; p += 1024) {
-            const u64 e = L[p];
-            if ((((u32)(e >> 32) & 0x7FFFFFFFu) - t_lo) >> sh == cut) {
+        lr_for_each(L, nL, [&](u64 e) {
+            if (lr_fine(e, t_lo, sh) == cut) {
                 const u32 slot = atomicAdd(&s_n[0], 1u);
-                if (slot < (u32)kCutCap) mem[slot] = (e & kTop) | lr_comp(e, w);
+                if (slot < (u32)kCutCap) cutmem[slot] = (e & kTop) | lr_comp(e, w);
             }
-        }
+        });
         __syncthreads();
         const u32 nm = s_n[0];
         if (nm > (u32)kCutCap) { if (tid == 0) a.fallback[r] = 1u; return; }
         const u32 rem = (k - 1) - (s_cut[1] + s_cut[2]);
         for (u32 i = tid; i < nm; i += 1024) {
-            const u64 me = mem[i] & ~kTop;
+            const u64 me = cutmem[i] & ~kTop;
             u32 gt = 0;
-            for (u32 j = 0; j < nm; ++j) gt += (mem[j] & ~kTop) > me ? 1u : 0u;
+            for (u32 j = 0; j < nm; ++j) gt += (cutmem[j] & ~kTop) > me ? 1u : 0u;
             if (gt == rem) s_thrK = me;
-            if (gt <= rem) atomicAdd((mem[i] & kTop) ? &s_n[2] : &s_n[1], 1u);
+            if (gt <= rem) atomicAdd((cutmem[i] & kTop) ? &s_n[2] : &s_n[1], 1u);
         }
         __syncthreads();
         thrK = s_thrK;
         n_pos = s_cut[1] + s_n[1];
         n_neg = s_cut[2] + s_n[2];
     }
-    __syncthreads();
 
-    // (c) block boundaries: class ranks j*K-1, one thread per boundary
+    // (c) block boundaries: class ranks j*K-1, one thread per boundary: first the group of
+    //     bins (binary search over the threads' first ranks), then the bin inside the group
     const u32 Kc0 = n_pos / (u32)M, Kc1 = n_neg / (u32)M;
     const int nt0 = Kc0 ? M - 1 : 0, nt1 = Kc1 ? M - 1 : 0, ntg = nt0 + nt1;
     if (tid < ntg) {
         const int cls = tid >= nt0 ? 1 : 0;
         const int j = (cls ? tid - nt0 : tid) + 1;
         const u32 Rk = (u32)j * (cls ? Kc1 : Kc0) - 1u;
-        const u32* pre = cls ? fn : fp;
-        int lo = 0, hi2 = kFB - 1;                   // smallest bin whose first class rank is <= Rk
+        const u32* tpre = cls ? tpre_n : tpre_p;
+        int lo = 0, hi2 = 1023;                      // last group whose first rank is <= Rk
         while (lo < hi2) {
-            const int mid = (lo + hi2) >> 1;
-            if (pre[mid] <= Rk) hi2 = mid; else lo = mid + 1;
+            const int mid = (lo + hi2 + 1) >> 1;
+            if (tpre[mid] <= Rk) lo = mid; else hi2 = mid - 1;
         }
-        tgbin[tid] = (u32)lo;
-        tgrem[tid] = Rk - pre[lo];
-        atomicOr(&bitmap[lo >> 5], 1u << (lo & 31));
+        u32 acc = tpre[lo];
+        const int top = kFB - lo * BPT;
+        u32 bin = (u32)(top - 1);
+        for (int jj = 0; jj < BPT; ++jj) {           // the bin of the group that holds rank Rk
+            const u32 c = fh[top - 1 - jj];
+            const u32 cc = cls ? c >> 16 : c & 0xFFFFu;
+            if (Rk < acc + cc) { bin = (u32)(top - 1 - jj); break; }
+            acc += cc;
+        }
+        tgbin[tid] = bin;
+        tgrem[tid] = Rk - acc;
+        atomicOr(&bitmap[bin >> 5], 1u << (bin & 31));
     }
-    __syncthreads();
-    u64* tmem = mem;                                 // [ntg][kTgtCap]
-    for (u32 p = tid; p < nL; p += 1024) {
-        const u64 e = L[p];
-        const u32 d = (((u32)(e >> 32) & 0x7FFFFFFFu) - t_lo) >> sh;
+    __syncthreads();                                 // the histogram is dead from here on
+    u64* tmem = (u64*)fh;                            // [ntg][tcap]
+    const u32 tcap = ntg ? (u32)(kFB / 2) / (u32)ntg : 1u;
+    lr_for_each(L, nL, [&](u64 e) {
+        const u32 d = lr_fine(e, t_lo, sh);
         if ((bitmap[d >> 5] >> (d & 31)) & 1u) {
             const int cls = (int)(e >> 63);
             const int t0 = cls ? nt0 : 0, t1 = cls ? ntg : nt0;
             for (int t = t0; t < t1; ++t) {
                 if (tgbin[t] == d) {
                     const u32 slot = atomicAdd(&tcnt[t], 1u);
-                    if (slot < (u32)kTgtCap) tmem[t * kTgtCap + slot] = lr_comp(e, w);
+                    if (slot < tcap) tmem[(u32)t * tcap + slot] = lr_comp(e, w);
                 }
             }
         }
-    }
+    });
     __syncthreads();
     int over = 0;
-    if (tid < ntg && tcnt[tid] > (u32)kTgtCap) over = 1;
+    if (tid < ntg && tcnt[tid] > tcap) over = 1;
     if (__syncthreads_or(over)) { if (tid == 0) a.fallback[r] = 1u; return; }
     u64* __restrict__ thr = a.thr + (size_t)r * (1 + kMaxB2);
-    for (int t = tid / kTgtCap; t < ntg; t += 1024 / kTgtCap) {
-        const u32 i = (u32)tid % kTgtCap, cnt = tcnt[t];
-        if (i < cnt) {
-            const u64 me = tmem[t * kTgtCap + i];
+    for (int t = 0; t < ntg; ++t) {                  // the member with exactly `rem` class-mates above it
+        const u32 cnt = tcnt[t];
+        for (u32 i = tid; i < cnt; i += 1024) {
+            const u64 me = tmem[(u32)t * tcap + i];
             u32 gt = 0;
-            for (u32 j = 0; j < cnt; ++j) gt += tmem[t * kTgtCap + j] > me ? 1u : 0u;
+            for (u32 j = 0; j < cnt; ++j) gt += tmem[(u32)t * tcap + j] > me ? 1u : 0u;
             if (gt == tgrem[t]) thr[1 + t] = me | (t >= nt0 ? 0ull : kTop);
         }
     }
@@ -357,7 +405,7 @@ __global__ __launch_bounds__(1024) void lr_bounds_kernel(LargeArgs a)
     for (int b = tid; b <= B2; b += 1024) {          // K, ..., K, K + remainder per class
         u32 v;
         if (b == B2) v = n_pos + n_neg;
-        else { const int s = b >= M ? 1 : 0, m = b - s * M; v = (s ? n_pos : 0u) + (u32)m * (s ? Kc1 : Kc0); }
+        else { const int s2 = b >= M ? 1 : 0, m = b - s2 * M; v = (s2 ? n_pos : 0u) + (u32)m * (s2 ? Kc1 : Kc0); }
         a.blk_start[(size_t)r * (B2 + 1) + b] = v;
     }
 }
@@ -611,7 +659,7 @@ template <int DT>
 __global__ __launch_bounds__(256) void lr_pack_kernel(LargeArgs a)
 {
     typedef Elem<DT> E;
-    __shared__ u32 sA[kStageWords];
+    __shared__ u32 sA[kPackWords];
     __shared__ u32 bs[kMaxB2 + 1], qsel[kMaxB2];
     __shared__ u64 coff[kMaxB2 + 1];
     __shared__ float vminf[kMaxB2], invs[kMaxB2];
@@ -621,7 +669,7 @@ __global__ __launch_bounds__(256) void lr_pack_kernel(LargeArgs a)
     if (a.fallback[r]) return;
     const int B2 = 2 * a.M, w = a.w;
     const u64 row_words = a.row_words[r];
-    const u64 c0 = (u64)blockIdx.x * kStageWords;
+    const u64 c0 = (u64)blockIdx.x * kPackWords;
     if (c0 >= row_words) return;
     const u32* st = a.rowst + (size_t)r * 16;
     const u32 n = st[3] + st[4];
@@ -634,26 +682,22 @@ __global__ __launch_bounds__(256) void lr_pack_kernel(LargeArgs a)
             vminf[b] = __uint_as_float(E::value_bits(a.vminb[r * B2 + b]));
         }
     }
-    const u64 cw = row_words - c0 < (u64)kStageWords ? row_words - c0 : (u64)kStageWords;
+    const u64 cw = row_words - c0 < (u64)kPackWords ? row_words - c0 : (u64)kPackWords;
     const u64 lo = c0 << 5, hi = (c0 + cw) << 5;
     const u64 idx_bits = (u64)n * (u64)w;
     for (int i = tid; i < (int)cw; i += 256) sA[i] = 0;
     __syncthreads();
-    if (tid == 0) {     // entries whose code field meets [lo, hi)
-        u32 plo = n, phi = 0;
-        for (int b = 0; b < B2; ++b) {
-            const u32 cnt = bs[b + 1] - bs[b];
-            if (!cnt) continue;
-            const u64 cs = idx_bits + coff[b], ce = idx_bits + coff[b + 1];
-            if (ce <= lo || cs >= hi) continue;
-            const u64 q = (u64)qsel[b];
-            const u64 jlo = ((lo > cs ? lo : cs) - cs) / q;
-            const u64 jhi = ((hi < ce ? hi : ce) - cs + q - 1) / q;
-            const u32 a0 = bs[b] + (u32)jlo, a1 = bs[b] + (u32)jhi;
-            plo = a0 < plo ? a0 : plo;
-            phi = a1 > phi ? a1 : phi;
-        }
-        s_range[0] = plo; s_range[1] = phi;
+    if (tid == 0) { s_range[0] = n; s_range[1] = 0; }
+    __syncthreads();
+    for (int b = tid; b < B2; b += 256) {     // entries whose code field meets [lo, hi), one thread per block
+        const u32 cnt = bs[b + 1] - bs[b];
+        if (!cnt) continue;
+        const u64 cs = idx_bits + coff[b], ce = idx_bits + coff[b + 1];
+        if (ce <= lo || cs >= hi) continue;
+        const u32 q = qsel[b];
+        const u32 dlo = (u32)((lo > cs ? lo : cs) - cs), dhi = (u32)((hi < ce ? hi : ce) - cs);   // < 2^31: one block's bits
+        atomicMin(&s_range[0], bs[b] + dlo / q);
+        atomicMax(&s_range[1], bs[b] + (dhi + q - 1) / q);
     }
     __syncthreads();
     const u32* __restrict__ bo_idx = a.bo_idx + (size_t)r * (size_t)a.k;
