@@ -335,7 +335,7 @@ int slicer_encode(const void* x, slicer_dtype dt, int64_t rows, int64_t row_len,
     fa.chunk_tot = (u64*)(ws + p.off_chunk_tot);
     fa.slots = ea.slots;
     fa.cap_words = p.cap_words;
-    fa.chunks_per_row = (int)std::max<u64>(1, (p.cap_words + 4095) / 4096);
+    fa.chunks_per_row = (int)std::max<u64>(1, (p.cap_words + kGatherWords - 1) / kGatherWords);
     fa.stream = (u32*)stream;
     fa.meta = meta;
     fa.mv = ea.mv;

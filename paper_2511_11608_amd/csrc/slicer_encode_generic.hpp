@@ -529,6 +529,7 @@ __global__ __launch_bounds__(BLOCK) void enc_generic_kernel(EncArgs a)
 // and copies each row's slot to its place in the contiguous stream.
 
 constexpr int kScanRows = 1024;
+constexpr int kGatherWords = 1024;   // slot words one wavefront copies
 
 struct FinishArgs {
     int64_t R, N, k;
@@ -539,7 +540,7 @@ struct FinishArgs {
     u64* chunk_tot;         // [ceil(R / kScanRows)]
     const u32* slots;
     u64 cap_words;
-    int chunks_per_row;     // gather workgroups per row (4096 words each)
+    int chunks_per_row;     // gather wavefronts per row (kGatherWords words each)
     u32* stream;
     void* meta;
     MetaView mv;
@@ -573,7 +574,7 @@ __global__ __launch_bounds__(kScanRows) void enc_rowscan_kernel(FinishArgs a)
 
 __global__ __launch_bounds__(256) void enc_gather_kernel(FinishArgs a)
 {
-    // one wavefront per (row, 4096-word chunk of its slot); no workgroup barrier
+    // one wavefront per (row, kGatherWords-word chunk of its slot); no workgroup barrier
     const u32 lane = lane_id();
     const int64_t item = (int64_t)blockIdx.x * (256 / kWave) + threadIdx.x / kWave;
     const int64_t r = item / a.chunks_per_row;
@@ -605,9 +606,9 @@ __global__ __launch_bounds__(256) void enc_gather_kernel(FinishArgs a)
         for (size_t o = kHeaderBytes + 16 * (size_t)a.R + 18 * (size_t)a.R * a.M; o < meta_bytes(a.R, a.M); ++o) m8[o] = 0;
     }
     const u64 nw = a.row_words[r];
-    const u64 j0 = c * 4096ull;
+    const u64 j0 = c * (u64)kGatherWords;
     if (j0 >= nw) return;
-    const u64 j1 = j0 + 4096ull < nw ? j0 + 4096ull : nw;
+    const u64 j1 = j0 + (u64)kGatherWords < nw ? j0 + (u64)kGatherWords : nw;
     const u32* __restrict__ src = a.slots + (size_t)r * a.cap_words;
     u32* __restrict__ dst = a.stream + off;
     for (u64 j = j0 + lane; j < j1; j += kWave) dst[j] = src[j];
