@@ -8,8 +8,8 @@ of the five); input buffers rotate over > 256 MB of distinct device memory so th
 the Infinity Cache does not stand in for HBM.
 
 Prints ONE JSON line: whole-step throughput in GB/s of input IF, the roofline
-record of the dominant kernel (the per-row encode kernel; its duration is read with
-HIP events recorded around that kernel on its stream), and the CPU oracle timed on
+record of the dominant kernel (the encode kernel that does the selection, quantisation
+and packing of a row; its duration is read with HIP events recorded around it on its stream), and the CPU oracle timed on
 a bounded sample of the same workload.
 """
 from __future__ import annotations
@@ -106,6 +106,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", type=int, default=4, help="1..5 (default 4: LLM prefill, the headline config)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run plain device copies of the input tensor (known size), the yardstick that "
+                         "scales the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this codec build runs on ONE GPU (rows are independent; sharding is by rows, "
@@ -187,17 +190,25 @@ def main() -> int:
     out_bytes = 4 * words + meta_bytes
     bpe = 8.0 * out_bytes / n_el
 
-    enc_kernel = "enc_generic_kernel"
+    path = binding.slicer_encode_path(binding.SLICER_F32 if wl.dtype == "f32" else binding.SLICER_BF16,
+                                      wl.rows, wl.row_len, keep, M, bits)
+    enc_kernel = {0: "enc_generic_kernel", 1: "enc_small_kernel", 2: "lr_* stages (hist..pack)"}[path]
+    dec_kernel = "dec_small_kernel" if wl.row_len * (4 if wl.dtype == "f32" else 2) <= 16384 else "dec_kernel"
     enc_alg_bytes = in_bytes + out_bytes                 # read x once, write stream + meta
     dec_alg_bytes = out_bytes + in_bytes                 # read stream + meta, write y once
     achieved = enc_alg_bytes / (enc_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": enc_kernel, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": achieved / HBM_PEAK_GBS, "traffic": load_traffic(wl.name, enc_kernel),
                 "algorithmic_bytes_per_launch": enc_alg_bytes, "kernel_ms": enc_ms,
-                "decode_kernel": {"kernel": "dec_kernel", "kernel_ms": dec_ms,
+                "decode_kernel": {"kernel": dec_kernel, "kernel_ms": dec_ms,
                                   "achieved": dec_alg_bytes / (dec_ms * 1e-3) / 1e9,
                                   "frac": dec_alg_bytes / (dec_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                                  "traffic": load_traffic(wl.name, "dec_kernel")}}
+                                  "traffic": load_traffic(wl.name, dec_kernel)}}
+
+    if args.copy_probe:
+        for i in range(4):
+            ys[i % n_out].copy_(xd[i % n_buf])          # reads in_bytes, writes in_bytes
+        torch.cuda.synchronize()
 
     threads = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)))
     cpu = None if args.no_cpu else cpu_baseline(wl, threads)

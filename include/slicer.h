@@ -109,6 +109,15 @@ int slicer_decode(const void* stream, const void* meta, void* y, void* hip_strea
 int slicer_decode_as(const void* stream, const void* meta, void* y, slicer_dtype dt,
                      int64_t rows, int64_t row_len, int n_blocks, void* hip_stream);
 
+/*
+ * Which kernel family slicer_encode uses for a shape (for benchmarks and profiles, which
+ * name the dominant kernel): 0 = generic (one workgroup per row, any shape), 1 = row-resident
+ * (one wavefront per row, rows up to 8192 bf16 / 2048 fp32 elements), 2 = long-row stages
+ * (rows of 32768 elements and more).  Assumes a 16-byte aligned x.  Negative: error code.
+ */
+int slicer_encode_path(slicer_dtype dt, int64_t rows, int64_t row_len, double keep_ratio,
+                       int n_blocks, uint32_t bit_set);
+
 /* Reads meta.total_words (the packed size of Sec. 3.3's payload, in 32-bit words)
  * to the host.  Waits for `hip_stream`. */
 int slicer_stream_words(const void* meta, uint64_t* words, void* hip_stream);

@@ -40,6 +40,8 @@ def load() -> C.CDLL:
         szp = C.POINTER(C.c_size_t)
         L.slicer_sizes.restype = cint
         L.slicer_sizes.argtypes = [cint, i64, i64, dbl, cint, u32, szp, szp, szp]
+        L.slicer_encode_path.restype = cint
+        L.slicer_encode_path.argtypes = [cint, i64, i64, dbl, cint, u32]
         L.slicer_encode.restype = cint
         L.slicer_encode.argtypes = [vp, cint, i64, i64, dbl, cint, u32, dbl, vp, vp, vp, vp]
         L.slicer_decode.restype = cint
@@ -80,6 +82,14 @@ def slicer_sizes(dt: int, rows: int, row_len: int, keep_ratio: float, n_blocks: 
     _check("slicer_sizes", load().slicer_sizes(dt, rows, row_len, keep_ratio, n_blocks, bit_set,
                                                C.byref(a), C.byref(b), C.byref(c)))
     return a.value, b.value, c.value
+
+
+def slicer_encode_path(dt: int, rows: int, row_len: int, keep_ratio: float, n_blocks: int, bit_set: int) -> int:
+    """0 generic, 1 row-resident, 2 long-row kernel family for this shape."""
+    rc = load().slicer_encode_path(dt, rows, row_len, keep_ratio, n_blocks, bit_set)
+    if rc < 0:
+        raise SlicerError("slicer_encode_path", rc)
+    return rc
 
 
 def alloc_buffers(x: torch.Tensor, keep_ratio: float, n_blocks: int, bit_set: int):

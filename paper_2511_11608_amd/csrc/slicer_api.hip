@@ -244,6 +244,15 @@ int slicer_sizes(slicer_dtype dt, int64_t rows, int64_t row_len, double keep_rat
     return SLICER_OK;
 }
 
+int slicer_encode_path(slicer_dtype dt, int64_t rows, int64_t row_len, double keep_ratio, int n_blocks,
+                       uint32_t bit_set)
+{
+    int rc = check_args((int)dt, rows, row_len, keep_ratio, n_blocks, bit_set);
+    if (rc) return rc;
+    Plan p = make_plan((int)dt, rows, row_len, keep_ratio, n_blocks, bit_set);
+    return p.small_epl ? 1 : (p.large_C ? 2 : 0);
+}
+
 int slicer_encode(const void* x, slicer_dtype dt, int64_t rows, int64_t row_len, double keep_ratio,
                   int n_blocks, uint32_t bit_set, double distortion_budget, void* stream, void* meta,
                   void* workspace, void* hip_stream)

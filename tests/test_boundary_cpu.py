@@ -27,7 +27,7 @@ def declared_symbols():
 def test_exports_every_declared_symbol(lib):
     names = declared_symbols()
     assert {"slicer_sizes", "slicer_encode", "slicer_decode", "slicer_decode_as", "slicer_stream_words",
-            "slicer_profile_events", "slicer_last_hip_error", "slicer_strerror"} <= set(names)
+            "slicer_encode_path", "slicer_profile_events", "slicer_last_hip_error", "slicer_strerror"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
@@ -60,3 +60,14 @@ def test_argument_errors_and_strings(lib):
     # null pointers are rejected before anything is launched
     assert lib.slicer_encode(None, 0, 1, 8, 0.5, 1, 0b100, 1e-3, None, None, None, None) == -1
     assert lib.slicer_decode_as(None, None, None, 0, 1, 8, 1, None) == -1
+
+
+def test_encode_path_by_shape(lib):
+    from paper_2511_11608_amd import binding, synth
+    B = synth.BITS_2_TO_8
+    assert binding.slicer_encode_path(binding.SLICER_BF16, 16384, 4096, 0.10, 8, B) == 1     # LLM prefill
+    assert binding.slicer_encode_path(binding.SLICER_BF16, 256, 8192, 0.10, 8, B) == 1       # AR decode step
+    assert binding.slicer_encode_path(binding.SLICER_F32, 12608, 768, 0.15, 8, B) == 1       # ViT tokens
+    assert binding.slicer_encode_path(binding.SLICER_F32, 32, 401408, 0.20, 16, B) == 2      # ResNet stage 3
+    assert binding.slicer_encode_path(binding.SLICER_F32, 1, 200704, 0.10, 4, B) == 2        # CNN map
+    assert binding.slicer_encode_path(binding.SLICER_F32, 3, 4097, 0.5, 3, B) == 0           # odd length
