@@ -126,7 +126,7 @@ Plan make_plan(int dt, int64_t rows, int64_t row_len, double keep_ratio, int n_b
     int nq = 0;
     for (int q = 1; q <= 16; ++q) nq += (bit_set >> q) & 1u;
     if (row_len % epc == 0 && row_len <= max_n && 2 * n_blocks <= kWave) {
-        const int64_t margin = std::max<int64_t>(64, row_len / (dt == SLICER_F32 ? 8 : 16));   // room for the undecided coarse bin
+        const int64_t margin = std::max<int64_t>(64, row_len / (dt == SLICER_F32 ? 16 : 32));  // room for the undecided coarse bin
         int64_t cap = std::min<int64_t>(1984, (p.k + margin + 63) / 64 * 64);   // ranks are 11-bit fields
         int epl = epc;
         while ((int64_t)epl * kWave < row_len) epl *= 2;

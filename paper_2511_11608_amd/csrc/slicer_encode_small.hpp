@@ -1,19 +1,25 @@
 // Row-resident encoder for short rows: ONE WAVEFRONT PER ROW, the row held in
 // registers, every list in LDS, no workgroup barrier anywhere.
 //
-//   1. load the row (16-byte coalesced loads); 10-bit histogram of the magnitude
-//      key's top bits in LDS; scan from the top -> the bin B1 that holds rank k-1;
+// All ordering is done on one integer per element, the "comp": magnitude key in the high
+// bits, inverted index in the low bits (larger comp = larger magnitude, then lower index:
+// the tie rule of the top-K filter and of the block ranks), and the sign class as the top
+// bit, positive class on top.  Comps are distinct, so a comp is a complete rank threshold.
+//
+//   1. load the row (16-byte coalesced loads); 11-bit histogram of the magnitude key's
+//      top bits in LDS; two-level scan from the top -> the bin B1 that holds rank k-1;
 //   2. ordered compaction of everything at or above B1 into a short list L
 //      (ascending index: the kept set plus the undecided bin);
 //   3. L is bucketed into 1024 fine bins, linear in the key from the list's lower
 //      bound, both sign classes counted in one packed table; an exclusive scan from
 //      the top gives every bin's first rank, overall and per class.  Order
 //      statistics (rank k-1 overall for the top-K cut of Sec. 3.1; ranks j*K-1 per
-//      class for the block boundaries of Sec. 3.2) are located by binary search over
-//      the bins, one lane per boundary, and resolved inside their bin by comparing
-//      the bin's few members pairwise on "key, then lower index";
-//   4. an entry's block is the number of boundaries above it; a stable split by block
-//      id (wave ballots) restores ascending index inside each block;
+//      class for the block boundaries of Sec. 3.2) are located over the bins, one lane
+//      per boundary, and resolved inside their bin by comparing the bin's few members
+//      pairwise;
+//   4. an entry's block is the number of boundaries above it (plus one for the negative
+//      class); a stable split by block id (wave ballots) restores ascending index inside
+//      each block;
 //   5. ABQ sums on integer grids, bitwidth choice, bit offsets, packing through an
 //      LDS image of the row's stream segment.
 //
@@ -39,13 +45,17 @@ struct SmallArgs {
     u32* fallback;      // [R] 1 = redo this row with the generic kernel
     MetaView mv;
     int cap;            // list capacity, multiple of 64, < 2048
-    int region0_words;  // histogram region, later block-ordered arrays + stream image
+    int region0_words;  // fine histogram, later block-ordered indices + stream image
 };
 
+constexpr int kCoarseBits = 11;
+constexpr int kCoarseBins = 1 << kCoarseBits;
 constexpr int kFineBins = 1024;
 
-// Optional per-phase cycle accounting (development builds only, -DSLICER_PHASE_TIMING):
-// lane 0 of every wave adds the cycles since the previous mark to a global table.
+// Development builds only.  -DSLICER_PHASE_TIMING: lane 0 of every wave adds the cycles since
+// the previous mark to a global table.  -DSLICER_STOP_AFTER=i: leave the kernel after mark i
+// with an empty row (instruction and time accounting of the phases up to that mark; the
+// output is NOT a valid stream).
 #ifdef SLICER_PHASE_TIMING
 __device__ unsigned long long g_phase_cycles[16];
 #define SLICER_PT(i)                                                              \
@@ -54,34 +64,57 @@ __device__ unsigned long long g_phase_cycles[16];
         if (lane == 0) atomicAdd(&g_phase_cycles[i], (unsigned long long)(t_now_ - t_prev_)); \
         t_prev_ = clock64();                                                      \
     } while (0)
+#elif defined(SLICER_STOP_AFTER)
+#define SLICER_PT(i)                                                              \
+    do {                                                                          \
+        if ((i) == SLICER_STOP_AFTER) {                                           \
+            if (lane == 0) { a.row_words[r] = 0; a.mv.n_pos[r] = 0; a.mv.n_neg[r] = 0; a.fallback[r] = 0u; } \
+            return;                                                               \
+        }                                                                         \
+    } while (0)
 #else
 #define SLICER_PT(i) do { } while (0)
 #endif
 
-// LDS carve-up of one wave (word offsets); small_lds_words() on the host must match
+// LDS carve-up of one wave (word offsets); small_lds_words() on the host must match.
+// The coarse histogram (2048 words) overlays everything: nothing else is live before the
+// compaction.  The ABQ sums overlay the list (dead once the block-ordered arrays exist);
+// the quantiser table overlays the boundary work table.
 struct SmallLds {
-    u32* hist;      // [region0]   coarse / fine histogram; later bo_val, bo_idx, stream image
-    u32* Lent;      // [cap]       list entries, ascending index: bf16 raw << 16 | idx; fp32 raw
-    u32* S;         // [cap]       entries arranged by fine bin: in-bin comp << 1 | class
+    u32* hist;      // [region0]   fine histogram; later bo_idx, stream image
+    u32* Lent;      // [lent]      list entries, ascending index: bf16 raw << 16 | ~idx; fp32 raw
+    u64* sums;      //             (same storage) [B2][nq + 1]
+    u32* S;         // [cap]       entries arranged by fine bin; later bo_val
     uint16_t* Lidx; // [cap]       fp32 only: index of the entry
-    u64* thr;       // [B2]        block boundaries (full comps with the class on top; 32-bit for bf16), positive class first
-    u32* tg;        // [5][64]     boundary work table: bin, base, count, rank in bin, pair prefix
+    u32* thr;       // [2 * B2]    block boundaries (class-extended comps), positive class first
+    u32* tg;        // [5][ntg]    boundary work table: bin, base, count, rank in bin, pair prefix
+    float* invt;    //             (same storage) [B2][nq] quantiser scales
+    u32* qtab;      // [16]        allowed bitwidths
     u32* blk_start; // [B2 + 1]
     u32* vminb;     // [B2] key of the block's smallest / largest element
     u32* vmaxb;     // [B2]
-    u32* run;       // [B2]
-    u64* sums;      // [B2][nq + 1]
+    u32* run;       // [B2]        next free position of the block; later the chosen bitwidth index
 };
 
-// (the boundary work table and the ABQ sums are never live together: they share storage;
-//  bf16 entries carry their index, so only fp32 rows get the separate index list)
+__host__ __device__ inline int small_lent_words(int cap, int B2, int nq)
+{
+    const int sums = 2 * B2 * (nq + 1);
+    return ((cap > sums ? cap : sums) + 1) & ~1;
+}
+
+__host__ __device__ inline int small_tg_words(int B2, int nq)
+{
+    const int ntg = B2 > 2 ? B2 - 2 : 1;
+    const int tg = 5 * ntg, iv = B2 * nq;
+    return ((tg > iv ? tg : iv) + 1) & ~1;
+}
+
 __host__ __device__ inline int small_lds_words(int dt, int cap, int region0, int B2, int nq)
 {
-    int wds = region0 + cap + cap + (dt == 0 ? cap / 2 : 0);
-    wds += 2 * B2;                       // thr (u64)
-    const int sums = 2 * B2 * (nq + 1), tg = 5 * 64;
-    wds += sums > tg ? sums : tg;
+    int wds = region0 + small_lent_words(cap, B2, nq) + cap + (dt == 0 ? cap / 2 : 0);
+    wds += 2 * B2 + small_tg_words(B2, nq) + 16;
     wds += (B2 + 1) + B2 * 3;
+    if (wds < kCoarseBins) wds = kCoarseBins;
     return wds;
 }
 
@@ -90,16 +123,14 @@ __device__ inline SmallLds small_carve(u32* base, int dt, int cap, int region0, 
     SmallLds L;
     u32* p = base;
     L.hist = p;            p += region0;           // region0 is even
-    L.Lent = p;            p += cap;
+    L.Lent = p;
+    L.sums = (u64*)p;      p += small_lent_words(cap, B2, nq);
     L.S = p;               p += cap;
     L.Lidx = (uint16_t*)p; p += dt == 0 ? cap / 2 : 0;
-    L.thr = (u64*)p;       p += 2 * B2;            // cap is a multiple of 64: still 8-byte aligned
-    L.sums = (u64*)p;
+    L.thr = p;             p += 2 * B2;            // cap is a multiple of 64: still 8-byte aligned
     L.tg = p;
-    {
-        const int sums = 2 * B2 * (nq + 1), tg = 5 * 64;
-        p += sums > tg ? sums : tg;
-    }
+    L.invt = (float*)p;    p += small_tg_words(B2, nq);
+    L.qtab = p;            p += 16;
     L.blk_start = p;       p += B2 + 1;
     L.vminb = p;           p += B2;
     L.vmaxb = p;           p += B2;
@@ -113,14 +144,14 @@ template <int DT, int EPL, int NQ>
 __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
 {
     typedef Elem<DT> E;
-    typedef typename E::raw_t raw_t;
     typedef typename std::conditional<DT == 0, u64, u32>::type comp_t;   // bf16: key + index fit 31 bits
     constexpr comp_t kClsBit = (comp_t)1 << (8 * sizeof(comp_t) - 1);       // set for the positive class
+    constexpr int kHiShift = DT == 0 ? 32 : 0;                               // position of the key word in a comp
     constexpr int kRegThr = 14;                                              // boundaries held in registers
     constexpr int QN = NQ ? NQ : kMaxQ;
     constexpr int EPC = DT == 0 ? 4 : 8;            // elements per 16-byte chunk
     constexpr int NCH = EPL / EPC;                  // chunks per lane
-    constexpr int KS = E::kKeyBits - 10;            // coarse digit = key >> KS
+    constexpr int KS = E::kKeyBits - kCoarseBits;   // coarse digit = key >> KS
     extern __shared__ u32 smem[];
 
     const u32 lane = lane_id();
@@ -133,9 +164,20 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
     const u32 idxmask = (1u << w) - 1u;
     SmallLds L = small_carve(smem, DT, cap, a.region0_words, B2, nq);
 
-    // entry accessors: raw bits (sign + key) and index of list entry p
-    auto ent_raw = [&](u32 p) -> u32 { const u32 e = L.Lent[p]; return DT == 0 ? e : e >> 16; };
-    auto ent_idx = [&](u32 p) -> u32 { return DT == 0 ? (u32)L.Lidx[p] : (L.Lent[p] & 0xFFFFu); };
+    // ---- list entry accessors ---------------------------------------------------------------
+    // bf16: one word holds sign, key and inverted index, i.e. the comp with the class bit flipped
+    auto ent_cx = [&](u32 p) -> comp_t {          // class-extended comp of entry p
+        if (DT == 0) return ((comp_t)(L.Lent[p] ^ 0x80000000u) << kHiShift) | (comp_t)(u32)(~(u32)L.Lidx[p]);
+        return (comp_t)(L.Lent[p] ^ 0x80000000u);
+    };
+    auto cx_key = [&](comp_t cx) -> u32 {         // magnitude key
+        if (DT == 0) return (u32)((u64)cx >> kHiShift) & 0x7FFFFFFFu;
+        return ((u32)cx >> 16) & 0x7FFFu;
+    };
+    auto cx_idx = [&](comp_t cx) -> u32 {
+        if (DT == 0) return ~(u32)cx;
+        return 0xFFFFu - ((u32)cx & 0xFFFFu);
+    };
 
     // ---- 1. load the row, coarse histogram ------------------------------------------
     const uint4* __restrict__ xr = (const uint4*)((const char*)a.x + (size_t)r * (size_t)N * (DT == 0 ? 4 : 2));
@@ -148,9 +190,9 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
     auto word_of = [&](int c, int d) -> u32 { return d == 0 ? v[c].x : d == 1 ? v[c].y : d == 2 ? v[c].z : v[c].w; };
 
     {
-        uint4* h4 = (uint4*)L.hist;
+        uint4* h4 = (uint4*)smem;
 #pragma unroll
-        for (int i = 0; i < kFineBins / 4 / kWave; ++i) h4[i * kWave + lane] = make_uint4(0, 0, 0, 0);
+        for (int i = 0; i < kCoarseBins / 4 / kWave; ++i) h4[i * kWave + lane] = make_uint4(0, 0, 0, 0);
     }
     wave_sync();
 #pragma unroll
@@ -160,48 +202,47 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
             for (int d = 0; d < 4; ++d) {
                 const u32 wd = word_of(c, d);
                 if (DT == 0) {
-                    atomicAdd(&L.hist[(wd & 0x7FFFFFFFu) >> KS], 1u);
+                    atomicAdd(&smem[(wd & 0x7FFFFFFFu) >> KS], 1u);
                 } else {
-                    atomicAdd(&L.hist[(wd >> KS) & 0x3FFu], 1u);
-                    atomicAdd(&L.hist[(wd >> (16 + KS)) & 0x3FFu], 1u);
+                    atomicAdd(&smem[(wd >> KS) & (u32)(kCoarseBins - 1)], 1u);
+                    atomicAdd(&smem[(wd >> (16 + KS)) & (u32)(kCoarseBins - 1)], 1u);
                 }
             }
         }
     }
     wave_sync();
 
-    // scan from the top: the bin of rank k-1 and the count above it
-    u32 B1 = 0, c_gt = 0, cnt1 = 0;
+    // Scan from the top in two levels: every lane sums 32 bins; the lane that holds rank
+    // k-1 and the topmost non-empty lane are then opened bin by bin, 32 lanes each.
+    u32 B1 = 0, c_gt = 0, cnt1 = 0, topbin = 0;
     {
-        const int hi = kFineBins - (int)lane * 16;
-        u32 cs[16];
-        const uint4* h4 = (const uint4*)(L.hist + hi - 16);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const uint4 t = h4[3 - j];
-            cs[4 * j + 0] = t.w; cs[4 * j + 1] = t.z; cs[4 * j + 2] = t.y; cs[4 * j + 3] = t.x;
-        }
+        constexpr int BPL = kCoarseBins / kWave;       // 32
+        const uint4* h4 = (const uint4*)(smem + kCoarseBins - ((int)lane + 1) * BPL);
         u32 local = 0;
 #pragma unroll
-        for (int j = 0; j < 16; ++j) local += cs[j];          // cs[j] = hist[hi - 1 - j]
+        for (int j = 0; j < BPL / 4; ++j) {
+            const uint4 t = h4[j];
+            local += (t.x + t.y) + (t.z + t.w);
+        }
         const u32 incl = wave_scan_dpp(local), excl = incl - local;
         const u32 rem = k > 0 ? (u32)(k - 1) : 0u;
-        // bins of this lane (from its top) that end at or before rank rem, and their total
-        u32 acc = excl, nb = 0, ab = excl;
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            acc += cs[j];
-            const bool below = acc <= rem;
-            nb += below ? 1u : 0u;
-            ab = below ? acc : ab;
+        const u64 m_src = __ballot(local > 0 && excl <= rem && rem < incl);
+        const u64 m_top = __ballot(local > 0);
+        const int src = m_src ? (int)__builtin_ctzll(m_src) : 0;
+        const int top = m_top ? (int)__builtin_ctzll(m_top) : 0;
+        const u32 ex_src = bcast(excl, src);
+        const int grp = lane < 32u ? src : top;
+        const u32 c2 = smem[kCoarseBins - grp * BPL - 1 - (int)(lane & 31u)];
+        const u32 inc2 = wave_scan_dpp(c2);            // lanes 0..31: running count inside lane `src`
+        const u64 m_b1 = __ballot(lane < 32u && ex_src + inc2 > rem);
+        const u64 m_tb = __ballot(lane >= 32u && c2 > 0u);
+        if (m_src && m_b1) {
+            const int j1 = (int)__builtin_ctzll(m_b1);
+            B1 = (u32)(kCoarseBins - src * BPL - 1 - j1);
+            cnt1 = bcast(c2, j1);
+            c_gt = ex_src + bcast(inc2, j1) - cnt1;
         }
-        const u64 mm = __ballot(local > 0 && excl <= rem && rem < incl);
-        if (mm) {
-            const int src = (int)__builtin_ctzll(mm);
-            B1 = (u32)(kFineBins - src * 16 - 1) - bcast(nb, src);
-            c_gt = bcast(ab, src);
-            cnt1 = L.hist[B1];
-        }
+        if (m_tb) topbin = (u32)(kCoarseBins - top * BPL - 1 - ((int)__builtin_ctzll(m_tb) - 32));
     }
     wave_sync();
 
@@ -251,6 +292,7 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
         for (int c = 0; c < NCH; ++c) {
             u32 pos = basec[c];
             const u32 idx0 = (u32)((c * kWave + (int)lane) * EPC);
+            const u32 inv0 = 0xFFFFu - idx0;
 #pragma unroll
             for (int d = 0; d < 4; ++d) {
                 const u32 wd = word_of(c, d);
@@ -258,8 +300,8 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
                     if ((wd & 0x7FFFFFFFu) >= t_lo) { L.Lent[pos] = wd; L.Lidx[pos] = (uint16_t)(idx0 + d); ++pos; }
                 } else {
                     const u32 f = ((wd & 0x7FFF7FFFu) + C16) & 0x80008000u;
-                    if (f & 0x8000u) { L.Lent[pos] = (wd << 16) | (idx0 + 2 * d); ++pos; }
-                    if (f & 0x80000000u) { L.Lent[pos] = (wd & 0xFFFF0000u) | (idx0 + 2 * d + 1); ++pos; }
+                    if (f & 0x8000u) { L.Lent[pos] = (wd << 16) | (inv0 - 2 * d); ++pos; }
+                    if (f & 0x80000000u) { L.Lent[pos] = (wd & 0xFFFF0000u) | (inv0 - 2 * d - 1); ++pos; }
                 }
             }
         }
@@ -269,35 +311,37 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
 #pragma unroll
         for (int i = 0; i < kFineBins / 4 / kWave; ++i) h4[i * kWave + lane] = make_uint4(0, 0, 0, 0);
     }
+    if (lane == 0) {
+#pragma unroll
+        for (int t = 0; t < QN; ++t)
+            if (NQ || t < nq) L.qtab[t] = (u32)a.qlist[t];
+    }
     wave_sync();
 
     SLICER_PT(1);
     // ---- 3. fine bins ---------------------------------------------------------------------
-    // 1024 bins, linear in (key - t_lo) >> sh with sh from the largest key of the list; a full
-    // comp (fine bin, in-bin key bits, index) and an S entry (in-bin bits, index, class) must
-    // fit their words
+    // 1024 bins, linear in (key - t_lo) >> sh; sh from the top of the highest occupied coarse
+    // bin.  fp32 keeps the in-bin key bits, the inverted index and the class in one word of S.
     const int nslots = (int)((nL + kWave - 1) / kWave);
-    u32 kmax = t_lo;
-    for (int s = 0; s < nslots; ++s) {
-        const u32 p = s * kWave + lane;
-        if (p < nL) kmax = max(kmax, E::key((raw_t)ent_raw(p)));
-    }
-    kmax = wave_max_dpp(kmax);
-    const u32 range = kmax - t_lo;
+    const u32 kmax_ub = ((topbin + 1u) << KS) - 1u;
+    const u32 range = kmax_ub - t_lo;
     const int sh = range < (u32)kFineBins ? 0 : (32 - __clz((int)range)) - 10;
-    if (sh + w > 31 || (DT != 0 && 10 + sh + w > 31)) {
+    if (DT == 0 && sh + w + 1 > 32) {
         if (lane == 0) a.fallback[r] = 1u;
         return;
     }
+    const u32 inmask = (1u << sh) - 1u;
     for (int s = 0; s < nslots; ++s) {
         const u32 p = s * kWave + lane;
         if (p < nL) {
-            const u32 raw = ent_raw(p);
-            atomicAdd(&L.hist[(E::key((raw_t)raw) - t_lo) >> sh], E::neg((raw_t)raw) ? 0x10000u : 1u);
+            const u32 e = L.Lent[p];
+            const u32 key = DT == 0 ? (e & 0x7FFFFFFFu) : ((e >> 16) & 0x7FFFu);
+            atomicAdd(&L.hist[(key - t_lo) >> sh], (e >> 31) ? 0x10000u : 1u);
         }
     }
     wave_sync();
     u32 n_pos, n_neg;
+    int cut_lane = 0;
     {   // exclusive prefix from the top, per class; repack as pos | neg << 11 | fill << 22
         const int hi = kFineBins - (int)lane * 16;
         u32 cs[16];
@@ -317,7 +361,12 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
         const u32 incl = wave_scan_dpp(local);
         const u32 tot = bcast(incl, kWave - 1);
         n_pos = tot & 0xFFFFu; n_neg = tot >> 16;       // class sizes of L (of the kept set once cut)
-        u32 acc = incl - local;
+        const u32 excl = incl - local;
+        // the lane whose bins hold overall rank k-1 (meaningful when nL > k)
+        const u32 ov_ex = (excl & 0xFFFFu) + (excl >> 16), ov_in = (incl & 0xFFFFu) + (incl >> 16);
+        const u64 mc = __ballot(k > 0 && ov_ex <= (u32)(k - 1) && (u32)(k - 1) < ov_in);
+        cut_lane = mc ? (int)__builtin_ctzll(mc) : 0;
+        u32 acc = excl;
         u32 o[16];
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
@@ -328,63 +377,81 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
         for (int j = 0; j < 4; ++j) h4[3 - j] = make_uint4(o[4 * j + 3], o[4 * j + 2], o[4 * j + 1], o[4 * j + 0]);
     }
     wave_sync();
-    const u32 inmask = (1u << sh) - 1u;
     for (int s = 0; s < nslots; ++s) {
         const u32 p = s * kWave + lane;
         if (p < nL) {
-            const u32 raw = ent_raw(p);
-            const u32 rel = E::key((raw_t)raw) - t_lo;
+            const u32 e = L.Lent[p];
+            const u32 key = DT == 0 ? (e & 0x7FFFFFFFu) : ((e >> 16) & 0x7FFFu);
+            const u32 rel = key - t_lo;
             const u32 old = atomicAdd(&L.hist[rel >> sh], 1u << 22);
             const u32 at = (old & 0x7FFu) + ((old >> 11) & 0x7FFu) + (old >> 22);
-            L.S[at] = ((((rel & inmask) << w) | (idxmask - ent_idx(p))) << 1) | E::neg((raw_t)raw);
+            if (DT == 0) L.S[at] = ((((rel & inmask) << w) | (idxmask - (u32)L.Lidx[p])) << 1) | (e >> 31);
+            else L.S[at] = e;
         }
     }
     wave_sync();
+    // members of a fine bin compare on the plain comp; their class
+    auto s_plain = [&](u32 s) -> u32 { return DT == 0 ? s >> 1 : s & 0x7FFFFFFFu; };
+    auto s_neg = [&](u32 s) -> u32 { return DT == 0 ? s & 1u : s >> 31; };
+    // class-extended comp of a member of fine bin `bin`
+    auto s_cx = [&](u32 s, u32 bin) -> comp_t {
+        if (DT == 0) {
+            const u32 key = ((bin << sh) | ((s >> 1) >> w)) + t_lo;
+            const u32 idx = idxmask - ((s >> 1) & idxmask);
+            return ((comp_t)(key | ((s & 1u) ? 0u : 0x80000000u)) << kHiShift) | (comp_t)(u32)(~idx);
+        }
+        return (comp_t)(s ^ 0x80000000u);
+    };
 
     SLICER_PT(2);
     // ---- top-K cut: the comp of overall rank k-1 (ATKF) -----------------------------------------
-    // full comp of an entry: fine bin, in-bin key bits, inverted index
-    const int cshift = sh + w;
-    comp_t thrK = 0;                                // every entry of L is kept when nL <= k
+    comp_t thrK = 0;                                // plain comp; every entry of L is kept when nL <= k
     if (nL > (u32)k) {
-        int lo = 0, hi = kFineBins - 1;             // smallest bin whose first overall rank is <= k-1
-        while (lo < hi) {
-            const int mid = (lo + hi) >> 1;
-            const u32 wd = L.hist[mid];
-            if ((wd & 0x7FFu) + ((wd >> 11) & 0x7FFu) <= (u32)(k - 1)) hi = mid; else lo = mid + 1;
-        }
+        // open the 16 bins of the lane found by the scan: the last one whose first rank is <= k-1
+        const int hi = kFineBins - cut_lane * 16;
+        const u32 wj = lane < 16u ? L.hist[hi - 1 - (int)lane] : 0xFFFFFFFFu;
+        const u64 mj = __ballot(lane < 16u && (wj & 0x7FFu) + ((wj >> 11) & 0x7FFu) <= (u32)(k - 1));
+        const int lo = hi - (int)__popcll(mj);
         const u32 wd = L.hist[lo];
         const u32 pe = wd & 0x7FFu, ne = (wd >> 11) & 0x7FFu, cnt = wd >> 22, base = pe + ne;
         const u32 rem = (u32)(k - 1) - base;
-        u32 kp = 0, kn = 0, tin = 0;
+        u32 kp = 0, kn = 0;
         for (u32 g = 0; g < cnt; g += kWave) {       // members in groups of 64, one per lane
             const u32 i = g + lane;
             u32 me = 0, gt = 0;
             if (i < cnt) {
                 me = L.S[base + i];
-                for (u32 j = 0; j < cnt; ++j) gt += (L.S[base + j] >> 1) > (me >> 1) ? 1u : 0u;
+                for (u32 j = 0; j < cnt; ++j) gt += s_plain(L.S[base + j]) > s_plain(me) ? 1u : 0u;
             }
             const bool in = i < cnt && gt <= rem;
-            kp += (u32)__popcll(__ballot(in && !(me & 1u)));
-            kn += (u32)__popcll(__ballot(in && (me & 1u)));
+            kp += (u32)__popcll(__ballot(in && !s_neg(me)));
+            kn += (u32)__popcll(__ballot(in && s_neg(me)));
             const u64 hit = __ballot(i < cnt && gt == rem);
-            if (hit) tin = bcast(me >> 1, (int)__builtin_ctzll(hit));
+            if (hit) {
+                const int hl = (int)__builtin_ctzll(hit);
+                const comp_t cx = s_cx(me, (u32)lo) & ~kClsBit;
+                if (DT == 0) thrK = ((comp_t)bcast((u32)((u64)cx >> kHiShift), hl) << kHiShift) | (comp_t)bcast((u32)cx, hl);
+                else thrK = (comp_t)bcast((u32)cx, hl);
+            }
         }
-        thrK = ((comp_t)lo << cshift) | (comp_t)tin;
         n_pos = pe + kp; n_neg = ne + kn;
     }
     const u32 n = n_pos + n_neg;
-    const u32 n_cls[2] = { n_pos, n_neg };
     const u32 Kc[2] = { n_pos / (u32)M, n_neg / (u32)M };
 
     SLICER_PT(3);
     // ---- block boundaries: comps of class ranks j*K-1, one lane per boundary ------------------------
-    const int nt0 = Kc[0] ? M - 1 : 0, nt1 = Kc[1] ? M - 1 : 0, ntg = nt0 + nt1;
-    u32* tg_bin = L.tg; u32* tg_base = L.tg + 64; u32* tg_cnt = L.tg + 128; u32* tg_rem = L.tg + 192; u32* tg_pre = L.tg + 256;
+    // M-1 boundaries per class, positive class first.  A class with fewer than M members has
+    // K = 0 and every member in its last block: its boundaries sit above every comp of the class.
+    const int ntg = B2 - 2;
+    comp_t* thr = (comp_t*)L.thr;
     {
-        const bool act = (int)lane < ntg;
-        const int cls = (int)lane >= nt0 ? 1 : 0;
-        const int j = (cls ? (int)lane - nt0 : (int)lane) + 1;
+        const int ntp = ntg > 0 ? ntg : 1;
+        u32* tg_bin = L.tg; u32* tg_base = L.tg + ntp; u32* tg_cnt = L.tg + 2 * ntp; u32* tg_rem = L.tg + 3 * ntp; u32* tg_pre = L.tg + 4 * ntp;
+        const bool mine = (int)lane < ntg;
+        const int cls = (int)lane >= M - 1 ? 1 : 0;
+        const int j = (cls ? (int)lane - (M - 1) : (int)lane) + 1;
+        const bool act = mine && Kc[cls] > 0;
         const u32 R = act ? (u32)j * Kc[cls] - 1u : 0u;
         int lo = 0, hi = kFineBins - 1;             // smallest bin whose first class rank is <= R
         for (int it = 0; it < 10; ++it) {
@@ -397,9 +464,12 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
         const u32 pe = wd & 0x7FFu, ne = (wd >> 11) & 0x7FFu;
         const u32 cnt = act ? wd >> 22 : 0u;
         const u32 incl = wave_scan_dpp(cnt);
-        tg_bin[lane] = (u32)lo; tg_base[lane] = pe + ne; tg_cnt[lane] = cnt;
-        tg_rem[lane] = R - (cls ? ne : pe);
-        tg_pre[lane] = incl - cnt;
+        if (mine) {
+            tg_bin[lane] = (u32)lo; tg_base[lane] = pe + ne; tg_cnt[lane] = cnt;
+            tg_rem[lane] = R - (cls ? ne : pe);
+            tg_pre[lane] = incl - cnt;
+            if (!act) thr[lane] = cls ? (comp_t)(kClsBit - 1) : ~(comp_t)0;
+        }
         const u32 npairs = bcast(incl, kWave - 1);
         wave_sync();
         // one lane per (boundary, member of its bin): the member of the boundary's class
@@ -413,18 +483,16 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
                     if (tg_pre[mid] <= pr) tl = mid; else th = mid - 1;
                 }
                 const int t = tl;
-                const u32 tc = (u32)(t >= nt0 ? 1 : 0);
+                const u32 tc = (u32)(t >= M - 1 ? 1 : 0);
                 const u32 bs = tg_base[t], cn = tg_cnt[t];
                 const u32 me = L.S[bs + (pr - tg_pre[t])];
-                if ((me & 1u) == tc) {
+                if (s_neg(me) == tc) {
                     u32 gt = 0;
                     for (u32 jj = 0; jj < cn; ++jj) {
                         const u32 o = L.S[bs + jj];
-                        gt += ((o & 1u) == tc && (o >> 1) > (me >> 1)) ? 1u : 0u;
+                        gt += (s_neg(o) == tc && s_plain(o) > s_plain(me)) ? 1u : 0u;
                     }
-                    if (gt == tg_rem[t]) {
-                        ((comp_t*)L.thr)[t] = (tc ? (comp_t)0 : kClsBit) | ((comp_t)tg_bin[t] << cshift) | (comp_t)(me >> 1);
-                    }
+                    if (gt == tg_rem[t]) thr[t] = s_cx(me, tg_bin[t]);
                 }
             }
         }
@@ -433,8 +501,9 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
     // block starts in closed form (K, ..., K, K + remainder per class)
     if ((int)lane < B2) {
         const int s = (int)lane >= M ? 1 : 0, m = (int)lane - s * M;
-        L.blk_start[lane] = (s ? n_pos : 0u) + (u32)m * Kc[s];
-        L.run[lane] = 0;
+        const u32 st = (s ? n_pos : 0u) + (u32)m * Kc[s];
+        L.blk_start[lane] = st;
+        L.run[lane] = st;
         L.vminb[lane] = 0xFFFFFFFFu; L.vmaxb[lane] = 0;
     }
     if (lane == 0) L.blk_start[B2] = n;
@@ -447,13 +516,11 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
     u32* bo_val = L.S;
     uint16_t* bo_idx = (uint16_t*)(L.hist);
     u32* stage = L.hist + (k + 1) / 2;
-    const comp_t* thr = (const comp_t*)L.thr;
     int nbits = 0;
     while ((1 << nbits) < B2) ++nbits;
-    // An entry's block = number of boundaries of its class above it.  With the class as the
-    // top bit of the comp (positive class on top) one count over ALL boundaries serves both
-    // classes: a positive entry is above every negative boundary, a negative entry below
-    // every positive one.  Up to kRegThr boundaries are held in registers.
+    // An entry's block = number of boundaries above it, plus one for the negative class: a
+    // positive entry is above every negative boundary, a negative entry below every positive
+    // one.  Up to kRegThr boundaries are held in registers.
     comp_t tx[kRegThr];
 #pragma unroll
     for (int j = 0; j < kRegThr; ++j) tx[j] = j < ntg ? thr[j] : (comp_t)0;
@@ -462,21 +529,16 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
         bool kept = false;
         u32 b = 0, key = 0, idx = 0;
         if (p < nL) {
-            const u32 raw = ent_raw(p);
-            key = E::key((raw_t)raw);
-            idx = ent_idx(p);
-            const u32 rel = key - t_lo;
-            const comp_t comp = ((comp_t)(rel >> sh) << cshift) | (comp_t)(((rel & inmask) << w) | (idxmask - idx));
-            if (comp >= thrK) {
+            const comp_t cx = ent_cx(p);
+            if ((cx & ~kClsBit) >= thrK) {
                 kept = true;
-                const u32 cls = E::neg((raw_t)raw);
-                const comp_t cx = comp | (cls ? (comp_t)0 : kClsBit);
-                u32 above = 0;
+                u32 above = (cx & kClsBit) ? 0u : 1u;
 #pragma unroll
                 for (int j = 0; j < kRegThr; ++j) above += tx[j] > cx ? 1u : 0u;
                 for (int j = kRegThr; j < ntg; ++j) above += thr[j] > cx ? 1u : 0u;
-                const u32 m = Kc[cls] ? above - (cls ? (u32)nt0 : 0u) : (u32)(M - 1);
-                b = cls * (u32)M + m;
+                b = above;
+                key = cx_key(cx);
+                idx = cx_idx(cx);
                 atomicMin(&L.vminb[b], key);
                 atomicMax(&L.vmaxb[b], key);
             }
@@ -497,7 +559,7 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
         wave_sync();
         if (kept) {
             if (before == 0) L.run[b] = basep + (u32)__popc(plo) + (u32)__popc(phi);
-            const u32 pos = L.blk_start[b] + basep + before;
+            const u32 pos = basep + before;
             bo_val[pos] = E::value_bits(key);
             bo_idx[pos] = (uint16_t)idx;
         }
@@ -511,17 +573,18 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
     const u32 lpb = (u32)kWave / (u32)B2;
     const u32 myb = udiv16(lane, lpb), sub = lane - myb * lpb;
     const bool lane_on = myb < (u32)B2;
-    u32 r0 = 0, r1 = 0, bs0 = 0;
+    u32 r0 = 0, r1 = 0, bs0 = 0, mycnt = 0;
     float vmin = 0.f, rng = 0.f;
     int e = 0, dg = 1;
     u32 vmaxbits = 0;
     if (lane_on) {
         bs0 = L.blk_start[myb];
-        const u32 be = L.blk_start[myb + 1], cnt = be - bs0;
-        const u32 perb = udiv16(cnt + lpb - 1, lpb);
+        const u32 be = L.blk_start[myb + 1];
+        mycnt = be - bs0;
+        const u32 perb = udiv16(mycnt + lpb - 1, lpb);
         r0 = bs0 + sub * perb; r0 = r0 < be ? r0 : be;
         r1 = r0 + perb < be ? r0 + perb : be;
-        if (cnt) {
+        if (mycnt) {
             const u32 lo = E::value_bits(L.vminb[myb]);
             vmaxbits = E::value_bits(L.vmaxb[myb]);
             vmin = __uint_as_float(lo);
@@ -533,16 +596,21 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
     // longest run of any lane: the largest block holds K + (n mod M) entries
     const u32 mc0 = n_pos - Kc[0] * (u32)(M - 1), mc1 = n_neg - Kc[1] * (u32)(M - 1);
     const u32 T = udiv16((mc0 > mc1 ? mc0 : mc1) + lpb - 1, lpb);
-    float Lq[QN], inv[QN];
-#pragma unroll
-    for (int t = 0; t < QN; ++t) {
-        Lq[t] = (NQ || t < nq) ? (float)((1u << a.qlist[t]) - 1u) : 1.f;
-        inv[t] = dg ? 0.f : Lq[t] / rng;
-    }
-    if (lane_on && sub == 0) {
-        for (int t = 0; t <= nq; ++t) L.sums[myb * (nq + 1) + t] = 0;
+    // quantiser scales L / rng: the lanes of a block share the divisions through LDS
+    if (lane_on) {
+        for (u32 t = sub; t < (u32)nq; t += lpb) {
+            const float Lq = (float)((1u << L.qtab[t]) - 1u);
+            L.invt[myb * (u32)nq + t] = dg ? 0.f : Lq / rng;
+        }
+        if (sub == 0) {
+            for (int t = 0; t <= nq; ++t) L.sums[myb * (nq + 1) + t] = 0;
+            L.run[myb] = (mycnt && !dg) ? (u32)nq : 0u;     // index of the chosen bitwidth; nq = none feasible yet
+        }
     }
     wave_sync();
+    float inv[QN];
+#pragma unroll
+    for (int t = 0; t < QN; ++t) inv[t] = (lane_on && (NQ || t < nq)) ? L.invt[myb * (u32)nq + t] : 0.f;
     {
         u64 accE = 0;
         for (u32 i0 = 0; i0 < T; i0 += 8) {             // u32 partial sums hold 8 residuals of 2^28
@@ -581,22 +649,25 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
     }
     wave_sync();
 
-    // smallest feasible bitwidth per block (every lane of the block evaluates it); meta
-    u32 myq = (u32)a.qlist[0], flag = 0;
-    float my_inv = 0.f;
-    const u32 mycnt = lane_on ? L.blk_start[myb + 1] - bs0 : 0u;
+    // smallest feasible bitwidth per block: the lanes of a block test different candidates in
+    // ascending order and keep the minimum
     if (lane_on && mycnt && !dg) {
         const double rhs = a.beta * ldexp((double)L.sums[myb * (nq + 1) + nq], 2 * e - 40);
-        flag = 0x80u;                                   // cleared by the first feasible bitwidth
-#pragma unroll
-        for (int t = 0; t < QN; ++t) {
-            if ((NQ || t < nq) && flag) {
-                const float o = rng / Lq[t];
-                const double lhs = ((double)o * (double)o) * (double)L.sums[myb * (nq + 1) + t] * 0x1p-30;
-                myq = (u32)a.qlist[t]; my_inv = inv[t];   // stays at the largest if none is feasible
-                if (lhs <= rhs) flag = 0;
-            }
+        for (u32 t = sub; t < (u32)nq; t += lpb) {
+            const float Lq = (float)((1u << L.qtab[t]) - 1u);
+            const float o = rng / Lq;
+            const double lhs = ((double)o * (double)o) * (double)L.sums[myb * (nq + 1) + t] * 0x1p-30;
+            if (lhs <= rhs) { atomicMin(&L.run[myb], t); break; }
         }
+    }
+    wave_sync();
+    u32 myq = 0, flag = 0;
+    float my_inv = 0.f;
+    if (lane_on) {
+        u32 tb = L.run[myb];
+        if (tb == (u32)nq) { flag = 0x80u; tb = (u32)nq - 1u; }   // none feasible: the largest bitwidth, flagged
+        myq = L.qtab[tb];
+        my_inv = L.invt[myb * (u32)nq + tb];
     }
     if (lane_on && sub == 0) {
         const size_t mi = (size_t)r * (size_t)B2 + myb;
