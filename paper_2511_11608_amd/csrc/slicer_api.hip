@@ -61,7 +61,7 @@ struct Plan {
     u64 cap_words;          // per row
     size_t off_row_words, off_slots, off_kept, off_bo_idx, off_bo_val, off_fallback, off_row_local, off_chunk_tot, total;
     // row-resident fast path (0 = not eligible)
-    int small_epl, small_cap, small_region0, small_lds_bytes;
+    int small_epl, small_cap, small_region0, small_lds_bytes, small_maxs;
     // long-row path (large_C == 0: not eligible)
     int large_C, large_LC;
     u32 large_capL;
@@ -120,7 +120,7 @@ Plan make_plan(int dt, int64_t rows, int64_t row_len, double keep_ratio, int n_b
     // The one-wave-per-row kernel holds the row in registers (64 * EPL elements) and
     // its lists in LDS; it needs whole 16-byte chunks, 16-bit indices, one lane per
     // block and a list capacity below 1024 entries.
-    p.small_epl = 0; p.small_cap = 0; p.small_region0 = 0; p.small_lds_bytes = 0;
+    p.small_epl = 0; p.small_cap = 0; p.small_region0 = 0; p.small_lds_bytes = 0; p.small_maxs = 0;
     const int epc = dt == SLICER_F32 ? 4 : 8;
     const int64_t max_n = dt == SLICER_F32 ? 2048 : 8192;
     int nq = 0;
@@ -130,22 +130,32 @@ Plan make_plan(int dt, int64_t rows, int64_t row_len, double keep_ratio, int n_b
         int64_t cap = std::min<int64_t>(1984, (p.k + margin + 63) / 64 * 64);   // ranks are 11-bit fields
         int epl = epc;
         while ((int64_t)epl * kWave < row_len) epl *= 2;
-        const int64_t region0 = (std::max<int64_t>(kFineBins, (p.k + 1) / 2 + (int64_t)p.cap_words) + 1) & ~(int64_t)1;
-        const int64_t lds = 4 * (int64_t)small_lds_words(dt, (int)cap, (int)region0, 2 * n_blocks, nq);
+        const int maxs = cap <= 640 ? 10 : cap <= 1280 ? 20 : 0;             // list held in registers
+        const int64_t region0 = small_region0_words(p.k, p.cap_words, 2 * n_blocks, nq);
+        const int64_t lds = 4 * (int64_t)small_lds_words(dt, (int)cap, (int)region0, 2 * n_blocks, maxs);
         if (p.k + 64 <= cap && lds <= 64 * 1024) {
             p.small_epl = epl; p.small_cap = (int)cap; p.small_region0 = (int)region0; p.small_lds_bytes = (int)lds;
+            p.small_maxs = maxs;
         }
     }
     return p;
 }
 
 template <int DT, int EPL>
-void launch_small_epl(const SmallArgs& sa, int lds_bytes, hipStream_t st)
+void launch_small_epl(const SmallArgs& sa, int lds_bytes, int maxs, hipStream_t st)
 {
-    if (sa.nq == 7)     // the paper's bitwidth ladders are short; 7 = {2..8} is the benchmarked one
-        hipLaunchKernelGGL((enc_small_kernel<DT, EPL, 7>), dim3((unsigned)sa.R), dim3(kWave), (size_t)lds_bytes, st, sa);
-    else
-        hipLaunchKernelGGL((enc_small_kernel<DT, EPL, 0>), dim3((unsigned)sa.R), dim3(kWave), (size_t)lds_bytes, st, sa);
+    const dim3 g((unsigned)sa.R), b(kWave);
+    const size_t lds = (size_t)lds_bytes;
+    // the paper's bitwidth ladders are short; 7 = {2..8} is the benchmarked one
+    if (sa.nq == 7) {
+        if (maxs == 10) hipLaunchKernelGGL((enc_small_kernel<DT, EPL, 7, 10>), g, b, lds, st, sa);
+        else if (maxs == 20) hipLaunchKernelGGL((enc_small_kernel<DT, EPL, 7, 20>), g, b, lds, st, sa);
+        else hipLaunchKernelGGL((enc_small_kernel<DT, EPL, 7, 0>), g, b, lds, st, sa);
+    } else {
+        if (maxs == 10) hipLaunchKernelGGL((enc_small_kernel<DT, EPL, 0, 10>), g, b, lds, st, sa);
+        else if (maxs == 20) hipLaunchKernelGGL((enc_small_kernel<DT, EPL, 0, 20>), g, b, lds, st, sa);
+        else hipLaunchKernelGGL((enc_small_kernel<DT, EPL, 0, 0>), g, b, lds, st, sa);
+    }
 }
 
 template <int DT>
@@ -153,10 +163,10 @@ int launch_small(const SmallArgs& sa, const Plan& p, hipStream_t st)
 {
     constexpr int E0 = DT == 0 ? 4 : 16;      // smallest instantiated elements-per-lane
     const int lds = p.small_lds_bytes;
-    if (p.small_epl <= E0) launch_small_epl<DT, E0>(sa, lds, st);
-    else if (p.small_epl == E0 * 2) launch_small_epl<DT, E0 * 2>(sa, lds, st);
-    else if (p.small_epl == E0 * 4) launch_small_epl<DT, E0 * 4>(sa, lds, st);
-    else launch_small_epl<DT, E0 * 8>(sa, lds, st);
+    if (p.small_epl <= E0) launch_small_epl<DT, E0>(sa, lds, p.small_maxs, st);
+    else if (p.small_epl == E0 * 2) launch_small_epl<DT, E0 * 2>(sa, lds, p.small_maxs, st);
+    else if (p.small_epl == E0 * 4) launch_small_epl<DT, E0 * 4>(sa, lds, p.small_maxs, st);
+    else launch_small_epl<DT, E0 * 8>(sa, lds, p.small_maxs, st);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? SLICER_OK : hip_fail(e);
 }

@@ -78,17 +78,17 @@ __device__ unsigned long long g_phase_cycles[16];
 
 // LDS carve-up of one wave (word offsets); small_lds_words() on the host must match.
 // The coarse histogram (2048 words) overlays everything: nothing else is live before the
-// compaction.  The ABQ sums overlay the list (dead once the block-ordered arrays exist);
-// the quantiser table overlays the boundary work table.
+// compaction.  Region 0 is the fine histogram first; once the boundaries are known it holds
+// the block-ordered indices, the stream image, the ABQ sums and the quantiser scales.
+// MAXS > 0: the list is copied into registers after the compaction, so the bin-ordered
+// list S reuses the storage of L.
 struct SmallLds {
-    u32* hist;      // [region0]   fine histogram; later bo_idx, stream image
-    u32* Lent;      // [lent]      list entries, ascending index: bf16 raw << 16 | ~idx; fp32 raw
-    u64* sums;      //             (same storage) [B2][nq + 1]
+    u32* hist;      // [region0]   fine histogram; later bo_idx, stream image, sums, invt
+    u32* Lent;      // [cap]       list entries, ascending index: bf16 raw << 16 | ~idx; fp32 raw
     u32* S;         // [cap]       entries arranged by fine bin; later bo_val
-    uint16_t* Lidx; // [cap]       fp32 only: index of the entry
+    uint16_t* Lidx; // [cap]       fp32 only: index of the entry (inside region 0 when MAXS > 0)
     u32* thr;       // [2 * B2]    block boundaries (class-extended comps), positive class first
     u32* tg;        // [5][ntg]    boundary work table: bin, base, count, rank in bin, pair prefix
-    float* invt;    //             (same storage) [B2][nq] quantiser scales
     u32* qtab;      // [16]        allowed bitwidths
     u32* blk_start; // [B2 + 1]
     u32* vminb;     // [B2] key of the block's smallest / largest element
@@ -96,40 +96,41 @@ struct SmallLds {
     u32* run;       // [B2]        next free position of the block; later the chosen bitwidth index
 };
 
-__host__ __device__ inline int small_lent_words(int cap, int B2, int nq)
-{
-    const int sums = 2 * B2 * (nq + 1);
-    return ((cap > sums ? cap : sums) + 1) & ~1;
-}
-
-__host__ __device__ inline int small_tg_words(int B2, int nq)
+__host__ __device__ inline int small_tg_words(int B2)
 {
     const int ntg = B2 > 2 ? B2 - 2 : 1;
-    const int tg = 5 * ntg, iv = B2 * nq;
-    return ((tg > iv ? tg : iv) + 1) & ~1;
+    return (5 * ntg + 1) & ~1;
 }
 
-__host__ __device__ inline int small_lds_words(int dt, int cap, int region0, int B2, int nq)
+// words of region 0: fine histogram, or indices + stream image + sums + scales
+__host__ __device__ inline int small_region0_words(int64_t k, u64 cap_words, int B2, int nq)
 {
-    int wds = region0 + small_lent_words(cap, B2, nq) + cap + (dt == 0 ? cap / 2 : 0);
-    wds += 2 * B2 + small_tg_words(B2, nq) + 16;
+    const int64_t late = (((k + 1) / 2 + (int64_t)cap_words + 1) & ~(int64_t)1) + 2 * B2 * (nq + 1) + B2 * nq;
+    const int64_t r0 = late > kFineBins ? late : kFineBins;
+    return (int)((r0 + 1) & ~(int64_t)1);
+}
+
+__host__ __device__ inline int small_lds_words(int dt, int cap, int region0, int B2, int maxs)
+{
+    int wds = region0 + cap + (maxs ? 0 : cap) + ((dt == 0 && !maxs) ? cap / 2 : 0);
+    wds += 2 * B2 + small_tg_words(B2) + 16;
     wds += (B2 + 1) + B2 * 3;
     if (wds < kCoarseBins) wds = kCoarseBins;
     return wds;
 }
 
-__device__ inline SmallLds small_carve(u32* base, int dt, int cap, int region0, int B2, int nq)
+__device__ inline SmallLds small_carve(u32* base, int dt, int cap, int region0, int B2, int maxs)
 {
     SmallLds L;
     u32* p = base;
     L.hist = p;            p += region0;           // region0 is even
-    L.Lent = p;
-    L.sums = (u64*)p;      p += small_lent_words(cap, B2, nq);
-    L.S = p;               p += cap;
-    L.Lidx = (uint16_t*)p; p += dt == 0 ? cap / 2 : 0;
+    L.Lent = p;            p += cap;
+    L.S = maxs ? L.Lent : p;
+    p += maxs ? 0 : cap;
+    L.Lidx = maxs ? (uint16_t*)base : (uint16_t*)p;
+    p += (dt == 0 && !maxs) ? cap / 2 : 0;
     L.thr = p;             p += 2 * B2;            // cap is a multiple of 64: still 8-byte aligned
-    L.tg = p;
-    L.invt = (float*)p;    p += small_tg_words(B2, nq);
+    L.tg = p;              p += small_tg_words(B2);
     L.qtab = p;            p += 16;
     L.blk_start = p;       p += B2 + 1;
     L.vminb = p;           p += B2;
@@ -138,9 +139,19 @@ __device__ inline SmallLds small_carve(u32* base, int dt, int cap, int region0, 
     return L;
 }
 
+// LDS by byte offset: dynamic shared memory starts at offset 0 when the kernel has no static
+// LDS (checked at run time), so an address computed as an integer needs no base register.
+typedef __attribute__((address_space(3))) u32 lds_u32;
+__device__ inline lds_u32* lds_at(u32 byte_off) { return (lds_u32*)(uintptr_t)byte_off; }
+__device__ inline void lds_inc(u32 byte_off, u32 v)
+{
+    __hip_atomic_fetch_add(lds_at(byte_off), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+
 // NQ > 0: the number of allowed bitwidths is known at compile time (loops over the
 // candidate bitwidths unroll without predicates); NQ == 0: any number up to 16.
-template <int DT, int EPL, int NQ>
+// MAXS > 0: the list has at most 64 * MAXS entries and lives in registers.
+template <int DT, int EPL, int NQ, int MAXS>
 __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
 {
     typedef Elem<DT> E;
@@ -162,13 +173,24 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
     const int N = (int)a.N, M = a.M, w = a.w, B2 = 2 * a.M, nq = NQ ? NQ : a.nq, cap = a.cap;
     const int k = (int)a.k;
     const u32 idxmask = (1u << w) - 1u;
-    SmallLds L = small_carve(smem, DT, cap, a.region0_words, B2, nq);
+    SmallLds L = small_carve(smem, DT, cap, a.region0_words, B2, MAXS);
+    if (__builtin_amdgcn_groupstaticsize() != 0u) {             // integer LDS addresses assume offset 0
+        if (lane == 0) a.fallback[r] = 1u;
+        return;
+    }
+    const u32 lent_off = (u32)(L.Lent - smem) * 4u;
 
     // ---- list entry accessors ---------------------------------------------------------------
     // bf16: one word holds sign, key and inverted index, i.e. the comp with the class bit flipped
-    auto ent_cx = [&](u32 p) -> comp_t {          // class-extended comp of entry p
-        if (DT == 0) return ((comp_t)(L.Lent[p] ^ 0x80000000u) << kHiShift) | (comp_t)(u32)(~(u32)L.Lidx[p]);
-        return (comp_t)(L.Lent[p] ^ 0x80000000u);
+    constexpr int SLN = MAXS ? MAXS : 32;          // slots of 64 entries (cap < 2048)
+    u32 ent[MAXS ? MAXS : 1], eix[(MAXS && DT == 0) ? MAXS : 1];
+    auto ent_word = [&](int s) -> u32 { return MAXS ? ent[MAXS ? s : 0] : L.Lent[s * kWave + (int)lane]; };
+    auto ent_index = [&](int s) -> u32 {          // fp32 only
+        return MAXS ? eix[(MAXS && DT == 0) ? s : 0] : (u32)L.Lidx[s * kWave + (int)lane];
+    };
+    auto ent_cx = [&](int s) -> comp_t {          // class-extended comp of this lane's entry of slot s
+        if (DT == 0) return ((comp_t)(ent_word(s) ^ 0x80000000u) << kHiShift) | (comp_t)(u32)(~ent_index(s));
+        return (comp_t)(ent_word(s) ^ 0x80000000u);
     };
     auto cx_key = [&](comp_t cx) -> u32 {         // magnitude key
         if (DT == 0) return (u32)((u64)cx >> kHiShift) & 0x7FFFFFFFu;
@@ -202,10 +224,10 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
             for (int d = 0; d < 4; ++d) {
                 const u32 wd = word_of(c, d);
                 if (DT == 0) {
-                    atomicAdd(&smem[(wd & 0x7FFFFFFFu) >> KS], 1u);
+                    lds_inc(((wd & 0x7FFFFFFFu) >> KS) << 2, 1u);
                 } else {
-                    atomicAdd(&smem[(wd >> KS) & (u32)(kCoarseBins - 1)], 1u);
-                    atomicAdd(&smem[(wd >> (16 + KS)) & (u32)(kCoarseBins - 1)], 1u);
+                    lds_inc((wd >> (KS - 2)) & (u32)(4 * kCoarseBins - 4), 1u);
+                    lds_inc((wd >> (16 + KS - 2)) & (u32)(4 * kCoarseBins - 4), 1u);
                 }
             }
         }
@@ -288,23 +310,44 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
                 }
             }
         }
+        // every flagged element is stored at a running byte address that advances by its flag
+        const u32 lidx_off = (u32)((u32*)L.Lidx - smem) * 4u;
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
-            u32 pos = basec[c];
+            u32 wa = lent_off + basec[c] * 4u;
             const u32 idx0 = (u32)((c * kWave + (int)lane) * EPC);
             const u32 inv0 = 0xFFFFu - idx0;
 #pragma unroll
             for (int d = 0; d < 4; ++d) {
                 const u32 wd = word_of(c, d);
                 if (DT == 0) {
-                    if ((wd & 0x7FFFFFFFu) >= t_lo) { L.Lent[pos] = wd; L.Lidx[pos] = (uint16_t)(idx0 + d); ++pos; }
+                    const u32 fl = (wd & 0x7FFFFFFFu) >= t_lo ? 1u : 0u;
+                    if (fl) {
+                        *lds_at(wa) = wd;
+                        *(__attribute__((address_space(3))) uint16_t*)(uintptr_t)(lidx_off + ((wa - lent_off) >> 1)) = (uint16_t)(idx0 + d);
+                    }
+                    wa += fl << 2;
                 } else {
-                    const u32 f = ((wd & 0x7FFF7FFFu) + C16) & 0x80008000u;
-                    if (f & 0x8000u) { L.Lent[pos] = (wd << 16) | (inv0 - 2 * d); ++pos; }
-                    if (f & 0x80000000u) { L.Lent[pos] = (wd & 0xFFFF0000u) | (inv0 - 2 * d - 1); ++pos; }
+                    const u32 f = (wd & 0x7FFF7FFFu) + C16;
+                    const u32 f0 = (f >> 15) & 1u, f1 = f >> 31;
+                    if (f0) *lds_at(wa) = (wd << 16) | (inv0 - 2 * d);
+                    wa += f0 << 2;
+                    if (f1) *lds_at(wa) = (wd & 0xFFFF0000u) | (inv0 - 2 * d - 1);
+                    wa += f1 << 2;
                 }
             }
         }
+    }
+    if (MAXS) {
+        // the list moves into registers: its LDS storage is free for the bin-ordered list
+        wave_sync();
+#pragma unroll
+        for (int s = 0; s < SLN; ++s) {
+            const u32 p = s * kWave + lane;
+            if (MAXS) ent[MAXS ? s : 0] = p < nL ? L.Lent[p] : 0u;
+            if (MAXS && DT == 0) eix[(MAXS && DT == 0) ? s : 0] = p < nL ? (u32)L.Lidx[p] : 0u;
+        }
+        wave_sync();
     }
     {
         uint4* h4 = (uint4*)L.hist;
@@ -331,12 +374,14 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
         return;
     }
     const u32 inmask = (1u << sh) - 1u;
-    for (int s = 0; s < nslots; ++s) {
+#pragma unroll(MAXS ? MAXS : 1)
+    for (int s = 0; s < SLN; ++s) {
+        if (s >= nslots) break;
         const u32 p = s * kWave + lane;
         if (p < nL) {
-            const u32 e = L.Lent[p];
+            const u32 e = ent_word(s);
             const u32 key = DT == 0 ? (e & 0x7FFFFFFFu) : ((e >> 16) & 0x7FFFu);
-            atomicAdd(&L.hist[(key - t_lo) >> sh], (e >> 31) ? 0x10000u : 1u);
+            lds_inc(((key - t_lo) >> sh) << 2, (e >> 31) ? 0x10000u : 1u);
         }
     }
     wave_sync();
@@ -377,15 +422,17 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
         for (int j = 0; j < 4; ++j) h4[3 - j] = make_uint4(o[4 * j + 3], o[4 * j + 2], o[4 * j + 1], o[4 * j + 0]);
     }
     wave_sync();
-    for (int s = 0; s < nslots; ++s) {
+#pragma unroll(MAXS ? MAXS : 1)
+    for (int s = 0; s < SLN; ++s) {
+        if (s >= nslots) break;
         const u32 p = s * kWave + lane;
         if (p < nL) {
-            const u32 e = L.Lent[p];
+            const u32 e = ent_word(s);
             const u32 key = DT == 0 ? (e & 0x7FFFFFFFu) : ((e >> 16) & 0x7FFFu);
             const u32 rel = key - t_lo;
             const u32 old = atomicAdd(&L.hist[rel >> sh], 1u << 22);
             const u32 at = (old & 0x7FFu) + ((old >> 11) & 0x7FFu) + (old >> 22);
-            if (DT == 0) L.S[at] = ((((rel & inmask) << w) | (idxmask - (u32)L.Lidx[p])) << 1) | (e >> 31);
+            if (DT == 0) L.S[at] = ((((rel & inmask) << w) | (idxmask - ent_index(s))) << 1) | (e >> 31);
             else L.S[at] = e;
         }
     }
@@ -524,12 +571,14 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
     comp_t tx[kRegThr];
 #pragma unroll
     for (int j = 0; j < kRegThr; ++j) tx[j] = j < ntg ? thr[j] : (comp_t)0;
-    for (int s = 0; s < nslots; ++s) {
+#pragma unroll(MAXS ? MAXS : 1)
+    for (int s = 0; s < SLN; ++s) {
+        if (s >= nslots) break;
         const u32 p = s * kWave + lane;
         bool kept = false;
         u32 b = 0, key = 0, idx = 0;
         if (p < nL) {
-            const comp_t cx = ent_cx(p);
+            const comp_t cx = ent_cx(s);
             if ((cx & ~kClsBit) >= thrK) {
                 kept = true;
                 u32 above = (cx & kClsBit) ? 0u : 1u;
@@ -570,6 +619,8 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
     // ---- 5. ABQ -----------------------------------------------------------------------------------
     // Each block is walked by kWave / B2 lanes, each lane a contiguous run of the block-ordered
     // list, so a lane's quantiser constants and partial sums live in registers.
+    u64* sums = (u64*)(L.hist + ((((k + 1) / 2 + (int)a.cap_words) + 1) & ~1));
+    float* invt = (float*)(sums + B2 * (nq + 1));
     const u32 lpb = (u32)kWave / (u32)B2;
     const u32 myb = udiv16(lane, lpb), sub = lane - myb * lpb;
     const bool lane_on = myb < (u32)B2;
@@ -600,17 +651,17 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
     if (lane_on) {
         for (u32 t = sub; t < (u32)nq; t += lpb) {
             const float Lq = (float)((1u << L.qtab[t]) - 1u);
-            L.invt[myb * (u32)nq + t] = dg ? 0.f : Lq / rng;
+            invt[myb * (u32)nq + t] = dg ? 0.f : Lq / rng;
         }
         if (sub == 0) {
-            for (int t = 0; t <= nq; ++t) L.sums[myb * (nq + 1) + t] = 0;
+            for (int t = 0; t <= nq; ++t) sums[myb * (nq + 1) + t] = 0;
             L.run[myb] = (mycnt && !dg) ? (u32)nq : 0u;     // index of the chosen bitwidth; nq = none feasible yet
         }
     }
     wave_sync();
     float inv[QN];
 #pragma unroll
-    for (int t = 0; t < QN; ++t) inv[t] = (lane_on && (NQ || t < nq)) ? L.invt[myb * (u32)nq + t] : 0.f;
+    for (int t = 0; t < QN; ++t) inv[t] = (lane_on && (NQ || t < nq)) ? invt[myb * (u32)nq + t] : 0.f;
     {
         u64 accE = 0;
         for (u32 i0 = 0; i0 < T; i0 += 8) {             // u32 partial sums hold 8 residuals of 2^28
@@ -643,20 +694,20 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
             }
 #pragma unroll
             for (int t = 0; t < QN; ++t)
-                if ((NQ || t < nq) && acc[t]) atomicAdd(&L.sums[myb * (nq + 1) + t], (u64)acc[t]);
+                if ((NQ || t < nq) && acc[t]) atomicAdd(&sums[myb * (nq + 1) + t], (u64)acc[t]);
         }
-        if (accE) atomicAdd(&L.sums[myb * (nq + 1) + nq], accE);
+        if (accE) atomicAdd(&sums[myb * (nq + 1) + nq], accE);
     }
     wave_sync();
 
     // smallest feasible bitwidth per block: the lanes of a block test different candidates in
     // ascending order and keep the minimum
     if (lane_on && mycnt && !dg) {
-        const double rhs = a.beta * ldexp((double)L.sums[myb * (nq + 1) + nq], 2 * e - 40);
+        const double rhs = a.beta * ldexp((double)sums[myb * (nq + 1) + nq], 2 * e - 40);
         for (u32 t = sub; t < (u32)nq; t += lpb) {
             const float Lq = (float)((1u << L.qtab[t]) - 1u);
             const float o = rng / Lq;
-            const double lhs = ((double)o * (double)o) * (double)L.sums[myb * (nq + 1) + t] * 0x1p-30;
+            const double lhs = ((double)o * (double)o) * (double)sums[myb * (nq + 1) + t] * 0x1p-30;
             if (lhs <= rhs) { atomicMin(&L.run[myb], t); break; }
         }
     }
@@ -667,7 +718,7 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
         u32 tb = L.run[myb];
         if (tb == (u32)nq) { flag = 0x80u; tb = (u32)nq - 1u; }   // none feasible: the largest bitwidth, flagged
         myq = L.qtab[tb];
-        my_inv = L.invt[myb * (u32)nq + tb];
+        my_inv = invt[myb * (u32)nq + tb];
     }
     if (lane_on && sub == 0) {
         const size_t mi = (size_t)r * (size_t)B2 + myb;
