@@ -194,13 +194,13 @@ __device__ inline u32 wave_max_dpp(u32 v)
     return bcast(r, kWave - 1);
 }
 
-// x / d for x < 2^16 and 1 <= d < 2^16 (float estimate with a +-1 repair)
+// x / d for x < 2^16 and 1 <= d < 2^16.  (x + 0.5) / d lies at least 0.5 / d away from every
+// integer, far more than the error of the reciprocal and the product (a few 2^-24 of the
+// quotient, and quotient * d < 2^16), so the truncation needs no repair.
 __device__ inline u32 udiv16(u32 x, u32 d)
 {
-    u32 q = (u32)((float)x * (1.0f / (float)d));
-    if (q * d > x) --q;
-    if ((q + 1) * d <= x) ++q;
-    return q;
+    const float rd = __builtin_amdgcn_rcpf((float)d);
+    return (u32)(((float)x + 0.5f) * rd);
 }
 
 // ---- bit fields in a word stream (LSB first) -------------------------------------

@@ -312,11 +312,14 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
         }
         // every flagged element is stored at a running byte address that advances by its flag
         const u32 lidx_off = (u32)((u32*)L.Lidx - smem) * 4u;
+        // (the empty asm statements pin values in registers: the optimiser would otherwise
+        //  re-derive each flag and each inverted index with longer instruction sequences)
+        u32 linv = 0xFFFFu - lane * (u32)EPC;
+        asm volatile("" : "+v"(linv));
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
             u32 wa = lent_off + basec[c] * 4u;
             const u32 idx0 = (u32)((c * kWave + (int)lane) * EPC);
-            const u32 inv0 = 0xFFFFu - idx0;
 #pragma unroll
             for (int d = 0; d < 4; ++d) {
                 const u32 wd = word_of(c, d);
@@ -329,11 +332,16 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
                     wa += fl << 2;
                 } else {
                     const u32 f = (wd & 0x7FFF7FFFu) + C16;
-                    const u32 f0 = (f >> 15) & 1u, f1 = f >> 31;
-                    if (f0) *lds_at(wa) = (wd << 16) | (inv0 - 2 * d);
+                    u32 f0 = (f >> 15) & 1u, f1 = f >> 31;
+                    asm volatile("" : "+v"(f0));
+                    asm volatile("" : "+v"(f1));
+                    const u32 i0 = linv - (u32)(c * kWave * EPC + 2 * d), i1 = linv - (u32)(c * kWave * EPC + 2 * d + 1);
+                    if (f0) *lds_at(wa) = (wd << 16) | i0;
                     wa += f0 << 2;
-                    if (f1) *lds_at(wa) = (wd & 0xFFFF0000u) | (inv0 - 2 * d - 1);
+                    asm volatile("" : "+v"(wa));
+                    if (f1) *lds_at(wa) = __builtin_amdgcn_perm(wd, i1, 0x07060100u);   // wd's high half : i1's low half
                     wa += f1 << 2;
+                    asm volatile("" : "+v"(wa));
                 }
             }
         }
@@ -659,10 +667,20 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
         }
     }
     wave_sync();
+    // Residual of a code on the 2^-15 grid, rho = rint((y - rint(y)) * 2^15) with y = d * inv:
+    // z = d * (inv * 2^15) equals y * 2^15 exactly, rint(y) * 2^15 is a multiple of 2^15, and
+    // |rho| <= 2^14, so rho is rint(z) reduced to 15 signed bits (for |rho| = 2^14 the sign is
+    // lost, the square is not).  Bitwidths up to 8 keep z below 2^23, where adding 2^23 rounds
+    // to the integer grid with the same round-half-even.
     float inv[QN];
+    bool small_q = true;
 #pragma unroll
-    for (int t = 0; t < QN; ++t) inv[t] = (lane_on && (NQ || t < nq)) ? invt[myb * (u32)nq + t] : 0.f;
-    {
+    for (int t = 0; t < QN; ++t) {
+        inv[t] = (lane_on && (NQ || t < nq)) ? invt[myb * (u32)nq + t] * 32768.0f : 0.f;
+        if ((NQ || t < nq) && a.qlist[t] > 8) small_q = false;
+    }
+    auto abq_sums = [&](auto fast) {
+        constexpr bool kFast = decltype(fast)::value;
         u64 accE = 0;
         for (u32 i0 = 0; i0 < T; i0 += 8) {             // u32 partial sums hold 8 residuals of 2^28
             u32 acc[QN];
@@ -679,15 +697,10 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
 #pragma unroll
                     for (int t = 0; t < QN; ++t) {
                         if (NQ || t < nq) {
-                            // 0 <= y <= Lq (d <= rng and the roundings of Lq / rng, d * inv keep the
-                            // product at or below Lq): the clamp of the definition never acts
-                            const float y = d * inv[t];
-                            const float c = rintf(y);
-                            // rint((y - c) * 2^15): the product is exact, so one fused rounding onto the
-                            // integer grid of 1.5 * 2^23 is the same round-half-even
-                            const float tq = __fmaf_rn(y - c, 32768.0f, 12582912.0f);
-                            const int rho = (int)__float_as_uint(tq) - 0x4B400000;
-                            acc[t] += (u32)__mul24(rho, rho);
+                            const float z = d * inv[t];
+                            const u32 zi = kFast ? __float_as_uint(z + 8388608.0f) : (u32)rintf(z);
+                            const int rho = __builtin_amdgcn_sbfe((int)zi, 0u, 15u);
+                            acc[t] += (u32)(rho * rho);
                         }
                     }
                 }
@@ -697,7 +710,8 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
                 if ((NQ || t < nq) && acc[t]) atomicAdd(&sums[myb * (nq + 1) + t], (u64)acc[t]);
         }
         if (accE) atomicAdd(&sums[myb * (nq + 1) + nq], accE);
-    }
+    };
+    if (small_q) abq_sums(std::true_type()); else abq_sums(std::false_type());
     wave_sync();
 
     // smallest feasible bitwidth per block: the lanes of a block test different candidates in
@@ -751,12 +765,12 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
                     c = (u32)rintf(y);                    // already within [0, 2^q - 1]
                 }
                 {   // index field
-                    const u32 P = p * (u32)w, wi = P >> 5, sft = P & 31u, val = bo_idx[p];
+                    const u32 P = __umul24(p, (u32)w), wi = P >> 5, sft = P & 31u, val = bo_idx[p];
                     atomicOr(&stage[wi], val << sft);
                     if (sft + (u32)w > 32u) atomicOr(&stage[wi + 1], val >> (32u - sft));
                 }
                 {   // code field
-                    const u32 P = idx_bits + coff + (p - bs0) * myq, wi = P >> 5, sft = P & 31u;
+                    const u32 P = idx_bits + coff + __umul24(p - bs0, myq), wi = P >> 5, sft = P & 31u;
                     atomicOr(&stage[wi], c << sft);
                     if (sft + myq > 32u) atomicOr(&stage[wi + 1], c >> (32u - sft));
                 }
