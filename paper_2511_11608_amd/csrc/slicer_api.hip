@@ -162,7 +162,11 @@ template <int DT>
 int launch_small(const SmallArgs& sa, const Plan& p, hipStream_t st)
 {
     constexpr int E0 = DT == 0 ? 4 : 16;      // smallest instantiated elements-per-lane
+#ifdef SLICER_LDS_PAD
+    const int lds = p.small_lds_bytes + SLICER_LDS_PAD;     // development builds: occupancy experiments
+#else
     const int lds = p.small_lds_bytes;
+#endif
     if (p.small_epl <= E0) launch_small_epl<DT, E0>(sa, lds, p.small_maxs, st);
     else if (p.small_epl == E0 * 2) launch_small_epl<DT, E0 * 2>(sa, lds, p.small_maxs, st);
     else if (p.small_epl == E0 * 4) launch_small_epl<DT, E0 * 4>(sa, lds, p.small_maxs, st);
