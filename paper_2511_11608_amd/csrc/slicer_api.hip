@@ -219,6 +219,9 @@ int launch_decode(const void* stream, const void* meta, void* y, int dt, int64_t
     da.R = rows; da.N = row_len; da.M = n_blocks; da.w = index_bits(row_len);
     da.chunks_per_row = (int)((row_len + kDecChunk - 1) / kDecChunk);
     da.mv = meta_view(const_cast<void*>(meta), rows, n_blocks);
+    da.total_words = (const u64*)meta + 6;
+    // the stream segment of a row at keep ratios up to about 0.2 (longer segments are read from global memory)
+    da.stage_words = (int)std::min<int64_t>(1020, (row_len / 16 + 3) / 4 * 4);
     const u64 grid = (u64)rows * (u64)da.chunks_per_row;
     if (grid >= (1ull << 31)) return SLICER_EINVAL;
     const bool timed = g_ev_start && g_ev_stop;
@@ -226,11 +229,12 @@ int launch_decode(const void* stream, const void* meta, void* y, int dt, int64_t
     // short rows: one wavefront per row, the row assembled in LDS (16 KB per wave at most)
     const int64_t row_bytes = row_len * (dt == SLICER_F32 ? 4 : 2);
     if (row_bytes % 16 == 0 && row_bytes <= 16 * 1024 && 2 * n_blocks <= kWave && ((uintptr_t)y & 15) == 0) {
-        const unsigned g4 = (unsigned)((rows + 3) / 4);
+        // one wave per workgroup: the LDS of a row (image + stream segment) is the unit of occupancy
+        const size_t lds = (size_t)row_bytes + 16 * (size_t)((da.stage_words + 4) / 4);
         if (dt == SLICER_F32)
-            hipLaunchKernelGGL((dec_small_kernel<0>), dim3(g4), dim3(256), (size_t)(4 * row_bytes), st, da);
+            hipLaunchKernelGGL((dec_small_kernel<0>), dim3((unsigned)rows), dim3(kWave), lds, st, da);
         else
-            hipLaunchKernelGGL((dec_small_kernel<1>), dim3(g4), dim3(256), (size_t)(4 * row_bytes), st, da);
+            hipLaunchKernelGGL((dec_small_kernel<1>), dim3((unsigned)rows), dim3(kWave), lds, st, da);
     } else if (dt == SLICER_F32)
         hipLaunchKernelGGL((dec_kernel<0, 256>), dim3((unsigned)grid), dim3(256), 0, st, da);
     else

@@ -17,6 +17,8 @@ struct DecArgs {
     int M, w;
     int chunks_per_row;
     MetaView mv;
+    const u64* total_words;   // header field
+    int stage_words;          // short rows: words of LDS per wave for the row's stream segment
 };
 
 template <int DT, int BLOCK>
@@ -129,17 +131,15 @@ __global__ __launch_bounds__(BLOCK) void dec_kernel(DecArgs a)
 // ---- short rows: one wavefront per row, no workgroup barrier ---------------------------
 // Lane b * lpb + sub (lpb = 64 / 2M lanes per block) decodes entries sub, sub + lpb, ... of
 // block b, so neighbouring lanes read neighbouring bit fields; block offsets come from one
-// scan across the lanes.  The row is assembled in LDS and written with 16-byte stores.
+// scan across the lanes.  The row's stream segment is staged in LDS with one coalesced load
+// (when it fits), the row is assembled in LDS and written with 16-byte stores.
 
-__device__ inline u32 dec_scan_add(u32 v)     // inclusive prefix sum over the 64 lanes
+// bit field from a word array in LDS; the array is padded by one readable word
+__device__ inline u32 read_bits_lds(const u32* words, u32 bitpos, u32 nbits)
 {
-    const u32 lane = lane_id();
-#pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) {
-        const u32 t = __shfl_up(v, d);
-        if (lane >= (u32)d) v += t;
-    }
-    return v;
+    const u32 wi = bitpos >> 5, sh = bitpos & 31u;
+    const u64 two = (u64)words[wi] | ((u64)words[wi + 1] << 32);
+    return (u32)(two >> sh) & ((1u << nbits) - 1u);       // nbits <= 16
 }
 
 template <int DT>
@@ -150,17 +150,26 @@ __global__ __launch_bounds__(256) void dec_small_kernel(DecArgs a)
     extern __shared__ uint4 dec_smem[];
     const u32 lane = lane_id();
     const int wid = threadIdx.x / kWave;
-    const int64_t r = (int64_t)blockIdx.x * (256 / kWave) + wid;
+    const int64_t r = (int64_t)blockIdx.x * (int64_t)(blockDim.x / kWave) + wid;
     if (r >= a.R) return;
     const int N = (int)a.N, M = a.M, B2 = 2 * a.M, w = a.w;
     const int row_bytes = N * ESZ;                       // multiple of 16
-    uint4* tile4 = dec_smem + (size_t)wid * (row_bytes / 16);
+    const int per_wave16 = row_bytes / 16 + (a.stage_words + 4) / 4;
+    uint4* tile4 = dec_smem + (size_t)wid * per_wave16;
     raw_t* tile = (raw_t*)tile4;
+    u32* sw = (u32*)(tile4 + row_bytes / 16);            // [stage_words + 1..4]
 
+    const u64 off0 = a.mv.row_off[r];
+    const u64 off1 = r + 1 < a.R ? a.mv.row_off[r + 1] : *a.total_words;
+    const u32 n_pos = a.mv.n_pos[r], n_neg = a.mv.n_neg[r];
+    const u32* __restrict__ rw = a.stream + off0;
+    const u32 nw = (u32)(off1 - off0);
+    const bool staged = off1 >= off0 && nw <= (u32)a.stage_words;
+    if (staged) {
+        for (u32 i = lane; i <= nw; i += kWave) sw[i] = i < nw ? rw[i] : 0u;
+    }
     for (int i = lane; i < row_bytes / 16; i += kWave) tile4[i] = make_uint4(0, 0, 0, 0);
 
-    const u32 n_pos = a.mv.n_pos[r], n_neg = a.mv.n_neg[r];
-    const u32* __restrict__ rw = a.stream + a.mv.row_off[r];
     const u32 lpb = (u32)kWave / (u32)B2;
     const u32 myb = lane / lpb, sub = lane - myb * lpb;
     u32 cnt = 0, q = 0;
@@ -176,23 +185,31 @@ __global__ __launch_bounds__(256) void dec_small_kernel(DecArgs a)
     }
     // first entry and first code bit of my block: scans over one lane per block
     const bool head = sub == 0;
-    const u32 ie = dec_scan_add(head ? cnt : 0u) - (head ? cnt : 0u);
-    const u32 ce = dec_scan_add(head ? cnt * q : 0u) - (head ? cnt * q : 0u);
+    const u32 ie = wave_scan_dpp(head ? cnt : 0u) - (head ? cnt : 0u);
+    const u32 ce = wave_scan_dpp(head ? cnt * q : 0u) - (head ? cnt * q : 0u);
     const u32 n = n_pos + n_neg;
     const u32 istart = (u32)__shfl((int)ie, (int)(myb * lpb));
     const u32 cstart = n * (u32)w + (u32)__shfl((int)ce, (int)(myb * lpb));
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    __builtin_amdgcn_wave_barrier();
+    wave_sync();
 
-    for (u32 j = sub; j < cnt; j += lpb) {
-        const u32 idx = read_bits(rw, (u64)(istart + j) * (u32)w, w);
-        const u32 c = read_bits(rw, (u64)cstart + (u64)j * q, (int)q);
-        float val = __fadd_rn(vmin, __fmul_rn((float)c, step));      // two roundings, never fused
-        if (myb >= (u32)M) val = -val;
-        if (idx < (u32)N) tile[idx] = DT == 0 ? (raw_t)__float_as_uint(val) : (raw_t)f32_to_bf16_rne(val);
+    if (staged && (u64)cstart + (u64)cnt * q <= (u64)nw * 32u) {
+        for (u32 j = sub; j < cnt; j += lpb) {
+            const u32 idx = read_bits_lds(sw, (istart + j) * (u32)w, (u32)w);
+            const u32 c = read_bits_lds(sw, cstart + j * q, q);
+            float val = __fadd_rn(vmin, __fmul_rn((float)c, step));      // two roundings, never fused
+            if (myb >= (u32)M) val = -val;
+            if (idx < (u32)N) tile[idx] = DT == 0 ? (raw_t)__float_as_uint(val) : (raw_t)f32_to_bf16_rne(val);
+        }
+    } else {
+        for (u32 j = sub; j < cnt; j += lpb) {
+            const u32 idx = read_bits(rw, (u64)(istart + j) * (u32)w, w);
+            const u32 c = read_bits(rw, (u64)cstart + (u64)j * q, (int)q);
+            float val = __fadd_rn(vmin, __fmul_rn((float)c, step));      // two roundings, never fused
+            if (myb >= (u32)M) val = -val;
+            if (idx < (u32)N) tile[idx] = DT == 0 ? (raw_t)__float_as_uint(val) : (raw_t)f32_to_bf16_rne(val);
+        }
     }
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    __builtin_amdgcn_wave_barrier();
+    wave_sync();
 
     uint4* __restrict__ out = (uint4*)((char*)a.y + (size_t)r * (size_t)row_bytes);
     for (int i = lane; i < row_bytes / 16; i += kWave) out[i] = tile4[i];
