@@ -350,8 +350,10 @@ int slicer_encode(const void* x, slicer_dtype dt, int64_t rows, int64_t row_len,
         ea.only_flagged = la.fallback;
         ea.rows_per_wg = 1;
     }
-    rc = dt == SLICER_F32 ? launch_encode<0>(ea, st) : launch_encode<1>(ea, st);
-    if (rc) return rc;
+    if (!ea.only_flagged) {
+        rc = dt == SLICER_F32 ? launch_encode<0>(ea, st) : launch_encode<1>(ea, st);
+        if (rc) return rc;
+    }
 
     FinishArgs fa;
     fa.R = rows; fa.N = row_len; fa.k = p.k;
@@ -368,7 +370,13 @@ int slicer_encode(const void* x, slicer_dtype dt, int64_t rows, int64_t row_len,
     fa.mv = ea.mv;
     const u64 grid = ((u64)rows * (u64)fa.chunks_per_row + 3) / 4;     // four wavefronts per workgroup
     if (grid >= (1ull << 31)) return SLICER_EINVAL;
-    hipLaunchKernelGGL(enc_rowscan_kernel, dim3((unsigned)((rows + kScanRows - 1) / kScanRows)), dim3(kScanRows), 0, st, fa);
+    const dim3 gscan((unsigned)((rows + kScanRows - 1) / kScanRows));
+    if (!ea.only_flagged)
+        hipLaunchKernelGGL(enc_rowscan_kernel, gscan, dim3(kScanRows), 0, st, fa);
+    else if (dt == SLICER_F32)      // rows a fast path flagged are redone here, just before the scan of their chunk
+        hipLaunchKernelGGL((enc_fix_rowscan_kernel<0>), gscan, dim3(kScanRows), 0, st, ea, fa);
+    else
+        hipLaunchKernelGGL((enc_fix_rowscan_kernel<1>), gscan, dim3(kScanRows), 0, st, ea, fa);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e);
     hipLaunchKernelGGL(enc_gather_kernel, dim3((unsigned)grid), dim3(256), 0, st, fa);

@@ -100,8 +100,10 @@ __device__ inline void stage_or_bits(u32* stage, u64 lo, u64 hi, u64 P, u32 v, i
     if (sh + (u32)nb > 32u) atomicOr(&stage[wi + 1], v >> (32u - sh));
 }
 
+// Encodes rows [r_begin, r_end) one after the other with the whole workgroup; with
+// a.only_flagged set, only the rows whose flag is non-zero.
 template <int DT, int BLOCK>
-__global__ __launch_bounds__(BLOCK) void enc_generic_kernel(EncArgs a)
+__device__ inline void enc_generic_rows(const EncArgs& a, const int64_t r_begin, const int64_t r_end)
 {
     typedef Elem<DT> E;
     typedef typename E::raw_t raw_t;
@@ -128,13 +130,12 @@ __global__ __launch_bounds__(BLOCK) void enc_generic_kernel(EncArgs a)
     const int tid = threadIdx.x;
     const u32 lane = lane_id();
     const int wid = tid / kWave;
-    const int64_t r_end = ((int64_t)blockIdx.x + 1) * a.rows_per_wg < a.R ? ((int64_t)blockIdx.x + 1) * a.rows_per_wg : a.R;
     if (a.only_flagged) {       // one coalesced look at this workgroup's flags: usually none is set
         int any = 0;
-        for (int64_t r = (int64_t)blockIdx.x * a.rows_per_wg + tid; r < r_end; r += BLOCK) any |= (int)a.only_flagged[r];
+        for (int64_t r = r_begin + tid; r < r_end; r += BLOCK) any |= (int)a.only_flagged[r];
         if (!__syncthreads_or(any)) return;
     }
-    for (int64_t r = (int64_t)blockIdx.x * a.rows_per_wg; r < r_end; ++r) {
+    for (int64_t r = r_begin; r < r_end; ++r) {
     if (a.only_flagged && !a.only_flagged[r]) continue;      // uniform: the whole workgroup skips
     const int64_t N = a.N;
     const int M = a.M, w = a.w, B2 = 2 * a.M;
@@ -522,13 +523,20 @@ __global__ __launch_bounds__(BLOCK) void enc_generic_kernel(EncArgs a)
     }   // rows of this workgroup
 }
 
+template <int DT, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void enc_generic_kernel(EncArgs a)
+{
+    const int64_t r0 = (int64_t)blockIdx.x * a.rows_per_wg;
+    enc_generic_rows<DT, BLOCK>(a, r0, r0 + a.rows_per_wg < a.R ? r0 + a.rows_per_wg : a.R);
+}
+
 // ---- row offsets (exclusive scan of the row word counts), header, gather ------------------
-// Two launches: (1) every workgroup scans the word counts of 1024 consecutive rows and
+// Two launches: (1) every workgroup scans the word counts of 256 consecutive rows and
 // leaves the rows' offsets relative to its chunk plus the chunk total; (2) the gather
 // kernel adds the totals of the preceding chunks, writes the final offsets and the header
 // and copies each row's slot to its place in the contiguous stream.
 
-constexpr int kScanRows = 1024;
+constexpr int kScanRows = 256;
 constexpr int kGatherWords = 1024;   // slot words one wavefront copies
 
 struct FinishArgs {
@@ -546,7 +554,7 @@ struct FinishArgs {
     MetaView mv;
 };
 
-__global__ __launch_bounds__(kScanRows) void enc_rowscan_kernel(FinishArgs a)
+__device__ inline void rowscan_chunk(const FinishArgs& a)
 {
     __shared__ u64 s_part[kScanRows / kWave];
     const int tid = threadIdx.x;
@@ -570,6 +578,22 @@ __global__ __launch_bounds__(kScanRows) void enc_rowscan_kernel(FinishArgs a)
     }
     if (i < a.R) a.row_off_local[i] = wbase + inc - v;
     if (tid == 0) a.chunk_tot[blockIdx.x] = tot;
+}
+
+__global__ __launch_bounds__(kScanRows) void enc_rowscan_kernel(FinishArgs a)
+{
+    rowscan_chunk(a);
+}
+
+// The same scan, preceded by the generic encoder for the rows of this chunk that a fast
+// path flagged (normally none: one coalesced look at the flags, then straight to the scan).
+template <int DT>
+__global__ __launch_bounds__(kScanRows) void enc_fix_rowscan_kernel(EncArgs ea, FinishArgs a)
+{
+    const int64_t r0 = (int64_t)blockIdx.x * kScanRows;
+    enc_generic_rows<DT, kScanRows>(ea, r0, r0 + kScanRows < ea.R ? r0 + kScanRows : ea.R);
+    __syncthreads();
+    rowscan_chunk(a);
 }
 
 __global__ __launch_bounds__(256) void enc_gather_kernel(FinishArgs a)

@@ -268,9 +268,10 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
     }
     wave_sync();
 
-    // the list must hold everything from bin B1 up
+    // the list takes every non-zero key from bin B1 up (bin 0 also counts the zeros, which
+    // never enter the list: its length is known after the counting pass below)
     const u32 t_lo = (B1 << KS) > 1u ? (B1 << KS) : 1u;          // smallest non-zero key of bin B1
-    if (k > 0 && (int)(c_gt + cnt1) > cap) {
+    if (k > 0 && B1 > 0u && (int)(c_gt + cnt1) > cap) {
         if (lane == 0) a.fallback[r] = 1u;
         return;
     }
@@ -312,6 +313,10 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
         }
         // every flagged element is stored at a running byte address that advances by its flag
         const u32 lidx_off = (u32)((u32*)L.Lidx - smem) * 4u;
+        if ((int)nL > cap) {                                      // uniform
+            if (lane == 0) a.fallback[r] = 1u;
+            return;
+        }
         // (the empty asm statements pin values in registers: the optimiser would otherwise
         //  re-derive each flag and each inverted index with longer instruction sequences)
         u32 linv = 0xFFFFu - lane * (u32)EPC;
