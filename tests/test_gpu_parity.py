@@ -94,6 +94,30 @@ def test_random_parameters(oracle, dtype):
         check(oracle, x, dtype, keep, M, bits, budget)
 
 
+def _mixed_rows(rng, rows, N, dtype):
+    """Gaussian rows with per-row scale, plus sparse, constant, few-valued and one-sided rows."""
+    x = rng.standard_normal((rows, N)).astype(np.float32) * (10.0 ** rng.uniform(-2, 2, (rows, 1))).astype(np.float32)
+    x[1, rng.random(N) < 0.97] = 0                     # fewer non-zeros than k at most keep ratios
+    x[2, :] = np.float32(1.5)                          # one key: every rank is a tie
+    x[3, :] = rng.choice(np.array([-2.0, -1.0, 0.5, 1.0, 4.0], np.float32), N)
+    x[4, :] = np.abs(x[4, :])                          # one sign class only
+    x[5, :] = 0
+    x[6, : N // 2] *= np.float32(1e-30)                # wide key range: coarse fine bins
+    return synth.f32_to_bf16_bits(x) if dtype == "bf16" else x
+
+
+@pytest.mark.parametrize("dtype,N", [("bf16", 256), ("bf16", 4096), ("bf16", 8192), ("f32", 768), ("f32", 2048)])
+def test_row_resident_variants(oracle, dtype, N):
+    """Every variant of the one-wave-per-row encoder (list in registers or LDS, short or long
+    bitwidth ladders, up to 64 blocks) and both bit-field sources of the short-row decoder."""
+    rng = np.random.default_rng(N)
+    x = _mixed_rows(rng, 24, N, dtype)
+    for keep, M, bits, budget in ((0.02, 1, B28, 1e-3), (0.1, 8, B28, 1e-3), (0.15, 32, B28, 5e-4),
+                                  (0.25, 5, (1 << 1) | (1 << 16), 1e-5), (0.28, 3, 0xFE00, 1e-7),
+                                  (0.45, 8, B28, 1e-3), (0.6, 2, 0x1FFFE, 1e-4), (1.0, 16, B28, 1e-2)):
+        check(oracle, x, dtype, keep, M, bits, budget)
+
+
 def test_encode_is_deterministic():
     from tests.gpu_util import gpu_roundtrip
     wl = synth.llm_prefill(seed=3, rows=64)
