@@ -83,10 +83,18 @@ def cpu_baseline(wl, threads: int) -> dict:
     ref.decode(s, m, n_threads=threads)
     t2 = time.perf_counter()
     nbytes = x.nbytes
+    # one thread, on a slice of the sample sized for a few seconds
+    take1 = int(max(1, min(take, 4.0 / max(per_row, 1e-9))))
+    x1 = wl.x[:take1]
+    t3 = time.perf_counter()
+    s1, m1 = ref.encode(x1, wl.dtype, wl.keep_ratio, wl.n_blocks, wl.bit_set, wl.budget, n_threads=1)
+    ref.decode(s1, m1, n_threads=1)
+    t4 = time.perf_counter()
     return {"value": nbytes / (t2 - t0) / 1e9, "unit": "GB/s of input IF (encode+decode)",
             "cores": int(min(threads, take)), "kind": "oracle",
             "sample": f"first {take} of {rows} rows of the same workload, OpenMP over rows",
-            "encode_GBps": nbytes / (t1 - t0) / 1e9, "decode_GBps": nbytes / (t2 - t1) / 1e9}
+            "encode_GBps": nbytes / (t1 - t0) / 1e9, "decode_GBps": nbytes / (t2 - t1) / 1e9,
+            "single_thread_GBps": x1.nbytes / (t4 - t3) / 1e9, "single_thread_rows": take1}
 
 
 def load_traffic(workload: str, kernel: str):
@@ -214,6 +222,16 @@ def main() -> int:
     torch.cuda.synchronize()
     binding.slicer_profile_events(None, None)
 
+    # latency of single steps (submit, wait): the figure that matters for step-by-step decoding
+    lats = []
+    for i in range(min(K, 200)):
+        t_a = time.perf_counter()
+        step(W + i, None)
+        torch.cuda.synchronize()
+        lats.append((time.perf_counter() - t_a) * 1e6)
+    lat = {"p50": float(np.percentile(lats, 50)), "p99": float(np.percentile(lats, 99)), "n": len(lats),
+           "note": "one step submitted and waited for from the host, plain launches"}
+
     enc_ms = float(np.mean([ev.elapsed_ms(a, b) for a, b in e_enc]))
     dec_ms = float(np.mean([ev.elapsed_ms(a, b) for a, b in e_dec]))
 
@@ -240,6 +258,16 @@ def main() -> int:
     n_el = wl.rows * wl.row_len
     out_bytes = 4 * words + meta_bytes
     bpe = 8.0 * out_bytes / n_el
+    # where the bits go (Sec. 3.3: value bits, index bits, header): counts from the meta arrays
+    torch.cuda.synchronize()
+    mh = bufs[0][1][:meta_bytes].cpu().numpy()
+    R_, M_ = wl.rows, M
+    n_kept = int(mh[64 + 8 * R_: 64 + 16 * R_].view(np.uint32).sum())
+    w_bits = max(1, int(np.ceil(np.log2(wl.row_len)))) if wl.row_len > 1 else 1
+    idx_bits_total = n_kept * w_bits
+    value_bits_total = 32 * words - idx_bits_total          # codes + the word padding of each row
+    bit_split = {"index_bits_per_element": idx_bits_total / n_el, "value_bits_per_element": value_bits_total / n_el,
+                 "header_bits_per_element": 8.0 * meta_bytes / n_el, "kept_elements": n_kept}
 
     path = binding.slicer_encode_path(binding.SLICER_F32 if wl.dtype == "f32" else binding.SLICER_BF16,
                                       wl.rows, wl.row_len, keep, M, bits)
@@ -279,7 +307,8 @@ def main() -> int:
         "decode": {"GBps": in_bytes / (dec_call_ms * 1e-3) / 1e9, "ms": dec_call_ms,
                    "elements_per_s": n_el / (dec_call_ms * 1e-3),
                    "frac_hbm_peak": in_bytes / (dec_call_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
-        "bits_per_element": bpe, "stream_words": words, "meta_bytes": meta_bytes,
+        "bits_per_element": bpe, "bit_split": bit_split, "stream_words": words, "meta_bytes": meta_bytes,
+        "step_latency_us": lat,
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
