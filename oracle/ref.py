@@ -25,6 +25,12 @@ def lib() -> C.CDLL:
         L.slicer_ref_encode.restype = C.c_int
         L.slicer_ref_encode.argtypes = [C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_double, C.c_int,
                                         C.c_uint32, C.c_double, C.c_void_p, C.c_void_p, C.c_int]
+        L.slicer_ref_encode_ladder.restype = C.c_int
+        L.slicer_ref_encode_ladder.argtypes = [C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_double, C.c_int,
+                                               C.c_void_p, C.c_void_p, C.c_void_p, C.c_int]
+        L.slicer_ref_bound.restype = C.c_int
+        L.slicer_ref_bound.argtypes = [C.c_int, C.c_int64, C.c_int64, C.c_double, C.c_int, C.c_uint32,
+                                       C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)]
         L.slicer_ref_decode.restype = C.c_int
         L.slicer_ref_decode.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int]
         L.slicer_ref_analyze_row.restype = C.c_int
@@ -65,6 +71,40 @@ def encode(x: np.ndarray, dtype: str, keep_ratio: float, n_blocks: int, bit_set:
         raise ValueError(f"slicer_ref_encode: error {rc}")
     total = int(meta[48:56].view(np.uint64)[0])
     return stream[:total].copy(), meta
+
+
+def ladder_bit_set(ladder) -> int:
+    bs = 0
+    for q in ladder:
+        bs |= 1 << int(q)
+    return bs
+
+
+def encode_ladder(x: np.ndarray, dtype: str, keep_ratio: float, ladder, n_threads: int = 1):
+    """Fixed multi-level mode: block m of each sign class uses ladder[m] bits (n_blocks = len(ladder))."""
+    x = _check_x(x, dtype)
+    rows, row_len = x.shape
+    lad = np.ascontiguousarray(np.asarray(ladder, np.uint8))
+    M = int(lad.size)
+    cap, mb = sizes(dtype, rows, row_len, keep_ratio, M, ladder_bit_set(lad))
+    stream = np.zeros(max(cap // 4, 1), np.uint32)
+    meta = np.zeros(mb, np.uint8)
+    rc = lib().slicer_ref_encode_ladder(x.ctypes.data, _DT[dtype], rows, row_len, keep_ratio, M,
+                                        lad.ctypes.data, stream.ctypes.data, meta.ctypes.data, n_threads)
+    if rc:
+        raise ValueError(f"slicer_ref_encode_ladder: error {rc}")
+    total = int(meta[48:56].view(np.uint64)[0])
+    return stream[:total].copy(), meta
+
+
+def bound(dtype: str, rows: int, row_len: int, keep_ratio: float, n_blocks: int, bit_set: int):
+    """(value_bits, index_bits, header_bits) of the payload's upper bound."""
+    v, i, h = C.c_uint64(0), C.c_uint64(0), C.c_uint64(0)
+    rc = lib().slicer_ref_bound(_DT[dtype], rows, row_len, keep_ratio, n_blocks, bit_set,
+                                C.byref(v), C.byref(i), C.byref(h))
+    if rc:
+        raise ValueError(f"slicer_ref_bound: error {rc}")
+    return v.value, i.value, h.value
 
 
 def decode(stream: np.ndarray, meta: np.ndarray, n_threads: int = 1) -> np.ndarray:

@@ -40,6 +40,14 @@
  *     each), LSB-first in little-endian 32-bit words, row padded to a word.
  *  8. Decode (Eq. "dequnt"): y = 0; y[idx] = +-(vmin + c * o).
  *
+ * Fixed multi-level mode (Sec. 4.1 "multi-level quantization", Q = [q_1 > ... > q_M]):
+ * block m of either sign class is quantised with the given q_m (block 0 = largest
+ * magnitudes gets q_1); there is no search and no distortion guard, everything else
+ * (ATKF, MS, AIQ, packing) is as above.  The header's bit_set is the set of ladder values.
+ *
+ * Payload bound (Sec. 3.3, "Predictive Bit/Time Model"): every kept slot at the largest
+ * bitwidth, plus index and header bits; see slicer_ref_bound.
+ *
  * Wire format, version 1 (little-endian):
  *   meta:  0 u32 magic 0x52434C53   4 u32 version   8 u32 dtype   12 u32 M
  *         16 u64 rows  24 u64 row_len  32 u64 k  40 u32 bit_set  44 u32 w
@@ -178,8 +186,9 @@ static uint32_t aiq_code(float a, float vmin, float inv, float L, float* y_out)
     return (uint32_t)r;
 }
 
+/* fixed_q > 0: the block's bitwidth is given (multi-level mode), no search */
 static void quantise_block(const kv_t* el, uint32_t cnt, uint32_t bit_set, double beta,
-                           int b, row_result* out)
+                           int fixed_q, int b, row_result* out)
 {
     /* block range (Sec. 3.2.1: v^min, v^max) */
     float vmin = bits_to_float(el[0].key), vmax = vmin;
@@ -204,8 +213,8 @@ static void quantise_block(const kv_t* el, uint32_t cnt, uint32_t bit_set, doubl
     if (out->e_exp) out->e_exp[b] = e;
 
     int degenerate = !(rng >= 0x1p-100f);
-    int chosen = -1;
-    for (int q = 1; q <= 16; ++q) {
+    int chosen = fixed_q > 0 ? fixed_q : -1;
+    for (int q = 1; q <= 16 && fixed_q <= 0; ++q) {
         if (!((bit_set >> q) & 1u)) continue;
         if (chosen >= 0 && !out->s_int) break; /* later sums only wanted for inspection */
         uint64_t S = 0;
@@ -254,8 +263,9 @@ static void quantise_block(const kv_t* el, uint32_t cnt, uint32_t bit_set, doubl
     }
 }
 
+/* ladder != NULL: multi-level mode, ladder[m] = bitwidth of block m of each class */
 static int analyze_row(const void* x, int dt, int64_t N, int64_t k, int M, uint32_t bit_set,
-                       double beta, row_result* out)
+                       double beta, const uint8_t* ladder, row_result* out)
 {
     kv_t* all = (kv_t*)malloc(sizeof(kv_t) * (size_t)N);
     kv_t* cls = (kv_t*)malloc(sizeof(kv_t) * (size_t)(k > 0 ? k : 1));
@@ -272,7 +282,8 @@ static int analyze_row(const void* x, int dt, int64_t N, int64_t k, int M, uint3
     qsort(all, (size_t)N, sizeof(kv_t), cmp_mag_desc_idx_asc);
 
     for (int b = 0; b < 2 * M; ++b) {
-        out->vmin[b] = 0.0f; out->vmax[b] = 0.0f; out->qb[b] = (uint8_t)min_bit(bit_set);
+        out->vmin[b] = 0.0f; out->vmax[b] = 0.0f;
+        out->qb[b] = ladder ? ladder[b % M] : (uint8_t)min_bit(bit_set);   /* empty blocks keep this */
         out->count[b] = 0;
         if (out->e_int) out->e_int[b] = 0;
         if (out->e_exp) out->e_exp[b] = 0;
@@ -298,7 +309,7 @@ static int analyze_row(const void* x, int dt, int64_t N, int64_t k, int M, uint3
             out->count[b] = cnt;
             if (cnt > 0) {
                 for (uint32_t j = 0; j < cnt; ++j) out->block_of[cls[start + j].idx] = b;
-                quantise_block(cls + start, cnt, bit_set, beta, b, out);
+                quantise_block(cls + start, cnt, bit_set, beta, ladder ? (int)ladder[m] : 0, b, out);
             }
             start += cnt;
         }
@@ -388,8 +399,9 @@ static void row_result_free(row_result* rr)
 
 /* ---- public: encode ---------------------------------------------------- */
 
-int slicer_ref_encode(const void* x, int dt, int64_t R, int64_t N, double keep, int M,
-                      uint32_t bit_set, double beta, void* stream, void* meta, int n_threads)
+static int encode_common(const void* x, int dt, int64_t R, int64_t N, double keep, int M,
+                         uint32_t bit_set, double beta, const uint8_t* ladder,
+                         void* stream, void* meta, int n_threads)
 {
     int rc = check_args(dt, R, N, keep, M, bit_set);
     if (rc) return rc;
@@ -418,7 +430,7 @@ int slicer_ref_encode(const void* x, int dt, int64_t R, int64_t N, double keep, 
         uint32_t* idxbuf = (uint32_t*)malloc(sizeof(uint32_t) * (size_t)(k > 0 ? k : 1));
         seg[r] = (uint32_t*)calloc((size_t)(cap_words > 0 ? cap_words : 1), 4);
         const void* xr = (const char*)x + (size_t)r * (size_t)N * esz;
-        if (analyze_row(xr, dt, N, k, M, bit_set, beta, &rr) != 0) {
+        if (analyze_row(xr, dt, N, k, M, bit_set, beta, ladder, &rr) != 0) {
             fail = 1;
         } else {
             seg_words[r] = pack_row(&rr, N, M, w, seg[r], idxbuf);
@@ -458,6 +470,51 @@ int slicer_ref_encode(const void* x, int dt, int64_t R, int64_t N, double keep, 
     put_u64(mt + 48, total);
     put_u64(mt + 56, 0);
     return fail ? -3 : 0;
+}
+
+int slicer_ref_encode(const void* x, int dt, int64_t R, int64_t N, double keep, int M,
+                      uint32_t bit_set, double beta, void* stream, void* meta, int n_threads)
+{
+    return encode_common(x, dt, R, N, keep, M, bit_set, beta, NULL, stream, meta, n_threads);
+}
+
+/* set of the ladder's bitwidths; 0 if an entry is outside 1..16 */
+static uint32_t ladder_bit_set(const uint8_t* ladder, int M)
+{
+    uint32_t bs = 0;
+    for (int m = 0; m < M; ++m) {
+        if (ladder[m] < 1 || ladder[m] > 16) return 0;
+        bs |= 1u << ladder[m];
+    }
+    return bs;
+}
+
+int slicer_ref_encode_ladder(const void* x, int dt, int64_t R, int64_t N, double keep, int M,
+                             const uint8_t* ladder, void* stream, void* meta, int n_threads)
+{
+    if (!ladder || M < 1 || M > 64) return -1;
+    uint32_t bs = ladder_bit_set(ladder, M);
+    if (!bs) return -1;
+    return encode_common(x, dt, R, N, keep, M, bs, 0.0, ladder, stream, meta, n_threads);
+}
+
+/* Sec. 3.3: value bits with every block at q_bit = max(bit_set), index bits, header bits.
+ * Every row is taken to send its full k entries; the zero bits that pad a row's segment to
+ * a whole word are counted with the header, so the three parts add up to the worst-case
+ * size of stream + meta in bits. */
+int slicer_ref_bound(int dt, int64_t R, int64_t N, double keep, int M, uint32_t bit_set,
+                     uint64_t* value_bits, uint64_t* idx_bits, uint64_t* header_bits)
+{
+    int rc = check_args(dt, R, N, keep, M, bit_set);
+    if (rc) return rc;
+    const uint64_t k = (uint64_t)keep_count(keep, N);
+    const uint64_t w = (uint64_t)index_bits(N), qb = (uint64_t)max_bit(bit_set);
+    const uint64_t row_bits = k * (w + qb);
+    const uint64_t pad = (32 - row_bits % 32) % 32;
+    if (value_bits) *value_bits = (uint64_t)R * k * qb;
+    if (idx_bits) *idx_bits = (uint64_t)R * k * w;
+    if (header_bits) *header_bits = 8 * (uint64_t)meta_size(R, M) + (uint64_t)R * pad;
+    return 0;
 }
 
 /* ---- public: decode (Eq. "dequnt") -------------------------------------- */
@@ -528,7 +585,7 @@ int slicer_ref_analyze_row(const void* x_row, int dt, int64_t N, double keep, in
     if (!x_row || !(beta >= 0.0)) return -1;
     row_result rr;
     row_result_alloc(&rr, N, M, 1);
-    rc = analyze_row(x_row, dt, N, keep_count(keep, N), M, bit_set, beta, &rr);
+    rc = analyze_row(x_row, dt, N, keep_count(keep, N), M, bit_set, beta, NULL, &rr);
     if (rc == 0) {
         if (block_of) memcpy(block_of, rr.block_of, sizeof(int32_t) * (size_t)N);
         if (code_of) memcpy(code_of, rr.code_of, sizeof(uint32_t) * (size_t)N);

@@ -35,6 +35,19 @@ int slicer_ref_encode(const void* x, int dtype, int64_t rows, int64_t row_len,
                       double distortion_budget, void* stream, void* meta,
                       int n_threads);
 
+/* Fixed multi-level mode (Sec. 4.1: Q = [q_1 > ... > q_M], assigned in descending order of
+ * magnitude): block m of each sign class is quantised with ladder[m] bits, 1..16, no search.
+ * Buffers sized by slicer_ref_sizes with bit_set = the set of ladder values. */
+int slicer_ref_encode_ladder(const void* x, int dtype, int64_t rows, int64_t row_len,
+                             double keep_ratio, int n_blocks, const uint8_t* ladder,
+                             void* stream, void* meta, int n_threads);
+
+/* Upper bound of the payload before any data is seen (Sec. 3.3): value bits at
+ * q_bit = max(bit_set), index bits, header bits (meta + word padding of the rows). */
+int slicer_ref_bound(int dtype, int64_t rows, int64_t row_len, double keep_ratio, int n_blocks,
+                     uint32_t bit_set, uint64_t* value_bits, uint64_t* index_bits,
+                     uint64_t* header_bits);
+
 /* Decode into dense y (same dtype and shape as the encoded tensor). */
 int slicer_ref_decode(const void* stream, const void* meta, void* y, int n_threads);
 

@@ -412,3 +412,86 @@ def test_decode_is_two_fp32_roundings(oracle):
             sign = -1.0 if b >= wl.n_blocks else 1.0
             assert np.array_equal(y[r][idx], (sign * want).astype(np.float32))
     assert n_diff_fma > 0      # the sample does tell a fused multiply-add apart
+
+
+# ----------------------------------------------------------------------------
+# fixed multi-level mode (Sec. 4.1: Q = [q_1 > ... > q_M]) and the payload bound (Sec. 3.3)
+# ----------------------------------------------------------------------------
+
+def test_golden_ladder(oracle):
+    g = GOLD["ladder"]
+    x = np.array([g["x"]], np.float32)
+    s, m = oracle.encode_ladder(x, "f32", g["keep_ratio"], g["ladder"])
+    assert [int(v) for v in s] == [int(v, 16) for v in g["words"]]
+    assert streamfmt.arrays(m)["q"][0].tolist() == g["q"]
+    assert streamfmt.header(m)["bit_set"] == bits_of(g["ladder"])
+    assert oracle.decode(s, m)[0].tolist() == g["decoded"]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_ladder_equals_single_bitwidth_search(oracle, dtype):
+    """With one allowed bitwidth and any budget the search can only return that bitwidth, so a
+    constant ladder must give the same bytes except for the infeasible flags of the search."""
+    wl = synth.vit_tokens(seed=2, rows=6) if dtype == "f32" else synth.llm_prefill(seed=2, rows=6)
+    for q in (2, 5, 8, 16):
+        s0, m0 = oracle.encode(wl.x, wl.dtype, wl.keep_ratio, 4, 1 << q, 1e30)
+        s1, m1 = oracle.encode_ladder(wl.x, wl.dtype, wl.keep_ratio, [q] * 4)
+        assert np.array_equal(s0, s1) and np.array_equal(m0, m1)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_ladder_blocks_bits_and_error(oracle, dtype):
+    wl = synth.vit_tokens(seed=4, rows=5) if dtype == "f32" else synth.llm_prefill(seed=4, rows=5)
+    ladder = [8, 6, 5, 4, 3, 3, 2, 2]
+    M = len(ladder)
+    s, m = oracle.encode_ladder(wl.x, wl.dtype, wl.keep_ratio, ladder)
+    s_abq, m_abq = oracle.encode(wl.x, wl.dtype, wl.keep_ratio, M, bits_of(ladder), 1e-3)
+    h, a, a2 = streamfmt.header(m), streamfmt.arrays(m), streamfmt.arrays(m_abq)
+    # selection and blocks do not depend on the quantiser: same counts and ranges as the search mode
+    for name in ("n_pos", "n_neg", "vmin", "vmax"):
+        assert np.array_equal(a[name], a2[name])
+    assert np.array_equal(a["q"], np.tile(np.array(ladder * 2, np.uint8), (wl.rows, 1)))
+    y = f32(oracle.decode(s, m), dtype)
+    xf = f32(wl.x, dtype)
+    for r in range(wl.rows):
+        pr = streamfmt.parse_row(s, m, r)
+        sizes = streamfmt.block_sizes(int(a["n_pos"][r]), M) + streamfmt.block_sizes(int(a["n_neg"][r]), M)
+        bits = sum(n * (h["w"] + ladder[b % M]) for b, n in enumerate(sizes))
+        assert pr["bits"] == bits
+        for b, (idx, codes) in enumerate(pr["blocks"]):
+            if not idx:
+                continue
+            q = ladder[b % M]
+            assert max(codes) <= (1 << q) - 1
+            o = (float(a["vmax"][r, b]) - float(a["vmin"][r, b])) / ((1 << q) - 1)
+            err = np.abs(np.abs(xf[r, idx]) - np.abs(y[r, idx]))
+            tol = o / 2 * (1 + 2.0 ** -10) + (2.0 ** -8 * float(a["vmax"][r, b]) if dtype == "bf16" else 0.0)   # + half a bf16 ulp of the output
+            assert err.max() <= tol
+
+
+def test_ladder_rejects_bad_entries(oracle):
+    x = np.ones((1, 8), np.float32)
+    for lad in ([0, 2], [17], []):
+        with pytest.raises((ValueError, ZeroDivisionError)):
+            oracle.encode_ladder(x, "f32", 0.5, lad)
+
+
+@pytest.mark.parametrize("cfg", [1, 3, 4, 5])
+def test_bound_closed_form_and_dominates(oracle, cfg):
+    """B^UB of Sec. 3.3 = k*q_bit value bits + k*w index bits per row + header; the three parts add
+    up to the worst-case buffer sizes, and no encoded payload exceeds them."""
+    wl = synth.make_config(cfg, rows=3) if cfg != 1 else synth.make_config(1)
+    R, N = wl.x.shape
+    k = int(np.floor(wl.keep_ratio * N))
+    w = max(1, int(np.ceil(np.log2(N))))
+    v, i, hb = oracle.bound(wl.dtype, R, N, wl.keep_ratio, wl.n_blocks, wl.bit_set)
+    assert v == R * k * 8 and i == R * k * w
+    cap, mb = oracle.sizes(wl.dtype, R, N, wl.keep_ratio, wl.n_blocks, wl.bit_set)
+    assert v + i + hb == 8 * (cap + mb)
+    s, m = oracle.encode(wl.x, wl.dtype, wl.keep_ratio, wl.n_blocks, wl.bit_set, wl.budget)
+    assert 32 * s.size + 8 * mb <= v + i + hb
+    # the bound is attained when every kept slot is used at the largest bitwidth
+    x = np.arange(1, 65, dtype=np.float32).reshape(1, 64) * np.float32(1.37)
+    s, m = oracle.encode(x, "f32", 1.0, 2, 1 << 7, 0.0)
+    v, i, hb = oracle.bound("f32", 1, 64, 1.0, 2, 1 << 7)
+    assert 32 * s.size + 8 * m.size == v + i + hb
