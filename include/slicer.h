@@ -110,6 +110,37 @@ int slicer_decode_as(const void* stream, const void* meta, void* y, slicer_dtype
                      int64_t rows, int64_t row_len, int n_blocks, void* hip_stream);
 
 /*
+ * Fixed multi-level mode (Sec. 4.1: "multi-level quantization Q = [q_1, ..., q_M] ... with
+ * q_1 > ... > q_M bits assigned in descending order of activation magnitude"): block m of
+ * either sign class (block 0 = largest magnitudes) is quantised with ladder[m] bits; there
+ * is no bitwidth search and no distortion guard, everything else is slicer_encode.
+ *   ladder   HOST pointer, n_blocks entries, each 1..16 (any order is accepted; it is read
+ *            during the call, not afterwards).
+ * Buffers are sized by slicer_sizes with bit_set = slicer_ladder_bit_set(ladder, n_blocks),
+ * which is also the bit_set written to the header.  Errors as slicer_encode; SLICER_EINVAL for
+ * a null ladder or an entry outside 1..16.
+ */
+int slicer_encode_ladder(const void* x, slicer_dtype dt, int64_t rows, int64_t row_len,
+                         double keep_ratio, int n_blocks, const uint8_t* ladder,
+                         void* stream, void* meta, void* workspace, void* hip_stream);
+
+/* The set of bitwidths of a ladder (bit q set <=> some ladder[m] == q); 0 for an invalid ladder. */
+uint32_t slicer_ladder_bit_set(const uint8_t* ladder, int n_blocks);
+
+/*
+ * Upper bound of the payload, known before any data is seen (Sec. 3.3, "Predictive Bit/Time
+ * Model": every block at q_bit = max(bit_set), plus index and header bits), for a control
+ * plane that must check a bit budget before execution.  Host computation only.
+ *   value_bits   rows * k * q_bit
+ *   index_bits   rows * k * w
+ *   header_bits  8 * meta_bytes + the zero bits that pad every row's segment to a 32-bit word
+ * The three add up to 8 * (stream_capacity_bytes + meta_bytes) of slicer_sizes; no encode
+ * call with these arguments produces more.  Any output pointer may be null.
+ */
+int slicer_bound(slicer_dtype dt, int64_t rows, int64_t row_len, double keep_ratio, int n_blocks,
+                 uint32_t bit_set, uint64_t* value_bits, uint64_t* index_bits, uint64_t* header_bits);
+
+/*
  * Which kernel family slicer_encode uses for a shape (for benchmarks and profiles, which
  * name the dominant kernel): 0 = generic (one workgroup per row, any shape), 1 = row-resident
  * (one wavefront per row, rows up to 8192 bf16 / 2048 fp32 elements), 2 = long-row stages

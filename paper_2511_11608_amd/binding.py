@@ -44,6 +44,12 @@ def load() -> C.CDLL:
         L.slicer_encode_path.argtypes = [cint, i64, i64, dbl, cint, u32]
         L.slicer_encode.restype = cint
         L.slicer_encode.argtypes = [vp, cint, i64, i64, dbl, cint, u32, dbl, vp, vp, vp, vp]
+        L.slicer_encode_ladder.restype = cint
+        L.slicer_encode_ladder.argtypes = [vp, cint, i64, i64, dbl, cint, C.c_char_p, vp, vp, vp, vp]
+        L.slicer_ladder_bit_set.restype = u32
+        L.slicer_ladder_bit_set.argtypes = [C.c_char_p, cint]
+        L.slicer_bound.restype = cint
+        L.slicer_bound.argtypes = [cint, i64, i64, dbl, cint, u32] + [C.POINTER(C.c_uint64)] * 3
         L.slicer_decode.restype = cint
         L.slicer_decode.argtypes = [vp, vp, vp, vp]
         L.slicer_decode_as.restype = cint
@@ -111,6 +117,32 @@ def slicer_encode(x: torch.Tensor, keep_ratio: float, n_blocks: int, bit_set: in
     _check("slicer_encode", load().slicer_encode(
         x.data_ptr(), _dt_of(x), rows, row_len, keep_ratio, n_blocks, bit_set, distortion_budget,
         stream_buf.data_ptr(), meta.data_ptr(), workspace.data_ptr(), _stream_handle(stream)))
+
+
+def slicer_ladder_bit_set(ladder) -> int:
+    """Set of the ladder's bitwidths (0 if an entry is outside 1..16)."""
+    lad = bytes(int(q) & 0xFF for q in ladder)
+    return load().slicer_ladder_bit_set(lad, len(lad))
+
+
+def slicer_encode_ladder(x: torch.Tensor, keep_ratio: float, ladder, stream_buf: torch.Tensor, meta: torch.Tensor,
+                         workspace: torch.Tensor, stream=None) -> None:
+    """Fixed multi-level mode: block m of each sign class uses ladder[m] bits (n_blocks = len(ladder))."""
+    if not x.is_cuda or not x.is_contiguous() or x.dim() != 2:
+        raise ValueError("x must be a contiguous 2-D tensor on the GPU")
+    rows, row_len = x.shape
+    lad = bytes(int(q) & 0xFF for q in ladder)
+    _check("slicer_encode_ladder", load().slicer_encode_ladder(
+        x.data_ptr(), _dt_of(x), rows, row_len, keep_ratio, len(lad), lad,
+        stream_buf.data_ptr(), meta.data_ptr(), workspace.data_ptr(), _stream_handle(stream)))
+
+
+def slicer_bound(dt: int, rows: int, row_len: int, keep_ratio: float, n_blocks: int, bit_set: int):
+    """(value_bits, index_bits, header_bits) of the payload's upper bound; host computation."""
+    v, i, h = C.c_uint64(0), C.c_uint64(0), C.c_uint64(0)
+    _check("slicer_bound", load().slicer_bound(dt, rows, row_len, keep_ratio, n_blocks, bit_set,
+                                               C.byref(v), C.byref(i), C.byref(h)))
+    return v.value, i.value, h.value
 
 
 def slicer_decode(stream_buf: torch.Tensor, meta: torch.Tensor, y: torch.Tensor, stream=None) -> None:

@@ -271,9 +271,9 @@ int slicer_encode_path(slicer_dtype dt, int64_t rows, int64_t row_len, double ke
     return p.small_epl ? 1 : (p.large_C ? 2 : 0);
 }
 
-int slicer_encode(const void* x, slicer_dtype dt, int64_t rows, int64_t row_len, double keep_ratio,
-                  int n_blocks, uint32_t bit_set, double distortion_budget, void* stream, void* meta,
-                  void* workspace, void* hip_stream)
+static int encode_impl(const void* x, slicer_dtype dt, int64_t rows, int64_t row_len, double keep_ratio,
+                       int n_blocks, uint32_t bit_set, double distortion_budget, const Ladder& lad,
+                       void* stream, void* meta, void* workspace, void* hip_stream)
 {
     int rc = check_args((int)dt, rows, row_len, keep_ratio, n_blocks, bit_set);
     if (rc) return rc;
@@ -302,6 +302,7 @@ int slicer_encode(const void* x, slicer_dtype dt, int64_t rows, int64_t row_len,
     ea.mv = meta_view(meta, rows, n_blocks);
     ea.only_flagged = nullptr;
     ea.rows_per_wg = 1;
+    ea.lad = lad;
 
     if (p.small_epl && ((uintptr_t)x & 15) == 0) {
         // fast path; rows it cannot hold are flagged and redone by the generic kernel
@@ -315,6 +316,7 @@ int slicer_encode(const void* x, slicer_dtype dt, int64_t rows, int64_t row_len,
         sa.fallback = (u32*)(ws + p.off_fallback);
         sa.mv = ea.mv;
         sa.cap = p.small_cap; sa.region0_words = p.small_region0;
+        sa.lad = lad;
         const bool timed = g_ev_start && g_ev_stop;
         if (timed) SLICER_HIP(hipEventRecord(g_ev_start, st));
         rc = dt == SLICER_F32 ? launch_small<0>(sa, p, st) : launch_small<1>(sa, p, st);
@@ -342,6 +344,7 @@ int slicer_encode(const void* x, slicer_dtype dt, int64_t rows, int64_t row_len,
         la.row_words = ea.row_words; la.slots = ea.slots;
         la.fallback = (u32*)(ws + p.off_fallback);
         la.mv = ea.mv;
+        la.lad = lad;
         const bool timed = g_ev_start && g_ev_stop;
         if (timed) SLICER_HIP(hipEventRecord(g_ev_start, st));
         rc = dt == SLICER_F32 ? launch_large<0>(la, p, st) : launch_large<1>(la, p, st);
@@ -382,6 +385,59 @@ int slicer_encode(const void* x, slicer_dtype dt, int64_t rows, int64_t row_len,
     hipLaunchKernelGGL(enc_gather_kernel, dim3((unsigned)grid), dim3(256), 0, st, fa);
     e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e);
+    return SLICER_OK;
+}
+
+int slicer_encode(const void* x, slicer_dtype dt, int64_t rows, int64_t row_len, double keep_ratio,
+                  int n_blocks, uint32_t bit_set, double distortion_budget, void* stream, void* meta,
+                  void* workspace, void* hip_stream)
+{
+    Ladder none;
+    none.on = 0;
+    for (int j = 0; j < kMaxBlocks / 8; ++j) none.nib[j] = 0;
+    return encode_impl(x, dt, rows, row_len, keep_ratio, n_blocks, bit_set, distortion_budget, none,
+                       stream, meta, workspace, hip_stream);
+}
+
+uint32_t slicer_ladder_bit_set(const uint8_t* ladder, int n_blocks)
+{
+    if (!ladder || n_blocks < 1 || n_blocks > kMaxBlocks) return 0;
+    uint32_t bs = 0;
+    for (int m = 0; m < n_blocks; ++m) {
+        if (ladder[m] < 1 || ladder[m] > 16) return 0;
+        bs |= 1u << ladder[m];
+    }
+    return bs;
+}
+
+int slicer_encode_ladder(const void* x, slicer_dtype dt, int64_t rows, int64_t row_len, double keep_ratio,
+                         int n_blocks, const uint8_t* ladder, void* stream, void* meta, void* workspace,
+                         void* hip_stream)
+{
+    const uint32_t bit_set = slicer_ladder_bit_set(ladder, n_blocks);
+    if (!bit_set) return SLICER_EINVAL;
+    Ladder lad;
+    lad.on = 1;
+    for (int j = 0; j < kMaxBlocks / 8; ++j) lad.nib[j] = 0;
+    for (int m = 0; m < n_blocks; ++m) {
+        uint32_t t = 0;                                  // position of ladder[m] among the set's bitwidths, ascending
+        for (int q = 1; q < ladder[m]; ++q) t += (bit_set >> q) & 1u;
+        lad.nib[m >> 3] |= t << ((m & 7) * 4);
+    }
+    return encode_impl(x, dt, rows, row_len, keep_ratio, n_blocks, bit_set, 0.0, lad, stream, meta, workspace,
+                       hip_stream);
+}
+
+int slicer_bound(slicer_dtype dt, int64_t rows, int64_t row_len, double keep_ratio, int n_blocks,
+                 uint32_t bit_set, uint64_t* value_bits, uint64_t* index_bits_out, uint64_t* header_bits)
+{
+    int rc = check_args((int)dt, rows, row_len, keep_ratio, n_blocks, bit_set);
+    if (rc) return rc;
+    const Plan p = make_plan((int)dt, rows, row_len, keep_ratio, n_blocks, bit_set);
+    const u64 R = (u64)rows, k = (u64)p.k;
+    if (value_bits) *value_bits = R * k * (u64)p.qmax;
+    if (index_bits_out) *index_bits_out = R * k * (u64)p.w;
+    if (header_bits) *header_bits = 8ull * (u64)meta_bytes(rows, n_blocks) + R * (32ull * p.cap_words - k * (u64)(p.w + p.qmax));
     return SLICER_OK;
 }
 

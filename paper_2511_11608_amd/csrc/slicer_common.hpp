@@ -47,6 +47,21 @@ __host__ __device__ inline MetaView meta_view(void* meta, int64_t R, int M)
     return v;
 }
 
+// ---- fixed multi-level mode (Sec. 4.1: Q = [q_1 > ... > q_M]) --------------------------------
+// Block m of either sign class takes the bitwidth qlist[index(m)]; four bits per block.
+struct Ladder {
+    int on;
+    u32 nib[kMaxBlocks / 8];
+};
+
+__host__ __device__ inline u32 ladder_index(const Ladder& l, int m)
+{
+    u32 wsel = l.nib[0];
+#pragma unroll
+    for (int j = 1; j < kMaxBlocks / 8; ++j) wsel = (m >> 3) == j ? l.nib[j] : wsel;   // no indexed access to kernel arguments
+    return (wsel >> ((m & 7) * 4)) & 15u;
+}
+
 // ---- element types ---------------------------------------------------------
 // Magnitude key: the bit pattern with the sign cleared orders finite values by
 // |x| (ATKF, Sec. 3.1).  bf16 keys are kept as 15-bit integers.

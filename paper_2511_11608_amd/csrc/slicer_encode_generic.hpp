@@ -31,6 +31,7 @@ struct EncArgs {
     u32* bo_val;            // [R][k]   block-ordered |x| (fp32 bits)
     const u32* only_flagged;// if set: rows with a zero flag are skipped (already encoded)
     int64_t rows_per_wg;    // consecutive rows a workgroup walks (1 unless only_flagged is set)
+    Ladder lad;             // fixed multi-level mode: no search, block m uses qlist[index(m)]
     // meta
     MetaView mv;
 };
@@ -442,6 +443,10 @@ __device__ inline void enc_generic_rows(const EncArgs& a, const int64_t r_begin,
                 if (chosen < 0) { chosen = a.nq - 1; flag = 0x80u; }
                 tsel = chosen; q = a.qlist[chosen];
             }
+        }
+        if (a.lad.on) {             // the bitwidth is given, also for empty and degenerate blocks
+            tsel = (int)ladder_index(a.lad, b % M);
+            q = a.qlist[tsel]; flag = 0;
         }
         qsel[b] = q;
         inv_sel[b] = cnt ? inv_tab[b][tsel] : 0.f;

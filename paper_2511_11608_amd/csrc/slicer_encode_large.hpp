@@ -63,6 +63,7 @@ struct LargeArgs {
     u32* slots;
     u32* fallback;
     MetaView mv;
+    Ladder lad;             // fixed multi-level mode
 };
 
 template <int DT>
@@ -633,6 +634,11 @@ __global__ __launch_bounds__(128) void lr_choose_kernel(LargeArgs a)
                     if (lhs <= rhs) flag = 0;
                 }
             }
+        }
+        if (a.lad.on) {             // the bitwidth is given, also for empty and degenerate blocks
+            q = a.qlist[ladder_index(a.lad, b % a.M)];
+            flag = 0; inv = 0.f;
+            if (cnt && vmax - vmin >= 0x1p-100f) inv = (float)((1u << q) - 1u) / (vmax - vmin);
         }
         a.qsel[r * B2 + b] = (u32)q;
         a.inv_sel[r * B2 + b] = inv;

@@ -46,6 +46,7 @@ struct SmallArgs {
     MetaView mv;
     int cap;            // list capacity, multiple of 64, < 2048
     int region0_words;  // fine histogram, later block-ordered indices + stream image
+    Ladder lad;         // fixed multi-level mode: no sums, no search
 };
 
 constexpr int kCoarseBits = 11;
@@ -716,12 +717,16 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
         }
         if (accE) atomicAdd(&sums[myb * (nq + 1) + nq], accE);
     };
-    if (small_q) abq_sums(std::true_type()); else abq_sums(std::false_type());
+    if (!a.lad.on) {
+        if (small_q) abq_sums(std::true_type()); else abq_sums(std::false_type());
+    }
     wave_sync();
 
     // smallest feasible bitwidth per block: the lanes of a block test different candidates in
     // ascending order and keep the minimum
-    if (lane_on && mycnt && !dg) {
+    if (a.lad.on) {
+        if (lane_on && sub == 0) L.run[myb] = ladder_index(a.lad, (int)(myb >= (u32)M ? myb - (u32)M : myb));
+    } else if (lane_on && mycnt && !dg) {
         const double rhs = a.beta * ldexp((double)sums[myb * (nq + 1) + nq], 2 * e - 40);
         for (u32 t = sub; t < (u32)nq; t += lpb) {
             const float Lq = (float)((1u << L.qtab[t]) - 1u);

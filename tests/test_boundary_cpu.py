@@ -27,7 +27,8 @@ def declared_symbols():
 def test_exports_every_declared_symbol(lib):
     names = declared_symbols()
     assert {"slicer_sizes", "slicer_encode", "slicer_decode", "slicer_decode_as", "slicer_stream_words",
-            "slicer_encode_path", "slicer_profile_events", "slicer_last_hip_error", "slicer_strerror"} <= set(names)
+            "slicer_encode_path", "slicer_profile_events", "slicer_last_hip_error", "slicer_strerror",
+            "slicer_encode_ladder", "slicer_ladder_bit_set", "slicer_bound"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
@@ -71,3 +72,28 @@ def test_encode_path_by_shape(lib):
     assert binding.slicer_encode_path(binding.SLICER_F32, 32, 401408, 0.20, 16, B) == 2      # ResNet stage 3
     assert binding.slicer_encode_path(binding.SLICER_F32, 1, 200704, 0.10, 4, B) == 2        # CNN map
     assert binding.slicer_encode_path(binding.SLICER_F32, 3, 4097, 0.5, 3, B) == 0           # odd length
+
+
+def test_bound_matches_the_oracle_and_the_buffer_sizes(lib, oracle):
+    """slicer_bound is host arithmetic: it must agree with the oracle's statement of Sec. 3.3 and
+    with the worst-case buffer sizes, on the five workload shapes and a few odd ones."""
+    from paper_2511_11608_amd import binding, synth
+    B = synth.BITS_2_TO_8
+    cases = [("f32", 1, 200704, 0.1, 4, B), ("f32", 32, 401408, 0.2, 16, B), ("f32", 12608, 768, 0.15, 8, B),
+             ("bf16", 16384, 4096, 0.1, 8, B), ("bf16", 256, 8192, 0.1, 8, B), ("f32", 3, 1, 1.0, 1, 2),
+             ("bf16", 7, 1000, 0.0, 64, 1 << 16), ("f32", 5, 4097, 0.37, 3, 0x1FFFE)]
+    for dtype, R, N, keep, M, bits in cases:
+        dt = binding.SLICER_F32 if dtype == "f32" else binding.SLICER_BF16
+        got = binding.slicer_bound(dt, R, N, keep, M, bits)
+        assert got == oracle.bound(dtype, R, N, keep, M, bits)
+        cap, mb, _ = binding.slicer_sizes(dt, R, N, keep, M, bits)
+        assert sum(got) == 8 * (cap + mb)
+    with pytest.raises(binding.SlicerError):
+        binding.slicer_bound(binding.SLICER_F32, 1, 16, 1.5, 2, B)
+
+
+def test_ladder_bit_set(lib):
+    from paper_2511_11608_amd import binding
+    assert binding.slicer_ladder_bit_set([8, 6, 4, 2]) == (1 << 8) | (1 << 6) | (1 << 4) | (1 << 2)
+    assert binding.slicer_ladder_bit_set([3, 3, 3]) == 1 << 3
+    assert binding.slicer_ladder_bit_set([0, 3]) == 0 and binding.slicer_ladder_bit_set([17]) == 0

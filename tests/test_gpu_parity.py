@@ -118,6 +118,37 @@ def test_row_resident_variants(oracle, dtype, N):
         check(oracle, x, dtype, keep, M, bits, budget)
 
 
+def check_ladder(oracle, x, dtype, keep, ladder):
+    from tests.gpu_util import gpu_encode_ladder, gpu_decode
+    s_ref, m_ref = oracle.encode_ladder(x, dtype, keep, ladder, n_threads=8)
+    y_ref = oracle.decode(s_ref, m_ref, n_threads=8)
+    sb, meta, words = gpu_encode_ladder(x, dtype, keep, ladder)
+    m_gpu = meta.cpu().numpy()
+    assert np.array_equal(m_ref[:64], m_gpu[:64]), (streamfmt.header(m_ref), streamfmt.header(m_gpu))
+    s_gpu = sb[:words].cpu().numpy().view(np.uint32)
+    ok = np.array_equal(m_ref, m_gpu) and np.array_equal(s_ref, s_gpu)
+    assert ok, explain_mismatch(s_ref, m_ref, s_gpu, m_gpu, x.shape[0])
+    y_gpu = gpu_decode(sb, meta, x.shape, dtype, len(ladder))
+    assert np.array_equal(y_ref.view(np.uint32 if dtype == "f32" else np.uint16),
+                          y_gpu.view(np.uint32 if dtype == "f32" else np.uint16))
+
+
+@pytest.mark.parametrize("name", ["cnn_map_ragged", "resnet_2rows", "vit", "llm", "ar_step"])
+def test_ladder_mode_workloads(oracle, name):
+    """Fixed multi-level mode (Sec. 4.1) on every kernel family: row-resident, long-row stages, generic."""
+    wl = CASES[name]()
+    for ladder in ([8, 6, 5, 4, 3, 3, 2, 2], [4], [16, 1], [2, 9, 2, 9, 5]):
+        check_ladder(oracle, wl.x, wl.dtype, wl.keep_ratio, ladder)
+
+
+@pytest.mark.parametrize("dtype,N", [("bf16", 4096), ("f32", 768), ("bf16", 1000), ("f32", 40000)])
+def test_ladder_mode_mixed_rows(oracle, dtype, N):
+    rng = np.random.default_rng(N + 1)
+    x = _mixed_rows(rng, 12, N, dtype)
+    for keep, ladder in ((0.1, [8, 7, 6, 5, 4, 3, 2, 2]), (1.0, [3, 2]), (0.3, list(range(16, 0, -1)) * 2), (0.0, [5])):
+        check_ladder(oracle, x, dtype, keep, ladder)
+
+
 def test_encode_is_deterministic():
     from tests.gpu_util import gpu_roundtrip
     wl = synth.llm_prefill(seed=3, rows=64)
