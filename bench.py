@@ -65,20 +65,26 @@ def make_workload(which: int):
     return wl, [wl.x]
 
 
-def cpu_baseline(wl, threads: int) -> dict:
+def cpu_baseline(wl, threads: int, ladder=None) -> dict:
     """The oracle as it stands (encode + decode) on a bounded sample of the rows."""
     from oracle import ref
     ref.lib()
+
+    def ref_encode(x, n_threads):
+        if ladder:
+            return ref.encode_ladder(x, wl.dtype, wl.keep_ratio, ladder, n_threads=n_threads)
+        return ref.encode(x, wl.dtype, wl.keep_ratio, wl.n_blocks, wl.bit_set, wl.budget, n_threads=n_threads)
+
     rows = wl.rows
     probe = max(1, min(rows, 64 if wl.row_len < 100_000 else 2))
     t0 = time.perf_counter()
-    s, m = ref.encode(wl.x[:probe], wl.dtype, wl.keep_ratio, wl.n_blocks, wl.bit_set, wl.budget, n_threads=threads)
+    s, m = ref_encode(wl.x[:probe], threads)
     ref.decode(s, m, n_threads=threads)
     per_row = (time.perf_counter() - t0) / probe * min(threads, probe)      # core-seconds per row
     take = int(max(probe, min(rows, 15.0 / max(per_row, 1e-9))))
     x = wl.x[:take]
     t0 = time.perf_counter()
-    s, m = ref.encode(x, wl.dtype, wl.keep_ratio, wl.n_blocks, wl.bit_set, wl.budget, n_threads=threads)
+    s, m = ref_encode(x, threads)
     t1 = time.perf_counter()
     ref.decode(s, m, n_threads=threads)
     t2 = time.perf_counter()
@@ -87,7 +93,7 @@ def cpu_baseline(wl, threads: int) -> dict:
     take1 = int(max(1, min(take, 4.0 / max(per_row, 1e-9))))
     x1 = wl.x[:take1]
     t3 = time.perf_counter()
-    s1, m1 = ref.encode(x1, wl.dtype, wl.keep_ratio, wl.n_blocks, wl.bit_set, wl.budget, n_threads=1)
+    s1, m1 = ref_encode(x1, 1)
     ref.decode(s1, m1, n_threads=1)
     t4 = time.perf_counter()
     return {"value": nbytes / (t2 - t0) / 1e9, "unit": "GB/s of input IF (encode+decode)",
@@ -114,6 +120,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", type=int, default=4, help="1..5 (default 4: LLM prefill, the headline config)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--ladder", type=str, default="",
+                    help="time the fixed multi-level mode instead of the bitwidth search: comma-separated "
+                         "bitwidths, one per block of a sign class, e.g. 8,7,6,5,4,3,2,2")
     ap.add_argument("--eager", action="store_true",
                     help="time plain launches instead of replaying a captured HIP graph of the steps")
     ap.add_argument("--copy-probe", action="store_true",
@@ -132,6 +141,18 @@ def main() -> int:
     binding.load()
     wl, xs = make_workload(args.workload)
     M, bits, keep, beta = wl.n_blocks, wl.bit_set, wl.keep_ratio, wl.budget
+    ladder = [int(q) for q in args.ladder.split(",")] if args.ladder else None
+    if ladder:
+        M, bits = len(ladder), binding.slicer_ladder_bit_set(ladder)
+        if not bits:
+            print("bench.py: --ladder entries must be 1..16", file=sys.stderr)
+            return 2
+
+    def encode(x, sb, meta, ws):
+        if ladder:
+            binding.slicer_encode_ladder(x, keep, ladder, sb, meta, ws)
+        else:
+            binding.slicer_encode(x, keep, M, bits, beta, sb, meta, ws)
     in_bytes = wl.nbytes
 
     # distinct input buffers: > 256 MB in flight so that reads come from HBM
@@ -157,7 +178,7 @@ def main() -> int:
         sb, meta, ws = bufs[i % n_out]
         if timed_idx is not None:
             binding.slicer_profile_events(*e_enc[timed_idx])
-        binding.slicer_encode(x, keep, M, bits, beta, sb, meta, ws)
+        encode(x, sb, meta, ws)
         if timed_idx is not None:
             binding.slicer_profile_events(*e_dec[timed_idx])
         binding.slicer_decode_as(sb, meta, ys[i % n_out], M)
@@ -246,12 +267,12 @@ def main() -> int:
         ev.hip.hipEventRecord(b, st)
         return ev.elapsed_ms(a, b) / K
 
-    enc_call_ms = timed_loop(lambda i: binding.slicer_encode(xd[i % n_buf], keep, M, bits, beta, *bufs[i % n_out]))
+    enc_call_ms = timed_loop(lambda i: encode(xd[i % n_buf], *bufs[i % n_out]))
     dec_call_ms = timed_loop(lambda i: binding.slicer_decode_as(bufs[i % n_out][0], bufs[i % n_out][1],
                                                                   ys[i % n_out], M))
 
     # compressed size of the last batch encoded into bufs[0]
-    binding.slicer_encode(xd[0], keep, M, bits, beta, *bufs[0])
+    encode(xd[0], *bufs[0])
     words = binding.slicer_stream_words(bufs[0][1])
     _, meta_bytes, _ = binding.slicer_sizes(binding.SLICER_F32 if wl.dtype == "f32" else binding.SLICER_BF16,
                                             wl.rows, wl.row_len, keep, M, bits)
@@ -290,7 +311,7 @@ def main() -> int:
         torch.cuda.synchronize()
 
     threads = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)))
-    cpu = None if args.no_cpu else cpu_baseline(wl, threads)
+    cpu = None if args.no_cpu else cpu_baseline(wl, threads, ladder)
 
     out = {
         "metric": "codec encode+decode throughput, GB/s of input IF",
@@ -299,7 +320,8 @@ def main() -> int:
         "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl.dtype, "data": "synthetic", "launch": launch,
-        "config": {"workload": f"{wl.name} [{wl.rows}x{wl.row_len}] keep={keep} M={M} bits=2..8 budget={beta}",
+        "config": {"workload": f"{wl.name} [{wl.rows}x{wl.row_len}] keep={keep} M={M} "
+                               + (f"ladder={ladder}" if ladder else f"bits=2..8 budget={beta}"),
                    "input_bytes": in_bytes, "distinct_input_buffers": n_buf},
         "encode": {"GBps": in_bytes / (enc_call_ms * 1e-3) / 1e9, "ms": enc_call_ms,
                    "elements_per_s": n_el / (enc_call_ms * 1e-3),
