@@ -144,7 +144,7 @@ Plan make_plan(int dt, int64_t rows, int64_t row_len, double keep_ratio, int n_b
 template <int DT, int EPL>
 void launch_small_epl(const SmallArgs& sa, int lds_bytes, int maxs, hipStream_t st)
 {
-    const dim3 g((unsigned)sa.R), b(kWave);
+    const dim3 g((unsigned)xcd_grid(sa.R)), b(kWave);
     const size_t lds = (size_t)lds_bytes;
     // the paper's bitwidth ladders are short; 7 = {2..8} is the benchmarked one
     if (sa.nq == 7) {
@@ -232,9 +232,9 @@ int launch_decode(const void* stream, const void* meta, void* y, int dt, int64_t
         // one wave per workgroup: the LDS of a row (image + stream segment) is the unit of occupancy
         const size_t lds = (size_t)row_bytes + 16 * (size_t)((da.stage_words + 4) / 4);
         if (dt == SLICER_F32)
-            hipLaunchKernelGGL((dec_small_kernel<0>), dim3((unsigned)rows), dim3(kWave), lds, st, da);
+            hipLaunchKernelGGL((dec_small_kernel<0>), dim3((unsigned)xcd_grid(rows)), dim3(kWave), lds, st, da);
         else
-            hipLaunchKernelGGL((dec_small_kernel<1>), dim3((unsigned)rows), dim3(kWave), lds, st, da);
+            hipLaunchKernelGGL((dec_small_kernel<1>), dim3((unsigned)xcd_grid(rows)), dim3(kWave), lds, st, da);
     } else if (dt == SLICER_F32)
         hipLaunchKernelGGL((dec_kernel<0, 256>), dim3((unsigned)grid), dim3(256), 0, st, da);
     else
@@ -371,7 +371,7 @@ static int encode_impl(const void* x, slicer_dtype dt, int64_t rows, int64_t row
     fa.stream = (u32*)stream;
     fa.meta = meta;
     fa.mv = ea.mv;
-    const u64 grid = ((u64)rows * (u64)fa.chunks_per_row + 3) / 4;     // four wavefronts per workgroup
+    const u64 grid = (u64)xcd_grid((int64_t)(((u64)rows * (u64)fa.chunks_per_row + 3) / 4));     // four wavefronts per workgroup
     if (grid >= (1ull << 31)) return SLICER_EINVAL;
     const dim3 gscan((unsigned)((rows + kScanRows - 1) / kScanRows));
     if (!ea.only_flagged)

@@ -218,6 +218,21 @@ __device__ inline u32 udiv16(u32 x, u32 d)
     return (u32)(((float)x + 0.5f) * rd);
 }
 
+// ---- workgroup -> row mapping that keeps neighbouring rows on one XCD ---------------------------
+// Workgroups are handed to the 8 XCDs round-robin, and every XCD has its own L2.  Rows that
+// are neighbours in memory share cache lines (meta arrays, the ends of stream segments), so
+// workgroup i takes row (i % 8) * ceil(R / 8) + i / 8: each XCD walks one contiguous eighth of
+// the rows.  Launch 8 * ceil(R / 8) workgroups; the result is >= R for the few surplus ones.
+constexpr int kXcds = 8;
+
+__host__ __device__ inline int64_t xcd_grid(int64_t R) { return kXcds * ((R + kXcds - 1) / kXcds); }
+
+__device__ inline int64_t xcd_row(int64_t i, int64_t R)
+{
+    const int64_t chunk = (R + kXcds - 1) / kXcds;
+    return (i % kXcds) * chunk + i / kXcds;
+}
+
 // ---- bit fields in a word stream (LSB first) -------------------------------------
 
 __device__ inline u32 read_bits(const u32* __restrict__ words, u64 bitpos, int nbits)

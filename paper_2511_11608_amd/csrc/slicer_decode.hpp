@@ -150,7 +150,7 @@ __global__ __launch_bounds__(256) void dec_small_kernel(DecArgs a)
     extern __shared__ uint4 dec_smem[];
     const u32 lane = lane_id();
     const int wid = threadIdx.x / kWave;
-    const int64_t r = (int64_t)blockIdx.x * (int64_t)(blockDim.x / kWave) + wid;
+    const int64_t r = xcd_row((int64_t)blockIdx.x, a.R);       // one wave per workgroup
     if (r >= a.R) return;
     const int N = (int)a.N, M = a.M, B2 = 2 * a.M, w = a.w;
     const int row_bytes = N * ESZ;                       // multiple of 16

@@ -605,7 +605,9 @@ __global__ __launch_bounds__(256) void enc_gather_kernel(FinishArgs a)
 {
     // one wavefront per (row, kGatherWords-word chunk of its slot); no workgroup barrier
     const u32 lane = lane_id();
-    const int64_t item = (int64_t)blockIdx.x * (256 / kWave) + threadIdx.x / kWave;
+    const int64_t n_items = a.R * a.chunks_per_row;
+    const int64_t wg = xcd_row((int64_t)blockIdx.x, (n_items + 3) / 4);   // neighbouring rows stay on one XCD
+    const int64_t item = wg * (256 / kWave) + threadIdx.x / kWave;
     const int64_t r = item / a.chunks_per_row;
     const u64 c = (u64)(item % a.chunks_per_row);
     if (r >= a.R) return;

@@ -170,7 +170,8 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
 #ifdef SLICER_PHASE_TIMING
     long long t_prev_ = clock64();
 #endif
-    const int64_t r = blockIdx.x;
+    const int64_t r = xcd_row((int64_t)blockIdx.x, a.R);        // neighbouring rows stay on one XCD
+    if (r >= a.R) return;
     const int N = (int)a.N, M = a.M, w = a.w, B2 = 2 * a.M, nq = NQ ? NQ : a.nq, cap = a.cap;
     const int k = (int)a.k;
     const u32 idxmask = (1u << w) - 1u;
