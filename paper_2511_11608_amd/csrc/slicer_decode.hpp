@@ -115,7 +115,7 @@ __global__ __launch_bounds__(BLOCK) void dec_kernel(DecArgs a)
     const size_t g0 = (size_t)r * (size_t)a.N + (size_t)c0;
     if (DT == 0) {
         u32* __restrict__ out = (u32*)a.y + g0;
-        for (int i = tid; i < len; i += BLOCK) out[i] = (u32)tile[i];
+        for (int i = tid; i < len; i += BLOCK) __builtin_nontemporal_store((u32)tile[i], out + i);
     } else {
         uint16_t* __restrict__ out = (uint16_t*)a.y + g0;
         const int head = (int)(g0 & 1);
@@ -123,7 +123,7 @@ __global__ __launch_bounds__(BLOCK) void dec_kernel(DecArgs a)
         const int npair = (len - head) >> 1;
         u32* __restrict__ out2 = (u32*)(out + head);
         for (int t = tid; t < npair; t += BLOCK)
-            out2[t] = (u32)tile[head + 2 * t] | ((u32)tile[head + 2 * t + 1] << 16);
+            __builtin_nontemporal_store((u32)tile[head + 2 * t] | ((u32)tile[head + 2 * t + 1] << 16), out2 + t);
         if (((len - head) & 1) && tid == 0) out[len - 1] = (uint16_t)tile[len - 1];
     }
 }
@@ -212,7 +212,15 @@ __global__ __launch_bounds__(256) void dec_small_kernel(DecArgs a)
     wave_sync();
 
     uint4* __restrict__ out = (uint4*)((char*)a.y + (size_t)r * (size_t)row_bytes);
-    for (int i = lane; i < row_bytes / 16; i += kWave) out[i] = tile4[i];
+    // the output is written once and not read back by this library: streaming (non-temporal) stores
+    for (int i = lane; i < row_bytes / 16; i += kWave) {
+        const uint4 t = tile4[i];
+        u32* o = (u32*)(out + i);
+        __builtin_nontemporal_store(t.x, o);
+        __builtin_nontemporal_store(t.y, o + 1);
+        __builtin_nontemporal_store(t.z, o + 2);
+        __builtin_nontemporal_store(t.w, o + 3);
+    }
 }
 
 }  // namespace slicer
