@@ -103,6 +103,21 @@ def cpu_baseline(wl, threads: int, ladder=None) -> dict:
             "single_thread_GBps": x1.nbytes / (t4 - t3) / 1e9, "single_thread_rows": take1}
 
 
+VALU_PEAK_TLOPS = 256 * 4 * 16 * 2.4e9 / 1e12    # lane-operations/s: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz, one plain op per lane and cycle
+
+
+def alu_view(workload: str, kernel: str, kernel_ms: float):
+    """How close the kernel runs to the vector-ALU issue rate: VALU wave-instructions per launch (a committed
+    rocprofv3 --pmc SQ_INSTS_VALU count, 64 lane-operations each) over the duration measured in this run."""
+    try:
+        n = json.load(open(os.path.join(ROOT, "profiles", "valu_counts.json")))[workload][kernel]
+    except Exception:
+        return None
+    achieved = n * 64 / (kernel_ms * 1e-3) / 1e12
+    return {"bound": "alu", "achieved": achieved, "peak": VALU_PEAK_TLOPS, "unit": "T lane-op/s",
+            "frac": achieved / VALU_PEAK_TLOPS, "valu_wave_instructions_per_launch": n}
+
+
 def load_traffic(workload: str, kernel: str):
     """HBM bytes per launch from committed rocprofv3 --pmc summaries, if present."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
@@ -300,6 +315,7 @@ def main() -> int:
     roofline = {"bound": "hbm", "kernel": enc_kernel, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": achieved / HBM_PEAK_GBS, "traffic": load_traffic(wl.name, enc_kernel),
                 "algorithmic_bytes_per_launch": enc_alg_bytes, "kernel_ms": enc_ms,
+                "alu": None if ladder else alu_view(wl.name, enc_kernel, enc_ms),
                 "decode_kernel": {"kernel": dec_kernel, "kernel_ms": dec_ms,
                                   "achieved": dec_alg_bytes / (dec_ms * 1e-3) / 1e9,
                                   "frac": dec_alg_bytes / (dec_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
