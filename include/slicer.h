@@ -149,6 +149,23 @@ int slicer_bound(slicer_dtype dt, int64_t rows, int64_t row_len, double keep_rat
 int slicer_encode_path(slicer_dtype dt, int64_t rows, int64_t row_len, double keep_ratio,
                        int n_blocks, uint32_t bit_set);
 
+/*
+ * The decode calls TRUST stream and meta: they must be the bytes an encode call produced
+ * (the kernels guard only the scatter index, so a forged meta can make them read outside the
+ * stream).  A receiver of bytes from elsewhere calls slicer_check first: it verifies, on the
+ * GPU and without touching the stream, that the header matches (dt, rows, row_len, n_blocks),
+ * that every row's counts are possible (n_pos + n_neg <= k <= row_len), every bitwidth is in
+ * 1..16 and in the header's bit_set, every row's offset is the exclusive scan of the exact word
+ * counts implied by counts and bitwidths, and that total_words <= stream_words, the number of
+ * 32-bit words the caller actually holds.  After SLICER_OK, slicer_decode / slicer_decode_as
+ * with the same arguments stay inside stream[0, stream_words) and y.
+ *   scratch   device memory, at least 4 bytes, 4-byte aligned (overwritten)
+ * Waits for `hip_stream`.  SLICER_EFORMAT for any inconsistency, SLICER_EINVAL for bad
+ * arguments.
+ */
+int slicer_check(const void* meta, uint64_t stream_words, slicer_dtype dt, int64_t rows,
+                 int64_t row_len, int n_blocks, void* scratch, void* hip_stream);
+
 /* Reads meta.total_words (the packed size of Sec. 3.3's payload, in 32-bit words)
  * to the host.  Waits for `hip_stream`. */
 int slicer_stream_words(const void* meta, uint64_t* words, void* hip_stream);

@@ -54,6 +54,8 @@ def load() -> C.CDLL:
         L.slicer_decode.argtypes = [vp, vp, vp, vp]
         L.slicer_decode_as.restype = cint
         L.slicer_decode_as.argtypes = [vp, vp, vp, cint, i64, i64, cint, vp]
+        L.slicer_check.restype = cint
+        L.slicer_check.argtypes = [vp, C.c_uint64, cint, i64, i64, cint, vp, vp]
         L.slicer_stream_words.restype = cint
         L.slicer_stream_words.argtypes = [vp, C.POINTER(C.c_uint64), vp]
         L.slicer_profile_events.restype = cint
@@ -143,6 +145,14 @@ def slicer_bound(dt: int, rows: int, row_len: int, keep_ratio: float, n_blocks: 
     _check("slicer_bound", load().slicer_bound(dt, rows, row_len, keep_ratio, n_blocks, bit_set,
                                                C.byref(v), C.byref(i), C.byref(h)))
     return v.value, i.value, h.value
+
+
+def slicer_check(meta: torch.Tensor, stream_words: int, y_like: torch.Tensor, n_blocks: int, stream=None) -> None:
+    """Validate a received meta buffer against the shape of y_like and the words held; raises SlicerError (-4)."""
+    rows, row_len = y_like.shape
+    scratch = torch.empty(64, dtype=torch.int32, device=meta.device)
+    _check("slicer_check", load().slicer_check(meta.data_ptr(), stream_words, _dt_of(y_like), rows, row_len, n_blocks,
+                                              scratch.data_ptr(), _stream_handle(stream)))
 
 
 def slicer_decode(stream_buf: torch.Tensor, meta: torch.Tensor, y: torch.Tensor, stream=None) -> None:

@@ -484,6 +484,27 @@ int slicer_stream_words(const void* meta, uint64_t* words, void* hip_stream)
     return SLICER_OK;
 }
 
+int slicer_check(const void* meta, uint64_t stream_words, slicer_dtype dt, int64_t rows, int64_t row_len,
+                 int n_blocks, void* scratch, void* hip_stream)
+{
+    int rc = check_shape((int)dt, rows, row_len, n_blocks);
+    if (rc) return rc;
+    if (!meta || !scratch) return SLICER_EINVAL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    CheckArgs ca;
+    ca.meta = meta; ca.R = rows; ca.N = row_len; ca.M = n_blocks; ca.w = index_bits(row_len); ca.dt = (int)dt;
+    ca.avail_words = stream_words;
+    ca.flag = (u32*)scratch;
+    hipLaunchKernelGGL(meta_flag_clear_kernel, dim3(1), dim3(64), 0, st, ca.flag);
+    hipLaunchKernelGGL(meta_check_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, st, ca);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e);
+    u32 flag = 0;
+    SLICER_HIP(hipMemcpyAsync(&flag, scratch, 4, hipMemcpyDeviceToHost, st));
+    SLICER_HIP(hipStreamSynchronize(st));
+    return flag ? SLICER_EFORMAT : SLICER_OK;
+}
+
 int slicer_profile_events(void* start_event, void* stop_event)
 {
     if ((start_event == nullptr) != (stop_event == nullptr)) return SLICER_EINVAL;

@@ -128,6 +128,55 @@ __global__ __launch_bounds__(BLOCK) void dec_kernel(DecArgs a)
     }
 }
 
+// ---- consistency of a (stream, meta) pair that did not come from this process --------------
+// One thread per row: the row's counts, bitwidths and segment must be what an encoder
+// produces (offsets are the exclusive scan of the exact word counts), and the whole stream
+// must fit the words the caller holds.  Any violation sets a bit of *flag; nothing is decoded.
+struct CheckArgs {
+    const void* meta;
+    int64_t R, N;
+    int M, w, dt;
+    u64 avail_words;
+    u32* flag;          // device word, zeroed by the same launch sequence
+};
+
+__global__ __launch_bounds__(64) void meta_flag_clear_kernel(u32* flag) { if (threadIdx.x == 0) *flag = 0u; }
+
+__global__ __launch_bounds__(256) void meta_check_kernel(CheckArgs a)
+{
+    const int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const u32* h32 = (const u32*)a.meta;
+    const u64* h64 = (const u64*)a.meta;
+    const MetaView mv = meta_view(const_cast<void*>(a.meta), a.R, a.M);
+    u32 bad = 0;
+    const u64 total = h64[6];
+    if (r == 0) {
+        if (h32[0] != kMagic || h32[1] != kVersion) bad |= 1u;
+        if (h32[2] != (u32)a.dt || h32[3] != (u32)a.M || h64[2] != (u64)a.R || h64[3] != (u64)a.N || h32[11] != (u32)a.w) bad |= 2u;
+        if (h64[4] > (u64)a.N || (h32[10] & ~0x1FFFEu) || h32[10] == 0u) bad |= 2u;
+        if (total > a.avail_words || mv.row_off[0] != 0ull) bad |= 4u;
+    }
+    if (r < a.R) {
+        const u64 n_pos = mv.n_pos[r], n_neg = mv.n_neg[r];
+        if (n_pos + n_neg > h64[4] || n_pos + n_neg > (u64)a.N) {
+            bad |= 8u;
+        } else {
+            u64 bits = (n_pos + n_neg) * (u64)a.w;
+            for (int b = 0; b < 2 * a.M; ++b) {
+                const u32 q = mv.q[(size_t)r * 2 * a.M + b] & 0x7Fu;
+                if (q < 1u || q > 16u || !((h32[10] >> q) & 1u)) bad |= 16u;
+                const u64 nc = b < a.M ? n_pos : n_neg, K = nc / (u64)a.M;
+                const u64 cnt = (b % a.M) < a.M - 1 ? K : nc - K * (u64)(a.M - 1);
+                bits += cnt * q;
+            }
+            const u64 off0 = mv.row_off[r];
+            const u64 off1 = r + 1 < a.R ? mv.row_off[r + 1] : total;
+            if (off1 < off0 || off1 - off0 != (bits + 31) >> 5 || off1 > total) bad |= 32u;
+        }
+    }
+    if (bad) atomicOr(a.flag, bad);
+}
+
 // ---- short rows: one wavefront per row, no workgroup barrier ---------------------------
 // Lane b * lpb + sub (lpb = 64 / 2M lanes per block) decodes entries sub, sub + lpb, ... of
 // block b, so neighbouring lanes read neighbouring bit fields; block offsets come from one

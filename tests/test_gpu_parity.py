@@ -170,3 +170,44 @@ def test_error_codes():
     with pytest.raises(binding.SlicerError) as ei:
         binding.slicer_decode(sb, meta, x)
     assert ei.value.code == -4
+
+
+def test_check_accepts_encoder_output_and_rejects_forged_meta(oracle):
+    """slicer_check on what the encoder wrote (GPU and oracle bytes alike) and on single-field
+    forgeries of it.  Forged buffers only go to the checker, never to a decode call."""
+    import torch
+    from paper_2511_11608_amd import binding
+    from tests.gpu_util import gpu_encode
+    wl = synth.llm_prefill(seed=7, rows=40)
+    sb, meta, words = gpu_encode(wl.x, wl.dtype, wl.keep_ratio, wl.n_blocks, wl.bit_set, wl.budget)
+    y = torch.empty(wl.x.shape, dtype=torch.bfloat16, device="cuda")
+    M, R = wl.n_blocks, wl.rows
+    binding.slicer_check(meta, words, y, M)
+    s_ref, m_ref = oracle.encode(wl.x, wl.dtype, wl.keep_ratio, M, wl.bit_set, wl.budget)
+    binding.slicer_check(torch.from_numpy(m_ref).cuda(), int(s_ref.size), y, M)
+
+    good = meta.cpu().numpy().copy()
+    a = streamfmt.arrays(good)
+    o_npos, o_q = 64 + 8 * R, 64 + 16 * R + 16 * R * M
+
+    def forged(edit):
+        m = good.copy()
+        edit(m)
+        return torch.from_numpy(m).cuda()
+
+    def expect_reject(m, w=words, shape_like=y, blocks=M):
+        with pytest.raises(binding.SlicerError) as ei:
+            binding.slicer_check(m, w, shape_like, blocks)
+        assert ei.value.code == -4
+
+    expect_reject(meta, words - 1)                                                  # fewer words than the header claims
+    expect_reject(forged(lambda m: m.__setitem__(0, m[0] ^ 1)))                     # magic
+    expect_reject(forged(lambda m: m[48:56].view(np.uint64).__setitem__(0, words + 5)))   # total_words
+    expect_reject(forged(lambda m: m[64 + 8 * 3: 64 + 8 * 4].view(np.uint64).__setitem__(0, 1 << 40)))   # a row offset
+    expect_reject(forged(lambda m: m[o_npos + 4 * 5: o_npos + 4 * 6].view(np.uint32).__setitem__(0, 4000)))   # n_pos > k
+    expect_reject(forged(lambda m: m[o_npos + 4 * 5: o_npos + 4 * 6].view(np.uint32).__setitem__(0, int(a["n_pos"][5]) + 1)))
+    expect_reject(forged(lambda m: m.__setitem__(o_q + 7, 0)))                      # bitwidth 0
+    expect_reject(forged(lambda m: m.__setitem__(o_q + 7, 9)))                      # bitwidth outside the header's set
+    expect_reject(forged(lambda m: m.__setitem__(o_q + 7, int(good[o_q + 7]) ^ 1 if (int(good[o_q + 7]) ^ 1) in range(2, 9) else 8 if good[o_q + 7] != 8 else 7)))
+    expect_reject(meta, words, torch.empty((R, 2048), dtype=torch.bfloat16, device="cuda"))          # other row length
+    expect_reject(meta, words, y, M + 1)
