@@ -28,6 +28,8 @@ def lib() -> C.CDLL:
         L.slicer_ref_encode_ladder.restype = C.c_int
         L.slicer_ref_encode_ladder.argtypes = [C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_double, C.c_int,
                                                C.c_void_p, C.c_void_p, C.c_void_p, C.c_int]
+        L.slicer_ref_encode_ds.restype = C.c_int
+        L.slicer_ref_encode_ds.argtypes = L.slicer_ref_encode.argtypes
         L.slicer_ref_bound.restype = C.c_int
         L.slicer_ref_bound.argtypes = [C.c_int, C.c_int64, C.c_int64, C.c_double, C.c_int, C.c_uint32,
                                        C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)]
@@ -69,6 +71,22 @@ def encode(x: np.ndarray, dtype: str, keep_ratio: float, n_blocks: int, bit_set:
                                  budget, stream.ctypes.data, meta.ctypes.data, n_threads)
     if rc:
         raise ValueError(f"slicer_ref_encode: error {rc}")
+    total = int(meta[48:56].view(np.uint64)[0])
+    return stream[:total].copy(), meta
+
+
+def encode_ds(x: np.ndarray, dtype: str, keep_ratio: float, n_blocks: int, bit_set: int, delta: float,
+              n_threads: int = 1):
+    """The paper's DS guard with greedy descent from max(bit_set).  Returns (stream, meta)."""
+    x = _check_x(x, dtype)
+    rows, row_len = x.shape
+    cap, mb = sizes(dtype, rows, row_len, keep_ratio, n_blocks, bit_set)
+    stream = np.zeros(max(cap // 4, 1), np.uint32)
+    meta = np.zeros(mb, np.uint8)
+    rc = lib().slicer_ref_encode_ds(x.ctypes.data, _DT[dtype], rows, row_len, keep_ratio, n_blocks, bit_set,
+                                    delta, stream.ctypes.data, meta.ctypes.data, n_threads)
+    if rc:
+        raise ValueError(f"slicer_ref_encode_ds: error {rc}")
     total = int(meta[48:56].view(np.uint64)[0])
     return stream[:total].copy(), meta
 

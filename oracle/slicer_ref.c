@@ -45,6 +45,14 @@
  * magnitudes gets q_1); there is no search and no distortion guard, everything else
  * (ATKF, MS, AIQ, packing) is as above.  The header's bit_set is the set of ladder values.
  *
+ * Paper-literal guard (Sec. 3.2.1, Eq. "DS" and the greedy search under it): with
+ * q_bit = max(bit_set) and c_i(q) the AIQ code of element i at q bits,
+ *       DS(q) = (1/n) * sum_i | floor(c_i(q_bit) / 2^(q_bit - q)) - c_i(q) |,
+ * the bitwidth is lowered from q_bit through the allowed bitwidths in descending order for
+ * as long as DS(q) <= delta, and stops at the first violation (greedy: a lower bitwidth that
+ * would pass again is not looked at).  The sum is an integer; the test is
+ * (double)sum <= delta * (double)n.  See slicer_ref_encode_ds.
+ *
  * Payload bound (Sec. 3.3, "Predictive Bit/Time Model"): every kept slot at the largest
  * bitwidth, plus index and header bits; see slicer_ref_bound.
  *
@@ -186,7 +194,40 @@ static uint32_t aiq_code(float a, float vmin, float inv, float L, float* y_out)
     return (uint32_t)r;
 }
 
-/* fixed_q > 0: the block's bitwidth is given (multi-level mode), no search */
+/* DS guard (Eq. "DS"): greedy descent from q_bit; returns the chosen bitwidth.
+ * ds_sum (17 entries, may be NULL) receives the integer sums of the bitwidths that were looked at. */
+static int ds_greedy(const kv_t* el, uint32_t cnt, uint32_t bit_set, double delta,
+                     float vmin, float rng, int degenerate, uint64_t* ds_sum)
+{
+    const int qbit = max_bit(bit_set);
+    uint32_t* c0 = (uint32_t*)malloc(sizeof(uint32_t) * (size_t)cnt);
+    const float L0 = (float)((1u << qbit) - 1u);
+    const float inv0 = degenerate ? 0.0f : L0 / rng;
+    for (uint32_t j = 0; j < cnt; ++j) {
+        float y;
+        c0[j] = degenerate ? 0u : aiq_code(bits_to_float(el[j].key), vmin, inv0, L0, &y);
+    }
+    int chosen = qbit;
+    for (int q = qbit - 1; q >= 1; --q) {
+        if (!((bit_set >> q) & 1u)) continue;
+        const float L = (float)((1u << q) - 1u);
+        const float inv = degenerate ? 0.0f : L / rng;
+        uint64_t D = 0;
+        for (uint32_t j = 0; j < cnt; ++j) {
+            float y;
+            uint32_t c = degenerate ? 0u : aiq_code(bits_to_float(el[j].key), vmin, inv, L, &y);
+            uint32_t ref = c0[j] >> (qbit - q);
+            D += ref > c ? ref - c : c - ref;
+        }
+        if (ds_sum) ds_sum[q] = D;
+        if ((double)D <= delta * (double)cnt) chosen = q; else break;
+    }
+    free(c0);
+    return chosen;
+}
+
+/* fixed_q > 0: the block's bitwidth is given (multi-level mode), no search;
+ * fixed_q < 0: the DS guard with delta = beta (greedy descent) */
 static void quantise_block(const kv_t* el, uint32_t cnt, uint32_t bit_set, double beta,
                            int fixed_q, int b, row_result* out)
 {
@@ -214,7 +255,10 @@ static void quantise_block(const kv_t* el, uint32_t cnt, uint32_t bit_set, doubl
 
     int degenerate = !(rng >= 0x1p-100f);
     int chosen = fixed_q > 0 ? fixed_q : -1;
-    for (int q = 1; q <= 16 && fixed_q <= 0; ++q) {
+    if (fixed_q < 0)
+        chosen = ds_greedy(el, cnt, bit_set, beta, vmin, rng, degenerate,
+                           out->s_int ? out->s_int + (size_t)b * 17 : NULL);
+    for (int q = 1; q <= 16 && fixed_q == 0; ++q) {
         if (!((bit_set >> q) & 1u)) continue;
         if (chosen >= 0 && !out->s_int) break; /* later sums only wanted for inspection */
         uint64_t S = 0;
@@ -263,9 +307,10 @@ static void quantise_block(const kv_t* el, uint32_t cnt, uint32_t bit_set, doubl
     }
 }
 
-/* ladder != NULL: multi-level mode, ladder[m] = bitwidth of block m of each class */
+/* ladder != NULL: multi-level mode, ladder[m] = bitwidth of block m of each class;
+ * ds != 0: the DS guard with delta = beta instead of the relative-error budget */
 static int analyze_row(const void* x, int dt, int64_t N, int64_t k, int M, uint32_t bit_set,
-                       double beta, const uint8_t* ladder, row_result* out)
+                       double beta, const uint8_t* ladder, int ds, row_result* out)
 {
     kv_t* all = (kv_t*)malloc(sizeof(kv_t) * (size_t)N);
     kv_t* cls = (kv_t*)malloc(sizeof(kv_t) * (size_t)(k > 0 ? k : 1));
@@ -309,7 +354,7 @@ static int analyze_row(const void* x, int dt, int64_t N, int64_t k, int M, uint3
             out->count[b] = cnt;
             if (cnt > 0) {
                 for (uint32_t j = 0; j < cnt; ++j) out->block_of[cls[start + j].idx] = b;
-                quantise_block(cls + start, cnt, bit_set, beta, ladder ? (int)ladder[m] : 0, b, out);
+                quantise_block(cls + start, cnt, bit_set, beta, ladder ? (int)ladder[m] : (ds ? -1 : 0), b, out);
             }
             start += cnt;
         }
@@ -400,7 +445,7 @@ static void row_result_free(row_result* rr)
 /* ---- public: encode ---------------------------------------------------- */
 
 static int encode_common(const void* x, int dt, int64_t R, int64_t N, double keep, int M,
-                         uint32_t bit_set, double beta, const uint8_t* ladder,
+                         uint32_t bit_set, double beta, const uint8_t* ladder, int ds,
                          void* stream, void* meta, int n_threads)
 {
     int rc = check_args(dt, R, N, keep, M, bit_set);
@@ -430,7 +475,7 @@ static int encode_common(const void* x, int dt, int64_t R, int64_t N, double kee
         uint32_t* idxbuf = (uint32_t*)malloc(sizeof(uint32_t) * (size_t)(k > 0 ? k : 1));
         seg[r] = (uint32_t*)calloc((size_t)(cap_words > 0 ? cap_words : 1), 4);
         const void* xr = (const char*)x + (size_t)r * (size_t)N * esz;
-        if (analyze_row(xr, dt, N, k, M, bit_set, beta, ladder, &rr) != 0) {
+        if (analyze_row(xr, dt, N, k, M, bit_set, beta, ladder, ds, &rr) != 0) {
             fail = 1;
         } else {
             seg_words[r] = pack_row(&rr, N, M, w, seg[r], idxbuf);
@@ -475,7 +520,7 @@ static int encode_common(const void* x, int dt, int64_t R, int64_t N, double kee
 int slicer_ref_encode(const void* x, int dt, int64_t R, int64_t N, double keep, int M,
                       uint32_t bit_set, double beta, void* stream, void* meta, int n_threads)
 {
-    return encode_common(x, dt, R, N, keep, M, bit_set, beta, NULL, stream, meta, n_threads);
+    return encode_common(x, dt, R, N, keep, M, bit_set, beta, NULL, 0, stream, meta, n_threads);
 }
 
 /* set of the ladder's bitwidths; 0 if an entry is outside 1..16 */
@@ -495,7 +540,13 @@ int slicer_ref_encode_ladder(const void* x, int dt, int64_t R, int64_t N, double
     if (!ladder || M < 1 || M > 64) return -1;
     uint32_t bs = ladder_bit_set(ladder, M);
     if (!bs) return -1;
-    return encode_common(x, dt, R, N, keep, M, bs, 0.0, ladder, stream, meta, n_threads);
+    return encode_common(x, dt, R, N, keep, M, bs, 0.0, ladder, 0, stream, meta, n_threads);
+}
+
+int slicer_ref_encode_ds(const void* x, int dt, int64_t R, int64_t N, double keep, int M,
+                         uint32_t bit_set, double delta, void* stream, void* meta, int n_threads)
+{
+    return encode_common(x, dt, R, N, keep, M, bit_set, delta, NULL, 1, stream, meta, n_threads);
 }
 
 /* Sec. 3.3: value bits with every block at q_bit = max(bit_set), index bits, header bits.
@@ -585,7 +636,7 @@ int slicer_ref_analyze_row(const void* x_row, int dt, int64_t N, double keep, in
     if (!x_row || !(beta >= 0.0)) return -1;
     row_result rr;
     row_result_alloc(&rr, N, M, 1);
-    rc = analyze_row(x_row, dt, N, keep_count(keep, N), M, bit_set, beta, NULL, &rr);
+    rc = analyze_row(x_row, dt, N, keep_count(keep, N), M, bit_set, beta, NULL, 0, &rr);
     if (rc == 0) {
         if (block_of) memcpy(block_of, rr.block_of, sizeof(int32_t) * (size_t)N);
         if (code_of) memcpy(code_of, rr.code_of, sizeof(uint32_t) * (size_t)N);

@@ -42,6 +42,14 @@ int slicer_ref_encode_ladder(const void* x, int dtype, int64_t rows, int64_t row
                              double keep_ratio, int n_blocks, const uint8_t* ladder,
                              void* stream, void* meta, int n_threads);
 
+/* Paper-literal guard (Sec. 3.2.1, Eq. "DS"): bitwidths are lowered greedily from
+ * q_bit = max(bit_set) through bit_set in descending order while
+ *   DS(q) = (1/n) sum | floor(c(q_bit) / 2^(q_bit - q)) - c(q) |  <=  delta,
+ * stopping at the first violation.  delta >= 0.  The infeasible flag is never set. */
+int slicer_ref_encode_ds(const void* x, int dtype, int64_t rows, int64_t row_len,
+                         double keep_ratio, int n_blocks, uint32_t bit_set, double delta,
+                         void* stream, void* meta, int n_threads);
+
 /* Upper bound of the payload before any data is seen (Sec. 3.3): value bits at
  * q_bit = max(bit_set), index bits, header bits (meta + word padding of the rows). */
 int slicer_ref_bound(int dtype, int64_t rows, int64_t row_len, double keep_ratio, int n_blocks,
