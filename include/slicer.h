@@ -110,6 +110,20 @@ int slicer_decode_as(const void* stream, const void* meta, void* y, slicer_dtype
                      int64_t rows, int64_t row_len, int n_blocks, void* hip_stream);
 
 /*
+ * Encode with the paper's own guard (Sec. 3.2.1, Eq. "DS", "greedily lowers the bit precision q
+ * from an initial maximum q_bit until a user-defined distortion threshold delta is met"):
+ * with q_bit = max(bit_set) and c(q) the block's AIQ codes at q bits,
+ *     DS(q) = (1/n) * sum | floor(c(q_bit) / 2^(q_bit - q)) - c(q) |,
+ * a block's bitwidth goes down through bit_set in descending order while DS(q) <= delta and
+ * stops at the first violation.  The integer sum is compared as (double)sum <= delta * n.
+ * delta >= 0; the infeasible flag of slicer_encode is never set.  Everything else (arguments,
+ * buffers, errors, asynchrony) as slicer_encode.
+ */
+int slicer_encode_ds(const void* x, slicer_dtype dt, int64_t rows, int64_t row_len,
+                     double keep_ratio, int n_blocks, uint32_t bit_set, double delta,
+                     void* stream, void* meta, void* workspace, void* hip_stream);
+
+/*
  * Fixed multi-level mode (Sec. 4.1: "multi-level quantization Q = [q_1, ..., q_M] ... with
  * q_1 > ... > q_M bits assigned in descending order of activation magnitude"): block m of
  * either sign class (block 0 = largest magnitudes) is quantised with ladder[m] bits; there

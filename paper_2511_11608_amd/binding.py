@@ -44,6 +44,8 @@ def load() -> C.CDLL:
         L.slicer_encode_path.argtypes = [cint, i64, i64, dbl, cint, u32]
         L.slicer_encode.restype = cint
         L.slicer_encode.argtypes = [vp, cint, i64, i64, dbl, cint, u32, dbl, vp, vp, vp, vp]
+        L.slicer_encode_ds.restype = cint
+        L.slicer_encode_ds.argtypes = L.slicer_encode.argtypes
         L.slicer_encode_ladder.restype = cint
         L.slicer_encode_ladder.argtypes = [vp, cint, i64, i64, dbl, cint, C.c_char_p, vp, vp, vp, vp]
         L.slicer_ladder_bit_set.restype = u32
@@ -118,6 +120,17 @@ def slicer_encode(x: torch.Tensor, keep_ratio: float, n_blocks: int, bit_set: in
     rows, row_len = x.shape
     _check("slicer_encode", load().slicer_encode(
         x.data_ptr(), _dt_of(x), rows, row_len, keep_ratio, n_blocks, bit_set, distortion_budget,
+        stream_buf.data_ptr(), meta.data_ptr(), workspace.data_ptr(), _stream_handle(stream)))
+
+
+def slicer_encode_ds(x: torch.Tensor, keep_ratio: float, n_blocks: int, bit_set: int, delta: float,
+                     stream_buf: torch.Tensor, meta: torch.Tensor, workspace: torch.Tensor, stream=None) -> None:
+    """Encode with the DS guard of Sec. 3.2.1 (greedy descent from max(bit_set) while DS <= delta)."""
+    if not x.is_cuda or not x.is_contiguous() or x.dim() != 2:
+        raise ValueError("x must be a contiguous 2-D tensor on the GPU")
+    rows, row_len = x.shape
+    _check("slicer_encode_ds", load().slicer_encode_ds(
+        x.data_ptr(), _dt_of(x), rows, row_len, keep_ratio, n_blocks, bit_set, delta,
         stream_buf.data_ptr(), meta.data_ptr(), workspace.data_ptr(), _stream_handle(stream)))
 
 

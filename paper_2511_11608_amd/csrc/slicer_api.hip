@@ -272,7 +272,7 @@ int slicer_encode_path(slicer_dtype dt, int64_t rows, int64_t row_len, double ke
 }
 
 static int encode_impl(const void* x, slicer_dtype dt, int64_t rows, int64_t row_len, double keep_ratio,
-                       int n_blocks, uint32_t bit_set, double distortion_budget, const Ladder& lad,
+                       int n_blocks, uint32_t bit_set, double distortion_budget, const Ladder& lad, int guard,
                        void* stream, void* meta, void* workspace, void* hip_stream)
 {
     int rc = check_args((int)dt, rows, row_len, keep_ratio, n_blocks, bit_set);
@@ -303,6 +303,7 @@ static int encode_impl(const void* x, slicer_dtype dt, int64_t rows, int64_t row
     ea.only_flagged = nullptr;
     ea.rows_per_wg = 1;
     ea.lad = lad;
+    ea.guard = guard;
 
     if (p.small_epl && ((uintptr_t)x & 15) == 0) {
         // fast path; rows it cannot hold are flagged and redone by the generic kernel
@@ -317,6 +318,7 @@ static int encode_impl(const void* x, slicer_dtype dt, int64_t rows, int64_t row
         sa.mv = ea.mv;
         sa.cap = p.small_cap; sa.region0_words = p.small_region0;
         sa.lad = lad;
+        sa.guard = guard;
         const bool timed = g_ev_start && g_ev_stop;
         if (timed) SLICER_HIP(hipEventRecord(g_ev_start, st));
         rc = dt == SLICER_F32 ? launch_small<0>(sa, p, st) : launch_small<1>(sa, p, st);
@@ -345,6 +347,7 @@ static int encode_impl(const void* x, slicer_dtype dt, int64_t rows, int64_t row
         la.fallback = (u32*)(ws + p.off_fallback);
         la.mv = ea.mv;
         la.lad = lad;
+        la.guard = guard;
         const bool timed = g_ev_start && g_ev_stop;
         if (timed) SLICER_HIP(hipEventRecord(g_ev_start, st));
         rc = dt == SLICER_F32 ? launch_large<0>(la, p, st) : launch_large<1>(la, p, st);
@@ -395,7 +398,18 @@ int slicer_encode(const void* x, slicer_dtype dt, int64_t rows, int64_t row_len,
     Ladder none;
     none.on = 0;
     for (int j = 0; j < kMaxBlocks / 8; ++j) none.nib[j] = 0;
-    return encode_impl(x, dt, rows, row_len, keep_ratio, n_blocks, bit_set, distortion_budget, none,
+    return encode_impl(x, dt, rows, row_len, keep_ratio, n_blocks, bit_set, distortion_budget, none, 0,
+                       stream, meta, workspace, hip_stream);
+}
+
+int slicer_encode_ds(const void* x, slicer_dtype dt, int64_t rows, int64_t row_len, double keep_ratio,
+                     int n_blocks, uint32_t bit_set, double delta, void* stream, void* meta, void* workspace,
+                     void* hip_stream)
+{
+    Ladder none;
+    none.on = 0;
+    for (int j = 0; j < kMaxBlocks / 8; ++j) none.nib[j] = 0;
+    return encode_impl(x, dt, rows, row_len, keep_ratio, n_blocks, bit_set, delta, none, 1,
                        stream, meta, workspace, hip_stream);
 }
 
@@ -424,7 +438,7 @@ int slicer_encode_ladder(const void* x, slicer_dtype dt, int64_t rows, int64_t r
         for (int q = 1; q < ladder[m]; ++q) t += (bit_set >> q) & 1u;
         lad.nib[m >> 3] |= t << ((m & 7) * 4);
     }
-    return encode_impl(x, dt, rows, row_len, keep_ratio, n_blocks, bit_set, 0.0, lad, stream, meta, workspace,
+    return encode_impl(x, dt, rows, row_len, keep_ratio, n_blocks, bit_set, 0.0, lad, 0, stream, meta, workspace,
                        hip_stream);
 }
 

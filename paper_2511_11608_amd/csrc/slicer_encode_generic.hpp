@@ -32,6 +32,7 @@ struct EncArgs {
     const u32* only_flagged;// if set: rows with a zero flag are skipped (already encoded)
     int64_t rows_per_wg;    // consecutive rows a workgroup walks (1 unless only_flagged is set)
     Ladder lad;             // fixed multi-level mode: no search, block m uses qlist[index(m)]
+    int guard;              // 0: relative squared-error budget (beta); 1: the DS mismatch of Eq. "DS" (beta = delta), greedy descent
     // meta
     MetaView mv;
 };
@@ -400,7 +401,21 @@ __device__ inline void enc_generic_rows(const EncArgs& a, const int64_t r_begin,
             float av = __uint_as_float(abits);
             u64 A = energy_grid(abits, e);
             accE += A * A;
-            if (!dg) {
+            if (!dg && a.guard == 1) {
+                // Eq. "DS": codes at q_bit shifted down against the codes at q
+                const float d = av - vmin;
+                const int top = a.nq - 1, qtop = a.qlist[top];
+                const u32 c0 = (u32)fminf(fmaxf(rintf(d * inv_tab[b][top]), 0.f), (float)((1u << qtop) - 1u));
+#pragma unroll
+                for (int t = 0; t < kMaxQ; ++t) {
+                    if (t < top) {
+                        const float L = (float)((1u << a.qlist[t]) - 1u);
+                        const u32 c = (u32)fminf(fmaxf(rintf(d * inv_tab[b][t]), 0.f), L);
+                        const u32 ref = c0 >> (qtop - a.qlist[t]);
+                        acc[t] += (u64)(ref > c ? ref - c : c - ref);
+                    }
+                }
+            } else if (!dg) {
                 float d = av - vmin;
 #pragma unroll
                 for (int t = 0; t < kMaxQ; ++t) {
@@ -443,6 +458,13 @@ __device__ inline void enc_generic_rows(const EncArgs& a, const int64_t r_begin,
                 if (chosen < 0) { chosen = a.nq - 1; flag = 0x80u; }
                 tsel = chosen; q = a.qlist[chosen];
             }
+        }
+        if (a.guard == 1) {         // greedy descent from q_bit while the mismatch stays within delta
+            int chosen = cnt ? a.nq - 1 : 0;
+            for (int t = a.nq - 2; t >= 0 && cnt; --t) {
+                if ((double)sums[b][t] <= a.beta * (double)cnt) chosen = t; else break;
+            }
+            tsel = chosen; q = a.qlist[chosen]; flag = 0;
         }
         if (a.lad.on) {             // the bitwidth is given, also for empty and degenerate blocks
             tsel = (int)ladder_index(a.lad, b % M);

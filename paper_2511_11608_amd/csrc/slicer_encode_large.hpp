@@ -64,6 +64,7 @@ struct LargeArgs {
     u32* fallback;
     MetaView mv;
     Ladder lad;             // fixed multi-level mode
+    int guard;              // 0: relative squared-error budget; 1: DS mismatch, greedy descent (beta = delta)
 };
 
 template <int DT>
@@ -577,7 +578,19 @@ __global__ __launch_bounds__(256) void lr_abq_kernel(LargeArgs a)
             const float av = __uint_as_float(bo_val[p]);
             const u64 A = (u64)(u32)rintf(ldexpf(av, 20 - e));
             accE += A * A;
-            if (!dg) {
+            if (!dg && a.guard == 1) {
+                const float d = av - vmin;
+                const int top = nq - 1, qtop = a.qlist[top];
+                const u32 c0 = (u32)fminf(fmaxf(rintf(d * inv_tab[b][top]), 0.f), (float)((1u << qtop) - 1u));
+#pragma unroll
+                for (int t = 0; t < kMaxQ; ++t) {
+                    if (t < top) {
+                        const u32 c = (u32)fminf(fmaxf(rintf(d * inv_tab[b][t]), 0.f), (float)((1u << a.qlist[t]) - 1u));
+                        const u32 ref = c0 >> (qtop - a.qlist[t]);
+                        acc[t] += (u64)(ref > c ? ref - c : c - ref);
+                    }
+                }
+            } else if (!dg) {
                 const float d = av - vmin;
 #pragma unroll
                 for (int t = 0; t < kMaxQ; ++t) {
@@ -634,6 +647,15 @@ __global__ __launch_bounds__(128) void lr_choose_kernel(LargeArgs a)
                     if (lhs <= rhs) flag = 0;
                 }
             }
+        }
+        if (a.guard == 1) {         // greedy descent from q_bit while the mismatch stays within delta
+            int chosen = cnt ? nq - 1 : 0;
+            const u64* sm = a.sums + ((size_t)r * B2 + b) * (nq + 1);
+            for (int t = nq - 2; t >= 0 && cnt; --t) {
+                if ((double)sm[t] <= a.beta * (double)cnt) chosen = t; else break;
+            }
+            q = a.qlist[chosen]; flag = 0; inv = 0.f;
+            if (cnt && vmax - vmin >= 0x1p-100f) inv = (float)((1u << q) - 1u) / (vmax - vmin);
         }
         if (a.lad.on) {             // the bitwidth is given, also for empty and degenerate blocks
             q = a.qlist[ladder_index(a.lad, b % a.M)];

@@ -47,6 +47,7 @@ struct SmallArgs {
     int cap;            // list capacity, multiple of 64, < 2048
     int region0_words;  // fine histogram, later block-ordered indices + stream image
     Ladder lad;         // fixed multi-level mode: no sums, no search
+    int guard;          // 0: relative squared-error budget; 1: DS mismatch of Eq. "DS", greedy descent (beta = delta)
 };
 
 constexpr int kCoarseBits = 11;
@@ -670,7 +671,8 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
         }
         if (sub == 0) {
             for (int t = 0; t <= nq; ++t) sums[myb * (nq + 1) + t] = 0;
-            L.run[myb] = (mycnt && !dg) ? (u32)nq : 0u;     // index of the chosen bitwidth; nq = none feasible yet
+            // budget guard: index of the chosen bitwidth, nq = none feasible yet; DS guard: mask of violations
+            L.run[myb] = (mycnt && !dg && a.guard == 0) ? (u32)nq : 0u;
         }
     }
     wave_sync();
@@ -683,11 +685,15 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
     bool small_q = true;
 #pragma unroll
     for (int t = 0; t < QN; ++t) {
-        inv[t] = (lane_on && (NQ || t < nq)) ? invt[myb * (u32)nq + t] * 32768.0f : 0.f;
+        inv[t] = (lane_on && (NQ || t < nq)) ? invt[myb * (u32)nq + t] : 0.f;
         if ((NQ || t < nq) && a.qlist[t] > 8) small_q = false;
     }
     auto abq_sums = [&](auto fast) {
         constexpr bool kFast = decltype(fast)::value;
+        // bitwidths up to 8: the scale times 2^15 stays finite (scale <= 255 * 2^100), one multiply per code
+        float inv15[QN];
+#pragma unroll
+        for (int t = 0; t < QN; ++t) inv15[t] = inv[t] * 32768.0f;
         u64 accE = 0;
         for (u32 i0 = 0; i0 < T; i0 += 8) {             // u32 partial sums hold 8 residuals of 2^28
             u32 acc[QN];
@@ -704,8 +710,9 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
 #pragma unroll
                     for (int t = 0; t < QN; ++t) {
                         if (NQ || t < nq) {
-                            const float z = d * inv[t];
-                            const u32 zi = kFast ? __float_as_uint(z + 8388608.0f) : (u32)rintf(z);
+                            // (wider bitwidths: y first, then the exact scaling, so that nothing overflows)
+                            const u32 zi = kFast ? __float_as_uint(d * inv15[t] + 8388608.0f)
+                                                 : (u32)rintf((d * inv[t]) * 32768.0f);
                             const int rho = __builtin_amdgcn_sbfe((int)zi, 0u, 15u);
                             acc[t] += (u32)(rho * rho);
                         }
@@ -718,8 +725,39 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
         }
         if (accE) atomicAdd(&sums[myb * (nq + 1) + nq], accE);
     };
+    // Eq. "DS": sum over the block of | (code at q_bit >> (q_bit - q)) - code at q | for every lower bitwidth
+    auto ds_sums = [&]() {
+        const int top = nq - 1, qtop = (int)L.qtab[top];
+        const float inv_top = lane_on ? invt[myb * (u32)nq + (u32)top] : 0.f;
+        for (u32 i0 = 0; i0 < T; i0 += 8) {
+            u32 acc[QN];
+#pragma unroll
+            for (int t = 0; t < QN; ++t) acc[t] = 0;
+            const u32 i1 = i0 + 8 < T ? i0 + 8 : T;
+            for (u32 i = i0; i < i1; ++i) {
+                const u32 p = r0 + i;
+                if (p < r1) {
+                    const float d = __uint_as_float(bo_val[p]) - vmin;
+                    const u32 c0 = (u32)rintf(d * inv_top);           // within [0, 2^q - 1]: no clamp needed
+#pragma unroll
+                    for (int t = 0; t < QN; ++t) {
+                        if ((NQ || t < nq) && t < top) {
+                            const u32 c = (u32)rintf(d * inv[t]);
+                            const u32 ref = c0 >> (u32)(qtop - a.qlist[t]);
+                            acc[t] += ref > c ? ref - c : c - ref;
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < QN; ++t)
+                if ((NQ || t < nq) && acc[t]) atomicAdd(&sums[myb * (nq + 1) + t], (u64)acc[t]);
+        }
+    };
     if (!a.lad.on) {
-        if (small_q) abq_sums(std::true_type()); else abq_sums(std::false_type());
+        if (a.guard == 1) ds_sums();
+        else if (small_q) abq_sums(std::true_type());
+        else abq_sums(std::false_type());
     }
     wave_sync();
 
@@ -727,6 +765,17 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
     // ascending order and keep the minimum
     if (a.lad.on) {
         if (lane_on && sub == 0) L.run[myb] = ladder_index(a.lad, (int)(myb >= (u32)M ? myb - (u32)M : myb));
+    } else if (a.guard == 1) {
+        // greedy descent: the chosen index is one above the highest violating candidate below q_bit
+        if (lane_on && mycnt && !dg) {
+            for (u32 t = sub; t + 1 < (u32)nq; t += lpb)
+                if (!((double)sums[myb * (nq + 1) + t] <= a.beta * (double)mycnt)) atomicOr(&L.run[myb], 1u << t);
+        }
+        wave_sync();
+        if (lane_on && sub == 0) {
+            const u32 viol = L.run[myb];
+            L.run[myb] = viol ? 32u - (u32)__clz((int)viol) : 0u;
+        }
     } else if (lane_on && mycnt && !dg) {
         const double rhs = a.beta * ldexp((double)sums[myb * (nq + 1) + nq], 2 * e - 40);
         for (u32 t = sub; t < (u32)nq; t += lpb) {

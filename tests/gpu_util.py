@@ -31,6 +31,17 @@ def gpu_encode(x: np.ndarray, dtype: str, keep_ratio, n_blocks, bit_set, budget)
     return sb, meta, words
 
 
+def gpu_encode_ds(x: np.ndarray, dtype: str, keep_ratio, n_blocks, bit_set, delta):
+    xd = to_device(x, dtype)
+    sb, meta, ws = binding.alloc_buffers(xd, keep_ratio, n_blocks, bit_set)
+    ws.fill_(0xA5)
+    sb.fill_(-1)
+    meta.fill_(0xFF)
+    binding.slicer_encode_ds(xd, keep_ratio, n_blocks, bit_set, delta, sb, meta, ws)
+    words = binding.slicer_stream_words(meta)
+    return sb, meta, words
+
+
 def gpu_encode_ladder(x: np.ndarray, dtype: str, keep_ratio, ladder):
     xd = to_device(x, dtype)
     sb, meta, ws = binding.alloc_buffers(xd, keep_ratio, len(ladder), binding.slicer_ladder_bit_set(ladder))

@@ -103,6 +103,7 @@ def _mixed_rows(rng, rows, N, dtype):
     x[4, :] = np.abs(x[4, :])                          # one sign class only
     x[5, :] = 0
     x[6, : N // 2] *= np.float32(1e-30)                # wide key range: coarse fine bins
+    x[7, :] = rng.standard_normal(N).astype(np.float32) * np.float32(2e-30)   # block ranges just above 2^-100: huge scales
     return synth.f32_to_bf16_bits(x) if dtype == "bf16" else x
 
 
@@ -147,6 +148,38 @@ def test_ladder_mode_mixed_rows(oracle, dtype, N):
     x = _mixed_rows(rng, 12, N, dtype)
     for keep, ladder in ((0.1, [8, 7, 6, 5, 4, 3, 2, 2]), (1.0, [3, 2]), (0.3, list(range(16, 0, -1)) * 2), (0.0, [5])):
         check_ladder(oracle, x, dtype, keep, ladder)
+
+
+def check_ds(oracle, x, dtype, keep, M, bits, delta):
+    from tests.gpu_util import gpu_encode_ds, gpu_decode
+    s_ref, m_ref = oracle.encode_ds(x, dtype, keep, M, bits, delta, n_threads=8)
+    y_ref = oracle.decode(s_ref, m_ref, n_threads=8)
+    sb, meta, words = gpu_encode_ds(x, dtype, keep, M, bits, delta)
+    m_gpu = meta.cpu().numpy()
+    assert np.array_equal(m_ref[:64], m_gpu[:64]), (streamfmt.header(m_ref), streamfmt.header(m_gpu))
+    s_gpu = sb[:words].cpu().numpy().view(np.uint32)
+    ok = np.array_equal(m_ref, m_gpu) and np.array_equal(s_ref, s_gpu)
+    assert ok, explain_mismatch(s_ref, m_ref, s_gpu, m_gpu, x.shape[0])
+    y_gpu = gpu_decode(sb, meta, x.shape, dtype, M)
+    assert np.array_equal(y_ref.view(np.uint32 if dtype == "f32" else np.uint16),
+                          y_gpu.view(np.uint32 if dtype == "f32" else np.uint16))
+
+
+@pytest.mark.parametrize("name", ["cnn_map_ragged", "resnet_2rows", "vit", "llm", "ar_step"])
+def test_ds_guard_workloads(oracle, name):
+    """The paper's DS guard (Eq. "DS", greedy descent) on every kernel family."""
+    wl = CASES[name]()
+    for delta in (0.0, 0.26, 0.45, 1e6):
+        check_ds(oracle, wl.x, wl.dtype, wl.keep_ratio, wl.n_blocks, wl.bit_set, delta)
+
+
+@pytest.mark.parametrize("dtype,N", [("bf16", 4096), ("f32", 768), ("bf16", 1000), ("f32", 40000)])
+def test_ds_guard_mixed_rows(oracle, dtype, N):
+    rng = np.random.default_rng(N + 2)
+    x = _mixed_rows(rng, 12, N, dtype)
+    for keep, M, bits, delta in ((0.1, 8, B28, 0.3), (1.0, 3, 0x1FFFE, 0.4), (0.3, 32, (1 << 1) | (1 << 9) | (1 << 16), 0.5),
+                                 (0.2, 2, 1 << 6, 0.0), (0.0, 1, B28, 0.1)):
+        check_ds(oracle, x, dtype, keep, M, bits, delta)
 
 
 def test_encode_is_deterministic():
