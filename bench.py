@@ -65,7 +65,7 @@ def make_workload(which: int):
     return wl, [wl.x]
 
 
-def cpu_baseline(wl, threads: int, ladder=None) -> dict:
+def cpu_baseline(wl, threads: int, ladder=None, ds=None) -> dict:
     """The oracle as it stands (encode + decode) on a bounded sample of the rows."""
     from oracle import ref
     ref.lib()
@@ -73,6 +73,8 @@ def cpu_baseline(wl, threads: int, ladder=None) -> dict:
     def ref_encode(x, n_threads):
         if ladder:
             return ref.encode_ladder(x, wl.dtype, wl.keep_ratio, ladder, n_threads=n_threads)
+        if ds is not None:
+            return ref.encode_ds(x, wl.dtype, wl.keep_ratio, wl.n_blocks, wl.bit_set, ds, n_threads=n_threads)
         return ref.encode(x, wl.dtype, wl.keep_ratio, wl.n_blocks, wl.bit_set, wl.budget, n_threads=n_threads)
 
     rows = wl.rows
@@ -138,6 +140,8 @@ def main() -> int:
     ap.add_argument("--ladder", type=str, default="",
                     help="time the fixed multi-level mode instead of the bitwidth search: comma-separated "
                          "bitwidths, one per block of a sign class, e.g. 8,7,6,5,4,3,2,2")
+    ap.add_argument("--ds", type=float, default=None,
+                    help="time the paper's DS guard with greedy descent at this delta instead of the budget search")
     ap.add_argument("--eager", action="store_true",
                     help="time plain launches instead of replaying a captured HIP graph of the steps")
     ap.add_argument("--copy-probe", action="store_true",
@@ -166,6 +170,8 @@ def main() -> int:
     def encode(x, sb, meta, ws):
         if ladder:
             binding.slicer_encode_ladder(x, keep, ladder, sb, meta, ws)
+        elif args.ds is not None:
+            binding.slicer_encode_ds(x, keep, M, bits, args.ds, sb, meta, ws)
         else:
             binding.slicer_encode(x, keep, M, bits, beta, sb, meta, ws)
     in_bytes = wl.nbytes
@@ -315,7 +321,7 @@ def main() -> int:
     roofline = {"bound": "hbm", "kernel": enc_kernel, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": achieved / HBM_PEAK_GBS, "traffic": load_traffic(wl.name, enc_kernel),
                 "algorithmic_bytes_per_launch": enc_alg_bytes, "kernel_ms": enc_ms,
-                "alu": None if ladder else alu_view(wl.name, enc_kernel, enc_ms),
+                "alu": None if (ladder or args.ds is not None) else alu_view(wl.name, enc_kernel, enc_ms),
                 "decode_kernel": {"kernel": dec_kernel, "kernel_ms": dec_ms,
                                   "achieved": dec_alg_bytes / (dec_ms * 1e-3) / 1e9,
                                   "frac": dec_alg_bytes / (dec_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
@@ -327,7 +333,7 @@ def main() -> int:
         torch.cuda.synchronize()
 
     threads = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)))
-    cpu = None if args.no_cpu else cpu_baseline(wl, threads, ladder)
+    cpu = None if args.no_cpu else cpu_baseline(wl, threads, ladder, args.ds)
 
     out = {
         "metric": "codec encode+decode throughput, GB/s of input IF",
@@ -337,7 +343,8 @@ def main() -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl.dtype, "data": "synthetic", "launch": launch,
         "config": {"workload": f"{wl.name} [{wl.rows}x{wl.row_len}] keep={keep} M={M} "
-                               + (f"ladder={ladder}" if ladder else f"bits=2..8 budget={beta}"),
+                               + (f"ladder={ladder}" if ladder else f"bits=2..8 DS delta={args.ds}" if args.ds is not None
+                                  else f"bits=2..8 budget={beta}"),
                    "input_bytes": in_bytes, "distinct_input_buffers": n_buf},
         "encode": {"GBps": in_bytes / (enc_call_ms * 1e-3) / 1e9, "ms": enc_call_ms,
                    "elements_per_s": n_el / (enc_call_ms * 1e-3),
