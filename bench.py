@@ -155,7 +155,7 @@ def main() -> int:
 
     import torch
     from paper_2511_11608_amd import binding
-    from tests.gpu_util import to_device     # numpy -> device tensor (plumbing only)
+    from paper_2511_11608_amd.devmem import to_device     # numpy -> device tensor (plumbing only)
 
     binding.load()
     wl, xs = make_workload(args.workload)

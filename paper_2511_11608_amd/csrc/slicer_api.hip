@@ -119,7 +119,7 @@ Plan make_plan(int dt, int64_t rows, int64_t row_len, double keep_ratio, int n_b
 
     // The one-wave-per-row kernel holds the row in registers (64 * EPL elements) and
     // its lists in LDS; it needs whole 16-byte chunks, 16-bit indices, one lane per
-    // block and a list capacity below 1024 entries.
+    // block and a list capacity below 2048 entries (11-bit rank fields).
     p.small_epl = 0; p.small_cap = 0; p.small_region0 = 0; p.small_lds_bytes = 0; p.small_maxs = 0;
     const int epc = dt == SLICER_F32 ? 4 : 8;
     const int64_t max_n = dt == SLICER_F32 ? 2048 : 8192;
@@ -325,7 +325,6 @@ static int encode_impl(const void* x, slicer_dtype dt, int64_t rows, int64_t row
         if (rc) return rc;
         if (timed) SLICER_HIP(hipEventRecord(g_ev_stop, st));
         ea.only_flagged = sa.fallback;
-        ea.rows_per_wg = (rows + 1023) / 1024;     // few workgroups: flagged rows are rare
     }
     if (!ea.only_flagged && p.large_C && ((uintptr_t)x & 15) == 0) {
         // long rows: multi-workgroup stages; rows they cannot hold are flagged for the generic kernel

@@ -7,17 +7,17 @@
 //   select    per row: the bin B1 that holds overall rank k-1, the list offsets of the chunks
 //   compact   per chunk: ordered compaction of everything at or above B1 into the row's
 //             list L (ascending index)
-//   bounds    per row: 8192-bin fine histogram of the list in LDS, ranks of the bins; the comp of overall rank k-1 (ATKF cut,
-//             Sec. 3.1) and of class ranks j*K-1 (block boundaries, Sec. 3.2), each resolved
+//   bounds    per row: 8192-bin fine histogram of the list in LDS, ranks of the bins; the comp
+//             of overall rank k-1 (ATKF cut, Sec. 3.1) and of class ranks j*K-1 (block boundaries, Sec. 3.2), each resolved
 //             inside its bin by pairwise comparison of the bin's members
 //   blockcount / scatter   per 2048 list entries: block id, per-block counts, block min/max;
 //             then a stable split by block id (ascending index inside a block)
 //   abq / choose / pack    integer ABQ sums (Sec. 3.2.1) with 64-bit atomics, per-block
-//             bitwidth, bit offsets, and the row's stream image 4096 words at a time
+//             bitwidth, bit offsets, and the row's stream image 1024 words per workgroup
 //
 // comp = key << w | (2^w - 1 - index): larger comp = larger magnitude, then lower index.
 // Rows that do not fit the lists (heavy ties, more zeros than dropped elements) are
-// flagged and redone by the generic kernel.
+// flagged and redone by the generic encoder inside the row-scan kernel.
 #pragma once
 
 #include "slicer_common.hpp"

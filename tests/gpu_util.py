@@ -6,18 +6,7 @@ import numpy as np
 import torch
 
 from paper_2511_11608_amd import binding
-
-
-def to_device(x: np.ndarray, dtype: str) -> torch.Tensor:
-    if dtype == "f32":
-        return torch.from_numpy(np.ascontiguousarray(x)).cuda()
-    return torch.from_numpy(np.ascontiguousarray(x).view(np.int16)).cuda().view(torch.bfloat16)
-
-
-def to_host(y: torch.Tensor) -> np.ndarray:
-    if y.dtype == torch.bfloat16:
-        return y.view(torch.int16).cpu().numpy().view(np.uint16)
-    return y.cpu().numpy()
+from paper_2511_11608_amd.devmem import to_device, to_host  # noqa: F401 (re-exported for the tests)
 
 
 def gpu_encode(x: np.ndarray, dtype: str, keep_ratio, n_blocks, bit_set, budget):
