@@ -69,7 +69,7 @@ def test_workload_parity(oracle, name):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("N", [1, 2, 63, 64, 65, 257, 1000, 4097, 16385, 40000])
+@pytest.mark.parametrize("N", [1, 2, 63, 64, 65, 257, 1000, 2048, 4097, 8192, 16384, 16385, 32768, 40000])
 def test_adversarial_rows(oracle, dtype, N):
     x = synth.adversarial_rows(dtype, N, seed=N)
     for keep, M, bits, budget in ((0.0, 1, B28, 1e-3), (0.3, 2, B28, 1e-3), (1.0, 5, B28, 0.0),
