@@ -550,11 +550,16 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
                 const u32 bs = tg_base[t], cn = tg_cnt[t];
                 const u32 me = L.S[bs + (pr - tg_pre[t])];
                 if (s_neg(me) == tc) {
+                    // one compare per member: with the class bit moved to the top and set for the
+                    // boundary's class, "same class and larger comp" is a plain unsigned "larger"
+                    const u32 fm = DT == 0 ? (tc ^ 1u) : (tc ? 0u : 0x80000000u);
+                    auto key_of = [&](u32 sv) -> u32 {
+                        const u32 xv = sv ^ fm;
+                        return DT == 0 ? __builtin_amdgcn_alignbit(xv, xv, 1) : xv;     // fp32: rotate the class bit up
+                    };
+                    const u32 mk = key_of(me);
                     u32 gt = 0;
-                    for (u32 jj = 0; jj < cn; ++jj) {
-                        const u32 o = L.S[bs + jj];
-                        gt += (s_neg(o) == tc && s_plain(o) > s_plain(me)) ? 1u : 0u;
-                    }
+                    for (u32 jj = 0; jj < cn; ++jj) gt += key_of(L.S[bs + jj]) > mk ? 1u : 0u;
                     if (gt == tg_rem[t]) thr[t] = s_cx(me, tg_bin[t]);
                 }
             }
