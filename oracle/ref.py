@@ -28,6 +28,12 @@ def lib() -> C.CDLL:
         L.slicer_ref_encode_ladder.restype = C.c_int
         L.slicer_ref_encode_ladder.argtypes = [C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_double, C.c_int,
                                                C.c_void_p, C.c_void_p, C.c_void_p, C.c_int]
+        L.slicer_ref_sizes_pn.restype = C.c_int
+        L.slicer_ref_sizes_pn.argtypes = [C.c_int, C.c_int64, C.c_int64, C.c_double, C.c_int, C.c_int, C.c_uint32,
+                                          C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
+        L.slicer_ref_encode_pn.restype = C.c_int
+        L.slicer_ref_encode_pn.argtypes = [C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_double, C.c_int, C.c_int,
+                                           C.c_uint32, C.c_double, C.c_void_p, C.c_void_p, C.c_int]
         L.slicer_ref_encode_ds.restype = C.c_int
         L.slicer_ref_encode_ds.argtypes = L.slicer_ref_encode.argtypes
         L.slicer_ref_bound.restype = C.c_int
@@ -71,6 +77,26 @@ def encode(x: np.ndarray, dtype: str, keep_ratio: float, n_blocks: int, bit_set:
                                  budget, stream.ctypes.data, meta.ctypes.data, n_threads)
     if rc:
         raise ValueError(f"slicer_ref_encode: error {rc}")
+    total = int(meta[48:56].view(np.uint64)[0])
+    return stream[:total].copy(), meta
+
+
+def encode_pn(x: np.ndarray, dtype: str, keep_ratio: float, n_blocks: int, n_blocks_neg: int, bit_set: int,
+              budget: float, n_threads: int = 1):
+    """Separate block counts for the positive and the negative class.  Returns (stream, meta)."""
+    x = _check_x(x, dtype)
+    rows, row_len = x.shape
+    a, b = C.c_size_t(0), C.c_size_t(0)
+    rc = lib().slicer_ref_sizes_pn(_DT[dtype], rows, row_len, keep_ratio, n_blocks, n_blocks_neg, bit_set,
+                                   C.byref(a), C.byref(b))
+    if rc:
+        raise ValueError(f"slicer_ref_sizes_pn: error {rc}")
+    stream = np.zeros(max(a.value // 4, 1), np.uint32)
+    meta = np.zeros(b.value, np.uint8)
+    rc = lib().slicer_ref_encode_pn(x.ctypes.data, _DT[dtype], rows, row_len, keep_ratio, n_blocks, n_blocks_neg,
+                                    bit_set, budget, stream.ctypes.data, meta.ctypes.data, n_threads)
+    if rc:
+        raise ValueError(f"slicer_ref_encode_pn: error {rc}")
     total = int(meta[48:56].view(np.uint64)[0])
     return stream[:total].copy(), meta
 

@@ -59,14 +59,14 @@
  * Wire format, version 1 (little-endian):
  *   meta:  0 u32 magic 0x52434C53   4 u32 version   8 u32 dtype   12 u32 M
  *         16 u64 rows  24 u64 row_len  32 u64 k  40 u32 bit_set  44 u32 w
- *         48 u64 total_words  56 u64 0
+ *         48 u64 total_words  56 u32 M(-) if it differs from M (else 0)  60 u32 0
  *         64            u64 row_word_off[R]   (exclusive scan of row words)
  *         64+8R         u32 n_pos[R]
  *         64+12R        u32 n_neg[R]
- *         64+16R        f32 vmin[R][2M]
- *         64+16R+8RM    f32 vmax[R][2M]
- *         64+16R+16RM   u8  q[R][2M]
- *         size = 64 + 16R + 18RM rounded up to a multiple of 8
+ *         64+16R        f32 vmin[R][B]     B = M + M(-) blocks per row (2M when equal)
+ *         64+16R+4RB    f32 vmax[R][B]
+ *         64+16R+8RB    u8  q[R][B]
+ *         size = 64 + 16R + 9RB rounded up to a multiple of 8
  *   stream: total_words 32-bit words, rows concatenated.
  */
 #include "slicer_ref.h"
@@ -137,23 +137,31 @@ static int index_bits(int64_t N)
 static int max_bit(uint32_t bit_set) { int q = 16; while (!((bit_set >> q) & 1u)) --q; return q; }
 static int min_bit(uint32_t bit_set) { int q = 1;  while (!((bit_set >> q) & 1u)) ++q; return q; }
 
-static size_t meta_size(int64_t R, int M)
+/* B2 = number of blocks per row = M(+) + M(-) */
+static size_t meta_size(int64_t R, int B2)
 {
-    size_t s = REF_HDR + 16 * (size_t)R + 18 * (size_t)R * (size_t)M;
+    size_t s = REF_HDR + 16 * (size_t)R + 9 * (size_t)R * (size_t)B2;
     return (s + 7) & ~(size_t)7;
+}
+
+int slicer_ref_sizes_pn(int dt, int64_t rows, int64_t N, double keep, int M, int Mn, uint32_t bit_set,
+                        size_t* stream_cap, size_t* meta_bytes)
+{
+    int rc = check_args(dt, rows, N, keep, M, bit_set);
+    if (rc) return rc;
+    if (Mn < 1 || Mn > 128) return -1;
+    int64_t k = keep_count(keep, N);
+    uint64_t bits = (uint64_t)k * (uint64_t)(index_bits(N) + max_bit(bit_set));
+    uint64_t words = (bits + 31) / 32;
+    if (stream_cap) *stream_cap = (size_t)(words * 4 * (uint64_t)rows);
+    if (meta_bytes) *meta_bytes = meta_size(rows, M + Mn);
+    return 0;
 }
 
 int slicer_ref_sizes(int dt, int64_t rows, int64_t N, double keep, int M, uint32_t bit_set,
                      size_t* stream_cap, size_t* meta_bytes)
 {
-    int rc = check_args(dt, rows, N, keep, M, bit_set);
-    if (rc) return rc;
-    int64_t k = keep_count(keep, N);
-    uint64_t bits = (uint64_t)k * (uint64_t)(index_bits(N) + max_bit(bit_set));
-    uint64_t words = (bits + 31) / 32;
-    if (stream_cap) *stream_cap = (size_t)(words * 4 * (uint64_t)rows);
-    if (meta_bytes) *meta_bytes = meta_size(rows, M);
-    return 0;
+    return slicer_ref_sizes_pn(dt, rows, N, keep, M, M, bit_set, stream_cap, meta_bytes);
 }
 
 /* ---- one row: everything up to (but not including) packing ------------- */
@@ -309,7 +317,9 @@ static void quantise_block(const kv_t* el, uint32_t cnt, uint32_t bit_set, doubl
 
 /* ladder != NULL: multi-level mode, ladder[m] = bitwidth of block m of each class;
  * ds != 0: the DS guard with delta = beta instead of the relative-error budget */
-static int analyze_row(const void* x, int dt, int64_t N, int64_t k, int M, uint32_t bit_set,
+/* M, Mn: blocks of the positive and of the negative class (Sec. 3.3: M(+), M(-)); block
+ * numbers are +0..+M-1 then -0..-Mn-1 */
+static int analyze_row(const void* x, int dt, int64_t N, int64_t k, int M, int Mn, uint32_t bit_set,
                        double beta, const uint8_t* ladder, int ds, row_result* out)
 {
     kv_t* all = (kv_t*)malloc(sizeof(kv_t) * (size_t)N);
@@ -326,9 +336,9 @@ static int analyze_row(const void* x, int dt, int64_t N, int64_t k, int M, uint3
     }
     qsort(all, (size_t)N, sizeof(kv_t), cmp_mag_desc_idx_asc);
 
-    for (int b = 0; b < 2 * M; ++b) {
+    for (int b = 0; b < M + Mn; ++b) {
         out->vmin[b] = 0.0f; out->vmax[b] = 0.0f;
-        out->qb[b] = ladder ? ladder[b % M] : (uint8_t)min_bit(bit_set);   /* empty blocks keep this */
+        out->qb[b] = ladder ? ladder[b < M ? b : b - M] : (uint8_t)min_bit(bit_set);   /* empty blocks keep this */
         out->count[b] = 0;
         if (out->e_int) out->e_int[b] = 0;
         if (out->e_exp) out->e_exp[b] = 0;
@@ -346,10 +356,11 @@ static int analyze_row(const void* x, int dt, int64_t N, int64_t k, int M, uint3
         if (s == 0) out->n_pos = n; else out->n_neg = n;
 
         /* MS: equal-cardinality blocks in rank order, remainder to the last */
-        uint32_t K = n / (uint32_t)M;
+        const int Ms = s ? Mn : M;
+        uint32_t K = n / (uint32_t)Ms;
         uint32_t start = 0;
-        for (int m = 0; m < M; ++m) {
-            uint32_t cnt = (m < M - 1) ? K : n - start;
+        for (int m = 0; m < Ms; ++m) {
+            uint32_t cnt = (m < Ms - 1) ? K : n - start;
             int b = s * M + m;
             out->count[b] = cnt;
             if (cnt > 0) {
@@ -386,14 +397,14 @@ static uint32_t get_bits(const uint32_t* words, uint64_t bitpos, int nbits)
 
 /* Pack one analysed row into `words` (zero-filled by the caller); returns the
  * number of 32-bit words used. */
-static uint64_t pack_row(const row_result* rr, int64_t N, int M, int w, uint32_t* words,
+static uint64_t pack_row(const row_result* rr, int64_t N, int B2, int w, uint32_t* words,
                          uint32_t* scratch_idx /* [n_pos+n_neg] */)
 {
     /* element indices in stream order: block by block, ascending inside
      * (one ascending sweep appends each kept index to its block's list) */
     uint32_t n = 0;
-    uint32_t* fill = (uint32_t*)malloc(sizeof(uint32_t) * 2 * (size_t)M);
-    for (int b = 0; b < 2 * M; ++b) { fill[b] = n; n += rr->count[b]; }
+    uint32_t* fill = (uint32_t*)malloc(sizeof(uint32_t) * (size_t)B2);
+    for (int b = 0; b < B2; ++b) { fill[b] = n; n += rr->count[b]; }
     for (int64_t i = 0; i < N; ++i)
         if (rr->block_of[i] >= 0) scratch_idx[fill[rr->block_of[i]]++] = (uint32_t)i;
     free(fill);
@@ -413,26 +424,26 @@ static void put_u64(uint8_t* p, uint64_t v) { memcpy(p, &v, 8); }
 static uint32_t get_u32(const uint8_t* p) { uint32_t v; memcpy(&v, p, 4); return v; }
 static uint64_t get_u64(const uint8_t* p) { uint64_t v; memcpy(&v, p, 8); return v; }
 
-static size_t off_rowoff(int64_t R, int M) { (void)R; (void)M; return REF_HDR; }
-static size_t off_npos(int64_t R, int M)   { (void)M; return REF_HDR + 8 * (size_t)R; }
-static size_t off_nneg(int64_t R, int M)   { (void)M; return REF_HDR + 12 * (size_t)R; }
-static size_t off_vmin(int64_t R, int M)   { (void)M; return REF_HDR + 16 * (size_t)R; }
-static size_t off_vmax(int64_t R, int M)   { return REF_HDR + 16 * (size_t)R + 8 * (size_t)R * M; }
-static size_t off_q(int64_t R, int M)      { return REF_HDR + 16 * (size_t)R + 16 * (size_t)R * M; }
+static size_t off_rowoff(int64_t R, int B2) { (void)R; (void)B2; return REF_HDR; }
+static size_t off_npos(int64_t R, int B2)   { (void)B2; return REF_HDR + 8 * (size_t)R; }
+static size_t off_nneg(int64_t R, int B2)   { (void)B2; return REF_HDR + 12 * (size_t)R; }
+static size_t off_vmin(int64_t R, int B2)   { (void)B2; return REF_HDR + 16 * (size_t)R; }
+static size_t off_vmax(int64_t R, int B2)   { return REF_HDR + 16 * (size_t)R + 4 * (size_t)R * B2; }
+static size_t off_q(int64_t R, int B2)      { return REF_HDR + 16 * (size_t)R + 8 * (size_t)R * B2; }
 
-static void row_result_alloc(row_result* rr, int64_t N, int M, int with_sums)
+static void row_result_alloc(row_result* rr, int64_t N, int B2, int with_sums)
 {
     memset(rr, 0, sizeof(*rr));
     rr->block_of = (int32_t*)malloc(sizeof(int32_t) * (size_t)N);
     rr->code_of = (uint32_t*)malloc(sizeof(uint32_t) * (size_t)N);
-    rr->vmin = (float*)malloc(sizeof(float) * 2 * (size_t)M);
-    rr->vmax = (float*)malloc(sizeof(float) * 2 * (size_t)M);
-    rr->qb = (uint8_t*)malloc(2 * (size_t)M);
-    rr->count = (uint32_t*)malloc(sizeof(uint32_t) * 2 * (size_t)M);
+    rr->vmin = (float*)malloc(sizeof(float) * (size_t)B2);
+    rr->vmax = (float*)malloc(sizeof(float) * (size_t)B2);
+    rr->qb = (uint8_t*)malloc((size_t)B2);
+    rr->count = (uint32_t*)malloc(sizeof(uint32_t) * (size_t)B2);
     if (with_sums) {
-        rr->s_int = (uint64_t*)malloc(sizeof(uint64_t) * 17 * 2 * (size_t)M);
-        rr->e_int = (uint64_t*)malloc(sizeof(uint64_t) * 2 * (size_t)M);
-        rr->e_exp = (int32_t*)malloc(sizeof(int32_t) * 2 * (size_t)M);
+        rr->s_int = (uint64_t*)malloc(sizeof(uint64_t) * 17 * (size_t)B2);
+        rr->e_int = (uint64_t*)malloc(sizeof(uint64_t) * (size_t)B2);
+        rr->e_exp = (int32_t*)malloc(sizeof(int32_t) * (size_t)B2);
     }
 }
 
@@ -444,12 +455,14 @@ static void row_result_free(row_result* rr)
 
 /* ---- public: encode ---------------------------------------------------- */
 
-static int encode_common(const void* x, int dt, int64_t R, int64_t N, double keep, int M,
+static int encode_common(const void* x, int dt, int64_t R, int64_t N, double keep, int M, int Mn,
                          uint32_t bit_set, double beta, const uint8_t* ladder, int ds,
                          void* stream, void* meta, int n_threads)
 {
     int rc = check_args(dt, R, N, keep, M, bit_set);
     if (rc) return rc;
+    if (Mn < 1 || Mn > 128) return -1;
+    const int B2 = M + Mn;
     if (!x || !stream || !meta) return -1;
     if (!(beta >= 0.0)) return -1;
 
@@ -458,7 +471,7 @@ static int encode_common(const void* x, int dt, int64_t R, int64_t N, double kee
     const size_t esz = dt == SLICER_REF_F32 ? 4 : 2;
     const uint64_t cap_words = ((uint64_t)k * (uint64_t)(w + max_bit(bit_set)) + 31) / 32;
     uint8_t* mt = (uint8_t*)meta;
-    memset(mt, 0, meta_size(R, M));
+    memset(mt, 0, meta_size(R, B2));
 
     /* per-row segments go to private buffers first; offsets need all rows */
     uint32_t** seg = (uint32_t**)calloc((size_t)R, sizeof(uint32_t*));
@@ -471,21 +484,21 @@ static int encode_common(const void* x, int dt, int64_t R, int64_t N, double kee
 #endif
     for (int64_t r = 0; r < R; ++r) {
         row_result rr;
-        row_result_alloc(&rr, N, M, 0);
+        row_result_alloc(&rr, N, B2, 0);
         uint32_t* idxbuf = (uint32_t*)malloc(sizeof(uint32_t) * (size_t)(k > 0 ? k : 1));
         seg[r] = (uint32_t*)calloc((size_t)(cap_words > 0 ? cap_words : 1), 4);
         const void* xr = (const char*)x + (size_t)r * (size_t)N * esz;
-        if (analyze_row(xr, dt, N, k, M, bit_set, beta, ladder, ds, &rr) != 0) {
+        if (analyze_row(xr, dt, N, k, M, Mn, bit_set, beta, ladder, ds, &rr) != 0) {
             fail = 1;
         } else {
-            seg_words[r] = pack_row(&rr, N, M, w, seg[r], idxbuf);
-            put_u32(mt + off_npos(R, M) + 4 * (size_t)r, rr.n_pos);
-            put_u32(mt + off_nneg(R, M) + 4 * (size_t)r, rr.n_neg);
-            for (int b = 0; b < 2 * M; ++b) {
-                size_t e = (size_t)r * 2 * M + b;
-                memcpy(mt + off_vmin(R, M) + 4 * e, &rr.vmin[b], 4);
-                memcpy(mt + off_vmax(R, M) + 4 * e, &rr.vmax[b], 4);
-                mt[off_q(R, M) + e] = rr.qb[b];
+            seg_words[r] = pack_row(&rr, N, B2, w, seg[r], idxbuf);
+            put_u32(mt + off_npos(R, B2) + 4 * (size_t)r, rr.n_pos);
+            put_u32(mt + off_nneg(R, B2) + 4 * (size_t)r, rr.n_neg);
+            for (int b = 0; b < B2; ++b) {
+                size_t e = (size_t)r * B2 + b;
+                memcpy(mt + off_vmin(R, B2) + 4 * e, &rr.vmin[b], 4);
+                memcpy(mt + off_vmax(R, B2) + 4 * e, &rr.vmax[b], 4);
+                mt[off_q(R, B2) + e] = rr.qb[b];
             }
         }
         free(idxbuf);
@@ -495,7 +508,7 @@ static int encode_common(const void* x, int dt, int64_t R, int64_t N, double kee
     uint64_t total = 0;
     uint32_t* out = (uint32_t*)stream;
     for (int64_t r = 0; r < R; ++r) {
-        put_u64(mt + off_rowoff(R, M) + 8 * (size_t)r, total);
+        put_u64(mt + off_rowoff(R, B2) + 8 * (size_t)r, total);
         if (seg[r]) memcpy(out + total, seg[r], (size_t)seg_words[r] * 4);
         total += seg_words[r];
         free(seg[r]);
@@ -513,14 +526,21 @@ static int encode_common(const void* x, int dt, int64_t R, int64_t N, double kee
     put_u32(mt + 40, bit_set);
     put_u32(mt + 44, (uint32_t)w);
     put_u64(mt + 48, total);
-    put_u64(mt + 56, 0);
+    put_u32(mt + 56, Mn != M ? (uint32_t)Mn : 0u);   /* 0: M(-) = M(+) */
+    put_u32(mt + 60, 0);
     return fail ? -3 : 0;
 }
 
 int slicer_ref_encode(const void* x, int dt, int64_t R, int64_t N, double keep, int M,
                       uint32_t bit_set, double beta, void* stream, void* meta, int n_threads)
 {
-    return encode_common(x, dt, R, N, keep, M, bit_set, beta, NULL, 0, stream, meta, n_threads);
+    return encode_common(x, dt, R, N, keep, M, M, bit_set, beta, NULL, 0, stream, meta, n_threads);
+}
+
+int slicer_ref_encode_pn(const void* x, int dt, int64_t R, int64_t N, double keep, int M, int Mn,
+                         uint32_t bit_set, double beta, void* stream, void* meta, int n_threads)
+{
+    return encode_common(x, dt, R, N, keep, M, Mn, bit_set, beta, NULL, 0, stream, meta, n_threads);
 }
 
 /* set of the ladder's bitwidths; 0 if an entry is outside 1..16 */
@@ -540,13 +560,13 @@ int slicer_ref_encode_ladder(const void* x, int dt, int64_t R, int64_t N, double
     if (!ladder || M < 1 || M > 64) return -1;
     uint32_t bs = ladder_bit_set(ladder, M);
     if (!bs) return -1;
-    return encode_common(x, dt, R, N, keep, M, bs, 0.0, ladder, 0, stream, meta, n_threads);
+    return encode_common(x, dt, R, N, keep, M, M, bs, 0.0, ladder, 0, stream, meta, n_threads);
 }
 
 int slicer_ref_encode_ds(const void* x, int dt, int64_t R, int64_t N, double keep, int M,
                          uint32_t bit_set, double delta, void* stream, void* meta, int n_threads)
 {
-    return encode_common(x, dt, R, N, keep, M, bit_set, delta, NULL, 1, stream, meta, n_threads);
+    return encode_common(x, dt, R, N, keep, M, M, bit_set, delta, NULL, 1, stream, meta, n_threads);
 }
 
 /* Sec. 3.3: value bits with every block at q_bit = max(bit_set), index bits, header bits.
@@ -564,7 +584,7 @@ int slicer_ref_bound(int dt, int64_t R, int64_t N, double keep, int M, uint32_t 
     const uint64_t pad = (32 - row_bits % 32) % 32;
     if (value_bits) *value_bits = (uint64_t)R * k * qb;
     if (idx_bits) *idx_bits = (uint64_t)R * k * w;
-    if (header_bits) *header_bits = 8 * (uint64_t)meta_size(R, M) + (uint64_t)R * pad;
+    if (header_bits) *header_bits = 8 * (uint64_t)meta_size(R, 2 * M) + (uint64_t)R * pad;
     return 0;
 }
 
@@ -577,6 +597,8 @@ int slicer_ref_decode(const void* stream, const void* meta, void* y, int n_threa
     if (get_u32(mt) != REF_MAGIC || get_u32(mt + 4) != REF_VERSION) return -1;
     const int dt = (int)get_u32(mt + 8);
     const int M = (int)get_u32(mt + 12);
+    const int Mn = get_u32(mt + 56) ? (int)get_u32(mt + 56) : M;      /* 0: M(-) = M(+) */
+    const int B2 = M + Mn;
     const int64_t R = (int64_t)get_u64(mt + 16);
     const int64_t N = (int64_t)get_u64(mt + 24);
     const int w = (int)get_u32(mt + 44);
@@ -590,22 +612,23 @@ int slicer_ref_decode(const void* stream, const void* meta, void* y, int n_threa
 #pragma omp parallel for schedule(dynamic, 1) num_threads(n_threads)
 #endif
     for (int64_t r = 0; r < R; ++r) {
-        const uint32_t* rw = words + get_u64(mt + off_rowoff(R, M) + 8 * (size_t)r);
-        const uint32_t n_cls[2] = { get_u32(mt + off_npos(R, M) + 4 * (size_t)r),
-                                    get_u32(mt + off_nneg(R, M) + 4 * (size_t)r) };
+        const uint32_t* rw = words + get_u64(mt + off_rowoff(R, B2) + 8 * (size_t)r);
+        const uint32_t n_cls[2] = { get_u32(mt + off_npos(R, B2) + 4 * (size_t)r),
+                                    get_u32(mt + off_nneg(R, B2) + 4 * (size_t)r) };
         const uint64_t n = (uint64_t)n_cls[0] + n_cls[1];
         uint64_t ipos = 0;              /* bit cursor in the index section */
         uint64_t cpos = n * (uint64_t)w; /* bit cursor in the code section */
         for (int s = 0; s < 2; ++s) {
-            uint32_t K = n_cls[s] / (uint32_t)M, start = 0;
-            for (int m = 0; m < M; ++m) {
-                uint32_t cnt = (m < M - 1) ? K : n_cls[s] - start;
+            const int Ms = s ? Mn : M;
+            uint32_t K = n_cls[s] / (uint32_t)Ms, start = 0;
+            for (int m = 0; m < Ms; ++m) {
+                uint32_t cnt = (m < Ms - 1) ? K : n_cls[s] - start;
                 start += cnt;
-                size_t e = (size_t)r * 2 * M + (size_t)(s * M + m);
+                size_t e = (size_t)r * B2 + (size_t)(s * M + m);
                 float vmin, vmax;
-                memcpy(&vmin, mt + off_vmin(R, M) + 4 * e, 4);
-                memcpy(&vmax, mt + off_vmax(R, M) + 4 * e, 4);
-                int q = mt[off_q(R, M) + e] & 0x7F;
+                memcpy(&vmin, mt + off_vmin(R, B2) + 4 * e, 4);
+                memcpy(&vmax, mt + off_vmax(R, B2) + 4 * e, 4);
+                int q = mt[off_q(R, B2) + e] & 0x7F;
                 float L = (float)((1u << q) - 1u);
                 float o = (vmax - vmin) / L;
                 for (uint32_t j = 0; j < cnt; ++j) {
@@ -635,8 +658,8 @@ int slicer_ref_analyze_row(const void* x_row, int dt, int64_t N, double keep, in
     if (rc) return rc;
     if (!x_row || !(beta >= 0.0)) return -1;
     row_result rr;
-    row_result_alloc(&rr, N, M, 1);
-    rc = analyze_row(x_row, dt, N, keep_count(keep, N), M, bit_set, beta, NULL, 0, &rr);
+    row_result_alloc(&rr, N, 2 * M, 1);
+    rc = analyze_row(x_row, dt, N, keep_count(keep, N), M, M, bit_set, beta, NULL, 0, &rr);
     if (rc == 0) {
         if (block_of) memcpy(block_of, rr.block_of, sizeof(int32_t) * (size_t)N);
         if (code_of) memcpy(code_of, rr.code_of, sizeof(uint32_t) * (size_t)N);

@@ -56,6 +56,16 @@ int slicer_ref_bound(int dtype, int64_t rows, int64_t row_len, double keep_ratio
                      uint32_t bit_set, uint64_t* value_bits, uint64_t* index_bits,
                      uint64_t* header_bits);
 
+/* Separate block counts per sign class (Sec. 3.3 lists M(+) and M(-) as two knobs):
+ * n_blocks blocks for the positive class, n_blocks_neg for the negative one.  Block order in
+ * meta and stream: +0..+M-1, -0..-M(-)-1.  slicer_ref_encode is the case n_blocks_neg = n_blocks. */
+int slicer_ref_sizes_pn(int dtype, int64_t rows, int64_t row_len, double keep_ratio,
+                        int n_blocks, int n_blocks_neg, uint32_t bit_set,
+                        size_t* stream_capacity_bytes, size_t* meta_bytes);
+int slicer_ref_encode_pn(const void* x, int dtype, int64_t rows, int64_t row_len,
+                         double keep_ratio, int n_blocks, int n_blocks_neg, uint32_t bit_set,
+                         double distortion_budget, void* stream, void* meta, int n_threads);
+
 /* Decode into dense y (same dtype and shape as the encoded tensor). */
 int slicer_ref_decode(const void* stream, const void* meta, void* y, int n_threads);
 

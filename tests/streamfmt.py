@@ -16,20 +16,21 @@ def header(meta: np.ndarray) -> dict:
     u32 = lambda o: int(m[o:o + 4].view(np.uint32)[0])
     u64 = lambda o: int(m[o:o + 8].view(np.uint64)[0])
     return dict(magic=u32(0), version=u32(4), dtype=u32(8), M=u32(12), rows=u64(16), row_len=u64(24),
-                k=u64(32), bit_set=u32(40), w=u32(44), total_words=u64(48), reserved=u64(56))
+                k=u64(32), bit_set=u32(40), w=u32(44), total_words=u64(48), reserved=u64(56),
+                M_neg=u32(56) or u32(12))          # 0 at offset 56: the negative class has M blocks too
 
 
 def arrays(meta: np.ndarray) -> dict:
     h = header(meta)
-    R, M = h["rows"], h["M"]
+    R, B = h["rows"], h["M"] + h["M_neg"]          # B blocks per row: positive class first
     m = np.ascontiguousarray(meta, np.uint8)
     o = 64
     row_off = m[o:o + 8 * R].view(np.uint64); o += 8 * R
     n_pos = m[o:o + 4 * R].view(np.uint32); o += 4 * R
     n_neg = m[o:o + 4 * R].view(np.uint32); o += 4 * R
-    vmin = m[o:o + 8 * R * M].view(np.float32).reshape(R, 2 * M); o += 8 * R * M
-    vmax = m[o:o + 8 * R * M].view(np.float32).reshape(R, 2 * M); o += 8 * R * M
-    q = m[o:o + 2 * R * M].reshape(R, 2 * M); o += 2 * R * M
+    vmin = m[o:o + 4 * R * B].view(np.float32).reshape(R, B); o += 4 * R * B
+    vmax = m[o:o + 4 * R * B].view(np.float32).reshape(R, B); o += 4 * R * B
+    q = m[o:o + R * B].reshape(R, B); o += R * B
     size = (o + 7) // 8 * 8
     return dict(row_off=row_off, n_pos=n_pos, n_neg=n_neg, vmin=vmin, vmax=vmax, q=q, size=size)
 
@@ -52,8 +53,8 @@ def parse_row(stream: np.ndarray, meta: np.ndarray, r: int) -> dict:
     """Blocks of row r: list (2M entries) of (indices, codes), plus bit accounting."""
     h = header(meta)
     a = arrays(meta)
-    M, w = h["M"], h["w"]
-    sizes = block_sizes(int(a["n_pos"][r]), M) + block_sizes(int(a["n_neg"][r]), M)
+    w = h["w"]
+    sizes = block_sizes(int(a["n_pos"][r]), h["M"]) + block_sizes(int(a["n_neg"][r]), h["M_neg"])
     n = sum(sizes)
     words = np.ascontiguousarray(stream, np.uint32)[int(a["row_off"][r]):]
     ipos, cpos = 0, n * w

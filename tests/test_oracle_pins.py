@@ -555,3 +555,39 @@ def test_ds_limits_and_monotonicity(oracle, dtype):
     sizes = np.array([streamfmt.block_sizes(int(a["n_pos"][r]), M) + streamfmt.block_sizes(int(a["n_neg"][r]), M)
                       for r in range(wl.rows)])
     assert (a["q"][sizes >= 20] == 8).all()
+
+
+# ----------------------------------------------------------------------------
+# separate block counts for the two sign classes (Sec. 3.3 lists M(+) and M(-) as two knobs)
+# ----------------------------------------------------------------------------
+
+def test_pn_equals_single_count_when_equal(oracle):
+    wl = synth.vit_tokens(seed=6, rows=5)
+    a = oracle.encode(wl.x, wl.dtype, wl.keep_ratio, 5, B28, 1e-3)
+    b = oracle.encode_pn(wl.x, wl.dtype, wl.keep_ratio, 5, 5, B28, 1e-3)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("Mp,Mn", [(1, 4), (6, 2), (3, 8)])
+def test_pn_each_class_is_split_by_its_own_count(oracle, dtype, Mp, Mn):
+    """Blocks of a class depend only on that class's count: the positive blocks of (Mp, Mn) are those of
+    (Mp, Mp), the negative blocks those of (Mn, Mn) - ranges, bitwidths, indices and codes alike."""
+    wl = synth.vit_tokens(seed=8, rows=4) if dtype == "f32" else synth.llm_prefill(seed=8, rows=4)
+    s, m = oracle.encode_pn(wl.x, wl.dtype, wl.keep_ratio, Mp, Mn, B28, 1e-3)
+    sp, mp = oracle.encode(wl.x, wl.dtype, wl.keep_ratio, Mp, B28, 1e-3)
+    sn, mn = oracle.encode(wl.x, wl.dtype, wl.keep_ratio, Mn, B28, 1e-3)
+    h, a, ap, an = streamfmt.header(m), streamfmt.arrays(m), streamfmt.arrays(mp), streamfmt.arrays(mn)
+    assert (h["M"], h["M_neg"]) == (Mp, Mn) and a["q"].shape == (wl.rows, Mp + Mn)
+    assert m.size == (64 + 16 * wl.rows + 9 * wl.rows * (Mp + Mn) + 7) // 8 * 8
+    for name in ("vmin", "vmax", "q"):
+        assert np.array_equal(a[name][:, :Mp], ap[name][:, :Mp])
+        assert np.array_equal(a[name][:, Mp:], an[name][:, Mn:])
+    assert np.array_equal(a["n_pos"], ap["n_pos"]) and np.array_equal(a["n_neg"], an["n_neg"])
+    for r in range(wl.rows):
+        pr, prp, prn = streamfmt.parse_row(s, m, r), streamfmt.parse_row(sp, mp, r), streamfmt.parse_row(sn, mn, r)
+        assert pr["blocks"][:Mp] == prp["blocks"][:Mp] and pr["blocks"][Mp:] == prn["blocks"][Mn:]
+        assert pr["words"] == int((a["row_off"][r + 1] if r + 1 < wl.rows else h["total_words"]) - a["row_off"][r])
+    # the decoded tensor: positive values as in (Mp, Mp), negative values as in (Mn, Mn)
+    y, yp, yn = (f32(oracle.decode(*t), dtype) for t in ((s, m), (sp, mp), (sn, mn)))
+    assert np.array_equal(y, np.where(yp > 0, yp, 0) + np.where(yn < 0, yn, 0))
