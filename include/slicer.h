@@ -32,10 +32,11 @@
  *           each), least-significant bit first, padded with zeros to a word.
  *   meta    0 u32 magic 0x52434C53   4 u32 version   8 u32 dtype   12 u32 M
  *           16 u64 rows   24 u64 row_len   32 u64 k   40 u32 bit_set   44 u32 w
- *           48 u64 total_words   56 u64 0
+ *           48 u64 total_words   56 u32 M(-) if the negative class has its own block count
+ *           (0: it has M blocks too)   60 u32 0
  *           then  u64 row_word_off[R], u32 n_pos[R], u32 n_neg[R],
- *                 f32 vmin[R][2M], f32 vmax[R][2M], u8 q[R][2M] (bit 7: no bitwidth
- *                 met the budget, the largest was used), padded to 8 bytes.
+ *                 f32 vmin[R][B], f32 vmax[R][B], u8 q[R][B] with B = M + M(-) blocks per row
+ *                 (bit 7 of q: no bitwidth met the budget, the largest was used), padded to 8 bytes.
  */
 #ifndef SLICER_H
 #define SLICER_H
@@ -108,6 +109,29 @@ int slicer_decode(const void* stream, const void* meta, void* y, void* hip_strea
  */
 int slicer_decode_as(const void* stream, const void* meta, void* y, slicer_dtype dt,
                      int64_t rows, int64_t row_len, int n_blocks, void* hip_stream);
+
+/*
+ * Separate block counts for the two sign classes (Sec. 3.3 lists M(+) and M(-) as two knobs of
+ * the configuration): n_blocks blocks for the positive class, n_blocks_neg for the negative
+ * one, each in [1, SLICER_MAX_BLOCKS].  Block order in meta and stream: +0..+M-1, then
+ * -0..-M(-)-1; meta holds n_blocks + n_blocks_neg entries per row (meta_bytes = 64 + 16 rows +
+ * 9 rows (n_blocks + n_blocks_neg), rounded up to 8), and header offset 56 holds n_blocks_neg
+ * when it differs from n_blocks (0 otherwise, so equal counts give the bytes of slicer_encode).
+ * slicer_decode reads both counts from the header.  Everything else as the calls without _pn.
+ */
+int slicer_sizes_pn(slicer_dtype dt, int64_t rows, int64_t row_len, double keep_ratio,
+                    int n_blocks, int n_blocks_neg, uint32_t bit_set,
+                    size_t* stream_capacity_bytes, size_t* meta_bytes, size_t* workspace_bytes);
+int slicer_encode_pn(const void* x, slicer_dtype dt, int64_t rows, int64_t row_len,
+                     double keep_ratio, int n_blocks, int n_blocks_neg, uint32_t bit_set,
+                     double distortion_budget,
+                     void* stream, void* meta, void* workspace, void* hip_stream);
+int slicer_decode_as_pn(const void* stream, const void* meta, void* y, slicer_dtype dt,
+                        int64_t rows, int64_t row_len, int n_blocks, int n_blocks_neg,
+                        void* hip_stream);
+int slicer_check_pn(const void* meta, uint64_t stream_words, slicer_dtype dt, int64_t rows,
+                    int64_t row_len, int n_blocks, int n_blocks_neg, void* scratch,
+                    void* hip_stream);
 
 /*
  * Encode with the paper's own guard (Sec. 3.2.1, Eq. "DS", "greedily lowers the bit precision q

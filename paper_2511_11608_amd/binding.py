@@ -44,6 +44,14 @@ def load() -> C.CDLL:
         L.slicer_encode_path.argtypes = [cint, i64, i64, dbl, cint, u32]
         L.slicer_encode.restype = cint
         L.slicer_encode.argtypes = [vp, cint, i64, i64, dbl, cint, u32, dbl, vp, vp, vp, vp]
+        L.slicer_sizes_pn.restype = cint
+        L.slicer_sizes_pn.argtypes = [cint, i64, i64, dbl, cint, cint, u32, szp, szp, szp]
+        L.slicer_encode_pn.restype = cint
+        L.slicer_encode_pn.argtypes = [vp, cint, i64, i64, dbl, cint, cint, u32, dbl, vp, vp, vp, vp]
+        L.slicer_decode_as_pn.restype = cint
+        L.slicer_decode_as_pn.argtypes = [vp, vp, vp, cint, i64, i64, cint, cint, vp]
+        L.slicer_check_pn.restype = cint
+        L.slicer_check_pn.argtypes = [vp, C.c_uint64, cint, i64, i64, cint, cint, vp, vp]
         L.slicer_encode_ds.restype = cint
         L.slicer_encode_ds.argtypes = L.slicer_encode.argtypes
         L.slicer_encode_ladder.restype = cint
@@ -121,6 +129,46 @@ def slicer_encode(x: torch.Tensor, keep_ratio: float, n_blocks: int, bit_set: in
     _check("slicer_encode", load().slicer_encode(
         x.data_ptr(), _dt_of(x), rows, row_len, keep_ratio, n_blocks, bit_set, distortion_budget,
         stream_buf.data_ptr(), meta.data_ptr(), workspace.data_ptr(), _stream_handle(stream)))
+
+
+def alloc_buffers_pn(x: torch.Tensor, keep_ratio: float, n_blocks: int, n_blocks_neg: int, bit_set: int):
+    """Device buffers for separate block counts of the two sign classes."""
+    rows, row_len = x.shape
+    a, b, c = C.c_size_t(0), C.c_size_t(0), C.c_size_t(0)
+    _check("slicer_sizes_pn", load().slicer_sizes_pn(_dt_of(x), rows, row_len, keep_ratio, n_blocks, n_blocks_neg,
+                                                    bit_set, C.byref(a), C.byref(b), C.byref(c)))
+    dev = x.device
+    return (torch.empty(max(a.value // 4, 1), dtype=torch.int32, device=dev),
+            torch.empty(b.value, dtype=torch.uint8, device=dev),
+            torch.empty(max(c.value, 256), dtype=torch.uint8, device=dev))
+
+
+def slicer_encode_pn(x: torch.Tensor, keep_ratio: float, n_blocks: int, n_blocks_neg: int, bit_set: int,
+                     distortion_budget: float, stream_buf: torch.Tensor, meta: torch.Tensor, workspace: torch.Tensor,
+                     stream=None) -> None:
+    """slicer_encode with n_blocks blocks for the positive and n_blocks_neg for the negative class."""
+    if not x.is_cuda or not x.is_contiguous() or x.dim() != 2:
+        raise ValueError("x must be a contiguous 2-D tensor on the GPU")
+    rows, row_len = x.shape
+    _check("slicer_encode_pn", load().slicer_encode_pn(
+        x.data_ptr(), _dt_of(x), rows, row_len, keep_ratio, n_blocks, n_blocks_neg, bit_set, distortion_budget,
+        stream_buf.data_ptr(), meta.data_ptr(), workspace.data_ptr(), _stream_handle(stream)))
+
+
+def slicer_decode_as_pn(stream_buf: torch.Tensor, meta: torch.Tensor, y: torch.Tensor, n_blocks: int,
+                        n_blocks_neg: int, stream=None) -> None:
+    rows, row_len = y.shape
+    _check("slicer_decode_as_pn", load().slicer_decode_as_pn(stream_buf.data_ptr(), meta.data_ptr(), y.data_ptr(),
+                                                            _dt_of(y), rows, row_len, n_blocks, n_blocks_neg,
+                                                            _stream_handle(stream)))
+
+
+def slicer_check_pn(meta: torch.Tensor, stream_words: int, y_like: torch.Tensor, n_blocks: int, n_blocks_neg: int,
+                    stream=None) -> None:
+    rows, row_len = y_like.shape
+    scratch = torch.empty(64, dtype=torch.int32, device=meta.device)
+    _check("slicer_check_pn", load().slicer_check_pn(meta.data_ptr(), stream_words, _dt_of(y_like), rows, row_len,
+                                                    n_blocks, n_blocks_neg, scratch.data_ptr(), _stream_handle(stream)))
 
 
 def slicer_encode_ds(x: torch.Tensor, keep_ratio: float, n_blocks: int, bit_set: int, delta: float,

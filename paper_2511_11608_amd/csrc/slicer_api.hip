@@ -71,8 +71,9 @@ struct Plan {
 
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
-Plan make_plan(int dt, int64_t rows, int64_t row_len, double keep_ratio, int n_blocks, uint32_t bit_set)
+Plan make_plan(int dt, int64_t rows, int64_t row_len, double keep_ratio, int n_blocks, int n_blocks_neg, uint32_t bit_set)
 {
+    const int B2_all = n_blocks + n_blocks_neg;          // blocks per row
     Plan p;
     p.k = (int64_t)std::floor(keep_ratio * (double)row_len);   // ATKF: k = floor((1-s) N)
     p.w = index_bits(row_len);
@@ -97,7 +98,7 @@ Plan make_plan(int dt, int64_t rows, int64_t row_len, double keep_ratio, int n_b
         int nq_l = 0;
         for (int q = 1; q <= 16; ++q) nq_l += (bit_set >> q) & 1u;
         if (row_len >= 32768 && row_len % epc_l == 0 && C <= 1024 && rows <= 65535 && capL < ((int64_t)1 << 27)) {
-            const size_t R = (size_t)rows, B2 = 2 * (size_t)n_blocks;
+            const size_t R = (size_t)rows, B2 = (size_t)B2_all;
             p.large_C = (int)C; p.large_capL = (u32)capL; p.large_LC = (int)((capL + kLCE - 1) / kLCE);
             p.lo_ch_cum = o;    o = align256(o + 4 * R * (size_t)C * kLBins);
             p.lo_ch_off = o;    o = align256(o + 4 * R * (size_t)C);
@@ -125,14 +126,14 @@ Plan make_plan(int dt, int64_t rows, int64_t row_len, double keep_ratio, int n_b
     const int64_t max_n = dt == SLICER_F32 ? 2048 : 8192;
     int nq = 0;
     for (int q = 1; q <= 16; ++q) nq += (bit_set >> q) & 1u;
-    if (row_len % epc == 0 && row_len <= max_n && 2 * n_blocks <= kWave) {
+    if (row_len % epc == 0 && row_len <= max_n && B2_all <= kWave) {
         const int64_t margin = std::max<int64_t>(64, row_len / (dt == SLICER_F32 ? 16 : 32));  // room for the undecided coarse bin
         int64_t cap = std::min<int64_t>(1984, (p.k + margin + 63) / 64 * 64);   // ranks are 11-bit fields
         int epl = epc;
         while ((int64_t)epl * kWave < row_len) epl *= 2;
         const int maxs = cap <= 640 ? 10 : cap <= 1280 ? 20 : 0;             // list held in registers
-        const int64_t region0 = small_region0_words(p.k, p.cap_words, 2 * n_blocks, nq);
-        const int64_t lds = 4 * (int64_t)small_lds_words(dt, (int)cap, (int)region0, 2 * n_blocks, maxs);
+        const int64_t region0 = small_region0_words(p.k, p.cap_words, B2_all, nq);
+        const int64_t lds = 4 * (int64_t)small_lds_words(dt, (int)cap, (int)region0, B2_all, maxs);
         if (p.k + 64 <= cap && lds <= 64 * 1024) {
             p.small_epl = epl; p.small_cap = (int)cap; p.small_region0 = (int)region0; p.small_lds_bytes = (int)lds;
             p.small_maxs = maxs;
@@ -211,14 +212,14 @@ int launch_encode(const EncArgs& ea, hipStream_t st)
 }
 
 int launch_decode(const void* stream, const void* meta, void* y, int dt, int64_t rows, int64_t row_len,
-                  int n_blocks, hipStream_t st)
+                  int n_blocks, int n_blocks_neg, hipStream_t st)
 {
     DecArgs da;
     da.stream = (const u32*)stream;
     da.y = y;
-    da.R = rows; da.N = row_len; da.M = n_blocks; da.w = index_bits(row_len);
+    da.R = rows; da.N = row_len; da.M = n_blocks; da.Mn = n_blocks_neg; da.w = index_bits(row_len);
     da.chunks_per_row = (int)((row_len + kDecChunk - 1) / kDecChunk);
-    da.mv = meta_view(const_cast<void*>(meta), rows, n_blocks);
+    da.mv = meta_view(const_cast<void*>(meta), rows, n_blocks + n_blocks_neg);
     da.total_words = (const u64*)meta + 6;
     // the stream segment of a row at keep ratios up to about 0.2 (longer segments are read from global memory)
     da.stage_words = (int)std::min<int64_t>(1020, (row_len / 16 + 3) / 4 * 4);
@@ -228,7 +229,7 @@ int launch_decode(const void* stream, const void* meta, void* y, int dt, int64_t
     if (timed) SLICER_HIP(hipEventRecord(g_ev_start, st));
     // short rows: one wavefront per row, the row assembled in LDS (16 KB per wave at most)
     const int64_t row_bytes = row_len * (dt == SLICER_F32 ? 4 : 2);
-    if (row_bytes % 16 == 0 && row_bytes <= 16 * 1024 && 2 * n_blocks <= kWave && ((uintptr_t)y & 15) == 0) {
+    if (row_bytes % 16 == 0 && row_bytes <= 16 * 1024 && n_blocks + n_blocks_neg <= kWave && ((uintptr_t)y & 15) == 0) {
         // one wave per workgroup: the LDS of a row (image + stream segment) is the unit of occupancy
         const size_t lds = (size_t)row_bytes + 16 * (size_t)((da.stage_words + 4) / 4);
         if (dt == SLICER_F32)
@@ -249,17 +250,26 @@ int launch_decode(const void* stream, const void* meta, void* y, int dt, int64_t
 
 extern "C" {
 
+int slicer_sizes_pn(slicer_dtype dt, int64_t rows, int64_t row_len, double keep_ratio, int n_blocks,
+                    int n_blocks_neg, uint32_t bit_set, size_t* stream_capacity_bytes, size_t* meta_bytes_out,
+                    size_t* workspace_bytes)
+{
+    int rc = check_args((int)dt, rows, row_len, keep_ratio, n_blocks, bit_set);
+    if (rc) return rc;
+    if (n_blocks_neg < 1 || n_blocks_neg > SLICER_MAX_BLOCKS) return SLICER_EINVAL;
+    Plan p = make_plan((int)dt, rows, row_len, keep_ratio, n_blocks, n_blocks_neg, bit_set);
+    if (stream_capacity_bytes) *stream_capacity_bytes = (size_t)(p.cap_words * 4ull * (u64)rows);
+    if (meta_bytes_out) *meta_bytes_out = meta_bytes(rows, n_blocks + n_blocks_neg);
+    if (workspace_bytes) *workspace_bytes = p.total;
+    return SLICER_OK;
+}
+
 int slicer_sizes(slicer_dtype dt, int64_t rows, int64_t row_len, double keep_ratio, int n_blocks,
                  uint32_t bit_set, size_t* stream_capacity_bytes, size_t* meta_bytes_out,
                  size_t* workspace_bytes)
 {
-    int rc = check_args((int)dt, rows, row_len, keep_ratio, n_blocks, bit_set);
-    if (rc) return rc;
-    Plan p = make_plan((int)dt, rows, row_len, keep_ratio, n_blocks, bit_set);
-    if (stream_capacity_bytes) *stream_capacity_bytes = (size_t)(p.cap_words * 4ull * (u64)rows);
-    if (meta_bytes_out) *meta_bytes_out = meta_bytes(rows, n_blocks);
-    if (workspace_bytes) *workspace_bytes = p.total;
-    return SLICER_OK;
+    return slicer_sizes_pn(dt, rows, row_len, keep_ratio, n_blocks, n_blocks, bit_set, stream_capacity_bytes,
+                           meta_bytes_out, workspace_bytes);
 }
 
 int slicer_encode_path(slicer_dtype dt, int64_t rows, int64_t row_len, double keep_ratio, int n_blocks,
@@ -267,12 +277,12 @@ int slicer_encode_path(slicer_dtype dt, int64_t rows, int64_t row_len, double ke
 {
     int rc = check_args((int)dt, rows, row_len, keep_ratio, n_blocks, bit_set);
     if (rc) return rc;
-    Plan p = make_plan((int)dt, rows, row_len, keep_ratio, n_blocks, bit_set);
+    Plan p = make_plan((int)dt, rows, row_len, keep_ratio, n_blocks, n_blocks, bit_set);
     return p.small_epl ? 1 : (p.large_C ? 2 : 0);
 }
 
 static int encode_impl(const void* x, slicer_dtype dt, int64_t rows, int64_t row_len, double keep_ratio,
-                       int n_blocks, uint32_t bit_set, double distortion_budget, const Ladder& lad, int guard,
+                       int n_blocks, int n_blocks_neg, uint32_t bit_set, double distortion_budget, const Ladder& lad, int guard,
                        void* stream, void* meta, void* workspace, void* hip_stream)
 {
     int rc = check_args((int)dt, rows, row_len, keep_ratio, n_blocks, bit_set);
@@ -280,14 +290,15 @@ static int encode_impl(const void* x, slicer_dtype dt, int64_t rows, int64_t row
     if (!x || !stream || !meta || !workspace) return SLICER_EINVAL;
     if (!(distortion_budget >= 0.0)) return SLICER_EINVAL;
     if (rows >= ((int64_t)1 << 31)) return SLICER_EINVAL;
+    if (n_blocks_neg < 1 || n_blocks_neg > SLICER_MAX_BLOCKS) return SLICER_EINVAL;
     hipStream_t st = (hipStream_t)hip_stream;
-    Plan p = make_plan((int)dt, rows, row_len, keep_ratio, n_blocks, bit_set);
+    Plan p = make_plan((int)dt, rows, row_len, keep_ratio, n_blocks, n_blocks_neg, bit_set);
     char* ws = (char*)workspace;
 
     EncArgs ea;
     ea.x = x;
     ea.R = rows; ea.N = row_len; ea.k = p.k;
-    ea.M = n_blocks; ea.w = p.w;
+    ea.M = n_blocks; ea.Mn = n_blocks_neg; ea.w = p.w;
     ea.nq = 0;
     for (int q = 1; q <= 16; ++q)
         if ((bit_set >> q) & 1u) ea.qlist[ea.nq++] = q;
@@ -299,7 +310,7 @@ static int encode_impl(const void* x, slicer_dtype dt, int64_t rows, int64_t row
     ea.kept = (u64*)(ws + p.off_kept);
     ea.bo_idx = (u32*)(ws + p.off_bo_idx);
     ea.bo_val = (u32*)(ws + p.off_bo_val);
-    ea.mv = meta_view(meta, rows, n_blocks);
+    ea.mv = meta_view(meta, rows, n_blocks + n_blocks_neg);
     ea.only_flagged = nullptr;
     ea.rows_per_wg = 1;
     ea.lad = lad;
@@ -309,7 +320,7 @@ static int encode_impl(const void* x, slicer_dtype dt, int64_t rows, int64_t row
         // fast path; rows it cannot hold are flagged and redone by the generic kernel
         SmallArgs sa;
         sa.x = x; sa.R = rows; sa.N = row_len; sa.k = p.k;
-        sa.M = n_blocks; sa.w = p.w; sa.nq = ea.nq;
+        sa.M = n_blocks; sa.Mn = n_blocks_neg; sa.w = p.w; sa.nq = ea.nq;
         for (int t = 0; t < kMaxQ; ++t) sa.qlist[t] = ea.qlist[t];
         sa.beta = distortion_budget;
         sa.cap_words = p.cap_words;
@@ -330,7 +341,7 @@ static int encode_impl(const void* x, slicer_dtype dt, int64_t rows, int64_t row
         // long rows: multi-workgroup stages; rows they cannot hold are flagged for the generic kernel
         LargeArgs la;
         la.x = x; la.R = rows; la.N = row_len; la.k = p.k;
-        la.M = n_blocks; la.w = p.w; la.nq = ea.nq;
+        la.M = n_blocks; la.Mn = n_blocks_neg; la.w = p.w; la.nq = ea.nq;
         for (int t = 0; t < kMaxQ; ++t) la.qlist[t] = ea.qlist[t];
         la.beta = distortion_budget; la.cap_words = p.cap_words;
         la.C = p.large_C; la.LC = p.large_LC; la.capL = p.large_capL;
@@ -362,7 +373,7 @@ static int encode_impl(const void* x, slicer_dtype dt, int64_t rows, int64_t row
 
     FinishArgs fa;
     fa.R = rows; fa.N = row_len; fa.k = p.k;
-    fa.M = n_blocks; fa.w = p.w; fa.dt = (int)dt;
+    fa.M = n_blocks; fa.Mn = n_blocks_neg; fa.w = p.w; fa.dt = (int)dt;
     fa.bit_set = bit_set;
     fa.row_words = ea.row_words;
     fa.row_off_local = (u64*)(ws + p.off_row_local);
@@ -397,7 +408,18 @@ int slicer_encode(const void* x, slicer_dtype dt, int64_t rows, int64_t row_len,
     Ladder none;
     none.on = 0;
     for (int j = 0; j < kMaxBlocks / 8; ++j) none.nib[j] = 0;
-    return encode_impl(x, dt, rows, row_len, keep_ratio, n_blocks, bit_set, distortion_budget, none, 0,
+    return encode_impl(x, dt, rows, row_len, keep_ratio, n_blocks, n_blocks, bit_set, distortion_budget, none, 0,
+                       stream, meta, workspace, hip_stream);
+}
+
+int slicer_encode_pn(const void* x, slicer_dtype dt, int64_t rows, int64_t row_len, double keep_ratio,
+                     int n_blocks, int n_blocks_neg, uint32_t bit_set, double distortion_budget, void* stream,
+                     void* meta, void* workspace, void* hip_stream)
+{
+    Ladder none;
+    none.on = 0;
+    for (int j = 0; j < kMaxBlocks / 8; ++j) none.nib[j] = 0;
+    return encode_impl(x, dt, rows, row_len, keep_ratio, n_blocks, n_blocks_neg, bit_set, distortion_budget, none, 0,
                        stream, meta, workspace, hip_stream);
 }
 
@@ -408,7 +430,7 @@ int slicer_encode_ds(const void* x, slicer_dtype dt, int64_t rows, int64_t row_l
     Ladder none;
     none.on = 0;
     for (int j = 0; j < kMaxBlocks / 8; ++j) none.nib[j] = 0;
-    return encode_impl(x, dt, rows, row_len, keep_ratio, n_blocks, bit_set, delta, none, 1,
+    return encode_impl(x, dt, rows, row_len, keep_ratio, n_blocks, n_blocks, bit_set, delta, none, 1,
                        stream, meta, workspace, hip_stream);
 }
 
@@ -437,7 +459,7 @@ int slicer_encode_ladder(const void* x, slicer_dtype dt, int64_t rows, int64_t r
         for (int q = 1; q < ladder[m]; ++q) t += (bit_set >> q) & 1u;
         lad.nib[m >> 3] |= t << ((m & 7) * 4);
     }
-    return encode_impl(x, dt, rows, row_len, keep_ratio, n_blocks, bit_set, 0.0, lad, 0, stream, meta, workspace,
+    return encode_impl(x, dt, rows, row_len, keep_ratio, n_blocks, n_blocks, bit_set, 0.0, lad, 0, stream, meta, workspace,
                        hip_stream);
 }
 
@@ -446,21 +468,28 @@ int slicer_bound(slicer_dtype dt, int64_t rows, int64_t row_len, double keep_rat
 {
     int rc = check_args((int)dt, rows, row_len, keep_ratio, n_blocks, bit_set);
     if (rc) return rc;
-    const Plan p = make_plan((int)dt, rows, row_len, keep_ratio, n_blocks, bit_set);
+    const Plan p = make_plan((int)dt, rows, row_len, keep_ratio, n_blocks, n_blocks, bit_set);
     const u64 R = (u64)rows, k = (u64)p.k;
     if (value_bits) *value_bits = R * k * (u64)p.qmax;
     if (index_bits_out) *index_bits_out = R * k * (u64)p.w;
-    if (header_bits) *header_bits = 8ull * (u64)meta_bytes(rows, n_blocks) + R * (32ull * p.cap_words - k * (u64)(p.w + p.qmax));
+    if (header_bits) *header_bits = 8ull * (u64)meta_bytes(rows, 2 * n_blocks) + R * (32ull * p.cap_words - k * (u64)(p.w + p.qmax));
     return SLICER_OK;
+}
+
+int slicer_decode_as_pn(const void* stream, const void* meta, void* y, slicer_dtype dt, int64_t rows,
+                        int64_t row_len, int n_blocks, int n_blocks_neg, void* hip_stream)
+{
+    int rc = check_shape((int)dt, rows, row_len, n_blocks);
+    if (rc) return rc;
+    if (n_blocks_neg < 1 || n_blocks_neg > SLICER_MAX_BLOCKS) return SLICER_EINVAL;
+    if (!stream || !meta || !y) return SLICER_EINVAL;
+    return launch_decode(stream, meta, y, (int)dt, rows, row_len, n_blocks, n_blocks_neg, (hipStream_t)hip_stream);
 }
 
 int slicer_decode_as(const void* stream, const void* meta, void* y, slicer_dtype dt, int64_t rows,
                      int64_t row_len, int n_blocks, void* hip_stream)
 {
-    int rc = check_shape((int)dt, rows, row_len, n_blocks);
-    if (rc) return rc;
-    if (!stream || !meta || !y) return SLICER_EINVAL;
-    return launch_decode(stream, meta, y, (int)dt, rows, row_len, n_blocks, (hipStream_t)hip_stream);
+    return slicer_decode_as_pn(stream, meta, y, dt, rows, row_len, n_blocks, n_blocks, hip_stream);
 }
 
 static int read_header(const void* meta, hipStream_t st, uint32_t* h32)
@@ -481,10 +510,11 @@ int slicer_decode(const void* stream, const void* meta, void* y, void* hip_strea
     const uint64_t* h64 = (const uint64_t*)h32;
     const int dt = (int)h32[2], M = (int)h32[3];
     const int64_t rows = (int64_t)h64[2], row_len = (int64_t)h64[3];
+    const int Mn = h32[14] ? (int)h32[14] : M;           // 0: the negative class has M blocks too
     rc = check_shape(dt, rows, row_len, M);
-    if (rc) return SLICER_EFORMAT;
+    if (rc || Mn < 1 || Mn > SLICER_MAX_BLOCKS) return SLICER_EFORMAT;
     if ((int)h32[11] != index_bits(row_len)) return SLICER_EFORMAT;
-    return launch_decode(stream, meta, y, dt, rows, row_len, M, st);
+    return launch_decode(stream, meta, y, dt, rows, row_len, M, Mn, st);
 }
 
 int slicer_stream_words(const void* meta, uint64_t* words, void* hip_stream)
@@ -500,12 +530,19 @@ int slicer_stream_words(const void* meta, uint64_t* words, void* hip_stream)
 int slicer_check(const void* meta, uint64_t stream_words, slicer_dtype dt, int64_t rows, int64_t row_len,
                  int n_blocks, void* scratch, void* hip_stream)
 {
+    return slicer_check_pn(meta, stream_words, dt, rows, row_len, n_blocks, n_blocks, scratch, hip_stream);
+}
+
+int slicer_check_pn(const void* meta, uint64_t stream_words, slicer_dtype dt, int64_t rows, int64_t row_len,
+                    int n_blocks, int n_blocks_neg, void* scratch, void* hip_stream)
+{
     int rc = check_shape((int)dt, rows, row_len, n_blocks);
     if (rc) return rc;
+    if (n_blocks_neg < 1 || n_blocks_neg > SLICER_MAX_BLOCKS) return SLICER_EINVAL;
     if (!meta || !scratch) return SLICER_EINVAL;
     hipStream_t st = (hipStream_t)hip_stream;
     CheckArgs ca;
-    ca.meta = meta; ca.R = rows; ca.N = row_len; ca.M = n_blocks; ca.w = index_bits(row_len); ca.dt = (int)dt;
+    ca.meta = meta; ca.R = rows; ca.N = row_len; ca.M = n_blocks; ca.Mn = n_blocks_neg; ca.w = index_bits(row_len); ca.dt = (int)dt;
     ca.avail_words = stream_words;
     ca.flag = (u32*)scratch;
     hipLaunchKernelGGL(meta_flag_clear_kernel, dim3(1), dim3(64), 0, st, ca.flag);

@@ -28,21 +28,22 @@ struct MetaView {
     uint8_t* q;
 };
 
-__host__ __device__ inline size_t meta_bytes(int64_t R, int M)
+// B2 = blocks per row = M(+) + M(-)
+__host__ __device__ inline size_t meta_bytes(int64_t R, int B2)
 {
-    size_t s = kHeaderBytes + 16 * (size_t)R + 18 * (size_t)R * (size_t)M;
+    size_t s = kHeaderBytes + 16 * (size_t)R + 9 * (size_t)R * (size_t)B2;
     return (s + 7) & ~(size_t)7;
 }
 
-__host__ __device__ inline MetaView meta_view(void* meta, int64_t R, int M)
+__host__ __device__ inline MetaView meta_view(void* meta, int64_t R, int B2)
 {
     uint8_t* p = (uint8_t*)meta + kHeaderBytes;
     MetaView v;
     v.row_off = (u64*)p;              p += 8 * (size_t)R;
     v.n_pos = (u32*)p;                p += 4 * (size_t)R;
     v.n_neg = (u32*)p;                p += 4 * (size_t)R;
-    v.vmin = (float*)p;               p += 8 * (size_t)R * M;
-    v.vmax = (float*)p;               p += 8 * (size_t)R * M;
+    v.vmin = (float*)p;               p += 4 * (size_t)R * B2;
+    v.vmax = (float*)p;               p += 4 * (size_t)R * B2;
     v.q = p;
     return v;
 }

@@ -14,7 +14,7 @@ struct DecArgs {
     const u32* stream;
     void* y;
     int64_t R, N;
-    int M, w;
+    int M, Mn, w;             // blocks of the positive / negative class
     int chunks_per_row;
     MetaView mv;
     const u64* total_words;   // header field
@@ -38,7 +38,7 @@ __global__ __launch_bounds__(BLOCK) void dec_kernel(DecArgs a)
     const int64_t c0 = (int64_t)(blockIdx.x % a.chunks_per_row) * kDecChunk;
     const int64_t c1 = c0 + kDecChunk < a.N ? c0 + kDecChunk : a.N;
     const int len = (int)(c1 - c0);
-    const int M = a.M, B2 = 2 * a.M, w = a.w;
+    const int M = a.M, B2 = a.M + a.Mn, w = a.w;
     const u32* __restrict__ rw = a.stream + a.mv.row_off[r];
     u32 n_cls[2] = { a.mv.n_pos[r], a.mv.n_neg[r] };
     if ((u64)n_cls[0] + n_cls[1] > (u64)a.N) n_cls[0] = n_cls[1] = 0;   // not a valid row: write zeros
@@ -58,10 +58,11 @@ __global__ __launch_bounds__(BLOCK) void dec_kernel(DecArgs a)
         u32 ia = 0;
         u64 ca = n * (u64)w;
         for (int s = 0; s < 2; ++s) {
-            u32 K = n_cls[s] / (u32)M;
-            for (int m = 0; m < M; ++m) {
+            const int Ms = s ? a.Mn : M;
+            u32 K = n_cls[s] / (u32)Ms;
+            for (int m = 0; m < Ms; ++m) {
                 int b = s * M + m;
-                u32 cnt = (m < M - 1) ? K : n_cls[s] - K * (u32)(M - 1);
+                u32 cnt = (m < Ms - 1) ? K : n_cls[s] - K * (u32)(Ms - 1);
                 istart[b] = ia; cstart[b] = ca;
                 ia += cnt; ca += (u64)cnt * (u64)qv[b];
             }
@@ -135,7 +136,7 @@ __global__ __launch_bounds__(BLOCK) void dec_kernel(DecArgs a)
 struct CheckArgs {
     const void* meta;
     int64_t R, N;
-    int M, w, dt;
+    int M, Mn, w, dt;
     u64 avail_words;
     u32* flag;          // device word, zeroed by the same launch sequence
 };
@@ -147,11 +148,12 @@ __global__ __launch_bounds__(256) void meta_check_kernel(CheckArgs a)
     const int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const u32* h32 = (const u32*)a.meta;
     const u64* h64 = (const u64*)a.meta;
-    const MetaView mv = meta_view(const_cast<void*>(a.meta), a.R, a.M);
+    const MetaView mv = meta_view(const_cast<void*>(a.meta), a.R, a.M + a.Mn);
     u32 bad = 0;
     const u64 total = h64[6];
     if (r == 0) {
         if (h32[0] != kMagic || h32[1] != kVersion) bad |= 1u;
+        if (h32[14] != (a.Mn != a.M ? (u32)a.Mn : 0u) || h32[15] != 0u) bad |= 2u;
         if (h32[2] != (u32)a.dt || h32[3] != (u32)a.M || h64[2] != (u64)a.R || h64[3] != (u64)a.N || h32[11] != (u32)a.w) bad |= 2u;
         if (h64[4] > (u64)a.N || (h32[10] & ~0x1FFFEu) || h32[10] == 0u) bad |= 2u;
         if (total > a.avail_words || mv.row_off[0] != 0ull) bad |= 4u;
@@ -162,11 +164,12 @@ __global__ __launch_bounds__(256) void meta_check_kernel(CheckArgs a)
             bad |= 8u;
         } else {
             u64 bits = (n_pos + n_neg) * (u64)a.w;
-            for (int b = 0; b < 2 * a.M; ++b) {
-                const u32 q = mv.q[(size_t)r * 2 * a.M + b] & 0x7Fu;
+            for (int b = 0; b < a.M + a.Mn; ++b) {
+                const u32 q = mv.q[(size_t)r * (a.M + a.Mn) + b] & 0x7Fu;
                 if (q < 1u || q > 16u || !((h32[10] >> q) & 1u)) bad |= 16u;
-                const u64 nc = b < a.M ? n_pos : n_neg, K = nc / (u64)a.M;
-                const u64 cnt = (b % a.M) < a.M - 1 ? K : nc - K * (u64)(a.M - 1);
+                const int Ms = b < a.M ? a.M : a.Mn, m = b < a.M ? b : b - a.M;
+                const u64 nc = b < a.M ? n_pos : n_neg, K = nc / (u64)Ms;
+                const u64 cnt = m < Ms - 1 ? K : nc - K * (u64)(Ms - 1);
                 bits += cnt * q;
             }
             const u64 off0 = mv.row_off[r];
@@ -201,7 +204,7 @@ __global__ __launch_bounds__(256) void dec_small_kernel(DecArgs a)
     const int wid = threadIdx.x / kWave;
     const int64_t r = xcd_row((int64_t)blockIdx.x, a.R);       // one wave per workgroup
     if (r >= a.R) return;
-    const int N = (int)a.N, M = a.M, B2 = 2 * a.M, w = a.w;
+    const int N = (int)a.N, M = a.M, B2 = a.M + a.Mn, w = a.w;
     const int row_bytes = N * ESZ;                       // multiple of 16
     const int per_wave16 = row_bytes / 16 + (a.stage_words + 4) / 4;
     uint4* tile4 = dec_smem + (size_t)wid * per_wave16;
@@ -225,8 +228,9 @@ __global__ __launch_bounds__(256) void dec_small_kernel(DecArgs a)
     float vmin = 0.f, step = 0.f;
     if (myb < (u32)B2 && (u64)n_pos + n_neg <= (u64)N) {
         const u32 cls = myb >= (u32)M ? 1u : 0u, m = myb - cls * (u32)M;
-        const u32 nc = cls ? n_neg : n_pos, K = nc / (u32)M;
-        cnt = (m < (u32)(M - 1)) ? K : nc - K * (u32)(M - 1);
+        const u32 Ms = cls ? (u32)a.Mn : (u32)M;
+        const u32 nc = cls ? n_neg : n_pos, K = nc / Ms;
+        cnt = (m < Ms - 1u) ? K : nc - K * (Ms - 1u);
         const size_t mi = (size_t)r * (size_t)B2 + myb;
         q = a.mv.q[mi] & 0x7Fu;
         vmin = a.mv.vmin[mi];

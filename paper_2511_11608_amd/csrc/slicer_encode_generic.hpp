@@ -19,7 +19,7 @@ namespace slicer {
 struct EncArgs {
     const void* x;
     int64_t R, N, k;
-    int M, w, nq;
+    int M, Mn, w, nq;       // blocks of the positive / negative class (block order +0..+M-1, -0..-Mn-1)
     int qlist[kMaxQ];       // allowed bitwidths, ascending
     double beta;
     u64 cap_words;          // per-row slot capacity in words
@@ -140,7 +140,8 @@ __device__ inline void enc_generic_rows(const EncArgs& a, const int64_t r_begin,
     for (int64_t r = r_begin; r < r_end; ++r) {
     if (a.only_flagged && !a.only_flagged[r]) continue;      // uniform: the whole workgroup skips
     const int64_t N = a.N;
-    const int M = a.M, w = a.w, B2 = 2 * a.M;
+    const int M = a.M, Mn = a.Mn, w = a.w, B2 = a.M + a.Mn;
+    const int Mc[2] = { M, Mn };
     const raw_t* __restrict__ xr = (const raw_t*)a.x + (size_t)r * (size_t)N;
     u64* __restrict__ kept = a.kept + (size_t)r * (size_t)a.k;
     u32* __restrict__ bo_idx = a.bo_idx + (size_t)r * (size_t)a.k;
@@ -212,10 +213,10 @@ __device__ inline void enc_generic_rows(const EncArgs& a, const int64_t r_begin,
     if (tid == 0) {
         u32 acc = 0;
         for (int s = 0; s < 2; ++s) {
-            u32 K = n_cls[s] / (u32)M;
-            for (int m = 0; m < M; ++m) {
+            u32 K = n_cls[s] / (u32)Mc[s];
+            for (int m = 0; m < Mc[s]; ++m) {
                 blk_start[s * M + m] = acc;
-                acc += (m < M - 1) ? K : n_cls[s] - K * (u32)(M - 1);
+                acc += (m < Mc[s] - 1) ? K : n_cls[s] - K * (u32)(Mc[s] - 1);
             }
         }
         blk_start[B2] = acc;
@@ -230,8 +231,8 @@ __device__ inline void enc_generic_rows(const EncArgs& a, const int64_t r_begin,
     // MS: thresholds comp(rank j*K - 1), j = 1..M-1, per class, in batches
     // ------------------------------------------------------------------
     {
-        const u32 Kc[2] = { n_cls[0] / (u32)M, n_cls[1] / (u32)M };
-        const int nt[2] = { Kc[0] ? M - 1 : 0, Kc[1] ? M - 1 : 0 };
+        const u32 Kc[2] = { n_cls[0] / (u32)M, n_cls[1] / (u32)Mn };
+        const int nt[2] = { Kc[0] ? M - 1 : 0, Kc[1] ? Mn - 1 : 0 };
         const int ntot = nt[0] + nt[1];
         for (int t0 = 0; t0 < ntot; t0 += kTgtBatch) {
             const int nb = ntot - t0 < kTgtBatch ? ntot - t0 : kTgtBatch;
@@ -307,9 +308,10 @@ __device__ inline void enc_generic_rows(const EncArgs& a, const int64_t r_begin,
             key = (u32)(e >> 32) & 0x7FFFFFFFu;
             idx = (u32)e;
             u64 comp = ((u64)key << w) | (idxmask - (u64)idx);
-            int m = M - 1;
-            if (n_cls[s] >= (u32)M) {       // K >= 1: block = #{j : comp < thr_j}, thr decreasing in j
-                int lo = 0, hi = M - 1;     // count of thresholds above comp lies in [lo, hi]
+            const int Ms = s ? Mn : M;
+            int m = Ms - 1;
+            if (n_cls[s] >= (u32)Ms) {      // K >= 1: block = #{j : comp < thr_j}, thr decreasing in j
+                int lo = 0, hi = Ms - 1;    // count of thresholds above comp lies in [lo, hi]
                 while (lo < hi) {
                     int mid = (lo + hi) >> 1;           // is thr[mid] > comp ?
                     if (s_thr[s][mid] > comp) lo = mid + 1; else hi = mid;
@@ -467,7 +469,7 @@ __device__ inline void enc_generic_rows(const EncArgs& a, const int64_t r_begin,
             tsel = chosen; q = a.qlist[chosen]; flag = 0;
         }
         if (a.lad.on) {             // the bitwidth is given, also for empty and degenerate blocks
-            tsel = (int)ladder_index(a.lad, b % M);
+            tsel = (int)ladder_index(a.lad, b < M ? b : b - M);
             q = a.qlist[tsel]; flag = 0;
         }
         qsel[b] = q;
@@ -568,7 +570,7 @@ constexpr int kGatherWords = 1024;   // slot words one wavefront copies
 
 struct FinishArgs {
     int64_t R, N, k;
-    int M, w, dt;
+    int M, Mn, w, dt;
     u32 bit_set;
     const u64* row_words;   // [R]
     u64* row_off_local;     // [R]  offset of the row inside its chunk of kScanRows rows
@@ -654,9 +656,11 @@ __global__ __launch_bounds__(256) void enc_gather_kernel(FinishArgs a)
         h32[0] = kMagic; h32[1] = kVersion; h32[2] = (u32)a.dt; h32[3] = (u32)a.M;
         h64[2] = (u64)a.R; h64[3] = (u64)a.N; h64[4] = (u64)a.k;
         h32[10] = a.bit_set; h32[11] = (u32)a.w;
-        h64[6] = total; h64[7] = 0;
+        h64[6] = total;
+        h32[14] = a.Mn != a.M ? (u32)a.Mn : 0u;        // 0: the negative class has M blocks too
+        h32[15] = 0;
         uint8_t* m8 = (uint8_t*)a.meta;     // zero the padding after the last array
-        for (size_t o = kHeaderBytes + 16 * (size_t)a.R + 18 * (size_t)a.R * a.M; o < meta_bytes(a.R, a.M); ++o) m8[o] = 0;
+        for (size_t o = kHeaderBytes + 16 * (size_t)a.R + 9 * (size_t)a.R * (a.M + a.Mn); o < meta_bytes(a.R, a.M + a.Mn); ++o) m8[o] = 0;
     }
     const u64 nw = a.row_words[r];
     const u64 j0 = c * (u64)kGatherWords;

@@ -37,7 +37,7 @@ constexpr u64 kTop = 1ull << 63;
 struct LargeArgs {
     const void* x;
     int64_t R, N, k;
-    int M, w, nq;
+    int M, Mn, w, nq;       // blocks of the positive / negative class
     int qlist[kMaxQ];
     double beta;
     u64 cap_words;
@@ -77,7 +77,7 @@ __global__ __launch_bounds__(256) void lr_hist_kernel(LargeArgs a)
     __shared__ u32 scr[256 / kWave + 1];
     const int tid = threadIdx.x, c = blockIdx.x;
     const int64_t r = blockIdx.y;
-    const int B2 = 2 * a.M;
+    const int B2 = a.M + a.Mn;
     for (int i = tid; i < kLBins; i += 256) h[i] = 0;
     // this launch also clears what later stages accumulate into
     if (c == 0) {
@@ -277,7 +277,7 @@ __global__ __launch_bounds__(1024) void lr_bounds_kernel(LargeArgs a)
     const int tid = threadIdx.x;
     const int64_t r = blockIdx.x;
     if (a.fallback[r]) return;
-    const int M = a.M, B2 = 2 * a.M, w = a.w;
+    const int M = a.M, Mn = a.Mn, B2 = a.M + a.Mn, w = a.w;
     u32* st = a.rowst + (size_t)r * 16;
     const u32 t_lo = st[0], nL = st[2];
     const int sh = (int)st[1];
@@ -345,8 +345,8 @@ __global__ __launch_bounds__(1024) void lr_bounds_kernel(LargeArgs a)
 
     // (c) block boundaries: class ranks j*K-1, one thread per boundary: first the group of
     //     bins (binary search over the threads' first ranks), then the bin inside the group
-    const u32 Kc0 = n_pos / (u32)M, Kc1 = n_neg / (u32)M;
-    const int nt0 = Kc0 ? M - 1 : 0, nt1 = Kc1 ? M - 1 : 0, ntg = nt0 + nt1;
+    const u32 Kc0 = n_pos / (u32)M, Kc1 = n_neg / (u32)Mn;
+    const int nt0 = Kc0 ? M - 1 : 0, nt1 = Kc1 ? Mn - 1 : 0, ntg = nt0 + nt1;
     if (tid < ntg) {
         const int cls = tid >= nt0 ? 1 : 0;
         const int j = (cls ? tid - nt0 : tid) + 1;
@@ -419,7 +419,7 @@ __global__ __launch_bounds__(256) void lr_blockcount_kernel(LargeArgs a)
     const int tid = threadIdx.x, lc = blockIdx.x;
     const int64_t r = blockIdx.y;
     if (a.fallback[r]) return;
-    const int M = a.M, B2 = 2 * a.M, w = a.w;
+    const int M = a.M, Mn = a.Mn, B2 = a.M + a.Mn, w = a.w;
     const u32* st = a.rowst + (size_t)r * 16;
     const u32 nL = st[2];
     const u32 Kc[2] = { st[5], st[6] };
@@ -440,7 +440,7 @@ __global__ __launch_bounds__(256) void lr_blockcount_kernel(LargeArgs a)
             const u64 cx = comp | (cls ? 0ull : kTop);
             int lo = 0, hi = ntg;                   // boundaries above cx (they are sorted, largest first)
             while (lo < hi) { const int mid = (lo + hi) >> 1; if (thr_s[1 + mid] > cx) lo = mid + 1; else hi = mid; }
-            const u32 m = Kc[cls] ? (u32)lo - (cls ? (u32)nt0 : 0u) : (u32)(M - 1);
+            const u32 m = Kc[cls] ? (u32)lo - (cls ? (u32)nt0 : 0u) : (u32)((cls ? Mn : M) - 1);
             b = cls * (u32)M + m;
             const u32 key = (u32)(e >> 32) & 0x7FFFFFFFu;
             atomicAdd(&cnt[b], 1u);
@@ -466,7 +466,7 @@ __global__ __launch_bounds__(256) void lr_scatter_kernel(LargeArgs a)
     const u32 lane = lane_id();
     const int64_t r = blockIdx.y;
     if (a.fallback[r]) return;
-    const int B2 = 2 * a.M;
+    const int B2 = a.M + a.Mn;
     const u32 nL = a.rowst[(size_t)r * 16 + 2];
     if ((u32)lc * kLCE >= nL) return;
     for (int b = tid; b < B2; b += 256) {
@@ -529,7 +529,7 @@ __global__ __launch_bounds__(256) void lr_abq_kernel(LargeArgs a)
     const int tid = threadIdx.x, pc = blockIdx.x;
     const int64_t r = blockIdx.y;
     if (a.fallback[r]) return;
-    const int B2 = 2 * a.M, nq = a.nq;
+    const int B2 = a.M + a.Mn, nq = a.nq;
     const u32* st = a.rowst + (size_t)r * 16;
     const u32 n = st[3] + st[4];
     const u32 p0 = (u32)pc * kPCH, p1 = p0 + kPCH < n ? p0 + kPCH : n;
@@ -621,7 +621,7 @@ __global__ __launch_bounds__(128) void lr_choose_kernel(LargeArgs a)
     const int b = threadIdx.x;
     const int64_t r = blockIdx.x;
     if (a.fallback[r]) return;
-    const int B2 = 2 * a.M, nq = a.nq;
+    const int B2 = a.M + a.Mn, nq = a.nq;
     const u32* st = a.rowst + (size_t)r * 16;
     const u32 n = st[3] + st[4];
     if (b < B2) {
@@ -658,7 +658,7 @@ __global__ __launch_bounds__(128) void lr_choose_kernel(LargeArgs a)
             if (cnt && vmax - vmin >= 0x1p-100f) inv = (float)((1u << q) - 1u) / (vmax - vmin);
         }
         if (a.lad.on) {             // the bitwidth is given, also for empty and degenerate blocks
-            q = a.qlist[ladder_index(a.lad, b % a.M)];
+            q = a.qlist[ladder_index(a.lad, b < a.M ? b : b - a.M)];
             flag = 0; inv = 0.f;
             if (cnt && vmax - vmin >= 0x1p-100f) inv = (float)((1u << q) - 1u) / (vmax - vmin);
         }
@@ -695,7 +695,7 @@ __global__ __launch_bounds__(256) void lr_pack_kernel(LargeArgs a)
     const int tid = threadIdx.x;
     const int64_t r = blockIdx.y;
     if (a.fallback[r]) return;
-    const int B2 = 2 * a.M, w = a.w;
+    const int B2 = a.M + a.Mn, w = a.w;
     const u64 row_words = a.row_words[r];
     const u64 c0 = (u64)blockIdx.x * kPackWords;
     if (c0 >= row_words) return;

@@ -36,7 +36,7 @@ namespace slicer {
 struct SmallArgs {
     const void* x;
     int64_t R, N, k;
-    int M, w, nq;
+    int M, Mn, w, nq;   // blocks of the positive / negative class
     int qlist[kMaxQ];
     double beta;
     u64 cap_words;
@@ -173,7 +173,7 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
 #endif
     const int64_t r = xcd_row((int64_t)blockIdx.x, a.R);        // neighbouring rows stay on one XCD
     if (r >= a.R) return;
-    const int N = (int)a.N, M = a.M, w = a.w, B2 = 2 * a.M, nq = NQ ? NQ : a.nq, cap = a.cap;
+    const int N = (int)a.N, M = a.M, Mn = a.Mn, w = a.w, B2 = a.M + a.Mn, nq = NQ ? NQ : a.nq, cap = a.cap;
     const int k = (int)a.k;
     const u32 idxmask = (1u << w) - 1u;
     SmallLds L = small_carve(smem, DT, cap, a.region0_words, B2, MAXS);
@@ -500,11 +500,11 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
         n_pos = pe + kp; n_neg = ne + kn;
     }
     const u32 n = n_pos + n_neg;
-    const u32 Kc[2] = { n_pos / (u32)M, n_neg / (u32)M };
+    const u32 Kc[2] = { n_pos / (u32)M, n_neg / (u32)Mn };
 
     SLICER_PT(3);
     // ---- block boundaries: comps of class ranks j*K-1, one lane per boundary ------------------------
-    // M-1 boundaries per class, positive class first.  A class with fewer than M members has
+    // M-1 boundaries for the positive class, then Mn-1 for the negative one.  A class with fewer than M members has
     // K = 0 and every member in its last block: its boundaries sit above every comp of the class.
     const int ntg = B2 - 2;
     comp_t* thr = (comp_t*)L.thr;
@@ -666,7 +666,7 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
         }
     }
     // longest run of any lane: the largest block holds K + (n mod M) entries
-    const u32 mc0 = n_pos - Kc[0] * (u32)(M - 1), mc1 = n_neg - Kc[1] * (u32)(M - 1);
+    const u32 mc0 = n_pos - Kc[0] * (u32)(M - 1), mc1 = n_neg - Kc[1] * (u32)(Mn - 1);
     const u32 T = udiv16((mc0 > mc1 ? mc0 : mc1) + lpb - 1, lpb);
     // quantiser scales L / rng: the lanes of a block share the divisions through LDS
     if (lane_on) {

@@ -28,7 +28,8 @@ def test_exports_every_declared_symbol(lib):
     names = declared_symbols()
     assert {"slicer_sizes", "slicer_encode", "slicer_decode", "slicer_decode_as", "slicer_stream_words",
             "slicer_encode_path", "slicer_profile_events", "slicer_last_hip_error", "slicer_strerror",
-            "slicer_encode_ladder", "slicer_ladder_bit_set", "slicer_bound", "slicer_check", "slicer_encode_ds"} <= set(names)
+            "slicer_encode_ladder", "slicer_ladder_bit_set", "slicer_bound", "slicer_check", "slicer_encode_ds",
+            "slicer_sizes_pn", "slicer_encode_pn", "slicer_decode_as_pn", "slicer_check_pn"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
@@ -97,3 +98,17 @@ def test_ladder_bit_set(lib):
     assert binding.slicer_ladder_bit_set([8, 6, 4, 2]) == (1 << 8) | (1 << 6) | (1 << 4) | (1 << 2)
     assert binding.slicer_ladder_bit_set([3, 3, 3]) == 1 << 3
     assert binding.slicer_ladder_bit_set([0, 3]) == 0 and binding.slicer_ladder_bit_set([17]) == 0
+
+
+def test_sizes_pn(lib, oracle):
+    from paper_2511_11608_amd import binding
+    import ctypes as C
+    for Mp, Mn in ((1, 1), (3, 8), (64, 1), (8, 8)):
+        a, b, c = C.c_size_t(0), C.c_size_t(0), C.c_size_t(0)
+        assert lib.slicer_sizes_pn(binding.SLICER_BF16, 100, 4096, 0.1, Mp, Mn, 0x1FC, C.byref(a), C.byref(b), C.byref(c)) == 0
+        assert b.value == (64 + 16 * 100 + 9 * 100 * (Mp + Mn) + 7) // 8 * 8
+        if Mp == Mn:
+            assert (a.value, b.value, c.value) == binding.slicer_sizes(binding.SLICER_BF16, 100, 4096, 0.1, Mp, 0x1FC)
+    a = C.c_size_t(0)
+    assert lib.slicer_sizes_pn(binding.SLICER_BF16, 100, 4096, 0.1, 4, 0, 0x1FC, C.byref(a), None, None) == -1
+    assert lib.slicer_sizes_pn(binding.SLICER_BF16, 100, 4096, 0.1, 4, 65, 0x1FC, C.byref(a), None, None) == -1

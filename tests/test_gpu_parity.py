@@ -182,6 +182,57 @@ def test_ds_guard_mixed_rows(oracle, dtype, N):
         check_ds(oracle, x, dtype, keep, M, bits, delta)
 
 
+@pytest.mark.parametrize("name", ["cnn_map_ragged", "resnet_2rows", "vit", "llm", "ar_step"])
+def test_separate_block_counts_workloads(oracle, name):
+    """M(+) != M(-) (Sec. 3.3) on every kernel family, through both decode entry points and the checker."""
+    import torch
+    from paper_2511_11608_amd import binding
+    from paper_2511_11608_amd.devmem import to_device, to_host
+    wl = CASES[name]()
+    xd = to_device(wl.x, wl.dtype)
+    for Mp, Mn in ((1, 5), (7, 2), (16, 3), (4, 4)):
+        s_ref, m_ref = oracle.encode_pn(wl.x, wl.dtype, wl.keep_ratio, Mp, Mn, wl.bit_set, wl.budget, n_threads=8)
+        y_ref = oracle.decode(s_ref, m_ref, n_threads=8)
+        sb, meta, ws = binding.alloc_buffers_pn(xd, wl.keep_ratio, Mp, Mn, wl.bit_set)
+        ws.fill_(0xA5); sb.fill_(-1); meta.fill_(0xFF)
+        binding.slicer_encode_pn(xd, wl.keep_ratio, Mp, Mn, wl.bit_set, wl.budget, sb, meta, ws)
+        words = binding.slicer_stream_words(meta)
+        m_gpu = meta.cpu().numpy()
+        s_gpu = sb[:words].cpu().numpy().view(np.uint32)
+        assert np.array_equal(m_ref[:64], m_gpu[:64]), (streamfmt.header(m_ref), streamfmt.header(m_gpu))
+        ok = np.array_equal(m_ref, m_gpu) and np.array_equal(s_ref, s_gpu)
+        assert ok, explain_mismatch(s_ref, m_ref, s_gpu, m_gpu, wl.x.shape[0])
+        binding.slicer_check_pn(meta, words, xd, Mp, Mn)
+        for via_header in (True, False):
+            y = torch.full_like(xd, 7.0)
+            if via_header:
+                binding.slicer_decode(sb, meta, y)
+            else:
+                binding.slicer_decode_as_pn(sb, meta, y, Mp, Mn)
+            torch.cuda.synchronize()
+            yv = np.uint32 if wl.dtype == "f32" else np.uint16
+            assert np.array_equal(y_ref.view(yv), to_host(y).view(yv))
+
+
+@pytest.mark.parametrize("dtype,N", [("bf16", 4096), ("f32", 768), ("bf16", 1000), ("f32", 40000)])
+def test_separate_block_counts_mixed_rows(oracle, dtype, N):
+    from paper_2511_11608_amd import binding
+    from paper_2511_11608_amd.devmem import to_device
+    rng = np.random.default_rng(N + 3)
+    x = _mixed_rows(rng, 12, N, dtype)
+    xd = to_device(x, dtype)
+    for keep, Mp, Mn, bits in ((0.1, 8, 3, B28), (1.0, 1, 9, 0x1FFFE), (0.3, 40, 24, B28), (0.02, 2, 1, 1 << 4)):
+        s_ref, m_ref = oracle.encode_pn(x, dtype, keep, Mp, Mn, bits, 1e-3, n_threads=8)
+        sb, meta, ws = binding.alloc_buffers_pn(xd, keep, Mp, Mn, bits)
+        ws.fill_(0x5A); sb.fill_(-1); meta.fill_(0xFF)
+        binding.slicer_encode_pn(xd, keep, Mp, Mn, bits, 1e-3, sb, meta, ws)
+        words = binding.slicer_stream_words(meta)
+        m_gpu = meta.cpu().numpy()
+        s_gpu = sb[:words].cpu().numpy().view(np.uint32)
+        ok = np.array_equal(m_ref, m_gpu) and np.array_equal(s_ref, s_gpu)
+        assert ok, explain_mismatch(s_ref, m_ref, s_gpu, m_gpu, x.shape[0])
+
+
 def test_encode_is_deterministic():
     from tests.gpu_util import gpu_roundtrip
     wl = synth.llm_prefill(seed=3, rows=64)
