@@ -65,7 +65,7 @@ struct Plan {
     // long-row path (large_C == 0: not eligible)
     int large_C, large_LC;
     u32 large_capL;
-    size_t lo_ch_cum, lo_ch_off, lo_L, lo_Lblk, lo_rowst, lo_thr, lo_blk_start,
+    size_t lo_ch_cum, lo_ch_off, lo_L, lo_Lblk, lo_Lfine, lo_rowst, lo_thr, lo_blk_start,
            lo_blkcnt, lo_vminb, lo_vmaxb, lo_sums, lo_qsel, lo_inv_sel, lo_code_off;
 };
 
@@ -94,7 +94,7 @@ Plan make_plan(int dt, int64_t rows, int64_t row_len, double keep_ratio, int n_b
     {
         const int epc_l = dt == SLICER_F32 ? 4 : 8;
         const int64_t C = (row_len + kLCH - 1) / kLCH;
-        const int64_t capL = p.k + std::max<int64_t>(4096, row_len / 16);
+        const int64_t capL = (p.k + std::max<int64_t>(4096, row_len / 16) + 7) & ~(int64_t)7;   // whole 16-byte groups of 2-byte entries
         int nq_l = 0;
         for (int q = 1; q <= 16; ++q) nq_l += (bit_set >> q) & 1u;
         if (row_len >= 32768 && row_len % epc_l == 0 && C <= 1024 && rows <= 65535 && capL < ((int64_t)1 << 27)) {
@@ -104,6 +104,7 @@ Plan make_plan(int dt, int64_t rows, int64_t row_len, double keep_ratio, int n_b
             p.lo_ch_off = o;    o = align256(o + 4 * R * (size_t)C);
             p.lo_L = o;         o = align256(o + 8 * R * (size_t)capL);
             p.lo_Lblk = o;      o = align256(o + R * (size_t)capL);
+            p.lo_Lfine = o;     o = align256(o + 2 * R * (size_t)capL);
             p.lo_rowst = o;     o = align256(o + 4 * R * 16);
             p.lo_thr = o;       o = align256(o + 8 * R * (1 + kMaxB2));
             p.lo_blk_start = o; o = align256(o + 4 * R * (B2 + 1));
@@ -181,14 +182,15 @@ int launch_large(const LargeArgs& la, const Plan& p, hipStream_t st)
 {
     const dim3 gC((unsigned)la.C, (unsigned)la.R), gL((unsigned)la.LC, (unsigned)la.R), gR((unsigned)la.R);
     const dim3 gP((unsigned)std::max<int64_t>(1, (la.k + kPCH - 1) / kPCH), (unsigned)la.R);
-    const dim3 gW((unsigned)std::max<u64>(1, (p.cap_words + kPackWords - 1) / kPackWords), (unsigned)la.R);
+    const dim3 gW((unsigned)std::max<u64>(1, (p.cap_words + (u64)la.pack_words - 1) / (u64)la.pack_words), (unsigned)la.R);
     hipLaunchKernelGGL((lr_hist_kernel<DT>), gC, dim3(256), 0, st, la);
     hipLaunchKernelGGL((lr_select_kernel<DT>), gR, dim3(1024), 0, st, la);
     hipLaunchKernelGGL((lr_compact_kernel<DT>), gC, dim3(256), 0, st, la);
     hipLaunchKernelGGL(lr_bounds_kernel, gR, dim3(1024), 0, st, la);
     hipLaunchKernelGGL(lr_blockcount_kernel, gL, dim3(256), 0, st, la);
     hipLaunchKernelGGL((lr_scatter_kernel<DT>), gL, dim3(256), 0, st, la);
-    hipLaunchKernelGGL((lr_abq_kernel<DT>), gP, dim3(256), 0, st, la);
+    if (la.nq == 7) hipLaunchKernelGGL((lr_abq_kernel<DT, 7>), gP, dim3(256), 0, st, la);   // {2..8}: the benchmarked set
+    else hipLaunchKernelGGL((lr_abq_kernel<DT, 0>), gP, dim3(256), 0, st, la);
     hipLaunchKernelGGL((lr_choose_kernel<DT>), gR, dim3(128), 0, st, la);
     hipLaunchKernelGGL((lr_pack_kernel<DT>), gW, dim3(256), 0, st, la);
     hipError_t e = hipGetLastError();
@@ -345,8 +347,11 @@ static int encode_impl(const void* x, slicer_dtype dt, int64_t rows, int64_t row
         for (int t = 0; t < kMaxQ; ++t) la.qlist[t] = ea.qlist[t];
         la.beta = distortion_budget; la.cap_words = p.cap_words;
         la.C = p.large_C; la.LC = p.large_LC; la.capL = p.large_capL;
+        la.pack_words = kPackWords;               // fewer words per workgroup while the launch is small
+        while (la.pack_words > 128 && (u64)rows * ((p.cap_words + (u64)la.pack_words - 1) / (u64)la.pack_words) < 1024) la.pack_words /= 2;
         la.ch_cum = (u32*)(ws + p.lo_ch_cum);     la.ch_off = (u32*)(ws + p.lo_ch_off);
         la.L = (u64*)(ws + p.lo_L);               la.Lblk = (uint8_t*)(ws + p.lo_Lblk);
+        la.Lfine = (uint16_t*)(ws + p.lo_Lfine);
         la.rowst = (u32*)(ws + p.lo_rowst);       la.thr = (u64*)(ws + p.lo_thr);
         la.blk_start = (u32*)(ws + p.lo_blk_start); la.blkcnt = (u32*)(ws + p.lo_blkcnt);
         la.vminb = (u32*)(ws + p.lo_vminb);       la.vmaxb = (u32*)(ws + p.lo_vmaxb);

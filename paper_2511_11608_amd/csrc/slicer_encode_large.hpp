@@ -6,8 +6,9 @@
 //             as "elements at or above the bin" (so sums over chunks are cumulative too)
 //   select    per row: the bin B1 that holds overall rank k-1, the list offsets of the chunks
 //   compact   per chunk: ordered compaction of everything at or above B1 into the row's
-//             list L (ascending index)
-//   bounds    per row: 8192-bin fine histogram of the list in LDS, ranks of the bins; the comp
+//             list L (ascending index), plus a 2-byte list of the entries' fine bins
+//   bounds    per row: 8192-bin fine histogram of the list in LDS (three scans of the 2-byte
+//             list; members of the few bins that matter are fetched from L), ranks of the bins; the comp
 //             of overall rank k-1 (ATKF cut, Sec. 3.1) and of class ranks j*K-1 (block boundaries, Sec. 3.2), each resolved
 //             inside its bin by pairwise comparison of the bin's members
 //   blockcount / scatter   per 2048 list entries: block id, per-block counts, block min/max;
@@ -29,7 +30,7 @@ constexpr int kLCH = 8192;          // elements per hist / compact workgroup
 constexpr int kLBins = 2048;        // coarse bins: top 11 bits of the key
 constexpr int kFB = 8192;           // fine bins of the list (kept in LDS by the bounds stage)
 constexpr int kLCE = 2048;          // list entries per blockcount / scatter workgroup
-constexpr int kPCH = 4096;          // block-ordered positions per abq workgroup
+constexpr int kPCH = 2048;          // block-ordered positions per abq workgroup
 constexpr int kCutCap = 2048;       // members of the top-K cut bin
 constexpr int kPackWords = 1024;    // stream words per pack workgroup
 constexpr u64 kTop = 1ull << 63;
@@ -42,10 +43,12 @@ struct LargeArgs {
     double beta;
     u64 cap_words;
     int C, LC;              // chunks per row, list chunks per row
+    int pack_words;         // stream words per pack workgroup (<= kPackWords)
     u32 capL;               // list capacity per row
     u32* ch_cum;            // [R][C][kLBins]  elements of the chunk at or above the bin
     u32* ch_off;            // [R][C]
     u64* L;                 // [R][capL]       class << 63 | key << 32 | index
+    uint16_t* Lfine;        // [R][capL]       fine bin of the entry | class << 15 (capL is a multiple of 8)
     uint8_t* Lblk;          // [R][capL]       block of the entry, 255 = not kept
     u32* rowst;             // [R][16]  0 t_lo 1 sh 2 nL 3 n_pos 4 n_neg 5 K0 6 K1 7 ntg 8 nt0
     u64* thr;               // [R][1 + kMaxB2] thr[0] = cut comp, then boundaries (class on top)
@@ -132,12 +135,28 @@ __global__ __launch_bounds__(1024) void lr_select_kernel(LargeArgs a)
     __shared__ u32 res[2];
     const int tid = threadIdx.x;
     const int64_t r = blockIdx.x;
-    for (int bin = tid; bin < kLBins; bin += 1024) {
-        u32 s = 0;
-        for (int c = 0; c < a.C; ++c) s += a.ch_cum[((size_t)r * a.C + c) * kLBins + bin];
-        rc[bin] = s;
+    // sum of the chunks' cumulative histograms: a thread takes four bins (one 16-byte load per
+    // chunk) of every second chunk, eight independent loads in flight
+    for (int bin = tid; bin <= kLBins; bin += 1024) rc[bin] = 0;
+    if (tid == 0) { res[0] = 0; res[1] = 0; }
+    __syncthreads();
+    {
+        const int q = tid & (kLBins / 4 - 1), g = tid / (kLBins / 4);          // 512 quads x 2 chunk groups
+        const uint4* __restrict__ src = (const uint4*)(a.ch_cum + (size_t)r * a.C * kLBins) + q;
+        u32 s0 = 0, s1 = 0, s2 = 0, s3 = 0;
+        for (int c0 = g; c0 < a.C; c0 += 16) {
+            uint4 t[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int c = c0 + 2 * u;
+                t[u] = c < a.C ? src[(size_t)c * (kLBins / 4)] : make_uint4(0, 0, 0, 0);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) { s0 += t[u].x; s1 += t[u].y; s2 += t[u].z; s3 += t[u].w; }
+        }
+        atomicAdd(&rc[4 * q + 0], s0); atomicAdd(&rc[4 * q + 1], s1);
+        atomicAdd(&rc[4 * q + 2], s2); atomicAdd(&rc[4 * q + 3], s3);
     }
-    if (tid == 0) { rc[kLBins] = 0; res[0] = 0; res[1] = 0; }
     __syncthreads();
     const u32 km1 = a.k > 0 ? (u32)(a.k - 1) : 0u;
     for (int bin = tid; bin < kLBins; bin += 1024) {
@@ -178,6 +197,7 @@ __global__ __launch_bounds__(256) void lr_compact_kernel(LargeArgs a)
     if (a.fallback[r]) return;
     const u32* st = a.rowst + (size_t)r * 16;
     const u32 t_lo = st[0], nL = st[2];
+    const int sh = (int)st[1];
     if (nL == 0) return;
     const int64_t seg0 = (int64_t)c * kLCH + (int64_t)wid * (kLCH / 4);
     const uint4* __restrict__ xr4 = (const uint4*)((const char*)a.x + ((size_t)r * (size_t)a.N + (size_t)seg0) * (DT == 0 ? 4 : 2));
@@ -223,6 +243,7 @@ __global__ __launch_bounds__(256) void lr_compact_kernel(LargeArgs a)
     u32 wbase = a.ch_off[(size_t)r * a.C + c];
     for (int v2 = 0; v2 < wid; ++v2) wbase += wtot[v2];
     u64* __restrict__ L = a.L + (size_t)r * a.capL;
+    uint16_t* __restrict__ Lfine = a.Lfine + (size_t)r * a.capL;
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
         u32 pos = wbase + basej[j];
@@ -233,7 +254,10 @@ __global__ __launch_bounds__(256) void lr_compact_kernel(LargeArgs a)
             const u32 key = E::key((typename E::raw_t)raw);
             if (key >= t_lo) {
                 const u32 neg = E::neg((typename E::raw_t)raw);
-                if (pos < a.capL) L[pos] = ((u64)neg << 63) | ((u64)key << 32) | (u64)(idx0 + e);
+                if (pos < a.capL) {
+                    L[pos] = ((u64)neg << 63) | ((u64)key << 32) | (u64)(idx0 + e);
+                    Lfine[pos] = (uint16_t)(((key - t_lo) >> sh) | (neg << 15));     // what the bounds stage scans
+                }
                 ++pos;
             }
         }
@@ -245,20 +269,27 @@ __device__ inline u64 lr_comp(u64 e, int w)       // key << w | inverted index
     return (((e >> 32) & 0x7FFFFFFFull) << w) | (((1ull << w) - 1ull) - (e & 0xFFFFFFFFull));
 }
 
-// fine bin of a list entry: linear in the key from the list's lower bound
-__device__ inline u32 lr_fine(u64 e, u32 t_lo, int sh) { return (((u32)(e >> 32) & 0x7FFFFFFFu) - t_lo) >> sh; }
-
-// Visit every entry of the row's list with eight independent loads in flight per thread.
+// Visit the row's 2-byte list in groups of eight entries (one 16-byte load), four independent
+// loads in flight per thread: f(first position, the eight entries, number of valid ones).
 template <typename F>
-__device__ inline void lr_for_each(const u64* __restrict__ L, u32 nL, F f)
+__device__ inline void lr_for_each_fine(const uint16_t* __restrict__ Lfine, u32 nL, F f)
 {
-    for (u32 p0 = 0; p0 < nL; p0 += 8 * 1024) {
-        u64 e8[8];
+    const uint4* __restrict__ q4 = (const uint4*)Lfine;
+    const u32 ng = (nL + 7u) / 8u;
+    for (u32 g0 = 0; g0 < ng; g0 += 4 * 1024) {
+        uint4 t[4];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) { const u32 p = p0 + u * 1024 + threadIdx.x; e8[u] = p < nL ? L[p] : 0ull; }
+        for (int u = 0; u < 4; ++u) { const u32 g = g0 + (u32)u * 1024 + threadIdx.x; t[u] = g < ng ? q4[g] : make_uint4(0, 0, 0, 0); }
 #pragma unroll
-        for (int u = 0; u < 8; ++u)
-            if (p0 + u * 1024 + threadIdx.x < nL) f(e8[u]);
+        for (int u = 0; u < 4; ++u) {
+            const u32 g = g0 + (u32)u * 1024 + threadIdx.x;
+            if (g < ng) {
+                const u32 v[8] = { t[u].x & 0xFFFFu, t[u].x >> 16, t[u].y & 0xFFFFu, t[u].y >> 16,
+                                   t[u].z & 0xFFFFu, t[u].z >> 16, t[u].w & 0xFFFFu, t[u].w >> 16 };
+                const u32 left = nL - g * 8u;
+                f(g * 8u, v, left < 8u ? left : 8u);
+            }
+        }
     }
 }
 
@@ -279,9 +310,9 @@ __global__ __launch_bounds__(1024) void lr_bounds_kernel(LargeArgs a)
     if (a.fallback[r]) return;
     const int M = a.M, Mn = a.Mn, B2 = a.M + a.Mn, w = a.w;
     u32* st = a.rowst + (size_t)r * 16;
-    const u32 t_lo = st[0], nL = st[2];
-    const int sh = (int)st[1];
+    const u32 nL = st[2];
     const u64* __restrict__ L = a.L + (size_t)r * a.capL;
+    const uint16_t* __restrict__ Lfine = a.Lfine + (size_t)r * a.capL;
     const u32 k = (u32)a.k;
 
     for (int i = tid; i < kFB; i += 1024) fh[i] = 0;
@@ -289,7 +320,11 @@ __global__ __launch_bounds__(1024) void lr_bounds_kernel(LargeArgs a)
     if (tid < kMaxB2) tcnt[tid] = 0;
     if (tid == 0) { s_cut[0] = 0xFFFFFFFFu; s_n[0] = 0; s_n[1] = 0; s_n[2] = 0; s_n[3] = 0; s_thrK = 0; }
     __syncthreads();
-    lr_for_each(L, nL, [&](u64 e) { atomicAdd(&fh[lr_fine(e, t_lo, sh)], (e >> 63) ? 0x10000u : 1u); });
+    lr_for_each_fine(Lfine, nL, [&](u32, const u32 (&v)[8], u32 nv) {
+#pragma unroll
+        for (int d = 0; d < 8; ++d)
+            if ((u32)d < nv) atomicAdd(&fh[v[d] & 0x7FFFu], (v[d] >> 15) ? 0x10000u : 1u);
+    });
     __syncthreads();
 
     // (a) class ranks from the top: thread t owns the BPT bins below kFB - BPT * t
@@ -320,15 +355,26 @@ __global__ __launch_bounds__(1024) void lr_bounds_kernel(LargeArgs a)
     u64 thrK = 0;
     if (nL > k) {
         const u32 cut = s_cut[0];
-        lr_for_each(L, nL, [&](u64 e) {
-            if (lr_fine(e, t_lo, sh) == cut) {
+        // positions first, then the members themselves with all loads in flight together
+        lr_for_each_fine(Lfine, nL, [&](u32 p, const u32 (&v)[8], u32 nv) {
+            u32 hits = 0;
+#pragma unroll
+            for (int d = 0; d < 8; ++d) hits |= ((u32)d < nv && (v[d] & 0x7FFFu) == cut) ? 1u << d : 0u;
+            while (hits) {
+                const u32 d = (u32)__builtin_ctz(hits);
+                hits &= hits - 1u;
                 const u32 slot = atomicAdd(&s_n[0], 1u);
-                if (slot < (u32)kCutCap) cutmem[slot] = (e & kTop) | lr_comp(e, w);
+                if (slot < (u32)kCutCap) cutmem[slot] = (u64)(p + d);
             }
         });
         __syncthreads();
         const u32 nm = s_n[0];
         if (nm > (u32)kCutCap) { if (tid == 0) a.fallback[r] = 1u; return; }
+        for (u32 i = tid; i < nm; i += 1024) {
+            const u64 e = L[(u32)cutmem[i]];
+            cutmem[i] = (e & kTop) | lr_comp(e, w);
+        }
+        __syncthreads();
         const u32 rem = (k - 1) - (s_cut[1] + s_cut[2]);
         for (u32 i = tid; i < nm; i += 1024) {
             const u64 me = cutmem[i] & ~kTop;
@@ -373,31 +419,55 @@ __global__ __launch_bounds__(1024) void lr_bounds_kernel(LargeArgs a)
     __syncthreads();                                 // the histogram is dead from here on
     u64* tmem = (u64*)fh;                            // [ntg][tcap]
     const u32 tcap = ntg ? (u32)(kFB / 2) / (u32)ntg : 1u;
-    lr_for_each(L, nL, [&](u64 e) {
-        const u32 d = lr_fine(e, t_lo, sh);
-        if ((bitmap[d >> 5] >> (d & 31)) & 1u) {
-            const int cls = (int)(e >> 63);
-            const int t0 = cls ? nt0 : 0, t1 = cls ? ntg : nt0;
-            for (int t = t0; t < t1; ++t) {
-                if (tgbin[t] == d) {
-                    const u32 slot = atomicAdd(&tcnt[t], 1u);
-                    if (slot < tcap) tmem[(u32)t * tcap + slot] = lr_comp(e, w);
-                }
-            }
+    // members of the boundary bins: their positions go to a flat list first (the cut's storage is
+    // free now), then one thread per hit finds its boundaries and fetches the member
+    u32* hitpos = (u32*)cutmem;
+    constexpr u32 kHitCap = 2 * kCutCap;
+    if (tid == 0) s_n[3] = 0;
+    __syncthreads();
+    lr_for_each_fine(Lfine, nL, [&](u32 p, const u32 (&v)[8], u32 nv) {
+        u32 hits = 0;
+#pragma unroll
+        for (int d = 0; d < 8; ++d) {
+            const u32 b = v[d] & 0x7FFFu;
+            hits |= ((u32)d < nv && ((bitmap[b >> 5] >> (b & 31u)) & 1u)) ? 1u << d : 0u;
+        }
+        while (hits) {
+            const u32 d = (u32)__builtin_ctz(hits);
+            hits &= hits - 1u;
+            const u32 slot = atomicAdd(&s_n[3], 1u);
+            if (slot < kHitCap) hitpos[slot] = p + d;
         }
     });
+    __syncthreads();
+    const u32 nhits = s_n[3];
+    if (nhits > kHitCap) { if (tid == 0) a.fallback[r] = 1u; return; }
+    for (u32 i = tid; i < nhits; i += 1024) {
+        const u32 p = hitpos[i];
+        const u64 e = L[p];
+        const u32 v = Lfine[p], d = v & 0x7FFFu;
+        const int cls = (int)(v >> 15);
+        const int t0 = cls ? nt0 : 0, t1 = cls ? ntg : nt0;
+        for (int t = t0; t < t1; ++t) {
+            if (tgbin[t] == d) {
+                const u32 slot = atomicAdd(&tcnt[t], 1u);
+                if (slot < tcap) tmem[(u32)t * tcap + slot] = lr_comp(e, w);
+            }
+        }
+    }
     __syncthreads();
     int over = 0;
     if (tid < ntg && tcnt[tid] > tcap) over = 1;
     if (__syncthreads_or(over)) { if (tid == 0) a.fallback[r] = 1u; return; }
+    const u32 nslots = (u32)ntg * tcap;              // <= kFB / 2
     u64* __restrict__ thr = a.thr + (size_t)r * (1 + kMaxB2);
-    for (int t = 0; t < ntg; ++t) {                  // the member with exactly `rem` class-mates above it
-        const u32 cnt = tcnt[t];
-        for (u32 i = tid; i < cnt; i += 1024) {
-            const u64 me = tmem[(u32)t * tcap + i];
+    for (u32 i = tid; i < nslots; i += 1024) {       // the member with exactly `rem` class-mates above it
+        const u32 t = i / tcap, sl = i - t * tcap, cnt = tcnt[t];
+        if (sl < cnt) {
+            const u64 me = tmem[i];
             u32 gt = 0;
-            for (u32 j = 0; j < cnt; ++j) gt += tmem[(u32)t * tcap + j] > me ? 1u : 0u;
-            if (gt == tgrem[t]) thr[1 + t] = me | (t >= nt0 ? 0ull : kTop);
+            for (u32 j = 0; j < cnt; ++j) gt += tmem[t * tcap + j] > me ? 1u : 0u;
+            if (gt == tgrem[t]) thr[1 + t] = me | ((int)t >= nt0 ? 0ull : kTop);
         }
     }
     if (tid == 0) {
@@ -424,15 +494,22 @@ __global__ __launch_bounds__(256) void lr_blockcount_kernel(LargeArgs a)
     const u32 nL = st[2];
     const u32 Kc[2] = { st[5], st[6] };
     const int ntg = (int)st[7], nt0 = (int)st[8];
+    const u64* __restrict__ L = a.L + (size_t)r * a.capL;
+    uint8_t* __restrict__ Lblk = a.Lblk + (size_t)r * a.capL;
+    const u32 p0 = (u32)lc * kLCE, p1 = p0 + kLCE < nL ? p0 + kLCE : nL;
+    constexpr int NJ = kLCE / 256;
+    u64 ev[NJ];
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) { const u32 p = p0 + (u32)j * 256 + (u32)tid; ev[j] = p < p1 ? L[p] : 0ull; }   // all loads in flight at once
     for (int i = tid; i <= ntg; i += 256) thr_s[i] = a.thr[(size_t)r * (1 + kMaxB2) + i];
     for (int b = tid; b < B2; b += 256) { cnt[b] = 0; kmin[b] = 0xFFFFFFFFu; kmax[b] = 0; }
     __syncthreads();
     const u64 thrK = thr_s[0];
-    const u64* __restrict__ L = a.L + (size_t)r * a.capL;
-    uint8_t* __restrict__ Lblk = a.Lblk + (size_t)r * a.capL;
-    const u32 p0 = (u32)lc * kLCE, p1 = p0 + kLCE < nL ? p0 + kLCE : nL;
-    for (u32 p = p0 + tid; p < p1; p += 256) {
-        const u64 e = L[p];
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+        const u32 p = p0 + (u32)j * 256 + (u32)tid;
+        if (p >= p1) break;
+        const u64 e = ev[j];
         const u64 comp = lr_comp(e, w);
         u32 b = 255u;
         if (comp >= thrK) {
@@ -459,35 +536,52 @@ __global__ __launch_bounds__(256) void lr_blockcount_kernel(LargeArgs a)
 template <int DT>
 __global__ __launch_bounds__(256) void lr_scatter_kernel(LargeArgs a)
 {
-    typedef Elem<DT> E;
     __shared__ u32 base[kMaxB2];
     __shared__ u32 cw[4][kMaxB2];
     const int tid = threadIdx.x, lc = blockIdx.x, wid = tid / kWave;
-    const u32 lane = lane_id();
     const int64_t r = blockIdx.y;
     if (a.fallback[r]) return;
     const int B2 = a.M + a.Mn;
     const u32 nL = a.rowst[(size_t)r * 16 + 2];
     if ((u32)lc * kLCE >= nL) return;
+    const u64* __restrict__ L = a.L + (size_t)r * a.capL;
+    const uint8_t* __restrict__ Lblk = a.Lblk + (size_t)r * a.capL;
+    // this thread's entries, all loads in flight at once
+    constexpr int NJ = kLCE / 256;
+    u32 bl[NJ];
+    u64 ev[NJ];
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+        const u32 p = (u32)lc * kLCE + (u32)j * 256 + (u32)tid;
+        bl[j] = p < nL ? (u32)Lblk[p] : 255u;
+        ev[j] = p < nL ? L[p] : 0ull;
+    }
     for (int b = tid; b < B2; b += 256) {
-        u32 s = a.blk_start[(size_t)r * (B2 + 1) + b];
-        for (int l2 = 0; l2 < lc; ++l2) s += a.blkcnt[((size_t)r * a.LC + l2) * B2 + b];
-        base[b] = s;
+        base[b] = a.blk_start[(size_t)r * (B2 + 1) + b];
         for (int v2 = 0; v2 < 4; ++v2) cw[v2][b] = 0;
+    }
+    __syncthreads();
+    {   // plus the block counts of the list chunks before this one (contiguous: [chunk][block])
+        const u32* __restrict__ bc = a.blkcnt + (size_t)r * a.LC * B2;
+        const u32 tot = (u32)lc * (u32)B2;
+        for (u32 i0 = (u32)tid; i0 < tot; i0 += 256 * 8) {
+            u32 t[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) { const u32 i = i0 + (u32)u * 256; t[u] = i < tot ? bc[i] : 0u; }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) { const u32 i = i0 + (u32)u * 256; if (t[u]) atomicAdd(&base[i % (u32)B2], t[u]); }
+        }
     }
     __syncthreads();
     int nbits = 0;
     while ((1 << nbits) < B2) ++nbits;
-    const u64* __restrict__ L = a.L + (size_t)r * a.capL;
-    const uint8_t* __restrict__ Lblk = a.Lblk + (size_t)r * a.capL;
     u32* __restrict__ bo_idx = a.bo_idx + (size_t)r * (size_t)a.k;
     u32* __restrict__ bo_val = a.bo_val + (size_t)r * (size_t)a.k;
-    for (int j = 0; j < kLCE / 256; ++j) {
-        const u32 p = (u32)lc * kLCE + (u32)j * 256 + (u32)tid;
-        u32 b = 0;
-        bool kept = false;
-        u64 e = 0;
-        if (p < nL) { b = Lblk[p]; kept = b != 255u; if (kept) e = L[p]; else b = 0; }
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+        const bool kept = bl[j] != 255u;
+        const u32 b = kept ? bl[j] : 0u;
+        const u64 e = ev[j];
         const u64 km = __ballot(kept);
         u32 plo = (u32)km, phi = (u32)(km >> 32);
         for (int bit = 0; bit < nbits; ++bit) {
@@ -517,10 +611,14 @@ __global__ __launch_bounds__(256) void lr_scatter_kernel(LargeArgs a)
     }
 }
 
-template <int DT>
+// NQ > 0: the number of allowed bitwidths is known at compile time; NQ == 0: any number up to 16.
+template <int DT, int NQ>
 __global__ __launch_bounds__(256) void lr_abq_kernel(LargeArgs a)
 {
     typedef Elem<DT> E;
+    constexpr int QN = NQ ? NQ : kMaxQ;
+    constexpr int NJ = kPCH / 256;               // entries per thread: u32 partial sums hold 8 residuals of 2^28
+    static_assert(NJ <= 8, "u32 partial sums");
     __shared__ u32 bs[kMaxB2 + 1];
     __shared__ float vminf[kMaxB2];
     __shared__ int e_tab[kMaxB2], degen[kMaxB2];
@@ -529,11 +627,15 @@ __global__ __launch_bounds__(256) void lr_abq_kernel(LargeArgs a)
     const int tid = threadIdx.x, pc = blockIdx.x;
     const int64_t r = blockIdx.y;
     if (a.fallback[r]) return;
-    const int B2 = a.M + a.Mn, nq = a.nq;
+    const int B2 = a.M + a.Mn, nq = NQ ? NQ : a.nq;
     const u32* st = a.rowst + (size_t)r * 16;
     const u32 n = st[3] + st[4];
     const u32 p0 = (u32)pc * kPCH, p1 = p0 + kPCH < n ? p0 + kPCH : n;
     if (p0 >= n) return;
+    const u32* __restrict__ bo_val = a.bo_val + (size_t)r * (size_t)a.k;
+    u32 vb[NJ];
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) { const u32 p = p0 + (u32)j * 256 + (u32)tid; vb[j] = p < p1 ? bo_val[p] : 0u; }   // all loads in flight at once
     for (int b = tid; b <= B2; b += 256) bs[b] = a.blk_start[(size_t)r * (B2 + 1) + b];
     __syncthreads();
     for (int b = tid; b < B2; b += 256) {
@@ -554,51 +656,73 @@ __global__ __launch_bounds__(256) void lr_abq_kernel(LargeArgs a)
         }
         sums[b][kMaxQ] = 0;
     }
+    bool small_q = true;
+#pragma unroll
+    for (int t = 0; t < QN; ++t)
+        if ((NQ || t < nq) && a.qlist[t] > 8) small_q = false;
     __syncthreads();
     {
-        const u32* __restrict__ bo_val = a.bo_val + (size_t)r * (size_t)a.k;
         int cur = -1;
-        u64 acc[kMaxQ];
+        u32 acc[QN];
         u64 accE = 0;
+        float inv[QN], inv15[QN];
 #pragma unroll
-        for (int t = 0; t < kMaxQ; ++t) acc[t] = 0;
+        for (int t = 0; t < QN; ++t) { acc[t] = 0; inv[t] = 0.f; inv15[t] = 0.f; }
         float vmin = 0.f;
         int e = 0, dg = 1;
         auto flush = [&]() {
             if (cur < 0) return;
 #pragma unroll
-            for (int t = 0; t < kMaxQ; ++t)
-                if (t < nq && acc[t]) { atomicAdd(&sums[cur][t], acc[t]); acc[t] = 0; }
+            for (int t = 0; t < QN; ++t)
+                if ((NQ || t < nq) && acc[t]) { atomicAdd(&sums[cur][t], (u64)acc[t]); acc[t] = 0; }
             if (accE) { atomicAdd(&sums[cur][kMaxQ], accE); accE = 0; }
         };
-        for (u32 p = p0 + tid; p < p1; p += 256) {
+        const int top = nq - 1, qtop = a.qlist[top];
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+            const u32 p = p0 + (u32)j * 256 + (u32)tid;
+            if (p >= p1) break;
             int b = cur < 0 ? 0 : cur;
             while (b < B2 - 1 && p >= bs[b + 1]) ++b;
-            if (b != cur) { flush(); cur = b; vmin = vminf[b]; e = e_tab[b]; dg = degen[b]; }
-            const float av = __uint_as_float(bo_val[p]);
-            const u64 A = (u64)(u32)rintf(ldexpf(av, 20 - e));
-            accE += A * A;
-            if (!dg && a.guard == 1) {
-                const float d = av - vmin;
-                const int top = nq - 1, qtop = a.qlist[top];
-                const u32 c0 = (u32)fminf(fmaxf(rintf(d * inv_tab[b][top]), 0.f), (float)((1u << qtop) - 1u));
+            if (b != cur) {
+                flush();
+                cur = b; vmin = vminf[b]; e = e_tab[b]; dg = degen[b];
 #pragma unroll
-                for (int t = 0; t < kMaxQ; ++t) {
-                    if (t < top) {
-                        const u32 c = (u32)fminf(fmaxf(rintf(d * inv_tab[b][t]), 0.f), (float)((1u << a.qlist[t]) - 1u));
-                        const u32 ref = c0 >> (qtop - a.qlist[t]);
-                        acc[t] += (u64)(ref > c ? ref - c : c - ref);
+                for (int t = 0; t < QN; ++t) {
+                    inv[t] = (NQ || t < nq) ? inv_tab[b][t] : 0.f;
+                    inv15[t] = inv[t] * 32768.0f;        // finite for bitwidths up to 8 (scale <= 255 * 2^100)
+                }
+            }
+            const float av = __uint_as_float(vb[j]);
+            const u64 A = (u64)(u32)rintf(ldexpf(av, 20 - e));     // 20-bit energy grid scaled to vmax
+            accE += A * A;
+            if (dg) continue;
+            const float d = av - vmin;
+            if (a.guard == 1) {
+                // Eq. "DS": | (code at q_bit >> (q_bit - q)) - code at q | for every lower bitwidth
+                float inv_top = 0.f;
+#pragma unroll
+                for (int t = 0; t < QN; ++t) inv_top = t == top ? inv[t] : inv_top;
+                const u32 c0 = (u32)rintf(d * inv_top);               // within [0, 2^q - 1]: no clamp needed
+#pragma unroll
+                for (int t = 0; t < QN; ++t) {
+                    if ((NQ || t < nq) && t < top) {
+                        const u32 c = (u32)rintf(d * inv[t]);
+                        const u32 ref = c0 >> (u32)(qtop - a.qlist[t]);
+                        acc[t] += ref > c ? ref - c : c - ref;
                     }
                 }
-            } else if (!dg) {
-                const float d = av - vmin;
+            } else {
+                // residual on the 2^-15 grid: rint(y * 2^15) reduced to 15 signed bits (Sec. 3.2.1 metric
+                // in the code domain); bitwidths up to 8 keep y * 2^15 below 2^23, where adding 2^23
+                // rounds to the integer grid with the same round-half-even
 #pragma unroll
-                for (int t = 0; t < kMaxQ; ++t) {
-                    if (t < nq) {
-                        const float y = d * inv_tab[b][t];
-                        const float c = fminf(fmaxf(rintf(y), 0.f), (float)((1u << a.qlist[t]) - 1u));
-                        const int rho = (int)rintf((y - c) * 32768.0f);
-                        acc[t] += (u64)(u32)(rho * rho);
+                for (int t = 0; t < QN; ++t) {
+                    if (NQ || t < nq) {
+                        const u32 zi = small_q ? __float_as_uint(d * inv15[t] + 8388608.0f)
+                                               : (u32)rintf((d * inv[t]) * 32768.0f);
+                        const int rho = __builtin_amdgcn_sbfe((int)zi, 0u, 15u);
+                        acc[t] += (u32)(rho * rho);
                     }
                 }
             }
@@ -697,7 +821,8 @@ __global__ __launch_bounds__(256) void lr_pack_kernel(LargeArgs a)
     if (a.fallback[r]) return;
     const int B2 = a.M + a.Mn, w = a.w;
     const u64 row_words = a.row_words[r];
-    const u64 c0 = (u64)blockIdx.x * kPackWords;
+    const u32 PW = (u32)a.pack_words;             // stream words per workgroup, <= kPackWords
+    const u64 c0 = (u64)blockIdx.x * PW;
     if (c0 >= row_words) return;
     const u32* st = a.rowst + (size_t)r * 16;
     const u32 n = st[3] + st[4];
@@ -710,7 +835,7 @@ __global__ __launch_bounds__(256) void lr_pack_kernel(LargeArgs a)
             vminf[b] = __uint_as_float(E::value_bits(a.vminb[r * B2 + b]));
         }
     }
-    const u64 cw = row_words - c0 < (u64)kPackWords ? row_words - c0 : (u64)kPackWords;
+    const u64 cw = row_words - c0 < (u64)PW ? row_words - c0 : (u64)PW;
     const u64 lo = c0 << 5, hi = (c0 + cw) << 5;
     const u64 idx_bits = (u64)n * (u64)w;
     for (int i = tid; i < (int)cw; i += 256) sA[i] = 0;
@@ -734,20 +859,37 @@ __global__ __launch_bounds__(256) void lr_pack_kernel(LargeArgs a)
         const u64 q0 = lo / (u64)w;
         u64 q1 = (hi + (u64)w - 1) / (u64)w;
         if (q1 > n) q1 = n;
-        for (u64 p = q0 + tid; p < q1; p += 256) stage_or_bits(sA, lo, hi, p * (u64)w, bo_idx[p], w);
+        for (u64 pb = q0 + tid; pb < q1; pb += 256 * 8) {        // eight independent loads in flight
+            u32 v8[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) { const u64 p = pb + (u64)u * 256; v8[u] = p < q1 ? bo_idx[p] : 0u; }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const u64 p = pb + (u64)u * 256;
+                if (p < q1) stage_or_bits(sA, lo, hi, p * (u64)w, v8[u], w);
+            }
+        }
     }
     {
         const u32 q0 = s_range[0], q1 = s_range[1];
         int b = 0;
-        for (u32 p = q0 + tid; p < q1; p += 256) {
-            while (b < B2 - 1 && p >= bs[b + 1]) ++b;
-            const int q = (int)qsel[b];
-            u32 c = 0;
-            if (invs[b] != 0.f) {
-                const float y = (__uint_as_float(bo_val[p]) - vminf[b]) * invs[b];
-                c = (u32)fminf(fmaxf(rintf(y), 0.f), (float)((1u << q) - 1u));
+        for (u32 pb = q0 + tid; pb < q1; pb += 256 * 8) {
+            u32 v8[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) { const u32 p = pb + (u32)u * 256; v8[u] = p < q1 ? bo_val[p] : 0u; }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const u32 p = pb + (u32)u * 256;
+                if (p >= q1) break;
+                while (b < B2 - 1 && p >= bs[b + 1]) ++b;
+                const int q = (int)qsel[b];
+                u32 c = 0;
+                if (invs[b] != 0.f) {
+                    const float y = (__uint_as_float(v8[u]) - vminf[b]) * invs[b];
+                    c = (u32)fminf(fmaxf(rintf(y), 0.f), (float)((1u << q) - 1u));
+                }
+                stage_or_bits(sA, lo, hi, idx_bits + coff[b] + (u64)(p - bs[b]) * (u64)q, c, q);
             }
-            stage_or_bits(sA, lo, hi, idx_bits + coff[b] + (u64)(p - bs[b]) * (u64)q, c, q);
         }
     }
     __syncthreads();
