@@ -66,7 +66,7 @@ struct Plan {
     int large_C, large_LC;
     u32 large_capL;
     size_t lo_ch_cum, lo_ch_off, lo_L, lo_Lblk, lo_Lfine, lo_rowst, lo_thr, lo_blk_start,
-           lo_blkcnt, lo_vminb, lo_vmaxb, lo_sums, lo_qsel, lo_inv_sel, lo_code_off;
+           lo_blkcnt, lo_vminb, lo_vmaxb, lo_sums, lo_qsel, lo_inv_sel, lo_code_off, lo_win_range;
 };
 
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
@@ -115,6 +115,7 @@ Plan make_plan(int dt, int64_t rows, int64_t row_len, double keep_ratio, int n_b
             p.lo_qsel = o;      o = align256(o + 4 * R * B2);
             p.lo_inv_sel = o;   o = align256(o + 4 * R * B2);
             p.lo_code_off = o;  o = align256(o + 8 * R * (B2 + 1));
+            p.lo_win_range = o; o = align256(o + 8 * R * (size_t)(p.cap_words / 64 + 8));    // pack windows of >= 64 words
         }
     }
     p.total = o ? o : 256;
@@ -182,7 +183,7 @@ int launch_large(const LargeArgs& la, const Plan& p, hipStream_t st)
 {
     const dim3 gC((unsigned)la.C, (unsigned)la.R), gL((unsigned)la.LC, (unsigned)la.R), gR((unsigned)la.R);
     const dim3 gP((unsigned)std::max<int64_t>(1, (la.k + kPCH - 1) / kPCH), (unsigned)la.R);
-    const dim3 gW((unsigned)std::max<u64>(1, (p.cap_words + (u64)la.pack_words - 1) / (u64)la.pack_words), (unsigned)la.R);
+    const dim3 gW((unsigned)la.nwin, (unsigned)la.R);
     hipLaunchKernelGGL((lr_hist_kernel<DT>), gC, dim3(256), 0, st, la);
     hipLaunchKernelGGL((lr_select_kernel<DT>), gR, dim3(1024), 0, st, la);
     hipLaunchKernelGGL((lr_compact_kernel<DT>), gC, dim3(256), 0, st, la);
@@ -347,8 +348,18 @@ static int encode_impl(const void* x, slicer_dtype dt, int64_t rows, int64_t row
         for (int t = 0; t < kMaxQ; ++t) la.qlist[t] = ea.qlist[t];
         la.beta = distortion_budget; la.cap_words = p.cap_words;
         la.C = p.large_C; la.LC = p.large_LC; la.capL = p.large_capL;
-        la.pack_words = kPackWords;               // fewer words per workgroup while the launch is small
+        // pack windows: index fields are w bits, code fields as short as one bit, so the windows
+        // from the first code bit on are a quarter of the others; all are smaller while the launch is small
+        la.pack_words = kPackWords;
         while (la.pack_words > 128 && (u64)rows * ((p.cap_words + (u64)la.pack_words - 1) / (u64)la.pack_words) < 1024) la.pack_words /= 2;
+        la.pack_words_code = std::max(64, la.pack_words / 4);
+        {
+            const u64 idx_words_max = ((u64)p.k * (u64)p.w) / 32;                              // largest first word with code bits
+            la.nwin_idx = (int)((idx_words_max + (u64)la.pack_words - 1) / (u64)la.pack_words);
+            const u64 code_words_max = ((u64)p.k * (u64)p.qmax + 31) / 32 + 2;                  // words from there to the end
+            la.nwin = la.nwin_idx + (int)((code_words_max + (u64)la.pack_words_code - 1) / (u64)la.pack_words_code);
+        }
+        la.win_range = (u32*)(ws + p.lo_win_range);
         la.ch_cum = (u32*)(ws + p.lo_ch_cum);     la.ch_off = (u32*)(ws + p.lo_ch_off);
         la.L = (u64*)(ws + p.lo_L);               la.Lblk = (uint8_t*)(ws + p.lo_Lblk);
         la.Lfine = (uint16_t*)(ws + p.lo_Lfine);

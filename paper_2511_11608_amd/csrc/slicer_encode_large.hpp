@@ -43,7 +43,11 @@ struct LargeArgs {
     double beta;
     u64 cap_words;
     int C, LC;              // chunks per row, list chunks per row
-    int pack_words;         // stream words per pack workgroup (<= kPackWords)
+    int pack_words;         // stream words per pack workgroup in the index section (<= kPackWords)
+    int pack_words_code;    // ... from the first word with code bits on (fields there are short: fewer words per workgroup)
+    int nwin_idx;           // windows that lie in the index section for sure (worst case of its length)
+    int nwin;               // pack workgroups (windows) per row
+    u32* win_range;         // [R][nwin][2] block-ordered entries whose code field meets the window
     u32 capL;               // list capacity per row
     u32* ch_cum;            // [R][C][kLBins]  elements of the chunk at or above the bin
     u32* ch_off;            // [R][C]
@@ -727,7 +731,25 @@ __global__ __launch_bounds__(256) void lr_abq_kernel(LargeArgs a)
                 }
             }
         }
-        flush();
+        // The positions of a wavefront are consecutive, so its lanes are nearly always in one
+        // block: the sums are then added up across the wavefront first (16-bit and 22-bit
+        // pieces, so that the lane sums fit 32 bits) and one lane adds them to the table.
+        const int cur0 = __builtin_amdgcn_readfirstlane(cur);
+        if (__all(cur == cur0)) {
+            if (cur0 >= 0) {
+#pragma unroll
+                for (int t = 0; t < QN; ++t) {
+                    if (NQ || t < nq) {
+                        const u32 lo16 = wave_sum(acc[t] & 0xFFFFu), hi16 = wave_sum(acc[t] >> 16);
+                        if ((tid & (kWave - 1)) == 0 && (lo16 | hi16)) atomicAdd(&sums[cur0][t], (u64)lo16 + ((u64)hi16 << 16));
+                    }
+                }
+                const u32 e0 = wave_sum((u32)accE & 0x3FFFFFu), e1 = wave_sum((u32)(accE >> 22) & 0x3FFFFFu), e2 = wave_sum((u32)(accE >> 44));
+                if ((tid & (kWave - 1)) == 0 && (e0 | e1 | e2)) atomicAdd(&sums[cur0][kMaxQ], (u64)e0 + ((u64)e1 << 22) + ((u64)e2 << 44));
+            }
+        } else {
+            flush();
+        }
     }
     __syncthreads();
     for (int i = tid; i < B2 * (nq + 1); i += 256) {
@@ -737,11 +759,32 @@ __global__ __launch_bounds__(256) void lr_abq_kernel(LargeArgs a)
     }
 }
 
+// Window x of a row's slot for the pack stage: windows of pack_words words up to the first word
+// that holds code bits (word wb), windows of pack_words_code words from there on.  Returns the
+// first word and the number of words (0: nothing to do).
+__device__ inline void lr_pack_window(const LargeArgs& a, int x, u64 wb, u64 row_words, u64* c0, u64* cw)
+{
+    u64 lo, hi;
+    if (x < a.nwin_idx) {
+        lo = (u64)x * (u64)a.pack_words;
+        hi = lo + (u64)a.pack_words;
+        hi = hi < wb ? hi : wb;
+    } else {
+        lo = wb + (u64)(x - a.nwin_idx) * (u64)a.pack_words_code;
+        hi = lo + (u64)a.pack_words_code;
+    }
+    hi = hi < row_words ? hi : row_words;
+    *c0 = lo;
+    *cw = hi > lo ? hi - lo : 0;
+}
+
 template <int DT>
 __global__ __launch_bounds__(128) void lr_choose_kernel(LargeArgs a)
 {
     typedef Elem<DT> E;
-    __shared__ u32 bits_s[kMaxB2];
+    __shared__ u32 bits_s[kMaxB2], q_s[kMaxB2], bs_s[kMaxB2 + 1];
+    __shared__ u64 co_s[kMaxB2 + 1];
+    __shared__ u64 s_words;
     const int b = threadIdx.x;
     const int64_t r = blockIdx.x;
     if (a.fallback[r]) return;
@@ -788,6 +831,9 @@ __global__ __launch_bounds__(128) void lr_choose_kernel(LargeArgs a)
         }
         a.qsel[r * B2 + b] = (u32)q;
         a.inv_sel[r * B2 + b] = inv;
+        q_s[b] = (u32)q;
+        bs_s[b] = a.blk_start[(size_t)r * (B2 + 1) + b];
+        if (b == B2 - 1) bs_s[B2] = bs_s[b] + cnt;
         bits_s[b] = cnt * (u32)q;             // < 2^31 * 16 would overflow: the list capacity keeps cnt small
         const size_t mi = (size_t)r * (size_t)B2 + b;
         a.mv.vmin[mi] = vmin; a.mv.vmax[mi] = vmax; a.mv.q[mi] = (uint8_t)((u32)q | flag);
@@ -796,100 +842,178 @@ __global__ __launch_bounds__(128) void lr_choose_kernel(LargeArgs a)
     if (b == 0) {
         u64 acc = 0;
         u64* co = a.code_off + (size_t)r * (B2 + 1);
-        for (int i = 0; i < B2; ++i) { co[i] = acc; acc += bits_s[i]; }
-        co[B2] = acc;
+        for (int i = 0; i < B2; ++i) { co[i] = acc; co_s[i] = acc; acc += bits_s[i]; }
+        co[B2] = acc; co_s[B2] = acc;
         const u64 bits = (u64)n * (u64)a.w + acc;
         u64 words = (bits + 31) >> 5;
         if (words > a.cap_words) words = a.cap_words;
         a.row_words[r] = words;
+        s_words = words;
         a.mv.n_pos[r] = st[3];
         a.mv.n_neg[r] = st[4];
     }
+    __syncthreads();
+    // for every window of the pack stage: the block-ordered entries whose code field meets it
+    {
+        const u64 idx_bits = (u64)n * (u64)a.w;
+        for (int wi = b; wi < a.nwin; wi += 128) {
+            u64 c0, cw;
+            lr_pack_window(a, wi, idx_bits >> 5, s_words, &c0, &cw);
+            const u64 lo = c0 << 5, hi = (c0 + cw) << 5;
+            u32 e0 = n, e1 = 0;
+            if (lo < hi) {
+                for (int i = 0; i < B2; ++i) {
+                    const u32 cnt = bs_s[i + 1] - bs_s[i];
+                    const u64 cs = idx_bits + co_s[i], ce = idx_bits + co_s[i + 1];
+                    if (!cnt || ce <= lo || cs >= hi) continue;
+                    const u32 q = q_s[i];
+                    const u32 dlo = (u32)((lo > cs ? lo : cs) - cs), dhi = (u32)((hi < ce ? hi : ce) - cs);   // < 2^31: one block's bits
+                    const u32 f0 = bs_s[i] + dlo / q, f1 = bs_s[i] + (dhi + q - 1) / q;
+                    e0 = f0 < e0 ? f0 : e0;
+                    e1 = f1 > e1 ? f1 : e1;
+                }
+            }
+            a.win_range[((size_t)r * a.nwin + wi) * 2 + 0] = e0;
+            a.win_range[((size_t)r * a.nwin + wi) * 2 + 1] = e1;
+        }
+    }
 }
+
+// A thread packs a run of consecutive fields into whole words in registers and writes each
+// word of the window image once: the first and the last word of a run may be shared with the
+// neighbouring runs (atomic OR), the words between belong to this run alone (plain store).
+struct RunPacker {
+    u32* stage;
+    int nwords;          // words of the window
+    u64 acc;
+    int fill, wi;
+    bool first;
+    __device__ inline void begin(u32* st, int nw, int rel)      // rel: first bit, relative to the window (may be negative)
+    {
+        stage = st; nwords = nw;
+        wi = rel >> 5; fill = rel & 31; acc = 0; first = true;
+    }
+    __device__ inline void put(u32 wd, bool shared)
+    {
+        if (wi >= 0 && wi < nwords) {
+            if (shared) atomicOr(&stage[wi], wd); else stage[wi] = wd;
+        }
+    }
+    __device__ inline void append(u32 v, int nb)                 // nb <= 32, v < 2^nb
+    {
+        acc |= (u64)v << fill;
+        fill += nb;
+        if (fill >= 32) {
+            put((u32)acc, first);
+            first = false;
+            acc >>= 32; fill -= 32; ++wi;
+        }
+    }
+    __device__ inline void finish() { if (fill > 0) put((u32)acc, true); }
+};
 
 template <int DT>
 __global__ __launch_bounds__(256) void lr_pack_kernel(LargeArgs a)
 {
     typedef Elem<DT> E;
+    constexpr int RUN = 8;                        // consecutive entries per thread and run
     __shared__ u32 sA[kPackWords];
     __shared__ u32 bs[kMaxB2 + 1], qsel[kMaxB2];
-    __shared__ u64 coff[kMaxB2 + 1];
+    __shared__ u32 crel[kMaxB2];                  // first code bit of the block relative to the window, modulo 2^32
     __shared__ float vminf[kMaxB2], invs[kMaxB2];
-    __shared__ u32 s_range[2];
     const int tid = threadIdx.x;
     const int64_t r = blockIdx.y;
-    if (a.fallback[r]) return;
     const int B2 = a.M + a.Mn, w = a.w;
+    // everything the workgroup needs to know its work, in one round of loads
+    const u32 fb = a.fallback[r];
     const u64 row_words = a.row_words[r];
-    const u32 PW = (u32)a.pack_words;             // stream words per workgroup, <= kPackWords
-    const u64 c0 = (u64)blockIdx.x * PW;
-    if (c0 >= row_words) return;
-    const u32* st = a.rowst + (size_t)r * 16;
-    const u32 n = st[3] + st[4];
-    for (int b = tid; b <= B2; b += 256) {
-        bs[b] = a.blk_start[(size_t)r * (B2 + 1) + b];
-        coff[b] = a.code_off[(size_t)r * (B2 + 1) + b];
-        if (b < B2) {
-            qsel[b] = a.qsel[r * B2 + b];
-            invs[b] = a.inv_sel[r * B2 + b];
-            vminf[b] = __uint_as_float(E::value_bits(a.vminb[r * B2 + b]));
-        }
-    }
-    const u64 cw = row_words - c0 < (u64)PW ? row_words - c0 : (u64)PW;
-    const u64 lo = c0 << 5, hi = (c0 + cw) << 5;
+    const u32 n = a.rowst[(size_t)r * 16 + 3] + a.rowst[(size_t)r * 16 + 4];
+    // the windows with code fields hold the most entries: they are started first
+    const int nwc = a.nwin - a.nwin_idx;
+    const int win = (int)blockIdx.x < nwc ? a.nwin_idx + (int)blockIdx.x : (int)blockIdx.x - nwc;
+    const u32 cq0 = a.win_range[((size_t)r * a.nwin + win) * 2 + 0];
+    const u32 cq1 = a.win_range[((size_t)r * a.nwin + win) * 2 + 1];
+    if (fb) return;
     const u64 idx_bits = (u64)n * (u64)w;
-    for (int i = tid; i < (int)cw; i += 256) sA[i] = 0;
-    __syncthreads();
-    if (tid == 0) { s_range[0] = n; s_range[1] = 0; }
-    __syncthreads();
-    for (int b = tid; b < B2; b += 256) {     // entries whose code field meets [lo, hi), one thread per block
-        const u32 cnt = bs[b + 1] - bs[b];
-        if (!cnt) continue;
-        const u64 cs = idx_bits + coff[b], ce = idx_bits + coff[b + 1];
-        if (ce <= lo || cs >= hi) continue;
-        const u32 q = qsel[b];
-        const u32 dlo = (u32)((lo > cs ? lo : cs) - cs), dhi = (u32)((hi < ce ? hi : ce) - cs);   // < 2^31: one block's bits
-        atomicMin(&s_range[0], bs[b] + dlo / q);
-        atomicMax(&s_range[1], bs[b] + (dhi + q - 1) / q);
-    }
-    __syncthreads();
+    u64 c0, cw;
+    lr_pack_window(a, win, idx_bits >> 5, row_words, &c0, &cw);
+    if (cw == 0) return;
+    const u64 lo = c0 << 5, hi = (c0 + cw) << 5;
     const u32* __restrict__ bo_idx = a.bo_idx + (size_t)r * (size_t)a.k;
     const u32* __restrict__ bo_val = a.bo_val + (size_t)r * (size_t)a.k;
+    // index fields that meet the window
+    u32 iq0 = 0, iq1 = 0;
     if (lo < idx_bits) {
-        const u64 q0 = lo / (u64)w;
-        u64 q1 = (hi + (u64)w - 1) / (u64)w;
-        if (q1 > n) q1 = n;
-        for (u64 pb = q0 + tid; pb < q1; pb += 256 * 8) {        // eight independent loads in flight
-            u32 v8[8];
+        iq0 = (u32)(lo / (u64)w);
+        const u64 t1 = (hi + (u64)w - 1) / (u64)w;
+        iq1 = t1 > (u64)n ? n : (u32)t1;
+    }
+    // first run of both sections: the loads are in flight while the block tables arrive
+    u32 vi[RUN], vc[RUN];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) { const u64 p = pb + (u64)u * 256; v8[u] = p < q1 ? bo_idx[p] : 0u; }
+    for (int u = 0; u < RUN; ++u) { const u32 p = iq0 + (u32)tid * RUN + (u32)u; vi[u] = p < iq1 ? bo_idx[p] : 0u; }
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const u64 p = pb + (u64)u * 256;
-                if (p < q1) stage_or_bits(sA, lo, hi, p * (u64)w, v8[u], w);
+    for (int u = 0; u < RUN; ++u) { const u32 p = cq0 + (u32)tid * RUN + (u32)u; vc[u] = p < cq1 ? bo_val[p] : 0u; }
+    for (int b = tid; b < B2; b += 256) {
+        const u32 b0 = a.blk_start[(size_t)r * (B2 + 1) + b];
+        bs[b] = b0;
+        if (b == B2 - 1) bs[B2] = a.blk_start[(size_t)r * (B2 + 1) + B2];
+        qsel[b] = a.qsel[r * B2 + b];
+        invs[b] = a.inv_sel[r * B2 + b];
+        vminf[b] = __uint_as_float(E::value_bits(a.vminb[r * B2 + b]));
+        crel[b] = (u32)(idx_bits + a.code_off[(size_t)r * (B2 + 1) + b] - lo);
+    }
+    for (int i = tid; i < (int)cw; i += 256) sA[i] = 0;
+    __syncthreads();
+    // Bit positions are taken relative to the window in 32-bit arithmetic: the true value of
+    // every position handled here lies within a few bits of the window, so the wrapped
+    // difference is exact.
+    RunPacker rp;
+    {
+        const u32 lo32 = (u32)lo;
+        for (u32 p0 = iq0 + (u32)tid * RUN; p0 < iq1; p0 += 256 * RUN) {
+            if (p0 != iq0 + (u32)tid * RUN) {
+#pragma unroll
+                for (int u = 0; u < RUN; ++u) { const u32 p = p0 + (u32)u; vi[u] = p < iq1 ? bo_idx[p] : 0u; }
             }
+            rp.begin(sA, (int)cw, (int)(p0 * (u32)w - lo32));
+#pragma unroll
+            for (int u = 0; u < RUN; ++u)
+                if (p0 + (u32)u < iq1) rp.append(vi[u], w);
+            rp.finish();
         }
     }
     {
-        const u32 q0 = s_range[0], q1 = s_range[1];
+        // the block's constants stay in registers until the position leaves the block; the code
+        // sections of consecutive blocks are contiguous in the stream, so a run may cross blocks
         int b = 0;
-        for (u32 pb = q0 + tid; pb < q1; pb += 256 * 8) {
-            u32 v8[8];
+        for (u32 p0 = cq0 + (u32)tid * RUN; p0 < cq1; p0 += 256 * RUN) {
+            if (p0 != cq0 + (u32)tid * RUN) {
 #pragma unroll
-            for (int u = 0; u < 8; ++u) { const u32 p = pb + (u32)u * 256; v8[u] = p < q1 ? bo_val[p] : 0u; }
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const u32 p = pb + (u32)u * 256;
-                if (p >= q1) break;
-                while (b < B2 - 1 && p >= bs[b + 1]) ++b;
-                const int q = (int)qsel[b];
-                u32 c = 0;
-                if (invs[b] != 0.f) {
-                    const float y = (__uint_as_float(v8[u]) - vminf[b]) * invs[b];
-                    c = (u32)fminf(fmaxf(rintf(y), 0.f), (float)((1u << q) - 1u));
-                }
-                stage_or_bits(sA, lo, hi, idx_bits + coff[b] + (u64)(p - bs[b]) * (u64)q, c, q);
+                for (int u = 0; u < RUN; ++u) { const u32 p = p0 + (u32)u; vc[u] = p < cq1 ? bo_val[p] : 0u; }
             }
+            while (b < B2 - 1 && p0 >= bs[b + 1]) ++b;
+            u32 b_end = b < B2 - 1 ? bs[b + 1] : 0xFFFFFFFFu;
+            int q = (int)qsel[b];
+            float inv = invs[b], vmin = vminf[b], qmaxf = (float)((1u << q) - 1u);
+            rp.begin(sA, (int)cw, (int)(crel[b] + (p0 - bs[b]) * (u32)q));
+#pragma unroll
+            for (int u = 0; u < RUN; ++u) {
+                const u32 p = p0 + (u32)u;
+                if (p >= cq1) break;
+                if (p >= b_end) {
+                    while (b < B2 - 1 && p >= bs[b + 1]) ++b;
+                    b_end = b < B2 - 1 ? bs[b + 1] : 0xFFFFFFFFu;
+                    q = (int)qsel[b]; inv = invs[b]; vmin = vminf[b]; qmaxf = (float)((1u << q) - 1u);
+                }
+                u32 c = 0;
+                if (inv != 0.f) {
+                    const float y = (__uint_as_float(vc[u]) - vmin) * inv;
+                    c = (u32)fminf(fmaxf(rintf(y), 0.f), qmaxf);
+                }
+                rp.append(c, q);
+            }
+            rp.finish();
         }
     }
     __syncthreads();
