@@ -221,7 +221,8 @@ int launch_decode(const void* stream, const void* meta, void* y, int dt, int64_t
     da.stream = (const u32*)stream;
     da.y = y;
     da.R = rows; da.N = row_len; da.M = n_blocks; da.Mn = n_blocks_neg; da.w = index_bits(row_len);
-    da.chunks_per_row = (int)((row_len + kDecChunk - 1) / kDecChunk);
+    const int64_t dec_chunk = kDecChunkBytes / (dt == SLICER_F32 ? 4 : 2);
+    da.chunks_per_row = (int)((row_len + dec_chunk - 1) / dec_chunk);
     da.mv = meta_view(const_cast<void*>(meta), rows, n_blocks + n_blocks_neg);
     da.total_words = (const u64*)meta + 6;
     // the stream segment of a row at keep ratios up to about 0.2 (longer segments are read from global memory)

@@ -8,7 +8,7 @@
 
 namespace slicer {
 
-constexpr int kDecChunk = 8192;   // output elements per workgroup
+constexpr int kDecChunkBytes = 16384;   // output bytes per workgroup of the long-row decoder (its LDS image)
 
 struct DecArgs {
     const u32* stream;
@@ -25,12 +25,15 @@ template <int DT, int BLOCK>
 __global__ __launch_bounds__(BLOCK) void dec_kernel(DecArgs a)
 {
     typedef typename Elem<DT>::raw_t raw_t;
+    constexpr int kDecChunk = kDecChunkBytes / (int)sizeof(raw_t);
     __shared__ raw_t tile[kDecChunk];
     __shared__ float vminf[kMaxB2], stepf[kMaxB2];
     __shared__ int qv[kMaxB2];
     __shared__ u32 istart[kMaxB2 + 1];     // first element of the block in stream order
     __shared__ u64 cstart[kMaxB2 + 1];     // first code bit of the block
+    __shared__ u64 cbits[kMaxB2];          // code bits of the block
     __shared__ u32 act_lo[kMaxB2];         // first element of the block that lands in this chunk
+    __shared__ u32 s_hi[kMaxB2];           // first element of the block beyond this chunk
     __shared__ u32 pre[kMaxB2 + 1];        // prefix of per-block counts landing in this chunk
 
     const int tid = threadIdx.x;
@@ -44,6 +47,8 @@ __global__ __launch_bounds__(BLOCK) void dec_kernel(DecArgs a)
     if ((u64)n_cls[0] + n_cls[1] > (u64)a.N) n_cls[0] = n_cls[1] = 0;   // not a valid row: write zeros
     const u64 n = (u64)n_cls[0] + n_cls[1];
 
+    // block sizes in closed form (K, ..., K, K + remainder per class); every block's thread
+    // then sums the code bits of the blocks before it
     for (int b = tid; b < B2; b += BLOCK) {
         size_t mi = (size_t)r * (size_t)B2 + (size_t)b;
         int q = a.mv.q[mi] & 0x7F;
@@ -52,39 +57,59 @@ __global__ __launch_bounds__(BLOCK) void dec_kernel(DecArgs a)
         qv[b] = q;
         vminf[b] = vmin;
         stepf[b] = (vmax - vmin) / L;
+        const int s = b >= M ? 1 : 0, m = b - s * M, Ms = s ? a.Mn : M;
+        const u32 K = n_cls[s] / (u32)Ms;
+        const u32 cnt = (m < Ms - 1) ? K : n_cls[s] - K * (u32)(Ms - 1);
+        istart[b] = (s ? n_cls[0] : 0u) + (u32)m * K;
+        cbits[b] = (u64)cnt * (u64)q;
     }
-    __syncthreads();
-    if (tid == 0) {
-        u32 ia = 0;
-        u64 ca = n * (u64)w;
-        for (int s = 0; s < 2; ++s) {
-            const int Ms = s ? a.Mn : M;
-            u32 K = n_cls[s] / (u32)Ms;
-            for (int m = 0; m < Ms; ++m) {
-                int b = s * M + m;
-                u32 cnt = (m < Ms - 1) ? K : n_cls[s] - K * (u32)(Ms - 1);
-                istart[b] = ia; cstart[b] = ca;
-                ia += cnt; ca += (u64)cnt * (u64)qv[b];
-            }
-        }
-        istart[B2] = ia; cstart[B2] = ca;
-    }
+    if (tid == 0) istart[B2] = (u32)n;
     for (int i = tid; i < len; i += BLOCK) tile[i] = 0;
     __syncthreads();
+    for (int b = tid; b <= B2; b += BLOCK) {
+        u64 ca = n * (u64)w;
+        for (int i = 0; i < b; ++i) ca += cbits[i];
+        cstart[b] = ca;
+    }
+    __syncthreads();
 
-    // entries of each block that land in [c0, c1): indices ascend inside a block
-    for (int b = tid; b < B2; b += BLOCK) {
-        u32 first = istart[b], cnt = istart[b + 1] - first;
-        u32 lo = 0, hi = cnt;
-        if (a.chunks_per_row > 1) {
-            u32 l = 0, h = cnt;                    // first j with idx >= c0
-            while (l < h) { u32 m = (l + h) >> 1; if ((int64_t)read_bits(rw, (u64)(first + m) * w, w) < c0) l = m + 1; else h = m; }
-            lo = l; h = cnt;                       // first j with idx >= c1
-            while (l < h) { u32 m = (l + h) >> 1; if ((int64_t)read_bits(rw, (u64)(first + m) * w, w) < c1) l = m + 1; else h = m; }
-            hi = l;
+    // Entries of each block that land in [c0, c1): indices ascend inside a block, so both ends
+    // are lower bounds.  Every probe is a dependent global load: G lanes share one search and
+    // probe G points of the interval at once (G + 1 parts per step instead of two).
+    if (a.chunks_per_row > 1) {
+        int G = BLOCK / (2 * B2);                  // lanes per (block, end); a power of two that divides the wavefront
+        G = G >= 16 ? 16 : G >= 8 ? 8 : G >= 4 ? 4 : G >= 2 ? 2 : 1;
+        const u32 lane = lane_id();
+        const u32 gl = lane & (u32)(G - 1), gbase = lane - gl;
+        const u64 gmask = (G == 64 ? ~0ull : ((1ull << G) - 1ull)) << gbase;
+        for (int unit0 = 0; unit0 < 2 * B2; unit0 += BLOCK / G) {
+            const int unit = unit0 + tid / G;
+            const bool on = unit < 2 * B2;
+            const int b = on ? unit >> 1 : 0;
+            const int64_t target = (unit & 1) ? c1 : c0;
+            const u32 first = istart[b], cnt = istart[b + 1] - first;
+            u32 l = 0, h = on ? cnt : 0;           // first j with idx >= target
+            while (__any(l < h)) {
+                // probe i < G sits at l + floor(span * (i + 1) / (G + 1)): ascending, all below h
+                const u32 span = h - l, Gp = (u32)G + 1u;
+                const u32 qd = span / Gp, rm = span - qd * Gp;
+                auto point = [&](u32 m) -> u32 { return l + qd * m + udiv16(rm * m, Gp); };   // l + floor(span * m / Gp)
+                bool below = false;
+                if (l < h) below = (int64_t)read_bits(rw, (u64)(first + point(gl + 1u)) * w, w) < target;
+                const u64 bal = __ballot(below) & gmask;
+                if (l < h) {
+                    const u32 t = (u32)__popcll(bal);          // probes below the target (a prefix of them)
+                    const u32 nl = t ? point(t) + 1u : l;      // one past probe t - 1
+                    const u32 nh = t < (u32)G ? point(t + 1u) : h;   // probe t
+                    l = nl; h = nh;
+                }
+            }
+            if (on && gl == 0) { if (unit & 1) s_hi[b] = l; else act_lo[b] = l; }
         }
-        act_lo[b] = lo;
-        pre[b + 1] = hi - lo;
+        __syncthreads();
+        for (int b = tid; b < B2; b += BLOCK) pre[b + 1] = s_hi[b] - act_lo[b];
+    } else {
+        for (int b = tid; b < B2; b += BLOCK) { act_lo[b] = 0; pre[b + 1] = istart[b + 1] - istart[b]; }
     }
     __syncthreads();
     if (tid == 0) {
@@ -95,20 +120,34 @@ __global__ __launch_bounds__(BLOCK) void dec_kernel(DecArgs a)
     __syncthreads();
 
     const u32 total = pre[B2];
-    for (u32 t = tid; t < total; t += BLOCK) {
-        int lo = 0, hi = B2 - 1;                   // block b with pre[b] <= t < pre[b+1]
-        while (lo < hi) { int mid = (lo + hi) >> 1; if (pre[mid + 1] <= t) lo = mid + 1; else hi = mid; }
-        const int b = lo;
-        const u32 j = act_lo[b] + (t - pre[b]);
-        const int q = qv[b];
-        const u32 idx = read_bits(rw, (u64)(istart[b] + j) * w, w);
-        const u32 c = read_bits(rw, cstart[b] + (u64)j * (u64)q, q);
-        float val = __fadd_rn(vminf[b], __fmul_rn((float)c, stepf[b]));   // two roundings, never fused
-        if (b >= M) val = -val;
-        const int64_t rel = (int64_t)idx - c0;
-        if (rel >= 0 && rel < len) {
-            if (DT == 0) tile[rel] = (raw_t)__float_as_uint(val);
-            else tile[rel] = (raw_t)f32_to_bf16_rne(val);
+    for (u32 t0 = tid; t0 < total; t0 += 4 * BLOCK) {      // four entries per thread with all their loads in flight
+        int bb[4];
+        u32 idx4[4], c4[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const u32 t = t0 + (u32)u * BLOCK;
+            bb[u] = -1; idx4[u] = 0; c4[u] = 0;
+            if (t < total) {
+                int lo = 0, hi = B2 - 1;               // block b with pre[b] <= t < pre[b+1]
+                while (lo < hi) { int mid = (lo + hi) >> 1; if (pre[mid + 1] <= t) lo = mid + 1; else hi = mid; }
+                const int b = lo;
+                const u32 j = act_lo[b] + (t - pre[b]);
+                bb[u] = b;
+                idx4[u] = read_bits(rw, (u64)(istart[b] + j) * w, w);
+                c4[u] = read_bits(rw, cstart[b] + (u64)j * (u64)qv[b], qv[b]);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (bb[u] < 0) continue;
+            const int b = bb[u];
+            float val = __fadd_rn(vminf[b], __fmul_rn((float)c4[u], stepf[b]));   // two roundings, never fused
+            if (b >= M) val = -val;
+            const int64_t rel = (int64_t)idx4[u] - c0;
+            if (rel >= 0 && rel < len) {
+                if (DT == 0) tile[rel] = (raw_t)__float_as_uint(val);
+                else tile[rel] = (raw_t)f32_to_bf16_rne(val);
+            }
         }
     }
     __syncthreads();
