@@ -14,7 +14,10 @@
 //   blockcount / scatter   per 2048 list entries: block id, per-block counts, block min/max;
 //             then a stable split by block id (ascending index inside a block)
 //   abq / choose / pack    integer ABQ sums (Sec. 3.2.1) with 64-bit atomics, per-block
-//             bitwidth, bit offsets, and the row's stream image 1024 words per workgroup
+//             bitwidth, bit offsets, and the row's stream image, one window of words per workgroup
+//
+// Every stage is bound by the latency of its loads, not by their volume: a thread issues all
+// its loads before it uses the first, and nothing is a chain of dependent global loads.
 //
 // comp = key << w | (2^w - 1 - index): larger comp = larger magnitude, then lower index.
 // Rows that do not fit the lists (heavy ties, more zeros than dropped elements) are
@@ -630,16 +633,19 @@ __global__ __launch_bounds__(256) void lr_abq_kernel(LargeArgs a)
     __shared__ u64 sums[kMaxB2][kMaxQ + 1];
     const int tid = threadIdx.x, pc = blockIdx.x;
     const int64_t r = blockIdx.y;
+    // the values first: their loads need nothing but the launch geometry (positions beyond the
+    // row's count hold leftovers and are never used) and are the longest wait of the kernel
+    const u32 p0 = (u32)pc * kPCH;
+    const u32* __restrict__ bo_val = a.bo_val + (size_t)r * (size_t)a.k;
+    u32 vb[NJ];
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) { const u32 p = p0 + (u32)j * 256 + (u32)tid; vb[j] = (int64_t)p < a.k ? bo_val[p] : 0u; }
     if (a.fallback[r]) return;
     const int B2 = a.M + a.Mn, nq = NQ ? NQ : a.nq;
     const u32* st = a.rowst + (size_t)r * 16;
     const u32 n = st[3] + st[4];
-    const u32 p0 = (u32)pc * kPCH, p1 = p0 + kPCH < n ? p0 + kPCH : n;
+    const u32 p1 = p0 + kPCH < n ? p0 + kPCH : n;
     if (p0 >= n) return;
-    const u32* __restrict__ bo_val = a.bo_val + (size_t)r * (size_t)a.k;
-    u32 vb[NJ];
-#pragma unroll
-    for (int j = 0; j < NJ; ++j) { const u32 p = p0 + (u32)j * 256 + (u32)tid; vb[j] = p < p1 ? bo_val[p] : 0u; }   // all loads in flight at once
     for (int b = tid; b <= B2; b += 256) bs[b] = a.blk_start[(size_t)r * (B2 + 1) + b];
     __syncthreads();
     for (int b = tid; b < B2; b += 256) {
@@ -853,28 +859,33 @@ __global__ __launch_bounds__(128) void lr_choose_kernel(LargeArgs a)
         a.mv.n_neg[r] = st[4];
     }
     __syncthreads();
-    // for every window of the pack stage: the block-ordered entries whose code field meets it
+    // for every window of the pack stage: the block-ordered entries whose code field meets it.
+    // Code fields lie at or after word wb, i.e. in the short windows only: every block's thread
+    // walks the few windows its code section meets.
     {
-        const u64 idx_bits = (u64)n * (u64)a.w;
-        for (int wi = b; wi < a.nwin; wi += 128) {
-            u64 c0, cw;
-            lr_pack_window(a, wi, idx_bits >> 5, s_words, &c0, &cw);
-            const u64 lo = c0 << 5, hi = (c0 + cw) << 5;
-            u32 e0 = n, e1 = 0;
-            if (lo < hi) {
-                for (int i = 0; i < B2; ++i) {
-                    const u32 cnt = bs_s[i + 1] - bs_s[i];
-                    const u64 cs = idx_bits + co_s[i], ce = idx_bits + co_s[i + 1];
-                    if (!cnt || ce <= lo || cs >= hi) continue;
-                    const u32 q = q_s[i];
+        const u64 idx_bits = (u64)n * (u64)a.w, wb = idx_bits >> 5;
+        u32* __restrict__ wr = a.win_range + (size_t)r * a.nwin * 2;
+        for (int wi = b; wi < a.nwin; wi += 128) { wr[2 * wi] = n; wr[2 * wi + 1] = 0; }
+        __syncthreads();
+        const int csh = 31 - __clz(a.pack_words_code);          // pack_words_code is a power of two
+        const int tpb = 128 / B2 > 0 ? 128 / B2 : 1;           // threads per block (B2 <= 128)
+        const int bb = b / tpb, sub = b - bb * tpb;
+        if (bb < B2) {
+            const u32 cnt = bs_s[bb + 1] - bs_s[bb];
+            const u64 cs = idx_bits + co_s[bb], ce = idx_bits + co_s[bb + 1];
+            if (cnt && ce > cs) {
+                const u32 q = q_s[bb];
+                const int w0 = a.nwin_idx + (int)(((cs >> 5) - wb) >> csh), w1 = a.nwin_idx + (int)((((ce - 1) >> 5) - wb) >> csh);
+                for (int wi = w0 + sub; wi <= w1 && wi < a.nwin; wi += tpb) {
+                    u64 c0, cw;
+                    lr_pack_window(a, wi, wb, s_words, &c0, &cw);
+                    const u64 lo = c0 << 5, hi = (c0 + cw) << 5;
+                    if (cw == 0 || ce <= lo || cs >= hi) continue;
                     const u32 dlo = (u32)((lo > cs ? lo : cs) - cs), dhi = (u32)((hi < ce ? hi : ce) - cs);   // < 2^31: one block's bits
-                    const u32 f0 = bs_s[i] + dlo / q, f1 = bs_s[i] + (dhi + q - 1) / q;
-                    e0 = f0 < e0 ? f0 : e0;
-                    e1 = f1 > e1 ? f1 : e1;
+                    atomicMin(&wr[2 * wi], bs_s[bb] + dlo / q);
+                    atomicMax(&wr[2 * wi + 1], bs_s[bb] + (dhi + q - 1) / q);
                 }
             }
-            a.win_range[((size_t)r * a.nwin + wi) * 2 + 0] = e0;
-            a.win_range[((size_t)r * a.nwin + wi) * 2 + 1] = e1;
         }
     }
 }
