@@ -181,8 +181,8 @@ int slicer_bound(slicer_dtype dt, int64_t rows, int64_t row_len, double keep_rat
 /*
  * Which kernel family slicer_encode uses for a shape (for benchmarks and profiles, which
  * name the dominant kernel): 0 = generic (one workgroup per row, any shape), 1 = row-resident
- * (one wavefront per row, rows up to 8192 bf16 / 2048 fp32 elements), 2 = long-row stages
- * (rows of 32768 elements and more).  Assumes a 16-byte aligned x.  Negative: error code.
+ * (one wavefront per row, rows up to 8192 bf16 / 4096 fp32 elements), 2 = long-row stages
+ * (rows of more than 4096 elements that the row-resident kernel does not take).  Assumes a 16-byte aligned x.  Negative: error code.
  */
 int slicer_encode_path(slicer_dtype dt, int64_t rows, int64_t row_len, double keep_ratio,
                        int n_blocks, uint32_t bit_set);

@@ -97,7 +97,7 @@ Plan make_plan(int dt, int64_t rows, int64_t row_len, double keep_ratio, int n_b
         const int64_t capL = (p.k + std::max<int64_t>(4096, row_len / 16) + 7) & ~(int64_t)7;   // whole 16-byte groups of 2-byte entries
         int nq_l = 0;
         for (int q = 1; q <= 16; ++q) nq_l += (bit_set >> q) & 1u;
-        if (row_len >= 32768 && row_len % epc_l == 0 && C <= 1024 && rows <= 65535 && capL < ((int64_t)1 << 27)) {
+        if (row_len > 4096 && row_len % epc_l == 0 && C <= 1024 && rows <= 65535 && capL < ((int64_t)1 << 27)) {
             const size_t R = (size_t)rows, B2 = (size_t)B2_all;
             p.large_C = (int)C; p.large_capL = (u32)capL; p.large_LC = (int)((capL + kLCE - 1) / kLCE);
             p.lo_ch_cum = o;    o = align256(o + 4 * R * (size_t)C * kLBins);
@@ -125,7 +125,7 @@ Plan make_plan(int dt, int64_t rows, int64_t row_len, double keep_ratio, int n_b
     // block and a list capacity below 2048 entries (11-bit rank fields).
     p.small_epl = 0; p.small_cap = 0; p.small_region0 = 0; p.small_lds_bytes = 0; p.small_maxs = 0;
     const int epc = dt == SLICER_F32 ? 4 : 8;
-    const int64_t max_n = dt == SLICER_F32 ? 2048 : 8192;
+    const int64_t max_n = dt == SLICER_F32 ? 4096 : 8192;
     int nq = 0;
     for (int q = 1; q <= 16; ++q) nq += (bit_set >> q) & 1u;
     if (row_len % epc == 0 && row_len <= max_n && B2_all <= kWave) {
@@ -173,7 +173,8 @@ int launch_small(const SmallArgs& sa, const Plan& p, hipStream_t st)
     if (p.small_epl <= E0) launch_small_epl<DT, E0>(sa, lds, p.small_maxs, st);
     else if (p.small_epl == E0 * 2) launch_small_epl<DT, E0 * 2>(sa, lds, p.small_maxs, st);
     else if (p.small_epl == E0 * 4) launch_small_epl<DT, E0 * 4>(sa, lds, p.small_maxs, st);
-    else launch_small_epl<DT, E0 * 8>(sa, lds, p.small_maxs, st);
+    else if (p.small_epl == E0 * 8 || DT != 0) launch_small_epl<DT, E0 * 8>(sa, lds, p.small_maxs, st);
+    else launch_small_epl<DT, DT == 0 ? E0 * 16 : E0 * 8>(sa, lds, p.small_maxs, st);   // fp32 rows of 4096
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? SLICER_OK : hip_fail(e);
 }

@@ -210,6 +210,17 @@ __device__ inline u32 wave_max_dpp(u32 v)
     return bcast(r, kWave - 1);
 }
 
+// Two unsigned 16-bit lanes in one 32-bit register (packed 16-bit integer instructions): bf16
+// magnitude keys are handled two at a time.
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+__device__ inline u16x2 as_u16x2(u32 v) { return __builtin_bit_cast(u16x2, v); }
+__device__ inline u32 from_u16x2(u16x2 v) { return __builtin_bit_cast(u32, v); }
+__device__ inline u32 pk_max_u16(u32 a, u32 b) { return from_u16x2(__builtin_elementwise_max(as_u16x2(a), as_u16x2(b))); }
+__device__ inline u32 pk_min_u16(u32 a, u32 b) { return from_u16x2(__builtin_elementwise_min(as_u16x2(a), as_u16x2(b))); }
+__device__ inline u32 pk_sub_sat_u16(u32 a, u32 b) { return from_u16x2(__builtin_elementwise_sub_sat(as_u16x2(a), as_u16x2(b))); }
+__device__ inline u32 pk_shl_u16(u32 a, int n) { return from_u16x2(as_u16x2(a) << (unsigned short)n); }
+__device__ inline u32 pk_shr_u16(u32 a, int n) { return from_u16x2(as_u16x2(a) >> (unsigned short)n); }
+
 // x / d for x < 2^16 and 1 <= d < 2^16.  (x + 0.5) / d lies at least 0.5 / d away from every
 // integer, far more than the error of the reciprocal and the product (a few 2^-24 of the
 // quotient, and quotient * d < 2^16), so the truncation needs no repair.

@@ -164,7 +164,6 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
     constexpr int QN = NQ ? NQ : kMaxQ;
     constexpr int EPC = DT == 0 ? 4 : 8;            // elements per 16-byte chunk
     constexpr int NCH = EPL / EPC;                  // chunks per lane
-    constexpr int KS = E::kKeyBits - kCoarseBits;   // coarse digit = key >> KS
     extern __shared__ u32 smem[];
 
     const u32 lane = lane_id();
@@ -214,35 +213,71 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
     }
     auto word_of = [&](int c, int d) -> u32 { return d == 0 ? v[c].x : d == 1 ? v[c].y : d == 2 ? v[c].z : v[c].w; };
 
+    // Largest magnitude key of the row: the histogram window hangs from it.
+    u32 kmax;
     {
-        uint4* h4 = (uint4*)smem;
+        u32 mx = 0;
 #pragma unroll
-        for (int i = 0; i < kCoarseBins / 4 / kWave; ++i) h4[i * kWave + lane] = make_uint4(0, 0, 0, 0);
-    }
-    wave_sync();
-#pragma unroll
-    for (int c = 0; c < NCH; ++c) {
-        if ((c * kWave + (int)lane) * EPC < N) {
+        for (int c = 0; c < NCH; ++c) {
 #pragma unroll
             for (int d = 0; d < 4; ++d) {
                 const u32 wd = word_of(c, d);
-                if (DT == 0) {
-                    lds_inc(((wd & 0x7FFFFFFFu) >> KS) << 2, 1u);
-                } else {
-                    lds_inc((wd >> (KS - 2)) & (u32)(4 * kCoarseBins - 4), 1u);
-                    lds_inc((wd >> (16 + KS - 2)) & (u32)(4 * kCoarseBins - 4), 1u);
+                if (DT == 0) mx = max(mx, wd & 0x7FFFFFFFu);
+                else mx = pk_max_u16(mx, wd & 0x7FFF7FFFu);
+            }
+        }
+        if (DT == 1) mx = max(mx & 0xFFFFu, mx >> 16);
+        kmax = wave_max_dpp(mx);
+    }
+
+    // Coarse histogram over a window of 2048 bins that hangs from `wtop`: bin = (wtop - key) >> S,
+    // bin 0 on top.  First pass: S = 0 (bf16: one key per bin) or 16 (fp32: the same 128 bins per
+    // octave), i.e. 16 octaves below the largest key, everything further down in the last bin.
+    // Values of one row crowd into a few octaves, so bins this fine keep the lanes of an LDS
+    // atomic on different addresses, and the bin of rank k-1 holds little beyond the kept set.
+    // If rank k-1 lies below the window, a second pass with 16 times wider bins hangs from the
+    // window's lower end and reaches key 0.
+    constexpr int S1 = DT == 0 ? 16 : 0;
+    u32 wtop = kmax, above = 0;                     // above = number of keys > wtop
+    int S = S1;
+    u32 B1 = 0, c_gt = 0, cnt1 = 0;
+    bool found = false;
+    auto hist_pass = [&](auto shift) {
+        constexpr int SH = decltype(shift)::value;
+        {
+            uint4* h4 = (uint4*)smem;
+#pragma unroll
+            for (int i = 0; i < kCoarseBins / 4 / kWave; ++i) h4[i * kWave + lane] = make_uint4(0, 0, 0, 0);
+        }
+        wave_sync();
+        const u32 wt2 = wtop * 0x10001u;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            if ((c * kWave + (int)lane) * EPC < N) {
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    const u32 wd = word_of(c, d);
+                    if (DT == 0) {
+                        const u32 key = wd & 0x7FFFFFFFu;
+                        const u32 df = wtop > key ? wtop - key : 0u;
+                        lds_inc(min((df >> (SH - 2)) & ~3u, (u32)(4 * kCoarseBins - 4)), 1u);
+                    } else {
+                        u32 b = pk_sub_sat_u16(wt2, wd & 0x7FFF7FFFu);
+                        if (SH) b = pk_shr_u16(b, SH);
+                        b = pk_shl_u16(pk_min_u16(b, (u32)(kCoarseBins - 1) * 0x10001u), 2);
+                        lds_inc(b & 0xFFFFu, 1u);
+                        lds_inc(b >> 16, 1u);
+                    }
                 }
             }
         }
-    }
-    wave_sync();
-
-    // Scan from the top in two levels: every lane sums 32 bins; the lane that holds rank
-    // k-1 and the topmost non-empty lane are then opened bin by bin, 32 lanes each.
-    u32 B1 = 0, c_gt = 0, cnt1 = 0, topbin = 0;
-    {
+        wave_sync();
+        if (above && lane == 0) smem[0] -= above;   // keys above the window were counted in bin 0
+        wave_sync();
+        // Scan from the top in two levels: every lane sums 32 bins, the lane that holds the rank
+        // is then opened bin by bin.
         constexpr int BPL = kCoarseBins / kWave;       // 32
-        const uint4* h4 = (const uint4*)(smem + kCoarseBins - ((int)lane + 1) * BPL);
+        const uint4* h4 = (const uint4*)(smem + (int)lane * BPL);
         u32 local = 0;
 #pragma unroll
         for (int j = 0; j < BPL / 4; ++j) {
@@ -250,31 +285,36 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
             local += (t.x + t.y) + (t.z + t.w);
         }
         const u32 incl = wave_scan_dpp(local), excl = incl - local;
-        const u32 rem = k > 0 ? (u32)(k - 1) : 0u;
+        const u32 rem = (k > 0 ? (u32)(k - 1) : 0u) - above;
         const u64 m_src = __ballot(local > 0 && excl <= rem && rem < incl);
-        const u64 m_top = __ballot(local > 0);
         const int src = m_src ? (int)__builtin_ctzll(m_src) : 0;
-        const int top = m_top ? (int)__builtin_ctzll(m_top) : 0;
         const u32 ex_src = bcast(excl, src);
-        const int grp = lane < 32u ? src : top;
-        const u32 c2 = smem[kCoarseBins - grp * BPL - 1 - (int)(lane & 31u)];
+        const u32 c2 = lane < (u32)BPL ? smem[src * BPL + (int)lane] : 0u;
         const u32 inc2 = wave_scan_dpp(c2);            // lanes 0..31: running count inside lane `src`
-        const u64 m_b1 = __ballot(lane < 32u && ex_src + inc2 > rem);
-        const u64 m_tb = __ballot(lane >= 32u && c2 > 0u);
-        if (m_src && m_b1) {
+        const u64 m_b1 = __ballot(lane < (u32)BPL && ex_src + inc2 > rem);
+        found = m_src && m_b1;
+        if (found) {
             const int j1 = (int)__builtin_ctzll(m_b1);
-            B1 = (u32)(kCoarseBins - src * BPL - 1 - j1);
+            B1 = (u32)(src * BPL + j1);
             cnt1 = bcast(c2, j1);
             c_gt = ex_src + bcast(inc2, j1) - cnt1;
         }
-        if (m_tb) topbin = (u32)(kCoarseBins - top * BPL - 1 - ((int)__builtin_ctzll(m_tb) - 32));
+        wave_sync();
+    };
+    hist_pass(std::integral_constant<int, S1>());
+    if (found && B1 == (u32)(kCoarseBins - 1) && (wtop >> S1) > (u32)(kCoarseBins - 1)) {
+        above = c_gt;
+        wtop -= (u32)(kCoarseBins - 1) << S1;
+        S = S1 + 4;
+        hist_pass(std::integral_constant<int, S1 + 4>());
     }
-    wave_sync();
+    c_gt += above;
 
-    // the list takes every non-zero key from bin B1 up (bin 0 also counts the zeros, which
-    // never enter the list: its length is known after the counting pass below)
-    const u32 t_lo = (B1 << KS) > 1u ? (B1 << KS) : 1u;          // smallest non-zero key of bin B1
-    if (k > 0 && B1 > 0u && (int)(c_gt + cnt1) > cap) {
+    // the list takes every non-zero key from bin B1 up (a bin that reaches key 0 also counts the
+    // zeros, which never enter the list: its length is known after the counting pass below)
+    const long long lowk = (long long)wtop - ((long long)(B1 + 1u) << S) + 1;
+    const u32 t_lo = lowk > 1 ? (u32)lowk : 1u;                  // smallest non-zero key of bin B1
+    if (k > 0 && lowk >= 1 && (int)(c_gt + cnt1) > cap) {
         if (lane == 0) a.fallback[r] = 1u;
         return;
     }
@@ -382,8 +422,7 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
     // 1024 bins, linear in (key - t_lo) >> sh; sh from the top of the highest occupied coarse
     // bin.  fp32 keeps the in-bin key bits, the inverted index and the class in one word of S.
     const int nslots = (int)((nL + kWave - 1) / kWave);
-    const u32 kmax_ub = ((topbin + 1u) << KS) - 1u;
-    const u32 range = kmax_ub - t_lo;
+    const u32 range = kmax > t_lo ? kmax - t_lo : 0u;
     const int sh = range < (u32)kFineBins ? 0 : (32 - __clz((int)range)) - 10;
     if (DT == 0 && sh + w + 1 > 32) {
         if (lane == 0) a.fallback[r] = 1u;

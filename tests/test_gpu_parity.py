@@ -69,7 +69,7 @@ def test_workload_parity(oracle, name):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("N", [1, 2, 63, 64, 65, 257, 1000, 2048, 4097, 8192, 16384, 16385, 32768, 40000])
+@pytest.mark.parametrize("N", [1, 2, 63, 64, 65, 257, 1000, 2048, 4096, 4097, 4104, 6144, 8192, 12288, 16384, 16385, 32768, 40000])
 def test_adversarial_rows(oracle, dtype, N):
     x = synth.adversarial_rows(dtype, N, seed=N)
     for keep, M, bits, budget in ((0.0, 1, B28, 1e-3), (0.3, 2, B28, 1e-3), (1.0, 5, B28, 0.0),
@@ -107,7 +107,7 @@ def _mixed_rows(rng, rows, N, dtype):
     return synth.f32_to_bf16_bits(x) if dtype == "bf16" else x
 
 
-@pytest.mark.parametrize("dtype,N", [("bf16", 256), ("bf16", 4096), ("bf16", 8192), ("f32", 768), ("f32", 2048)])
+@pytest.mark.parametrize("dtype,N", [("bf16", 256), ("bf16", 4096), ("bf16", 8192), ("f32", 768), ("f32", 2048), ("f32", 4096)])
 def test_row_resident_variants(oracle, dtype, N):
     """Every variant of the one-wave-per-row encoder (list in registers or LDS, short or long
     bitwidth ladders, up to 64 blocks) and both bit-field sources of the short-row decoder."""
