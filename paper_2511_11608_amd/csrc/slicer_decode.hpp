@@ -305,13 +305,12 @@ __global__ __launch_bounds__(256) void dec_small_kernel(DecArgs a)
 
     uint4* __restrict__ out = (uint4*)((char*)a.y + (size_t)r * (size_t)row_bytes);
     // the output is written once and not read back by this library: streaming (non-temporal) stores
+    typedef u32 u32x4 __attribute__((ext_vector_type(4)));
     for (int i = lane; i < row_bytes / 16; i += kWave) {
         const uint4 t = tile4[i];
-        u32* o = (u32*)(out + i);
-        __builtin_nontemporal_store(t.x, o);
-        __builtin_nontemporal_store(t.y, o + 1);
-        __builtin_nontemporal_store(t.z, o + 2);
-        __builtin_nontemporal_store(t.w, o + 3);
+        u32x4 v4;
+        v4.x = t.x; v4.y = t.y; v4.z = t.z; v4.w = t.w;
+        __builtin_nontemporal_store(v4, (u32x4*)(out + i));       // one 16-byte store
     }
 }
 
