@@ -6,8 +6,9 @@
 // the tie rule of the top-K filter and of the block ranks), and the sign class as the top
 // bit, positive class on top.  Comps are distinct, so a comp is a complete rank threshold.
 //
-//   1. load the row (16-byte coalesced loads); 11-bit histogram of the magnitude key's
-//      top bits in LDS; two-level scan from the top -> the bin B1 that holds rank k-1;
+//   1. load the row (16-byte coalesced loads); its largest magnitude key; a 2048-bin
+//      histogram in LDS over a window that hangs from that key (bf16: one key per bin);
+//      two-level scan from the top -> the bin B1 that holds rank k-1;
 //   2. ordered compaction of everything at or above B1 into a short list L
 //      (ascending index: the kept set plus the undecided bin);
 //   3. L is bucketed into 1024 fine bins, linear in the key from the list's lower
