@@ -228,7 +228,8 @@ int launch_decode(const void* stream, const void* meta, void* y, int dt, int64_t
     da.total_words = (const u64*)meta + 6;
     // the stream segment of a row at keep ratios up to about 0.2 (longer segments are read from global memory)
     da.stage_words = (int)std::min<int64_t>(1020, (row_len / 16 + 3) / 4 * 4);
-    const u64 grid = (u64)rows * (u64)da.chunks_per_row;
+    da.xcd_map = (rows >= 32 && da.chunks_per_row > 1) ? 1 : 0;
+    const u64 grid = (u64)(da.xcd_map ? xcd_grid(rows) : rows) * (u64)da.chunks_per_row;
     if (grid >= (1ull << 31)) return SLICER_EINVAL;
     const bool timed = g_ev_start && g_ev_stop;
     if (timed) SLICER_HIP(hipEventRecord(g_ev_start, st));

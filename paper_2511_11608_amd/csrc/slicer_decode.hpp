@@ -19,6 +19,7 @@ struct DecArgs {
     MetaView mv;
     const u64* total_words;   // header field
     int stage_words;          // short rows: words of LDS per wave for the row's stream segment
+    int xcd_map;              // long rows: all chunks of a row run on one XCD (grid = kXcds * ceil(R / kXcds) * chunks_per_row)
 };
 
 template <int DT, int BLOCK>
@@ -37,8 +38,20 @@ __global__ __launch_bounds__(BLOCK) void dec_kernel(DecArgs a)
     __shared__ u32 pre[kMaxB2 + 1];        // prefix of per-block counts landing in this chunk
 
     const int tid = threadIdx.x;
-    const int64_t r = blockIdx.x / a.chunks_per_row;
-    const int64_t c0 = (int64_t)(blockIdx.x % a.chunks_per_row) * kDecChunk;
+    // Workgroups are dealt to the XCDs round-robin and every XCD has its own L2.  The chunks of a
+    // row all search the row's index lists, so with enough rows to go round, row r is decoded on
+    // XCD r % 8 only and its stream segment is fetched into one L2 instead of eight.
+    int64_t r, ch;
+    if (a.xcd_map) {
+        const int64_t j = (int64_t)blockIdx.x / kXcds;
+        r = (j / a.chunks_per_row) * kXcds + (int64_t)blockIdx.x % kXcds;
+        ch = j % a.chunks_per_row;
+        if (r >= a.R) return;                       // the whole workgroup: no barrier is skipped
+    } else {
+        r = blockIdx.x / a.chunks_per_row;
+        ch = blockIdx.x % a.chunks_per_row;
+    }
+    const int64_t c0 = ch * kDecChunk;
     const int64_t c1 = c0 + kDecChunk < a.N ? c0 + kDecChunk : a.N;
     const int len = (int)(c1 - c0);
     const int M = a.M, B2 = a.M + a.Mn, w = a.w;
