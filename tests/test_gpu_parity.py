@@ -119,6 +119,24 @@ def test_row_resident_variants(oracle, dtype, N):
         check(oracle, x, dtype, keep, M, bits, budget)
 
 
+@pytest.mark.parametrize("dtype,N", [("bf16", 4096), ("f32", 768), ("f32", 4096), ("bf16", 8192)])
+def test_wide_dynamic_range_rows(oracle, dtype, N):
+    """Magnitudes spread evenly over many octaves: the row kernel's histogram window covers 16
+    octaves below the row's largest value, so these rows put rank k-1 inside the window, on its
+    last bin, and below it (second, coarser pass), with and without zeros under it."""
+    rng = np.random.default_rng(7 * N)
+    rows = 12
+    spans = np.array([4, 12, 15.9, 16.0, 16.1, 17, 24, 40, 60, 90, 120, 30], np.float32)[:, None]
+    mag = np.exp2(-spans * rng.random((rows, N)).astype(np.float32)) * np.float32(8.0)
+    x = (mag * rng.choice(np.array([-1.0, 1.0], np.float32), (rows, N))).astype(np.float32)
+    x[11, rng.random(N) < 0.5] = 0                      # zeros below a wide range
+    x[10, 0] = np.float32(3e38)                         # one huge value on top of 120 octaves
+    if dtype == "bf16":
+        x = synth.f32_to_bf16_bits(x)
+    for keep, M in ((0.05, 4), (0.3, 8), (0.5, 3), (0.9, 8), (1.0, 2)):
+        check(oracle, x, dtype, keep, M, B28, 1e-3)
+
+
 def check_ladder(oracle, x, dtype, keep, ladder):
     from tests.gpu_util import gpu_encode_ladder, gpu_decode
     s_ref, m_ref = oracle.encode_ladder(x, dtype, keep, ladder, n_threads=8)
