@@ -44,6 +44,12 @@ def lib() -> C.CDLL:
         L.slicer_ref_analyze_row.restype = C.c_int
         L.slicer_ref_analyze_row.argtypes = [C.c_void_p, C.c_int, C.c_int64, C.c_double, C.c_int, C.c_uint32,
                                              C.c_double] + [C.c_void_p] * 8
+        L.slicer_ref_encode_atkf.restype = C.c_int
+        L.slicer_ref_encode_atkf.argtypes = [C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_double, C.c_double, C.c_int,
+                                             C.c_int, C.c_uint32, C.c_double, C.c_void_p, C.c_void_p, C.c_int]
+        L.slicer_ref_analyze_row_atkf.restype = C.c_int
+        L.slicer_ref_analyze_row_atkf.argtypes = [C.c_void_p, C.c_int, C.c_int64, C.c_double, C.c_double, C.c_int,
+                                                  C.c_uint32, C.c_double] + [C.c_void_p] * 5
         _lib = L
     return _lib
 
@@ -99,6 +105,42 @@ def encode_pn(x: np.ndarray, dtype: str, keep_ratio: float, n_blocks: int, n_blo
         raise ValueError(f"slicer_ref_encode_pn: error {rc}")
     total = int(meta[48:56].view(np.uint64)[0])
     return stream[:total].copy(), meta
+
+
+def encode_atkf(x: np.ndarray, dtype: str, keep_ratio: float, lam: float, n_blocks: int, n_blocks_neg: int,
+                bit_set: int, budget: float, n_threads: int = 1):
+    """Asymmetric thresholds of Sec. 3.1 (lambda in [0, 1)).  Returns (stream, meta)."""
+    x = _check_x(x, dtype)
+    rows, row_len = x.shape
+    a, b = C.c_size_t(0), C.c_size_t(0)
+    rc = lib().slicer_ref_sizes_pn(_DT[dtype], rows, row_len, keep_ratio, n_blocks, n_blocks_neg, bit_set,
+                                   C.byref(a), C.byref(b))
+    if rc:
+        raise ValueError(f"slicer_ref_sizes_pn: error {rc}")
+    stream = np.zeros(max(a.value // 4, 1), np.uint32)
+    meta = np.zeros(b.value, np.uint8)
+    rc = lib().slicer_ref_encode_atkf(x.ctypes.data, _DT[dtype], rows, row_len, keep_ratio, lam, n_blocks,
+                                      n_blocks_neg, bit_set, budget, stream.ctypes.data, meta.ctypes.data, n_threads)
+    if rc:
+        raise ValueError(f"slicer_ref_encode_atkf: error {rc}")
+    total = int(meta[48:56].view(np.uint64)[0])
+    return stream[:total].copy(), meta
+
+
+def analyze_row_atkf(x_row: np.ndarray, dtype: str, keep_ratio: float, lam: float, n_blocks: int, bit_set: int,
+                     budget: float):
+    """Per-element view of one row under the asymmetric thresholds (block_of, code_of, vmin, vmax, qb)."""
+    x_row = np.ascontiguousarray(x_row)
+    N = x_row.shape[0]
+    M2 = 2 * n_blocks
+    out = dict(block_of=np.empty(N, np.int32), code_of=np.empty(N, np.uint32),
+               vmin=np.empty(M2, np.float32), vmax=np.empty(M2, np.float32), qb=np.empty(M2, np.uint8))
+    rc = lib().slicer_ref_analyze_row_atkf(x_row.ctypes.data, _DT[dtype], N, keep_ratio, lam, n_blocks, bit_set,
+                                           budget, *[out[k].ctypes.data for k in
+                                                     ("block_of", "code_of", "vmin", "vmax", "qb")])
+    if rc:
+        raise ValueError(f"slicer_ref_analyze_row_atkf: error {rc}")
+    return out
 
 
 def encode_ds(x: np.ndarray, dtype: str, keep_ratio: float, n_blocks: int, bit_set: int, delta: float,

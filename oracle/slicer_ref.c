@@ -53,6 +53,16 @@
  * would pass again is not looked at).  The sum is an integer; the test is
  * (double)sum <= delta * (double)n.  See slicer_ref_encode_ds.
  *
+ * Asymmetric thresholds (Sec. 3.1 with lambda in [0,1); slicer_ref_encode_atkf): with tau the
+ * k-th largest |x| of the row, tau+ = (1+lambda)*tau and tau- = (1-lambda)*tau (each one fp32
+ * operation on lambda rounded to fp32), the strictly retained set is
+ *       S = { x > tau+ }  union  { x < -tau- }.
+ * |S| < k: S is filled up to k elements from { i not in S : |x_i| <= tau }, largest magnitude
+ * first (the ties at tau, then the next lower magnitudes; equal magnitudes: lower index first).
+ * Positive values in (tau, tau+] are therefore never sent: that is what the shifted cut-off does.
+ * |S| >= k (the paper is silent; its claim of an exact count decides): the k largest magnitudes
+ * of S are kept (equal magnitudes: lower index first).  lambda = 0 gives item 1 above.
+ *
  * Payload bound (Sec. 3.3, "Predictive Bit/Time Model"): every kept slot at the largest
  * bitwidth, plus index and header bits; see slicer_ref_bound.
  *
@@ -319,12 +329,47 @@ static void quantise_block(const kv_t* el, uint32_t cnt, uint32_t bit_set, doubl
  * ds != 0: the DS guard with delta = beta instead of the relative-error budget */
 /* M, Mn: blocks of the positive and of the negative class (Sec. 3.3: M(+), M(-)); block
  * numbers are +0..+M-1 then -0..-Mn-1 */
+/* ATKF with asymmetric thresholds (Sec. 3.1): `all` holds the row in (magnitude desc, index asc)
+ * order; writes the retained elements to `sel` in the same order and returns their number (<= k). */
+static int64_t atkf_asymmetric(const void* x, int dt, const kv_t* all, int64_t N, int64_t k, float lambda, kv_t* sel)
+{
+    if (k <= 0) return 0;
+    const float tau = bits_to_float(all[k - 1].key);           /* k-th largest |x| */
+    const float one_plus = 1.0f + lambda, one_minus = 1.0f - lambda;
+    const float tau_pos = one_plus * tau;                        /* tau+ = (1 + lambda) tau */
+    const float tau_neg = one_minus * tau;                       /* |tau-| = (1 - lambda) tau */
+    uint8_t* strict = (uint8_t*)malloc((size_t)N);
+    if (!strict) return -1;
+    int64_t c = 0;
+    for (int64_t r = 0; r < N; ++r) {                           /* S_strict = { x > tau+ or x < tau- } */
+        const float a = bits_to_float(all[r].key);
+        const int neg = (int)(load_bits(x, dt, all[r].idx) >> 31);
+        strict[r] = neg ? (a > tau_neg) : (a > tau_pos);
+        c += strict[r];
+    }
+    int64_t n = 0;
+    if (c >= k) {                                               /* more than asked for: the k largest of S_strict */
+        for (int64_t r = 0; r < N && n < k; ++r)
+            if (strict[r]) sel[n++] = all[r];
+    } else {                                                    /* S_strict, filled from |x| <= tau downwards */
+        int64_t fill = k - c;
+        for (int64_t r = 0; r < N; ++r) {
+            if (strict[r]) sel[n++] = all[r];
+            else if (fill > 0 && all[r].key <= all[k - 1].key) { sel[n++] = all[r]; --fill; }
+        }
+    }
+    free(strict);
+    return n;
+}
+
+/* lambda < 0: plain top-K (the k largest magnitudes); lambda >= 0: asymmetric thresholds */
 static int analyze_row(const void* x, int dt, int64_t N, int64_t k, int M, int Mn, uint32_t bit_set,
-                       double beta, const uint8_t* ladder, int ds, row_result* out)
+                       double beta, const uint8_t* ladder, int ds, float lambda, row_result* out)
 {
     kv_t* all = (kv_t*)malloc(sizeof(kv_t) * (size_t)N);
     kv_t* cls = (kv_t*)malloc(sizeof(kv_t) * (size_t)(k > 0 ? k : 1));
-    if (!all || !cls) { free(all); free(cls); return -3; }
+    kv_t* sel = (kv_t*)malloc(sizeof(kv_t) * (size_t)(k > 0 ? k : 1));
+    if (!all || !cls || !sel) { free(all); free(cls); free(sel); return -3; }
 
     /* ATKF: order all elements by magnitude (bit pattern with the sign cleared
      * orders finite values by |x|), ties by lower index; keep the first k. */
@@ -335,6 +380,13 @@ static int analyze_row(const void* x, int dt, int64_t N, int64_t k, int M, int M
         out->code_of[i] = 0;
     }
     qsort(all, (size_t)N, sizeof(kv_t), cmp_mag_desc_idx_asc);
+    int64_t n_sel = k;
+    if (lambda >= 0.0f) {
+        n_sel = atkf_asymmetric(x, dt, all, N, k, lambda, sel);
+        if (n_sel < 0) { free(all); free(cls); free(sel); return -3; }
+    } else {
+        for (int64_t r = 0; r < k; ++r) sel[r] = all[r];
+    }
 
     for (int b = 0; b < M + Mn; ++b) {
         out->vmin[b] = 0.0f; out->vmax[b] = 0.0f;
@@ -348,10 +400,10 @@ static int analyze_row(const void* x, int dt, int64_t N, int64_t k, int M, int M
     for (int s = 0; s < 2; ++s) { /* s = 0: positive class, s = 1: negative class */
         /* kept non-zeros of this sign, still in (magnitude desc, index asc) order */
         uint32_t n = 0;
-        for (int64_t r = 0; r < k; ++r) {
-            if (all[r].key == 0) continue;                       /* exact zero: not sent */
-            int neg = (int)(load_bits(x, dt, all[r].idx) >> 31);
-            if (neg == s) cls[n++] = all[r];
+        for (int64_t r = 0; r < n_sel; ++r) {
+            if (sel[r].key == 0) continue;                       /* exact zero: not sent */
+            int neg = (int)(load_bits(x, dt, sel[r].idx) >> 31);
+            if (neg == s) cls[n++] = sel[r];
         }
         if (s == 0) out->n_pos = n; else out->n_neg = n;
 
@@ -372,6 +424,7 @@ static int analyze_row(const void* x, int dt, int64_t N, int64_t k, int M, int M
     }
     free(all);
     free(cls);
+    free(sel);
     return 0;
 }
 
@@ -456,7 +509,7 @@ static void row_result_free(row_result* rr)
 /* ---- public: encode ---------------------------------------------------- */
 
 static int encode_common(const void* x, int dt, int64_t R, int64_t N, double keep, int M, int Mn,
-                         uint32_t bit_set, double beta, const uint8_t* ladder, int ds,
+                         uint32_t bit_set, double beta, const uint8_t* ladder, int ds, float lambda,
                          void* stream, void* meta, int n_threads)
 {
     int rc = check_args(dt, R, N, keep, M, bit_set);
@@ -488,7 +541,7 @@ static int encode_common(const void* x, int dt, int64_t R, int64_t N, double kee
         uint32_t* idxbuf = (uint32_t*)malloc(sizeof(uint32_t) * (size_t)(k > 0 ? k : 1));
         seg[r] = (uint32_t*)calloc((size_t)(cap_words > 0 ? cap_words : 1), 4);
         const void* xr = (const char*)x + (size_t)r * (size_t)N * esz;
-        if (analyze_row(xr, dt, N, k, M, Mn, bit_set, beta, ladder, ds, &rr) != 0) {
+        if (analyze_row(xr, dt, N, k, M, Mn, bit_set, beta, ladder, ds, lambda, &rr) != 0) {
             fail = 1;
         } else {
             seg_words[r] = pack_row(&rr, N, B2, w, seg[r], idxbuf);
@@ -534,13 +587,21 @@ static int encode_common(const void* x, int dt, int64_t R, int64_t N, double kee
 int slicer_ref_encode(const void* x, int dt, int64_t R, int64_t N, double keep, int M,
                       uint32_t bit_set, double beta, void* stream, void* meta, int n_threads)
 {
-    return encode_common(x, dt, R, N, keep, M, M, bit_set, beta, NULL, 0, stream, meta, n_threads);
+    return encode_common(x, dt, R, N, keep, M, M, bit_set, beta, NULL, 0, -1.0f, stream, meta, n_threads);
 }
 
 int slicer_ref_encode_pn(const void* x, int dt, int64_t R, int64_t N, double keep, int M, int Mn,
                          uint32_t bit_set, double beta, void* stream, void* meta, int n_threads)
 {
-    return encode_common(x, dt, R, N, keep, M, Mn, bit_set, beta, NULL, 0, stream, meta, n_threads);
+    return encode_common(x, dt, R, N, keep, M, Mn, bit_set, beta, NULL, 0, -1.0f, stream, meta, n_threads);
+}
+
+/* Sec. 3.1 with an asymmetry factor: lambda in [0, 1), rounded to fp32 once */
+int slicer_ref_encode_atkf(const void* x, int dt, int64_t R, int64_t N, double keep, double lambda, int M, int Mn,
+                           uint32_t bit_set, double beta, void* stream, void* meta, int n_threads)
+{
+    if (!(lambda >= 0.0 && lambda < 1.0)) return -1;
+    return encode_common(x, dt, R, N, keep, M, Mn, bit_set, beta, NULL, 0, (float)lambda, stream, meta, n_threads);
 }
 
 /* set of the ladder's bitwidths; 0 if an entry is outside 1..16 */
@@ -560,13 +621,13 @@ int slicer_ref_encode_ladder(const void* x, int dt, int64_t R, int64_t N, double
     if (!ladder || M < 1 || M > 64) return -1;
     uint32_t bs = ladder_bit_set(ladder, M);
     if (!bs) return -1;
-    return encode_common(x, dt, R, N, keep, M, M, bs, 0.0, ladder, 0, stream, meta, n_threads);
+    return encode_common(x, dt, R, N, keep, M, M, bs, 0.0, ladder, 0, -1.0f, stream, meta, n_threads);
 }
 
 int slicer_ref_encode_ds(const void* x, int dt, int64_t R, int64_t N, double keep, int M,
                          uint32_t bit_set, double delta, void* stream, void* meta, int n_threads)
 {
-    return encode_common(x, dt, R, N, keep, M, M, bit_set, delta, NULL, 1, stream, meta, n_threads);
+    return encode_common(x, dt, R, N, keep, M, M, bit_set, delta, NULL, 1, -1.0f, stream, meta, n_threads);
 }
 
 /* Sec. 3.3: value bits with every block at q_bit = max(bit_set), index bits, header bits.
@@ -649,17 +710,17 @@ int slicer_ref_decode(const void* stream, const void* meta, void* y, int n_threa
 
 /* ---- public: per-element view of one row -------------------------------- */
 
-int slicer_ref_analyze_row(const void* x_row, int dt, int64_t N, double keep, int M,
-                           uint32_t bit_set, double beta, int32_t* block_of, uint32_t* code_of,
-                           float* vmin, float* vmax, uint8_t* qb, uint64_t* s_int,
-                           uint64_t* e_int, int32_t* e_exp)
+static int analyze_row_public(const void* x_row, int dt, int64_t N, double keep, float lambda, int M,
+                              uint32_t bit_set, double beta, int32_t* block_of, uint32_t* code_of,
+                              float* vmin, float* vmax, uint8_t* qb, uint64_t* s_int,
+                              uint64_t* e_int, int32_t* e_exp)
 {
     int rc = check_args(dt, 1, N, keep, M, bit_set);
     if (rc) return rc;
     if (!x_row || !(beta >= 0.0)) return -1;
     row_result rr;
     row_result_alloc(&rr, N, 2 * M, 1);
-    rc = analyze_row(x_row, dt, N, keep_count(keep, N), M, M, bit_set, beta, NULL, 0, &rr);
+    rc = analyze_row(x_row, dt, N, keep_count(keep, N), M, M, bit_set, beta, NULL, 0, lambda, &rr);
     if (rc == 0) {
         if (block_of) memcpy(block_of, rr.block_of, sizeof(int32_t) * (size_t)N);
         if (code_of) memcpy(code_of, rr.code_of, sizeof(uint32_t) * (size_t)N);
@@ -672,4 +733,20 @@ int slicer_ref_analyze_row(const void* x_row, int dt, int64_t N, double keep, in
     }
     row_result_free(&rr);
     return rc;
+}
+
+int slicer_ref_analyze_row(const void* x_row, int dt, int64_t N, double keep, int M,
+                           uint32_t bit_set, double beta, int32_t* block_of, uint32_t* code_of,
+                           float* vmin, float* vmax, uint8_t* qb, uint64_t* s_int,
+                           uint64_t* e_int, int32_t* e_exp)
+{
+    return analyze_row_public(x_row, dt, N, keep, -1.0f, M, bit_set, beta, block_of, code_of, vmin, vmax, qb, s_int, e_int, e_exp);
+}
+
+int slicer_ref_analyze_row_atkf(const void* x_row, int dt, int64_t N, double keep, double lambda, int M,
+                                uint32_t bit_set, double beta, int32_t* block_of, uint32_t* code_of,
+                                float* vmin, float* vmax, uint8_t* qb)
+{
+    if (!(lambda >= 0.0 && lambda < 1.0)) return -1;
+    return analyze_row_public(x_row, dt, N, keep, (float)lambda, M, bit_set, beta, block_of, code_of, vmin, vmax, qb, NULL, NULL, NULL);
 }

@@ -66,6 +66,19 @@ int slicer_ref_encode_pn(const void* x, int dtype, int64_t rows, int64_t row_len
                          double keep_ratio, int n_blocks, int n_blocks_neg, uint32_t bit_set,
                          double distortion_budget, void* stream, void* meta, int n_threads);
 
+/* Asymmetric thresholds of Sec. 3.1: tau = k-th largest |x|, tau+ = (1 + lambda) tau,
+ * tau- = -(1 - lambda) tau; retained are x > tau+ and x < tau-, filled up to k from |x| <= tau
+ * downwards, or cut to the k largest when there are more (see the top of slicer_ref.c).
+ * lambda in [0, 1), used as an fp32 value; lambda = 0 equals slicer_ref_encode_pn. */
+int slicer_ref_encode_atkf(const void* x, int dtype, int64_t rows, int64_t row_len,
+                           double keep_ratio, double lambda, int n_blocks, int n_blocks_neg,
+                           uint32_t bit_set, double distortion_budget, void* stream, void* meta,
+                           int n_threads);
+/* per-element view of one row under the same rule (n_blocks for both classes) */
+int slicer_ref_analyze_row_atkf(const void* x_row, int dtype, int64_t row_len, double keep_ratio,
+                                double lambda, int n_blocks, uint32_t bit_set, double distortion_budget,
+                                int32_t* block_of, uint32_t* code_of, float* vmin, float* vmax, uint8_t* qb);
+
 /* Decode into dense y (same dtype and shape as the encoded tensor). */
 int slicer_ref_decode(const void* stream, const void* meta, void* y, int n_threads);
 

@@ -591,3 +591,99 @@ def test_pn_each_class_is_split_by_its_own_count(oracle, dtype, Mp, Mn):
     # the decoded tensor: positive values as in (Mp, Mp), negative values as in (Mn, Mn)
     y, yp, yn = (f32(oracle.decode(*t), dtype) for t in ((s, m), (sp, mp), (sn, mn)))
     assert np.array_equal(y, np.where(yp > 0, yp, 0) + np.where(yn < 0, yn, 0))
+
+
+# ----------------------------------------------------------------------------
+# asymmetric thresholds (Sec. 3.1 with lambda > 0)
+# ----------------------------------------------------------------------------
+
+def test_golden_atkf_lambda(oracle):
+    g = GOLD["atkf_lambda"]
+    x = np.array(g["x"], np.float32)
+    bs = bits_of(g["bits"])
+    a = oracle.analyze_row_atkf(x, "f32", g["keep_ratio"], g["lambda"], g["n_blocks"], bs, g["budget"])
+    assert np.nonzero(a["block_of"] >= 0)[0].tolist() == g["kept"]
+    assert a["block_of"].tolist() == g["block_of"]
+    a0 = oracle.analyze_row_atkf(x, "f32", g["keep_ratio"], 0.0, g["n_blocks"], bs, g["budget"])
+    assert np.nonzero(a0["block_of"] >= 0)[0].tolist() == g["kept_lambda0"]
+    t = g["trim"]
+    at = oracle.analyze_row_atkf(np.array(t["x"], np.float32), "f32", t["keep_ratio"], t["lambda"], 1, bs, 0.0)
+    assert np.nonzero(at["block_of"] >= 0)[0].tolist() == t["kept"]
+    # the stream of the whole call decodes to the kept values (ranges of singleton / two-point blocks are exact)
+    s, m = oracle.encode_atkf(x[None, :], "f32", g["keep_ratio"], g["lambda"], g["n_blocks"], g["n_blocks"], bs, 0.0)
+    y = oracle.decode(s, m)[0]
+    want = np.where(np.isin(np.arange(x.size), g["kept"]), x, 0).astype(np.float32)
+    assert y.tolist() == want.tolist()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_atkf_lambda_zero_is_plain_topk(oracle, dtype):
+    """lambda = 0: tau+ = tau- = tau, the strict set is |x| > tau and the fill takes the ties at tau by
+    lower index: byte for byte the plain top-K encode."""
+    wl = synth.vit_tokens(seed=5, rows=6) if dtype == "f32" else synth.llm_prefill(seed=5, rows=6)
+    for Mp, Mn in ((4, 4), (3, 7)):
+        s0, m0 = oracle.encode_pn(wl.x, wl.dtype, wl.keep_ratio, Mp, Mn, wl.bit_set, wl.budget)
+        s1, m1 = oracle.encode_atkf(wl.x, wl.dtype, wl.keep_ratio, 0.0, Mp, Mn, wl.bit_set, wl.budget)
+        assert np.array_equal(s0, s1) and np.array_equal(m0, m1)
+
+
+def _atkf_rows(dtype):
+    rng = np.random.default_rng(31)
+    rows = []
+    for N in (7, 64, 257, 1000):
+        rows.append(rng.standard_normal(N).astype(np.float32))
+        r = rng.standard_normal(N).astype(np.float32); r[rng.random(N) < 0.6] = 0; rows.append(r)
+        rows.append(-np.abs(rng.standard_normal(N)).astype(np.float32))                       # one sign only
+        rows.append(rng.choice(np.array([-2, -1, -0.5, 0.5, 1, 2, 0], np.float32), N))        # heavy ties
+        rows.append((rng.standard_normal(N) - 0.8).astype(np.float32))                        # mostly negative: |S| > k
+    return [synth.f32_to_bf16_bits(r) for r in rows] if dtype == "bf16" else rows
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("lam", [0.1, 0.5, 0.9])
+def test_atkf_lambda_properties(oracle, dtype, lam):
+    """What Sec. 3.1 fixes about the retained set, checked on the oracle's output: tau is the k-th
+    largest magnitude (numpy sort); everything beyond the shifted cut-offs is kept while it fits;
+    no positive in (tau, tau+] is kept; the fill is the largest of what is allowed; the count is exact."""
+    lam32 = np.float32(lam)
+    for row in _atkf_rows(dtype):
+        x = f32(row, dtype)
+        N = x.size
+        for keep in (0.05, 0.3, 0.6, 1.0):
+            k = int(np.floor(keep * N))
+            if k == 0:
+                continue
+            a = oracle.analyze_row_atkf(row, dtype, keep, lam, 2, B28, 1e-3)
+            kept = a["block_of"] >= 0
+            mag = np.abs(x)
+            tau = np.sort(mag)[::-1][k - 1]
+            tp, tn = (np.float32(1) + lam32) * tau, (np.float32(1) - lam32) * tau
+            strict = ((x > 0) & (mag > tp)) | ((x < 0) & (mag > tn))
+            c = int(strict.sum())
+            order = np.lexsort((np.arange(N), -mag.astype(np.float64)))           # (magnitude desc, index asc) ranks
+            rank = np.empty(N, np.int64); rank[order] = np.arange(N)
+            if c >= k:
+                assert kept.sum() == k and not (kept & ~strict).any()
+                assert rank[kept].max() < rank[strict & ~kept].min() if (strict & ~kept).any() else True
+            else:
+                assert (kept | ~strict).all()                                     # all of S is kept
+                allowed = ~strict & (mag <= tau)
+                fill = kept & ~strict
+                assert not (fill & ~allowed).any()                                # nothing from (tau, tau+]
+                want_fill = min(k - c, int(allowed.sum()))
+                sent_fill = int(fill.sum())
+                zeros_taken = want_fill - sent_fill                               # zeros that the fill reached are not sent
+                assert 0 <= zeros_taken <= int((allowed & (mag == 0)).sum())
+                if sent_fill:
+                    dropped = allowed & ~kept & (mag > 0)
+                    if dropped.any():
+                        assert rank[fill].max() < rank[dropped].min()
+                        assert zeros_taken == 0
+            assert not (kept & (x > 0) & (mag > tau) & (mag <= tp)).any()     # the shifted cut-off holds in both cases
+
+
+def test_atkf_rejects_bad_lambda(oracle):
+    x = np.ones((1, 8), np.float32)
+    for lam in (-0.1, 1.0, 1.5, float("nan")):
+        with pytest.raises(ValueError):
+            oracle.encode_atkf(x, "f32", 0.5, lam, 2, 2, B28, 1e-3)
