@@ -65,7 +65,7 @@ def make_workload(which: int):
     return wl, [wl.x]
 
 
-def cpu_baseline(wl, threads: int, ladder=None, ds=None) -> dict:
+def cpu_baseline(wl, threads: int, ladder=None, ds=None, lam=None) -> dict:
     """The oracle as it stands (encode + decode) on a bounded sample of the rows."""
     from oracle import ref
     ref.lib()
@@ -75,6 +75,9 @@ def cpu_baseline(wl, threads: int, ladder=None, ds=None) -> dict:
             return ref.encode_ladder(x, wl.dtype, wl.keep_ratio, ladder, n_threads=n_threads)
         if ds is not None:
             return ref.encode_ds(x, wl.dtype, wl.keep_ratio, wl.n_blocks, wl.bit_set, ds, n_threads=n_threads)
+        if lam is not None:
+            return ref.encode_atkf(x, wl.dtype, wl.keep_ratio, lam, wl.n_blocks, wl.n_blocks, wl.bit_set, wl.budget,
+                                   n_threads=n_threads)
         return ref.encode(x, wl.dtype, wl.keep_ratio, wl.n_blocks, wl.bit_set, wl.budget, n_threads=n_threads)
 
     rows = wl.rows
@@ -142,6 +145,9 @@ def main() -> int:
                          "bitwidths, one per block of a sign class, e.g. 8,7,6,5,4,3,2,2")
     ap.add_argument("--ds", type=float, default=None,
                     help="time the paper's DS guard with greedy descent at this delta instead of the budget search")
+    ap.add_argument("--lam", type=float, default=None,
+                    help="time the asymmetric thresholds of Sec. 3.1 at this asymmetry factor (0 < lambda < 1; "
+                         "runs on the generic kernel)")
     ap.add_argument("--eager", action="store_true",
                     help="time plain launches instead of replaying a captured HIP graph of the steps")
     ap.add_argument("--copy-probe", action="store_true",
@@ -172,6 +178,8 @@ def main() -> int:
             binding.slicer_encode_ladder(x, keep, ladder, sb, meta, ws)
         elif args.ds is not None:
             binding.slicer_encode_ds(x, keep, M, bits, args.ds, sb, meta, ws)
+        elif args.lam is not None:
+            binding.slicer_encode_atkf(x, keep, args.lam, M, M, bits, beta, sb, meta, ws)
         else:
             binding.slicer_encode(x, keep, M, bits, beta, sb, meta, ws)
     in_bytes = wl.nbytes
@@ -313,6 +321,8 @@ def main() -> int:
 
     path = binding.slicer_encode_path(binding.SLICER_F32 if wl.dtype == "f32" else binding.SLICER_BF16,
                                       wl.rows, wl.row_len, keep, M, bits)
+    if args.lam is not None and args.lam > 0:
+        path = 0                                         # the second selection is built in the generic kernel only
     enc_kernel = {0: "enc_generic_kernel", 1: "enc_small_kernel", 2: "lr_* stages (hist..pack)"}[path]
     dec_kernel = "dec_small_kernel" if wl.row_len * (4 if wl.dtype == "f32" else 2) <= 16384 else "dec_kernel"
     enc_alg_bytes = in_bytes + out_bytes                 # read x once, write stream + meta
@@ -321,7 +331,7 @@ def main() -> int:
     roofline = {"bound": "hbm", "kernel": enc_kernel, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": achieved / HBM_PEAK_GBS, "traffic": load_traffic(wl.name, enc_kernel),
                 "algorithmic_bytes_per_launch": enc_alg_bytes, "kernel_ms": enc_ms,
-                "alu": None if (ladder or args.ds is not None) else alu_view(wl.name, enc_kernel, enc_ms),
+                "alu": None if (ladder or args.ds is not None or args.lam is not None) else alu_view(wl.name, enc_kernel, enc_ms),
                 "decode_kernel": {"kernel": dec_kernel, "kernel_ms": dec_ms,
                                   "achieved": dec_alg_bytes / (dec_ms * 1e-3) / 1e9,
                                   "frac": dec_alg_bytes / (dec_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
@@ -333,7 +343,7 @@ def main() -> int:
         torch.cuda.synchronize()
 
     threads = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)))
-    cpu = None if args.no_cpu else cpu_baseline(wl, threads, ladder, args.ds)
+    cpu = None if args.no_cpu else cpu_baseline(wl, threads, ladder, args.ds, args.lam)
 
     out = {
         "metric": "codec encode+decode throughput, GB/s of input IF",
@@ -344,7 +354,7 @@ def main() -> int:
         "dtype": wl.dtype, "data": "synthetic", "launch": launch,
         "config": {"workload": f"{wl.name} [{wl.rows}x{wl.row_len}] keep={keep} M={M} "
                                + (f"ladder={ladder}" if ladder else f"bits=2..8 DS delta={args.ds}" if args.ds is not None
-                                  else f"bits=2..8 budget={beta}"),
+                                  else f"bits=2..8 budget={beta}") + (f" lambda={args.lam}" if args.lam is not None else ""),
                    "input_bytes": in_bytes, "distinct_input_buffers": n_buf},
         "encode": {"GBps": in_bytes / (enc_call_ms * 1e-3) / 1e9, "ms": enc_call_ms,
                    "elements_per_s": n_el / (enc_call_ms * 1e-3),

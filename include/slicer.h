@@ -126,6 +126,22 @@ int slicer_encode_pn(const void* x, slicer_dtype dt, int64_t rows, int64_t row_l
                      double keep_ratio, int n_blocks, int n_blocks_neg, uint32_t bit_set,
                      double distortion_budget,
                      void* stream, void* meta, void* workspace, void* hip_stream);
+/*
+ * The asymmetric thresholds of Sec. 3.1 (Eq. "split_filter" with an asymmetry factor lambda in
+ * [0, 1), used as an fp32 value): tau = the k-th largest |x| of the row, tau+ = (1 + lambda) tau,
+ * tau- = -(1 - lambda) tau (one fp32 multiplication each); strictly retained are x > tau+ and
+ * x < tau-.  Fewer than k of them: the set is filled up to k from the elements with |x| <= tau
+ * that are not in it, largest magnitude first (equal magnitudes: lower index first), so positive
+ * values in (tau, tau+] are never sent.  k or more (the section is silent; its exact count
+ * decides): the k largest magnitudes of the set stay.  lambda = 0 is slicer_encode_pn and takes
+ * its kernels; lambda > 0 runs on the generic one-workgroup-per-row kernel (the second selection
+ * over a subset of the row is built there only).  Buffers, format and decode as slicer_encode_pn;
+ * SLICER_EINVAL for lambda outside [0, 1).
+ */
+int slicer_encode_atkf(const void* x, slicer_dtype dt, int64_t rows, int64_t row_len,
+                       double keep_ratio, double lambda, int n_blocks, int n_blocks_neg,
+                       uint32_t bit_set, double distortion_budget,
+                       void* stream, void* meta, void* workspace, void* hip_stream);
 int slicer_decode_as_pn(const void* stream, const void* meta, void* y, slicer_dtype dt,
                         int64_t rows, int64_t row_len, int n_blocks, int n_blocks_neg,
                         void* hip_stream);

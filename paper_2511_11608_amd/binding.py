@@ -48,6 +48,8 @@ def load() -> C.CDLL:
         L.slicer_sizes_pn.argtypes = [cint, i64, i64, dbl, cint, cint, u32, szp, szp, szp]
         L.slicer_encode_pn.restype = cint
         L.slicer_encode_pn.argtypes = [vp, cint, i64, i64, dbl, cint, cint, u32, dbl, vp, vp, vp, vp]
+        L.slicer_encode_atkf.restype = cint
+        L.slicer_encode_atkf.argtypes = [vp, cint, i64, i64, dbl, dbl, cint, cint, u32, dbl, vp, vp, vp, vp]
         L.slicer_decode_as_pn.restype = cint
         L.slicer_decode_as_pn.argtypes = [vp, vp, vp, cint, i64, i64, cint, cint, vp]
         L.slicer_check_pn.restype = cint
@@ -152,6 +154,18 @@ def slicer_encode_pn(x: torch.Tensor, keep_ratio: float, n_blocks: int, n_blocks
     rows, row_len = x.shape
     _check("slicer_encode_pn", load().slicer_encode_pn(
         x.data_ptr(), _dt_of(x), rows, row_len, keep_ratio, n_blocks, n_blocks_neg, bit_set, distortion_budget,
+        stream_buf.data_ptr(), meta.data_ptr(), workspace.data_ptr(), _stream_handle(stream)))
+
+
+def slicer_encode_atkf(x: torch.Tensor, keep_ratio: float, lam: float, n_blocks: int, n_blocks_neg: int, bit_set: int,
+                       distortion_budget: float, stream_buf: torch.Tensor, meta: torch.Tensor, workspace: torch.Tensor,
+                       stream=None) -> None:
+    """slicer_encode_pn with the asymmetric thresholds of Sec. 3.1 (asymmetry factor lam in [0, 1))."""
+    if not x.is_cuda or not x.is_contiguous() or x.dim() != 2:
+        raise ValueError("x must be a contiguous 2-D tensor on the GPU")
+    rows, row_len = x.shape
+    _check("slicer_encode_atkf", load().slicer_encode_atkf(
+        x.data_ptr(), _dt_of(x), rows, row_len, keep_ratio, lam, n_blocks, n_blocks_neg, bit_set, distortion_budget,
         stream_buf.data_ptr(), meta.data_ptr(), workspace.data_ptr(), _stream_handle(stream)))
 
 

@@ -289,8 +289,10 @@ int slicer_encode_path(slicer_dtype dt, int64_t rows, int64_t row_len, double ke
 
 static int encode_impl(const void* x, slicer_dtype dt, int64_t rows, int64_t row_len, double keep_ratio,
                        int n_blocks, int n_blocks_neg, uint32_t bit_set, double distortion_budget, const Ladder& lad, int guard,
-                       void* stream, void* meta, void* workspace, void* hip_stream)
+                       void* stream, void* meta, void* workspace, void* hip_stream, double lambda = 0.0)
 {
+    if (!(lambda >= 0.0 && lambda < 1.0)) return SLICER_EINVAL;
+    const bool asym = (float)lambda > 0.0f;      // lambda = 0 is the plain top-K filter: every fast path applies
     int rc = check_args((int)dt, rows, row_len, keep_ratio, n_blocks, bit_set);
     if (rc) return rc;
     if (!x || !stream || !meta || !workspace) return SLICER_EINVAL;
@@ -321,8 +323,12 @@ static int encode_impl(const void* x, slicer_dtype dt, int64_t rows, int64_t row
     ea.rows_per_wg = 1;
     ea.lad = lad;
     ea.guard = guard;
+    ea.asym = asym ? 1 : 0;
+    ea.one_plus = 1.0f + (float)lambda;
+    ea.one_minus = 1.0f - (float)lambda;
 
-    if (p.small_epl && ((uintptr_t)x & 15) == 0) {
+    // asymmetric thresholds need a second selection over a subset of the row: the generic kernel has it
+    if (!asym && p.small_epl && ((uintptr_t)x & 15) == 0) {
         // fast path; rows it cannot hold are flagged and redone by the generic kernel
         SmallArgs sa;
         sa.x = x; sa.R = rows; sa.N = row_len; sa.k = p.k;
@@ -343,7 +349,7 @@ static int encode_impl(const void* x, slicer_dtype dt, int64_t rows, int64_t row
         if (timed) SLICER_HIP(hipEventRecord(g_ev_stop, st));
         ea.only_flagged = sa.fallback;
     }
-    if (!ea.only_flagged && p.large_C && ((uintptr_t)x & 15) == 0) {
+    if (!asym && !ea.only_flagged && p.large_C && ((uintptr_t)x & 15) == 0) {
         // long rows: multi-workgroup stages; rows they cannot hold are flagged for the generic kernel
         LargeArgs la;
         la.x = x; la.R = rows; la.N = row_len; la.k = p.k;
@@ -440,6 +446,17 @@ int slicer_encode_pn(const void* x, slicer_dtype dt, int64_t rows, int64_t row_l
     for (int j = 0; j < kMaxBlocks / 8; ++j) none.nib[j] = 0;
     return encode_impl(x, dt, rows, row_len, keep_ratio, n_blocks, n_blocks_neg, bit_set, distortion_budget, none, 0,
                        stream, meta, workspace, hip_stream);
+}
+
+int slicer_encode_atkf(const void* x, slicer_dtype dt, int64_t rows, int64_t row_len, double keep_ratio, double lambda,
+                       int n_blocks, int n_blocks_neg, uint32_t bit_set, double distortion_budget, void* stream,
+                       void* meta, void* workspace, void* hip_stream)
+{
+    Ladder none;
+    none.on = 0;
+    for (int j = 0; j < kMaxBlocks / 8; ++j) none.nib[j] = 0;
+    return encode_impl(x, dt, rows, row_len, keep_ratio, n_blocks, n_blocks_neg, bit_set, distortion_budget, none, 0,
+                       stream, meta, workspace, hip_stream, lambda);
 }
 
 int slicer_encode_ds(const void* x, slicer_dtype dt, int64_t rows, int64_t row_len, double keep_ratio,

@@ -33,6 +33,8 @@ struct EncArgs {
     int64_t rows_per_wg;    // consecutive rows a workgroup walks (1 unless only_flagged is set)
     Ladder lad;             // fixed multi-level mode: no search, block m uses qlist[index(m)]
     int guard;              // 0: relative squared-error budget (beta); 1: the DS mismatch of Eq. "DS" (beta = delta), greedy descent
+    int asym;               // 1: asymmetric thresholds of Sec. 3.1 (lambda > 0)
+    float one_plus, one_minus;   // 1 + lambda, 1 - lambda in fp32
     // meta
     MetaView mv;
 };
@@ -128,6 +130,7 @@ __device__ inline void enc_generic_rows(const EncArgs& a, const int64_t r_begin,
     __shared__ u32 cnt_wave[NW][kMaxB2];
     __shared__ u32 run_base[kMaxB2];
     __shared__ u32 s_range[2];
+    __shared__ u32 s_asym[4];                    // asymmetric thresholds: smallest kept key, |S_strict|, fill candidates
 
     const int tid = threadIdx.x;
     const u32 lane = lane_id();
@@ -154,11 +157,12 @@ __device__ inline void enc_generic_rows(const EncArgs& a, const int64_t r_begin,
     // ------------------------------------------------------------------
     // ATKF: comp of descending rank k-1 over the whole row -> kept <=> comp >= thrK
     // ------------------------------------------------------------------
-    u64 thrK = ~0ull;      // k == 0: nothing kept
-    if (a.k > 0) {
+    // select_rank(pred, rank): a comp threshold t such that exactly rank + 1 of the elements with
+    // pred(key, neg) have comp >= t (MSD radix select; needs rank < number of such elements)
+    auto select_rank = [&](auto pred, u32 rank) -> u64 {
         u64 prefix = 0;
         int hi = TB;
-        u32 rem = (u32)(a.k - 1);
+        u32 rem = rank;
         for (;;) {
             const int bits = hi < kSelBits ? hi : kSelBits;
             const int shift = hi - bits;
@@ -166,9 +170,10 @@ __device__ inline void enc_generic_rows(const EncArgs& a, const int64_t r_begin,
             for (int i = tid; i < NB; i += BLOCK) sA[i] = 0;
             __syncthreads();
             for (int64_t i = tid; i < N; i += BLOCK) {
-                u32 key = E::key(xr[i]);
+                const raw_t rv = xr[i];
+                u32 key = E::key(rv);
                 u64 comp = ((u64)key << w) | (idxmask - (u64)i);
-                if ((comp >> hi) == prefix) atomicAdd(&sA[(u32)(comp >> shift) & (u32)(NB - 1)], 1u);
+                if (pred(key, E::neg(rv)) && (comp >> hi) == prefix) atomicAdd(&sA[(u32)(comp >> shift) & (u32)(NB - 1)], 1u);
             }
             __syncthreads();
             block_find_desc<BLOCK>(sA, NB, rem, s_scan, s_out);
@@ -179,7 +184,57 @@ __device__ inline void enc_generic_rows(const EncArgs& a, const int64_t r_begin,
             hi = shift;
             if (rem == cnt - 1 || hi == 0) break;
         }
-        thrK = prefix << hi;
+        return prefix << hi;
+    };
+    u64 thrK = ~0ull;      // k == 0: nothing kept
+    if (a.k > 0) thrK = select_rank([](u32, u32) { return true; }, (u32)(a.k - 1));
+
+    // Asymmetric thresholds (Sec. 3.1, lambda > 0).  tau = the k-th largest magnitude = the smallest
+    // key at or above thrK; strictly retained are the positives above (1 + lambda) tau and the
+    // negatives above (1 - lambda) tau.  Fewer than k of them: the set is filled from the elements
+    // at or below tau that are not in it, largest first (thr2 is the last one taken); k or more:
+    // only the k largest of the set stay (thr2 is the last one kept).
+    u32 tp_bits = 0, tn_bits = 0, tau_key = 0;
+    u64 thr2 = 0;
+    bool asym_trim = false;
+    auto is_strict = [&](u32 key, u32 neg) -> bool {       // |x| as an fp32 pattern orders like the value
+        return E::value_bits(key) > (neg ? tn_bits : tp_bits);
+    };
+    if (a.asym && a.k > 0) {
+        if (tid == 0) { s_asym[0] = 0xFFFFFFFFu; s_asym[1] = 0; s_asym[2] = 0; }
+        __syncthreads();
+        u32 kmin = 0xFFFFFFFFu;
+        for (int64_t i = tid; i < N; i += BLOCK) {
+            const u32 key = E::key(xr[i]);
+            const u64 comp = ((u64)key << w) | (idxmask - (u64)i);
+            if (comp >= thrK) kmin = key < kmin ? key : kmin;
+        }
+        atomicMin(&s_asym[0], kmin);
+        __syncthreads();
+        tau_key = s_asym[0];
+        const float tau = __uint_as_float(E::value_bits(tau_key));
+        tp_bits = __float_as_uint(__fmul_rn(a.one_plus, tau));
+        tn_bits = __float_as_uint(__fmul_rn(a.one_minus, tau));
+        u32 c_loc = 0, f_loc = 0;
+        for (int64_t i = tid; i < N; i += BLOCK) {
+            const raw_t rv = xr[i];
+            const u32 key = E::key(rv);
+            if (is_strict(key, E::neg(rv))) ++c_loc;
+            else if (key <= tau_key) ++f_loc;
+        }
+        atomicAdd(&s_asym[1], c_loc);
+        atomicAdd(&s_asym[2], f_loc);
+        __syncthreads();
+        const u32 c = s_asym[1], f = s_asym[2];
+        __syncthreads();
+        if ((int64_t)c >= a.k) {
+            asym_trim = true;
+            thr2 = select_rank(is_strict, (u32)(a.k - 1));
+        } else {
+            const u32 D = (u32)(a.k - (int64_t)c);
+            if (f > D) thr2 = select_rank([&](u32 key, u32 neg) { return !is_strict(key, neg) && key <= tau_key; }, D - 1u);
+            else thr2 = 0;                                  // every candidate is taken
+        }
     }
 
     // ------------------------------------------------------------------
@@ -194,7 +249,13 @@ __device__ inline void enc_generic_rows(const EncArgs& a, const int64_t r_begin,
             key = E::key(rv);
             neg = E::neg(rv);
             u64 comp = ((u64)key << w) | (idxmask - (u64)i);
-            flag = (comp >= thrK && key != 0) ? 1u : 0u;
+            if (a.asym && a.k > 0) {
+                const bool st = is_strict(key, neg);
+                const bool in = asym_trim ? (st && comp >= thr2) : (st || (key <= tau_key && comp >= thr2));
+                flag = (in && key != 0) ? 1u : 0u;
+            } else {
+                flag = (comp >= thrK && key != 0) ? 1u : 0u;
+            }
         }
         // one scan carries both counts: kept in the low half, kept negatives in the high half
         u32 tot;

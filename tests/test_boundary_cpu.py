@@ -29,7 +29,7 @@ def test_exports_every_declared_symbol(lib):
     assert {"slicer_sizes", "slicer_encode", "slicer_decode", "slicer_decode_as", "slicer_stream_words",
             "slicer_encode_path", "slicer_profile_events", "slicer_last_hip_error", "slicer_strerror",
             "slicer_encode_ladder", "slicer_ladder_bit_set", "slicer_bound", "slicer_check", "slicer_encode_ds",
-            "slicer_sizes_pn", "slicer_encode_pn", "slicer_decode_as_pn", "slicer_check_pn"} <= set(names)
+            "slicer_sizes_pn", "slicer_encode_pn", "slicer_decode_as_pn", "slicer_check_pn", "slicer_encode_atkf"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 

@@ -251,6 +251,51 @@ def test_separate_block_counts_mixed_rows(oracle, dtype, N):
         assert ok, explain_mismatch(s_ref, m_ref, s_gpu, m_gpu, x.shape[0])
 
 
+def check_atkf(oracle, x, dtype, keep, lam, Mp, Mn, bits, budget):
+    import torch
+    from paper_2511_11608_amd import binding
+    from paper_2511_11608_amd.devmem import to_device, to_host
+    xd = to_device(x, dtype)
+    s_ref, m_ref = oracle.encode_atkf(x, dtype, keep, lam, Mp, Mn, bits, budget, n_threads=8)
+    y_ref = oracle.decode(s_ref, m_ref, n_threads=8)
+    sb, meta, ws = binding.alloc_buffers_pn(xd, keep, Mp, Mn, bits)
+    ws.fill_(0x3C); sb.fill_(-1); meta.fill_(0xFF)
+    binding.slicer_encode_atkf(xd, keep, lam, Mp, Mn, bits, budget, sb, meta, ws)
+    words = binding.slicer_stream_words(meta)
+    m_gpu = meta.cpu().numpy()
+    s_gpu = sb[:words].cpu().numpy().view(np.uint32)
+    assert np.array_equal(m_ref[:64], m_gpu[:64]), (streamfmt.header(m_ref), streamfmt.header(m_gpu))
+    ok = np.array_equal(m_ref, m_gpu) and np.array_equal(s_ref, s_gpu)
+    assert ok, explain_mismatch(s_ref, m_ref, s_gpu, m_gpu, x.shape[0])
+    y = torch.full_like(xd, 7.0)
+    binding.slicer_decode(sb, meta, y)
+    torch.cuda.synchronize()
+    yv = np.uint32 if dtype == "f32" else np.uint16
+    assert np.array_equal(y_ref.view(yv), to_host(y).view(yv))
+
+
+@pytest.mark.parametrize("name", ["cnn_map_ragged", "resnet_2rows", "vit", "llm", "ar_step"])
+def test_asymmetric_thresholds_workloads(oracle, name):
+    """Sec. 3.1 with lambda > 0 (second selection over a subset of the row), and lambda = 0 through
+    the same entry point (the fast kernels)."""
+    wl = CASES[name]()
+    x = wl.x[:24] if wl.x.shape[0] > 24 else wl.x
+    for lam in (0.0, 0.05, 0.5, 0.95):
+        check_atkf(oracle, x, wl.dtype, wl.keep_ratio, lam, wl.n_blocks, wl.n_blocks, wl.bit_set, wl.budget)
+
+
+@pytest.mark.parametrize("dtype,N", [("bf16", 4096), ("f32", 768), ("bf16", 1000), ("f32", 5000)])
+def test_asymmetric_thresholds_mixed_rows(oracle, dtype, N):
+    """Degenerate rows (sparse, constant, few-valued, one-sided, all zero) and a mostly negative row, where
+    the strict set is larger than k and is cut back."""
+    rng = np.random.default_rng(N + 4)
+    x = _mixed_rows(rng, 12, N, dtype)
+    neg_row = (rng.standard_normal(N) - 0.8).astype(np.float32)
+    x[8] = synth.f32_to_bf16_bits(neg_row) if dtype == "bf16" else neg_row
+    for keep, lam, Mp, Mn in ((0.1, 0.3, 8, 8), (0.02, 0.9, 1, 3), (0.5, 0.1, 5, 2), (1.0, 0.5, 4, 4), (0.0, 0.2, 2, 2)):
+        check_atkf(oracle, x, dtype, keep, lam, Mp, Mn, B28, 1e-3)
+
+
 def test_encode_is_deterministic():
     from tests.gpu_util import gpu_roundtrip
     wl = synth.llm_prefill(seed=3, rows=64)
