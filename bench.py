@@ -155,8 +155,8 @@ def main() -> int:
                          "scales the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this codec build runs on ONE GPU (rows are independent; sharding is by rows, "
-              "see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this codec build runs on ONE GPU (rows are independent codec instances, so more GPUs "
+              "would each take a share of the rows with nothing exchanged); run with --gpus 1", file=sys.stderr)
         return 2
 
     import torch
