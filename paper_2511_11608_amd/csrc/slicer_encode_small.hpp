@@ -437,13 +437,13 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
         if (p < nL) {
             const u32 e = ent_word(s);
             const u32 key = DT == 0 ? (e & 0x7FFFFFFFu) : ((e >> 16) & 0x7FFFu);
-            lds_inc(((key - t_lo) >> sh) << 2, (e >> 31) ? 0x10000u : 1u);
+            lds_inc(((key - t_lo) >> sh) << 2, (e >> 31) ? 0x800u : 1u);    // 11-bit fields: the list has fewer than 2048 entries
         }
     }
     wave_sync();
     u32 n_pos, n_neg;
     int cut_lane = 0;
-    {   // exclusive prefix from the top, per class; repack as pos | neg << 11 | fill << 22
+    {   // exclusive prefix from the top, per class, in the counting format pos | neg << 11 (fill << 22 is added later)
         const int hi = kFineBins - (int)lane * 16;
         u32 cs[16];
         uint4* h4 = (uint4*)(L.hist + hi - 16);
@@ -452,26 +452,31 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
             const uint4 t = h4[3 - j];
             cs[4 * j + 0] = t.w; cs[4 * j + 1] = t.z; cs[4 * j + 2] = t.y; cs[4 * j + 3] = t.x;
         }
-        u32 local = 0, big = 0;
+        u32 local = 0;
 #pragma unroll
-        for (int j = 0; j < 16; ++j) { local += cs[j]; big |= ((cs[j] & 0xFFFFu) + (cs[j] >> 16)) >> 10; }
-        if (__ballot(big != 0u)) {                      // a fine bin with 1024+ members overflows its fill field
-            if (lane == 0) a.fallback[r] = 1u;
-            return;
+        for (int j = 0; j < 16; ++j) local += cs[j];
+        if (nL >= 1024u) {                              // a fine bin with 1024+ members overflows its 10-bit fill field
+            u32 big = 0;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) big |= ((cs[j] & 0x7FFu) + (cs[j] >> 11)) >> 10;
+            if (__ballot(big != 0u)) {
+                if (lane == 0) a.fallback[r] = 1u;
+                return;
+            }
         }
         const u32 incl = wave_scan_dpp(local);
         const u32 tot = bcast(incl, kWave - 1);
-        n_pos = tot & 0xFFFFu; n_neg = tot >> 16;       // class sizes of L (of the kept set once cut)
+        n_pos = tot & 0x7FFu; n_neg = tot >> 11;        // class sizes of L (of the kept set once cut)
         const u32 excl = incl - local;
         // the lane whose bins hold overall rank k-1 (meaningful when nL > k)
-        const u32 ov_ex = (excl & 0xFFFFu) + (excl >> 16), ov_in = (incl & 0xFFFFu) + (incl >> 16);
+        const u32 ov_ex = (excl & 0x7FFu) + (excl >> 11), ov_in = (incl & 0x7FFu) + (incl >> 11);
         const u64 mc = __ballot(k > 0 && ov_ex <= (u32)(k - 1) && (u32)(k - 1) < ov_in);
         cut_lane = mc ? (int)__builtin_ctzll(mc) : 0;
         u32 acc = excl;
         u32 o[16];
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
-            o[j] = (acc & 0xFFFFu) | ((acc >> 16) << 11);
+            o[j] = acc;
             acc += cs[j];
         }
 #pragma unroll
