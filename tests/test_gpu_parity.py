@@ -59,6 +59,9 @@ CASES = {
     "vit": lambda: synth.vit_tokens(seed=0, rows=700),                               # config 3
     "llm": lambda: synth.llm_prefill(seed=0, rows=300),                              # config 4
     "ar_step": lambda: synth.ar_decode_step(seed=0, step=5, rows=64),                 # config 5
+    "llm_wide": lambda: synth.llm_prefill(seed=2, rows=300, width=12288),            # between the row-resident and the long-row home ranges
+    "vit_wide": lambda: synth.vit_tokens(seed=2, rows=200, width=8192),
+    "vit_4096": lambda: synth.vit_tokens(seed=3, rows=200, width=4096),              # widest fp32 row of the row-resident kernel
 }
 
 
