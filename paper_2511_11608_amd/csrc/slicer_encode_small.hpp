@@ -245,6 +245,7 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
     bool found = false;
     auto hist_pass = [&](auto shift) {
         constexpr int SH = decltype(shift)::value;
+        constexpr int SHB = SH >= 2 ? SH - 2 : 0;      // fp32: shift that leaves the bin number times 4 (SH is 16 or 20 there)
         {
             uint4* h4 = (uint4*)smem;
 #pragma unroll
@@ -261,7 +262,7 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
                     if (DT == 0) {
                         const u32 key = wd & 0x7FFFFFFFu;
                         const u32 df = wtop > key ? wtop - key : 0u;
-                        lds_inc(min((df >> (SH - 2)) & ~3u, (u32)(4 * kCoarseBins - 4)), 1u);
+                        lds_inc(min((df >> SHB) & ~3u, (u32)(4 * kCoarseBins - 4)), 1u);
                     } else {
                         u32 b = pk_sub_sat_u16(wt2, wd & 0x7FFF7FFFu);
                         if (SH) b = pk_shr_u16(b, SH);
