@@ -146,8 +146,8 @@ def main() -> int:
     ap.add_argument("--ds", type=float, default=None,
                     help="time the paper's DS guard with greedy descent at this delta instead of the budget search")
     ap.add_argument("--lam", type=float, default=None,
-                    help="time the asymmetric thresholds of Sec. 3.1 at this asymmetry factor (0 < lambda < 1; "
-                         "runs on the generic kernel)")
+                    help="time the asymmetric thresholds of Sec. 3.1 at this asymmetry factor (0 < lambda < 1; bf16 rows "
+                         "of up to 8192 elements on the row-resident kernel, everything else on the generic kernel)")
     ap.add_argument("--eager", action="store_true",
                     help="time plain launches instead of replaying a captured HIP graph of the steps")
     ap.add_argument("--copy-probe", action="store_true",
@@ -321,8 +321,8 @@ def main() -> int:
 
     path = binding.slicer_encode_path(binding.SLICER_F32 if wl.dtype == "f32" else binding.SLICER_BF16,
                                       wl.rows, wl.row_len, keep, M, bits)
-    if args.lam is not None and args.lam > 0:
-        path = 0                                         # the second selection is built in the generic kernel only
+    if args.lam is not None and args.lam > 0 and not (wl.dtype == "bf16" and path == 1):
+        path = 0                                         # the second selection: row-resident kernel for bf16 rows, else the generic kernel
     enc_kernel = {0: "enc_generic_kernel", 1: "enc_small_kernel", 2: "lr_* stages (hist..pack)"}[path]
     dec_kernel = "dec_small_kernel" if wl.row_len * (4 if wl.dtype == "f32" else 2) <= 16384 else "dec_kernel"
     enc_alg_bytes = in_bytes + out_bytes                 # read x once, write stream + meta

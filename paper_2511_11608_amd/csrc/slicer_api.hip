@@ -144,25 +144,38 @@ Plan make_plan(int dt, int64_t rows, int64_t row_len, double keep_ratio, int n_b
     return p;
 }
 
-template <int DT, int EPL>
-void launch_small_epl(const SmallArgs& sa, int lds_bytes, int maxs, hipStream_t st)
+template <int DT, int EPL, bool ASYM>
+void launch_small_variant(const SmallArgs& sa, dim3 g, dim3 b, size_t lds, int maxs, hipStream_t st)
 {
-    const dim3 g((unsigned)xcd_grid(sa.R)), b(kWave);
-    const size_t lds = (size_t)lds_bytes;
     // the paper's bitwidth ladders are short; 7 = {2..8} is the benchmarked one
     if (sa.nq == 7) {
-        if (maxs == 10) hipLaunchKernelGGL((enc_small_kernel<DT, EPL, 7, 10>), g, b, lds, st, sa);
-        else if (maxs == 20) hipLaunchKernelGGL((enc_small_kernel<DT, EPL, 7, 20>), g, b, lds, st, sa);
-        else hipLaunchKernelGGL((enc_small_kernel<DT, EPL, 7, 0>), g, b, lds, st, sa);
+        if (maxs == 10) hipLaunchKernelGGL((enc_small_kernel<DT, EPL, 7, 10, ASYM>), g, b, lds, st, sa);
+        else if (maxs == 20) hipLaunchKernelGGL((enc_small_kernel<DT, EPL, 7, 20, ASYM>), g, b, lds, st, sa);
+        else hipLaunchKernelGGL((enc_small_kernel<DT, EPL, 7, 0, ASYM>), g, b, lds, st, sa);
     } else {
-        if (maxs == 10) hipLaunchKernelGGL((enc_small_kernel<DT, EPL, 0, 10>), g, b, lds, st, sa);
-        else if (maxs == 20) hipLaunchKernelGGL((enc_small_kernel<DT, EPL, 0, 20>), g, b, lds, st, sa);
-        else hipLaunchKernelGGL((enc_small_kernel<DT, EPL, 0, 0>), g, b, lds, st, sa);
+        if (maxs == 10) hipLaunchKernelGGL((enc_small_kernel<DT, EPL, 0, 10, ASYM>), g, b, lds, st, sa);
+        else if (maxs == 20) hipLaunchKernelGGL((enc_small_kernel<DT, EPL, 0, 20, ASYM>), g, b, lds, st, sa);
+        else hipLaunchKernelGGL((enc_small_kernel<DT, EPL, 0, 0, ASYM>), g, b, lds, st, sa);
     }
 }
 
+// asym: the asymmetric thresholds of Sec. 3.1 with lambda > 0 (bf16 rows only)
+template <int DT, int EPL>
+void launch_small_epl(const SmallArgs& sa, int lds_bytes, int maxs, hipStream_t st, bool asym)
+{
+    const dim3 g((unsigned)xcd_grid(sa.R)), b(kWave);
+    const size_t lds = (size_t)lds_bytes;
+    if constexpr (DT == 1) {
+        if (asym) {
+            launch_small_variant<DT, EPL, true>(sa, g, b, lds, maxs, st);
+            return;
+        }
+    }
+    launch_small_variant<DT, EPL, false>(sa, g, b, lds, maxs, st);
+}
+
 template <int DT>
-int launch_small(const SmallArgs& sa, const Plan& p, hipStream_t st)
+int launch_small(const SmallArgs& sa, const Plan& p, hipStream_t st, bool asym)
 {
     constexpr int E0 = DT == 0 ? 4 : 16;      // smallest instantiated elements-per-lane
 #ifdef SLICER_LDS_PAD
@@ -170,11 +183,11 @@ int launch_small(const SmallArgs& sa, const Plan& p, hipStream_t st)
 #else
     const int lds = p.small_lds_bytes;
 #endif
-    if (p.small_epl <= E0) launch_small_epl<DT, E0>(sa, lds, p.small_maxs, st);
-    else if (p.small_epl == E0 * 2) launch_small_epl<DT, E0 * 2>(sa, lds, p.small_maxs, st);
-    else if (p.small_epl == E0 * 4) launch_small_epl<DT, E0 * 4>(sa, lds, p.small_maxs, st);
-    else if (p.small_epl == E0 * 8 || DT != 0) launch_small_epl<DT, E0 * 8>(sa, lds, p.small_maxs, st);
-    else launch_small_epl<DT, DT == 0 ? E0 * 16 : E0 * 8>(sa, lds, p.small_maxs, st);   // fp32 rows of 4096
+    if (p.small_epl <= E0) launch_small_epl<DT, E0>(sa, lds, p.small_maxs, st, asym);
+    else if (p.small_epl == E0 * 2) launch_small_epl<DT, E0 * 2>(sa, lds, p.small_maxs, st, asym);
+    else if (p.small_epl == E0 * 4) launch_small_epl<DT, E0 * 4>(sa, lds, p.small_maxs, st, asym);
+    else if (p.small_epl == E0 * 8 || DT != 0) launch_small_epl<DT, E0 * 8>(sa, lds, p.small_maxs, st, asym);
+    else launch_small_epl<DT, DT == 0 ? E0 * 16 : E0 * 8>(sa, lds, p.small_maxs, st, asym);   // fp32 rows of 4096
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? SLICER_OK : hip_fail(e);
 }
@@ -327,8 +340,9 @@ static int encode_impl(const void* x, slicer_dtype dt, int64_t rows, int64_t row
     ea.one_plus = 1.0f + (float)lambda;
     ea.one_minus = 1.0f - (float)lambda;
 
-    // asymmetric thresholds need a second selection over a subset of the row: the generic kernel has it
-    if (!asym && p.small_epl && ((uintptr_t)x & 15) == 0) {
+    // asymmetric thresholds need a second selection over a subset of the row: the generic kernel has it for
+    // every shape, the row-resident kernel for bf16 rows (rows it flags are redone generically, same rule)
+    if ((!asym || dt == SLICER_BF16) && p.small_epl && ((uintptr_t)x & 15) == 0) {
         // fast path; rows it cannot hold are flagged and redone by the generic kernel
         SmallArgs sa;
         sa.x = x; sa.R = rows; sa.N = row_len; sa.k = p.k;
@@ -342,9 +356,10 @@ static int encode_impl(const void* x, slicer_dtype dt, int64_t rows, int64_t row
         sa.cap = p.small_cap; sa.region0_words = p.small_region0;
         sa.lad = lad;
         sa.guard = guard;
+        sa.one_plus = ea.one_plus; sa.one_minus = ea.one_minus;
         const bool timed = g_ev_start && g_ev_stop;
         if (timed) SLICER_HIP(hipEventRecord(g_ev_start, st));
-        rc = dt == SLICER_F32 ? launch_small<0>(sa, p, st) : launch_small<1>(sa, p, st);
+        rc = dt == SLICER_F32 ? launch_small<0>(sa, p, st, false) : launch_small<1>(sa, p, st, asym);
         if (rc) return rc;
         if (timed) SLICER_HIP(hipEventRecord(g_ev_stop, st));
         ea.only_flagged = sa.fallback;

@@ -218,6 +218,8 @@ __device__ inline u32 from_u16x2(u16x2 v) { return __builtin_bit_cast(u32, v); }
 __device__ inline u32 pk_max_u16(u32 a, u32 b) { return from_u16x2(__builtin_elementwise_max(as_u16x2(a), as_u16x2(b))); }
 __device__ inline u32 pk_min_u16(u32 a, u32 b) { return from_u16x2(__builtin_elementwise_min(as_u16x2(a), as_u16x2(b))); }
 __device__ inline u32 pk_sub_sat_u16(u32 a, u32 b) { return from_u16x2(__builtin_elementwise_sub_sat(as_u16x2(a), as_u16x2(b))); }
+__device__ inline u32 pk_add_u16(u32 a, u32 b) { return from_u16x2(as_u16x2(a) + as_u16x2(b)); }
+__device__ inline u32 pk_mul_lo_u16(u32 a, u32 b) { return from_u16x2(as_u16x2(a) * as_u16x2(b)); }
 __device__ inline u32 pk_shl_u16(u32 a, int n) { return from_u16x2(as_u16x2(a) << (unsigned short)n); }
 __device__ inline u32 pk_shr_u16(u32 a, int n) { return from_u16x2(as_u16x2(a) >> (unsigned short)n); }
 

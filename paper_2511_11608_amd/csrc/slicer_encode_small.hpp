@@ -49,6 +49,7 @@ struct SmallArgs {
     int region0_words;  // fine histogram, later block-ordered indices + stream image
     Ladder lad;         // fixed multi-level mode: no sums, no search
     int guard;          // 0: relative squared-error budget; 1: DS mismatch of Eq. "DS", greedy descent (beta = delta)
+    float one_plus, one_minus;   // asymmetric thresholds of Sec. 3.1 (ASYM kernels): 1 + lambda, 1 - lambda in fp32
 };
 
 constexpr int kCoarseBits = 11;
@@ -154,9 +155,16 @@ __device__ inline void lds_inc(u32 byte_off, u32 v)
 // NQ > 0: the number of allowed bitwidths is known at compile time (loops over the
 // candidate bitwidths unroll without predicates); NQ == 0: any number up to 16.
 // MAXS > 0: the list has at most 64 * MAXS entries and lives in registers.
-template <int DT, int EPL, int NQ, int MAXS>
+// ASYM (bf16 only): the asymmetric thresholds of Sec. 3.1 with lambda > 0.  The kept set is not a
+// plain top-K then: after the first selection has given tau, the strict set is counted, a second
+// selection over a subset of the row (the fill candidates, or the strict set when it is too large)
+// gives the last key taken, and the list is built from that rule; the equal keys at the end are cut
+// in index order.  Both selections need the exact key of their rank, i.e. one key per histogram bin:
+// rows whose ranks lie below the 2048-key window are flagged for the generic kernel.
+template <int DT, int EPL, int NQ, int MAXS, bool ASYM = false>
 __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
 {
+    static_assert(!ASYM || DT == 1, "the asymmetric fast path is built for bf16 rows");
     typedef Elem<DT> E;
     typedef typename std::conditional<DT == 0, u64, u32>::type comp_t;   // bf16: key + index fit 31 bits
     constexpr comp_t kClsBit = (comp_t)1 << (8 * sizeof(comp_t) - 1);       // set for the positive class
@@ -243,8 +251,13 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
     int S = S1;
     u32 B1 = 0, c_gt = 0, cnt1 = 0;
     bool found = false;
-    auto hist_pass = [&](auto shift) {
+    u32 rank_t = k > 0 ? (u32)(k - 1) : 0u;         // the rank the pass looks for (among the keys the functor lets through)
+    auto all_keys = [](u32 wd) -> u32 { return wd & 0x7FFF7FFFu; };
+    // skip0: keys that the functor turned into 0 are not counted at all (they would all meet on one
+    // LDS address); the pass then reports found = false when the rank lies beyond the counted keys
+    auto hist_pass = [&](auto shift, auto key_pair, auto skip0) {
         constexpr int SH = decltype(shift)::value;
+        constexpr bool kSkip0 = decltype(skip0)::value;
         constexpr int SHB = SH >= 2 ? SH - 2 : 0;      // fp32: shift that leaves the bin number times 4 (SH is 16 or 20 there)
         {
             uint4* h4 = (uint4*)smem;
@@ -264,11 +277,12 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
                         const u32 df = wtop > key ? wtop - key : 0u;
                         lds_inc(min((df >> SHB) & ~3u, (u32)(4 * kCoarseBins - 4)), 1u);
                     } else {
-                        u32 b = pk_sub_sat_u16(wt2, wd & 0x7FFF7FFFu);
+                        const u32 kp = key_pair(wd);
+                        u32 b = pk_sub_sat_u16(wt2, kp);
                         if (SH) b = pk_shr_u16(b, SH);
                         b = pk_shl_u16(pk_min_u16(b, (u32)(kCoarseBins - 1) * 0x10001u), 2);
-                        lds_inc(b & 0xFFFFu, 1u);
-                        lds_inc(b >> 16, 1u);
+                        if (!kSkip0 || (kp & 0xFFFFu)) lds_inc(b & 0xFFFFu, 1u);
+                        if (!kSkip0 || (kp >> 16)) lds_inc(b >> 16, 1u);
                     }
                 }
             }
@@ -287,7 +301,7 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
             local += (t.x + t.y) + (t.z + t.w);
         }
         const u32 incl = wave_scan_dpp(local), excl = incl - local;
-        const u32 rem = (k > 0 ? (u32)(k - 1) : 0u) - above;
+        const u32 rem = rank_t - above;
         const u64 m_src = __ballot(local > 0 && excl <= rem && rem < incl);
         const int src = m_src ? (int)__builtin_ctzll(m_src) : 0;
         const u32 ex_src = bcast(excl, src);
@@ -303,20 +317,89 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
         }
         wave_sync();
     };
-    hist_pass(std::integral_constant<int, S1>());
+    hist_pass(std::integral_constant<int, S1>(), all_keys, std::false_type());
     if (found && B1 == (u32)(kCoarseBins - 1) && (wtop >> S1) > (u32)(kCoarseBins - 1)) {
         above = c_gt;
         wtop -= (u32)(kCoarseBins - 1) << S1;
         S = S1 + 4;
-        hist_pass(std::integral_constant<int, S1 + 4>());
+        hist_pass(std::integral_constant<int, S1 + 4>(), all_keys, std::false_type());
     }
     c_gt += above;
+
+    // ---- asymmetric thresholds: strict set, second selection ------------------------------------
+    // Everything per pair of keys (packed 16-bit lanes): st = 1 where the element is strictly
+    // retained, inF = 1 where it is a fill candidate (not strict, at or below tau).
+    constexpr u32 kOne2 = 0x00010001u;
+    u32 tau2 = 0, tp2 = 0, dthr2 = 0, t2_2 = 0;     // tau, tau+ and (tau- minus tau+), last key taken: duplicated in both halves
+    u32 t2_key = 0, need_ties = 0, cnt_ties = 0, tn_key = 0;
+    bool trim = false;
+    auto gt01 = [&](u32 a2, u32 b2) -> u32 { return pk_min_u16(pk_sub_sat_u16(a2, b2), kOne2); };   // a > b, per half
+    // (each use starts from an opaque copy of the word: the flags are recomputed where they are needed
+    //  instead of being held in registers for the whole row from one phase to the next)
+    auto strict01 = [&](u32 wd) -> u32 {
+        asm volatile("" : "+v"(wd));
+        const u32 neg01 = (wd >> 15) & kOne2;
+        return gt01(wd & 0x7FFF7FFFu, pk_add_u16(tp2, pk_mul_lo_u16(neg01, dthr2)));
+    };
+    auto fill01 = [&](u32 wd, u32 st) -> u32 {
+        asm volatile("" : "+v"(wd));
+        return (st ^ kOne2) & (gt01(wd & 0x7FFF7FFFu, tau2) ^ kOne2);
+    };
+    if (ASYM && k > 0) {
+        if (!found || S != 0) {                      // tau is not the key of one bin
+            if (lane == 0) a.fallback[r] = 1u;
+            return;
+        }
+        const u32 tau_key = wtop - B1;
+        const float tau = __uint_as_float(tau_key << 16);
+        const u32 tp_key = __float_as_uint(__fmul_rn(a.one_plus, tau)) >> 16;    // (key << 16) > T  <=>  key > (T >> 16)
+        tn_key = __float_as_uint(__fmul_rn(a.one_minus, tau)) >> 16;
+        tau2 = tau_key * 0x10001u; tp2 = tp_key * 0x10001u; dthr2 = ((tn_key - tp_key) & 0xFFFFu) * 0x10001u;
+        u32 accS = 0, accF = 0;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            if ((c * kWave + (int)lane) * EPC < N) {
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    const u32 wd = word_of(c, d);
+                    const u32 st = strict01(wd);
+                    accS = pk_add_u16(accS, st);
+                    accF = pk_add_u16(accF, fill01(wd, st));
+                }
+            }
+        }
+        const u32 both = ((accS & 0xFFFFu) + (accS >> 16)) | (((accF & 0xFFFFu) + (accF >> 16)) << 16);
+        const u32 tot = bcast(wave_scan_dpp(both), kWave - 1);
+        const u32 c_strict = tot & 0xFFFFu, f_fill = tot >> 16;
+        trim = c_strict >= (u32)k;
+        const u32 D = trim ? 0u : (u32)k - c_strict;
+        if (trim || f_fill > D) {
+            // rank k-1 of the strict set, or rank D-1 of the fill candidates: the other keys count as 0
+            rank_t = trim ? (u32)(k - 1) : D - 1u;
+            wtop = trim ? kmax : tau_key;
+            above = 0;
+            if (trim) hist_pass(std::integral_constant<int, 0>(), [&](u32 wd) -> u32 { return pk_mul_lo_u16(wd & 0x7FFF7FFFu, strict01(wd)); }, std::true_type());
+            else hist_pass(std::integral_constant<int, 0>(), [&](u32 wd) -> u32 { return pk_mul_lo_u16(wd & 0x7FFF7FFFu, fill01(wd, strict01(wd))); }, std::true_type());
+            if (found) {
+                if (B1 == (u32)(kCoarseBins - 1) && wtop > (u32)(kCoarseBins - 1)) {     // below the window of single keys
+                    if (lane == 0) a.fallback[r] = 1u;
+                    return;
+                }
+                t2_key = wtop - B1;
+                need_ties = rank_t + 1u - c_gt;
+                cnt_ties = cnt1;
+            }                                            // else: the rank lies among zeros, every non-zero candidate is taken
+        }
+        if (t2_key == 0) { t2_key = 1; need_ties = 0; cnt_ties = 0; }     // the rank falls on zeros (never sent) or every candidate is taken
+        t2_2 = t2_key * 0x10001u;
+    }
 
     // the list takes every non-zero key from bin B1 up (a bin that reaches key 0 also counts the
     // zeros, which never enter the list: its length is known after the counting pass below)
     const long long lowk = (long long)wtop - ((long long)(B1 + 1u) << S) + 1;
-    const u32 t_lo = lowk > 1 ? (u32)lowk : 1u;                  // smallest non-zero key of bin B1
-    if (k > 0 && lowk >= 1 && (int)(c_gt + cnt1) > cap) {
+    u32 t_lo = lowk > 1 ? (u32)lowk : 1u;                        // smallest non-zero key of bin B1
+    if (ASYM && k > 0) t_lo = trim ? t2_key : min(t2_key, tn_key + 1u);   // smallest key the list can hold
+    if (!ASYM && k > 0 && lowk >= 1 && (int)(c_gt + cnt1) > cap) {
         if (lane == 0) a.fallback[r] = 1u;
         return;
     }
@@ -327,6 +410,15 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
     if (k > 0) {
         u32 cntc[NCH];
         const u32 C16 = (0x8000u - t_lo) * 0x10001u;            // bf16: bit 15 / 31 of (key + C16) <=> key >= t_lo
+        // bits 15 and 31: the element goes to the list
+        auto list_flags = [&](u32 wd) -> u32 {
+            if (!ASYM) return (wd & 0x7FFF7FFFu) + C16;
+            const u32 st = strict01(wd);
+            u32 wk = wd;
+            asm volatile("" : "+v"(wk));
+            const u32 ge = gt01(t2_2, wk & 0x7FFF7FFFu) ^ kOne2;              // key >= last key taken
+            return (trim ? (st & ge) : (st | (fill01(wd, st) & ge))) << 15;
+        };
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
             u32 n1 = 0;
@@ -334,7 +426,7 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
             for (int d = 0; d < 4; ++d) {
                 const u32 wd = word_of(c, d);
                 if (DT == 0) n1 += ((wd & 0x7FFFFFFFu) >= t_lo) ? 1u : 0u;
-                else n1 += (u32)__popc(((wd & 0x7FFF7FFFu) + C16) & 0x80008000u);
+                else n1 += (u32)__popc(list_flags(wd) & 0x80008000u);
             }
             cntc[c] = n1;
         }
@@ -381,7 +473,7 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
                     }
                     wa += fl << 2;
                 } else {
-                    const u32 f = (wd & 0x7FFF7FFFu) + C16;
+                    const u32 f = list_flags(wd);
                     u32 f0 = (f >> 15) & 1u, f1 = f >> 31;
                     asm volatile("" : "+v"(f0));
                     asm volatile("" : "+v"(f1));
@@ -395,6 +487,33 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
                 }
             }
         }
+    }
+    if (ASYM && k > 0 && need_ties < cnt_ties) {
+        // The list holds every candidate with the last key taken; only the first need_ties of them
+        // in index order stay.  The list is in index order: the others are squeezed out in place.
+        wave_sync();
+        u32 seen = 0, dead = 0;
+        for (u32 p0 = 0; p0 < nL; p0 += kWave) {
+            const u32 p = p0 + lane;
+            u32 e = 0;
+            bool tie = false;
+            if (p < nL) {
+                e = L.Lent[p];
+                const u32 wd = e >> 16;                                  // sign and key in the low half, as in the row
+                const u32 st = strict01(wd) & 1u;
+                const u32 cand = trim ? st : (fill01(wd, st) & 1u);
+                tie = cand && (wd & 0x7FFFu) == t2_key;
+            }
+            const u64 mt = __ballot(tie);
+            const bool drop = tie && seen + mask_rank(mt) >= need_ties;
+            const u64 md = __ballot(drop);
+            wave_sync();
+            if (p < nL && !drop) L.Lent[p - dead - mask_rank(md)] = e;
+            wave_sync();
+            seen += (u32)__popcll(mt);
+            dead += (u32)__popcll(md);
+        }
+        nL -= dead;
     }
     if (MAXS) {
         // the list moves into registers: its LDS storage is free for the bin-ordered list

@@ -127,6 +127,12 @@ def test_wide_dynamic_range_rows(oracle, dtype, N):
     """Magnitudes spread evenly over many octaves: the row kernel's histogram window covers 16
     octaves below the row's largest value, so these rows put rank k-1 inside the window, on its
     last bin, and below it (second, coarser pass), with and without zeros under it."""
+    x = _wide_range_rows(N, dtype)
+    for keep, M in ((0.05, 4), (0.3, 8), (0.5, 3), (0.9, 8), (1.0, 2)):
+        check(oracle, x, dtype, keep, M, B28, 1e-3)
+
+
+def _wide_range_rows(N, dtype):
     rng = np.random.default_rng(7 * N)
     rows = 12
     spans = np.array([4, 12, 15.9, 16.0, 16.1, 17, 24, 40, 60, 90, 120, 30], np.float32)[:, None]
@@ -134,10 +140,7 @@ def test_wide_dynamic_range_rows(oracle, dtype, N):
     x = (mag * rng.choice(np.array([-1.0, 1.0], np.float32), (rows, N))).astype(np.float32)
     x[11, rng.random(N) < 0.5] = 0                      # zeros below a wide range
     x[10, 0] = np.float32(3e38)                         # one huge value on top of 120 octaves
-    if dtype == "bf16":
-        x = synth.f32_to_bf16_bits(x)
-    for keep, M in ((0.05, 4), (0.3, 8), (0.5, 3), (0.9, 8), (1.0, 2)):
-        check(oracle, x, dtype, keep, M, B28, 1e-3)
+    return synth.f32_to_bf16_bits(x) if dtype == "bf16" else x
 
 
 def check_ladder(oracle, x, dtype, keep, ladder):
@@ -297,6 +300,16 @@ def test_asymmetric_thresholds_mixed_rows(oracle, dtype, N):
     x[8] = synth.f32_to_bf16_bits(neg_row) if dtype == "bf16" else neg_row
     for keep, lam, Mp, Mn in ((0.1, 0.3, 8, 8), (0.02, 0.9, 1, 3), (0.5, 0.1, 5, 2), (1.0, 0.5, 4, 4), (0.0, 0.2, 2, 2)):
         check_atkf(oracle, x, dtype, keep, lam, Mp, Mn, B28, 1e-3)
+
+
+@pytest.mark.parametrize("dtype,N", [("bf16", 4096), ("bf16", 8192), ("f32", 768)])
+def test_asymmetric_thresholds_wide_range(oracle, dtype, N):
+    """Rows on which the row-resident kernel cannot take both selections from its window of single
+    keys (tau or the last fill key lies more than 16 octaves down): they are redone by the generic
+    kernel under the same rule, next to rows that stay on the fast path."""
+    x = _wide_range_rows(N, dtype)
+    for keep, lam, M in ((0.05, 0.2, 4), (0.3, 0.6, 8), (0.9, 0.95, 8), (1.0, 0.5, 2)):
+        check_atkf(oracle, x, dtype, keep, lam, M, M, B28, 1e-3)
 
 
 def test_encode_is_deterministic():
