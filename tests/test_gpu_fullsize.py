@@ -8,7 +8,7 @@ import numpy as np
 import pytest
 
 from paper_2511_11608_amd import synth
-from tests.test_gpu_parity import check
+from tests.test_gpu_parity import check, check_atkf
 
 pytestmark = pytest.mark.gpu
 
@@ -25,6 +25,14 @@ def test_full_size_workload(oracle, cfg):
 def test_ar_decode_steps(oracle, step):
     wl = synth.ar_decode_step(seed=0, step=step)
     check(oracle, wl.x, wl.dtype, wl.keep_ratio, wl.n_blocks, wl.bit_set, wl.budget, use_header=True)
+
+
+@pytest.mark.parametrize("lam", [0.1, 0.7])
+def test_full_size_llm_prefill_asymmetric(oracle, lam):
+    """The headline tensor under the asymmetric thresholds of Sec. 3.1 (row-resident kernel with its
+    second selection), every row against the oracle."""
+    wl = synth.make_config(4)
+    check_atkf(oracle, wl.x, wl.dtype, wl.keep_ratio, lam, wl.n_blocks, wl.n_blocks, wl.bit_set, wl.budget)
 
 
 def test_size_accounting_llm_prefill(oracle):
