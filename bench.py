@@ -7,6 +7,12 @@ default workload is the LLM-prefill configuration (bf16 [16384, 4096], the large
 of the five); input buffers rotate over > 256 MB of distinct device memory so that
 the Infinity Cache does not stand in for HBM.
 
+Consecutive steps work on independent batches (the paper's many clients, or the successive
+token batches of one client), so the K timed steps alternate over three HIP streams by default:
+step i+1 fills the ramp, the drain and the launch gaps of step i.  `value` is the throughput of
+those K steps; `single_stream` in the same line is the figure with every step on one stream,
+`step_latency_us` the time of one step submitted alone.
+
 Prints ONE JSON line: whole-step throughput in GB/s of input IF, the roofline
 record of the dominant kernel (the encode kernel that does the selection, quantisation
 and packing of a row; its duration is read with HIP events recorded around it on its stream), and the CPU oracle timed on
@@ -136,8 +142,8 @@ def load_traffic(workload: str, kernel: str):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", type=int, default=4, help="1..5 (default 4: LLM prefill, the headline config)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--ladder", type=str, default="",
@@ -148,6 +154,9 @@ def main() -> int:
     ap.add_argument("--lam", type=float, default=None,
                     help="time the asymmetric thresholds of Sec. 3.1 at this asymmetry factor (0 < lambda < 1; bf16 rows "
                          "of up to 8192 elements on the row-resident kernel, everything else on the generic kernel)")
+    ap.add_argument("--streams", type=int, default=3,
+                    help="HIP streams the steps alternate over (default 3): consecutive steps work on independent "
+                         "batches, so step i+1 fills the ramp, the drain and the launch gaps of step i; 1 = one stream")
     ap.add_argument("--eager", action="store_true",
                     help="time plain launches instead of replaying a captured HIP graph of the steps")
     ap.add_argument("--copy-probe", action="store_true",
@@ -173,15 +182,15 @@ def main() -> int:
             print("bench.py: --ladder entries must be 1..16", file=sys.stderr)
             return 2
 
-    def encode(x, sb, meta, ws):
+    def encode(x, sb, meta, ws, st=None):
         if ladder:
-            binding.slicer_encode_ladder(x, keep, ladder, sb, meta, ws)
+            binding.slicer_encode_ladder(x, keep, ladder, sb, meta, ws, stream=st)
         elif args.ds is not None:
-            binding.slicer_encode_ds(x, keep, M, bits, args.ds, sb, meta, ws)
+            binding.slicer_encode_ds(x, keep, M, bits, args.ds, sb, meta, ws, stream=st)
         elif args.lam is not None:
-            binding.slicer_encode_atkf(x, keep, args.lam, M, M, bits, beta, sb, meta, ws)
+            binding.slicer_encode_atkf(x, keep, args.lam, M, M, bits, beta, sb, meta, ws, stream=st)
         else:
-            binding.slicer_encode(x, keep, M, bits, beta, sb, meta, ws)
+            binding.slicer_encode(x, keep, M, bits, beta, sb, meta, ws, stream=st)
     in_bytes = wl.nbytes
 
     # distinct input buffers: > 256 MB in flight so that reads come from HBM
@@ -193,7 +202,11 @@ def main() -> int:
     while len(xd) < n_buf:
         xd.append(torch.roll(x0[len(xd) % len(x0)], shifts=shift, dims=0).contiguous())
         shift += 1
-    n_out = min(n_buf, 4)
+    # Steps alternate over S streams (default priority).  Output buffer set j is only ever used by
+    # stream j % S (n_out is a multiple of S), so the steps that share buffers stay in order.
+    S = max(1, min(int(args.streams), 8))
+    side = [torch.cuda.Stream() for _ in range(S)] if S > 1 else []
+    n_out = S * max(1, -(-min(n_buf, 4) // S))
     bufs = [binding.alloc_buffers(xd[0], keep, M, bits) for _ in range(n_out)]
     ys = [torch.empty_like(xd[0]) for _ in range(n_out)]
 
@@ -202,36 +215,60 @@ def main() -> int:
     e_enc = [(ev.create(), ev.create()) for _ in range(K)]
     e_dec = [(ev.create(), ev.create()) for _ in range(K)]
 
-    def step(i: int, timed_idx: int | None):
+    def step(i: int, timed_idx: int | None, multi: bool = False):
         x = xd[i % n_buf]
         sb, meta, ws = bufs[i % n_out]
+        st = side[i % S] if (multi and S > 1) else None      # None: the current stream
         if timed_idx is not None:
             binding.slicer_profile_events(*e_enc[timed_idx])
-        encode(x, sb, meta, ws)
+        encode(x, sb, meta, ws, st)
         if timed_idx is not None:
             binding.slicer_profile_events(*e_dec[timed_idx])
-        binding.slicer_decode_as(sb, meta, ys[i % n_out], M)
+        binding.slicer_decode_as(sb, meta, ys[i % n_out], M, stream=st)
+
+    def fork():                                   # the side streams start after everything queued on the current one
+        cur = torch.cuda.current_stream()
+        for sd in side:
+            sd.wait_stream(cur)
+
+    def join():
+        cur = torch.cuda.current_stream()
+        for sd in side:
+            cur.wait_stream(sd)
 
     for i in range(max(W, n_buf)):               # every kernel is loaded and every buffer touched before a capture
         step(i, None)
     torch.cuda.synchronize()
 
+    # single stream, plain launches: the figure without any overlap between steps (reported beside `value`)
+    t0 = time.perf_counter()
+    for i in range(K):
+        step(W + i, None)
+    torch.cuda.synchronize()
+    single_ms = (time.perf_counter() - t0) * 1e3 / K
+
     # The launch-bound part of a step (four short kernels back to back) is captured once into a
-    # HIP graph of n_buf consecutive steps and replayed; every replay is checked against the
-    # plain launches.  Anything wrong with capture or replay falls back to plain launches.
-    graph, launch = None, "eager"
-    if not args.eager:
+    # HIP graph of n_cap consecutive steps (over the S streams: fork, steps, join) and replayed;
+    # every replay is checked against the plain launches.  Anything wrong with capture or replay
+    # falls back to plain launches.
+    n_cap = max(n_buf, n_out)
+    graph, launch = None, "plain launches"
+    # (with several streams the launch gaps of one step are filled by its neighbours, and plain launches
+    #  overlap better than a replayed graph, whose fork and join drain the device every n_cap steps)
+    if not args.eager and S == 1:
         try:
             def snapshot():
                 torch.cuda.synchronize()
                 return [(b[0].clone(), b[1].clone(), y.clone()) for b, y in zip(bufs, ys)]
-            for i in range(n_buf):
+            for i in range(n_cap):
                 step(i, None)
             want = snapshot()
             g = torch.cuda.CUDAGraph()
             with torch.cuda.graph(g):
-                for i in range(n_buf):
-                    step(i, None)
+                fork()
+                for i in range(n_cap):
+                    step(i, None, multi=True)
+                join()
             ok = True
             for _ in range(3):
                 for b, y in zip(bufs, ys):
@@ -245,7 +282,7 @@ def main() -> int:
                     ok = ok and torch.equal(m0[:meta_b], m1[:meta_b]) and torch.equal(y0, y1) \
                         and torch.equal(s0.view(torch.int32)[:nw], s1.view(torch.int32)[:nw])
             if ok:
-                graph, launch = g, f"hipGraph of {n_buf} steps"
+                graph, launch = g, f"hipGraph of {n_cap} steps"
             else:
                 print("bench.py: graph replay differs from plain launches; timing plain launches", file=sys.stderr)
         except Exception as e:                   # capture unsupported: plain launches
@@ -253,18 +290,30 @@ def main() -> int:
             graph = None
     torch.cuda.synchronize()
 
+    if S > 1:                                      # the side streams' first launches create their queues: not timed
+        fork()
+        for i in range(max(W, 2 * S)):
+            step(i, None, multi=True)
+        join()
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
     if graph is not None:
-        for _ in range(K // n_buf):
+        for _ in range(K // n_cap):
             graph.replay()
-        for i in range(K - K % n_buf, K):
-            step(i, None)
+        if K % n_cap:
+            fork()
+            for i in range(K - K % n_cap, K):
+                step(i, None, multi=True)
+            join()
     else:
+        fork()
         for i in range(K):
-            step(W + i, None)
+            step(W + i, None, multi=True)
+        join()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / K
+    launch += f", steps alternate over {S} streams" if S > 1 else ", one stream"
 
     # kernel durations: the same K steps with HIP events around the dominant kernels
     for i in range(K):
@@ -364,6 +413,8 @@ def main() -> int:
                    "frac_hbm_peak": in_bytes / (dec_call_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
         "bits_per_element": bpe, "bit_split": bit_split, "stream_words": words, "meta_bytes": meta_bytes,
         "step_latency_us": lat,
+        "single_stream": {"ms_per_step": single_ms, "value": in_bytes / (single_ms * 1e-3) / 1e9,
+                          "note": "the same steps on one stream, plain launches: no overlap between steps"},
         "roofline": roofline,
         "cpu_baseline": cpu,
     }

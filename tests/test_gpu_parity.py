@@ -312,6 +312,38 @@ def test_asymmetric_thresholds_wide_range(oracle, dtype, N):
         check_atkf(oracle, x, dtype, keep, lam, M, M, B28, 1e-3)
 
 
+def test_concurrent_calls_on_three_streams(oracle):
+    """Independent batches encoded and decoded on three streams at once (each call with buffers of its
+    own, as the benchmark does): every result is the oracle's, whatever the overlap."""
+    import torch
+    from paper_2511_11608_amd import binding
+    from paper_2511_11608_amd.devmem import to_device, to_host
+    wls = [synth.llm_prefill(seed=11 + i, rows=700) for i in range(3)] + [synth.vit_tokens(seed=21 + i, rows=500) for i in range(3)]
+    refs = []
+    for wl in wls:
+        s_ref, m_ref = oracle.encode(wl.x, wl.dtype, wl.keep_ratio, wl.n_blocks, wl.bit_set, wl.budget, n_threads=8)
+        refs.append((s_ref, m_ref, oracle.decode(s_ref, m_ref, n_threads=8)))
+    xs = [to_device(wl.x, wl.dtype) for wl in wls]
+    bufs = [binding.alloc_buffers(x, wl.keep_ratio, wl.n_blocks, wl.bit_set) for x, wl in zip(xs, wls)]
+    ys = [torch.empty_like(x) for x in xs]
+    streams = [torch.cuda.Stream() for _ in range(3)]
+    torch.cuda.synchronize()
+    for rep in range(4):
+        for b, y in zip(bufs, ys):
+            b[0].fill_(-1); b[1].fill_(0xFF); y.fill_(3.0)
+        torch.cuda.synchronize()
+        for i, (wl, x, (sb, meta, ws), y) in enumerate(zip(wls, xs, bufs, ys)):
+            st = streams[i % 3]
+            binding.slicer_encode(x, wl.keep_ratio, wl.n_blocks, wl.bit_set, wl.budget, sb, meta, ws, stream=st)
+            binding.slicer_decode_as(sb, meta, y, wl.n_blocks, stream=st)
+        torch.cuda.synchronize()
+        for wl, (sb, meta, ws), y, (s_ref, m_ref, y_ref) in zip(wls, bufs, ys, refs):
+            assert np.array_equal(meta.cpu().numpy(), m_ref)
+            assert np.array_equal(sb[:s_ref.size].cpu().numpy().view(np.uint32), s_ref)
+            yv = np.uint32 if wl.dtype == "f32" else np.uint16
+            assert np.array_equal(to_host(y).view(yv), y_ref.view(yv))
+
+
 def test_encode_is_deterministic():
     from tests.gpu_util import gpu_roundtrip
     wl = synth.llm_prefill(seed=3, rows=64)
