@@ -757,6 +757,7 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
     comp_t tx[kRegThr];
 #pragma unroll
     for (int j = 0; j < kRegThr; ++j) tx[j] = j < ntg ? thr[j] : (comp_t)0;
+    const bool tree8 = DT == 1 && M == 8 && Mn == 8;      // (one-word comps: a select is one instruction)
 #pragma unroll(MAXS ? MAXS : 1)
     for (int s = 0; s < SLN; ++s) {
         if (s >= nslots) break;
@@ -767,10 +768,26 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
             const comp_t cx = ent_cx(s);
             if ((cx & ~kClsBit) >= thrK) {
                 kept = true;
-                u32 above = (cx & kClsBit) ? 0u : 1u;
+                u32 above;
+                if (tree8) {
+                    // 8 + 8 blocks: the 14 boundaries and the class bit are 15 separators in descending
+                    // order; four compares walk them as a binary tree (the first is the class bit itself)
+                    const bool c1 = !(cx & kClsBit);
+                    comp_t m = c1 ? tx[10] : tx[3];
+                    const bool c2 = m > cx;
+                    m = c1 ? (c2 ? tx[12] : tx[8]) : (c2 ? tx[5] : tx[1]);
+                    const bool c3 = m > cx;
+                    const comp_t lo4 = c3 ? (c2 ? tx[6] : tx[2]) : (c2 ? tx[4] : tx[0]);
+                    const comp_t hi4 = c3 ? (c2 ? tx[13] : tx[9]) : (c2 ? tx[11] : tx[7]);
+                    m = c1 ? hi4 : lo4;
+                    const bool c4 = m > cx;
+                    above = (c1 ? 8u : 0u) + (c2 ? 4u : 0u) + (c3 ? 2u : 0u) + (c4 ? 1u : 0u);
+                } else {
+                    above = (cx & kClsBit) ? 0u : 1u;
 #pragma unroll
-                for (int j = 0; j < kRegThr; ++j) above += tx[j] > cx ? 1u : 0u;
-                for (int j = kRegThr; j < ntg; ++j) above += thr[j] > cx ? 1u : 0u;
+                    for (int j = 0; j < kRegThr; ++j) above += tx[j] > cx ? 1u : 0u;
+                    for (int j = kRegThr; j < ntg; ++j) above += thr[j] > cx ? 1u : 0u;
+                }
                 b = above;
                 key = cx_key(cx);
                 idx = cx_idx(cx);
