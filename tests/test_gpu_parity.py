@@ -312,6 +312,26 @@ def test_asymmetric_thresholds_wide_range(oracle, dtype, N):
         check_atkf(oracle, x, dtype, keep, lam, M, M, B28, 1e-3)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_asymmetric_thresholds_random_parameters(oracle, dtype):
+    """Random row lengths, keep ratios, asymmetry factors, block counts and value scales; few-valued rows
+    make long runs of equal keys at both selections (the cut of the ties in index order)."""
+    rng = np.random.default_rng(321)
+    for it in range(16):
+        rows = int(rng.integers(1, 9))
+        N = int(rng.integers(1, 400)) * 8 if it % 2 == 0 else int(rng.integers(1, 3000))
+        x = rng.standard_normal((rows, N)).astype(np.float32) * np.float32(10.0 ** rng.integers(-3, 4))
+        if it % 3 == 0:
+            x = np.round(x * np.float32(2.0 / max(1e-30, float(np.abs(x).max())))) * np.float32(0.5)     # a handful of distinct values
+        x[rng.random((rows, N)) < rng.random() * 0.8] = 0
+        if dtype == "bf16":
+            x = synth.f32_to_bf16_bits(x)
+        keep = float(rng.random())
+        lam = float(rng.random() * 0.98 + 0.01)
+        Mp, Mn = int(rng.integers(1, 12)), int(rng.integers(1, 12))
+        check_atkf(oracle, x, dtype, keep, lam, Mp, Mn, B28, float(10.0 ** rng.uniform(-5, -2)))
+
+
 def test_concurrent_calls_on_three_streams(oracle):
     """Independent batches encoded and decoded on three streams at once (each call with buffers of its
     own, as the benchmark does): every result is the oracle's, whatever the overlap."""
