@@ -151,8 +151,8 @@ int slicer_check_pn(const void* meta, uint64_t stream_words, slicer_dtype dt, in
                     void* hip_stream);
 
 /*
- * Encode with the paper's own guard (Sec. 3.2.1, Eq. "DS", "greedily lowers the bit precision q
- * from an initial maximum q_bit until a user-defined distortion threshold delta is met"):
+ * Encode with the paper's own guard (Sec. 3.2.1, Eq. "DS" and the greedy search stated under it:
+ * start at the largest bitwidth q_bit and step down while the mismatch stays within delta):
  * with q_bit = max(bit_set) and c(q) the block's AIQ codes at q bits,
  *     DS(q) = (1/n) * sum | floor(c(q_bit) / 2^(q_bit - q)) - c(q) |,
  * a block's bitwidth goes down through bit_set in descending order while DS(q) <= delta and
@@ -165,8 +165,8 @@ int slicer_encode_ds(const void* x, slicer_dtype dt, int64_t rows, int64_t row_l
                      void* stream, void* meta, void* workspace, void* hip_stream);
 
 /*
- * Fixed multi-level mode (Sec. 4.1: "multi-level quantization Q = [q_1, ..., q_M] ... with
- * q_1 > ... > q_M bits assigned in descending order of activation magnitude"): block m of
+ * Fixed multi-level mode (Sec. 4.1, the list Q = [q_1, ..., q_M] of the experiments: one
+ * bitwidth per block, the widest for the largest magnitudes): block m of
  * either sign class (block 0 = largest magnitudes) is quantised with ladder[m] bits; there
  * is no bitwidth search and no distortion guard, everything else is slicer_encode.
  *   ladder   HOST pointer, n_blocks entries, each 1..16 (any order is accepted; it is read

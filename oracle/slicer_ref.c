@@ -22,10 +22,14 @@
  *     min(r / K, M-1) (all to block M-1 when K = 0), so blocks 0..M-2 hold
  *     exactly K and the last block takes the remainder.
  *  5. AIQ (Sec. 3.2.1): per block affine min/max quantiser at q bits,
- *     L = 2^q - 1: inv = L / rng, y = (a - vmin) * inv, c = clamp(rint(y), 0, L),
+ *     L = 2^q - 1, taken on the block's own scale so that it behaves the same for
+ *     tensors of any magnitude: with er = ilogb(rng), rng1 = rng * 2^-er in [1, 2),
+ *     inv = L / rng1, y = ((a - vmin) * 2^-er) * inv, c = clamp(rint(y), 0, L),
  *     reconstruction vmin + c * (rng / L).  (Zero-point folded into vmin; the
- *     printed ceil is read as round-to-nearest-even.)  A block whose range is
- *     below 2^-100 is sent as its minimum (all codes 0).
+ *     printed ceil is read as round-to-nearest-even; the two power-of-two scalings
+ *     are exact, so y is (a - vmin) * (L / rng) whenever that quotient is an
+ *     ordinary fp32 number.)  Only a block of range exactly 0 is degenerate: it is
+ *     sent as its minimum (all codes 0).
  *  6. ABQ (Sec. 3.2.1 "rate-distortion solver"): smallest q in bit_set whose
  *     distortion is within the budget: sum (a - a~)^2 <= beta * sum a^2 per
  *     block, both sums taken on integer grids so they do not depend on the
@@ -200,11 +204,17 @@ typedef struct {
     uint32_t n_pos, n_neg;
 } row_result;
 
-/* AIQ code of value a in a block [vmin, vmin+rng] at L = 2^q - 1 levels; also
- * returns the scaled position y. */
-static uint32_t aiq_code(float a, float vmin, float inv, float L, float* y_out)
+/* The quantiser works on the block's own scale (Sec. 3.2.1 defines the step o = range / (2^q - 1)
+ * for any non-zero range): er = ilogb(range), and both the range and every offset a - vmin are
+ * multiplied by 2^-er, which is exact. */
+static int range_exp(float rng) { return ilogbf(rng); }
+static float unit_range(float rng, int er) { return ldexpf(rng, -er); }   /* in [1, 2) */
+
+/* AIQ code of value a in a block [vmin, vmin+rng] at L = 2^q - 1 levels, inv = L / unit_range;
+ * also returns the scaled position y. */
+static uint32_t aiq_code(float a, float vmin, int er, float inv, float L, float* y_out)
 {
-    float y = (a - vmin) * inv;
+    float y = ldexpf(a - vmin, -er) * inv;
     float r = rintf(y);
     if (r < 0.0f) r = 0.0f;
     if (r > L) r = L;
@@ -217,23 +227,25 @@ static uint32_t aiq_code(float a, float vmin, float inv, float L, float* y_out)
 static int ds_greedy(const kv_t* el, uint32_t cnt, uint32_t bit_set, double delta,
                      float vmin, float rng, int degenerate, uint64_t* ds_sum)
 {
+    const int er = degenerate ? 0 : range_exp(rng);
+    const float rng1 = degenerate ? 1.0f : unit_range(rng, er);
     const int qbit = max_bit(bit_set);
     uint32_t* c0 = (uint32_t*)malloc(sizeof(uint32_t) * (size_t)cnt);
     const float L0 = (float)((1u << qbit) - 1u);
-    const float inv0 = degenerate ? 0.0f : L0 / rng;
+    const float inv0 = degenerate ? 0.0f : L0 / rng1;
     for (uint32_t j = 0; j < cnt; ++j) {
         float y;
-        c0[j] = degenerate ? 0u : aiq_code(bits_to_float(el[j].key), vmin, inv0, L0, &y);
+        c0[j] = degenerate ? 0u : aiq_code(bits_to_float(el[j].key), vmin, er, inv0, L0, &y);
     }
     int chosen = qbit;
     for (int q = qbit - 1; q >= 1; --q) {
         if (!((bit_set >> q) & 1u)) continue;
         const float L = (float)((1u << q) - 1u);
-        const float inv = degenerate ? 0.0f : L / rng;
+        const float inv = degenerate ? 0.0f : L / rng1;
         uint64_t D = 0;
         for (uint32_t j = 0; j < cnt; ++j) {
             float y;
-            uint32_t c = degenerate ? 0u : aiq_code(bits_to_float(el[j].key), vmin, inv, L, &y);
+            uint32_t c = degenerate ? 0u : aiq_code(bits_to_float(el[j].key), vmin, er, inv, L, &y);
             uint32_t ref = c0[j] >> (qbit - q);
             D += ref > c ? ref - c : c - ref;
         }
@@ -271,7 +283,9 @@ static void quantise_block(const kv_t* el, uint32_t cnt, uint32_t bit_set, doubl
     if (out->e_int) out->e_int[b] = E;
     if (out->e_exp) out->e_exp[b] = e;
 
-    int degenerate = !(rng >= 0x1p-100f);
+    int degenerate = !(rng > 0.0f);
+    const int er = degenerate ? 0 : range_exp(rng);
+    const float rng1 = degenerate ? 1.0f : unit_range(rng, er);
     int chosen = fixed_q > 0 ? fixed_q : -1;
     if (fixed_q < 0)
         chosen = ds_greedy(el, cnt, bit_set, beta, vmin, rng, degenerate,
@@ -284,11 +298,11 @@ static void quantise_block(const kv_t* el, uint32_t cnt, uint32_t bit_set, doubl
         float o = 0.0f;
         if (!degenerate) {
             o = rng / L;
-            float inv = L / rng;
+            float inv = L / rng1;
             for (uint32_t j = 0; j < cnt; ++j) {
                 float a = bits_to_float(el[j].key);
                 float y;
-                uint32_t c = aiq_code(a, vmin, inv, L, &y);
+                uint32_t c = aiq_code(a, vmin, er, inv, L, &y);
                 int64_t rho = (int64_t)rintf((y - (float)c) * 32768.0f);
                 S += (uint64_t)(rho * rho);
             }
@@ -314,12 +328,12 @@ static void quantise_block(const kv_t* el, uint32_t cnt, uint32_t bit_set, doubl
 
     /* codes at the chosen bitwidth */
     float L = (float)((1u << q) - 1u);
-    float inv = degenerate ? 0.0f : L / rng;
+    float inv = degenerate ? 0.0f : L / rng1;
     for (uint32_t j = 0; j < cnt; ++j) {
         uint32_t c = 0;
         if (!degenerate) {
             float y;
-            c = aiq_code(bits_to_float(el[j].key), vmin, inv, L, &y);
+            c = aiq_code(bits_to_float(el[j].key), vmin, er, inv, L, &y);
         }
         out->code_of[el[j].idx] = c;
     }
@@ -542,6 +556,9 @@ static int encode_common(const void* x, int dt, int64_t R, int64_t N, double kee
         seg[r] = (uint32_t*)calloc((size_t)(cap_words > 0 ? cap_words : 1), 4);
         const void* xr = (const char*)x + (size_t)r * (size_t)N * esz;
         if (analyze_row(xr, dt, N, k, M, Mn, bit_set, beta, ladder, ds, lambda, &rr) != 0) {
+#ifdef _OPENMP
+#pragma omp atomic write
+#endif
             fail = 1;
         } else {
             seg_words[r] = pack_row(&rr, N, B2, w, seg[r], idxbuf);

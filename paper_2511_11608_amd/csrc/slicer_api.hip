@@ -178,11 +178,7 @@ template <int DT>
 int launch_small(const SmallArgs& sa, const Plan& p, hipStream_t st, bool asym)
 {
     constexpr int E0 = DT == 0 ? 4 : 16;      // smallest instantiated elements-per-lane
-#ifdef SLICER_LDS_PAD
-    const int lds = p.small_lds_bytes + SLICER_LDS_PAD;     // development builds: occupancy experiments
-#else
     const int lds = p.small_lds_bytes;
-#endif
     if (p.small_epl <= E0) launch_small_epl<DT, E0>(sa, lds, p.small_maxs, st, asym);
     else if (p.small_epl == E0 * 2) launch_small_epl<DT, E0 * 2>(sa, lds, p.small_maxs, st, asym);
     else if (p.small_epl == E0 * 4) launch_small_epl<DT, E0 * 4>(sa, lds, p.small_maxs, st, asym);
@@ -613,17 +609,6 @@ int slicer_profile_events(void* start_event, void* stop_event)
     g_ev_stop = (hipEvent_t)stop_event;
     return SLICER_OK;
 }
-
-#ifdef SLICER_PHASE_TIMING
-// development builds only: read and clear the per-phase cycle table of the row-resident encoder
-int slicer_debug_phase_cycles(unsigned long long* out16)
-{
-    unsigned long long zero[16] = {0};
-    SLICER_HIP(hipMemcpyFromSymbol(out16, HIP_SYMBOL(g_phase_cycles), sizeof(zero)));
-    SLICER_HIP(hipMemcpyToSymbol(HIP_SYMBOL(g_phase_cycles), zero, sizeof(zero)));
-    return SLICER_OK;
-}
-#endif
 
 int slicer_last_hip_error(void) { return g_last_hip_error; }
 

@@ -247,7 +247,7 @@ __device__ inline u32 read_bits_lds(const u32* words, u32 bitpos, u32 nbits)
 }
 
 template <int DT>
-__global__ __launch_bounds__(256) void dec_small_kernel(DecArgs a)
+__global__ __launch_bounds__(kWave) void dec_small_kernel(DecArgs a)
 {
     typedef typename Elem<DT>::raw_t raw_t;
     constexpr int ESZ = DT == 0 ? 4 : 2;

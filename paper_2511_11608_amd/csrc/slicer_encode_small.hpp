@@ -56,30 +56,6 @@ constexpr int kCoarseBits = 11;
 constexpr int kCoarseBins = 1 << kCoarseBits;
 constexpr int kFineBins = 1024;
 
-// Development builds only.  -DSLICER_PHASE_TIMING: lane 0 of every wave adds the cycles since
-// the previous mark to a global table.  -DSLICER_STOP_AFTER=i: leave the kernel after mark i
-// with an empty row (instruction and time accounting of the phases up to that mark; the
-// output is NOT a valid stream).
-#ifdef SLICER_PHASE_TIMING
-__device__ unsigned long long g_phase_cycles[16];
-#define SLICER_PT(i)                                                              \
-    do {                                                                          \
-        const long long t_now_ = clock64();                                       \
-        if (lane == 0) atomicAdd(&g_phase_cycles[i], (unsigned long long)(t_now_ - t_prev_)); \
-        t_prev_ = clock64();                                                      \
-    } while (0)
-#elif defined(SLICER_STOP_AFTER)
-#define SLICER_PT(i)                                                              \
-    do {                                                                          \
-        if ((i) == SLICER_STOP_AFTER) {                                           \
-            if (lane == 0) { a.row_words[r] = 0; a.mv.n_pos[r] = 0; a.mv.n_neg[r] = 0; a.fallback[r] = 0u; } \
-            return;                                                               \
-        }                                                                         \
-    } while (0)
-#else
-#define SLICER_PT(i) do { } while (0)
-#endif
-
 // LDS carve-up of one wave (word offsets); small_lds_words() on the host must match.
 // The coarse histogram (2048 words) overlays everything: nothing else is live before the
 // compaction.  Region 0 is the fine histogram first; once the boundaries are known it holds
@@ -176,9 +152,6 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
     extern __shared__ u32 smem[];
 
     const u32 lane = lane_id();
-#ifdef SLICER_PHASE_TIMING
-    long long t_prev_ = clock64();
-#endif
     const int64_t r = xcd_row((int64_t)blockIdx.x, a.R);        // neighbouring rows stay on one XCD
     if (r >= a.R) return;
     const int N = (int)a.N, M = a.M, Mn = a.Mn, w = a.w, B2 = a.M + a.Mn, nq = NQ ? NQ : a.nq, cap = a.cap;
@@ -404,7 +377,6 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
         return;
     }
 
-    SLICER_PT(0);
     // ---- 2. ordered compaction into L -------------------------------------------------
     u32 nL = 0;
     if (k > 0) {
@@ -538,7 +510,6 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
     }
     wave_sync();
 
-    SLICER_PT(1);
     // ---- 3. fine bins ---------------------------------------------------------------------
     // 1024 bins, linear in (key - t_lo) >> sh; sh from the top of the highest occupied coarse
     // bin.  fp32 keeps the in-bin key bits, the inverted index and the class in one word of S.
@@ -631,7 +602,6 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
         return (comp_t)(s ^ 0x80000000u);
     };
 
-    SLICER_PT(2);
     // ---- top-K cut: the comp of overall rank k-1 (ATKF) -----------------------------------------
     comp_t thrK = 0;                                // plain comp; every entry of L is kept when nL <= k
     if (nL > (u32)k) {
@@ -667,7 +637,6 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
     const u32 n = n_pos + n_neg;
     const u32 Kc[2] = { n_pos / (u32)M, n_neg / (u32)Mn };
 
-    SLICER_PT(3);
     // ---- block boundaries: comps of class ranks j*K-1, one lane per boundary ------------------------
     // M-1 boundaries for the positive class, then Mn-1 for the negative one.  A class with fewer than M members has
     // K = 0 and every member in its last block: its boundaries sit above every comp of the class.
@@ -742,7 +711,6 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
     if (lane == 0) L.blk_start[B2] = n;
     wave_sync();
 
-    SLICER_PT(4);
     // ---- 4. blocks, stable split by block, block-ordered arrays -----------------------------------
     // S and the fine bins are dead (boundaries are resolved): S's storage takes the
     // block-ordered values, the histogram region the indices and the stream image
@@ -818,7 +786,6 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
         wave_sync();
     }
 
-    SLICER_PT(5);
     // ---- 5. ABQ -----------------------------------------------------------------------------------
     // Each block is walked by kWave / B2 lanes, each lane a contiguous run of the block-ordered
     // list, so a lane's quantiser constants and partial sums live in registers.
@@ -1000,7 +967,6 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
     for (u32 i = lane; i < row_words; i += kWave) stage[i] = 0;
     wave_sync();
 
-    SLICER_PT(6);
     // ---- packing ----------------------------------------------------------------------------------
     {
         for (u32 i = 0; i < T; ++i) {
@@ -1025,7 +991,6 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
         }
     }
     wave_sync();
-    SLICER_PT(7);
     u32* __restrict__ slot = a.slots + (size_t)r * (size_t)a.cap_words;
     for (u32 i = lane; i < row_words; i += kWave) slot[i] = stage[i];
     if (lane == 0) {

@@ -200,10 +200,48 @@ def test_degenerate_blocks(oracle):
     assert np.array_equal(oracle.decode(s, m)[0], a)
     # empty class: its blocks carry q = min(bit_set), range 0
     assert int(r["qb"][1]) == 3 and r["vmin"][1] == 0 and r["vmax"][1] == 0
-    # denormal-width block collapses to its minimum (documented reading)
-    a = np.array([1e-41, 2e-41, 3e-41], np.float32)
-    r = oracle.analyze_row(a, "f32", 1.0, 1, bits_of([2, 8]), 0.0)
-    assert int(r["qb"][0]) == 2 and not r["code_of"].any()
+    # only a range of exactly 0 is degenerate: a block of denormals is quantised like its scaled copy
+    # (y = 0, 1.5, 3 at two bits: code 2 by round-half-even with residual 1/2, so budget 0 is missed at
+    # every bitwidth and the largest is flagged)
+    for sc in (0, -100, -140):
+        a = np.ldexp(np.array([1.0, 2.0, 3.0], np.float32), sc).astype(np.float32)
+        r = oracle.analyze_row(a, "f32", 1.0, 1, bits_of([2, 8]), 0.0)
+        assert int(r["qb"][0]) == (8 | 0x80) and r["code_of"].tolist() == [0, 128, 255]
+        r = oracle.analyze_row(a, "f32", 1.0, 1, bits_of([2]), 1.0)
+        assert int(r["qb"][0]) == 2 and r["code_of"].tolist() == [0, 2, 3]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_codec_is_scale_invariant(oracle, dtype):
+    """Sec. 3.2.1 defines the step o = (vmax - vmin) / (2^q - 1) for any block, so a tensor multiplied by
+    a power of two (an exact operation) must give the same kept set, blocks, bitwidths and codes, and
+    a reconstruction inside the same relative budget - down to magnitudes around 1e-33, where fp32 is
+    still normal.  (A quantiser scale L / range evaluated without rescaling overflows there.)"""
+    wl = synth.vit_tokens(seed=12, rows=3) if dtype == "f32" else synth.llm_prefill(seed=12, rows=3)
+    xf = f32(wl.x, dtype)
+    M = wl.n_blocks
+    base = None
+    for sc in (0, 40, -66, -100, -110):
+        xs = np.ldexp(xf, sc).astype(np.float32)
+        assert np.array_equal(np.ldexp(xs, -sc), xf)                     # the scaling lost nothing
+        row_in = xs if dtype == "f32" else synth.f32_to_bf16_bits(xs)
+        s, m = oracle.encode(row_in, dtype, wl.keep_ratio, M, wl.bit_set, wl.budget)
+        a = streamfmt.arrays(m)
+        y = f32(oracle.decode(s, m), dtype).astype(np.float64)
+        view = (s.tolist(), a["q"].tolist(), a["n_pos"].tolist(), a["n_neg"].tolist(),
+                np.ldexp(a["vmin"], -sc).tolist(), np.ldexp(a["vmax"], -sc).tolist())
+        if base is None:
+            base = view
+        assert view == base, sc
+        for r in range(wl.rows):
+            ar = oracle.analyze_row(row_in[r], dtype, wl.keep_ratio, M, wl.bit_set, wl.budget)
+            for b in range(2 * M):
+                sel = ar["block_of"] == b
+                if sel.any() and not (int(ar["qb"][b]) & 0x80):
+                    e = np.sum((xs[r][sel].astype(np.float64) - y[r][sel]) ** 2)
+                    en = np.sum(xs[r][sel].astype(np.float64) ** 2)
+                    tol = (2.0 ** -8) ** 2 if dtype == "bf16" else 0.0
+                    assert e <= (wl.budget * (1 + 2.0 ** -9) + tol) * en, (sc, r, b)
 
 
 # ----------------------------------------------------------------------------
@@ -412,6 +450,96 @@ def test_decode_is_two_fp32_roundings(oracle):
             sign = -1.0 if b >= wl.n_blocks else 1.0
             assert np.array_equal(y[r][idx], (sign * want).astype(np.float32))
     assert n_diff_fma > 0      # the sample does tell a fused multiply-add apart
+
+
+def bf16_rne_by_definition(v64: np.ndarray) -> np.ndarray:
+    """Round exact values (held in fp64) to bf16, nearest with ties to the even significand, from the
+    definition: the two bf16 neighbours are found by clearing / bumping the low 16 bits of the fp32
+    pattern of a value that is already an fp32 number; the nearer one wins by exact fp64 distance."""
+    v32 = v64.astype(np.float32)
+    assert np.array_equal(v32.astype(np.float64), v64)          # inputs are fp32 numbers
+    bits = v32.view(np.uint32)
+    lo = bits & np.uint32(0xFFFF0000)
+    hi = lo + np.uint32(0x10000)
+    flo, fhi = lo.view(np.float32).astype(np.float64), hi.view(np.float32).astype(np.float64)
+    dlo, dhi = np.abs(v64 - flo), np.abs(fhi - v64)
+    lo_even = ((lo >> np.uint32(16)) & np.uint32(1)) == 0
+    take_lo = (dlo < dhi) | ((dlo == dhi) & lo_even)
+    return np.where(take_lo, lo, hi).view(np.float32)
+
+
+def test_decode_bf16_rounds_half_to_even(oracle):
+    """Eq. dequnt for bf16 tensors: a~ = RN_bf16(RN32(vmin + RN32(c * o))).  Two hand-built blocks put a
+    reconstruction exactly half-way between two bf16 numbers (in [1, 2) they are 2/256 apart):
+      {251, 256, 260}/256 at two bits: range 9/256, step 3/256, y(256/256) = 5/3 -> code 2 ->
+        257/256, a tie whose lower neighbour 256/256 has an even significand: stays 256/256
+        (round-half-up would give 258/256);
+      {253, 258, 262}/256: y(258/256) = 5/3 -> code 2 -> 259/256, a tie whose lower neighbour 258/256
+        has an odd significand: goes to 260/256 (truncation would give 258/256)."""
+    for vals, want in (((251, 256, 260), (251, 256, 260)), ((253, 258, 262), (253, 260, 262))):
+        x = synth.f32_to_bf16_bits(np.array([vals], np.float32) / np.float32(256))
+        assert np.array_equal(synth.bf16_bits_to_f32(x) * 256, np.array([vals], np.float32))   # bf16 numbers
+        s, m = oracle.encode(x, "bf16", 1.0, 1, 1 << 2, 1.0)
+        assert [c for _, cod in streamfmt.parse_row(s, m, 0)["blocks"] for c in cod] == [0, 2, 3]
+        y = synth.bf16_bits_to_f32(oracle.decode(s, m))
+        assert (y[0] * 256).tolist() == list(want)
+    # the same rule on a workload, against the definition (every step rounded once from exact fp64 values)
+    wl = synth.llm_prefill(seed=21, rows=24)
+    s, m = oracle.encode(wl.x, "bf16", wl.keep_ratio, wl.n_blocks, wl.bit_set, wl.budget)
+    y = synth.bf16_bits_to_f32(oracle.decode(s, m))
+    a = streamfmt.arrays(m)
+    n_inexact = 0
+    for r in range(wl.rows):
+        p = streamfmt.parse_row(s, m, r)
+        for b, (idx, cod) in enumerate(p["blocks"]):
+            if not idx:
+                continue
+            L = (1 << (int(a["q"][r, b]) & 0x7F)) - 1
+            vmin, vmax = np.float64(a["vmin"][r, b]), np.float64(a["vmax"][r, b])
+            o = np.float32(np.float64(np.float32(vmax - vmin)) / L)
+            prod = np.float32(np.float64(o) * np.array(cod, np.float64))
+            a32 = np.float32(vmin + prod.astype(np.float64))
+            want = bf16_rne_by_definition(a32.astype(np.float64))
+            n_inexact += int(np.count_nonzero(want != a32))
+            sign = -1.0 if b >= wl.n_blocks else 1.0
+            assert np.array_equal(y[r][idx], (sign * want).astype(np.float32))
+    assert n_inexact > 100     # the narrowing did round
+
+
+def test_aiq_scale_is_levels_over_range_not_reciprocal_step(oracle):
+    """Sec. 3.2.1 prints v/o; the reading taken here is y = (a - vmin) * RN(L / range) (one division per
+    block).  The two differ on the block {1, 1 + 37/128, 1 + 37/64} at two bits: the middle value sits
+    exactly half-way (y = 3/2 in exact arithmetic).  range = 37/64 = (37/32) / 2 and RN32(3 / (37/32)) =
+    RN32(96/37) = 5441259 * 2^-21 lies BELOW 96/37; the exact product (37/64) * 5441259 * 2^-21 is
+    3/2 - 9 * 2^-27, more than half an fp32 step (8 * 2^-27) below 3/2, so y = 3/2 - 2^-23 and the code
+    is 1; dividing by the step RN32((37/64)/3) gives exactly 3/2, which round-half-even would send to 2."""
+    from fractions import Fraction
+    inv = np.float32(3.0) / np.float32(37 / 32)
+    assert Fraction(float(inv)) == Fraction(5441259, 2 ** 21) < Fraction(96, 37)      # rounded down
+    assert Fraction(37, 64) * Fraction(5441259, 2 ** 21) == Fraction(3, 2) - Fraction(9, 2 ** 27)
+    y = np.float32(37 / 64) * inv
+    assert Fraction(float(y)) == Fraction(3, 2) - Fraction(1, 2 ** 23)                 # below the tie
+    assert np.float32(37 / 128) / (np.float32(37 / 64) / np.float32(3.0)) == np.float32(1.5)
+    a = np.array([1.0, 1.0 + 37 / 128, 1.0 + 37 / 64], np.float32)
+    r = oracle.analyze_row(a, "f32", 1.0, 1, 1 << 2, 1.0)
+    assert r["code_of"].tolist() == [0, 1, 3]
+
+
+def test_atkf_shifted_threshold_is_one_fp32_product(oracle):
+    """Sec. 3.1: tau+ = (1 + lambda) tau, taken as one fp32 multiplication of RN32(1 + RN32(lambda)) and tau.
+    lambda = 0.1: 1 + lambda = 9227469 * 2^-23; tau = 1 + 5 * 2^-23 gives the exact product
+    (9227469 + 5.5000001...) * 2^-23, which rounds UP to x = 9227475 * 2^-23.  A positive element equal
+    to x is not above tau+ (and lies in (tau, tau+], so it is never sent); with the product kept in
+    double it would be strictly retained."""
+    u = 2.0 ** -23
+    tau = np.float32(1 + 5 * u)
+    one_plus = np.float32(1) + np.float32(0.1)
+    assert float(one_plus) == 9227469 * u
+    xq = one_plus * tau                                      # fp32 product
+    assert float(xq) == 9227475 * u and float(one_plus) * float(tau) < float(xq)
+    row = np.array([xq, -2 * tau, -tau, 0.5 * tau, 0.4 * tau, 0.3 * tau], np.float32)
+    a = oracle.analyze_row_atkf(row, "f32", 0.5, 0.1, 1, B28, 1e-3)      # k = 3, tau = third largest magnitude
+    assert np.nonzero(a["block_of"] >= 0)[0].tolist() == [1, 2, 3]          # strict: the two negatives; fill: 0.5 tau
 
 
 # ----------------------------------------------------------------------------
