@@ -167,6 +167,13 @@ __device__ inline u32 energy_grid(u32 bits, int e)
     return q;
 }
 
+// The quantiser of Sec. 3.2.1 works on the block's own scale: with er = ilogb(range), the range
+// and every offset a - vmin are multiplied by 2^-er (exact), so the scale L / range stays an
+// ordinary fp32 number however small or large the tensor's values are.
+__device__ inline int range_exp(float rng) { return ilogb_bits(__float_as_uint(rng)); }   // rng > 0
+__device__ inline float unit_range(float rng, int er) { return ldexpf(rng, -er); }        // in [1, 2)
+__device__ inline float to_unit(float d, int er) { return ldexpf(d, -er); }
+
 // ---- wave-level primitives without LDS traffic -------------------------------------
 
 __device__ inline void wave_sync()

@@ -122,7 +122,7 @@ __device__ inline void enc_generic_rows(const EncArgs& a, const int64_t r_begin,
     __shared__ int tg_cls[kTgtBatch], tg_j[kTgtBatch], tg_done[kTgtBatch], tg_owner[kTgtBatch];
     __shared__ u32 blk_start[kMaxB2 + 1];
     __shared__ u32 vminb[kMaxB2], vmaxb[kMaxB2];
-    __shared__ int e_tab[kMaxB2], degen[kMaxB2], qsel[kMaxB2];
+    __shared__ int e_tab[kMaxB2], er_tab[kMaxB2], degen[kMaxB2], qsel[kMaxB2];
     __shared__ float inv_sel[kMaxB2];
     __shared__ u64 code_off[kMaxB2 + 1];
     __shared__ float inv_tab[kMaxB2][kMaxQ];
@@ -419,18 +419,19 @@ __device__ inline void enc_generic_rows(const EncArgs& a, const int64_t r_begin,
     // ------------------------------------------------------------------
     for (int b = tid; b < B2; b += BLOCK) {
         u32 cnt = blk_start[b + 1] - blk_start[b];
-        int dg = 1, e = 0;
-        float rng = 0.f;
+        int dg = 1, e = 0, er = 0;
+        float rng1 = 1.f;
         if (cnt) {
             u32 vminbits = E::value_bits(vminb[b]), vmaxbits = E::value_bits(vmaxb[b]);
-            rng = __uint_as_float(vmaxbits) - __uint_as_float(vminbits);
-            dg = !(rng >= 0x1p-100f);
+            const float rng = __uint_as_float(vmaxbits) - __uint_as_float(vminbits);
+            dg = !(rng > 0.f);                       // only a range of exactly 0 is degenerate
+            if (!dg) { er = range_exp(rng); rng1 = unit_range(rng, er); }
             e = ilogb_bits(vmaxbits) + 1;
         }
-        degen[b] = dg; e_tab[b] = e;
+        degen[b] = dg; e_tab[b] = e; er_tab[b] = er;
         for (int t = 0; t < a.nq; ++t) {
             float L = (float)((1u << a.qlist[t]) - 1u);
-            inv_tab[b][t] = dg ? 0.f : L / rng;
+            inv_tab[b][t] = dg ? 0.f : L / rng1;
             sums[b][t] = 0;
         }
         sums[b][kMaxQ] = 0;
@@ -443,7 +444,7 @@ __device__ inline void enc_generic_rows(const EncArgs& a, const int64_t r_begin,
 #pragma unroll
         for (int t = 0; t < kMaxQ; ++t) acc[t] = 0;
         float vmin = 0.f;
-        int e = 0, dg = 1;
+        int e = 0, dg = 1, er = 0;
         auto flush = [&]() {
             if (cur < 0) return;
 #pragma unroll
@@ -458,7 +459,7 @@ __device__ inline void enc_generic_rows(const EncArgs& a, const int64_t r_begin,
                 flush();
                 cur = b;
                 vmin = __uint_as_float(E::value_bits(vminb[b]));
-                e = e_tab[b]; dg = degen[b];
+                e = e_tab[b]; dg = degen[b]; er = er_tab[b];
             }
             u32 abits = bo_val[p];
             float av = __uint_as_float(abits);
@@ -466,7 +467,7 @@ __device__ inline void enc_generic_rows(const EncArgs& a, const int64_t r_begin,
             accE += A * A;
             if (!dg && a.guard == 1) {
                 // Eq. "DS": codes at q_bit shifted down against the codes at q
-                const float d = av - vmin;
+                const float d = to_unit(av - vmin, er);
                 const int top = a.nq - 1, qtop = a.qlist[top];
                 const u32 c0 = (u32)fminf(fmaxf(rintf(d * inv_tab[b][top]), 0.f), (float)((1u << qtop) - 1u));
 #pragma unroll
@@ -479,7 +480,7 @@ __device__ inline void enc_generic_rows(const EncArgs& a, const int64_t r_begin,
                     }
                 }
             } else if (!dg) {
-                float d = av - vmin;
+                float d = to_unit(av - vmin, er);
 #pragma unroll
                 for (int t = 0; t < kMaxQ; ++t) {
                     if (t < a.nq) {
@@ -599,7 +600,7 @@ __device__ inline void enc_generic_rows(const EncArgs& a, const int64_t r_begin,
                 if (!degen[b]) {
                     float L = (float)((1u << q) - 1u);
                     float vmin = __uint_as_float(E::value_bits(vminb[b]));
-                    float y = (__uint_as_float(bo_val[p]) - vmin) * inv_sel[b];
+                    float y = to_unit(__uint_as_float(bo_val[p]) - vmin, er_tab[b]) * inv_sel[b];
                     c = (u32)fminf(fmaxf(rintf(y), 0.f), L);
                 }
                 stage_or_bits(sA, lo, hi, idx_bits + code_off[b] + (u64)(p - blk_start[b]) * (u64)q, c, q);

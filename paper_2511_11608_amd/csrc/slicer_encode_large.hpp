@@ -628,7 +628,7 @@ __global__ __launch_bounds__(256) void lr_abq_kernel(LargeArgs a)
     static_assert(NJ <= 8, "u32 partial sums");
     __shared__ u32 bs[kMaxB2 + 1];
     __shared__ float vminf[kMaxB2];
-    __shared__ int e_tab[kMaxB2], degen[kMaxB2];
+    __shared__ int e_tab[kMaxB2], er_tab[kMaxB2], degen[kMaxB2];
     __shared__ float inv_tab[kMaxB2][kMaxQ];
     __shared__ u64 sums[kMaxB2][kMaxQ + 1];
     const int tid = threadIdx.x, pc = blockIdx.x;
@@ -650,18 +650,19 @@ __global__ __launch_bounds__(256) void lr_abq_kernel(LargeArgs a)
     __syncthreads();
     for (int b = tid; b < B2; b += 256) {
         const u32 cnt = bs[b + 1] - bs[b];
-        int dg = 1, e = 0;
-        float rng = 0.f, vmin = 0.f;
+        int dg = 1, e = 0, er = 0;
+        float rng1 = 1.f, vmin = 0.f;
         if (cnt) {
             const u32 lo = E::value_bits(a.vminb[r * B2 + b]), hi = E::value_bits(a.vmaxb[r * B2 + b]);
             vmin = __uint_as_float(lo);
-            rng = __uint_as_float(hi) - vmin;
-            dg = !(rng >= 0x1p-100f);
+            const float rng = __uint_as_float(hi) - vmin;
+            dg = !(rng > 0.f);                       // only a range of exactly 0 is degenerate
+            if (!dg) { er = range_exp(rng); rng1 = unit_range(rng, er); }
             e = ilogb_bits(hi) + 1;
         }
-        vminf[b] = vmin; degen[b] = dg; e_tab[b] = e;
+        vminf[b] = vmin; degen[b] = dg; e_tab[b] = e; er_tab[b] = er;
         for (int t = 0; t < nq; ++t) {
-            inv_tab[b][t] = dg ? 0.f : (float)((1u << a.qlist[t]) - 1u) / rng;
+            inv_tab[b][t] = dg ? 0.f : (float)((1u << a.qlist[t]) - 1u) / rng1;
             sums[b][t] = 0;
         }
         sums[b][kMaxQ] = 0;
@@ -679,7 +680,7 @@ __global__ __launch_bounds__(256) void lr_abq_kernel(LargeArgs a)
 #pragma unroll
         for (int t = 0; t < QN; ++t) { acc[t] = 0; inv[t] = 0.f; inv15[t] = 0.f; }
         float vmin = 0.f;
-        int e = 0, dg = 1;
+        int e = 0, dg = 1, er = 0;
         auto flush = [&]() {
             if (cur < 0) return;
 #pragma unroll
@@ -696,18 +697,18 @@ __global__ __launch_bounds__(256) void lr_abq_kernel(LargeArgs a)
             while (b < B2 - 1 && p >= bs[b + 1]) ++b;
             if (b != cur) {
                 flush();
-                cur = b; vmin = vminf[b]; e = e_tab[b]; dg = degen[b];
+                cur = b; vmin = vminf[b]; e = e_tab[b]; dg = degen[b]; er = er_tab[b];
 #pragma unroll
                 for (int t = 0; t < QN; ++t) {
                     inv[t] = (NQ || t < nq) ? inv_tab[b][t] : 0.f;
-                    inv15[t] = inv[t] * 32768.0f;        // finite for bitwidths up to 8 (scale <= 255 * 2^100)
+                    inv15[t] = inv[t] * 32768.0f;        // the scale is at most 2^16 - 1
                 }
             }
             const float av = __uint_as_float(vb[j]);
             const u64 A = (u64)(u32)rintf(ldexpf(av, 20 - e));     // 20-bit energy grid scaled to vmax
             accE += A * A;
             if (dg) continue;
-            const float d = av - vmin;
+            const float d = to_unit(av - vmin, er);
             if (a.guard == 1) {
                 // Eq. "DS": | (code at q_bit >> (q_bit - q)) - code at q | for every lower bitwidth
                 float inv_top = 0.f;
@@ -807,7 +808,8 @@ __global__ __launch_bounds__(128) void lr_choose_kernel(LargeArgs a)
             vmin = __uint_as_float(E::value_bits(a.vminb[r * B2 + b]));
             vmax = __uint_as_float(hi);
             const float rng = vmax - vmin;
-            if (rng >= 0x1p-100f) {
+            if (rng > 0.f) {
+                const float rng1 = unit_range(rng, range_exp(rng));
                 const int e = ilogb_bits(hi) + 1;
                 const u64* sm = a.sums + ((size_t)r * B2 + b) * (nq + 1);
                 const double rhs = a.beta * ldexp((double)sm[nq], 2 * e - 40);
@@ -816,7 +818,7 @@ __global__ __launch_bounds__(128) void lr_choose_kernel(LargeArgs a)
                     const float Lq = (float)((1u << a.qlist[t]) - 1u);
                     const float o = rng / Lq;
                     const double lhs = ((double)o * (double)o) * (double)sm[t] * 0x1p-30;
-                    q = a.qlist[t]; inv = Lq / rng;
+                    q = a.qlist[t]; inv = Lq / rng1;
                     if (lhs <= rhs) flag = 0;
                 }
             }
@@ -828,12 +830,12 @@ __global__ __launch_bounds__(128) void lr_choose_kernel(LargeArgs a)
                 if ((double)sm[t] <= a.beta * (double)cnt) chosen = t; else break;
             }
             q = a.qlist[chosen]; flag = 0; inv = 0.f;
-            if (cnt && vmax - vmin >= 0x1p-100f) inv = (float)((1u << q) - 1u) / (vmax - vmin);
+            if (cnt && vmax - vmin > 0.f) inv = (float)((1u << q) - 1u) / unit_range(vmax - vmin, range_exp(vmax - vmin));
         }
         if (a.lad.on) {             // the bitwidth is given, also for empty and degenerate blocks
             q = a.qlist[ladder_index(a.lad, b < a.M ? b : b - a.M)];
             flag = 0; inv = 0.f;
-            if (cnt && vmax - vmin >= 0x1p-100f) inv = (float)((1u << q) - 1u) / (vmax - vmin);
+            if (cnt && vmax - vmin > 0.f) inv = (float)((1u << q) - 1u) / unit_range(vmax - vmin, range_exp(vmax - vmin));
         }
         a.qsel[r * B2 + b] = (u32)q;
         a.inv_sel[r * B2 + b] = inv;
@@ -932,6 +934,7 @@ __global__ __launch_bounds__(256) void lr_pack_kernel(LargeArgs a)
     __shared__ u32 bs[kMaxB2 + 1], qsel[kMaxB2];
     __shared__ u32 crel[kMaxB2];                  // first code bit of the block relative to the window, modulo 2^32
     __shared__ float vminf[kMaxB2], invs[kMaxB2];
+    __shared__ int ers[kMaxB2];
     const int tid = threadIdx.x;
     const int64_t r = blockIdx.y;
     const int B2 = a.M + a.Mn, w = a.w;
@@ -972,6 +975,10 @@ __global__ __launch_bounds__(256) void lr_pack_kernel(LargeArgs a)
         qsel[b] = a.qsel[r * B2 + b];
         invs[b] = a.inv_sel[r * B2 + b];
         vminf[b] = __uint_as_float(E::value_bits(a.vminb[r * B2 + b]));
+        {
+            const float rng = __uint_as_float(E::value_bits(a.vmaxb[r * B2 + b])) - vminf[b];
+            ers[b] = rng > 0.f ? range_exp(rng) : 0;      // blocks of range 0 have inv = 0 and are not scaled
+        }
         crel[b] = (u32)(idx_bits + a.code_off[(size_t)r * (B2 + 1) + b] - lo);
     }
     for (int i = tid; i < (int)cw; i += 256) sA[i] = 0;
@@ -1007,6 +1014,7 @@ __global__ __launch_bounds__(256) void lr_pack_kernel(LargeArgs a)
             u32 b_end = b < B2 - 1 ? bs[b + 1] : 0xFFFFFFFFu;
             int q = (int)qsel[b];
             float inv = invs[b], vmin = vminf[b], qmaxf = (float)((1u << q) - 1u);
+            int er = ers[b];
             rp.begin(sA, (int)cw, (int)(crel[b] + (p0 - bs[b]) * (u32)q));
 #pragma unroll
             for (int u = 0; u < RUN; ++u) {
@@ -1015,11 +1023,11 @@ __global__ __launch_bounds__(256) void lr_pack_kernel(LargeArgs a)
                 if (p >= b_end) {
                     while (b < B2 - 1 && p >= bs[b + 1]) ++b;
                     b_end = b < B2 - 1 ? bs[b + 1] : 0xFFFFFFFFu;
-                    q = (int)qsel[b]; inv = invs[b]; vmin = vminf[b]; qmaxf = (float)((1u << q) - 1u);
+                    q = (int)qsel[b]; inv = invs[b]; vmin = vminf[b]; qmaxf = (float)((1u << q) - 1u); er = ers[b];
                 }
                 u32 c = 0;
                 if (inv != 0.f) {
-                    const float y = (__uint_as_float(vc[u]) - vmin) * inv;
+                    const float y = to_unit(__uint_as_float(vc[u]) - vmin, er) * inv;
                     c = (u32)fminf(fmaxf(rintf(y), 0.f), qmaxf);
                 }
                 rp.append(c, q);

@@ -795,8 +795,8 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
     const u32 myb = udiv16(lane, lpb), sub = lane - myb * lpb;
     const bool lane_on = myb < (u32)B2;
     u32 r0 = 0, r1 = 0, bs0 = 0, mycnt = 0;
-    float vmin = 0.f, rng = 0.f;
-    int e = 0, dg = 1;
+    float vmin = 0.f, rng = 0.f, rng1 = 1.f;
+    int e = 0, dg = 1, er = 0;
     u32 vmaxbits = 0;
     if (lane_on) {
         bs0 = L.blk_start[myb];
@@ -810,18 +810,19 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
             vmaxbits = E::value_bits(L.vmaxb[myb]);
             vmin = __uint_as_float(lo);
             rng = __uint_as_float(vmaxbits) - vmin;
-            dg = !(rng >= 0x1p-100f);
+            dg = !(rng > 0.f);                       // only a range of exactly 0 is degenerate
+            if (!dg) { er = range_exp(rng); rng1 = unit_range(rng, er); }
             e = ilogb_bits(vmaxbits) + 1;
         }
     }
     // longest run of any lane: the largest block holds K + (n mod M) entries
     const u32 mc0 = n_pos - Kc[0] * (u32)(M - 1), mc1 = n_neg - Kc[1] * (u32)(Mn - 1);
     const u32 T = udiv16((mc0 > mc1 ? mc0 : mc1) + lpb - 1, lpb);
-    // quantiser scales L / rng: the lanes of a block share the divisions through LDS
+    // quantiser scales L / (range brought to [1, 2)): the lanes of a block share the divisions through LDS
     if (lane_on) {
         for (u32 t = sub; t < (u32)nq; t += lpb) {
             const float Lq = (float)((1u << L.qtab[t]) - 1u);
-            invt[myb * (u32)nq + t] = dg ? 0.f : Lq / rng;
+            invt[myb * (u32)nq + t] = dg ? 0.f : Lq / rng1;
         }
         if (sub == 0) {
             for (int t = 0; t <= nq; ++t) sums[myb * (nq + 1) + t] = 0;
@@ -844,7 +845,7 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
     }
     auto abq_sums = [&](auto fast) {
         constexpr bool kFast = decltype(fast)::value;
-        // bitwidths up to 8: the scale times 2^15 stays finite (scale <= 255 * 2^100), one multiply per code
+        // bitwidths up to 8: y * 2^15 stays below 2^23, one multiply per code
         float inv15[QN];
 #pragma unroll
         for (int t = 0; t < QN; ++t) inv15[t] = inv[t] * 32768.0f;
@@ -860,7 +861,7 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
                     const float av = __uint_as_float(bo_val[p]);
                     const u64 A = (u64)(u32)rintf(ldexpf(av, 20 - e));   // 20-bit energy grid scaled to vmax
                     accE += A * A;
-                    const float d = av - vmin;
+                    const float d = to_unit(av - vmin, er);
 #pragma unroll
                     for (int t = 0; t < QN; ++t) {
                         if (NQ || t < nq) {
@@ -891,7 +892,7 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
             for (u32 i = i0; i < i1; ++i) {
                 const u32 p = r0 + i;
                 if (p < r1) {
-                    const float d = __uint_as_float(bo_val[p]) - vmin;
+                    const float d = to_unit(__uint_as_float(bo_val[p]) - vmin, er);
                     const u32 c0 = (u32)rintf(d * inv_top);           // within [0, 2^q - 1]: no clamp needed
 #pragma unroll
                     for (int t = 0; t < QN; ++t) {
@@ -974,7 +975,7 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
             if (p < r1) {
                 u32 c = 0;
                 if (!dg) {
-                    const float y = (__uint_as_float(bo_val[p]) - vmin) * my_inv;
+                    const float y = to_unit(__uint_as_float(bo_val[p]) - vmin, er) * my_inv;
                     c = (u32)rintf(y);                    // already within [0, 2^q - 1]
                 }
                 {   // index field

@@ -80,6 +80,24 @@ def test_adversarial_rows(oracle, dtype, N):
         check(oracle, x, dtype, keep, M, bits, budget, use_header=(M != 2))
 
 
+@pytest.mark.parametrize("dtype,rows,N", [("bf16", 40, 4096), ("f32", 40, 768), ("f32", 3, 50_000), ("bf16", 2, 40_960),
+                                          ("f32", 5, 4097), ("bf16", 3, 1001)])
+@pytest.mark.parametrize("scale", [-105, -120, 100])
+def test_tiny_and_huge_magnitudes(oracle, dtype, rows, N, scale):
+    """The quantiser works on each block's own scale (Sec. 3.2.1 defines the step for any non-zero range):
+    tensors multiplied by 2^-105 or 2^-120 (block ranges far below what a scale L / range could hold in
+    fp32, the second partly denormal) and by 2^100 go through every encoder family bit-exactly."""
+    rng = np.random.default_rng(N + scale)
+    x = rng.standard_normal((rows, N)).astype(np.float32)
+    x[rng.random((rows, N)) < 0.3] = 0
+    x[:, :: 97] *= np.float32(40)
+    x = np.ldexp(x, scale).astype(np.float32)
+    if dtype == "bf16":
+        x = synth.f32_to_bf16_bits(x)
+    for keep, M, bits, budget in ((0.1, 8, B28, 1e-3), (0.3, 3, (1 << 2) | (1 << 12) | (1 << 16), 1e-7)):
+        check(oracle, x, dtype, keep, M, bits, budget)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_random_parameters(oracle, dtype):
     rng = np.random.default_rng(123)
