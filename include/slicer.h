@@ -55,7 +55,8 @@ enum {
     SLICER_EINVAL = -1,       /* null pointer or argument out of range */
     SLICER_EUNSUPPORTED = -2, /* unknown dtype */
     SLICER_EHIP = -3,         /* a HIP call failed; see slicer_last_hip_error() */
-    SLICER_EFORMAT = -4       /* meta header is not a version-1 header */
+    SLICER_EFORMAT = -4,      /* meta header is not a version-1 header */
+    SLICER_ETOOBIG = -5       /* slicer_encode_static: the shape needs more scratch than the library holds */
 };
 
 #define SLICER_MAX_BLOCKS 64  /* n_blocks (per sign class) accepted by the library */
@@ -92,6 +93,23 @@ int slicer_encode(const void* x, slicer_dtype dt, int64_t rows, int64_t row_len,
                   double keep_ratio, int n_blocks, uint32_t bit_set,
                   double distortion_budget,
                   void* stream, void* meta, void* workspace, void* hip_stream);
+
+/*
+ * slicer_encode for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The call
+ * allocates nothing (no hipMalloc, hipFree or allocating library routine); its workspace is a
+ * static device array of SLICER_STATIC_SCRATCH_BYTES inside the library, of which every GPU the
+ * library runs on holds a copy until the process ends.  Arguments, output and errors as
+ * slicer_encode (same kernels, byte-identical stream and meta), plus SLICER_ETOOBIG when the
+ * shape's workspace_bytes (slicer_sizes) exceed SLICER_STATIC_SCRATCH_BYTES.  All calls on one
+ * GPU share that GPU's array: calls that overlap in time on one GPU (two streams, two host
+ * threads) race and give undefined output; calls on one stream are ordered and safe.  The
+ * array keeps the last call's contents; the kernels write every word before they read it.
+ */
+#define SLICER_STATIC_SCRATCH_BYTES (64u << 20)
+int slicer_encode_static(const void* x, slicer_dtype dt, int64_t rows, int64_t row_len,
+                         double keep_ratio, int n_blocks, uint32_t bit_set,
+                         double distortion_budget, void* stream, void* meta, void* hip_stream);
 
 /*
  * Decode (Eq. "dequnt": de-quantise every block and scatter it into a zero

@@ -44,6 +44,8 @@ def load() -> C.CDLL:
         L.slicer_encode_path.argtypes = [cint, i64, i64, dbl, cint, u32]
         L.slicer_encode.restype = cint
         L.slicer_encode.argtypes = [vp, cint, i64, i64, dbl, cint, u32, dbl, vp, vp, vp, vp]
+        L.slicer_encode_static.restype = cint
+        L.slicer_encode_static.argtypes = [vp, cint, i64, i64, dbl, cint, u32, dbl, vp, vp, vp]
         L.slicer_sizes_pn.restype = cint
         L.slicer_sizes_pn.argtypes = [cint, i64, i64, dbl, cint, cint, u32, szp, szp, szp]
         L.slicer_encode_pn.restype = cint
@@ -131,6 +133,17 @@ def slicer_encode(x: torch.Tensor, keep_ratio: float, n_blocks: int, bit_set: in
     _check("slicer_encode", load().slicer_encode(
         x.data_ptr(), _dt_of(x), rows, row_len, keep_ratio, n_blocks, bit_set, distortion_budget,
         stream_buf.data_ptr(), meta.data_ptr(), workspace.data_ptr(), _stream_handle(stream)))
+
+
+def slicer_encode_static(x: torch.Tensor, keep_ratio: float, n_blocks: int, bit_set: int, distortion_budget: float,
+                         stream_buf: torch.Tensor, meta: torch.Tensor, stream=None) -> None:
+    """slicer_encode on the library's static scratch: no workspace argument, nothing allocated."""
+    if not x.is_cuda or not x.is_contiguous() or x.dim() != 2:
+        raise ValueError("x must be a contiguous 2-D tensor on the GPU")
+    rows, row_len = x.shape
+    _check("slicer_encode_static", load().slicer_encode_static(
+        x.data_ptr(), _dt_of(x), rows, row_len, keep_ratio, n_blocks, bit_set, distortion_budget,
+        stream_buf.data_ptr(), meta.data_ptr(), _stream_handle(stream)))
 
 
 def alloc_buffers_pn(x: torch.Tensor, keep_ratio: float, n_blocks: int, n_blocks_neg: int, bit_set: int):

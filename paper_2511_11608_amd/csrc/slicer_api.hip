@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 #include <algorithm>
 #include <cmath>
+#include <mutex>
 
 #include "slicer_common.hpp"
 #include "slicer_encode_generic.hpp"
@@ -13,6 +14,10 @@
 #include "slicer_decode.hpp"
 
 using namespace slicer;
+
+// Scratch of slicer_encode_static: the workspace of an encode call for callers that cannot
+// allocate.  Every GPU the library runs on holds its own copy until the process ends.
+static __device__ __align__(256) unsigned char scratch[SLICER_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -448,6 +453,46 @@ int slicer_encode(const void* x, slicer_dtype dt, int64_t rows, int64_t row_len,
                        stream, meta, workspace, hip_stream);
 }
 
+// Address of this device's copy of `scratch`, looked up once per device.  The array's name is a
+// host-side stand-in: only the pointer hipGetSymbolAddress returns is usable as a kernel argument.
+static int static_scratch(void** out)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static void* ptr[kMaxDevices] = {};
+    int dev = 0;
+    SLICER_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return SLICER_EINVAL;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[dev]) {
+        void* p = nullptr;
+        SLICER_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return SLICER_EHIP;
+        ptr[dev] = p;
+    }
+    *out = ptr[dev];
+    return SLICER_OK;
+}
+
+int slicer_encode_static(const void* x, slicer_dtype dt, int64_t rows, int64_t row_len, double keep_ratio,
+                         int n_blocks, uint32_t bit_set, double distortion_budget, void* stream, void* meta,
+                         void* hip_stream)
+{
+    int rc = check_args((int)dt, rows, row_len, keep_ratio, n_blocks, bit_set);
+    if (rc) return rc;
+    const Plan p = make_plan((int)dt, rows, row_len, keep_ratio, n_blocks, n_blocks, bit_set);
+    if (p.total > (size_t)SLICER_STATIC_SCRATCH_BYTES) return SLICER_ETOOBIG;
+    if (!x || !stream || !meta) return SLICER_EINVAL;
+    void* ws = nullptr;
+    rc = static_scratch(&ws);
+    if (rc) return rc;
+    Ladder none;
+    none.on = 0;
+    for (int j = 0; j < kMaxBlocks / 8; ++j) none.nib[j] = 0;
+    return encode_impl(x, dt, rows, row_len, keep_ratio, n_blocks, n_blocks, bit_set, distortion_budget, none, 0,
+                       stream, meta, ws, hip_stream);
+}
+
 int slicer_encode_pn(const void* x, slicer_dtype dt, int64_t rows, int64_t row_len, double keep_ratio,
                      int n_blocks, int n_blocks_neg, uint32_t bit_set, double distortion_budget, void* stream,
                      void* meta, void* workspace, void* hip_stream)
@@ -620,6 +665,7 @@ const char* slicer_strerror(int code)
         case SLICER_EUNSUPPORTED: return "unsupported dtype";
         case SLICER_EHIP: return "HIP call failed (see slicer_last_hip_error)";
         case SLICER_EFORMAT: return "meta header is not a version-1 SLICER header";
+        case SLICER_ETOOBIG: return "shape needs more scratch than the library's static buffer holds";
         default: return "unknown error";
     }
 }

@@ -57,11 +57,14 @@ def test_argument_errors_and_strings(lib):
             binding.slicer_sizes(a["dt"], a["rows"], a["row_len"], a["keep_ratio"], a["n_blocks"], a["bit_set"])
         assert ei.value.code == code
     assert lib.slicer_strerror(0) == b"ok"
-    for code in (-1, -2, -3, -4, -99):
+    for code in (-1, -2, -3, -4, -5, -99):
         assert len(lib.slicer_strerror(code)) > 0
     # null pointers are rejected before anything is launched
     assert lib.slicer_encode(None, 0, 1, 8, 0.5, 1, 0b100, 1e-3, None, None, None, None) == -1
     assert lib.slicer_decode_as(None, None, None, 0, 1, 8, 1, None) == -1
+    # the entry point without a workspace: shapes beyond its static scratch are refused before anything else
+    assert lib.slicer_encode_static(None, 1, 16384, 4096, 0.1, 8, 0x1FC, 1e-3, None, None, None) == -5
+    assert lib.slicer_encode_static(None, 1, 16, 4096, 0.1, 8, 0x1FC, 1e-3, None, None, None) == -1
 
 
 def test_encode_path_by_shape(lib):
