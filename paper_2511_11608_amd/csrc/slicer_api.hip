@@ -64,7 +64,7 @@ struct Plan {
     int64_t k;
     int w, qmax;
     u64 cap_words;          // per row
-    size_t off_row_words, off_slots, off_kept, off_bo_idx, off_bo_val, off_fallback, off_row_local, off_chunk_tot, total;
+    size_t off_row_words, off_slots, off_kept, off_bo_idx, off_bo_val, off_fallback, off_row_local, off_chunk_tot, off_hint, total;
     // row-resident fast path (0 = not eligible)
     int small_epl, small_cap, small_region0, small_lds_bytes, small_maxs;
     // long-row path (large_C == 0: not eligible)
@@ -94,6 +94,7 @@ Plan make_plan(int dt, int64_t rows, int64_t row_len, double keep_ratio, int n_b
     p.off_fallback = o;  o = align256(o + 4 * (size_t)rows);
     p.off_row_local = o; o = align256(o + 8 * (size_t)rows);
     p.off_chunk_tot = o; o = align256(o + 8 * (size_t)((rows + kScanRows - 1) / kScanRows));
+    p.off_hint = o;      o = align256(o + 4 * (size_t)kHintSlots);
     // Long rows: every pass is spread over many workgroups (slicer_encode_large.hpp).
     p.large_C = 0; p.large_LC = 0; p.large_capL = 0;
     {
@@ -358,6 +359,7 @@ static int encode_impl(const void* x, slicer_dtype dt, int64_t rows, int64_t row
         sa.lad = lad;
         sa.guard = guard;
         sa.one_plus = ea.one_plus; sa.one_minus = ea.one_minus;
+        sa.hint = (u32*)(ws + p.off_hint);
         const bool timed = g_ev_start && g_ev_stop;
         if (timed) SLICER_HIP(hipEventRecord(g_ev_start, st));
         rc = dt == SLICER_F32 ? launch_small<0>(sa, p, st, false) : launch_small<1>(sa, p, st, asym);

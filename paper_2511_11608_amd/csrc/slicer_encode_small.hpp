@@ -50,7 +50,18 @@ struct SmallArgs {
     Ladder lad;         // fixed multi-level mode: no sums, no search
     int guard;          // 0: relative squared-error budget; 1: DS mismatch of Eq. "DS", greedy descent (beta = delta)
     float one_plus, one_minus;   // asymmetric thresholds of Sec. 3.1 (ASYM kernels): 1 + lambda, 1 - lambda in fp32
+    u32* hint;          // [kHintSlots] cut keys of rows encoded earlier with this workspace (any contents are safe)
 };
+
+// Threshold hints.  Rows of one tensor (tokens of one sequence, successive decode steps) have their
+// top-K cut at nearly the same magnitude, so a wave first tries the cut key some earlier row left in
+// the workspace, lowered by kHintDelta steps of the key's top 15 bits: if the number of keys at or
+// above it lies in [k, k + kHintSlack] the list is built from it directly, and the row's largest key,
+// the 2048-bin histogram and its scan are skipped.  The count decides, not the hint: a stale,
+// foreign or garbage value only sends the row down the histogram path, and the output never depends on it.
+constexpr int kHintSlots = 512;
+constexpr u32 kHintDelta = 8;
+constexpr u32 kHintSlack = 120;
 
 constexpr int kCoarseBits = 11;
 constexpr int kCoarseBins = 1 << kCoarseBits;
@@ -194,10 +205,14 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
         v[c] = base < N ? xr[c * kWave + lane] : make_uint4(0, 0, 0, 0);
     }
     auto word_of = [&](int c, int d) -> u32 { return d == 0 ? v[c].x : d == 1 ? v[c].y : d == 2 ? v[c].z : v[c].w; };
+    constexpr bool kHint = !ASYM && MAXS > 0;       // (the list must be in registers: its largest key is taken from there)
+    const u32 hslot = (u32)blockIdx.x & (u32)(kHintSlots - 1);
+    u32 hint_key = 0;
+    if (kHint) hint_key = a.hint[hslot] & (DT == 0 ? 0x7FFFFFFFu : 0x7FFFu);
 
     // Largest magnitude key of the row: the histogram window hangs from it.
-    u32 kmax;
-    {
+    u32 kmax = 0;
+    auto row_kmax = [&]() {
         u32 mx = 0;
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
@@ -210,7 +225,7 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
         }
         if (DT == 1) mx = max(mx & 0xFFFFu, mx >> 16);
         kmax = wave_max_dpp(mx);
-    }
+    };
 
     // Coarse histogram over a window of 2048 bins that hangs from `wtop`: bin = (wtop - key) >> S,
     // bin 0 on top.  First pass: S = 0 (bf16: one key per bin) or 16 (fp32: the same 128 bins per
@@ -220,7 +235,7 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
     // If rank k-1 lies below the window, a second pass with 16 times wider bins hangs from the
     // window's lower end and reaches key 0.
     constexpr int S1 = DT == 0 ? 16 : 0;
-    u32 wtop = kmax, above = 0;                     // above = number of keys > wtop
+    u32 wtop = 0, above = 0;                        // above = number of keys > wtop
     int S = S1;
     u32 B1 = 0, c_gt = 0, cnt1 = 0;
     bool found = false;
@@ -290,14 +305,65 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
         }
         wave_sync();
     };
-    hist_pass(std::integral_constant<int, S1>(), all_keys, std::false_type());
-    if (found && B1 == (u32)(kCoarseBins - 1) && (wtop >> S1) > (u32)(kCoarseBins - 1)) {
-        above = c_gt;
-        wtop -= (u32)(kCoarseBins - 1) << S1;
-        S = S1 + 4;
-        hist_pass(std::integral_constant<int, S1 + 4>(), all_keys, std::false_type());
+    // List length and positions for a lower key bound t_lo: per 16-byte chunk the number of keys at or
+    // above it, then exclusive positions (three chunk counts share one scan: 10-bit fields, a chunk
+    // holds at most 512 keys).
+    u32 t_lo = 1u, nL = 0;
+    u32 cntc[NCH], basec[NCH];
+    auto scan_counts = [&]() {
+        nL = 0;
+#pragma unroll
+        for (int g = 0; g < (NCH + 2) / 3; ++g) {
+            u32 pk = cntc[3 * g];
+            if (3 * g + 1 < NCH) pk |= cntc[3 * g + 1] << 10;
+            if (3 * g + 2 < NCH) pk |= cntc[3 * g + 2] << 20;
+            const u32 incl = wave_scan_dpp(pk);
+            const u32 tot = bcast(incl, kWave - 1);
+            const u32 ex = incl - pk;
+#pragma unroll
+            for (int j = 0; j < 3; ++j) {
+                if (3 * g + j < NCH) {
+                    basec[3 * g + j] = nL + ((ex >> (10 * j)) & 0x3FFu);
+                    nL += (tot >> (10 * j)) & 0x3FFu;
+                }
+            }
+        }
+    };
+    auto count_plain = [&]() {
+        const u32 C16 = (0x8000u - t_lo) * 0x10001u;            // bf16: bit 15 / 31 of (key + C16) <=> key >= t_lo
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            u32 n1 = 0;
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                const u32 wd = word_of(c, d);
+                if (DT == 0) n1 += ((wd & 0x7FFFFFFFu) >= t_lo) ? 1u : 0u;
+                else n1 += (u32)__popc(((wd & 0x7FFF7FFFu) + C16) & 0x80008000u);
+            }
+            cntc[c] = n1;
+        }
+        scan_counts();
+    };
+    // the hinted bound: accepted when it keeps at least k keys and not many more
+    bool hinted = false;
+    if (kHint && k > 0) {
+        const u32 dlt = kHintDelta << (DT == 0 ? 16 : 0);
+        t_lo = hint_key > dlt ? hint_key - dlt : 1u;
+        count_plain();
+        hinted = nL >= (u32)k && nL <= (u32)k + kHintSlack && (int)nL <= cap;
     }
-    c_gt += above;
+    if (!hinted) {
+        row_kmax();
+        wtop = kmax;
+        hist_pass(std::integral_constant<int, S1>(), all_keys, std::false_type());
+        if (found && B1 == (u32)(kCoarseBins - 1) && (wtop >> S1) > (u32)(kCoarseBins - 1)) {
+            above = c_gt;
+            wtop -= (u32)(kCoarseBins - 1) << S1;
+            S = S1 + 4;
+            hist_pass(std::integral_constant<int, S1 + 4>(), all_keys, std::false_type());
+        }
+        c_gt += above;
+    }
 
     // ---- asymmetric thresholds: strict set, second selection ------------------------------------
     // Everything per pair of keys (packed 16-bit lanes): st = 1 where the element is strictly
@@ -369,18 +435,19 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
 
     // the list takes every non-zero key from bin B1 up (a bin that reaches key 0 also counts the
     // zeros, which never enter the list: its length is known after the counting pass below)
-    const long long lowk = (long long)wtop - ((long long)(B1 + 1u) << S) + 1;
-    u32 t_lo = lowk > 1 ? (u32)lowk : 1u;                        // smallest non-zero key of bin B1
-    if (ASYM && k > 0) t_lo = trim ? t2_key : min(t2_key, tn_key + 1u);   // smallest key the list can hold
-    if (!ASYM && k > 0 && lowk >= 1 && (int)(c_gt + cnt1) > cap) {
-        if (lane == 0) a.fallback[r] = 1u;
-        return;
+    if (!hinted) {
+        const long long lowk = (long long)wtop - ((long long)(B1 + 1u) << S) + 1;
+        t_lo = lowk > 1 ? (u32)lowk : 1u;                        // smallest non-zero key of bin B1
+        if (ASYM && k > 0) t_lo = trim ? t2_key : min(t2_key, tn_key + 1u);   // smallest key the list can hold
+        if (!ASYM && k > 0 && lowk >= 1 && (int)(c_gt + cnt1) > cap) {
+            if (lane == 0) a.fallback[r] = 1u;
+            return;
+        }
     }
 
     // ---- 2. ordered compaction into L -------------------------------------------------
-    u32 nL = 0;
+    if (k == 0) nL = 0;
     if (k > 0) {
-        u32 cntc[NCH];
         const u32 C16 = (0x8000u - t_lo) * 0x10001u;            // bf16: bit 15 / 31 of (key + C16) <=> key >= t_lo
         // bits 15 and 31: the element goes to the list
         auto list_flags = [&](u32 wd) -> u32 {
@@ -391,34 +458,17 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
             const u32 ge = gt01(t2_2, wk & 0x7FFF7FFFu) ^ kOne2;              // key >= last key taken
             return (trim ? (st & ge) : (st | (fill01(wd, st) & ge))) << 15;
         };
+        if (ASYM) {
 #pragma unroll
-        for (int c = 0; c < NCH; ++c) {
-            u32 n1 = 0;
+            for (int c = 0; c < NCH; ++c) {
+                u32 n1 = 0;
 #pragma unroll
-            for (int d = 0; d < 4; ++d) {
-                const u32 wd = word_of(c, d);
-                if (DT == 0) n1 += ((wd & 0x7FFFFFFFu) >= t_lo) ? 1u : 0u;
-                else n1 += (u32)__popc(list_flags(wd) & 0x80008000u);
+                for (int d = 0; d < 4; ++d) n1 += (u32)__popc(list_flags(word_of(c, d)) & 0x80008000u);
+                cntc[c] = n1;
             }
-            cntc[c] = n1;
-        }
-        // exclusive positions: three chunk counts share one scan (10-bit fields, totals <= 512)
-        u32 basec[NCH];
-#pragma unroll
-        for (int g = 0; g < (NCH + 2) / 3; ++g) {
-            u32 pk = cntc[3 * g];
-            if (3 * g + 1 < NCH) pk |= cntc[3 * g + 1] << 10;
-            if (3 * g + 2 < NCH) pk |= cntc[3 * g + 2] << 20;
-            const u32 incl = wave_scan_dpp(pk);
-            const u32 tot = bcast(incl, kWave - 1);
-            const u32 ex = incl - pk;
-#pragma unroll
-            for (int j = 0; j < 3; ++j) {
-                if (3 * g + j < NCH) {
-                    basec[3 * g + j] = nL + ((ex >> (10 * j)) & 0x3FFu);
-                    nL += (tot >> (10 * j)) & 0x3FFu;
-                }
-            }
+            scan_counts();
+        } else if (!hinted) {
+            count_plain();
         }
         // every flagged element is stored at a running byte address that advances by its flag
         const u32 lidx_off = (u32)((u32*)L.Lidx - smem) * 4u;
@@ -497,6 +547,13 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
             if (MAXS && DT == 0) eix[(MAXS && DT == 0) ? s : 0] = p < nL ? (u32)L.Lidx[p] : 0u;
         }
         wave_sync();
+        if (kHint && hinted) {                        // the row's largest key is the list's largest
+            u32 mx = 0;
+#pragma unroll
+            for (int s = 0; s < SLN; ++s) mx = max(mx, ent[MAXS ? s : 0] & 0x7FFFFFFFu);
+            kmax = wave_max_dpp(mx);
+            if (DT == 1) kmax >>= 16;
+        }
     }
     {
         uint4* h4 = (uint4*)L.hist;
@@ -999,6 +1056,7 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
         a.mv.n_pos[r] = n_pos;
         a.mv.n_neg[r] = n_neg;
         a.fallback[r] = 0u;
+        if (kHint && k > 0) a.hint[hslot] = nL > (u32)k ? cx_key(thrK) : t_lo;    // this row's cut key, for a later row
     }
 }
 
