@@ -16,7 +16,11 @@ those K steps; `single_stream` in the same line is the figure with every step on
 Prints ONE JSON line: whole-step throughput in GB/s of input IF, the roofline
 record of the dominant kernel (the encode kernel that does the selection, quantisation
 and packing of a row; its duration is read with HIP events recorded around it on its stream), and the CPU oracle timed on
-a bounded sample of the same workload.
+a bounded sample of the same workload.  The same line carries `workloads`: all five
+configurations at full size, each measured in a short single-stream loop (encode and decode call,
+dominant kernel, step latency, bits per element, oracle on a small sample; the AR-decode
+workload over its 512 steps with fresh seeds), and `device_copy`: a plain device copy timed in
+the same run, the practical HBM rate next to the published 8 TB/s.
 """
 from __future__ import annotations
 
@@ -62,16 +66,22 @@ class HipEvents:
         return ms.value
 
 
-def make_workload(which: int):
+AR_STEPS = 512          # the AR-decode workload: 512 steps, a fresh seed per step
+
+
+def make_workload(which: int, ar_steps: int = AR_STEPS):
     from paper_2511_11608_amd import synth
     if which == 5:
-        steps = [synth.ar_decode_step(seed=0, step=s) for s in range(64)]
+        from concurrent.futures import ThreadPoolExecutor
+        workers = max(1, min(16, os.cpu_count() or 1))
+        with ThreadPoolExecutor(max_workers=workers) as ex:     # numpy's generators release the GIL
+            steps = list(ex.map(lambda s: synth.ar_decode_step(seed=0, step=s), range(ar_steps)))
         return steps[0], [s.x for s in steps]
     wl = synth.make_config(which)
     return wl, [wl.x]
 
 
-def cpu_baseline(wl, threads: int, ladder=None, ds=None, lam=None) -> dict:
+def cpu_baseline(wl, threads: int, ladder=None, ds=None, lam=None, seconds: float = 15.0) -> dict:
     """The oracle as it stands (encode + decode) on a bounded sample of the rows."""
     from oracle import ref
     ref.lib()
@@ -92,7 +102,7 @@ def cpu_baseline(wl, threads: int, ladder=None, ds=None, lam=None) -> dict:
     s, m = ref_encode(wl.x[:probe], threads)
     ref.decode(s, m, n_threads=threads)
     per_row = (time.perf_counter() - t0) / probe * min(threads, probe)      # core-seconds per row
-    take = int(max(probe, min(rows, 15.0 / max(per_row, 1e-9))))
+    take = int(max(probe, min(rows, seconds / max(per_row, 1e-9))))
     x = wl.x[:take]
     t0 = time.perf_counter()
     s, m = ref_encode(x, threads)
@@ -101,7 +111,7 @@ def cpu_baseline(wl, threads: int, ladder=None, ds=None, lam=None) -> dict:
     t2 = time.perf_counter()
     nbytes = x.nbytes
     # one thread, on a slice of the sample sized for a few seconds
-    take1 = int(max(1, min(take, 4.0 / max(per_row, 1e-9))))
+    take1 = int(max(1, min(take, 0.27 * seconds / max(per_row, 1e-9))))
     x1 = wl.x[:take1]
     t3 = time.perf_counter()
     s1, m1 = ref_encode(x1, 1)
@@ -139,6 +149,126 @@ def load_traffic(workload: str, kernel: str):
         return None
 
 
+def measure_workload(which: int, ev: "HipEvents", threads: int, cpu_seconds: float, pregenerated=None,
+                     steps: int = 40) -> dict:
+    """One entry of the line's `workloads` array: a short single-stream measurement of workload `which`
+    at its full size (encode call, decode call, dominant encode kernel, step latency, compressed size)
+    and the oracle on a bounded sample.  The AR-decode workload runs its 512 steps, each with its own seed."""
+    import torch
+    from paper_2511_11608_amd import binding
+    from paper_2511_11608_amd.devmem import to_device
+
+    wl, xs = pregenerated if pregenerated is not None else make_workload(which)
+    M, bits, keep, beta = wl.n_blocks, wl.bit_set, wl.keep_ratio, wl.budget
+    dt = binding.SLICER_F32 if wl.dtype == "f32" else binding.SLICER_BF16
+    in_bytes = wl.nbytes
+    x0 = [to_device(x, wl.dtype) for x in xs]
+    n_buf = min(max(len(x0), int(np.ceil(320e6 / in_bytes)) + 1), 512)      # > 256 MB of distinct inputs in flight
+    xd, shift = list(x0), 1
+    while len(xd) < n_buf:
+        xd.append(torch.roll(x0[len(xd) % len(x0)], shifts=shift, dims=0).contiguous())
+        shift += 1
+    n_out = min(n_buf, 4)
+    bufs = [binding.alloc_buffers(xd[0], keep, M, bits) for _ in range(n_out)]
+    ys = [torch.empty_like(xd[0]) for _ in range(n_out)]
+    K = len(xs) if which == 5 else steps
+
+    def enc(i):
+        binding.slicer_encode(xd[i % n_buf], keep, M, bits, beta, *bufs[i % n_out])
+
+    def dec(i):
+        binding.slicer_decode_as(bufs[i % n_out][0], bufs[i % n_out][1], ys[i % n_out], M)
+
+    for i in range(max(3, min(n_buf, 8))):
+        enc(i); dec(i)
+    torch.cuda.synchronize()
+    st = torch.cuda.current_stream().cuda_stream
+    ev.hip.hipEventRecord.argtypes = [C.c_void_p, C.c_void_p]
+
+    def timed_loop(fn):
+        a, b = ev.create(), ev.create()
+        ev.hip.hipEventRecord(a, st)
+        for i in range(K):
+            fn(i)
+        ev.hip.hipEventRecord(b, st)
+        return ev.elapsed_ms(a, b) / K
+
+    enc_ms = timed_loop(enc)
+    dec_ms = timed_loop(dec)
+    # dominant encode kernel (or the chain of long-row stages): HIP events recorded inside the call
+    pairs = [(ev.create(), ev.create()) for _ in range(min(K, 40))]
+    for i, pr in enumerate(pairs):
+        binding.slicer_profile_events(*pr)
+        enc(i)
+    binding.slicer_profile_events(None, None)
+    torch.cuda.synchronize()
+    kern_ms = float(np.mean([ev.elapsed_ms(a, b) for a, b in pairs]))
+    lats = []
+    for i in range(min(K, 512)):
+        t_a = time.perf_counter()
+        enc(i); dec(i)
+        torch.cuda.synchronize()
+        lats.append((time.perf_counter() - t_a) * 1e6)
+    enc(0)
+    words = binding.slicer_stream_words(bufs[0][1])
+    _, meta_bytes, _ = binding.slicer_sizes(dt, wl.rows, wl.row_len, keep, M, bits)
+    out_bytes = 4 * words + meta_bytes
+    path = binding.slicer_encode_path(dt, wl.rows, wl.row_len, keep, M, bits)
+    kernel = {0: "enc_generic_kernel", 1: "enc_small_kernel", 2: "lr_* stages (hist..pack)"}[path]
+    alg = in_bytes + out_bytes
+    rec = {
+        "workload": f"{wl.name} [{wl.rows}x{wl.row_len}] keep={keep} M={M} bits=2..8 budget={beta}",
+        "config": which, "dtype": wl.dtype, "input_bytes": in_bytes, "steps": K,
+        "encode_ms": enc_ms, "decode_ms": dec_ms,
+        "encode_GBps": in_bytes / (enc_ms * 1e-3) / 1e9, "decode_GBps": in_bytes / (dec_ms * 1e-3) / 1e9,
+        "frac_hbm_peak": in_bytes / (enc_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "decode_frac_hbm_peak": in_bytes / (dec_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "bits_per_element": 8.0 * out_bytes / (wl.rows * wl.row_len),
+        "roofline": {"bound": "hbm", "kernel": kernel, "kernel_ms": kern_ms, "algorithmic_bytes_per_launch": alg,
+                     "achieved": alg / (kern_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": alg / (kern_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        "step_latency_us": {"p50": float(np.percentile(lats, 50)), "p99": float(np.percentile(lats, 99)), "n": len(lats)},
+        "inputs": f"{len(xs)} seeded batch(es), {n_buf} distinct device buffers",
+    }
+    if cpu_seconds > 0:
+        c = cpu_baseline(wl, threads, seconds=cpu_seconds)
+        rec["cpu_baseline"] = {k: c[k] for k in ("value", "unit", "cores", "kind", "sample", "single_thread_GBps")}
+    del xd, x0, bufs, ys
+    torch.cuda.empty_cache()
+    return rec
+
+
+def copy_rate(ev: "HipEvents", nbytes: int = 256 << 20, reps: int = 20) -> dict:
+    """A plain device copy measured in this run, next to the published 8 TB/s: bytes read + written per second."""
+    import torch
+    src = [torch.empty(nbytes, dtype=torch.uint8, device="cuda").fill_(i) for i in range(3)]
+    dst = [torch.empty(nbytes, dtype=torch.uint8, device="cuda") for _ in range(3)]
+    for i in range(3):
+        dst[i].copy_(src[i])
+    torch.cuda.synchronize()
+    st = torch.cuda.current_stream().cuda_stream
+    ev.hip.hipEventRecord.argtypes = [C.c_void_p, C.c_void_p]
+    a, b = ev.create(), ev.create()
+    ev.hip.hipEventRecord(a, st)
+    for i in range(reps):
+        dst[i % 3].copy_(src[i % 3])
+    ev.hip.hipEventRecord(b, st)
+    ms = ev.elapsed_ms(a, b) / reps
+    return {"GBps_read_plus_write": 2 * nbytes / (ms * 1e-3) / 1e9, "bytes_per_copy": nbytes, "kernel": "device-to-device copy (torch copy_)",
+            "frac_of_published_peak": 2 * nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+
+
+def profile_source() -> dict:
+    """Which commit the committed counter tables (HBM traffic, VALU counts) were taken at."""
+    out = {}
+    for name in ("hbm_traffic.json", "valu_counts.json"):
+        try:
+            out[name] = json.load(open(os.path.join(ROOT, "profiles", name))).get("_source", "unrecorded")
+        except Exception:
+            out[name] = "missing"
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -146,6 +276,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", type=int, default=4, help="1..5 (default 4: LLM prefill, the headline config)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--no-workloads", action="store_true",
+                    help="skip the per-workload array (all five configurations measured in short loops)")
     ap.add_argument("--ladder", type=str, default="",
                     help="time the fixed multi-level mode instead of the bitwidth search: comma-separated "
                          "bitwidths, one per block of a sign class, e.g. 8,7,6,5,4,3,2,2")
@@ -393,6 +525,19 @@ def main() -> int:
 
     threads = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)))
     cpu = None if args.no_cpu else cpu_baseline(wl, threads, ladder, args.ds, args.lam)
+    roofline["traffic_source"] = profile_source()
+    copy = copy_rate(ev)
+
+    # all five configurations, each at its full size, in short single-stream loops
+    workloads = None
+    plain = not (ladder or args.ds is not None or args.lam is not None)
+    if plain and not args.no_workloads:
+        del xd, x0, bufs, ys
+        torch.cuda.empty_cache()
+        workloads = []
+        for which in (1, 2, 3, 4, 5):
+            pre = (wl, xs) if which == args.workload and which != 5 else None
+            workloads.append(measure_workload(which, ev, threads, 0.0 if args.no_cpu else 3.0, pre))
 
     out = {
         "metric": "codec encode+decode throughput, GB/s of input IF",
@@ -417,6 +562,8 @@ def main() -> int:
                           "note": "the same steps on one stream, plain launches: no overlap between steps"},
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "device_copy": copy,
+        "workloads": workloads,
     }
     print(json.dumps(out))
     return 0
