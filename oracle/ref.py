@@ -36,6 +36,12 @@ def lib() -> C.CDLL:
                                            C.c_uint32, C.c_double, C.c_void_p, C.c_void_p, C.c_int]
         L.slicer_ref_encode_ds.restype = C.c_int
         L.slicer_ref_encode_ds.argtypes = L.slicer_ref_encode.argtypes
+        L.slicer_ref_sizes_csr.restype = C.c_int
+        L.slicer_ref_sizes_csr.argtypes = [C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_double, C.c_int, C.c_uint32,
+                                           C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
+        L.slicer_ref_encode_csr.restype = C.c_int
+        L.slicer_ref_encode_csr.argtypes = [C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_double, C.c_int,
+                                            C.c_uint32, C.c_double, C.c_void_p, C.c_void_p, C.c_int]
         L.slicer_ref_bound.restype = C.c_int
         L.slicer_ref_bound.argtypes = [C.c_int, C.c_int64, C.c_int64, C.c_double, C.c_int, C.c_uint32,
                                        C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)]
@@ -155,6 +161,28 @@ def encode_ds(x: np.ndarray, dtype: str, keep_ratio: float, n_blocks: int, bit_s
                                     delta, stream.ctypes.data, meta.ctypes.data, n_threads)
     if rc:
         raise ValueError(f"slicer_ref_encode_ds: error {rc}")
+    total = int(meta[48:56].view(np.uint64)[0])
+    return stream[:total].copy(), meta
+
+
+def encode_csr(x: np.ndarray, dtype: str, n_rows: int, n_cols: int, keep_ratio: float, n_blocks: int, bit_set: int,
+               budget: float, n_threads: int = 1):
+    """Two-dimensional instances: x is [instances, n_rows * n_cols]; blocks are stored as CSR triples.
+    Returns (stream, meta)."""
+    x = _check_x(x, dtype)
+    rows, row_len = x.shape
+    if row_len != n_rows * n_cols:
+        raise ValueError("row length must be n_rows * n_cols")
+    a, b = C.c_size_t(0), C.c_size_t(0)
+    rc = lib().slicer_ref_sizes_csr(_DT[dtype], rows, n_rows, n_cols, keep_ratio, n_blocks, bit_set, C.byref(a), C.byref(b))
+    if rc:
+        raise ValueError(f"slicer_ref_sizes_csr: error {rc}")
+    stream = np.zeros(max(a.value // 4, 1), np.uint32)
+    meta = np.zeros(b.value, np.uint8)
+    rc = lib().slicer_ref_encode_csr(x.ctypes.data, _DT[dtype], rows, n_rows, n_cols, keep_ratio, n_blocks, bit_set,
+                                     budget, stream.ctypes.data, meta.ctypes.data, n_threads)
+    if rc:
+        raise ValueError(f"slicer_ref_encode_csr: error {rc}")
     total = int(meta[48:56].view(np.uint64)[0])
     return stream[:total].copy(), meta
 

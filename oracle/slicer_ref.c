@@ -67,13 +67,26 @@
  * |S| >= k (the paper is silent; its claim of an exact count decides): the k largest magnitudes
  * of S are kept (equal magnitudes: lower index first).  lambda = 0 gives item 1 above.
  *
+ * Two-dimensional instance (Sec. 3.2: an IF X of shape N x K, and step 3, CSR(X_m) = (v_m, c_m, r_m);
+ * slicer_ref_encode_csr): one codec instance is a whole n_rows x n_cols tensor.  ATKF and MS work on
+ * its flattened view of length T = n_rows * n_cols (the footnote of Sec. 3.2 step 1), so kept set,
+ * blocks, ranges, bitwidths and codes are those of a flat row of length T.  Only the index encoding
+ * differs: every block is stored as a CSR triple - its values in row-major order (v), the column of
+ * every value (c), and n_rows + 1 row pointers (r): r[j] = number of the block's entries in tensor
+ * rows before j, i.e. the exclusive scan of the block's per-row counts, r[n_rows] = block size.
+ * Segment of an instance: all row pointers (blocks in order, wp = max(1, ceil(log2(k + 1))) bits
+ * each: any block size fits), then all columns (wc = max(1, ceil(log2 n_cols)) bits each, blocks
+ * in order, row-major inside a block), then all codes.  Header: offset 44 holds wc, offset 60 holds
+ * n_cols (0 there marks flat indices).
+ *
  * Payload bound (Sec. 3.3, "Predictive Bit/Time Model"): every kept slot at the largest
  * bitwidth, plus index and header bits; see slicer_ref_bound.
  *
  * Wire format, version 1 (little-endian):
  *   meta:  0 u32 magic 0x52434C53   4 u32 version   8 u32 dtype   12 u32 M
  *         16 u64 rows  24 u64 row_len  32 u64 k  40 u32 bit_set  44 u32 w
- *         48 u64 total_words  56 u32 M(-) if it differs from M (else 0)  60 u32 0
+ *         48 u64 total_words  56 u32 M(-) if it differs from M (else 0)
+ *         60 u32 n_cols of a two-dimensional instance (0: flat indices)
  *         64            u64 row_word_off[R]   (exclusive scan of row words)
  *         64+8R         u32 n_pos[R]
  *         64+12R        u32 n_neg[R]
@@ -176,6 +189,29 @@ int slicer_ref_sizes(int dt, int64_t rows, int64_t N, double keep, int M, uint32
                      size_t* stream_cap, size_t* meta_bytes)
 {
     return slicer_ref_sizes_pn(dt, rows, N, keep, M, M, bit_set, stream_cap, meta_bytes);
+}
+
+static int bits_for_count(int64_t k) /* bits that hold any value in 0..k */
+{
+    int w = 1;
+    while (((int64_t)1 << w) <= k) ++w;
+    return w;
+}
+
+/* Two-dimensional instances: `rows` tensors of n_rows x n_cols each. */
+int slicer_ref_sizes_csr(int dt, int64_t rows, int64_t n_rows, int64_t n_cols, double keep, int M,
+                         uint32_t bit_set, size_t* stream_cap, size_t* meta_bytes)
+{
+    if (n_rows <= 0 || n_cols <= 0 || n_rows > ((int64_t)1 << 31) / n_cols) return -1;
+    const int64_t T = n_rows * n_cols;
+    int rc = check_args(dt, rows, T, keep, M, bit_set);
+    if (rc) return rc;
+    const int64_t k = keep_count(keep, T);
+    const uint64_t bits = (uint64_t)(2 * M) * (uint64_t)(n_rows + 1) * (uint64_t)bits_for_count(k)
+                        + (uint64_t)k * (uint64_t)(index_bits(n_cols) + max_bit(bit_set));
+    if (stream_cap) *stream_cap = (size_t)(((bits + 31) / 32) * 4 * (uint64_t)rows);
+    if (meta_bytes) *meta_bytes = meta_size(rows, 2 * M);
+    return 0;
 }
 
 /* ---- one row: everything up to (but not including) packing ------------- */
@@ -484,6 +520,39 @@ static uint64_t pack_row(const row_result* rr, int64_t N, int B2, int w, uint32_
     return (bw.bitpos + 31) / 32;
 }
 
+/* Sec. 3.2 step 3 for a two-dimensional instance: every block as CSR(values, columns, row pointers).
+ * The row pointers of a block are the exclusive scan of its per-row entry counts. */
+static uint64_t pack_row_csr(const row_result* rr, int64_t n_rows, int64_t n_cols, int B2, int wp, int wc,
+                             uint32_t* words, uint32_t* scratch_idx /* [n_pos+n_neg] */)
+{
+    const int64_t T = n_rows * n_cols;
+    uint32_t n = 0;
+    uint32_t* fill = (uint32_t*)malloc(sizeof(uint32_t) * (size_t)B2);
+    uint32_t* start = (uint32_t*)malloc(sizeof(uint32_t) * (size_t)(B2 + 1));
+    for (int b = 0; b < B2; ++b) { fill[b] = n; start[b] = n; n += rr->count[b]; }
+    start[B2] = n;
+    for (int64_t i = 0; i < T; ++i)                      /* row-major sweep: CSR order inside every block */
+        if (rr->block_of[i] >= 0) scratch_idx[fill[rr->block_of[i]]++] = (uint32_t)i;
+    free(fill);
+    bitw_t bw = { words, 0 };
+    uint32_t* per_row = (uint32_t*)malloc(sizeof(uint32_t) * (size_t)n_rows);
+    for (int b = 0; b < B2; ++b) {                       /* r: row pointers */
+        memset(per_row, 0, sizeof(uint32_t) * (size_t)n_rows);
+        for (uint32_t j = start[b]; j < start[b + 1]; ++j) per_row[scratch_idx[j] / (uint32_t)n_cols]++;
+        uint32_t acc = 0;
+        for (int64_t row = 0; row < n_rows; ++row) { put_bits(&bw, acc, wp); acc += per_row[row]; }
+        put_bits(&bw, acc, wp);
+    }
+    free(per_row);
+    free(start);
+    for (uint32_t j = 0; j < n; ++j) put_bits(&bw, scratch_idx[j] % (uint32_t)n_cols, wc);     /* c: columns */
+    for (uint32_t j = 0; j < n; ++j) {                                                       /* v: codes */
+        uint32_t i = scratch_idx[j];
+        put_bits(&bw, rr->code_of[i], rr->qb[rr->block_of[i]] & 0x7F);
+    }
+    return (bw.bitpos + 31) / 32;
+}
+
 /* ---- meta accessors ---------------------------------------------------- */
 
 static void put_u32(uint8_t* p, uint32_t v) { memcpy(p, &v, 4); }
@@ -522,9 +591,10 @@ static void row_result_free(row_result* rr)
 
 /* ---- public: encode ---------------------------------------------------- */
 
+/* csr_cols > 0: two-dimensional instances of (N / csr_cols) x csr_cols, blocks stored as CSR triples */
 static int encode_common(const void* x, int dt, int64_t R, int64_t N, double keep, int M, int Mn,
                          uint32_t bit_set, double beta, const uint8_t* ladder, int ds, float lambda,
-                         void* stream, void* meta, int n_threads)
+                         void* stream, void* meta, int n_threads, int64_t csr_cols)
 {
     int rc = check_args(dt, R, N, keep, M, bit_set);
     if (rc) return rc;
@@ -534,9 +604,12 @@ static int encode_common(const void* x, int dt, int64_t R, int64_t N, double kee
     if (!(beta >= 0.0)) return -1;
 
     const int64_t k = keep_count(keep, N);
-    const int w = index_bits(N);
+    const int64_t csr_rows = csr_cols > 0 ? N / csr_cols : 0;
+    const int w = csr_cols > 0 ? index_bits(csr_cols) : index_bits(N);
+    const int wp = bits_for_count(k);
     const size_t esz = dt == SLICER_REF_F32 ? 4 : 2;
-    const uint64_t cap_words = ((uint64_t)k * (uint64_t)(w + max_bit(bit_set)) + 31) / 32;
+    const uint64_t cap_words = (((csr_cols > 0 ? (uint64_t)B2 * (uint64_t)(csr_rows + 1) * (uint64_t)wp : 0)
+                                 + (uint64_t)k * (uint64_t)(w + max_bit(bit_set))) + 31) / 32;
     uint8_t* mt = (uint8_t*)meta;
     memset(mt, 0, meta_size(R, B2));
 
@@ -561,7 +634,8 @@ static int encode_common(const void* x, int dt, int64_t R, int64_t N, double kee
 #endif
             fail = 1;
         } else {
-            seg_words[r] = pack_row(&rr, N, B2, w, seg[r], idxbuf);
+            seg_words[r] = csr_cols > 0 ? pack_row_csr(&rr, csr_rows, csr_cols, B2, wp, w, seg[r], idxbuf)
+                                        : pack_row(&rr, N, B2, w, seg[r], idxbuf);
             put_u32(mt + off_npos(R, B2) + 4 * (size_t)r, rr.n_pos);
             put_u32(mt + off_nneg(R, B2) + 4 * (size_t)r, rr.n_neg);
             for (int b = 0; b < B2; ++b) {
@@ -597,20 +671,28 @@ static int encode_common(const void* x, int dt, int64_t R, int64_t N, double kee
     put_u32(mt + 44, (uint32_t)w);
     put_u64(mt + 48, total);
     put_u32(mt + 56, Mn != M ? (uint32_t)Mn : 0u);   /* 0: M(-) = M(+) */
-    put_u32(mt + 60, 0);
+    put_u32(mt + 60, (uint32_t)csr_cols);            /* 0: flat indices */
     return fail ? -3 : 0;
 }
 
 int slicer_ref_encode(const void* x, int dt, int64_t R, int64_t N, double keep, int M,
                       uint32_t bit_set, double beta, void* stream, void* meta, int n_threads)
 {
-    return encode_common(x, dt, R, N, keep, M, M, bit_set, beta, NULL, 0, -1.0f, stream, meta, n_threads);
+    return encode_common(x, dt, R, N, keep, M, M, bit_set, beta, NULL, 0, -1.0f, stream, meta, n_threads, 0);
 }
 
 int slicer_ref_encode_pn(const void* x, int dt, int64_t R, int64_t N, double keep, int M, int Mn,
                          uint32_t bit_set, double beta, void* stream, void* meta, int n_threads)
 {
-    return encode_common(x, dt, R, N, keep, M, Mn, bit_set, beta, NULL, 0, -1.0f, stream, meta, n_threads);
+    return encode_common(x, dt, R, N, keep, M, Mn, bit_set, beta, NULL, 0, -1.0f, stream, meta, n_threads, 0);
+}
+
+/* Sec. 3.2 with X of shape n_rows x n_cols per instance: CSR triples per block */
+int slicer_ref_encode_csr(const void* x, int dt, int64_t R, int64_t n_rows, int64_t n_cols, double keep, int M,
+                          uint32_t bit_set, double beta, void* stream, void* meta, int n_threads)
+{
+    if (n_rows <= 0 || n_cols <= 0 || n_rows > ((int64_t)1 << 31) / n_cols) return -1;
+    return encode_common(x, dt, R, n_rows * n_cols, keep, M, M, bit_set, beta, NULL, 0, -1.0f, stream, meta, n_threads, n_cols);
 }
 
 /* Sec. 3.1 with an asymmetry factor: lambda in [0, 1), rounded to fp32 once */
@@ -618,7 +700,7 @@ int slicer_ref_encode_atkf(const void* x, int dt, int64_t R, int64_t N, double k
                            uint32_t bit_set, double beta, void* stream, void* meta, int n_threads)
 {
     if (!(lambda >= 0.0 && lambda < 1.0)) return -1;
-    return encode_common(x, dt, R, N, keep, M, Mn, bit_set, beta, NULL, 0, (float)lambda, stream, meta, n_threads);
+    return encode_common(x, dt, R, N, keep, M, Mn, bit_set, beta, NULL, 0, (float)lambda, stream, meta, n_threads, 0);
 }
 
 /* set of the ladder's bitwidths; 0 if an entry is outside 1..16 */
@@ -638,13 +720,13 @@ int slicer_ref_encode_ladder(const void* x, int dt, int64_t R, int64_t N, double
     if (!ladder || M < 1 || M > 64) return -1;
     uint32_t bs = ladder_bit_set(ladder, M);
     if (!bs) return -1;
-    return encode_common(x, dt, R, N, keep, M, M, bs, 0.0, ladder, 0, -1.0f, stream, meta, n_threads);
+    return encode_common(x, dt, R, N, keep, M, M, bs, 0.0, ladder, 0, -1.0f, stream, meta, n_threads, 0);
 }
 
 int slicer_ref_encode_ds(const void* x, int dt, int64_t R, int64_t N, double keep, int M,
                          uint32_t bit_set, double delta, void* stream, void* meta, int n_threads)
 {
-    return encode_common(x, dt, R, N, keep, M, M, bit_set, delta, NULL, 1, -1.0f, stream, meta, n_threads);
+    return encode_common(x, dt, R, N, keep, M, M, bit_set, delta, NULL, 1, -1.0f, stream, meta, n_threads, 0);
 }
 
 /* Sec. 3.3: value bits with every block at q_bit = max(bit_set), index bits, header bits.
@@ -680,6 +762,9 @@ int slicer_ref_decode(const void* stream, const void* meta, void* y, int n_threa
     const int64_t R = (int64_t)get_u64(mt + 16);
     const int64_t N = (int64_t)get_u64(mt + 24);
     const int w = (int)get_u32(mt + 44);
+    const int64_t csr_cols = (int64_t)get_u32(mt + 60);                /* 0: flat indices */
+    const int64_t csr_rows = csr_cols > 0 ? N / csr_cols : 0;
+    const int wp = bits_for_count((int64_t)get_u64(mt + 32));
     const uint32_t* words = (const uint32_t*)stream;
     const size_t esz = dt == SLICER_REF_F32 ? 4 : 2;
     if (n_threads < 1) n_threads = 1;
@@ -694,8 +779,10 @@ int slicer_ref_decode(const void* stream, const void* meta, void* y, int n_threa
         const uint32_t n_cls[2] = { get_u32(mt + off_npos(R, B2) + 4 * (size_t)r),
                                     get_u32(mt + off_nneg(R, B2) + 4 * (size_t)r) };
         const uint64_t n = (uint64_t)n_cls[0] + n_cls[1];
-        uint64_t ipos = 0;              /* bit cursor in the index section */
-        uint64_t cpos = n * (uint64_t)w; /* bit cursor in the code section */
+        const uint64_t ptr_bits = csr_cols > 0 ? (uint64_t)B2 * (uint64_t)(csr_rows + 1) * (uint64_t)wp : 0;
+        uint64_t ppos = 0;               /* bit cursor in the row pointers of the current block */
+        uint64_t ipos = ptr_bits;        /* bit cursor in the index (column) section */
+        uint64_t cpos = ptr_bits + n * (uint64_t)w; /* bit cursor in the code section */
         for (int s = 0; s < 2; ++s) {
             const int Ms = s ? Mn : M;
             uint32_t K = n_cls[s] / (uint32_t)Ms, start = 0;
@@ -709,8 +796,13 @@ int slicer_ref_decode(const void* stream, const void* meta, void* y, int n_threa
                 int q = mt[off_q(R, B2) + e] & 0x7F;
                 float L = (float)((1u << q) - 1u);
                 float o = (vmax - vmin) / L;
+                int64_t trow = 0;        /* CSR: tensor row of the current entry */
                 for (uint32_t j = 0; j < cnt; ++j) {
                     uint32_t idx = get_bits(rw, ipos, w); ipos += (uint64_t)w;
+                    if (csr_cols > 0) {  /* entry j lies in the row whose pointer range holds j: r[trow] <= j < r[trow+1] */
+                        while (trow + 1 < csr_rows && get_bits(rw, ppos + (uint64_t)(trow + 1) * wp, wp) <= j) ++trow;
+                        idx = (uint32_t)(trow * csr_cols) + idx;
+                    }
                     uint32_t c = get_bits(rw, cpos, q);   cpos += (uint64_t)q;
                     float prod = (float)c * o;   /* two roundings: no fused multiply-add */
                     float a = vmin + prod;
@@ -719,6 +811,7 @@ int slicer_ref_decode(const void* stream, const void* meta, void* y, int n_threa
                     if (dt == SLICER_REF_F32) memcpy((char*)y + 4 * at, &a, 4);
                     else { uint16_t h = float_to_bf16_rne(a); memcpy((char*)y + 2 * at, &h, 2); }
                 }
+                ppos += (uint64_t)(csr_rows + 1) * wp;
             }
         }
     }

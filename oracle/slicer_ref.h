@@ -50,6 +50,16 @@ int slicer_ref_encode_ds(const void* x, int dtype, int64_t rows, int64_t row_len
                          double keep_ratio, int n_blocks, uint32_t bit_set, double delta,
                          void* stream, void* meta, int n_threads);
 
+/* Two-dimensional instances (Sec. 3.2: X of shape N x K; step 3: CSR(X_m) = (v_m, c_m, r_m)): x holds
+ * `rows` tensors of n_rows x n_cols, each one codec instance over its flattened view; every block is
+ * stored as values, columns and n_rows + 1 row pointers (see slicer_ref.c).  slicer_ref_decode reads the
+ * index format from the header. */
+int slicer_ref_sizes_csr(int dtype, int64_t rows, int64_t n_rows, int64_t n_cols, double keep_ratio,
+                         int n_blocks, uint32_t bit_set, size_t* stream_capacity_bytes, size_t* meta_bytes);
+int slicer_ref_encode_csr(const void* x, int dtype, int64_t rows, int64_t n_rows, int64_t n_cols,
+                          double keep_ratio, int n_blocks, uint32_t bit_set, double distortion_budget,
+                          void* stream, void* meta, int n_threads);
+
 /* Upper bound of the payload before any data is seen (Sec. 3.3): value bits at
  * q_bit = max(bit_set), index bits, header bits (meta + word padding of the rows). */
 int slicer_ref_bound(int dtype, int64_t rows, int64_t row_len, double keep_ratio, int n_blocks,

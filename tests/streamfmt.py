@@ -17,7 +17,8 @@ def header(meta: np.ndarray) -> dict:
     u64 = lambda o: int(m[o:o + 8].view(np.uint64)[0])
     return dict(magic=u32(0), version=u32(4), dtype=u32(8), M=u32(12), rows=u64(16), row_len=u64(24),
                 k=u64(32), bit_set=u32(40), w=u32(44), total_words=u64(48), reserved=u64(56),
-                M_neg=u32(56) or u32(12))          # 0 at offset 56: the negative class has M blocks too
+                M_neg=u32(56) or u32(12),          # 0 at offset 56: the negative class has M blocks too
+                n_cols=u32(60))                    # non-zero: two-dimensional instance, blocks stored as CSR triples
 
 
 def arrays(meta: np.ndarray) -> dict:
@@ -66,4 +67,30 @@ def parse_row(stream: np.ndarray, meta: np.ndarray, r: int) -> dict:
         ipos += cnt * w
         cpos += cnt * q
         blocks.append((idx, cod))
+    return dict(blocks=blocks, sizes=sizes, bits=cpos, words=(cpos + 31) // 32)
+
+
+def parse_row_csr(stream: np.ndarray, meta: np.ndarray, r: int) -> dict:
+    """Blocks of the two-dimensional instance r: list of (row pointers, columns, codes) per block."""
+    h = header(meta)
+    a = arrays(meta)
+    wc, n_cols = h["w"], h["n_cols"]
+    n_rows = h["row_len"] // n_cols
+    wp = max(1, int(h["k"]).bit_length())                      # holds any value in 0..k
+    sizes = block_sizes(int(a["n_pos"][r]), h["M"]) + block_sizes(int(a["n_neg"][r]), h["M_neg"])
+    n = sum(sizes)
+    words = np.ascontiguousarray(stream, np.uint32)[int(a["row_off"][r]):]
+    ppos = 0
+    ipos = len(sizes) * (n_rows + 1) * wp
+    cpos = ipos + n * wc
+    blocks = []
+    for b, cnt in enumerate(sizes):
+        q = int(a["q"][r, b]) & 0x7F
+        ptr = [_bits(words, ppos + j * wp, wp) for j in range(n_rows + 1)]
+        col = [_bits(words, ipos + j * wc, wc) for j in range(cnt)]
+        cod = [_bits(words, cpos + j * q, q) for j in range(cnt)]
+        ppos += (n_rows + 1) * wp
+        ipos += cnt * wc
+        cpos += cnt * q
+        blocks.append((ptr, col, cod))
     return dict(blocks=blocks, sizes=sizes, bits=cpos, words=(cpos + 31) // 32)

@@ -48,6 +48,10 @@ MUTANTS = [
     ("ds_floor_dropped", "uint32_t ref = c0[j] >> (qbit - q);", "uint32_t ref = (c0[j] + (1u << (qbit - q)) / 2) >> (qbit - q);"),
     ("ds_not_greedy", "if ((double)D <= delta * (double)cnt) chosen = q; else break;",
      "if ((double)D <= delta * (double)cnt) chosen = q;"),
+    ("csr_pointers_inclusive", "for (int64_t row = 0; row < n_rows; ++row) { put_bits(&bw, acc, wp); acc += per_row[row]; }",
+     "for (int64_t row = 0; row < n_rows; ++row) { acc += per_row[row]; put_bits(&bw, acc, wp); }"),
+    ("csr_column_is_row", "put_bits(&bw, scratch_idx[j] % (uint32_t)n_cols, wc);", "put_bits(&bw, scratch_idx[j] / (uint32_t)n_cols, wc);"),
+    ("csr_decode_row_off_by_one", "get_bits(rw, ppos + (uint64_t)(trow + 1) * wp, wp) <= j", "get_bits(rw, ppos + (uint64_t)(trow + 1) * wp, wp) < j"),
     ("fill_takes_from_above_tau", "else if (fill > 0 && all[r].key <= all[k - 1].key)", "else if (fill > 0)"),
 ]
 

@@ -815,3 +815,66 @@ def test_atkf_rejects_bad_lambda(oracle):
     for lam in (-0.1, 1.0, 1.5, float("nan")):
         with pytest.raises(ValueError):
             oracle.encode_atkf(x, "f32", 0.5, lam, 2, 2, B28, 1e-3)
+
+
+# ----------------------------------------------------------------------------
+# two-dimensional instances: blocks stored as CSR triples (Sec. 3.2 step 3)
+# ----------------------------------------------------------------------------
+
+def test_golden_csr_3x4(oracle):
+    g, base = GOLD["csr_3x4"], GOLD["select_pack"]
+    x = np.array([base["x"]], np.float32)
+    s, m = oracle.encode_csr(x, "f32", g["n_rows"], g["n_cols"], base["keep_ratio"], base["n_blocks"],
+                             bits_of(base["bits"]), base["budget"])
+    assert [int(v) for v in s] == [int(v, 16) for v in g["words"]]
+    h = streamfmt.header(m)
+    assert (h["w"], h["n_cols"], h["row_len"], h["total_words"]) == (g["wc"], g["n_cols"], 12, 3)
+    p = streamfmt.parse_row_csr(s, m, 0)
+    assert [b[0] for b in p["blocks"]] == g["row_pointers"]
+    assert [b[1] for b in p["blocks"]] == g["columns"] and [b[2] for b in p["blocks"]] == g["codes"]
+    assert oracle.decode(s, m)[0].tolist() == base["decoded"]
+
+
+@pytest.mark.parametrize("dtype,shape", [("f32", (16, 196)), ("f32", (197, 96)), ("bf16", (24, 512)), ("f32", (1, 300)),
+                                         ("bf16", (300, 1)), ("f32", (5, 7))])
+def test_csr_instance_equals_flat_instance(oracle, dtype, shape):
+    """What Sec. 3.2 fixes about the CSR form of a block: the columns and the row pointers together name
+    exactly the entries of the flat index list (index = row * n_cols + column, row-major order), a
+    block's row pointers are the exclusive scan of its per-row entry counts (numpy bincount + cumsum),
+    everything that does not depend on the index encoding (counts, ranges, bitwidths, codes, decoded
+    tensor) is that of the flat instance, and the size is the closed form."""
+    n_rows, n_cols = shape
+    T = n_rows * n_cols
+    rng = np.random.default_rng(T)
+    x = rng.standard_normal((3, T)).astype(np.float32)
+    x[rng.random((3, T)) < 0.4] = 0
+    x[2, : T // 2] = 0                                         # empty tensor rows at the top
+    if dtype == "bf16":
+        x = synth.f32_to_bf16_bits(x)
+    for keep, M in ((0.2, 4), (1.0, 3), (0.0, 2), (0.05, 1)):
+        s0, m0 = oracle.encode(x, dtype, keep, M, B28, 1e-3)
+        s1, m1 = oracle.encode_csr(x, dtype, n_rows, n_cols, keep, M, B28, 1e-3)
+        h0, h1, a0, a1 = streamfmt.header(m0), streamfmt.header(m1), streamfmt.arrays(m0), streamfmt.arrays(m1)
+        assert h1["n_cols"] == n_cols and h0["n_cols"] == 0
+        assert h1["w"] == max(1, int(np.ceil(np.log2(n_cols)))) if n_cols > 1 else h1["w"] == 1
+        for name in ("n_pos", "n_neg", "vmin", "vmax", "q"):
+            assert np.array_equal(a0[name], a1[name])
+        assert np.array_equal(oracle.decode(s0, m0), oracle.decode(s1, m1))
+        wp = max(1, int(h1["k"]).bit_length())
+        off = 0
+        for r in range(3):
+            p0, p1 = streamfmt.parse_row(s0, m0, r), streamfmt.parse_row_csr(s1, m1, r)
+            assert int(a1["row_off"][r]) == off
+            n = sum(p1["sizes"])
+            bits = 2 * M * (n_rows + 1) * wp + n * h1["w"] + sum(c * (int(a1["q"][r, b]) & 0x7F) for b, c in enumerate(p1["sizes"]))
+            assert p1["bits"] == bits
+            off += (bits + 31) // 32
+            for (idx, cod), (ptr, col, cod1) in zip(p0["blocks"], p1["blocks"]):
+                idx = np.array(idx, np.int64)
+                assert cod == cod1 and col == (idx % n_cols).tolist()
+                counts = np.bincount(idx // n_cols, minlength=n_rows)
+                assert ptr == np.concatenate(([0], np.cumsum(counts))).tolist()
+                # and back: entry j lies in the tensor row whose pointer range holds j
+                rows_of = np.searchsorted(np.array(ptr[1:]), np.arange(len(col)), side="right")
+                assert np.array_equal(rows_of * n_cols + np.array(col, np.int64), idx)
+        assert off == h1["total_words"] == s1.size
