@@ -33,7 +33,7 @@
  *   meta    0 u32 magic 0x52434C53   4 u32 version   8 u32 dtype   12 u32 M
  *           16 u64 rows   24 u64 row_len   32 u64 k   40 u32 bit_set   44 u32 w
  *           48 u64 total_words   56 u32 M(-) if the negative class has its own block count
- *           (0: it has M blocks too)   60 u32 0
+ *           (0: it has M blocks too)   60 u32 n_cols of a two-dimensional instance (0: flat indices)
  *           then  u64 row_word_off[R], u32 n_pos[R], u32 n_neg[R],
  *                 f32 vmin[R][B], f32 vmax[R][B], u8 q[R][B] with B = M + M(-) blocks per row
  *                 (bit 7 of q: no bitwidth met the budget, the largest was used), padded to 8 bytes.
@@ -167,6 +167,32 @@ int slicer_decode_as_pn(const void* stream, const void* meta, void* y, slicer_dt
 int slicer_check_pn(const void* meta, uint64_t stream_words, slicer_dtype dt, int64_t rows,
                     int64_t row_len, int n_blocks, int n_blocks_neg, void* scratch,
                     void* hip_stream);
+
+/*
+ * Two-dimensional instances (Sec. 3.2: an IF X of shape N x K; step 3: every block stored as
+ * CSR(X_m) = (v_m, c_m, r_m)).  x holds `instances` tensors of n_rows x n_cols (row-major), each one
+ * codec instance: ATKF and MS work on its flattened view of length n_rows * n_cols (the footnote of
+ * Sec. 3.2 step 1), so kept set, blocks, ranges, bitwidths and codes are those of slicer_encode on rows
+ * of that length.  The index encoding differs: per instance the stream holds, for its blocks in order,
+ * first every block's n_rows + 1 row pointers (r: pointer j = number of the block's entries in tensor
+ * rows before j, the exclusive scan of its per-row counts; wp = max(1, ceil(log2(k + 1))) bits each),
+ * then the column of every entry (c: wc = max(1, ceil(log2 n_cols)) bits, row-major inside a block),
+ * then the codes (v), LSB-first, padded to a word.  Header: offset 44 holds wc, offset 60 n_cols (0
+ * there marks the flat index format of slicer_encode); meta arrays as slicer_encode.
+ *   stream_capacity_bytes  instances * ceil((2 n_blocks (n_rows + 1) wp + k (wc + q_bit)) / 32) * 4
+ * n_rows * n_cols < 2^31.  Served by the one-workgroup-per-instance encoder.  slicer_decode reads the
+ * index format from the header; slicer_decode_as_csr takes the shape from the caller (it reads k from
+ * the header in meta for the pointer width, nothing else).  slicer_check does not accept these metas.
+ * Errors as slicer_sizes / slicer_encode / slicer_decode_as.
+ */
+int slicer_sizes_csr(slicer_dtype dt, int64_t instances, int64_t n_rows, int64_t n_cols, double keep_ratio,
+                     int n_blocks, uint32_t bit_set,
+                     size_t* stream_capacity_bytes, size_t* meta_bytes, size_t* workspace_bytes);
+int slicer_encode_csr(const void* x, slicer_dtype dt, int64_t instances, int64_t n_rows, int64_t n_cols,
+                      double keep_ratio, int n_blocks, uint32_t bit_set, double distortion_budget,
+                      void* stream, void* meta, void* workspace, void* hip_stream);
+int slicer_decode_as_csr(const void* stream, const void* meta, void* y, slicer_dtype dt, int64_t instances,
+                         int64_t n_rows, int64_t n_cols, int n_blocks, void* hip_stream);
 
 /*
  * Encode with the paper's own guard (Sec. 3.2.1, Eq. "DS" and the greedy search stated under it:

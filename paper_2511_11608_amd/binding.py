@@ -46,6 +46,12 @@ def load() -> C.CDLL:
         L.slicer_encode.argtypes = [vp, cint, i64, i64, dbl, cint, u32, dbl, vp, vp, vp, vp]
         L.slicer_encode_static.restype = cint
         L.slicer_encode_static.argtypes = [vp, cint, i64, i64, dbl, cint, u32, dbl, vp, vp, vp]
+        L.slicer_sizes_csr.restype = cint
+        L.slicer_sizes_csr.argtypes = [cint, i64, i64, i64, dbl, cint, u32, szp, szp, szp]
+        L.slicer_encode_csr.restype = cint
+        L.slicer_encode_csr.argtypes = [vp, cint, i64, i64, i64, dbl, cint, u32, dbl, vp, vp, vp, vp]
+        L.slicer_decode_as_csr.restype = cint
+        L.slicer_decode_as_csr.argtypes = [vp, vp, vp, cint, i64, i64, i64, cint, vp]
         L.slicer_sizes_pn.restype = cint
         L.slicer_sizes_pn.argtypes = [cint, i64, i64, dbl, cint, cint, u32, szp, szp, szp]
         L.slicer_encode_pn.restype = cint
@@ -144,6 +150,35 @@ def slicer_encode_static(x: torch.Tensor, keep_ratio: float, n_blocks: int, bit_
     _check("slicer_encode_static", load().slicer_encode_static(
         x.data_ptr(), _dt_of(x), rows, row_len, keep_ratio, n_blocks, bit_set, distortion_budget,
         stream_buf.data_ptr(), meta.data_ptr(), _stream_handle(stream)))
+
+
+def alloc_buffers_csr(x: torch.Tensor, n_rows: int, n_cols: int, keep_ratio: float, n_blocks: int, bit_set: int):
+    """Device buffers for two-dimensional instances: x is [instances, n_rows * n_cols]."""
+    a, b, c = C.c_size_t(0), C.c_size_t(0), C.c_size_t(0)
+    _check("slicer_sizes_csr", load().slicer_sizes_csr(_dt_of(x), x.shape[0], n_rows, n_cols, keep_ratio, n_blocks,
+                                                      bit_set, C.byref(a), C.byref(b), C.byref(c)))
+    dev = x.device
+    return (torch.empty(max(a.value // 4, 1), dtype=torch.int32, device=dev),
+            torch.empty(b.value, dtype=torch.uint8, device=dev),
+            torch.empty(max(c.value, 256), dtype=torch.uint8, device=dev))
+
+
+def slicer_encode_csr(x: torch.Tensor, n_rows: int, n_cols: int, keep_ratio: float, n_blocks: int, bit_set: int,
+                      distortion_budget: float, stream_buf: torch.Tensor, meta: torch.Tensor, workspace: torch.Tensor,
+                      stream=None) -> None:
+    """Encode instances of n_rows x n_cols with every block stored as CSR(values, columns, row pointers)."""
+    if not x.is_cuda or not x.is_contiguous() or x.dim() != 2 or x.shape[1] != n_rows * n_cols:
+        raise ValueError("x must be a contiguous [instances, n_rows * n_cols] tensor on the GPU")
+    _check("slicer_encode_csr", load().slicer_encode_csr(
+        x.data_ptr(), _dt_of(x), x.shape[0], n_rows, n_cols, keep_ratio, n_blocks, bit_set, distortion_budget,
+        stream_buf.data_ptr(), meta.data_ptr(), workspace.data_ptr(), _stream_handle(stream)))
+
+
+def slicer_decode_as_csr(stream_buf: torch.Tensor, meta: torch.Tensor, y: torch.Tensor, n_rows: int, n_cols: int,
+                         n_blocks: int, stream=None) -> None:
+    _check("slicer_decode_as_csr", load().slicer_decode_as_csr(stream_buf.data_ptr(), meta.data_ptr(), y.data_ptr(),
+                                                              _dt_of(y), y.shape[0], n_rows, n_cols, n_blocks,
+                                                              _stream_handle(stream)))
 
 
 def alloc_buffers_pn(x: torch.Tensor, keep_ratio: float, n_blocks: int, n_blocks_neg: int, bit_set: int):

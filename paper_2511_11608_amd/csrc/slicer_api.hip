@@ -62,7 +62,7 @@ int index_bits(int64_t N)
 
 struct Plan {
     int64_t k;
-    int w, qmax;
+    int w, qmax, wc, wp;    // wc, wp: bits of a column / a row pointer of a two-dimensional instance
     u64 cap_words;          // per row
     size_t off_row_words, off_slots, off_kept, off_bo_idx, off_bo_val, off_fallback, off_row_local, off_chunk_tot, off_hint, total;
     // row-resident fast path (0 = not eligible)
@@ -76,7 +76,16 @@ struct Plan {
 
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
-Plan make_plan(int dt, int64_t rows, int64_t row_len, double keep_ratio, int n_blocks, int n_blocks_neg, uint32_t bit_set)
+int count_bits(int64_t k)      // bits that hold any value in 0..k
+{
+    int w = 1;
+    while (((int64_t)1 << w) <= k) ++w;
+    return w;
+}
+
+// csr_cols > 0: two-dimensional instances of (row_len / csr_cols) x csr_cols, blocks stored as CSR triples
+Plan make_plan(int dt, int64_t rows, int64_t row_len, double keep_ratio, int n_blocks, int n_blocks_neg, uint32_t bit_set,
+               int64_t csr_cols = 0)
 {
     const int B2_all = n_blocks + n_blocks_neg;          // blocks per row
     Plan p;
@@ -85,6 +94,11 @@ Plan make_plan(int dt, int64_t rows, int64_t row_len, double keep_ratio, int n_b
     p.qmax = 16;
     while (!((bit_set >> p.qmax) & 1u)) --p.qmax;
     p.cap_words = ((u64)p.k * (u64)(p.w + p.qmax) + 31) / 32;
+    p.wc = 0; p.wp = 0;
+    if (csr_cols > 0) {
+        p.wc = index_bits(csr_cols); p.wp = count_bits(p.k);
+        p.cap_words = ((u64)B2_all * (u64)(row_len / csr_cols + 1) * (u64)p.wp + (u64)p.k * (u64)(p.wc + p.qmax) + 31) / 32;
+    }
     size_t o = 0;
     p.off_row_words = o; o = align256(o + 8 * (size_t)rows);
     p.off_slots = o;     o = align256(o + 4 * (size_t)rows * (size_t)p.cap_words);
@@ -103,7 +117,7 @@ Plan make_plan(int dt, int64_t rows, int64_t row_len, double keep_ratio, int n_b
         const int64_t capL = (p.k + std::max<int64_t>(4096, row_len / 16) + 7) & ~(int64_t)7;   // whole 16-byte groups of 2-byte entries
         int nq_l = 0;
         for (int q = 1; q <= 16; ++q) nq_l += (bit_set >> q) & 1u;
-        if (row_len > 4096 && row_len % epc_l == 0 && C <= 1024 && rows <= 65535 && capL < ((int64_t)1 << 27)) {
+        if (csr_cols == 0 && row_len > 4096 && row_len % epc_l == 0 && C <= 1024 && rows <= 65535 && capL < ((int64_t)1 << 27)) {
             const size_t R = (size_t)rows, B2 = (size_t)B2_all;
             p.large_C = (int)C; p.large_capL = (u32)capL; p.large_LC = (int)((capL + kLCE - 1) / kLCE);
             p.lo_ch_cum = o;    o = align256(o + 4 * R * (size_t)C * kLBins);
@@ -134,7 +148,7 @@ Plan make_plan(int dt, int64_t rows, int64_t row_len, double keep_ratio, int n_b
     const int64_t max_n = dt == SLICER_F32 ? 4096 : 8192;
     int nq = 0;
     for (int q = 1; q <= 16; ++q) nq += (bit_set >> q) & 1u;
-    if (row_len % epc == 0 && row_len <= max_n && B2_all <= kWave) {
+    if (csr_cols == 0 && row_len % epc == 0 && row_len <= max_n && B2_all <= kWave) {
         const int64_t margin = std::max<int64_t>(64, row_len / (dt == SLICER_F32 ? 16 : 32));  // room for the undecided coarse bin
         int64_t cap = std::min<int64_t>(1984, (p.k + margin + 63) / 64 * 64);   // ranks are 11-bit fields
         int epl = epc;
@@ -304,7 +318,7 @@ int slicer_encode_path(slicer_dtype dt, int64_t rows, int64_t row_len, double ke
 
 static int encode_impl(const void* x, slicer_dtype dt, int64_t rows, int64_t row_len, double keep_ratio,
                        int n_blocks, int n_blocks_neg, uint32_t bit_set, double distortion_budget, const Ladder& lad, int guard,
-                       void* stream, void* meta, void* workspace, void* hip_stream, double lambda = 0.0)
+                       void* stream, void* meta, void* workspace, void* hip_stream, double lambda = 0.0, int64_t csr_cols = 0)
 {
     if (!(lambda >= 0.0 && lambda < 1.0)) return SLICER_EINVAL;
     const bool asym = (float)lambda > 0.0f;      // lambda = 0 is the plain top-K filter: every fast path applies
@@ -315,7 +329,7 @@ static int encode_impl(const void* x, slicer_dtype dt, int64_t rows, int64_t row
     if (rows >= ((int64_t)1 << 31)) return SLICER_EINVAL;
     if (n_blocks_neg < 1 || n_blocks_neg > SLICER_MAX_BLOCKS) return SLICER_EINVAL;
     hipStream_t st = (hipStream_t)hip_stream;
-    Plan p = make_plan((int)dt, rows, row_len, keep_ratio, n_blocks, n_blocks_neg, bit_set);
+    Plan p = make_plan((int)dt, rows, row_len, keep_ratio, n_blocks, n_blocks_neg, bit_set, csr_cols);
     char* ws = (char*)workspace;
 
     EncArgs ea;
@@ -341,6 +355,8 @@ static int encode_impl(const void* x, slicer_dtype dt, int64_t rows, int64_t row
     ea.asym = asym ? 1 : 0;
     ea.one_plus = 1.0f + (float)lambda;
     ea.one_minus = 1.0f - (float)lambda;
+    ea.csr_cols = csr_cols; ea.csr_rows = csr_cols > 0 ? row_len / csr_cols : 0;
+    ea.wc = p.wc; ea.wp = p.wp;
 
     // asymmetric thresholds need a second selection over a subset of the row: the generic kernel has it for
     // every shape, the row-resident kernel for bf16 rows (rows it flags are redone generically, same rule)
@@ -423,6 +439,8 @@ static int encode_impl(const void* x, slicer_dtype dt, int64_t rows, int64_t row
     fa.chunk_tot = (u64*)(ws + p.off_chunk_tot);
     fa.slots = ea.slots;
     fa.cap_words = p.cap_words;
+    fa.hdr_w = csr_cols > 0 ? (u32)p.wc : (u32)p.w;
+    fa.hdr_cols = (u32)csr_cols;
     fa.chunks_per_row = (int)std::max<u64>(1, (p.cap_words + kGatherWords - 1) / kGatherWords);
     fa.stream = (u32*)stream;
     fa.meta = meta;
@@ -504,6 +522,71 @@ int slicer_encode_pn(const void* x, slicer_dtype dt, int64_t rows, int64_t row_l
     for (int j = 0; j < kMaxBlocks / 8; ++j) none.nib[j] = 0;
     return encode_impl(x, dt, rows, row_len, keep_ratio, n_blocks, n_blocks_neg, bit_set, distortion_budget, none, 0,
                        stream, meta, workspace, hip_stream);
+}
+
+static int check_csr_shape(int64_t n_rows, int64_t n_cols)
+{
+    if (n_rows <= 0 || n_cols <= 0 || n_cols >= ((int64_t)1 << 31) || n_rows > (((int64_t)1 << 31) - 1) / n_cols) return SLICER_EINVAL;
+    return SLICER_OK;
+}
+
+int slicer_sizes_csr(slicer_dtype dt, int64_t instances, int64_t n_rows, int64_t n_cols, double keep_ratio, int n_blocks,
+                     uint32_t bit_set, size_t* stream_capacity_bytes, size_t* meta_bytes_out, size_t* workspace_bytes)
+{
+    int rc = check_csr_shape(n_rows, n_cols);
+    if (rc) return rc;
+    rc = check_args((int)dt, instances, n_rows * n_cols, keep_ratio, n_blocks, bit_set);
+    if (rc) return rc;
+    Plan p = make_plan((int)dt, instances, n_rows * n_cols, keep_ratio, n_blocks, n_blocks, bit_set, n_cols);
+    if (stream_capacity_bytes) *stream_capacity_bytes = (size_t)(p.cap_words * 4ull * (u64)instances);
+    if (meta_bytes_out) *meta_bytes_out = meta_bytes(instances, 2 * n_blocks);
+    if (workspace_bytes) *workspace_bytes = p.total;
+    return SLICER_OK;
+}
+
+int slicer_encode_csr(const void* x, slicer_dtype dt, int64_t instances, int64_t n_rows, int64_t n_cols, double keep_ratio,
+                      int n_blocks, uint32_t bit_set, double distortion_budget, void* stream, void* meta, void* workspace,
+                      void* hip_stream)
+{
+    int rc = check_csr_shape(n_rows, n_cols);
+    if (rc) return rc;
+    Ladder none;
+    none.on = 0;
+    for (int j = 0; j < kMaxBlocks / 8; ++j) none.nib[j] = 0;
+    return encode_impl(x, dt, instances, n_rows * n_cols, keep_ratio, n_blocks, n_blocks, bit_set, distortion_budget, none, 0,
+                       stream, meta, workspace, hip_stream, 0.0, n_cols);
+}
+
+static int launch_decode_csr(const void* stream, const void* meta, void* y, int dt, int64_t instances, int64_t n_rows,
+                             int64_t n_cols, int n_blocks, int n_blocks_neg, hipStream_t st)
+{
+    DecCsrArgs da;
+    da.stream = (const u32*)stream; da.y = y;
+    da.R = instances; da.n_rows = n_rows; da.n_cols = n_cols;
+    da.M = n_blocks; da.Mn = n_blocks_neg; da.wc = index_bits(n_cols);
+    da.mv = meta_view(const_cast<void*>(meta), instances, n_blocks + n_blocks_neg);
+    da.k_keep = (const u64*)meta + 4;
+    const u64 grid = (u64)instances * (u64)n_rows;
+    if (grid >= (1ull << 31)) return SLICER_EINVAL;
+    const bool timed = g_ev_start && g_ev_stop;
+    if (timed) SLICER_HIP(hipEventRecord(g_ev_start, st));
+    if (dt == SLICER_F32) hipLaunchKernelGGL((dec_csr_kernel<0>), dim3((unsigned)grid), dim3(256), 0, st, da);
+    else hipLaunchKernelGGL((dec_csr_kernel<1>), dim3((unsigned)grid), dim3(256), 0, st, da);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e);
+    if (timed) SLICER_HIP(hipEventRecord(g_ev_stop, st));
+    return SLICER_OK;
+}
+
+int slicer_decode_as_csr(const void* stream, const void* meta, void* y, slicer_dtype dt, int64_t instances, int64_t n_rows,
+                         int64_t n_cols, int n_blocks, void* hip_stream)
+{
+    int rc = check_csr_shape(n_rows, n_cols);
+    if (rc) return rc;
+    rc = check_shape((int)dt, instances, n_rows * n_cols, n_blocks);
+    if (rc) return rc;
+    if (!stream || !meta || !y) return SLICER_EINVAL;
+    return launch_decode_csr(stream, meta, y, (int)dt, instances, n_rows, n_cols, n_blocks, n_blocks, (hipStream_t)hip_stream);
 }
 
 int slicer_encode_atkf(const void* x, slicer_dtype dt, int64_t rows, int64_t row_len, double keep_ratio, double lambda,
@@ -607,6 +690,11 @@ int slicer_decode(const void* stream, const void* meta, void* y, void* hip_strea
     const int Mn = h32[14] ? (int)h32[14] : M;           // 0: the negative class has M blocks too
     rc = check_shape(dt, rows, row_len, M);
     if (rc || Mn < 1 || Mn > SLICER_MAX_BLOCKS) return SLICER_EFORMAT;
+    if (h32[15]) {                                        // two-dimensional instances: blocks stored as CSR triples
+        const int64_t n_cols = (int64_t)h32[15];
+        if (row_len % n_cols || (int)h32[11] != index_bits(n_cols)) return SLICER_EFORMAT;
+        return launch_decode_csr(stream, meta, y, dt, rows, row_len / n_cols, n_cols, M, Mn, st);
+    }
     if ((int)h32[11] != index_bits(row_len)) return SLICER_EFORMAT;
     return launch_decode(stream, meta, y, dt, rows, row_len, M, Mn, st);
 }

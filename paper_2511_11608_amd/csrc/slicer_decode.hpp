@@ -232,6 +232,97 @@ __global__ __launch_bounds__(256) void meta_check_kernel(CheckArgs a)
     if (bad) atomicOr(a.flag, bad);
 }
 
+// ---- two-dimensional instances: blocks stored as CSR triples (Sec. 3.2 step 3) ------------------
+// One workgroup per tensor row of an instance.  The row pointers of every block give the block's
+// entries that lie in this tensor row directly (no search); their columns and codes are read, the
+// values de-quantised (Eq. "dequnt") and placed into an LDS image of the row (a piece of it when the
+// row is longer than the image), which leaves with coalesced stores: every output element is
+// written exactly once.
+struct DecCsrArgs {
+    const u32* stream;
+    void* y;
+    int64_t R, n_rows, n_cols;     // R instances of n_rows x n_cols
+    int M, Mn, wc;
+    MetaView mv;
+    const u64* k_keep;             // header field k: fixes the width of a row pointer
+};
+
+constexpr int kCsrImage = 8192;    // elements of the LDS image
+
+template <int DT>
+__global__ __launch_bounds__(256) void dec_csr_kernel(DecCsrArgs a)
+{
+    typedef typename Elem<DT>::raw_t raw_t;
+    __shared__ raw_t tile[kCsrImage];
+    __shared__ float vminf[kMaxB2], stepf[kMaxB2];
+    __shared__ int qv[kMaxB2];
+    __shared__ u32 istart[kMaxB2 + 1], p_lo[kMaxB2], p_hi[kMaxB2];
+    __shared__ u64 cstart[kMaxB2 + 1];
+    const int tid = threadIdx.x;
+    const int64_t inst = (int64_t)blockIdx.x / a.n_rows, trow = (int64_t)blockIdx.x % a.n_rows;
+    const int M = a.M, B2 = a.M + a.Mn, wc = a.wc;
+    const int64_t T = a.n_rows * a.n_cols;
+    const u32* __restrict__ rw = a.stream + a.mv.row_off[inst];
+    u32 n_cls[2] = { a.mv.n_pos[inst], a.mv.n_neg[inst] };
+    if ((u64)n_cls[0] + n_cls[1] > (u64)T) n_cls[0] = n_cls[1] = 0;     // not a valid instance: write zeros
+    const u32 n = n_cls[0] + n_cls[1];
+    int wp = 1;
+    {
+        const u64 k = *a.k_keep;
+        while (wp < 32 && (1ull << wp) <= k) ++wp;
+    }
+    const u64 ptr_bits = (u64)B2 * (u64)(a.n_rows + 1) * (u64)wp;
+    if (tid < B2) {
+        const int s = tid >= M ? 1 : 0, m = tid - s * M, Ms = s ? a.Mn : M;
+        const u32 K = n_cls[s] / (u32)Ms;
+        const size_t mi = (size_t)inst * (size_t)B2 + tid;
+        const int q = a.mv.q[mi] & 0x7F;
+        qv[tid] = q;
+        const float vmin = a.mv.vmin[mi], vmax = a.mv.vmax[mi];
+        vminf[tid] = vmin;
+        stepf[tid] = __fdiv_rn(__fsub_rn(vmax, vmin), (float)((1u << q) - 1u));
+        istart[tid] = (s ? n_cls[0] : 0u) + (u32)m * K;
+        // this tensor row's share of the block: entries [r[trow], r[trow + 1]) of the block
+        const u64 pb = ((u64)tid * (u64)(a.n_rows + 1) + (u64)trow) * (u64)wp;
+        u32 lo = read_bits(rw, pb, wp), hi = read_bits(rw, pb + (u64)wp, wp);
+        const u32 cnt = (m < Ms - 1) ? K : n_cls[s] - (u32)m * K;
+        if (hi > cnt) hi = cnt;                                           // a forged pointer cannot leave the block
+        if (lo > hi) lo = hi;
+        p_lo[tid] = lo; p_hi[tid] = hi;
+    }
+    if (tid == 0) istart[B2] = n;
+    __syncthreads();
+    if (tid == 0) {
+        u64 acc = ptr_bits + (u64)n * (u64)wc;
+        for (int b = 0; b < B2; ++b) { cstart[b] = acc; acc += (u64)(istart[b + 1] - istart[b]) * (u64)qv[b]; }
+    }
+    __syncthreads();
+    raw_t* __restrict__ yrow = (raw_t*)a.y + (size_t)inst * (size_t)T + (size_t)trow * (size_t)a.n_cols;
+    for (int64_t c0 = 0; c0 < a.n_cols; c0 += kCsrImage) {
+        const int len = (int)(a.n_cols - c0 < kCsrImage ? a.n_cols - c0 : kCsrImage);
+        for (int i = tid; i < len; i += 256) tile[i] = (raw_t)0;
+        __syncthreads();
+        for (int b = 0; b < B2; ++b) {
+            const int q = qv[b];
+            const float vmin = vminf[b], step = stepf[b];
+            const u32 sign = b >= M ? 1u : 0u;
+            for (u32 p = p_lo[b] + (u32)tid; p < p_hi[b]; p += 256) {
+                const u32 e = istart[b] + p;
+                const int64_t col = (int64_t)read_bits(rw, ptr_bits + (u64)e * (u64)wc, wc) - c0;
+                if (col < 0 || col >= len) continue;
+                const u32 c = read_bits(rw, cstart[b] + (u64)p * (u64)q, q);
+                float v = __fadd_rn(vmin, __fmul_rn((float)c, step));
+                if (sign) v = -v;
+                if (DT == 0) tile[col] = (raw_t)__float_as_uint(v);
+                else tile[col] = (raw_t)f32_to_bf16_rne(v);
+            }
+        }
+        __syncthreads();
+        for (int i = tid; i < len; i += 256) yrow[c0 + i] = tile[i];
+        __syncthreads();
+    }
+}
+
 // ---- short rows: one wavefront per row, no workgroup barrier ---------------------------
 // Lane b * lpb + sub (lpb = 64 / 2M lanes per block) decodes entries sub, sub + lpb, ... of
 // block b, so neighbouring lanes read neighbouring bit fields; block offsets come from one

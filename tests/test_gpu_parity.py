@@ -444,3 +444,49 @@ def test_check_accepts_encoder_output_and_rejects_forged_meta(oracle):
     expect_reject(forged(lambda m: m.__setitem__(o_q + 7, int(good[o_q + 7]) ^ 1 if (int(good[o_q + 7]) ^ 1) in range(2, 9) else 8 if good[o_q + 7] != 8 else 7)))
     expect_reject(meta, words, torch.empty((R, 2048), dtype=torch.bfloat16, device="cuda"))          # other row length
     expect_reject(meta, words, y, M + 1)
+
+
+def check_csr(oracle, x, dtype, n_rows, n_cols, keep, M, bits, budget):
+    import torch
+    from paper_2511_11608_amd import binding
+    from paper_2511_11608_amd.devmem import to_device, to_host
+    xd = to_device(x, dtype)
+    s_ref, m_ref = oracle.encode_csr(x, dtype, n_rows, n_cols, keep, M, bits, budget, n_threads=8)
+    y_ref = oracle.decode(s_ref, m_ref, n_threads=8)
+    sb, meta, ws = binding.alloc_buffers_csr(xd, n_rows, n_cols, keep, M, bits)
+    ws.fill_(0x7E); sb.fill_(-1); meta.fill_(0xFF)
+    binding.slicer_encode_csr(xd, n_rows, n_cols, keep, M, bits, budget, sb, meta, ws)
+    words = binding.slicer_stream_words(meta)
+    m_gpu = meta.cpu().numpy()
+    s_gpu = sb[:words].cpu().numpy().view(np.uint32)
+    assert np.array_equal(m_ref[:64], m_gpu[:64]), (streamfmt.header(m_ref), streamfmt.header(m_gpu))
+    assert np.array_equal(m_ref, m_gpu) and np.array_equal(s_ref, s_gpu)
+    yv = np.uint32 if dtype == "f32" else np.uint16
+    for via_header in (True, False):
+        y = torch.full_like(xd, 7.0)
+        if via_header:
+            binding.slicer_decode(sb, meta, y)
+        else:
+            binding.slicer_decode_as_csr(sb, meta, y, n_rows, n_cols, M)
+        torch.cuda.synchronize()
+        assert np.array_equal(y_ref.view(yv), to_host(y).view(yv))
+
+
+@pytest.mark.parametrize("dtype,inst,n_rows,n_cols", [("f32", 1, 64, 3136), ("f32", 3, 197, 768), ("bf16", 2, 128, 4096),
+                                                      ("f32", 2, 5, 7), ("bf16", 4, 1, 1000), ("f32", 2, 1000, 1),
+                                                      ("bf16", 1, 3, 20000), ("f32", 1, 2048, 100)])
+def test_two_dimensional_instances_csr(oracle, dtype, inst, n_rows, n_cols):
+    """Sec. 3.2 step 3: whole n_rows x n_cols tensors as one instance, blocks stored as CSR(values, columns,
+    row pointers); the first shape is the CNN map of workload 1 as 64 channels x 56*56, the second a ViT
+    image (197 tokens x 768), the third an LLM slab (128 tokens x 4096).  Stream, meta and the decoded
+    tensor bit for bit against the oracle, through both decode entry points."""
+    T = n_rows * n_cols
+    rng = np.random.default_rng(T + inst)
+    x = rng.standard_normal((inst, T)).astype(np.float32)
+    x[rng.random((inst, T)) < 0.45] = 0
+    x[:, :: 211] *= np.float32(25)
+    x[-1, : T // 3] = 0                                   # empty tensor rows
+    if dtype == "bf16":
+        x = synth.f32_to_bf16_bits(x)
+    for keep, M, bits, budget in ((0.1, 4, B28, 1e-3), (0.5, 8, B28, 5e-4), (1.0, 3, (1 << 3) | (1 << 16), 1e-6), (0.0, 2, B28, 1e-3)):
+        check_csr(oracle, x, dtype, n_rows, n_cols, keep, M, bits, budget)
