@@ -214,7 +214,7 @@ def measure_workload(which: int, ev: "HipEvents", threads: int, cpu_seconds: flo
     _, meta_bytes, _ = binding.slicer_sizes(dt, wl.rows, wl.row_len, keep, M, bits)
     out_bytes = 4 * words + meta_bytes
     path = binding.slicer_encode_path(dt, wl.rows, wl.row_len, keep, M, bits)
-    kernel = {0: "enc_generic_kernel", 1: "enc_small_kernel", 2: "lr_* stages (hist..pack)"}[path]
+    kernel = {0: "enc_generic_kernel", 1: "enc_small_kernel", 2: "lr_* stages (hist..pack)", 3: "enc_wg_kernel"}[path]
     alg = in_bytes + out_bytes
     rec = {
         "workload": f"{wl.name} [{wl.rows}x{wl.row_len}] keep={keep} M={M} bits=2..8 budget={beta}",
@@ -504,7 +504,7 @@ def main() -> int:
                                       wl.rows, wl.row_len, keep, M, bits)
     if args.lam is not None and args.lam > 0 and not (wl.dtype == "bf16" and path == 1):
         path = 0                                         # the second selection: row-resident kernel for bf16 rows, else the generic kernel
-    enc_kernel = {0: "enc_generic_kernel", 1: "enc_small_kernel", 2: "lr_* stages (hist..pack)"}[path]
+    enc_kernel = {0: "enc_generic_kernel", 1: "enc_small_kernel", 2: "lr_* stages (hist..pack)", 3: "enc_wg_kernel"}[path]
     dec_kernel = "dec_small_kernel" if wl.row_len * (4 if wl.dtype == "f32" else 2) <= 16384 else "dec_kernel"
     enc_alg_bytes = in_bytes + out_bytes                 # read x once, write stream + meta
     dec_alg_bytes = out_bytes + in_bytes                 # read stream + meta, write y once

@@ -243,7 +243,9 @@ int slicer_bound(slicer_dtype dt, int64_t rows, int64_t row_len, double keep_rat
  * Which kernel family slicer_encode uses for a shape (for benchmarks and profiles, which
  * name the dominant kernel): 0 = generic (one workgroup per row, any shape), 1 = row-resident
  * (one wavefront per row, rows up to 8192 bf16 / 4096 fp32 elements), 2 = long-row stages
- * (rows of more than 4096 elements that the row-resident kernel does not take).  Assumes a 16-byte aligned x.  Negative: error code.
+ * (rows of more than 4096 elements that the row-resident kernel does not take), 3 = one workgroup per row
+ * (bf16 rows of 4097..32768 elements: all of them beyond 8192, shorter ones in batches of up to 1024 rows).
+ * Assumes a 16-byte aligned x and the budget guard.  Negative: error code.
  */
 int slicer_encode_path(slicer_dtype dt, int64_t rows, int64_t row_len, double keep_ratio,
                        int n_blocks, uint32_t bit_set);

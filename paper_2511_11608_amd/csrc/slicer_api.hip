@@ -10,6 +10,7 @@
 #include "slicer_common.hpp"
 #include "slicer_encode_generic.hpp"
 #include "slicer_encode_small.hpp"
+#include "slicer_encode_wg.hpp"
 #include "slicer_encode_large.hpp"
 #include "slicer_decode.hpp"
 
@@ -67,6 +68,8 @@ struct Plan {
     size_t off_row_words, off_slots, off_kept, off_bo_idx, off_bo_val, off_fallback, off_row_local, off_chunk_tot, off_hint, total;
     // row-resident fast path (0 = not eligible)
     int small_epl, small_cap, small_region0, small_lds_bytes, small_maxs;
+    // workgroup-per-row path for bf16 rows of up to 32768 elements (0 = not eligible)
+    int wg_ept, wg_cap, wg_region0, wg_lds_bytes;
     // long-row path (large_C == 0: not eligible)
     int large_C, large_LC;
     u32 large_capL;
@@ -161,7 +164,38 @@ Plan make_plan(int dt, int64_t rows, int64_t row_len, double keep_ratio, int n_b
             p.small_maxs = maxs;
         }
     }
+    // One workgroup per row (four wavefronts share the row): bf16 rows too long for one wavefront, and
+    // rows of more than 4096 elements in batches too small to fill the chip with one wavefront each.
+    p.wg_ept = 0; p.wg_cap = 0; p.wg_region0 = 0; p.wg_lds_bytes = 0;
+    if (csr_cols == 0 && dt == SLICER_BF16 && row_len % 8 == 0 && row_len > 4096 && row_len <= 32768 && B2_all <= kWave &&
+        (row_len > 8192 || rows <= 1024)) {
+        const int64_t margin = std::max<int64_t>(64, row_len / 32);
+        const int64_t cap = std::min<int64_t>(1984, (p.k + margin + 63) / 64 * 64);
+        const int64_t region0 = small_region0_words(p.k, p.cap_words, B2_all, nq);
+        const int64_t lds = 4 * (int64_t)wg_lds_words((int)cap, (int)region0, B2_all);
+        if (p.k + 64 <= cap && lds <= 64 * 1024) {
+            p.wg_ept = row_len <= 8192 ? 32 : row_len <= 16384 ? 64 : 128;
+            p.wg_cap = (int)cap; p.wg_region0 = (int)region0; p.wg_lds_bytes = (int)lds;
+        }
+    }
     return p;
+}
+
+int launch_wg(const SmallArgs& sa, const Plan& p, hipStream_t st)
+{
+    const dim3 g((unsigned)sa.R), b(kWgThreads);
+    const size_t lds = (size_t)p.wg_lds_bytes;
+    if (sa.nq == 7) {
+        if (p.wg_ept == 32) hipLaunchKernelGGL((enc_wg_kernel<32, 7>), g, b, lds, st, sa);
+        else if (p.wg_ept == 64) hipLaunchKernelGGL((enc_wg_kernel<64, 7>), g, b, lds, st, sa);
+        else hipLaunchKernelGGL((enc_wg_kernel<128, 7>), g, b, lds, st, sa);
+    } else {
+        if (p.wg_ept == 32) hipLaunchKernelGGL((enc_wg_kernel<32, 0>), g, b, lds, st, sa);
+        else if (p.wg_ept == 64) hipLaunchKernelGGL((enc_wg_kernel<64, 0>), g, b, lds, st, sa);
+        else hipLaunchKernelGGL((enc_wg_kernel<128, 0>), g, b, lds, st, sa);
+    }
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? SLICER_OK : hip_fail(e);
 }
 
 template <int DT, int EPL, bool ASYM>
@@ -313,7 +347,7 @@ int slicer_encode_path(slicer_dtype dt, int64_t rows, int64_t row_len, double ke
     int rc = check_args((int)dt, rows, row_len, keep_ratio, n_blocks, bit_set);
     if (rc) return rc;
     Plan p = make_plan((int)dt, rows, row_len, keep_ratio, n_blocks, n_blocks, bit_set);
-    return p.small_epl ? 1 : (p.large_C ? 2 : 0);
+    return p.wg_ept ? 3 : p.small_epl ? 1 : (p.large_C ? 2 : 0);
 }
 
 static int encode_impl(const void* x, slicer_dtype dt, int64_t rows, int64_t row_len, double keep_ratio,
@@ -360,7 +394,31 @@ static int encode_impl(const void* x, slicer_dtype dt, int64_t rows, int64_t row
 
     // asymmetric thresholds need a second selection over a subset of the row: the generic kernel has it for
     // every shape, the row-resident kernel for bf16 rows (rows it flags are redone generically, same rule)
-    if ((!asym || dt == SLICER_BF16) && p.small_epl && ((uintptr_t)x & 15) == 0) {
+    const bool use_wg = p.wg_ept && !asym && guard == 0 && ((uintptr_t)x & 15) == 0;
+    if (use_wg) {
+        // one workgroup per row; rows it cannot hold are flagged and redone by the generic kernel
+        SmallArgs sa;
+        sa.x = x; sa.R = rows; sa.N = row_len; sa.k = p.k;
+        sa.M = n_blocks; sa.Mn = n_blocks_neg; sa.w = p.w; sa.nq = ea.nq;
+        for (int t = 0; t < kMaxQ; ++t) sa.qlist[t] = ea.qlist[t];
+        sa.beta = distortion_budget;
+        sa.cap_words = p.cap_words;
+        sa.row_words = ea.row_words; sa.slots = ea.slots;
+        sa.fallback = (u32*)(ws + p.off_fallback);
+        sa.mv = ea.mv;
+        sa.cap = p.wg_cap; sa.region0_words = p.wg_region0;
+        sa.lad = lad;
+        sa.guard = guard;
+        sa.one_plus = ea.one_plus; sa.one_minus = ea.one_minus;
+        sa.hint = (u32*)(ws + p.off_hint);
+        const bool timed = g_ev_start && g_ev_stop;
+        if (timed) SLICER_HIP(hipEventRecord(g_ev_start, st));
+        rc = launch_wg(sa, p, st);
+        if (rc) return rc;
+        if (timed) SLICER_HIP(hipEventRecord(g_ev_stop, st));
+        ea.only_flagged = sa.fallback;
+    }
+    if (!use_wg && (!asym || dt == SLICER_BF16) && p.small_epl && ((uintptr_t)x & 15) == 0) {
         // fast path; rows it cannot hold are flagged and redone by the generic kernel
         SmallArgs sa;
         sa.x = x; sa.R = rows; sa.N = row_len; sa.k = p.k;

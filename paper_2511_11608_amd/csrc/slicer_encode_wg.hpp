@@ -1,0 +1,677 @@
+// Row-resident encoder for rows of 4 K to 32 K bf16 elements and small batches: ONE WORKGROUP
+// (four wavefronts) PER ROW.  A single wavefront needs about 30 us for an 8192-element row,
+// nearly all of it dependent-instruction and LDS latency, and a batch of a few hundred rows
+// (one auto-regressive decode step of Sec. 2.1, one hidden state per client) leaves three
+// quarters of the SIMDs idle; here the four wavefronts of a workgroup share the row.
+//
+// Same method and same data structures as the one-wavefront kernel (slicer_encode_small.hpp):
+// comps "key, inverted index, class bit" order everything; a 2048-bin LDS histogram over a window
+// that hangs from the row's largest key gives the bin of rank k-1 (ATKF, Sec. 3.1); everything at
+// or above it is compacted, in index order, into a list; the list is bucketed into 1024 fine bins,
+// the top-K cut and the block boundaries (MS, Sec. 3.2) are order statistics located over the bins
+// and resolved inside their bin; an entry's block is the number of boundaries above it; a stable
+// split by block, integer ABQ sums (Sec. 3.2.1), bitwidth choice, packing through an LDS image.
+// What changes is who does what: per-element passes and per-entry passes are dealt to the four
+// wavefronts (thread t owns 16-byte chunks t, t + 256, ...; wavefront v owns list slots v, v + 4,
+// ...), scans run over the workgroup, the two short serial steps (cut, boundaries) run on
+// wavefront 0, and workgroup barriers separate the stages.
+//
+// bf16 rows, budget guard or fixed ladder; rows it cannot hold are flagged for the generic kernel.
+#pragma once
+
+#include "slicer_encode_small.hpp"
+
+namespace slicer {
+
+constexpr int kWgThreads = 256;
+constexpr int kWgWaves = kWgThreads / kWave;
+constexpr int kWgSlots = 8;            // list slots (64 entries) per wavefront: lists of up to 2048 entries
+
+// words of LDS: the one-wavefront layout (list in LDS) followed by the workgroup's own tables
+__host__ __device__ inline int wg_main_words(int cap, int region0, int B2)
+{
+    return small_lds_words(1, cap, region0, B2, 0);
+}
+__host__ __device__ inline int wg_lds_words(int cap, int region0, int B2)
+{
+    // misc (32), chunk totals and their prefix (2 x 64), per-slot per-block counts as 16-bit (cap / 64 slots)
+    return wg_main_words(cap, region0, B2) + 32 + 128 + ((cap / kWave) * B2 + 1) / 2 + 2;
+}
+
+template <int EPT, int NQ>
+__global__ __launch_bounds__(kWgThreads) void enc_wg_kernel(SmallArgs a)
+{
+    typedef u32 comp_t;
+    constexpr comp_t kClsBit = 0x80000000u;          // set for the positive class
+    constexpr int kRegThr = 14;
+    constexpr int QN = NQ ? NQ : kMaxQ;
+    constexpr int EPC = 8, NCH = EPT / EPC;          // 16-byte chunks per thread
+    static_assert(NCH * kWgWaves <= kWave, "chunk totals are scanned by one wavefront");
+    extern __shared__ u32 smem[];
+
+    const u32 tid = threadIdx.x, lane = lane_id(), wv = tid / kWave;
+    const int64_t r = (int64_t)blockIdx.x;
+    if (r >= a.R) return;
+    const int N = (int)a.N, M = a.M, Mn = a.Mn, w = a.w, B2 = a.M + a.Mn, nq = NQ ? NQ : a.nq, cap = a.cap;
+    const int k = (int)a.k;
+    SmallLds L = small_carve(smem, 1, cap, a.region0_words, B2, 0);
+    u32* misc = smem + wg_main_words(cap, a.region0_words, B2);      // broadcast words and scan scratch
+    u32* ctab = misc + 32;                                           // [NCH][4] chunk totals per wavefront, then their prefixes
+    uint16_t* stab = (uint16_t*)(ctab + 128);                        // [slot][B2] entries of block b in slot s
+    auto give_up = [&]() { if (tid == 0) a.fallback[r] = 1u; };      // callers return right after, all threads alike
+    if (__builtin_amdgcn_groupstaticsize() != 0u) {                  // integer LDS addresses assume offset 0
+        give_up();
+        return;
+    }
+    const u32 lent_off = (u32)(L.Lent - smem) * 4u;
+
+    // ---- 1. load the row ---------------------------------------------------------------------
+    const uint4* __restrict__ xr = (const uint4*)((const char*)a.x + (size_t)r * (size_t)N * 2);
+    uint4 v[NCH];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        const int base = (c * kWgThreads + (int)tid) * EPC;
+        v[c] = base < N ? xr[c * kWgThreads + tid] : make_uint4(0, 0, 0, 0);
+    }
+    auto word_of = [&](int c, int d) -> u32 { return d == 0 ? v[c].x : d == 1 ? v[c].y : d == 2 ? v[c].z : v[c].w; };
+
+    // List length and positions for a lower key bound t_lo: counts per chunk, positions inside the
+    // wavefront (three chunk counts share a scan: 10-bit fields, at most 512 keys per wavefront and
+    // chunk), then the wavefronts' chunk totals are scanned in chunk order by wavefront 0.
+    u32 t_lo = 1u, nL = 0;
+    u32 cntc[NCH], basec[NCH];
+    auto count_pass = [&]() {
+        const u32 C16 = (0x8000u - t_lo) * 0x10001u;             // bit 15 / 31 of (key + C16) <=> key >= t_lo
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            u32 n1 = 0;
+#pragma unroll
+            for (int d = 0; d < 4; ++d) n1 += (u32)__popc(((word_of(c, d) & 0x7FFF7FFFu) + C16) & 0x80008000u);
+            cntc[c] = n1;
+        }
+#pragma unroll
+        for (int g = 0; g < (NCH + 2) / 3; ++g) {
+            u32 pk = cntc[3 * g];
+            if (3 * g + 1 < NCH) pk |= cntc[3 * g + 1] << 10;
+            if (3 * g + 2 < NCH) pk |= cntc[3 * g + 2] << 20;
+            const u32 incl = wave_scan_dpp(pk);
+            const u32 tot = bcast(incl, kWave - 1);
+            const u32 ex = incl - pk;
+#pragma unroll
+            for (int j = 0; j < 3; ++j) {
+                if (3 * g + j < NCH) {
+                    basec[3 * g + j] = (ex >> (10 * j)) & 0x3FFu;
+                    if (lane == 0) ctab[(3 * g + j) * kWgWaves + (int)wv] = (tot >> (10 * j)) & 0x3FFu;
+                }
+            }
+        }
+        __syncthreads();
+        if (wv == 0) {
+            const u32 t = (int)lane < NCH * kWgWaves ? ctab[lane] : 0u;
+            const u32 incl = wave_scan_dpp(t);
+            ctab[64 + lane] = incl - t;
+            if (lane == kWave - 1) misc[4] = incl;
+        }
+        __syncthreads();
+        nL = misc[4];
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) basec[c] += ctab[64 + c * kWgWaves + (int)wv];
+        __syncthreads();                             // the tables are free for the next use
+    };
+
+    // Threshold hint (see slicer_encode_small.hpp): the cut key an earlier row left in the workspace,
+    // lowered a few steps; accepted when it keeps at least k keys and not many more.  The count decides.
+    const u32 hslot = (u32)blockIdx.x & (u32)(kHintSlots - 1);
+    bool hinted = false;
+    if (k > 0) {
+        const u32 hint_key = a.hint[hslot] & 0x7FFFu;
+        t_lo = hint_key > kHintDelta ? hint_key - kHintDelta : 1u;
+        count_pass();
+        hinted = nL >= (u32)k && nL <= (u32)k + 2u * kHintSlack && (int)nL <= cap;
+    }
+
+    u32 kmax = 0;
+    if (!hinted) {
+    // largest magnitude key of the row
+    {
+        u32 mx = 0;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+#pragma unroll
+            for (int d = 0; d < 4; ++d) mx = pk_max_u16(mx, word_of(c, d) & 0x7FFF7FFFu);
+        }
+        mx = max(mx & 0xFFFFu, mx >> 16);
+        mx = wave_max_dpp(mx);
+        if (lane == 0) misc[16 + wv] = mx;
+        __syncthreads();
+        kmax = max(max(misc[16], misc[17]), max(misc[18], misc[19]));
+        __syncthreads();
+    }
+
+    // ---- coarse histogram: 2048 bins hanging from wtop, bin = (wtop - key) >> S ---------------
+    u32 wtop = kmax, above = 0;
+    int S = 0;
+    u32 B1 = 0, c_gt = 0, cnt1 = 0;
+    bool found = false;
+    const u32 rank_t = k > 0 ? (u32)(k - 1) : 0u;
+    auto hist_pass = [&](auto shift) {
+        constexpr int SH = decltype(shift)::value;
+        {
+            uint4* h4 = (uint4*)smem;
+#pragma unroll
+            for (int i = 0; i < kCoarseBins / 4 / kWgThreads; ++i) h4[i * kWgThreads + tid] = make_uint4(0, 0, 0, 0);
+            if (tid < 4) misc[tid] = 0;
+        }
+        __syncthreads();
+        const u32 wt2 = wtop * 0x10001u;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            if ((c * kWgThreads + (int)tid) * EPC < N) {
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    const u32 kp = word_of(c, d) & 0x7FFF7FFFu;
+                    u32 b = pk_sub_sat_u16(wt2, kp);
+                    if (SH) b = pk_shr_u16(b, SH);
+                    b = pk_shl_u16(pk_min_u16(b, (u32)(kCoarseBins - 1) * 0x10001u), 2);
+                    lds_inc(b & 0xFFFFu, 1u);
+                    lds_inc(b >> 16, 1u);
+                }
+            }
+        }
+        __syncthreads();
+        if (above && tid == 0) smem[0] -= above;     // keys above the window were counted in bin 0
+        __syncthreads();
+        // scan from the top: every thread sums 8 bins; the thread that holds the rank opens them
+        constexpr int BPT = kCoarseBins / kWgThreads;
+        u32 cs[BPT];
+        {
+            const uint4* h4 = (const uint4*)(smem + (int)tid * BPT);
+            const uint4 t0 = h4[0], t1 = h4[1];
+            cs[0] = t0.x; cs[1] = t0.y; cs[2] = t0.z; cs[3] = t0.w; cs[4] = t1.x; cs[5] = t1.y; cs[6] = t1.z; cs[7] = t1.w;
+        }
+        u32 local = 0;
+#pragma unroll
+        for (int j = 0; j < BPT; ++j) local += cs[j];
+        u32 total;
+        const u32 excl = block_excl_scan<kWgThreads>(local, misc + 20, &total);
+        const u32 rem = rank_t - above;
+        if (local > 0 && excl <= rem && rem < excl + local) {
+            u32 acc = excl;
+#pragma unroll
+            for (int j = 0; j < BPT; ++j) {
+                if (acc <= rem && rem < acc + cs[j]) { misc[0] = tid * BPT + j; misc[1] = acc; misc[2] = cs[j]; misc[3] = 1u; }
+                acc += cs[j];
+            }
+        }
+        __syncthreads();
+        found = misc[3] != 0u;
+        if (found) { B1 = misc[0]; c_gt = misc[1]; cnt1 = misc[2]; }
+        __syncthreads();
+    };
+    hist_pass(std::integral_constant<int, 0>());
+    if (found && B1 == (u32)(kCoarseBins - 1) && wtop > (u32)(kCoarseBins - 1)) {
+        above = c_gt;
+        wtop -= (u32)(kCoarseBins - 1);
+        S = 4;
+        hist_pass(std::integral_constant<int, 4>());
+    }
+    c_gt += above;
+    const long long lowk = (long long)wtop - ((long long)(B1 + 1u) << S) + 1;
+    t_lo = lowk > 1 ? (u32)lowk : 1u;                            // smallest non-zero key of bin B1
+    if (k > 0 && lowk >= 1 && (int)(c_gt + cnt1) > cap) {
+        give_up();
+        return;
+    }
+    if (k > 0) count_pass();
+    }   // !hinted
+
+
+    // ---- 2. ordered compaction into the list (ascending index) -----------------------------------
+    if (k == 0) nL = 0;
+    if (k > 0) {
+        const u32 C16 = (0x8000u - t_lo) * 0x10001u;
+        if ((int)nL > cap) {                                      // uniform
+            give_up();
+            return;
+        }
+        u32 linv = 0xFFFFu - tid * (u32)EPC;
+        asm volatile("" : "+v"(linv));
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            u32 wa = lent_off + basec[c] * 4u;
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                const u32 wd = word_of(c, d);
+                const u32 f = (wd & 0x7FFF7FFFu) + C16;
+                u32 f0 = (f >> 15) & 1u, f1 = f >> 31;
+                asm volatile("" : "+v"(f0));
+                asm volatile("" : "+v"(f1));
+                const u32 i0 = linv - (u32)(c * kWgThreads * EPC + 2 * d), i1 = linv - (u32)(c * kWgThreads * EPC + 2 * d + 1);
+                if (f0) *lds_at(wa) = (wd << 16) | i0;
+                wa += f0 << 2;
+                asm volatile("" : "+v"(wa));
+                if (f1) *lds_at(wa) = __builtin_amdgcn_perm(wd, i1, 0x07060100u);   // wd's high half : i1's low half
+                wa += f1 << 2;
+                asm volatile("" : "+v"(wa));
+            }
+        }
+    }
+    __syncthreads();
+    // wavefront v takes list slots v, v + 4, ...: entries into registers (sign, key, inverted index in one word)
+    const int nslots = (int)((nL + kWave - 1) / kWave);
+    u32 ent[kWgSlots];
+#pragma unroll
+    for (int j = 0; j < kWgSlots; ++j) {
+        const u32 p = (u32)(j * kWgWaves + (int)wv) * kWave + lane;
+        ent[j] = p < nL ? L.Lent[p] : 0u;
+    }
+    if (hinted) {                                                 // the row's largest key is the list's largest
+        u32 mx = 0;
+#pragma unroll
+        for (int j = 0; j < kWgSlots; ++j) mx = max(mx, ent[j] & 0x7FFFFFFFu);
+        mx = wave_max_dpp(mx) >> 16;
+        if (lane == 0) misc[16 + wv] = mx;
+    }
+    __syncthreads();                                              // (the histogram region overlays the list's neighbours)
+    if (hinted) kmax = max(max(misc[16], misc[17]), max(misc[18], misc[19]));
+    {
+        uint4* h4 = (uint4*)L.hist;
+        if (tid < kFineBins / 4) h4[tid] = make_uint4(0, 0, 0, 0);
+        if (tid < 16) misc[tid] = 0;
+        if ((int)tid < QN && (NQ || (int)tid < nq)) L.qtab[tid] = (u32)a.qlist[tid];
+        for (int i = (int)tid; i < (nslots * B2 + 1) / 2; i += kWgThreads) ((u32*)stab)[i] = 0;
+    }
+    __syncthreads();
+
+    // ---- 3. fine bins: 1024 bins linear in (key - t_lo) >> sh, both classes packed 11 + 11 bits --------
+    const u32 range = kmax > t_lo ? kmax - t_lo : 0u;
+    const int sh = range < (u32)kFineBins ? 0 : (32 - __clz((int)range)) - 10;
+#pragma unroll
+    for (int j = 0; j < kWgSlots; ++j) {
+        const u32 p = (u32)(j * kWgWaves + (int)wv) * kWave + lane;
+        if (p < nL) {
+            const u32 e = ent[j];
+            lds_inc(((((e >> 16) & 0x7FFFu) - t_lo) >> sh) << 2, (e >> 31) ? 0x800u : 1u);
+        }
+    }
+    __syncthreads();
+    u32 n_pos, n_neg;
+    {   // exclusive prefix from the top in the counting format pos | neg << 11 (fill << 22 is added later)
+        constexpr int FPT = kFineBins / kWgThreads;     // 4
+        const int hi = kFineBins - (int)tid * FPT;
+        const uint4 t = *(const uint4*)(L.hist + hi - FPT);
+        const u32 cs[FPT] = { t.w, t.z, t.y, t.x };
+        u32 local = 0, big = 0;
+#pragma unroll
+        for (int j = 0; j < FPT; ++j) { local += cs[j]; big |= ((cs[j] & 0x7FFu) + (cs[j] >> 11)) >> 10; }
+        if (nL >= 1024u && big != 0u) misc[10] = 1u;        // a fine bin with 1024+ members overflows its 10-bit fill field
+        __syncthreads();                                    // (no library reduction here: it would bring static LDS)
+        if (misc[10]) {
+            give_up();
+            return;
+        }
+        u32 tot;
+        const u32 excl = block_excl_scan<kWgThreads>(local, misc + 20, &tot);
+        n_pos = tot & 0x7FFu; n_neg = tot >> 11;
+        const u32 incl = excl + local;
+        const u32 ov_ex = (excl & 0x7FFu) + (excl >> 11), ov_in = (incl & 0x7FFu) + (incl >> 11);
+        if (k > 0 && ov_ex <= (u32)(k - 1) && (u32)(k - 1) < ov_in) misc[5] = tid;     // the thread whose bins hold overall rank k-1
+        u32 acc = excl, o[FPT];
+#pragma unroll
+        for (int j = 0; j < FPT; ++j) { o[j] = acc; acc += cs[j]; }
+        *(uint4*)(L.hist + hi - FPT) = make_uint4(o[3], o[2], o[1], o[0]);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < kWgSlots; ++j) {
+        const u32 p = (u32)(j * kWgWaves + (int)wv) * kWave + lane;
+        if (p < nL) {
+            const u32 e = ent[j];
+            const u32 rel = ((e >> 16) & 0x7FFFu) - t_lo;
+            const u32 old = atomicAdd(&L.hist[rel >> sh], 1u << 22);
+            L.S[(old & 0x7FFu) + ((old >> 11) & 0x7FFu) + (old >> 22)] = e;
+        }
+    }
+    __syncthreads();
+    auto s_plain = [&](u32 s) -> u32 { return s & 0x7FFFFFFFu; };
+    auto s_neg = [&](u32 s) -> u32 { return s >> 31; };
+
+    // ---- top-K cut and block boundaries: wavefront 0 ------------------------------------------------
+    const int ntg = B2 - 2;
+    comp_t* thr = (comp_t*)L.thr;
+    if (wv == 0) {
+        comp_t thrK = 0;                                // plain comp; every entry of the list is kept when nL <= k
+        if (nL > (u32)k) {
+            constexpr int FPT = kFineBins / kWgThreads;
+            const int hi = kFineBins - (int)misc[5] * FPT;
+            const u32 wj = lane < (u32)FPT ? L.hist[hi - 1 - (int)lane] : 0xFFFFFFFFu;
+            const u64 mj = __ballot(lane < (u32)FPT && (wj & 0x7FFu) + ((wj >> 11) & 0x7FFu) <= (u32)(k - 1));
+            const int lo = hi - (int)__popcll(mj);
+            const u32 wd = L.hist[lo];
+            const u32 pe = wd & 0x7FFu, ne = (wd >> 11) & 0x7FFu, cnt = wd >> 22, base = pe + ne;
+            const u32 rem = (u32)(k - 1) - base;
+            u32 kp = 0, kn = 0;
+            for (u32 g = 0; g < cnt; g += kWave) {
+                const u32 i = g + lane;
+                u32 me = 0, gt = 0;
+                if (i < cnt) {
+                    me = L.S[base + i];
+                    for (u32 j = 0; j < cnt; ++j) gt += s_plain(L.S[base + j]) > s_plain(me) ? 1u : 0u;
+                }
+                const bool in = i < cnt && gt <= rem;
+                kp += (u32)__popcll(__ballot(in && !s_neg(me)));
+                kn += (u32)__popcll(__ballot(in && s_neg(me)));
+                const u64 hit = __ballot(i < cnt && gt == rem);
+                if (hit) thrK = (comp_t)bcast(s_plain(me), (int)__builtin_ctzll(hit));
+            }
+            n_pos = pe + kp; n_neg = ne + kn;
+        }
+        const u32 Kc[2] = { n_pos / (u32)M, n_neg / (u32)Mn };
+        if (lane == 0) { misc[6] = thrK; misc[7] = n_pos; misc[8] = n_neg; }
+        // boundaries: comps of class ranks j*K-1, one lane per boundary
+        const int ntp = ntg > 0 ? ntg : 1;
+        u32* tg_bin = L.tg; u32* tg_base = L.tg + ntp; u32* tg_cnt = L.tg + 2 * ntp; u32* tg_rem = L.tg + 3 * ntp; u32* tg_pre = L.tg + 4 * ntp;
+        (void)tg_bin;
+        const bool mine = (int)lane < ntg;
+        const int cls = (int)lane >= M - 1 ? 1 : 0;
+        const int jb = (cls ? (int)lane - (M - 1) : (int)lane) + 1;
+        const bool act = mine && Kc[cls] > 0;
+        const u32 Rk = act ? (u32)jb * Kc[cls] - 1u : 0u;
+        int lo = 0, hi = kFineBins - 1;                 // smallest bin whose first class rank is <= Rk
+        for (int it = 0; it < 10; ++it) {
+            const int mid = (lo + hi) >> 1;
+            const u32 wd = L.hist[mid];
+            const u32 pc = cls ? (wd >> 11) & 0x7FFu : wd & 0x7FFu;
+            if (pc <= Rk) hi = mid; else lo = mid + 1;
+        }
+        const u32 wd = L.hist[lo];
+        const u32 pe = wd & 0x7FFu, ne = (wd >> 11) & 0x7FFu;
+        const u32 cnt = act ? wd >> 22 : 0u;
+        const u32 incl = wave_scan_dpp(cnt);
+        if (mine) {
+            tg_base[lane] = pe + ne; tg_cnt[lane] = cnt;
+            tg_rem[lane] = Rk - (cls ? ne : pe);
+            tg_pre[lane] = incl - cnt;
+            if (!act) thr[lane] = cls ? (comp_t)(kClsBit - 1) : ~(comp_t)0;
+        }
+        const u32 npairs = bcast(incl, kWave - 1);
+        wave_sync();
+        for (u32 g = 0; g < npairs; g += kWave) {
+            const u32 pr = g + lane;
+            if (pr < npairs) {
+                int tl = 0, th = ntg - 1;
+                while (tl < th) {
+                    const int mid = (tl + th + 1) >> 1;
+                    if (tg_pre[mid] <= pr) tl = mid; else th = mid - 1;
+                }
+                const int t = tl;
+                const u32 tc = (u32)(t >= M - 1 ? 1 : 0);
+                const u32 bs = tg_base[t], cn = tg_cnt[t];
+                const u32 me = L.S[bs + (pr - tg_pre[t])];
+                if (s_neg(me) == tc) {
+                    const u32 fm = tc ? 0u : 0x80000000u;     // same class and larger comp = plain unsigned "larger"
+                    const u32 mk = me ^ fm;
+                    u32 gt = 0;
+                    for (u32 jj = 0; jj < cn; ++jj) gt += (L.S[bs + jj] ^ fm) > mk ? 1u : 0u;
+                    if (gt == tg_rem[t]) thr[t] = (comp_t)(me ^ 0x80000000u);
+                }
+            }
+        }
+    }
+    __syncthreads();
+    const comp_t thrK = (comp_t)misc[6];
+    n_pos = misc[7]; n_neg = misc[8];
+    const u32 n = n_pos + n_neg;
+    const u32 Kc[2] = { n_pos / (u32)M, n_neg / (u32)Mn };
+    if ((int)tid < B2) {
+        const int s = (int)tid >= M ? 1 : 0, m = (int)tid - s * M;
+        L.blk_start[tid] = (s ? n_pos : 0u) + (u32)m * Kc[s];
+        L.vminb[tid] = 0xFFFFFFFFu; L.vmaxb[tid] = 0;
+    }
+    if (tid == 0) L.blk_start[B2] = n;
+
+    // ---- 4. blocks and stable split -----------------------------------------------------------------
+    u32* bo_val = L.S;
+    uint16_t* bo_idx = (uint16_t*)(L.hist);
+    u32* stage = L.hist + (k + 1) / 2;
+    int nbits = 0;
+    while ((1 << nbits) < B2) ++nbits;
+    comp_t tx[kRegThr];
+#pragma unroll
+    for (int j = 0; j < kRegThr; ++j) tx[j] = j < ntg ? thr[j] : (comp_t)0;
+    const bool tree8 = M == 8 && Mn == 8;
+    __syncthreads();                                 // S, the fine bins and the boundaries have been read: their storage is reused
+    u32 info[kWgSlots];                              // kept << 31 | block << 16 | entries of the same block before this one in the slot
+#pragma unroll
+    for (int j = 0; j < kWgSlots; ++j) {
+        const int slot = j * kWgWaves + (int)wv;
+        const u32 p = (u32)slot * kWave + lane;
+        bool kept = false;
+        u32 b = 0;
+        if (slot < nslots && p < nL) {
+            const comp_t cx = (comp_t)(ent[j] ^ 0x80000000u);
+            if ((cx & ~kClsBit) >= thrK) {
+                kept = true;
+                u32 abv;
+                if (tree8) {
+                    const bool c1 = !(cx & kClsBit);
+                    comp_t m = c1 ? tx[10] : tx[3];
+                    const bool c2 = m > cx;
+                    m = c1 ? (c2 ? tx[12] : tx[8]) : (c2 ? tx[5] : tx[1]);
+                    const bool c3 = m > cx;
+                    const comp_t lo4 = c3 ? (c2 ? tx[6] : tx[2]) : (c2 ? tx[4] : tx[0]);
+                    const comp_t hi4 = c3 ? (c2 ? tx[13] : tx[9]) : (c2 ? tx[11] : tx[7]);
+                    m = c1 ? hi4 : lo4;
+                    const bool c4 = m > cx;
+                    abv = (c1 ? 8u : 0u) + (c2 ? 4u : 0u) + (c3 ? 2u : 0u) + (c4 ? 1u : 0u);
+                } else {
+                    abv = (cx & kClsBit) ? 0u : 1u;
+#pragma unroll
+                    for (int t = 0; t < kRegThr; ++t) abv += tx[t] > cx ? 1u : 0u;
+                    for (int t = kRegThr; t < ntg; ++t) abv += thr[t] > cx ? 1u : 0u;
+                }
+                b = abv;
+                const u32 key = ((u32)cx >> 16) & 0x7FFFu;
+                atomicMin(&L.vminb[b], key);
+                atomicMax(&L.vmaxb[b], key);
+            }
+        }
+        if (slot < nslots) {                         // uniform in the wavefront
+            const u64 km = __ballot(kept);
+            u32 plo = (u32)km, phi = (u32)(km >> 32);
+            for (int bit = 0; bit < nbits; ++bit) {
+                const u32 onm = (u32)__builtin_amdgcn_sbfe((int)b, (u32)bit, 1u);
+                const u64 bal = __ballot(onm != 0u);
+                plo &= ~((u32)bal ^ onm);
+                phi &= ~((u32)(bal >> 32) ^ onm);
+            }
+            const u32 before = __builtin_amdgcn_mbcnt_hi(phi, __builtin_amdgcn_mbcnt_lo(plo, 0u));
+            if (kept && before == 0) stab[slot * B2 + (int)b] = (uint16_t)(__popc(plo) + __popc(phi));
+            info[j] = (kept ? 0x80000000u : 0u) | (b << 16) | before;
+        } else {
+            info[j] = 0;
+        }
+    }
+    __syncthreads();
+    if ((int)tid < B2) {                             // per block: entries in earlier slots
+        u32 acc = 0;
+        for (int s = 0; s < nslots; ++s) {
+            const u32 c = stab[s * B2 + (int)tid];
+            stab[s * B2 + (int)tid] = (uint16_t)acc;
+            acc += c;
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < kWgSlots; ++j) {
+        const int slot = j * kWgWaves + (int)wv;
+        if (info[j] >> 31) {
+            const u32 b = (info[j] >> 16) & 0x7FFFu, before = info[j] & 0xFFFFu;
+            const u32 pos = L.blk_start[b] + (u32)stab[slot * B2 + (int)b] + before;
+            const u32 e = ent[j];
+            bo_val[pos] = ((e >> 16) & 0x7FFFu) << 16;           // |x| as fp32 bits (exact widening)
+            bo_idx[pos] = (uint16_t)(0xFFFFu - (e & 0xFFFFu));
+        }
+    }
+    __syncthreads();
+
+    // ---- 5. ABQ: each block is walked by 256 / B2 threads ------------------------------------------
+    u64* sums = (u64*)(L.hist + ((((k + 1) / 2 + (int)a.cap_words) + 1) & ~1));
+    float* invt = (float*)(sums + B2 * (nq + 1));
+    const u32 lpb = (u32)kWgThreads / (u32)B2;
+    const u32 myb = udiv16(tid, lpb), sub = tid - myb * lpb;
+    const bool on = myb < (u32)B2;
+    u32 r0 = 0, r1 = 0, bs0 = 0, mycnt = 0;
+    float vmin = 0.f, rng = 0.f, rng1 = 1.f;
+    int e = 0, dg = 1, er = 0;
+    u32 vmaxbits = 0;
+    if (on) {
+        bs0 = L.blk_start[myb];
+        const u32 be = L.blk_start[myb + 1];
+        mycnt = be - bs0;
+        const u32 perb = udiv16(mycnt + lpb - 1, lpb);
+        r0 = bs0 + sub * perb; r0 = r0 < be ? r0 : be;
+        r1 = r0 + perb < be ? r0 + perb : be;
+        if (mycnt) {
+            vmaxbits = L.vmaxb[myb] << 16;
+            vmin = __uint_as_float(L.vminb[myb] << 16);
+            rng = __uint_as_float(vmaxbits) - vmin;
+            dg = !(rng > 0.f);                       // only a range of exactly 0 is degenerate
+            if (!dg) { er = range_exp(rng); rng1 = unit_range(rng, er); }
+            e = ilogb_bits(vmaxbits) + 1;
+        }
+    }
+    const u32 mc0 = n_pos - Kc[0] * (u32)(M - 1), mc1 = n_neg - Kc[1] * (u32)(Mn - 1);
+    const u32 T = udiv16((mc0 > mc1 ? mc0 : mc1) + lpb - 1, lpb);
+    __syncthreads();                                 // vminb / vmaxb / run have been read before `run` is reused below
+    if (on) {
+        for (u32 t = sub; t < (u32)nq; t += lpb) {
+            const float Lq = (float)((1u << L.qtab[t]) - 1u);
+            invt[myb * (u32)nq + t] = dg ? 0.f : Lq / rng1;
+        }
+        if (sub == 0) {
+            for (int t = 0; t <= nq; ++t) sums[myb * (nq + 1) + t] = 0;
+            L.run[myb] = (mycnt && !dg) ? (u32)nq : 0u;      // index of the chosen bitwidth, nq = none feasible yet
+        }
+    }
+    __syncthreads();
+    float inv[QN];
+    bool small_q = true;
+#pragma unroll
+    for (int t = 0; t < QN; ++t) {
+        inv[t] = (on && (NQ || t < nq)) ? invt[myb * (u32)nq + t] : 0.f;
+        if ((NQ || t < nq) && a.qlist[t] > 8) small_q = false;
+    }
+    if (!a.lad.on) {
+        // residual on the 2^-15 grid: rint(y * 2^15) reduced to 15 signed bits; bitwidths up to 8 keep
+        // y * 2^15 below 2^23, where adding 2^23 rounds to the integer grid with the same round-half-even
+        float inv15[QN];
+#pragma unroll
+        for (int t = 0; t < QN; ++t) inv15[t] = inv[t] * 32768.0f;
+        u64 accE = 0;
+        for (u32 i0 = 0; i0 < T; i0 += 8) {             // u32 partial sums hold 8 residuals of 2^28
+            u32 acc[QN];
+#pragma unroll
+            for (int t = 0; t < QN; ++t) acc[t] = 0;
+            const u32 i1 = i0 + 8 < T ? i0 + 8 : T;
+            for (u32 i = i0; i < i1; ++i) {
+                const u32 p = r0 + i;
+                if (p < r1) {
+                    const float av = __uint_as_float(bo_val[p]);
+                    const u64 A = (u64)(u32)rintf(ldexpf(av, 20 - e));   // 20-bit energy grid scaled to vmax
+                    accE += A * A;
+                    const float d = to_unit(av - vmin, er);
+#pragma unroll
+                    for (int t = 0; t < QN; ++t) {
+                        if (NQ || t < nq) {
+                            const u32 zi = small_q ? __float_as_uint(d * inv15[t] + 8388608.0f)
+                                                   : (u32)rintf((d * inv[t]) * 32768.0f);
+                            const int rho = __builtin_amdgcn_sbfe((int)zi, 0u, 15u);
+                            acc[t] += (u32)(rho * rho);
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < QN; ++t)
+                if ((NQ || t < nq) && acc[t]) atomicAdd(&sums[myb * (nq + 1) + t], (u64)acc[t]);
+        }
+        if (accE) atomicAdd(&sums[myb * (nq + 1) + nq], accE);
+    }
+    __syncthreads();
+    if (a.lad.on) {
+        if (on && sub == 0) L.run[myb] = ladder_index(a.lad, (int)(myb >= (u32)M ? myb - (u32)M : myb));
+    } else if (on && mycnt && !dg) {
+        const double rhs = a.beta * ldexp((double)sums[myb * (nq + 1) + nq], 2 * e - 40);
+        for (u32 t = sub; t < (u32)nq; t += lpb) {
+            const float Lq = (float)((1u << L.qtab[t]) - 1u);
+            const float o = rng / Lq;
+            const double lhs = ((double)o * (double)o) * (double)sums[myb * (nq + 1) + t] * 0x1p-30;
+            if (lhs <= rhs) { atomicMin(&L.run[myb], t); break; }
+        }
+    }
+    __syncthreads();
+    u32 myq = 0, flag = 0;
+    float my_inv = 0.f;
+    if (on) {
+        u32 tb = L.run[myb];
+        if (tb == (u32)nq) { flag = 0x80u; tb = (u32)nq - 1u; }   // none feasible: the largest bitwidth, flagged
+        myq = L.qtab[tb];
+        my_inv = invt[myb * (u32)nq + tb];
+    }
+    if (on && sub == 0) {
+        const size_t mi = (size_t)r * (size_t)B2 + myb;
+        a.mv.vmin[mi] = mycnt ? vmin : 0.f;
+        a.mv.vmax[mi] = mycnt ? __uint_as_float(vmaxbits) : 0.f;
+        a.mv.q[mi] = (uint8_t)(myq | flag);
+        L.thr[myb] = mycnt * myq;                    // code bits of the block (the boundaries are dead)
+    }
+    __syncthreads();
+    if (wv == 0) {                                   // bit offsets of the blocks' code sections
+        const u32 bits = (int)lane < B2 ? L.thr[lane] : 0u;
+        const u32 incl = wave_scan_dpp(bits);
+        if ((int)lane < B2) L.tg[lane] = incl - bits;
+        if (lane == kWave - 1) misc[9] = incl;
+    }
+    __syncthreads();
+    const u32 code_bits = misc[9];
+    const u32 coff = on ? L.tg[myb] : 0u;
+    const u32 idx_bits = n * (u32)w;
+    const u32 row_bits = idx_bits + code_bits;
+    u32 row_words = (row_bits + 31u) >> 5;
+    if ((u64)row_words > a.cap_words) row_words = (u32)a.cap_words;   // cannot happen (worst-case capacity)
+    __syncthreads();                                 // sums and scales have been read: the stage image overlays nothing live
+    for (u32 i = tid; i < row_words; i += kWgThreads) stage[i] = 0;
+    __syncthreads();
+
+    // ---- packing ---------------------------------------------------------------------------------
+    for (u32 i = 0; i < T; ++i) {
+        const u32 p = r0 + i;
+        if (p < r1) {
+            u32 c = 0;
+            if (!dg) c = (u32)rintf(to_unit(__uint_as_float(bo_val[p]) - vmin, er) * my_inv);   // already within [0, 2^q - 1]
+            {
+                const u32 P = __umul24(p, (u32)w), wi = P >> 5, sft = P & 31u, val = bo_idx[p];
+                atomicOr(&stage[wi], val << sft);
+                if (sft + (u32)w > 32u) atomicOr(&stage[wi + 1], val >> (32u - sft));
+            }
+            {
+                const u32 P = idx_bits + coff + __umul24(p - bs0, myq), wi = P >> 5, sft = P & 31u;
+                atomicOr(&stage[wi], c << sft);
+                if (sft + myq > 32u) atomicOr(&stage[wi + 1], c >> (32u - sft));
+            }
+        }
+    }
+    __syncthreads();
+    u32* __restrict__ slot = a.slots + (size_t)r * (size_t)a.cap_words;
+    for (u32 i = tid; i < row_words; i += kWgThreads) slot[i] = stage[i];
+    if (tid == 0) {
+        a.row_words[r] = row_words;
+        a.mv.n_pos[r] = n_pos;
+        a.mv.n_neg[r] = n_neg;
+        a.fallback[r] = 0u;
+        if (k > 0) a.hint[hslot] = nL > (u32)k ? ((u32)thrK >> 16) & 0x7FFFu : t_lo;     // this row's cut key, for a later row
+    }
+}
+
+}  // namespace slicer
