@@ -286,6 +286,8 @@ def main() -> int:
     ap.add_argument("--lam", type=float, default=None,
                     help="time the asymmetric thresholds of Sec. 3.1 at this asymmetry factor (0 < lambda < 1; bf16 rows "
                          "of up to 8192 elements on the row-resident kernel, everything else on the generic kernel)")
+    ap.add_argument("--keep-ratio", type=float, default=None, help="override the workload's keep ratio (1 - s)")
+    ap.add_argument("--n-blocks", type=int, default=None, help="override the workload's block count M per sign class")
     ap.add_argument("--streams", type=int, default=3,
                     help="HIP streams the steps alternate over (default 3): consecutive steps work on independent "
                          "batches, so step i+1 fills the ramp, the drain and the launch gaps of step i; 1 = one stream")
@@ -306,6 +308,10 @@ def main() -> int:
 
     binding.load()
     wl, xs = make_workload(args.workload)
+    if args.keep_ratio is not None:
+        wl.keep_ratio = args.keep_ratio
+    if args.n_blocks is not None:
+        wl.n_blocks = args.n_blocks
     M, bits, keep, beta = wl.n_blocks, wl.bit_set, wl.keep_ratio, wl.budget
     ladder = [int(q) for q in args.ladder.split(",")] if args.ladder else None
     if ladder:
@@ -530,7 +536,7 @@ def main() -> int:
 
     # all five configurations, each at its full size, in short single-stream loops
     workloads = None
-    plain = not (ladder or args.ds is not None or args.lam is not None)
+    plain = not (ladder or args.ds is not None or args.lam is not None or args.keep_ratio is not None or args.n_blocks is not None)
     if plain and not args.no_workloads:
         del xd, x0, bufs, ys
         torch.cuda.empty_cache()
