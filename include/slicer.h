@@ -153,8 +153,8 @@ int slicer_encode_pn(const void* x, slicer_dtype dt, int64_t rows, int64_t row_l
  * values in (tau, tau+] are never sent.  k or more (the section is silent; its exact count
  * decides): the k largest magnitudes of the set stay.  lambda = 0 is slicer_encode_pn and takes
  * its kernels; lambda > 0 needs a second selection over a subset of the row, which is built in the
- * row-resident kernel for bf16 rows (up to 8192 elements) and in the generic one-workgroup-per-row
- * kernel for everything else.  Buffers, format and decode as slicer_encode_pn;
+ * row-resident kernel (bf16 rows up to 8192 elements, fp32 rows up to 4096) and in the generic
+ * one-workgroup-per-row kernel for everything else.  Buffers, format and decode as slicer_encode_pn;
  * SLICER_EINVAL for lambda outside [0, 1).
  */
 int slicer_encode_atkf(const void* x, slicer_dtype dt, int64_t rows, int64_t row_len,

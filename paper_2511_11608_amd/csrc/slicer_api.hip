@@ -219,11 +219,9 @@ void launch_small_epl(const SmallArgs& sa, int lds_bytes, int maxs, hipStream_t 
 {
     const dim3 g((unsigned)xcd_grid(sa.R)), b(kWave);
     const size_t lds = (size_t)lds_bytes;
-    if constexpr (DT == 1) {
-        if (asym) {
-            launch_small_variant<DT, EPL, true>(sa, g, b, lds, maxs, st);
-            return;
-        }
+    if (asym) {
+        launch_small_variant<DT, EPL, true>(sa, g, b, lds, maxs, st);
+        return;
     }
     launch_small_variant<DT, EPL, false>(sa, g, b, lds, maxs, st);
 }
@@ -418,7 +416,7 @@ static int encode_impl(const void* x, slicer_dtype dt, int64_t rows, int64_t row
         if (timed) SLICER_HIP(hipEventRecord(g_ev_stop, st));
         ea.only_flagged = sa.fallback;
     }
-    if (!use_wg && (!asym || dt == SLICER_BF16) && p.small_epl && ((uintptr_t)x & 15) == 0) {
+    if (!use_wg && p.small_epl && ((uintptr_t)x & 15) == 0) {
         // fast path; rows it cannot hold are flagged and redone by the generic kernel
         SmallArgs sa;
         sa.x = x; sa.R = rows; sa.N = row_len; sa.k = p.k;
@@ -436,7 +434,7 @@ static int encode_impl(const void* x, slicer_dtype dt, int64_t rows, int64_t row
         sa.hint = (u32*)(ws + p.off_hint);
         const bool timed = g_ev_start && g_ev_stop;
         if (timed) SLICER_HIP(hipEventRecord(g_ev_start, st));
-        rc = dt == SLICER_F32 ? launch_small<0>(sa, p, st, false) : launch_small<1>(sa, p, st, asym);
+        rc = dt == SLICER_F32 ? launch_small<0>(sa, p, st, asym) : launch_small<1>(sa, p, st, asym);
         if (rc) return rc;
         if (timed) SLICER_HIP(hipEventRecord(g_ev_stop, st));
         ea.only_flagged = sa.fallback;

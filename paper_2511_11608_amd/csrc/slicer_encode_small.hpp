@@ -142,7 +142,7 @@ __device__ inline void lds_inc(u32 byte_off, u32 v)
 // NQ > 0: the number of allowed bitwidths is known at compile time (loops over the
 // candidate bitwidths unroll without predicates); NQ == 0: any number up to 16.
 // MAXS > 0: the list has at most 64 * MAXS entries and lives in registers.
-// ASYM (bf16 only): the asymmetric thresholds of Sec. 3.1 with lambda > 0.  The kept set is not a
+// ASYM: the asymmetric thresholds of Sec. 3.1 with lambda > 0.  The kept set is not a
 // plain top-K then: after the first selection has given tau, the strict set is counted, a second
 // selection over a subset of the row (the fill candidates, or the strict set when it is too large)
 // gives the last key taken, and the list is built from that rule; the equal keys at the end are cut
@@ -151,7 +151,6 @@ __device__ inline void lds_inc(u32 byte_off, u32 v)
 template <int DT, int EPL, int NQ, int MAXS, bool ASYM = false>
 __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
 {
-    static_assert(!ASYM || DT == 1, "the asymmetric fast path is built for bf16 rows");
     typedef Elem<DT> E;
     typedef typename std::conditional<DT == 0, u64, u32>::type comp_t;   // bf16: key + index fit 31 bits
     constexpr comp_t kClsBit = (comp_t)1 << (8 * sizeof(comp_t) - 1);       // set for the positive class
@@ -240,13 +239,16 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
     u32 B1 = 0, c_gt = 0, cnt1 = 0;
     bool found = false;
     u32 rank_t = k > 0 ? (u32)(k - 1) : 0u;         // the rank the pass looks for (among the keys the functor lets through)
-    auto all_keys = [](u32 wd) -> u32 { return wd & 0x7FFF7FFFu; };
+    auto all_keys = [](u32 wd) -> u32 { return wd & (DT == 0 ? 0x7FFFFFFFu : 0x7FFF7FFFu); };   // fp32: one key; bf16: a pair
     // skip0: keys that the functor turned into 0 are not counted at all (they would all meet on one
     // LDS address); the pass then reports found = false when the rank lies beyond the counted keys
-    auto hist_pass = [&](auto shift, auto key_pair, auto skip0) {
+    // windowed (fp32 narrowing passes): keys above the window or below its 2048 bins are not counted at all
+    // (they would all meet on the first or the last bin's LDS address); `above` then only enters the rank
+    auto hist_pass = [&](auto shift, auto key_pair, auto skip0, auto windowed) {
         constexpr int SH = decltype(shift)::value;
         constexpr bool kSkip0 = decltype(skip0)::value;
-        constexpr int SHB = SH >= 2 ? SH - 2 : 0;      // fp32: shift that leaves the bin number times 4 (SH is 16 or 20 there)
+        constexpr bool kWindowed = decltype(windowed)::value;
+        constexpr int SHB = SH >= 2 ? SH - 2 : 0;      // fp32: shift that leaves the bin number times 4
         {
             uint4* h4 = (uint4*)smem;
 #pragma unroll
@@ -261,9 +263,15 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
                 for (int d = 0; d < 4; ++d) {
                     const u32 wd = word_of(c, d);
                     if (DT == 0) {
-                        const u32 key = wd & 0x7FFFFFFFu;
+                        const u32 key = key_pair(wd);
                         const u32 df = wtop > key ? wtop - key : 0u;
-                        lds_inc(min((df >> SHB) & ~3u, (u32)(4 * kCoarseBins - 4)), 1u);
+                        const u32 b4 = SH >= 2 ? min((df >> SHB) & ~3u, (u32)(4 * kCoarseBins - 4))
+                                               : (min(df >> SH, (u32)(kCoarseBins - 1)) << 2);
+                        if (kWindowed) {
+                            if ((!kSkip0 || key) && key <= wtop && (df >> SH) < (u32)kCoarseBins) lds_inc(b4, 1u);
+                        } else if (!kSkip0 || key) {
+                            lds_inc(b4, 1u);
+                        }
                     } else {
                         const u32 kp = key_pair(wd);
                         u32 b = pk_sub_sat_u16(wt2, kp);
@@ -276,7 +284,7 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
             }
         }
         wave_sync();
-        if (above && lane == 0) smem[0] -= above;   // keys above the window were counted in bin 0
+        if (!kWindowed && above && lane == 0) smem[0] -= above;   // keys above the window were counted in bin 0
         wave_sync();
         // Scan from the top in two levels: every lane sums 32 bins, the lane that holds the rank
         // is then opened bin by bin.
@@ -352,15 +360,16 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
         count_plain();
         hinted = nL >= (u32)k && nL <= (u32)k + kHintSlack && (int)nL <= cap;
     }
-    if (!hinted) {
+    if (!hinted && ASYM && DT == 0) row_kmax();      // (its selections run further down)
+    if (!hinted && !(ASYM && DT == 0)) {
         row_kmax();
         wtop = kmax;
-        hist_pass(std::integral_constant<int, S1>(), all_keys, std::false_type());
+        hist_pass(std::integral_constant<int, S1>(), all_keys, std::false_type(), std::false_type());
         if (found && B1 == (u32)(kCoarseBins - 1) && (wtop >> S1) > (u32)(kCoarseBins - 1)) {
             above = c_gt;
             wtop -= (u32)(kCoarseBins - 1) << S1;
             S = S1 + 4;
-            hist_pass(std::integral_constant<int, S1 + 4>(), all_keys, std::false_type());
+            hist_pass(std::integral_constant<int, S1 + 4>(), all_keys, std::false_type(), std::false_type());
         }
         c_gt += above;
     }
@@ -384,7 +393,78 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
         asm volatile("" : "+v"(wd));
         return (st ^ kOne2) & (gt01(wd & 0x7FFF7FFFu, tau2) ^ kOne2);
     };
-    if (ASYM && k > 0) {
+    // fp32: the exact key of rank rank_t among the keys a functor lets through, by histogram passes over
+    // narrowing windows: bins of 2^16 keys, then 2^5 inside the bin found, then single keys (2^20, 2^9, 1
+    // when the values spread over more than 16 octaves).  Starts from wtop with above = 0; on success
+    // wtop - B1 is the key, above + c_gt the number of counted keys above it, cnt1 its multiplicity.
+    auto narrow = [&](int sh_done) { above += c_gt; wtop -= B1 << sh_done; };
+    auto exact_select32 = [&](auto key_fn, auto skip0) {
+        hist_pass(std::integral_constant<int, 16>(), key_fn, skip0, std::false_type());
+        if (!found) return;
+        if (B1 == (u32)(kCoarseBins - 1) && (wtop >> 16) > (u32)(kCoarseBins - 1)) {
+            narrow(16);
+            hist_pass(std::integral_constant<int, 20>(), key_fn, skip0, std::true_type());
+            if (!found) return;
+            narrow(20);
+            hist_pass(std::integral_constant<int, 9>(), key_fn, skip0, std::true_type());
+            if (!found) return;
+            narrow(9);
+        } else {
+            narrow(16);
+            hist_pass(std::integral_constant<int, 5>(), key_fn, skip0, std::true_type());
+            if (!found) return;
+            narrow(5);
+        }
+        hist_pass(std::integral_constant<int, 0>(), key_fn, skip0, std::true_type());
+    };
+    u32 tp_key32 = 0, tau_key32 = 0;
+    auto strict32 = [&](u32 wd) -> bool { return (wd & 0x7FFFFFFFu) > ((wd >> 31) ? tn_key : tp_key32); };
+    auto fill32 = [&](u32 wd) -> bool { return !strict32(wd) && (wd & 0x7FFFFFFFu) <= tau_key32; };
+    if (ASYM && DT == 0 && k > 0) {
+        // tau = the k-th largest magnitude, exactly (the first pass above has run on the same window: redo it
+        // as the first level of the exact selection)
+        wtop = kmax; above = 0; S = 0;
+        exact_select32(all_keys, std::false_type());
+        if (!found) {                                // cannot happen: every key is counted
+            if (lane == 0) a.fallback[r] = 1u;
+            return;
+        }
+        tau_key32 = wtop - B1;
+        const float tau = __uint_as_float(tau_key32);
+        tp_key32 = __float_as_uint(__fmul_rn(a.one_plus, tau));
+        tn_key = __float_as_uint(__fmul_rn(a.one_minus, tau));
+        u32 accS = 0, accF = 0;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            if ((c * kWave + (int)lane) * EPC < N) {
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    const u32 wd = word_of(c, d);
+                    accS += strict32(wd) ? 1u : 0u;
+                    accF += fill32(wd) ? 1u : 0u;
+                }
+            }
+        }
+        const u32 tot = bcast(wave_scan_dpp(accS | (accF << 16)), kWave - 1);
+        const u32 c_strict = tot & 0xFFFFu, f_fill = tot >> 16;
+        trim = c_strict >= (u32)k;
+        const u32 D = trim ? 0u : (u32)k - c_strict;
+        if (trim || f_fill > D) {
+            rank_t = trim ? (u32)(k - 1) : D - 1u;
+            wtop = trim ? kmax : tau_key32;
+            above = 0;
+            if (trim) exact_select32([&](u32 wd) -> u32 { return strict32(wd) ? wd & 0x7FFFFFFFu : 0u; }, std::true_type());
+            else exact_select32([&](u32 wd) -> u32 { return fill32(wd) ? wd & 0x7FFFFFFFu : 0u; }, std::true_type());
+            if (found) {
+                t2_key = wtop - B1;
+                need_ties = rank_t + 1u - (above + c_gt);
+                cnt_ties = cnt1;
+            }                                            // else: the rank lies among zeros, every non-zero candidate is taken
+        }
+        if (t2_key == 0) { t2_key = 1; need_ties = 0; cnt_ties = 0; }
+        S = 0; B1 = 0;
+    }
+    if (ASYM && DT == 1 && k > 0) {
         if (!found || S != 0) {                      // tau is not the key of one bin
             if (lane == 0) a.fallback[r] = 1u;
             return;
@@ -417,8 +497,8 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
             rank_t = trim ? (u32)(k - 1) : D - 1u;
             wtop = trim ? kmax : tau_key;
             above = 0;
-            if (trim) hist_pass(std::integral_constant<int, 0>(), [&](u32 wd) -> u32 { return pk_mul_lo_u16(wd & 0x7FFF7FFFu, strict01(wd)); }, std::true_type());
-            else hist_pass(std::integral_constant<int, 0>(), [&](u32 wd) -> u32 { return pk_mul_lo_u16(wd & 0x7FFF7FFFu, fill01(wd, strict01(wd))); }, std::true_type());
+            if (trim) hist_pass(std::integral_constant<int, 0>(), [&](u32 wd) -> u32 { return pk_mul_lo_u16(wd & 0x7FFF7FFFu, strict01(wd)); }, std::true_type(), std::false_type());
+            else hist_pass(std::integral_constant<int, 0>(), [&](u32 wd) -> u32 { return pk_mul_lo_u16(wd & 0x7FFF7FFFu, fill01(wd, strict01(wd))); }, std::true_type(), std::false_type());
             if (found) {
                 if (B1 == (u32)(kCoarseBins - 1) && wtop > (u32)(kCoarseBins - 1)) {     // below the window of single keys
                     if (lane == 0) a.fallback[r] = 1u;
@@ -458,12 +538,22 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
             const u32 ge = gt01(t2_2, wk & 0x7FFF7FFFu) ^ kOne2;              // key >= last key taken
             return (trim ? (st & ge) : (st | (fill01(wd, st) & ge))) << 15;
         };
+        // fp32: the element goes to the list
+        auto flag32 = [&](u32 wd) -> u32 {
+            const u32 key = wd & 0x7FFFFFFFu;
+            if (!ASYM) return key >= t_lo ? 1u : 0u;
+            const bool st = strict32(wd), ge = key >= t2_key;
+            return (trim ? (st && ge) : (st || (fill32(wd) && ge))) ? 1u : 0u;
+        };
         if (ASYM) {
 #pragma unroll
             for (int c = 0; c < NCH; ++c) {
                 u32 n1 = 0;
 #pragma unroll
-                for (int d = 0; d < 4; ++d) n1 += (u32)__popc(list_flags(word_of(c, d)) & 0x80008000u);
+                for (int d = 0; d < 4; ++d) {
+                    if (DT == 0) n1 += flag32(word_of(c, d));
+                    else n1 += (u32)__popc(list_flags(word_of(c, d)) & 0x80008000u);
+                }
                 cntc[c] = n1;
             }
             scan_counts();
@@ -488,7 +578,7 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
             for (int d = 0; d < 4; ++d) {
                 const u32 wd = word_of(c, d);
                 if (DT == 0) {
-                    const u32 fl = (wd & 0x7FFFFFFFu) >= t_lo ? 1u : 0u;
+                    const u32 fl = flag32(wd);
                     if (fl) {
                         *lds_at(wa) = wd;
                         *(__attribute__((address_space(3))) uint16_t*)(uintptr_t)(lidx_off + ((wa - lent_off) >> 1)) = (uint16_t)(idx0 + d);
@@ -517,20 +607,29 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
         u32 seen = 0, dead = 0;
         for (u32 p0 = 0; p0 < nL; p0 += kWave) {
             const u32 p = p0 + lane;
-            u32 e = 0;
+            u32 e = 0, ei = 0;
             bool tie = false;
             if (p < nL) {
                 e = L.Lent[p];
-                const u32 wd = e >> 16;                                  // sign and key in the low half, as in the row
-                const u32 st = strict01(wd) & 1u;
-                const u32 cand = trim ? st : (fill01(wd, st) & 1u);
-                tie = cand && (wd & 0x7FFFu) == t2_key;
+                if (DT == 0) {
+                    ei = L.Lidx[p];
+                    const bool cand = trim ? strict32(e) : fill32(e);
+                    tie = cand && (e & 0x7FFFFFFFu) == t2_key;
+                } else {
+                    const u32 wd = e >> 16;                              // sign and key in the low half, as in the row
+                    const u32 st = strict01(wd) & 1u;
+                    const u32 cand = trim ? st : (fill01(wd, st) & 1u);
+                    tie = cand && (wd & 0x7FFFu) == t2_key;
+                }
             }
             const u64 mt = __ballot(tie);
             const bool drop = tie && seen + mask_rank(mt) >= need_ties;
             const u64 md = __ballot(drop);
             wave_sync();
-            if (p < nL && !drop) L.Lent[p - dead - mask_rank(md)] = e;
+            if (p < nL && !drop) {
+                L.Lent[p - dead - mask_rank(md)] = e;
+                if (DT == 0) L.Lidx[p - dead - mask_rank(md)] = (uint16_t)ei;
+            }
             wave_sync();
             seen += (u32)__popcll(mt);
             dead += (u32)__popcll(md);

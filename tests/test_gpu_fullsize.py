@@ -37,6 +37,14 @@ def test_full_size_llm_prefill_asymmetric(oracle, lam):
     check_atkf(oracle, wl.x, wl.dtype, wl.keep_ratio, lam, wl.n_blocks, wl.n_blocks, wl.bit_set, wl.budget)
 
 
+@pytest.mark.parametrize("lam", [0.1, 0.7])
+def test_full_size_vit_tokens_asymmetric(oracle, lam):
+    """The ViT tensor (fp32, the workload whose outlier channels make the asymmetry matter) under the
+    asymmetric thresholds: row-resident kernel with the exact three-level selection, every row."""
+    wl = synth.make_config(3)
+    check_atkf(oracle, wl.x, wl.dtype, wl.keep_ratio, lam, wl.n_blocks, wl.n_blocks, wl.bit_set, wl.budget)
+
+
 def test_size_accounting_llm_prefill(oracle):
     """Properties that hold at any size: offsets are the exclusive scan of the row word
     counts in closed form, and the payload stays under the paper's upper bound (Sec. 3.3)."""

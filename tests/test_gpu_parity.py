@@ -308,7 +308,7 @@ def test_asymmetric_thresholds_workloads(oracle, name):
         check_atkf(oracle, x, wl.dtype, wl.keep_ratio, lam, wl.n_blocks, wl.n_blocks, wl.bit_set, wl.budget)
 
 
-@pytest.mark.parametrize("dtype,N", [("bf16", 4096), ("f32", 768), ("bf16", 1000), ("f32", 5000)])
+@pytest.mark.parametrize("dtype,N", [("bf16", 4096), ("f32", 768), ("bf16", 1000), ("f32", 5000), ("f32", 2048), ("f32", 4096), ("f32", 64)])
 def test_asymmetric_thresholds_mixed_rows(oracle, dtype, N):
     """Degenerate rows (sparse, constant, few-valued, one-sided, all zero) and a mostly negative row, where
     the strict set is larger than k and is cut back."""
@@ -320,11 +320,12 @@ def test_asymmetric_thresholds_mixed_rows(oracle, dtype, N):
         check_atkf(oracle, x, dtype, keep, lam, Mp, Mn, B28, 1e-3)
 
 
-@pytest.mark.parametrize("dtype,N", [("bf16", 4096), ("bf16", 8192), ("f32", 768)])
+@pytest.mark.parametrize("dtype,N", [("bf16", 4096), ("bf16", 8192), ("f32", 768), ("f32", 4096)])
 def test_asymmetric_thresholds_wide_range(oracle, dtype, N):
-    """Rows on which the row-resident kernel cannot take both selections from its window of single
-    keys (tau or the last fill key lies more than 16 octaves down): they are redone by the generic
-    kernel under the same rule, next to rows that stay on the fast path."""
+    """Rows whose tau or last fill key lies more than 16 octaves below the largest value: bf16 rows are then
+    redone by the generic kernel under the same rule (the row-resident kernel takes both selections from a
+    window of single keys), fp32 rows take the wider first level of the exact selection; next to rows that
+    stay on the ordinary path."""
     x = _wide_range_rows(N, dtype)
     for keep, lam, M in ((0.05, 0.2, 4), (0.3, 0.6, 8), (0.9, 0.95, 8), (1.0, 0.5, 2)):
         check_atkf(oracle, x, dtype, keep, lam, M, M, B28, 1e-3)
