@@ -284,8 +284,8 @@ def main() -> int:
     ap.add_argument("--ds", type=float, default=None,
                     help="time the paper's DS guard with greedy descent at this delta instead of the budget search")
     ap.add_argument("--lam", type=float, default=None,
-                    help="time the asymmetric thresholds of Sec. 3.1 at this asymmetry factor (0 < lambda < 1; bf16 rows "
-                         "of up to 8192 elements on the row-resident kernel, everything else on the generic kernel)")
+                    help="time the asymmetric thresholds of Sec. 3.1 at this asymmetry factor (0 < lambda < 1; rows of up to "
+                         "8192 bf16 / 4096 fp32 elements on the one-wavefront-per-row kernel, everything else on the generic kernel)")
     ap.add_argument("--keep-ratio", type=float, default=None, help="override the workload's keep ratio (1 - s)")
     ap.add_argument("--n-blocks", type=int, default=None, help="override the workload's block count M per sign class")
     ap.add_argument("--streams", type=int, default=3,
@@ -508,8 +508,13 @@ def main() -> int:
 
     path = binding.slicer_encode_path(binding.SLICER_F32 if wl.dtype == "f32" else binding.SLICER_BF16,
                                       wl.rows, wl.row_len, keep, M, bits)
-    if args.lam is not None and args.lam > 0 and not (wl.dtype == "bf16" and path == 1):
-        path = 0                                         # the second selection: row-resident kernel for bf16 rows, else the generic kernel
+    asym = args.lam is not None and args.lam > 0
+    if (asym or args.ds is not None) and path == 3:      # the workgroup-per-row kernel takes the budget guard at lambda = 0 only:
+        path = binding.slicer_encode_path(binding.SLICER_F32 if wl.dtype == "f32" else binding.SLICER_BF16,
+                                          2048, wl.row_len, keep, M, bits)      # what a large batch of these rows runs on
+        path = 0 if path == 3 else path
+    if asym and path != 1:
+        path = 0                                         # the second selection: one-wavefront-per-row kernel, else the generic kernel
     enc_kernel = {0: "enc_generic_kernel", 1: "enc_small_kernel", 2: "lr_* stages (hist..pack)", 3: "enc_wg_kernel"}[path]
     dec_kernel = "dec_small_kernel" if wl.row_len * (4 if wl.dtype == "f32" else 2) <= 16384 else "dec_kernel"
     enc_alg_bytes = in_bytes + out_bytes                 # read x once, write stream + meta
