@@ -69,7 +69,7 @@ struct Plan {
     // row-resident fast path (0 = not eligible)
     int small_epl, small_cap, small_region0, small_lds_bytes, small_maxs;
     // workgroup-per-row path for bf16 rows of up to 32768 elements (0 = not eligible)
-    int wg_ept, wg_cap, wg_region0, wg_lds_bytes;
+    int wg_ept, wg_nw, wg_cap, wg_region0, wg_lds_bytes;
     // long-row path (large_C == 0: not eligible)
     int large_C, large_LC;
     u32 large_capL;
@@ -166,7 +166,7 @@ Plan make_plan(int dt, int64_t rows, int64_t row_len, double keep_ratio, int n_b
     }
     // One workgroup per row (four wavefronts share the row): bf16 rows too long for one wavefront, and
     // rows of more than 4096 elements in batches too small to fill the chip with one wavefront each.
-    p.wg_ept = 0; p.wg_cap = 0; p.wg_region0 = 0; p.wg_lds_bytes = 0;
+    p.wg_ept = 0; p.wg_nw = 0; p.wg_cap = 0; p.wg_region0 = 0; p.wg_lds_bytes = 0;
     if (csr_cols == 0 && dt == SLICER_BF16 && row_len % 8 == 0 && row_len > 4096 && row_len <= 32768 && B2_all <= kWave &&
         (row_len > 8192 || rows <= 1024)) {
         const int64_t margin = std::max<int64_t>(64, row_len / 32);
@@ -174,25 +174,40 @@ Plan make_plan(int dt, int64_t rows, int64_t row_len, double keep_ratio, int n_b
         const int64_t region0 = small_region0_words(p.k, p.cap_words, B2_all, nq);
         const int64_t lds = 4 * (int64_t)wg_lds_words((int)cap, (int)region0, B2_all);
         if (p.k + 64 <= cap && lds <= 64 * 1024) {
-            p.wg_ept = row_len <= 8192 ? 32 : row_len <= 16384 ? 64 : 128;
+            // wavefronts per row: sixteen while that still leaves the chip room for every row at once (more
+            // wavefronts per SIMD hide each other's latencies), four for larger batches
+            p.wg_nw = rows <= 512 ? 16 : 4;
+            const int64_t per_thread = (row_len + 64 * p.wg_nw - 1) / (64 * p.wg_nw);
+            p.wg_ept = per_thread <= 8 ? 8 : per_thread <= 16 ? 16 : per_thread <= 32 ? 32 : per_thread <= 64 ? 64 : 128;
             p.wg_cap = (int)cap; p.wg_region0 = (int)region0; p.wg_lds_bytes = (int)lds;
         }
     }
     return p;
 }
 
+template <int NW, int NQ>
+void launch_wg_nw(const SmallArgs& sa, const Plan& p, hipStream_t st)
+{
+    const dim3 g((unsigned)sa.R), b(NW * kWave);
+    const size_t lds = (size_t)p.wg_lds_bytes;
+    // elements per thread: 16-byte chunks, and at most 64 chunk totals for the one-wavefront scan
+    if constexpr (NW == 16) {
+        if (p.wg_ept == 8) hipLaunchKernelGGL((enc_wg_kernel<16, 8, NQ>), g, b, lds, st, sa);
+        else if (p.wg_ept == 16) hipLaunchKernelGGL((enc_wg_kernel<16, 16, NQ>), g, b, lds, st, sa);
+        else hipLaunchKernelGGL((enc_wg_kernel<16, 32, NQ>), g, b, lds, st, sa);
+    } else {
+        if (p.wg_ept <= 32) hipLaunchKernelGGL((enc_wg_kernel<4, 32, NQ>), g, b, lds, st, sa);
+        else if (p.wg_ept == 64) hipLaunchKernelGGL((enc_wg_kernel<4, 64, NQ>), g, b, lds, st, sa);
+        else hipLaunchKernelGGL((enc_wg_kernel<4, 128, NQ>), g, b, lds, st, sa);
+    }
+}
+
 int launch_wg(const SmallArgs& sa, const Plan& p, hipStream_t st)
 {
-    const dim3 g((unsigned)sa.R), b(kWgThreads);
-    const size_t lds = (size_t)p.wg_lds_bytes;
-    if (sa.nq == 7) {
-        if (p.wg_ept == 32) hipLaunchKernelGGL((enc_wg_kernel<32, 7>), g, b, lds, st, sa);
-        else if (p.wg_ept == 64) hipLaunchKernelGGL((enc_wg_kernel<64, 7>), g, b, lds, st, sa);
-        else hipLaunchKernelGGL((enc_wg_kernel<128, 7>), g, b, lds, st, sa);
+    if (p.wg_nw == 16) {
+        if (sa.nq == 7) launch_wg_nw<16, 7>(sa, p, st); else launch_wg_nw<16, 0>(sa, p, st);
     } else {
-        if (p.wg_ept == 32) hipLaunchKernelGGL((enc_wg_kernel<32, 0>), g, b, lds, st, sa);
-        else if (p.wg_ept == 64) hipLaunchKernelGGL((enc_wg_kernel<64, 0>), g, b, lds, st, sa);
-        else hipLaunchKernelGGL((enc_wg_kernel<128, 0>), g, b, lds, st, sa);
+        if (sa.nq == 7) launch_wg_nw<4, 7>(sa, p, st); else launch_wg_nw<4, 0>(sa, p, st);
     }
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? SLICER_OK : hip_fail(e);

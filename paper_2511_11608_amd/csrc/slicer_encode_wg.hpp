@@ -1,8 +1,10 @@
 // Row-resident encoder for rows of 4 K to 32 K bf16 elements and small batches: ONE WORKGROUP
-// (four wavefronts) PER ROW.  A single wavefront needs about 30 us for an 8192-element row,
+// (4, 8 or 16 wavefronts) PER ROW.  A single wavefront needs about 30 us for an 8192-element row,
 // nearly all of it dependent-instruction and LDS latency, and a batch of a few hundred rows
 // (one auto-regressive decode step of Sec. 2.1, one hidden state per client) leaves three
-// quarters of the SIMDs idle; here the four wavefronts of a workgroup share the row.
+// quarters of the SIMDs idle; here the wavefronts of a workgroup share the row (four when the batch
+// fills the chip anyway, sixteen for the smallest batches: more wavefronts per SIMD hide each other's
+// latencies).
 //
 // Same method and same data structures as the one-wavefront kernel (slicer_encode_small.hpp):
 // comps "key, inverted index, class bit" order everything; a 2048-bin LDS histogram over a window
@@ -11,8 +13,8 @@
 // the top-K cut and the block boundaries (MS, Sec. 3.2) are order statistics located over the bins
 // and resolved inside their bin; an entry's block is the number of boundaries above it; a stable
 // split by block, integer ABQ sums (Sec. 3.2.1), bitwidth choice, packing through an LDS image.
-// What changes is who does what: per-element passes and per-entry passes are dealt to the four
-// wavefronts (thread t owns 16-byte chunks t, t + 256, ...; wavefront v owns list slots v, v + 4,
+// What changes is who does what: per-element passes and per-entry passes are dealt to the NW
+// wavefronts (thread t owns 16-byte chunks t, t + 64 NW, ...; wavefront v owns list slots v, v + NW,
 // ...), scans run over the workgroup, the two short serial steps (cut, boundaries) run on
 // wavefront 0, and workgroup barriers separate the stages.
 //
@@ -23,9 +25,8 @@
 
 namespace slicer {
 
-constexpr int kWgThreads = 256;
-constexpr int kWgWaves = kWgThreads / kWave;
-constexpr int kWgSlots = 8;            // list slots (64 entries) per wavefront: lists of up to 2048 entries
+constexpr int kWgMaxSlots = 32;        // list slots (64 entries): lists of up to 2048 entries
+constexpr int kWgMisc = 64;            // broadcast words (0..15), per-wavefront maxima (16..31), scan scratch (32..)
 
 // words of LDS: the one-wavefront layout (list in LDS) followed by the workgroup's own tables
 __host__ __device__ inline int wg_main_words(int cap, int region0, int B2)
@@ -34,13 +35,15 @@ __host__ __device__ inline int wg_main_words(int cap, int region0, int B2)
 }
 __host__ __device__ inline int wg_lds_words(int cap, int region0, int B2)
 {
-    // misc (32), chunk totals and their prefix (2 x 64), per-slot per-block counts as 16-bit (cap / 64 slots)
-    return wg_main_words(cap, region0, B2) + 32 + 128 + ((cap / kWave) * B2 + 1) / 2 + 2;
+    // misc, chunk totals and their prefix (2 x 64), per-slot per-block counts as 16-bit (cap / 64 slots)
+    return wg_main_words(cap, region0, B2) + kWgMisc + 128 + ((cap / kWave) * B2 + 1) / 2 + 2;
 }
 
-template <int EPT, int NQ>
-__global__ __launch_bounds__(kWgThreads) void enc_wg_kernel(SmallArgs a)
+template <int NW, int EPT, int NQ>
+__global__ __launch_bounds__(NW * kWave) void enc_wg_kernel(SmallArgs a)
 {
+    constexpr int kWgThreads = NW * kWave, kWgWaves = NW;
+    constexpr int kWgSlots = (kWgMaxSlots + NW - 1) / NW;     // list slots per wavefront
     typedef u32 comp_t;
     constexpr comp_t kClsBit = 0x80000000u;          // set for the positive class
     constexpr int kRegThr = 14;
@@ -56,7 +59,7 @@ __global__ __launch_bounds__(kWgThreads) void enc_wg_kernel(SmallArgs a)
     const int k = (int)a.k;
     SmallLds L = small_carve(smem, 1, cap, a.region0_words, B2, 0);
     u32* misc = smem + wg_main_words(cap, a.region0_words, B2);      // broadcast words and scan scratch
-    u32* ctab = misc + 32;                                           // [NCH][4] chunk totals per wavefront, then their prefixes
+    u32* ctab = misc + kWgMisc;                                           // [NCH][4] chunk totals per wavefront, then their prefixes
     uint16_t* stab = (uint16_t*)(ctab + 128);                        // [slot][B2] entries of block b in slot s
     auto give_up = [&]() { if (tid == 0) a.fallback[r] = 1u; };      // callers return right after, all threads alike
     if (__builtin_amdgcn_groupstaticsize() != 0u) {                  // integer LDS addresses assume offset 0
@@ -144,7 +147,9 @@ __global__ __launch_bounds__(kWgThreads) void enc_wg_kernel(SmallArgs a)
         mx = wave_max_dpp(mx);
         if (lane == 0) misc[16 + wv] = mx;
         __syncthreads();
-        kmax = max(max(misc[16], misc[17]), max(misc[18], misc[19]));
+        kmax = 0;
+#pragma unroll
+        for (int i = 0; i < NW; ++i) kmax = max(kmax, misc[16 + i]);
         __syncthreads();
     }
 
@@ -158,8 +163,7 @@ __global__ __launch_bounds__(kWgThreads) void enc_wg_kernel(SmallArgs a)
         constexpr int SH = decltype(shift)::value;
         {
             uint4* h4 = (uint4*)smem;
-#pragma unroll
-            for (int i = 0; i < kCoarseBins / 4 / kWgThreads; ++i) h4[i * kWgThreads + tid] = make_uint4(0, 0, 0, 0);
+            for (int i = (int)tid; i < kCoarseBins / 4; i += kWgThreads) h4[i] = make_uint4(0, 0, 0, 0);
             if (tid < 4) misc[tid] = 0;
         }
         __syncthreads();
@@ -181,19 +185,16 @@ __global__ __launch_bounds__(kWgThreads) void enc_wg_kernel(SmallArgs a)
         __syncthreads();
         if (above && tid == 0) smem[0] -= above;     // keys above the window were counted in bin 0
         __syncthreads();
-        // scan from the top: every thread sums 8 bins; the thread that holds the rank opens them
+        // scan from the top: every thread sums its BPT bins; the thread that holds the rank opens them
         constexpr int BPT = kCoarseBins / kWgThreads;
         u32 cs[BPT];
-        {
-            const uint4* h4 = (const uint4*)(smem + (int)tid * BPT);
-            const uint4 t0 = h4[0], t1 = h4[1];
-            cs[0] = t0.x; cs[1] = t0.y; cs[2] = t0.z; cs[3] = t0.w; cs[4] = t1.x; cs[5] = t1.y; cs[6] = t1.z; cs[7] = t1.w;
-        }
+#pragma unroll
+        for (int j = 0; j < BPT; ++j) cs[j] = smem[(int)tid * BPT + j];
         u32 local = 0;
 #pragma unroll
         for (int j = 0; j < BPT; ++j) local += cs[j];
         u32 total;
-        const u32 excl = block_excl_scan<kWgThreads>(local, misc + 20, &total);
+        const u32 excl = block_excl_scan<kWgThreads>(local, misc + 32, &total);
         const u32 rem = rank_t - above;
         if (local > 0 && excl <= rem && rem < excl + local) {
             u32 acc = excl;
@@ -273,10 +274,14 @@ __global__ __launch_bounds__(kWgThreads) void enc_wg_kernel(SmallArgs a)
         if (lane == 0) misc[16 + wv] = mx;
     }
     __syncthreads();                                              // (the histogram region overlays the list's neighbours)
-    if (hinted) kmax = max(max(misc[16], misc[17]), max(misc[18], misc[19]));
+    if (hinted) {
+        kmax = 0;
+#pragma unroll
+        for (int i = 0; i < NW; ++i) kmax = max(kmax, misc[16 + i]);
+    }
     {
         uint4* h4 = (uint4*)L.hist;
-        if (tid < kFineBins / 4) h4[tid] = make_uint4(0, 0, 0, 0);
+        for (int i = (int)tid; i < kFineBins / 4; i += kWgThreads) h4[i] = make_uint4(0, 0, 0, 0);
         if (tid < 16) misc[tid] = 0;
         if ((int)tid < QN && (NQ || (int)tid < nq)) L.qtab[tid] = (u32)a.qlist[tid];
         for (int i = (int)tid; i < (nslots * B2 + 1) / 2; i += kWgThreads) ((u32*)stab)[i] = 0;
@@ -297,10 +302,11 @@ __global__ __launch_bounds__(kWgThreads) void enc_wg_kernel(SmallArgs a)
     __syncthreads();
     u32 n_pos, n_neg;
     {   // exclusive prefix from the top in the counting format pos | neg << 11 (fill << 22 is added later)
-        constexpr int FPT = kFineBins / kWgThreads;     // 4
+        constexpr int FPT = kFineBins / kWgThreads;     // 4, 2 or 1
         const int hi = kFineBins - (int)tid * FPT;
-        const uint4 t = *(const uint4*)(L.hist + hi - FPT);
-        const u32 cs[FPT] = { t.w, t.z, t.y, t.x };
+        u32 cs[FPT];
+#pragma unroll
+        for (int j = 0; j < FPT; ++j) cs[j] = L.hist[hi - 1 - j];
         u32 local = 0, big = 0;
 #pragma unroll
         for (int j = 0; j < FPT; ++j) { local += cs[j]; big |= ((cs[j] & 0x7FFu) + (cs[j] >> 11)) >> 10; }
@@ -311,7 +317,7 @@ __global__ __launch_bounds__(kWgThreads) void enc_wg_kernel(SmallArgs a)
             return;
         }
         u32 tot;
-        const u32 excl = block_excl_scan<kWgThreads>(local, misc + 20, &tot);
+        const u32 excl = block_excl_scan<kWgThreads>(local, misc + 32, &tot);
         n_pos = tot & 0x7FFu; n_neg = tot >> 11;
         const u32 incl = excl + local;
         const u32 ov_ex = (excl & 0x7FFu) + (excl >> 11), ov_in = (incl & 0x7FFu) + (incl >> 11);
@@ -319,7 +325,8 @@ __global__ __launch_bounds__(kWgThreads) void enc_wg_kernel(SmallArgs a)
         u32 acc = excl, o[FPT];
 #pragma unroll
         for (int j = 0; j < FPT; ++j) { o[j] = acc; acc += cs[j]; }
-        *(uint4*)(L.hist + hi - FPT) = make_uint4(o[3], o[2], o[1], o[0]);
+#pragma unroll
+        for (int j = 0; j < FPT; ++j) L.hist[hi - 1 - j] = o[j];
     }
     __syncthreads();
 #pragma unroll
@@ -515,10 +522,11 @@ __global__ __launch_bounds__(kWgThreads) void enc_wg_kernel(SmallArgs a)
     }
     __syncthreads();
 
-    // ---- 5. ABQ: each block is walked by 256 / B2 threads ------------------------------------------
+    // ---- 5. ABQ: each block is walked by (64 NW) / B2 threads ---------------------------------------
     u64* sums = (u64*)(L.hist + ((((k + 1) / 2 + (int)a.cap_words) + 1) & ~1));
     float* invt = (float*)(sums + B2 * (nq + 1));
     const u32 lpb = (u32)kWgThreads / (u32)B2;
+    const bool wave_one_block = lpb % (u32)kWave == 0u;          // every wavefront then lies inside one block's threads
     const u32 myb = udiv16(tid, lpb), sub = tid - myb * lpb;
     const bool on = myb < (u32)B2;
     u32 r0 = 0, r1 = 0, bs0 = 0, mycnt = 0;
@@ -592,11 +600,31 @@ __global__ __launch_bounds__(kWgThreads) void enc_wg_kernel(SmallArgs a)
                     }
                 }
             }
+            if (wave_one_block) {
+                // the 64 lanes of this wavefront work on one block: add up across the wavefront first
+                // (16-bit pieces, so that the lane sums fit 32 bits), then one lane adds to the table
 #pragma unroll
-            for (int t = 0; t < QN; ++t)
-                if ((NQ || t < nq) && acc[t]) atomicAdd(&sums[myb * (nq + 1) + t], (u64)acc[t]);
+                for (int t = 0; t < QN; ++t) {
+                    if (NQ || t < nq) {
+                        const u32 lo16 = bcast(wave_scan_dpp(acc[t] & 0xFFFFu), kWave - 1);
+                        const u32 hi16 = bcast(wave_scan_dpp(acc[t] >> 16), kWave - 1);
+                        if (lane == 0 && (lo16 | hi16)) atomicAdd(&sums[myb * (nq + 1) + t], (u64)lo16 + ((u64)hi16 << 16));
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int t = 0; t < QN; ++t)
+                    if ((NQ || t < nq) && acc[t]) atomicAdd(&sums[myb * (nq + 1) + t], (u64)acc[t]);
+            }
         }
-        if (accE) atomicAdd(&sums[myb * (nq + 1) + nq], accE);
+        if (wave_one_block) {
+            const u32 e0 = bcast(wave_scan_dpp((u32)accE & 0x3FFFFFu), kWave - 1);
+            const u32 e1 = bcast(wave_scan_dpp((u32)(accE >> 22) & 0x3FFFFFu), kWave - 1);
+            const u32 e2 = bcast(wave_scan_dpp((u32)(accE >> 44)), kWave - 1);
+            if (lane == 0 && (e0 | e1 | e2)) atomicAdd(&sums[myb * (nq + 1) + nq], (u64)e0 + ((u64)e1 << 22) + ((u64)e2 << 44));
+        } else if (accE) {
+            atomicAdd(&sums[myb * (nq + 1) + nq], accE);
+        }
     }
     __syncthreads();
     if (a.lad.on) {
