@@ -174,9 +174,10 @@ Plan make_plan(int dt, int64_t rows, int64_t row_len, double keep_ratio, int n_b
         const int64_t region0 = small_region0_words(p.k, p.cap_words, B2_all, nq);
         const int64_t lds = 4 * (int64_t)wg_lds_words((int)cap, (int)region0, B2_all);
         if (p.k + 64 <= cap && lds <= 64 * 1024) {
-            // wavefronts per row: sixteen while that still leaves the chip room for every row at once (more
-            // wavefronts per SIMD hide each other's latencies), four for larger batches
-            p.wg_nw = rows <= 512 ? 16 : 4;
+            // wavefronts per row: sixteen for the smallest batches (more wavefronts per SIMD hide each other's
+            // latencies: 4 % less latency per call), four otherwise (a 256-row batch on sixteen leaves no room
+            // for a neighbouring stream's kernels: 20 % less throughput when steps overlap)
+            p.wg_nw = rows <= 128 ? 16 : 4;
             const int64_t per_thread = (row_len + 64 * p.wg_nw - 1) / (64 * p.wg_nw);
             p.wg_ept = per_thread <= 8 ? 8 : per_thread <= 16 ? 16 : per_thread <= 32 ? 32 : per_thread <= 64 ? 64 : 128;
             p.wg_cap = (int)cap; p.wg_region0 = (int)region0; p.wg_lds_bytes = (int)lds;
