@@ -447,6 +447,37 @@ def test_check_accepts_encoder_output_and_rejects_forged_meta(oracle):
     expect_reject(meta, words, y, M + 1)
 
 
+@pytest.mark.parametrize("dtype,N,rows", [("bf16", 4096, 700), ("f32", 768, 900), ("bf16", 8192, 96), ("bf16", 8192, 2000)])
+def test_one_workspace_reused_across_calls(oracle, dtype, N, rows):
+    """The workspace keeps threshold hints from one call to the next (and nothing else that matters): the
+    same buffers serve tensors of very different scale, sparsity and knobs in turn, so every call starts
+    from the previous call's hints, good, stale or far off.  Every call is compared with the oracle."""
+    import torch
+    from paper_2511_11608_amd import binding
+    from paper_2511_11608_amd.devmem import to_device
+    rng = np.random.default_rng(N + rows)
+    base = rng.standard_normal((rows, N)).astype(np.float32)
+    variants = [base, base * np.float32(300), base * np.float32(1e-3), np.where(rng.random((rows, N)) < 0.93, 0, base).astype(np.float32),
+                base, np.abs(base) * (10.0 ** rng.uniform(-3, 3, (rows, 1))).astype(np.float32), base * np.float32(300)]
+    keep_max, M, bits = 0.2, 8, B28
+    x0 = to_device(synth.f32_to_bf16_bits(base) if dtype == "bf16" else base, dtype)
+    sb, meta, ws = binding.alloc_buffers(x0, keep_max, M, bits)      # sized for the largest keep ratio used
+    ws.fill_(0x5A)
+    for i, xf in enumerate(variants):
+        x = synth.f32_to_bf16_bits(xf) if dtype == "bf16" else xf
+        keep = (0.1, 0.2, 0.05)[i % 3]
+        s_ref, m_ref = oracle.encode(x, dtype, keep, M, bits, 1e-3, n_threads=8)
+        sb.fill_(-1); meta.fill_(0xFF)
+        xd = to_device(x, dtype)
+        binding.slicer_encode(xd, keep, M, bits, 1e-3, sb, meta, ws)
+        words = binding.slicer_stream_words(meta)
+        mb = m_ref.size
+        m_gpu = meta[:mb].cpu().numpy()
+        s_gpu = sb[:words].cpu().numpy().view(np.uint32)
+        ok = np.array_equal(m_ref, m_gpu) and np.array_equal(s_ref, s_gpu)
+        assert ok, (i, explain_mismatch(s_ref, m_ref, s_gpu, m_gpu, rows))
+
+
 def check_csr(oracle, x, dtype, n_rows, n_cols, keep, M, bits, budget):
     import torch
     from paper_2511_11608_amd import binding
