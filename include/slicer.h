@@ -182,8 +182,10 @@ int slicer_check_pn(const void* meta, uint64_t stream_words, slicer_dtype dt, in
  *   stream_capacity_bytes  instances * ceil((2 n_blocks (n_rows + 1) wp + k (wc + q_bit)) / 32) * 4
  * n_rows * n_cols < 2^31.  Served by the one-workgroup-per-instance encoder.  slicer_decode reads the
  * index format from the header; slicer_decode_as_csr takes the shape from the caller (it reads k from
- * the header in meta for the pointer width, nothing else).  slicer_check does not accept these metas.
- * Errors as slicer_sizes / slicer_encode / slicer_decode_as.
+ * the header in meta for the pointer width, nothing else).  slicer_check_csr is slicer_check for these
+ * metas (slicer_check itself rejects them); the decoder clamps every row pointer to its block and every
+ * column to its tensor row, so after SLICER_OK a forged stream cannot take it outside stream or y.
+ * Errors as slicer_sizes / slicer_encode / slicer_decode_as / slicer_check.
  */
 int slicer_sizes_csr(slicer_dtype dt, int64_t instances, int64_t n_rows, int64_t n_cols, double keep_ratio,
                      int n_blocks, uint32_t bit_set,
@@ -193,6 +195,8 @@ int slicer_encode_csr(const void* x, slicer_dtype dt, int64_t instances, int64_t
                       void* stream, void* meta, void* workspace, void* hip_stream);
 int slicer_decode_as_csr(const void* stream, const void* meta, void* y, slicer_dtype dt, int64_t instances,
                          int64_t n_rows, int64_t n_cols, int n_blocks, void* hip_stream);
+int slicer_check_csr(const void* meta, uint64_t stream_words, slicer_dtype dt, int64_t instances,
+                     int64_t n_rows, int64_t n_cols, int n_blocks, void* scratch, void* hip_stream);
 
 /*
  * Encode with the paper's own guard (Sec. 3.2.1, Eq. "DS" and the greedy search stated under it:

@@ -52,6 +52,8 @@ def load() -> C.CDLL:
         L.slicer_encode_csr.argtypes = [vp, cint, i64, i64, i64, dbl, cint, u32, dbl, vp, vp, vp, vp]
         L.slicer_decode_as_csr.restype = cint
         L.slicer_decode_as_csr.argtypes = [vp, vp, vp, cint, i64, i64, i64, cint, vp]
+        L.slicer_check_csr.restype = cint
+        L.slicer_check_csr.argtypes = [vp, C.c_uint64, cint, i64, i64, i64, cint, vp, vp]
         L.slicer_sizes_pn.restype = cint
         L.slicer_sizes_pn.argtypes = [cint, i64, i64, dbl, cint, cint, u32, szp, szp, szp]
         L.slicer_encode_pn.restype = cint
@@ -179,6 +181,14 @@ def slicer_decode_as_csr(stream_buf: torch.Tensor, meta: torch.Tensor, y: torch.
     _check("slicer_decode_as_csr", load().slicer_decode_as_csr(stream_buf.data_ptr(), meta.data_ptr(), y.data_ptr(),
                                                               _dt_of(y), y.shape[0], n_rows, n_cols, n_blocks,
                                                               _stream_handle(stream)))
+
+
+def slicer_check_csr(meta: torch.Tensor, stream_words: int, y_like: torch.Tensor, n_rows: int, n_cols: int, n_blocks: int,
+                     stream=None) -> None:
+    """Validate a received meta buffer of two-dimensional instances; raises SlicerError (-4)."""
+    scratch = torch.empty(64, dtype=torch.int32, device=meta.device)
+    _check("slicer_check_csr", load().slicer_check_csr(meta.data_ptr(), stream_words, _dt_of(y_like), y_like.shape[0],
+                                                      n_rows, n_cols, n_blocks, scratch.data_ptr(), _stream_handle(stream)))
 
 
 def alloc_buffers_pn(x: torch.Tensor, keep_ratio: float, n_blocks: int, n_blocks_neg: int, bit_set: int):

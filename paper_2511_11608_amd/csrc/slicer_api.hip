@@ -787,8 +787,25 @@ int slicer_check(const void* meta, uint64_t stream_words, slicer_dtype dt, int64
     return slicer_check_pn(meta, stream_words, dt, rows, row_len, n_blocks, n_blocks, scratch, hip_stream);
 }
 
+static int check_impl(const void* meta, uint64_t stream_words, slicer_dtype dt, int64_t rows, int64_t row_len,
+                      int n_blocks, int n_blocks_neg, int64_t csr_cols, void* scratch, void* hip_stream);
+
 int slicer_check_pn(const void* meta, uint64_t stream_words, slicer_dtype dt, int64_t rows, int64_t row_len,
                     int n_blocks, int n_blocks_neg, void* scratch, void* hip_stream)
+{
+    return check_impl(meta, stream_words, dt, rows, row_len, n_blocks, n_blocks_neg, 0, scratch, hip_stream);
+}
+
+int slicer_check_csr(const void* meta, uint64_t stream_words, slicer_dtype dt, int64_t instances, int64_t n_rows,
+                     int64_t n_cols, int n_blocks, void* scratch, void* hip_stream)
+{
+    int rc = check_csr_shape(n_rows, n_cols);
+    if (rc) return rc;
+    return check_impl(meta, stream_words, dt, instances, n_rows * n_cols, n_blocks, n_blocks, n_cols, scratch, hip_stream);
+}
+
+static int check_impl(const void* meta, uint64_t stream_words, slicer_dtype dt, int64_t rows, int64_t row_len,
+                      int n_blocks, int n_blocks_neg, int64_t csr_cols, void* scratch, void* hip_stream)
 {
     int rc = check_shape((int)dt, rows, row_len, n_blocks);
     if (rc) return rc;
@@ -796,7 +813,9 @@ int slicer_check_pn(const void* meta, uint64_t stream_words, slicer_dtype dt, in
     if (!meta || !scratch) return SLICER_EINVAL;
     hipStream_t st = (hipStream_t)hip_stream;
     CheckArgs ca;
-    ca.meta = meta; ca.R = rows; ca.N = row_len; ca.M = n_blocks; ca.Mn = n_blocks_neg; ca.w = index_bits(row_len); ca.dt = (int)dt;
+    ca.meta = meta; ca.R = rows; ca.N = row_len; ca.M = n_blocks; ca.Mn = n_blocks_neg; ca.dt = (int)dt;
+    ca.csr_cols = csr_cols;
+    ca.w = csr_cols > 0 ? index_bits(csr_cols) : index_bits(row_len);
     ca.avail_words = stream_words;
     ca.flag = (u32*)scratch;
     hipLaunchKernelGGL(meta_flag_clear_kernel, dim3(1), dim3(64), 0, st, ca.flag);

@@ -191,6 +191,7 @@ struct CheckArgs {
     int M, Mn, w, dt;
     u64 avail_words;
     u32* flag;          // device word, zeroed by the same launch sequence
+    int64_t csr_cols;   // > 0: two-dimensional instances of (N / csr_cols) x csr_cols, w = bits of a column
 };
 
 __global__ __launch_bounds__(64) void meta_flag_clear_kernel(u32* flag) { if (threadIdx.x == 0) *flag = 0u; }
@@ -205,7 +206,7 @@ __global__ __launch_bounds__(256) void meta_check_kernel(CheckArgs a)
     const u64 total = h64[6];
     if (r == 0) {
         if (h32[0] != kMagic || h32[1] != kVersion) bad |= 1u;
-        if (h32[14] != (a.Mn != a.M ? (u32)a.Mn : 0u) || h32[15] != 0u) bad |= 2u;
+        if (h32[14] != (a.Mn != a.M ? (u32)a.Mn : 0u) || h32[15] != (u32)a.csr_cols) bad |= 2u;
         if (h32[2] != (u32)a.dt || h32[3] != (u32)a.M || h64[2] != (u64)a.R || h64[3] != (u64)a.N || h32[11] != (u32)a.w) bad |= 2u;
         if (h64[4] > (u64)a.N || (h32[10] & ~0x1FFFEu) || h32[10] == 0u) bad |= 2u;
         if (total > a.avail_words || mv.row_off[0] != 0ull) bad |= 4u;
@@ -216,6 +217,11 @@ __global__ __launch_bounds__(256) void meta_check_kernel(CheckArgs a)
             bad |= 8u;
         } else {
             u64 bits = (n_pos + n_neg) * (u64)a.w;
+            if (a.csr_cols > 0) {                      // row pointers of every block: n_rows + 1 fields that hold 0..k
+                int wp = 1;
+                while (wp < 32 && (1ull << wp) <= h64[4]) ++wp;
+                bits += (u64)(a.M + a.Mn) * (u64)(a.N / a.csr_cols + 1) * (u64)wp;
+            }
             for (int b = 0; b < a.M + a.Mn; ++b) {
                 const u32 q = mv.q[(size_t)r * (a.M + a.Mn) + b] & 0x7Fu;
                 if (q < 1u || q > 16u || !((h32[10] >> q) & 1u)) bad |= 16u;

@@ -493,6 +493,13 @@ def check_csr(oracle, x, dtype, n_rows, n_cols, keep, M, bits, budget):
     s_gpu = sb[:words].cpu().numpy().view(np.uint32)
     assert np.array_equal(m_ref[:64], m_gpu[:64]), (streamfmt.header(m_ref), streamfmt.header(m_gpu))
     assert np.array_equal(m_ref, m_gpu) and np.array_equal(s_ref, s_gpu)
+    # the checker takes what the encoder wrote, and neither a flat-format claim nor a short buffer
+    binding.slicer_check_csr(meta, words, xd, n_rows, n_cols, M)
+    if words:
+        with pytest.raises(binding.SlicerError):
+            binding.slicer_check_csr(meta, words - 1, xd, n_rows, n_cols, M)
+    with pytest.raises(binding.SlicerError):
+        binding.slicer_check(meta, words, xd, M)
     yv = np.uint32 if dtype == "f32" else np.uint16
     for via_header in (True, False):
         y = torch.full_like(xd, 7.0)
