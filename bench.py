@@ -286,6 +286,9 @@ def main() -> int:
     ap.add_argument("--lam", type=float, default=None,
                     help="time the asymmetric thresholds of Sec. 3.1 at this asymmetry factor (0 < lambda < 1; rows of up to "
                          "8192 bf16 / 4096 fp32 elements on the one-wavefront-per-row kernel, everything else on the generic kernel)")
+    ap.add_argument("--csr-cols", type=int, default=None,
+                    help="time the two-dimensional instance of Sec. 3.2 step 3: every row of the workload is one tensor of "
+                         "(row_len / K) x K whose blocks are stored as CSR triples; K must divide the row length")
     ap.add_argument("--keep-ratio", type=float, default=None, help="override the workload's keep ratio (1 - s)")
     ap.add_argument("--n-blocks", type=int, default=None, help="override the workload's block count M per sign class")
     ap.add_argument("--streams", type=int, default=3,
@@ -320,8 +323,21 @@ def main() -> int:
             print("bench.py: --ladder entries must be 1..16", file=sys.stderr)
             return 2
 
+    csr = args.csr_cols
+    if csr is not None and (csr < 1 or wl.row_len % csr):
+        print("bench.py: --csr-cols must divide the row length", file=sys.stderr)
+        return 2
+
+    def decode(sb, meta, y, st=None):
+        if csr is not None:
+            binding.slicer_decode_as_csr(sb, meta, y, wl.row_len // csr, csr, M, stream=st)
+        else:
+            binding.slicer_decode_as(sb, meta, y, M, stream=st)
+
     def encode(x, sb, meta, ws, st=None):
-        if ladder:
+        if csr is not None:
+            binding.slicer_encode_csr(x, wl.row_len // csr, csr, keep, M, bits, beta, sb, meta, ws, stream=st)
+        elif ladder:
             binding.slicer_encode_ladder(x, keep, ladder, sb, meta, ws, stream=st)
         elif args.ds is not None:
             binding.slicer_encode_ds(x, keep, M, bits, args.ds, sb, meta, ws, stream=st)
@@ -345,7 +361,10 @@ def main() -> int:
     S = max(1, min(int(args.streams), 8))
     side = [torch.cuda.Stream() for _ in range(S)] if S > 1 else []
     n_out = S * max(1, -(-min(n_buf, 4) // S))
-    bufs = [binding.alloc_buffers(xd[0], keep, M, bits) for _ in range(n_out)]
+    if csr is not None:
+        bufs = [binding.alloc_buffers_csr(xd[0], wl.row_len // csr, csr, keep, M, bits) for _ in range(n_out)]
+    else:
+        bufs = [binding.alloc_buffers(xd[0], keep, M, bits) for _ in range(n_out)]
     ys = [torch.empty_like(xd[0]) for _ in range(n_out)]
 
     ev = HipEvents()
@@ -362,7 +381,7 @@ def main() -> int:
         encode(x, sb, meta, ws, st)
         if timed_idx is not None:
             binding.slicer_profile_events(*e_dec[timed_idx])
-        binding.slicer_decode_as(sb, meta, ys[i % n_out], M, stream=st)
+        decode(sb, meta, ys[i % n_out], st)
 
     def fork():                                   # the side streams start after everything queued on the current one
         cur = torch.cuda.current_stream()
@@ -484,8 +503,7 @@ def main() -> int:
         return ev.elapsed_ms(a, b) / K
 
     enc_call_ms = timed_loop(lambda i: encode(xd[i % n_buf], *bufs[i % n_out]))
-    dec_call_ms = timed_loop(lambda i: binding.slicer_decode_as(bufs[i % n_out][0], bufs[i % n_out][1],
-                                                                  ys[i % n_out], M))
+    dec_call_ms = timed_loop(lambda i: decode(bufs[i % n_out][0], bufs[i % n_out][1], ys[i % n_out]))
 
     # compressed size of the last batch encoded into bufs[0]
     encode(xd[0], *bufs[0])
@@ -500,7 +518,7 @@ def main() -> int:
     mh = bufs[0][1][:meta_bytes].cpu().numpy()
     R_, M_ = wl.rows, M
     n_kept = int(mh[64 + 8 * R_: 64 + 16 * R_].view(np.uint32).sum())
-    w_bits = max(1, int(np.ceil(np.log2(wl.row_len)))) if wl.row_len > 1 else 1
+    w_bits = max(1, int(np.ceil(np.log2(csr if csr is not None else wl.row_len)))) if (csr or wl.row_len) > 1 else 1   # (CSR: column bits; the row pointers count with the values below)
     idx_bits_total = n_kept * w_bits
     value_bits_total = 32 * words - idx_bits_total          # codes + the word padding of each row
     bit_split = {"index_bits_per_element": idx_bits_total / n_el, "value_bits_per_element": value_bits_total / n_el,
@@ -515,8 +533,12 @@ def main() -> int:
         path = 0 if path == 3 else path
     if asym and path != 1:
         path = 0                                         # the second selection: one-wavefront-per-row kernel, else the generic kernel
+    if csr is not None:
+        path = 0                                         # two-dimensional instances: the one-workgroup-per-instance encoder
     enc_kernel = {0: "enc_generic_kernel", 1: "enc_small_kernel", 2: "lr_* stages (hist..pack)", 3: "enc_wg_kernel"}[path]
     dec_kernel = "dec_small_kernel" if wl.row_len * (4 if wl.dtype == "f32" else 2) <= 16384 else "dec_kernel"
+    if csr is not None:
+        dec_kernel = "dec_csr_kernel"
     enc_alg_bytes = in_bytes + out_bytes                 # read x once, write stream + meta
     dec_alg_bytes = out_bytes + in_bytes                 # read stream + meta, write y once
     achieved = enc_alg_bytes / (enc_ms * 1e-3) / 1e9
@@ -541,7 +563,7 @@ def main() -> int:
 
     # all five configurations, each at its full size, in short single-stream loops
     workloads = None
-    plain = not (ladder or args.ds is not None or args.lam is not None or args.keep_ratio is not None or args.n_blocks is not None)
+    plain = csr is None and not (ladder or args.ds is not None or args.lam is not None or args.keep_ratio is not None or args.n_blocks is not None)
     if plain and not args.no_workloads:
         del xd, x0, bufs, ys
         torch.cuda.empty_cache()
@@ -559,7 +581,8 @@ def main() -> int:
         "dtype": wl.dtype, "data": "synthetic", "launch": launch,
         "config": {"workload": f"{wl.name} [{wl.rows}x{wl.row_len}] keep={keep} M={M} "
                                + (f"ladder={ladder}" if ladder else f"bits=2..8 DS delta={args.ds}" if args.ds is not None
-                                  else f"bits=2..8 budget={beta}") + (f" lambda={args.lam}" if args.lam is not None else ""),
+                                  else f"bits=2..8 budget={beta}") + (f" lambda={args.lam}" if args.lam is not None else "")
+                               + (f" CSR blocks, instances of {wl.row_len // csr}x{csr}" if csr is not None else ""),
                    "input_bytes": in_bytes, "distinct_input_buffers": n_buf},
         "encode": {"GBps": in_bytes / (enc_call_ms * 1e-3) / 1e9, "ms": enc_call_ms,
                    "elements_per_s": n_el / (enc_call_ms * 1e-3),

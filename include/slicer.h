@@ -180,7 +180,8 @@ int slicer_check_pn(const void* meta, uint64_t stream_words, slicer_dtype dt, in
  * then the codes (v), LSB-first, padded to a word.  Header: offset 44 holds wc, offset 60 n_cols (0
  * there marks the flat index format of slicer_encode); meta arrays as slicer_encode.
  *   stream_capacity_bytes  instances * ceil((2 n_blocks (n_rows + 1) wp + k (wc + q_bit)) / 32) * 4
- * n_rows * n_cols < 2^31.  Served by the one-workgroup-per-instance encoder.  slicer_decode reads the
+ * n_rows * n_cols < 2^31.  The flat encoder of the shape does the work (its stream goes to the
+ * workspace) and two short kernels re-pack the index section into this form.  slicer_decode reads the
  * index format from the header; slicer_decode_as_csr takes the shape from the caller (it reads k from
  * the header in meta for the pointer width, nothing else).  slicer_check_csr is slicer_check for these
  * metas (slicer_check itself rejects them); the decoder clamps every row pointer to its block and every

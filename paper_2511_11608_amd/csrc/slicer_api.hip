@@ -13,6 +13,7 @@
 #include "slicer_encode_wg.hpp"
 #include "slicer_encode_large.hpp"
 #include "slicer_decode.hpp"
+#include "slicer_csr.hpp"
 
 using namespace slicer;
 
@@ -63,7 +64,7 @@ int index_bits(int64_t N)
 
 struct Plan {
     int64_t k;
-    int w, qmax, wc, wp;    // wc, wp: bits of a column / a row pointer of a two-dimensional instance
+    int w, qmax;
     u64 cap_words;          // per row
     size_t off_row_words, off_slots, off_kept, off_bo_idx, off_bo_val, off_fallback, off_row_local, off_chunk_tot, off_hint, total;
     // row-resident fast path (0 = not eligible)
@@ -86,9 +87,7 @@ int count_bits(int64_t k)      // bits that hold any value in 0..k
     return w;
 }
 
-// csr_cols > 0: two-dimensional instances of (row_len / csr_cols) x csr_cols, blocks stored as CSR triples
-Plan make_plan(int dt, int64_t rows, int64_t row_len, double keep_ratio, int n_blocks, int n_blocks_neg, uint32_t bit_set,
-               int64_t csr_cols = 0)
+Plan make_plan(int dt, int64_t rows, int64_t row_len, double keep_ratio, int n_blocks, int n_blocks_neg, uint32_t bit_set)
 {
     const int B2_all = n_blocks + n_blocks_neg;          // blocks per row
     Plan p;
@@ -97,11 +96,7 @@ Plan make_plan(int dt, int64_t rows, int64_t row_len, double keep_ratio, int n_b
     p.qmax = 16;
     while (!((bit_set >> p.qmax) & 1u)) --p.qmax;
     p.cap_words = ((u64)p.k * (u64)(p.w + p.qmax) + 31) / 32;
-    p.wc = 0; p.wp = 0;
-    if (csr_cols > 0) {
-        p.wc = index_bits(csr_cols); p.wp = count_bits(p.k);
-        p.cap_words = ((u64)B2_all * (u64)(row_len / csr_cols + 1) * (u64)p.wp + (u64)p.k * (u64)(p.wc + p.qmax) + 31) / 32;
-    }
+
     size_t o = 0;
     p.off_row_words = o; o = align256(o + 8 * (size_t)rows);
     p.off_slots = o;     o = align256(o + 4 * (size_t)rows * (size_t)p.cap_words);
@@ -120,7 +115,7 @@ Plan make_plan(int dt, int64_t rows, int64_t row_len, double keep_ratio, int n_b
         const int64_t capL = (p.k + std::max<int64_t>(4096, row_len / 16) + 7) & ~(int64_t)7;   // whole 16-byte groups of 2-byte entries
         int nq_l = 0;
         for (int q = 1; q <= 16; ++q) nq_l += (bit_set >> q) & 1u;
-        if (csr_cols == 0 && row_len > 4096 && row_len % epc_l == 0 && C <= 1024 && rows <= 65535 && capL < ((int64_t)1 << 27)) {
+        if (row_len > 4096 && row_len % epc_l == 0 && C <= 1024 && rows <= 65535 && capL < ((int64_t)1 << 27)) {
             const size_t R = (size_t)rows, B2 = (size_t)B2_all;
             p.large_C = (int)C; p.large_capL = (u32)capL; p.large_LC = (int)((capL + kLCE - 1) / kLCE);
             p.lo_ch_cum = o;    o = align256(o + 4 * R * (size_t)C * kLBins);
@@ -151,7 +146,7 @@ Plan make_plan(int dt, int64_t rows, int64_t row_len, double keep_ratio, int n_b
     const int64_t max_n = dt == SLICER_F32 ? 4096 : 8192;
     int nq = 0;
     for (int q = 1; q <= 16; ++q) nq += (bit_set >> q) & 1u;
-    if (csr_cols == 0 && row_len % epc == 0 && row_len <= max_n && B2_all <= kWave) {
+    if (row_len % epc == 0 && row_len <= max_n && B2_all <= kWave) {
         const int64_t margin = std::max<int64_t>(64, row_len / (dt == SLICER_F32 ? 16 : 32));  // room for the undecided coarse bin
         int64_t cap = std::min<int64_t>(1984, (p.k + margin + 63) / 64 * 64);   // ranks are 11-bit fields
         int epl = epc;
@@ -167,7 +162,7 @@ Plan make_plan(int dt, int64_t rows, int64_t row_len, double keep_ratio, int n_b
     // One workgroup per row (four wavefronts share the row): bf16 rows too long for one wavefront, and
     // rows of more than 4096 elements in batches too small to fill the chip with one wavefront each.
     p.wg_ept = 0; p.wg_nw = 0; p.wg_cap = 0; p.wg_region0 = 0; p.wg_lds_bytes = 0;
-    if (csr_cols == 0 && dt == SLICER_BF16 && row_len % 8 == 0 && row_len > 4096 && row_len <= 32768 && B2_all <= kWave &&
+    if (dt == SLICER_BF16 && row_len % 8 == 0 && row_len > 4096 && row_len <= 32768 && B2_all <= kWave &&
         (row_len > 8192 || rows <= 1024)) {
         const int64_t margin = std::max<int64_t>(64, row_len / 32);
         const int64_t cap = std::min<int64_t>(1984, (p.k + margin + 63) / 64 * 64);
@@ -366,7 +361,7 @@ int slicer_encode_path(slicer_dtype dt, int64_t rows, int64_t row_len, double ke
 
 static int encode_impl(const void* x, slicer_dtype dt, int64_t rows, int64_t row_len, double keep_ratio,
                        int n_blocks, int n_blocks_neg, uint32_t bit_set, double distortion_budget, const Ladder& lad, int guard,
-                       void* stream, void* meta, void* workspace, void* hip_stream, double lambda = 0.0, int64_t csr_cols = 0)
+                       void* stream, void* meta, void* workspace, void* hip_stream, double lambda = 0.0)
 {
     if (!(lambda >= 0.0 && lambda < 1.0)) return SLICER_EINVAL;
     const bool asym = (float)lambda > 0.0f;      // lambda = 0 is the plain top-K filter: every fast path applies
@@ -377,7 +372,7 @@ static int encode_impl(const void* x, slicer_dtype dt, int64_t rows, int64_t row
     if (rows >= ((int64_t)1 << 31)) return SLICER_EINVAL;
     if (n_blocks_neg < 1 || n_blocks_neg > SLICER_MAX_BLOCKS) return SLICER_EINVAL;
     hipStream_t st = (hipStream_t)hip_stream;
-    Plan p = make_plan((int)dt, rows, row_len, keep_ratio, n_blocks, n_blocks_neg, bit_set, csr_cols);
+    Plan p = make_plan((int)dt, rows, row_len, keep_ratio, n_blocks, n_blocks_neg, bit_set);
     char* ws = (char*)workspace;
 
     EncArgs ea;
@@ -403,8 +398,6 @@ static int encode_impl(const void* x, slicer_dtype dt, int64_t rows, int64_t row
     ea.asym = asym ? 1 : 0;
     ea.one_plus = 1.0f + (float)lambda;
     ea.one_minus = 1.0f - (float)lambda;
-    ea.csr_cols = csr_cols; ea.csr_rows = csr_cols > 0 ? row_len / csr_cols : 0;
-    ea.wc = p.wc; ea.wp = p.wp;
 
     // asymmetric thresholds need a second selection over a subset of the row: the generic kernel has it for
     // every shape, the row-resident kernel for bf16 rows (rows it flags are redone generically, same rule)
@@ -511,8 +504,6 @@ static int encode_impl(const void* x, slicer_dtype dt, int64_t rows, int64_t row
     fa.chunk_tot = (u64*)(ws + p.off_chunk_tot);
     fa.slots = ea.slots;
     fa.cap_words = p.cap_words;
-    fa.hdr_w = csr_cols > 0 ? (u32)p.wc : (u32)p.w;
-    fa.hdr_cols = (u32)csr_cols;
     fa.chunks_per_row = (int)std::max<u64>(1, (p.cap_words + kGatherWords - 1) / kGatherWords);
     fa.stream = (u32*)stream;
     fa.meta = meta;
@@ -602,6 +593,29 @@ static int check_csr_shape(int64_t n_rows, int64_t n_cols)
     return SLICER_OK;
 }
 
+// Two-dimensional instances: the flat encode (any kernel family) writes its stream into the workspace, the
+// repack kernels turn it into the CSR form.  Workspace: the flat plan's, then the flat stream, then its offsets.
+struct CsrPlan {
+    Plan flat;
+    int wc, wp;
+    u64 cap_words;          // per instance, CSR form
+    size_t off_tmp, off_flat_off, total;
+};
+
+static CsrPlan make_csr_plan(int dt, int64_t instances, int64_t n_rows, int64_t n_cols, double keep_ratio, int n_blocks,
+                             uint32_t bit_set)
+{
+    CsrPlan c;
+    c.flat = make_plan(dt, instances, n_rows * n_cols, keep_ratio, n_blocks, n_blocks, bit_set);
+    c.wc = index_bits(n_cols); c.wp = count_bits(c.flat.k);
+    c.cap_words = ((u64)(2 * n_blocks) * (u64)(n_rows + 1) * (u64)c.wp + (u64)c.flat.k * (u64)(c.wc + c.flat.qmax) + 31) / 32;
+    size_t o = align256(c.flat.total);
+    c.off_tmp = o;      o = align256(o + 4 * (size_t)instances * (size_t)c.flat.cap_words + 8);   // (+ one readable word)
+    c.off_flat_off = o; o = align256(o + 8 * (size_t)instances);
+    c.total = o;
+    return c;
+}
+
 int slicer_sizes_csr(slicer_dtype dt, int64_t instances, int64_t n_rows, int64_t n_cols, double keep_ratio, int n_blocks,
                      uint32_t bit_set, size_t* stream_capacity_bytes, size_t* meta_bytes_out, size_t* workspace_bytes)
 {
@@ -609,10 +623,10 @@ int slicer_sizes_csr(slicer_dtype dt, int64_t instances, int64_t n_rows, int64_t
     if (rc) return rc;
     rc = check_args((int)dt, instances, n_rows * n_cols, keep_ratio, n_blocks, bit_set);
     if (rc) return rc;
-    Plan p = make_plan((int)dt, instances, n_rows * n_cols, keep_ratio, n_blocks, n_blocks, bit_set, n_cols);
-    if (stream_capacity_bytes) *stream_capacity_bytes = (size_t)(p.cap_words * 4ull * (u64)instances);
+    const CsrPlan c = make_csr_plan((int)dt, instances, n_rows, n_cols, keep_ratio, n_blocks, bit_set);
+    if (stream_capacity_bytes) *stream_capacity_bytes = (size_t)(c.cap_words * 4ull * (u64)instances);
     if (meta_bytes_out) *meta_bytes_out = meta_bytes(instances, 2 * n_blocks);
-    if (workspace_bytes) *workspace_bytes = p.total;
+    if (workspace_bytes) *workspace_bytes = c.total;
     return SLICER_OK;
 }
 
@@ -622,11 +636,46 @@ int slicer_encode_csr(const void* x, slicer_dtype dt, int64_t instances, int64_t
 {
     int rc = check_csr_shape(n_rows, n_cols);
     if (rc) return rc;
+    rc = check_args((int)dt, instances, n_rows * n_cols, keep_ratio, n_blocks, bit_set);
+    if (rc) return rc;
+    if (!x || !stream || !meta || !workspace) return SLICER_EINVAL;
+    const CsrPlan c = make_csr_plan((int)dt, instances, n_rows, n_cols, keep_ratio, n_blocks, bit_set);
+    const u64 nwin = std::max<u64>(1, (c.cap_words + kCsrWin - 1) / kCsrWin);
+    if ((u64)instances * nwin >= (1ull << 31)) return SLICER_EINVAL;
+    char* ws = (char*)workspace;
+    hipStream_t st = (hipStream_t)hip_stream;
     Ladder none;
     none.on = 0;
     for (int j = 0; j < kMaxBlocks / 8; ++j) none.nib[j] = 0;
-    return encode_impl(x, dt, instances, n_rows * n_cols, keep_ratio, n_blocks, n_blocks, bit_set, distortion_budget, none, 0,
-                       stream, meta, workspace, hip_stream, 0.0, n_cols);
+    // flat encode: kept set, blocks, ranges, bitwidths, codes, flat indices (its stream goes to the workspace)
+    rc = encode_impl(x, dt, instances, n_rows * n_cols, keep_ratio, n_blocks, n_blocks, bit_set, distortion_budget, none, 0,
+                     ws + c.off_tmp, meta, workspace, hip_stream);
+    if (rc) return rc;
+    CsrArgs ca;
+    ca.R = instances; ca.n_rows = n_rows; ca.n_cols = n_cols; ca.k = c.flat.k;
+    ca.M = n_blocks; ca.Mn = n_blocks; ca.w = c.flat.w; ca.wc = c.wc; ca.wp = c.wp; ca.dt = (int)dt;
+    ca.bit_set = bit_set;
+    ca.nwin = (int)nwin;
+    ca.flat = (const u32*)(ws + c.off_tmp);
+    ca.flat_off = (u64*)(ws + c.off_flat_off);
+    ca.row_words = (u64*)(ws + c.flat.off_row_words);
+    ca.row_off_local = (const u64*)(ws + c.flat.off_row_local);
+    ca.chunk_tot = (const u64*)(ws + c.flat.off_chunk_tot);
+    ca.stream = (u32*)stream; ca.meta = meta;
+    ca.mv = meta_view(meta, instances, 2 * n_blocks);
+    hipLaunchKernelGGL(csr_sizes_kernel, dim3((unsigned)((instances + 255) / 256)), dim3(256), 0, st, ca);
+    FinishArgs fa;                                           // the row-offset scan, now over the CSR segment lengths
+    fa.R = instances; fa.N = n_rows * n_cols; fa.k = c.flat.k;
+    fa.M = n_blocks; fa.Mn = n_blocks; fa.w = c.flat.w; fa.dt = (int)dt; fa.bit_set = bit_set;
+    fa.row_words = ca.row_words;
+    fa.row_off_local = (u64*)(ws + c.flat.off_row_local);
+    fa.chunk_tot = (u64*)(ws + c.flat.off_chunk_tot);
+    fa.slots = nullptr; fa.cap_words = c.cap_words; fa.chunks_per_row = 1;
+    fa.stream = (u32*)stream; fa.meta = meta; fa.mv = ca.mv;
+    hipLaunchKernelGGL(enc_rowscan_kernel, dim3((unsigned)((instances + kScanRows - 1) / kScanRows)), dim3(kScanRows), 0, st, fa);
+    hipLaunchKernelGGL(csr_repack_kernel, dim3((unsigned)((u64)instances * nwin)), dim3(256), 0, st, ca);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? SLICER_OK : hip_fail(e);
 }
 
 static int launch_decode_csr(const void* stream, const void* meta, void* y, int dt, int64_t instances, int64_t n_rows,

@@ -262,7 +262,7 @@ __global__ __launch_bounds__(256) void dec_csr_kernel(DecCsrArgs a)
     __shared__ raw_t tile[kCsrImage];
     __shared__ float vminf[kMaxB2], stepf[kMaxB2];
     __shared__ int qv[kMaxB2];
-    __shared__ u32 istart[kMaxB2 + 1], p_lo[kMaxB2], p_hi[kMaxB2];
+    __shared__ u32 istart[kMaxB2 + 1], p_lo[kMaxB2], p_hi[kMaxB2], pre[kMaxB2 + 1];
     __shared__ u64 cstart[kMaxB2 + 1];
     const int tid = threadIdx.x;
     const int64_t inst = (int64_t)blockIdx.x / a.n_rows, trow = (int64_t)blockIdx.x % a.n_rows;
@@ -300,28 +300,39 @@ __global__ __launch_bounds__(256) void dec_csr_kernel(DecCsrArgs a)
     __syncthreads();
     if (tid == 0) {
         u64 acc = ptr_bits + (u64)n * (u64)wc;
-        for (int b = 0; b < B2; ++b) { cstart[b] = acc; acc += (u64)(istart[b + 1] - istart[b]) * (u64)qv[b]; }
+        u32 cnt = 0;
+        for (int b = 0; b < B2; ++b) {
+            cstart[b] = acc; acc += (u64)(istart[b + 1] - istart[b]) * (u64)qv[b];
+            pre[b] = cnt; cnt += p_hi[b] - p_lo[b];
+        }
+        pre[B2] = cnt;
     }
     __syncthreads();
+    const u32 row_total = pre[B2];
     raw_t* __restrict__ yrow = (raw_t*)a.y + (size_t)inst * (size_t)T + (size_t)trow * (size_t)a.n_cols;
     for (int64_t c0 = 0; c0 < a.n_cols; c0 += kCsrImage) {
         const int len = (int)(a.n_cols - c0 < kCsrImage ? a.n_cols - c0 : kCsrImage);
         for (int i = tid; i < len; i += 256) tile[i] = (raw_t)0;
         __syncthreads();
-        for (int b = 0; b < B2; ++b) {
-            const int q = qv[b];
-            const float vmin = vminf[b], step = stepf[b];
-            const u32 sign = b >= M ? 1u : 0u;
-            for (u32 p = p_lo[b] + (u32)tid; p < p_hi[b]; p += 256) {
-                const u32 e = istart[b] + p;
-                const int64_t col = (int64_t)read_bits(rw, ptr_bits + (u64)e * (u64)wc, wc) - c0;
-                if (col < 0 || col >= len) continue;
-                const u32 c = read_bits(rw, cstart[b] + (u64)p * (u64)q, q);
-                float v = __fadd_rn(vmin, __fmul_rn((float)c, step));
-                if (sign) v = -v;
-                if (DT == 0) tile[col] = (raw_t)__float_as_uint(v);
-                else tile[col] = (raw_t)f32_to_bf16_rne(v);
+        // all entries of this tensor row at once: entry t of the row belongs to the block whose range of the
+        // prefix holds t (the blocks' shares are short, so a loop per block would leave most threads idle)
+        for (u32 t = (u32)tid; t < row_total; t += 256) {
+            int bl = 0, bh = B2 - 1;                     // last block whose prefix is <= t
+            while (bl < bh) {
+                const int mid = (bl + bh + 1) >> 1;
+                if (pre[mid] <= t) bl = mid; else bh = mid - 1;
             }
+            const int b = bl;
+            const u32 p = p_lo[b] + (t - pre[b]);
+            const int q = qv[b];
+            const u32 e = istart[b] + p;
+            const int64_t col = (int64_t)read_bits(rw, ptr_bits + (u64)e * (u64)wc, wc) - c0;
+            if (col < 0 || col >= len) continue;
+            const u32 c = read_bits(rw, cstart[b] + (u64)p * (u64)q, q);
+            float v = __fadd_rn(vminf[b], __fmul_rn((float)c, stepf[b]));
+            if (b >= M) v = -v;
+            if (DT == 0) tile[col] = (raw_t)__float_as_uint(v);
+            else tile[col] = (raw_t)f32_to_bf16_rne(v);
         }
         __syncthreads();
         for (int i = tid; i < len; i += 256) yrow[c0 + i] = tile[i];

@@ -35,10 +35,6 @@ struct EncArgs {
     int guard;              // 0: relative squared-error budget (beta); 1: the DS mismatch of Eq. "DS" (beta = delta), greedy descent
     int asym;               // 1: asymmetric thresholds of Sec. 3.1 (lambda > 0)
     float one_plus, one_minus;   // 1 + lambda, 1 - lambda in fp32
-    // two-dimensional instances (Sec. 3.2 step 3): csr_cols > 0 stores every block as CSR(values, columns,
-    // row pointers) over a csr_rows x csr_cols tensor, N = csr_rows * csr_cols; wc bits per column, wp per pointer
-    int64_t csr_rows, csr_cols;
-    int wc, wp;
     // meta
     MetaView mv;
 };
@@ -561,13 +557,7 @@ __device__ inline void enc_generic_rows(const EncArgs& a, const int64_t r_begin,
     // ------------------------------------------------------------------
     // packing into the row's slot, staged through LDS one chunk at a time
     // ------------------------------------------------------------------
-    // index section: flat indices of w bits, or (two-dimensional instance) the row pointers of every block
-    // followed by the column of every entry
-    const bool csr = a.csr_cols > 0;
-    const int wi = csr ? a.wc : w;
-    const u64 n_ptr = csr ? (u64)B2 * (u64)(a.csr_rows + 1) : 0;
-    const u64 ptr_bits = n_ptr * (u64)a.wp;
-    const u64 idx_bits = ptr_bits + (u64)n * (u64)wi;
+    const u64 idx_bits = (u64)n * (u64)w;
     const u64 row_bits = idx_bits + code_off[B2];
     u64 row_words = (row_bits + 31) >> 5;
     if (row_words > a.cap_words) row_words = a.cap_words;   // cannot happen: the capacity is the worst case
@@ -593,29 +583,12 @@ __device__ inline void enc_generic_rows(const EncArgs& a, const int64_t r_begin,
             s_range[0] = plo; s_range[1] = phi;
         }
         __syncthreads();
-        if (lo < ptr_bits) {
-            // row pointer j of block b = number of the block's entries in tensor rows before j: a lower-bound
-            // search for j * csr_cols in the block's ascending index list
-            const u64 f0 = lo / (u64)a.wp;
-            u64 f1 = (hi + (u64)a.wp - 1) / (u64)a.wp;
-            if (f1 > n_ptr) f1 = n_ptr;
-            for (u64 f = f0 + tid; f < f1; f += BLOCK) {
-                const u32 b = (u32)(f / (u64)(a.csr_rows + 1));
-                const u64 target = (f % (u64)(a.csr_rows + 1)) * (u64)a.csr_cols;
-                u32 l = blk_start[b], h = blk_start[b + 1];
-                while (l < h) {
-                    const u32 mid = (l + h) >> 1;
-                    if ((u64)bo_idx[mid] < target) l = mid + 1; else h = mid;
-                }
-                stage_or_bits(sA, lo, hi, f * (u64)a.wp, l - blk_start[b], a.wp);
-            }
-        }
-        if (lo < idx_bits && hi > ptr_bits) {
-            u64 p0 = lo > ptr_bits ? (lo - ptr_bits) / (u64)wi : 0;
-            u64 p1 = (hi - ptr_bits + (u64)wi - 1) / (u64)wi;
+        if (lo < idx_bits) {
+            u64 p0 = lo / (u64)w;
+            u64 p1 = (hi + (u64)w - 1) / (u64)w;
             if (p1 > n) p1 = n;
             for (u64 p = p0 + tid; p < p1; p += BLOCK)
-                stage_or_bits(sA, lo, hi, ptr_bits + p * (u64)wi, csr ? (u32)((u64)bo_idx[p] % (u64)a.csr_cols) : bo_idx[p], wi);
+                stage_or_bits(sA, lo, hi, p * (u64)w, bo_idx[p], w);
         }
         {
             const u32 p0 = s_range[0], p1 = s_range[1];
@@ -666,7 +639,6 @@ struct FinishArgs {
     u64* chunk_tot;         // [ceil(R / kScanRows)]
     const u32* slots;
     u64 cap_words;
-    u32 hdr_w, hdr_cols;    // header: bits of an index field (flat index or column), n_cols of a two-dimensional instance (0: flat)
     int chunks_per_row;     // gather wavefronts per row (kGatherWords words each)
     u32* stream;
     void* meta;
@@ -745,10 +717,10 @@ __global__ __launch_bounds__(256) void enc_gather_kernel(FinishArgs a)
         u64* h64 = (u64*)a.meta;
         h32[0] = kMagic; h32[1] = kVersion; h32[2] = (u32)a.dt; h32[3] = (u32)a.M;
         h64[2] = (u64)a.R; h64[3] = (u64)a.N; h64[4] = (u64)a.k;
-        h32[10] = a.bit_set; h32[11] = a.hdr_w;
+        h32[10] = a.bit_set; h32[11] = (u32)a.w;
         h64[6] = total;
         h32[14] = a.Mn != a.M ? (u32)a.Mn : 0u;        // 0: the negative class has M blocks too
-        h32[15] = a.hdr_cols;
+        h32[15] = 0;
         uint8_t* m8 = (uint8_t*)a.meta;     // zero the padding after the last array
         for (size_t o = kHeaderBytes + 16 * (size_t)a.R + 9 * (size_t)a.R * (a.M + a.Mn); o < meta_bytes(a.R, a.M + a.Mn); ++o) m8[o] = 0;
     }
