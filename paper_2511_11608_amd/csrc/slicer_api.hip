@@ -687,7 +687,10 @@ static int launch_decode_csr(const void* stream, const void* meta, void* y, int 
     da.M = n_blocks; da.Mn = n_blocks_neg; da.wc = index_bits(n_cols);
     da.mv = meta_view(const_cast<void*>(meta), instances, n_blocks + n_blocks_neg);
     da.k_keep = (const u64*)meta + 4;
-    const u64 grid = (u64)instances * (u64)n_rows;
+    // several short tensor rows per workgroup, as long as about a thousand workgroups remain
+    da.rows_per_wg = (int)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(kCsrRows, instances * n_rows / 1024), kCsrImage / n_cols));
+    da.groups = (n_rows + da.rows_per_wg - 1) / da.rows_per_wg;
+    const u64 grid = (u64)instances * (u64)da.groups;
     if (grid >= (1ull << 31)) return SLICER_EINVAL;
     const bool timed = g_ev_start && g_ev_stop;
     if (timed) SLICER_HIP(hipEventRecord(g_ev_start, st));

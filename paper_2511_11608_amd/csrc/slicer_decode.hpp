@@ -249,11 +249,14 @@ struct DecCsrArgs {
     void* y;
     int64_t R, n_rows, n_cols;     // R instances of n_rows x n_cols
     int M, Mn, wc;
+    int rows_per_wg;               // consecutive tensor rows a workgroup decodes (their elements fit the LDS image)
+    int64_t groups;                // workgroups per instance = ceil(n_rows / rows_per_wg)
     MetaView mv;
     const u64* k_keep;             // header field k: fixes the width of a row pointer
 };
 
 constexpr int kCsrImage = 8192;    // elements of the LDS image
+constexpr int kCsrRows = 16;       // tensor rows per workgroup at most
 
 template <int DT>
 __global__ __launch_bounds__(256) void dec_csr_kernel(DecCsrArgs a)
@@ -262,10 +265,13 @@ __global__ __launch_bounds__(256) void dec_csr_kernel(DecCsrArgs a)
     __shared__ raw_t tile[kCsrImage];
     __shared__ float vminf[kMaxB2], stepf[kMaxB2];
     __shared__ int qv[kMaxB2];
-    __shared__ u32 istart[kMaxB2 + 1], p_lo[kMaxB2], p_hi[kMaxB2], pre[kMaxB2 + 1];
+    __shared__ u32 istart[kMaxB2 + 1], pre[kMaxB2 + 1];
+    __shared__ u32 ptrs[kMaxB2][kCsrRows + 1];       // row pointers trow0 .. trow0 + nr of every block
     __shared__ u64 cstart[kMaxB2 + 1];
     const int tid = threadIdx.x;
-    const int64_t inst = (int64_t)blockIdx.x / a.n_rows, trow = (int64_t)blockIdx.x % a.n_rows;
+    const int64_t inst = (int64_t)blockIdx.x / a.groups;
+    const int64_t trow0 = ((int64_t)blockIdx.x % a.groups) * a.rows_per_wg;
+    const int nr = (int)(a.n_rows - trow0 < a.rows_per_wg ? a.n_rows - trow0 : a.rows_per_wg);
     const int M = a.M, B2 = a.M + a.Mn, wc = a.wc;
     const int64_t T = a.n_rows * a.n_cols;
     const u32* __restrict__ rw = a.stream + a.mv.row_off[inst];
@@ -280,62 +286,76 @@ __global__ __launch_bounds__(256) void dec_csr_kernel(DecCsrArgs a)
     const u64 ptr_bits = (u64)B2 * (u64)(a.n_rows + 1) * (u64)wp;
     if (tid < B2) {
         const int s = tid >= M ? 1 : 0, m = tid - s * M, Ms = s ? a.Mn : M;
-        const u32 K = n_cls[s] / (u32)Ms;
         const size_t mi = (size_t)inst * (size_t)B2 + tid;
         const int q = a.mv.q[mi] & 0x7F;
         qv[tid] = q;
         const float vmin = a.mv.vmin[mi], vmax = a.mv.vmax[mi];
         vminf[tid] = vmin;
         stepf[tid] = __fdiv_rn(__fsub_rn(vmax, vmin), (float)((1u << q) - 1u));
-        istart[tid] = (s ? n_cls[0] : 0u) + (u32)m * K;
-        // this tensor row's share of the block: entries [r[trow], r[trow + 1]) of the block
-        const u64 pb = ((u64)tid * (u64)(a.n_rows + 1) + (u64)trow) * (u64)wp;
-        u32 lo = read_bits(rw, pb, wp), hi = read_bits(rw, pb + (u64)wp, wp);
-        const u32 cnt = (m < Ms - 1) ? K : n_cls[s] - (u32)m * K;
-        if (hi > cnt) hi = cnt;                                           // a forged pointer cannot leave the block
-        if (lo > hi) lo = hi;
-        p_lo[tid] = lo; p_hi[tid] = hi;
+        istart[tid] = (s ? n_cls[0] : 0u) + (u32)m * (n_cls[s] / (u32)Ms);
     }
     if (tid == 0) istart[B2] = n;
+    // the blocks' shares of these tensor rows: entries [r[trow0], r[trow0 + nr]) of every block, row by row;
+    // pointers are clamped to the block and made non-decreasing, so a forged stream cannot leave it
+    for (int i = tid; i < B2 * (nr + 1); i += 256) {
+        const int b = i / (nr + 1), j = i - b * (nr + 1);
+        const int s = b >= M ? 1 : 0, m = b - s * M, Ms = s ? a.Mn : M;
+        const u32 K = n_cls[s] / (u32)Ms;
+        const u32 cnt = (m < Ms - 1) ? K : n_cls[s] - (u32)m * K;
+        const u32 v = read_bits(rw, ((u64)b * (u64)(a.n_rows + 1) + (u64)(trow0 + j)) * (u64)wp, wp);
+        ptrs[b][j] = v < cnt ? v : cnt;
+    }
+    __syncthreads();
+    if (tid < B2) {
+        u32 run = ptrs[tid][0];
+        for (int j = 1; j <= nr; ++j) { run = ptrs[tid][j] > run ? ptrs[tid][j] : run; ptrs[tid][j] = run; }
+    }
     __syncthreads();
     if (tid == 0) {
         u64 acc = ptr_bits + (u64)n * (u64)wc;
         u32 cnt = 0;
         for (int b = 0; b < B2; ++b) {
             cstart[b] = acc; acc += (u64)(istart[b + 1] - istart[b]) * (u64)qv[b];
-            pre[b] = cnt; cnt += p_hi[b] - p_lo[b];
+            pre[b] = cnt; cnt += ptrs[b][nr] - ptrs[b][0];
         }
         pre[B2] = cnt;
     }
     __syncthreads();
-    const u32 row_total = pre[B2];
-    raw_t* __restrict__ yrow = (raw_t*)a.y + (size_t)inst * (size_t)T + (size_t)trow * (size_t)a.n_cols;
+    const u32 total = pre[B2];
+    raw_t* __restrict__ yrow = (raw_t*)a.y + (size_t)inst * (size_t)T + (size_t)trow0 * (size_t)a.n_cols;
+    // one piece of columns at a time (a single piece unless one tensor row is longer than the image)
     for (int64_t c0 = 0; c0 < a.n_cols; c0 += kCsrImage) {
         const int len = (int)(a.n_cols - c0 < kCsrImage ? a.n_cols - c0 : kCsrImage);
-        for (int i = tid; i < len; i += 256) tile[i] = (raw_t)0;
+        const int img = nr * len;                                  // nr > 1 only when a whole row fits: len = n_cols then
+        for (int i = tid; i < img; i += 256) tile[i] = (raw_t)0;
         __syncthreads();
-        // all entries of this tensor row at once: entry t of the row belongs to the block whose range of the
-        // prefix holds t (the blocks' shares are short, so a loop per block would leave most threads idle)
-        for (u32 t = (u32)tid; t < row_total; t += 256) {
+        // all entries of these tensor rows at once: entry t belongs to the block whose range of the prefix
+        // holds t, and to the tensor row whose pointer range holds its position in the block
+        for (u32 t = (u32)tid; t < total; t += 256) {
             int bl = 0, bh = B2 - 1;                     // last block whose prefix is <= t
             while (bl < bh) {
                 const int mid = (bl + bh + 1) >> 1;
                 if (pre[mid] <= t) bl = mid; else bh = mid - 1;
             }
             const int b = bl;
-            const u32 p = p_lo[b] + (t - pre[b]);
+            const u32 p = ptrs[b][0] + (t - pre[b]);
+            int row = 0;
+            while (row + 1 < nr && ptrs[b][row + 1] <= p) ++row;
             const int q = qv[b];
-            const u32 e = istart[b] + p;
-            const int64_t col = (int64_t)read_bits(rw, ptr_bits + (u64)e * (u64)wc, wc) - c0;
+            const int64_t col = (int64_t)read_bits(rw, ptr_bits + (u64)(istart[b] + p) * (u64)wc, wc) - c0;
             if (col < 0 || col >= len) continue;
             const u32 c = read_bits(rw, cstart[b] + (u64)p * (u64)q, q);
             float v = __fadd_rn(vminf[b], __fmul_rn((float)c, stepf[b]));
             if (b >= M) v = -v;
-            if (DT == 0) tile[col] = (raw_t)__float_as_uint(v);
-            else tile[col] = (raw_t)f32_to_bf16_rne(v);
+            if (DT == 0) tile[row * len + (int)col] = (raw_t)__float_as_uint(v);
+            else tile[row * len + (int)col] = (raw_t)f32_to_bf16_rne(v);
         }
         __syncthreads();
-        for (int i = tid; i < len; i += 256) yrow[c0 + i] = tile[i];
+        if (nr > 1) {
+            for (int i = tid; i < img; i += 256) yrow[i] = tile[i];           // whole rows, contiguous in y
+        } else {
+            for (int i = tid; i < len; i += 256) yrow[c0 + i] = tile[i];
+        }
         __syncthreads();
     }
 }
