@@ -513,7 +513,8 @@ def check_csr(oracle, x, dtype, n_rows, n_cols, keep, M, bits, budget):
 
 @pytest.mark.parametrize("dtype,inst,n_rows,n_cols", [("f32", 1, 64, 3136), ("f32", 3, 197, 768), ("bf16", 2, 128, 4096),
                                                       ("f32", 2, 5, 7), ("bf16", 4, 1, 1000), ("f32", 2, 1000, 1),
-                                                      ("bf16", 1, 3, 20000), ("f32", 1, 2048, 100)])
+                                                      ("bf16", 1, 3, 20000), ("f32", 1, 2048, 100),
+                                                      ("f32", 4, 4096, 50), ("bf16", 40, 300, 33)])   # many short tensor rows: 16 and 11 per decode workgroup
 def test_two_dimensional_instances_csr(oracle, dtype, inst, n_rows, n_cols):
     """Sec. 3.2 step 3: whole n_rows x n_cols tensors as one instance, blocks stored as CSR(values, columns,
     row pointers); the first shape is the CNN map of workload 1 as 64 channels x 56*56, the second a ViT
