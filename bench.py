@@ -533,9 +533,8 @@ def main() -> int:
         path = 0 if path == 3 else path
     if asym and path != 1:
         path = 0                                         # the second selection: one-wavefront-per-row kernel, else the generic kernel
-    if csr is not None:
-        path = 0                                         # two-dimensional instances: the one-workgroup-per-instance encoder
     enc_kernel = {0: "enc_generic_kernel", 1: "enc_small_kernel", 2: "lr_* stages (hist..pack)", 3: "enc_wg_kernel"}[path]
+    # (two-dimensional instances: the flat encoder of the shape is the dominant kernel; csr_repack_kernel follows it)
     dec_kernel = "dec_small_kernel" if wl.row_len * (4 if wl.dtype == "f32" else 2) <= 16384 else "dec_kernel"
     if csr is not None:
         dec_kernel = "dec_csr_kernel"
