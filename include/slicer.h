@@ -286,6 +286,21 @@ int slicer_stream_words(const void* meta, uint64_t* words, void* hip_stream);
  */
 int slicer_profile_events(void* start_event, void* stop_event);
 
+/*
+ * Diagnostic: runs ONE elementary operation of the codec's arithmetic (Sec. 3.2.1, Eq. "dequnt": the
+ * divisions, products, sums, roundings and scalings behind AIQ, the guard and the decoder), written as
+ * the kernels write it, on n pairs of 32-bit operands; for tests that compare the results bit for bit
+ * with the host's IEEE arithmetic.  a, b, out: device arrays of n 32-bit words (fp32 bit patterns).
+ *   op 0  a / b            1  __fdiv_rn(a, b)     2  a * b        3  a + b        4  a - b
+ *      5  rintf(a)         6  ldexpf(a, b mod 301 - 150)          7  a * b + 2^23 (two operations)
+ *      8  fp32 -> bf16, round to nearest even (result in the low 16 bits)
+ *      9  a + b * b (two operations)
+ *     10  energy grid: rint(|a| * 2^(20 - e)), e = ilogb(|a|) + 1 + (b mod 3), on the significand
+ *     11  hi ^ lo words of the double (a * a) * (double)b * 2^-30, all products in double
+ * Asynchronous on hip_stream.  SLICER_EINVAL for a null pointer, n <= 0 or an unknown op.
+ */
+int slicer_arith_probe(int op, const void* a, const void* b, void* out, int64_t n, void* hip_stream);
+
 /* hipError_t of the most recent failed HIP call made by this library on the
  * calling thread (0 if none). */
 int slicer_last_hip_error(void);

@@ -80,6 +80,8 @@ def load() -> C.CDLL:
         L.slicer_check.argtypes = [vp, C.c_uint64, cint, i64, i64, cint, vp, vp]
         L.slicer_stream_words.restype = cint
         L.slicer_stream_words.argtypes = [vp, C.POINTER(C.c_uint64), vp]
+        L.slicer_arith_probe.restype = cint
+        L.slicer_arith_probe.argtypes = [cint, vp, vp, vp, i64, vp]
         L.slicer_profile_events.restype = cint
         L.slicer_profile_events.argtypes = [vp, vp]
         L.slicer_last_hip_error.restype = cint
@@ -310,6 +312,12 @@ def slicer_stream_words(meta: torch.Tensor, stream=None) -> int:
     w = C.c_uint64(0)
     _check("slicer_stream_words", load().slicer_stream_words(meta.data_ptr(), C.byref(w), _stream_handle(stream)))
     return w.value
+
+
+def slicer_arith_probe(op: int, a: torch.Tensor, b: torch.Tensor, out: torch.Tensor, stream=None) -> None:
+    """One elementary operation of the codec's arithmetic on int32 tensors of fp32 bit patterns (see slicer.h)."""
+    _check("slicer_arith_probe", load().slicer_arith_probe(op, a.data_ptr(), b.data_ptr(), out.data_ptr(), a.numel(),
+                                                          _stream_handle(stream)))
 
 
 def slicer_profile_events(start_event, stop_event) -> None:

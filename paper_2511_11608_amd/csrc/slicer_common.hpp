@@ -158,8 +158,9 @@ __device__ inline u32 energy_grid(u32 bits, int e)
     u32 m = bits & 0x7FFFFFu;
     int ea;
     if (ex) { m |= 0x800000u; ea = ex - 127; } else { ea = -126; }
-    int s = 3 + e - ea;                 // a * 2^(20-e) = m / 2^s, s >= 4
+    int s = 3 + e - ea;                 // a * 2^(20-e) = m / 2^s; s >= 4 for normal numbers
     if (s > 25) return 0u;
+    if (s <= 0) return m << (-s);       // blocks of deep subnormals (largest value below 2^-129): exact, below 2^21
     u32 q = m >> s;
     u32 rem = m & ((1u << s) - 1u);
     u32 half = 1u << (s - 1);

@@ -82,11 +82,12 @@ def test_adversarial_rows(oracle, dtype, N):
 
 @pytest.mark.parametrize("dtype,rows,N", [("bf16", 40, 4096), ("f32", 40, 768), ("f32", 3, 50_000), ("bf16", 2, 40_960),
                                           ("f32", 5, 4097), ("bf16", 3, 1001)])
-@pytest.mark.parametrize("scale", [-105, -120, 100])
+@pytest.mark.parametrize("scale", [-105, -120, -143, 100])
 def test_tiny_and_huge_magnitudes(oracle, dtype, rows, N, scale):
     """The quantiser works on each block's own scale (Sec. 3.2.1 defines the step for any non-zero range):
-    tensors multiplied by 2^-105 or 2^-120 (block ranges far below what a scale L / range could hold in
-    fp32, the second partly denormal) and by 2^100 go through every encoder family bit-exactly."""
+    tensors multiplied by 2^-105, 2^-120 or 2^-143 (block ranges far below what a scale L / range could hold
+    in fp32; the second partly, the third wholly subnormal) and by 2^100 go through every encoder family
+    bit-exactly."""
     rng = np.random.default_rng(N + scale)
     x = rng.standard_normal((rows, N)).astype(np.float32)
     x[rng.random((rows, N)) < 0.3] = 0
