@@ -113,12 +113,6 @@ __device__ inline u32 wave_incl_scan(u32 v)
     return v;
 }
 
-__device__ inline u32 wave_sum(u32 v)
-{
-#pragma unroll
-    for (int d = kWave / 2; d > 0; d >>= 1) v += __shfl_xor(v, d);
-    return v;
-}
 
 // Exclusive prefix sum over the threads of a block (thread order); `total`
 // receives the block sum.  `scratch` holds BLOCK/64 + 1 words.  Two barriers.
@@ -204,6 +198,9 @@ __device__ inline u32 wave_scan_dpp(u32 v)
     r += dpp_get<0x143, 0xc, 0xf>(r);            // lane 31 -> rows 2,3
     return r;
 }
+
+// Sum over the 64 lanes, in every lane (data-parallel-primitive moves: no LDS crossbar traffic).
+__device__ inline u32 wave_sum(u32 v) { return bcast(wave_scan_dpp(v), kWave - 1); }
 
 // Maximum over the 64 lanes (unsigned), same data movement as the scan.
 __device__ inline u32 wave_max_dpp(u32 v)
