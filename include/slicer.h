@@ -249,7 +249,8 @@ int slicer_bound(slicer_dtype dt, int64_t rows, int64_t row_len, double keep_rat
  * name the dominant kernel): 0 = generic (one workgroup per row, any shape), 1 = row-resident
  * (one wavefront per row, rows up to 8192 bf16 / 4096 fp32 elements), 2 = long-row stages
  * (rows of more than 4096 elements that the row-resident kernel does not take), 3 = one workgroup per row
- * (bf16 rows of 4097..32768 elements: all of them beyond 8192, shorter ones in batches of up to 1024 rows).
+ * (rows of 4097..32768 bf16 / 4097..16384 fp32 elements: all of them beyond one wavefront's reach, bf16 rows
+ * of up to 8192 elements in batches of up to 1024 rows).
  * Assumes a 16-byte aligned x and the budget guard.  Negative: error code.
  */
 int slicer_encode_path(slicer_dtype dt, int64_t rows, int64_t row_len, double keep_ratio,

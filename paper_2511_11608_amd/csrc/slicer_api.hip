@@ -159,51 +159,56 @@ Plan make_plan(int dt, int64_t rows, int64_t row_len, double keep_ratio, int n_b
             p.small_maxs = maxs;
         }
     }
-    // One workgroup per row (four wavefronts share the row): bf16 rows too long for one wavefront, and
-    // rows of more than 4096 elements in batches too small to fill the chip with one wavefront each.
+    // One workgroup per row (the wavefronts of a workgroup share the row): rows too long for one wavefront
+    // (up to 32768 bf16 / 16384 fp32 elements), and bf16 rows of more than 4096 elements in batches too small
+    // to fill the chip with one wavefront each.
     p.wg_ept = 0; p.wg_nw = 0; p.wg_cap = 0; p.wg_region0 = 0; p.wg_lds_bytes = 0;
-    if (dt == SLICER_BF16 && row_len % 8 == 0 && row_len > 4096 && row_len <= 32768 && B2_all <= kWave &&
-        (row_len > 8192 || rows <= 1024)) {
-        const int64_t margin = std::max<int64_t>(64, row_len / 32);
-        const int64_t cap = std::min<int64_t>(1984, (p.k + margin + 63) / 64 * 64);
-        const int64_t region0 = small_region0_words(p.k, p.cap_words, B2_all, nq);
-        const int64_t lds = 4 * (int64_t)wg_lds_words((int)cap, (int)region0, B2_all);
-        if (p.k + 64 <= cap && lds <= 64 * 1024) {
-            // wavefronts per row: sixteen for the smallest batches (more wavefronts per SIMD hide each other's
-            // latencies: 4 % less latency per call), four otherwise (a 256-row batch on sixteen leaves no room
-            // for a neighbouring stream's kernels: 20 % less throughput when steps overlap)
-            p.wg_nw = rows <= 128 ? 16 : 4;
-            const int64_t per_thread = (row_len + 64 * p.wg_nw - 1) / (64 * p.wg_nw);
-            p.wg_ept = per_thread <= 8 ? 8 : per_thread <= 16 ? 16 : per_thread <= 32 ? 32 : per_thread <= 64 ? 64 : 128;
-            p.wg_cap = (int)cap; p.wg_region0 = (int)region0; p.wg_lds_bytes = (int)lds;
+    {
+        const int64_t wg_max = dt == SLICER_F32 ? 16384 : 32768;
+        if (row_len % epc == 0 && row_len > 4096 && row_len <= wg_max && B2_all <= kWave && (row_len > max_n || rows <= 1024)) {
+            const int64_t margin = std::max<int64_t>(64, row_len / (dt == SLICER_F32 ? 16 : 32));
+            const int64_t cap = std::min<int64_t>(1984, (p.k + margin + 63) / 64 * 64);
+            const int64_t region0 = small_region0_words(p.k, p.cap_words, B2_all, nq);
+            const int64_t lds = 4 * (int64_t)wg_lds_words(dt, (int)cap, (int)region0, B2_all);
+            if (p.k + 64 <= cap && lds <= 64 * 1024) {
+                // wavefronts per row: sixteen for the smallest batches (more wavefronts per SIMD hide each other's
+                // latencies: 4 % less latency per call), four otherwise (a 256-row batch on sixteen leaves no room
+                // for a neighbouring stream's kernels: 20 % less throughput when steps overlap)
+                p.wg_nw = rows <= 128 ? 16 : 4;
+                const int64_t chunks = (row_len / epc + 64 * p.wg_nw - 1) / (64 * p.wg_nw);     // 16-byte chunks per thread
+                p.wg_ept = (int)(chunks <= 1 ? 1 : chunks <= 2 ? 2 : chunks <= 4 ? 4 : chunks <= 8 ? 8 : 16);    // (kept as a chunk count)
+                p.wg_cap = (int)cap; p.wg_region0 = (int)region0; p.wg_lds_bytes = (int)lds;
+            }
         }
     }
     return p;
 }
 
-template <int NW, int NQ>
+// p.wg_ept: 16-byte chunks per thread (1..16; at most 64 chunk totals for the one-wavefront scan: 4 with 16 wavefronts)
+template <int DT, int NW, int NQ>
 void launch_wg_nw(const SmallArgs& sa, const Plan& p, hipStream_t st)
 {
+    constexpr int EPC = DT == 0 ? 4 : 8;
     const dim3 g((unsigned)sa.R), b(NW * kWave);
     const size_t lds = (size_t)p.wg_lds_bytes;
-    // elements per thread: 16-byte chunks, and at most 64 chunk totals for the one-wavefront scan
     if constexpr (NW == 16) {
-        if (p.wg_ept == 8) hipLaunchKernelGGL((enc_wg_kernel<16, 8, NQ>), g, b, lds, st, sa);
-        else if (p.wg_ept == 16) hipLaunchKernelGGL((enc_wg_kernel<16, 16, NQ>), g, b, lds, st, sa);
-        else hipLaunchKernelGGL((enc_wg_kernel<16, 32, NQ>), g, b, lds, st, sa);
+        if (p.wg_ept <= 1) hipLaunchKernelGGL((enc_wg_kernel<DT, 16, 1 * EPC, NQ>), g, b, lds, st, sa);
+        else if (p.wg_ept == 2) hipLaunchKernelGGL((enc_wg_kernel<DT, 16, 2 * EPC, NQ>), g, b, lds, st, sa);
+        else hipLaunchKernelGGL((enc_wg_kernel<DT, 16, 4 * EPC, NQ>), g, b, lds, st, sa);
     } else {
-        if (p.wg_ept <= 32) hipLaunchKernelGGL((enc_wg_kernel<4, 32, NQ>), g, b, lds, st, sa);
-        else if (p.wg_ept == 64) hipLaunchKernelGGL((enc_wg_kernel<4, 64, NQ>), g, b, lds, st, sa);
-        else hipLaunchKernelGGL((enc_wg_kernel<4, 128, NQ>), g, b, lds, st, sa);
+        if (p.wg_ept <= 4) hipLaunchKernelGGL((enc_wg_kernel<DT, 4, 4 * EPC, NQ>), g, b, lds, st, sa);
+        else if (p.wg_ept == 8) hipLaunchKernelGGL((enc_wg_kernel<DT, 4, 8 * EPC, NQ>), g, b, lds, st, sa);
+        else hipLaunchKernelGGL((enc_wg_kernel<DT, 4, 16 * EPC, NQ>), g, b, lds, st, sa);
     }
 }
 
+template <int DT>
 int launch_wg(const SmallArgs& sa, const Plan& p, hipStream_t st)
 {
     if (p.wg_nw == 16) {
-        if (sa.nq == 7) launch_wg_nw<16, 7>(sa, p, st); else launch_wg_nw<16, 0>(sa, p, st);
+        if (sa.nq == 7) launch_wg_nw<DT, 16, 7>(sa, p, st); else launch_wg_nw<DT, 16, 0>(sa, p, st);
     } else {
-        if (sa.nq == 7) launch_wg_nw<4, 7>(sa, p, st); else launch_wg_nw<4, 0>(sa, p, st);
+        if (sa.nq == 7) launch_wg_nw<DT, 4, 7>(sa, p, st); else launch_wg_nw<DT, 4, 0>(sa, p, st);
     }
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? SLICER_OK : hip_fail(e);
@@ -420,7 +425,7 @@ static int encode_impl(const void* x, slicer_dtype dt, int64_t rows, int64_t row
         sa.hint = (u32*)(ws + p.off_hint);
         const bool timed = g_ev_start && g_ev_stop;
         if (timed) SLICER_HIP(hipEventRecord(g_ev_start, st));
-        rc = launch_wg(sa, p, st);
+        rc = dt == SLICER_F32 ? launch_wg<0>(sa, p, st) : launch_wg<1>(sa, p, st);
         if (rc) return rc;
         if (timed) SLICER_HIP(hipEventRecord(g_ev_stop, st));
         ea.only_flagged = sa.fallback;

@@ -1,4 +1,4 @@
-// Row-resident encoder for rows of 4 K to 32 K bf16 elements and small batches: ONE WORKGROUP
+// Row-resident encoder for rows of 4 K to 32 K bf16 (16 K fp32) elements and small batches: ONE WORKGROUP
 // (4, 8 or 16 wavefronts) PER ROW.  A single wavefront needs about 30 us for an 8192-element row,
 // nearly all of it dependent-instruction and LDS latency, and a batch of a few hundred rows
 // (one auto-regressive decode step of Sec. 2.1, one hidden state per client) leaves three
@@ -18,7 +18,9 @@
 // ...), scans run over the workgroup, the two short serial steps (cut, boundaries) run on
 // wavefront 0, and workgroup barriers separate the stages.
 //
-// bf16 rows, budget guard or fixed ladder; rows it cannot hold are flagged for the generic kernel.
+// Budget guard or fixed ladder; rows it cannot hold are flagged for the generic kernel.  bf16 entries
+// are one word (sign, key, inverted index); fp32 entries keep the raw word in the list and the index
+// beside it, and the members of a fine bin compare on "in-bin key bits, inverted index, class".
 #pragma once
 
 #include "slicer_encode_small.hpp"
@@ -29,26 +31,29 @@ constexpr int kWgMaxSlots = 32;        // list slots (64 entries): lists of up t
 constexpr int kWgMisc = 64;            // broadcast words (0..15), per-wavefront maxima (16..31), scan scratch (32..)
 
 // words of LDS: the one-wavefront layout (list in LDS) followed by the workgroup's own tables
-__host__ __device__ inline int wg_main_words(int cap, int region0, int B2)
+__host__ __device__ inline int wg_main_words(int dt, int cap, int region0, int B2)
 {
-    return small_lds_words(1, cap, region0, B2, 0);
+    return small_lds_words(dt, cap, region0, B2, 0);
 }
-__host__ __device__ inline int wg_lds_words(int cap, int region0, int B2)
+__host__ __device__ inline int wg_lds_words(int dt, int cap, int region0, int B2)
 {
     // misc, chunk totals and their prefix (2 x 64), per-slot per-block counts as 16-bit (cap / 64 slots)
-    return wg_main_words(cap, region0, B2) + kWgMisc + 128 + ((cap / kWave) * B2 + 1) / 2 + 2;
+    return wg_main_words(dt, cap, region0, B2) + kWgMisc + 128 + ((cap / kWave) * B2 + 1) / 2 + 2;
 }
 
-template <int NW, int EPT, int NQ>
+template <int DT, int NW, int EPT, int NQ>
 __global__ __launch_bounds__(NW * kWave) void enc_wg_kernel(SmallArgs a)
 {
+    typedef Elem<DT> E;
     constexpr int kWgThreads = NW * kWave, kWgWaves = NW;
     constexpr int kWgSlots = (kWgMaxSlots + NW - 1) / NW;     // list slots per wavefront
-    typedef u32 comp_t;
-    constexpr comp_t kClsBit = 0x80000000u;          // set for the positive class
+    typedef typename std::conditional<DT == 0, u64, u32>::type comp_t;   // bf16: key + index fit 31 bits
+    constexpr comp_t kClsBit = (comp_t)1 << (8 * sizeof(comp_t) - 1);       // set for the positive class
+    constexpr int kHiShift = DT == 0 ? 32 : 0;       // position of the key word in a comp
+    constexpr u32 kKeyMask = DT == 0 ? 0x7FFFFFFFu : 0x7FFFu;
     constexpr int kRegThr = 14;
     constexpr int QN = NQ ? NQ : kMaxQ;
-    constexpr int EPC = 8, NCH = EPT / EPC;          // 16-byte chunks per thread
+    constexpr int EPC = DT == 0 ? 4 : 8, NCH = EPT / EPC;   // elements per 16-byte chunk, chunks per thread
     static_assert(NCH * kWgWaves <= kWave, "chunk totals are scanned by one wavefront");
     extern __shared__ u32 smem[];
 
@@ -57,8 +62,8 @@ __global__ __launch_bounds__(NW * kWave) void enc_wg_kernel(SmallArgs a)
     if (r >= a.R) return;
     const int N = (int)a.N, M = a.M, Mn = a.Mn, w = a.w, B2 = a.M + a.Mn, nq = NQ ? NQ : a.nq, cap = a.cap;
     const int k = (int)a.k;
-    SmallLds L = small_carve(smem, 1, cap, a.region0_words, B2, 0);
-    u32* misc = smem + wg_main_words(cap, a.region0_words, B2);      // broadcast words and scan scratch
+    SmallLds L = small_carve(smem, DT, cap, a.region0_words, B2, 0);
+    u32* misc = smem + wg_main_words(DT, cap, a.region0_words, B2);      // broadcast words and scan scratch
     u32* ctab = misc + kWgMisc;                                           // [NCH][4] chunk totals per wavefront, then their prefixes
     uint16_t* stab = (uint16_t*)(ctab + 128);                        // [slot][B2] entries of block b in slot s
     auto give_up = [&]() { if (tid == 0) a.fallback[r] = 1u; };      // callers return right after, all threads alike
@@ -69,7 +74,7 @@ __global__ __launch_bounds__(NW * kWave) void enc_wg_kernel(SmallArgs a)
     const u32 lent_off = (u32)(L.Lent - smem) * 4u;
 
     // ---- 1. load the row ---------------------------------------------------------------------
-    const uint4* __restrict__ xr = (const uint4*)((const char*)a.x + (size_t)r * (size_t)N * 2);
+    const uint4* __restrict__ xr = (const uint4*)((const char*)a.x + (size_t)r * (size_t)N * (DT == 0 ? 4 : 2));
     uint4 v[NCH];
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
@@ -89,7 +94,10 @@ __global__ __launch_bounds__(NW * kWave) void enc_wg_kernel(SmallArgs a)
         for (int c = 0; c < NCH; ++c) {
             u32 n1 = 0;
 #pragma unroll
-            for (int d = 0; d < 4; ++d) n1 += (u32)__popc(((word_of(c, d) & 0x7FFF7FFFu) + C16) & 0x80008000u);
+            for (int d = 0; d < 4; ++d) {
+                if (DT == 0) n1 += (word_of(c, d) & 0x7FFFFFFFu) >= t_lo ? 1u : 0u;
+                else n1 += (u32)__popc(((word_of(c, d) & 0x7FFF7FFFu) + C16) & 0x80008000u);
+            }
             cntc[c] = n1;
         }
 #pragma unroll
@@ -127,8 +135,9 @@ __global__ __launch_bounds__(NW * kWave) void enc_wg_kernel(SmallArgs a)
     const u32 hslot = (u32)blockIdx.x & (u32)(kHintSlots - 1);
     bool hinted = false;
     if (k > 0) {
-        const u32 hint_key = a.hint[hslot] & 0x7FFFu;
-        t_lo = hint_key > kHintDelta ? hint_key - kHintDelta : 1u;
+        const u32 hint_key = a.hint[hslot] & kKeyMask;
+        const u32 dlt = kHintDelta << (DT == 0 ? 16 : 0);
+        t_lo = hint_key > dlt ? hint_key - dlt : 1u;
         count_pass();
         hinted = nL >= (u32)k && nL <= (u32)k + 2u * kHintSlack && (int)nL <= cap;
     }
@@ -141,9 +150,12 @@ __global__ __launch_bounds__(NW * kWave) void enc_wg_kernel(SmallArgs a)
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
 #pragma unroll
-            for (int d = 0; d < 4; ++d) mx = pk_max_u16(mx, word_of(c, d) & 0x7FFF7FFFu);
+            for (int d = 0; d < 4; ++d) {
+                if (DT == 0) mx = max(mx, word_of(c, d) & 0x7FFFFFFFu);
+                else mx = pk_max_u16(mx, word_of(c, d) & 0x7FFF7FFFu);
+            }
         }
-        mx = max(mx & 0xFFFFu, mx >> 16);
+        if (DT == 1) mx = max(mx & 0xFFFFu, mx >> 16);
         mx = wave_max_dpp(mx);
         if (lane == 0) misc[16 + wv] = mx;
         __syncthreads();
@@ -154,13 +166,15 @@ __global__ __launch_bounds__(NW * kWave) void enc_wg_kernel(SmallArgs a)
     }
 
     // ---- coarse histogram: 2048 bins hanging from wtop, bin = (wtop - key) >> S ---------------
+    constexpr int S1 = DT == 0 ? 16 : 0;             // fp32: 65536 keys per bin (the same 128 bins per octave as bf16)
     u32 wtop = kmax, above = 0;
-    int S = 0;
+    int S = S1;
     u32 B1 = 0, c_gt = 0, cnt1 = 0;
     bool found = false;
     const u32 rank_t = k > 0 ? (u32)(k - 1) : 0u;
     auto hist_pass = [&](auto shift) {
         constexpr int SH = decltype(shift)::value;
+        constexpr int SHB = SH >= 2 ? SH - 2 : 0;      // fp32: shift that leaves the bin number times 4
         {
             uint4* h4 = (uint4*)smem;
             for (int i = (int)tid; i < kCoarseBins / 4; i += kWgThreads) h4[i] = make_uint4(0, 0, 0, 0);
@@ -173,12 +187,18 @@ __global__ __launch_bounds__(NW * kWave) void enc_wg_kernel(SmallArgs a)
             if ((c * kWgThreads + (int)tid) * EPC < N) {
 #pragma unroll
                 for (int d = 0; d < 4; ++d) {
-                    const u32 kp = word_of(c, d) & 0x7FFF7FFFu;
-                    u32 b = pk_sub_sat_u16(wt2, kp);
-                    if (SH) b = pk_shr_u16(b, SH);
-                    b = pk_shl_u16(pk_min_u16(b, (u32)(kCoarseBins - 1) * 0x10001u), 2);
-                    lds_inc(b & 0xFFFFu, 1u);
-                    lds_inc(b >> 16, 1u);
+                    if (DT == 0) {
+                        const u32 key = word_of(c, d) & 0x7FFFFFFFu;
+                        const u32 df = wtop > key ? wtop - key : 0u;
+                        lds_inc(min((df >> SHB) & ~3u, (u32)(4 * kCoarseBins - 4)), 1u);
+                    } else {
+                        const u32 kp = word_of(c, d) & 0x7FFF7FFFu;
+                        u32 b = pk_sub_sat_u16(wt2, kp);
+                        if (SH) b = pk_shr_u16(b, SH);
+                        b = pk_shl_u16(pk_min_u16(b, (u32)(kCoarseBins - 1) * 0x10001u), 2);
+                        lds_inc(b & 0xFFFFu, 1u);
+                        lds_inc(b >> 16, 1u);
+                    }
                 }
             }
         }
@@ -209,12 +229,12 @@ __global__ __launch_bounds__(NW * kWave) void enc_wg_kernel(SmallArgs a)
         if (found) { B1 = misc[0]; c_gt = misc[1]; cnt1 = misc[2]; }
         __syncthreads();
     };
-    hist_pass(std::integral_constant<int, 0>());
-    if (found && B1 == (u32)(kCoarseBins - 1) && wtop > (u32)(kCoarseBins - 1)) {
+    hist_pass(std::integral_constant<int, S1>());
+    if (found && B1 == (u32)(kCoarseBins - 1) && (wtop >> S1) > (u32)(kCoarseBins - 1)) {
         above = c_gt;
-        wtop -= (u32)(kCoarseBins - 1);
-        S = 4;
-        hist_pass(std::integral_constant<int, 4>());
+        wtop -= (u32)(kCoarseBins - 1) << S1;
+        S = S1 + 4;
+        hist_pass(std::integral_constant<int, S1 + 4>());
     }
     c_gt += above;
     const long long lowk = (long long)wtop - ((long long)(B1 + 1u) << S) + 1;
@@ -235,14 +255,25 @@ __global__ __launch_bounds__(NW * kWave) void enc_wg_kernel(SmallArgs a)
             give_up();
             return;
         }
+        const u32 lidx_off = (u32)((u32*)L.Lidx - smem) * 4u;
         u32 linv = 0xFFFFu - tid * (u32)EPC;
         asm volatile("" : "+v"(linv));
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
             u32 wa = lent_off + basec[c] * 4u;
+            const u32 idx0 = (u32)((c * kWgThreads + (int)tid) * EPC);
 #pragma unroll
             for (int d = 0; d < 4; ++d) {
                 const u32 wd = word_of(c, d);
+                if (DT == 0) {
+                    const u32 fl = (wd & 0x7FFFFFFFu) >= t_lo ? 1u : 0u;
+                    if (fl) {
+                        *lds_at(wa) = wd;
+                        *(__attribute__((address_space(3))) uint16_t*)(uintptr_t)(lidx_off + ((wa - lent_off) >> 1)) = (uint16_t)(idx0 + d);
+                    }
+                    wa += fl << 2;
+                    continue;
+                }
                 const u32 f = (wd & 0x7FFF7FFFu) + C16;
                 u32 f0 = (f >> 15) & 1u, f1 = f >> 31;
                 asm volatile("" : "+v"(f0));
@@ -260,17 +291,20 @@ __global__ __launch_bounds__(NW * kWave) void enc_wg_kernel(SmallArgs a)
     __syncthreads();
     // wavefront v takes list slots v, v + 4, ...: entries into registers (sign, key, inverted index in one word)
     const int nslots = (int)((nL + kWave - 1) / kWave);
-    u32 ent[kWgSlots];
+    u32 ent[kWgSlots], eix[DT == 0 ? kWgSlots : 1];           // fp32: the entry's index beside its raw word
 #pragma unroll
     for (int j = 0; j < kWgSlots; ++j) {
         const u32 p = (u32)(j * kWgWaves + (int)wv) * kWave + lane;
         ent[j] = p < nL ? L.Lent[p] : 0u;
+        if (DT == 0) eix[DT == 0 ? j : 0] = p < nL ? (u32)L.Lidx[p] : 0u;
     }
+    auto ent_key = [&](int j) -> u32 { return DT == 0 ? ent[j] & 0x7FFFFFFFu : (ent[j] >> 16) & 0x7FFFu; };
+    auto ent_idx = [&](int j) -> u32 { return DT == 0 ? eix[DT == 0 ? j : 0] : 0xFFFFu - (ent[j] & 0xFFFFu); };
     if (hinted) {                                                 // the row's largest key is the list's largest
         u32 mx = 0;
 #pragma unroll
         for (int j = 0; j < kWgSlots; ++j) mx = max(mx, ent[j] & 0x7FFFFFFFu);
-        mx = wave_max_dpp(mx) >> 16;
+        mx = wave_max_dpp(mx) >> (DT == 0 ? 0 : 16);
         if (lane == 0) misc[16 + wv] = mx;
     }
     __syncthreads();                                              // (the histogram region overlays the list's neighbours)
@@ -291,13 +325,15 @@ __global__ __launch_bounds__(NW * kWave) void enc_wg_kernel(SmallArgs a)
     // ---- 3. fine bins: 1024 bins linear in (key - t_lo) >> sh, both classes packed 11 + 11 bits --------
     const u32 range = kmax > t_lo ? kmax - t_lo : 0u;
     const int sh = range < (u32)kFineBins ? 0 : (32 - __clz((int)range)) - 10;
+    if (DT == 0 && sh + w + 1 > 32) {                             // in-bin key bits, index and class must share a word
+        give_up();
+        return;
+    }
+    const u32 inmask = (1u << sh) - 1u, idxmask = (1u << w) - 1u;
 #pragma unroll
     for (int j = 0; j < kWgSlots; ++j) {
         const u32 p = (u32)(j * kWgWaves + (int)wv) * kWave + lane;
-        if (p < nL) {
-            const u32 e = ent[j];
-            lds_inc(((((e >> 16) & 0x7FFFu) - t_lo) >> sh) << 2, (e >> 31) ? 0x800u : 1u);
-        }
+        if (p < nL) lds_inc(((ent_key(j) - t_lo) >> sh) << 2, (ent[j] >> 31) ? 0x800u : 1u);
     }
     __syncthreads();
     u32 n_pos, n_neg;
@@ -334,14 +370,25 @@ __global__ __launch_bounds__(NW * kWave) void enc_wg_kernel(SmallArgs a)
         const u32 p = (u32)(j * kWgWaves + (int)wv) * kWave + lane;
         if (p < nL) {
             const u32 e = ent[j];
-            const u32 rel = ((e >> 16) & 0x7FFFu) - t_lo;
+            const u32 rel = ent_key(j) - t_lo;
             const u32 old = atomicAdd(&L.hist[rel >> sh], 1u << 22);
-            L.S[(old & 0x7FFu) + ((old >> 11) & 0x7FFu) + (old >> 22)] = e;
+            const u32 at = (old & 0x7FFu) + ((old >> 11) & 0x7FFu) + (old >> 22);
+            if (DT == 0) L.S[at] = ((((rel & inmask) << w) | (idxmask - ent_idx(j))) << 1) | (e >> 31);
+            else L.S[at] = e;
         }
     }
     __syncthreads();
-    auto s_plain = [&](u32 s) -> u32 { return s & 0x7FFFFFFFu; };
-    auto s_neg = [&](u32 s) -> u32 { return s >> 31; };
+    // members of a fine bin compare on the plain comp; their class; their class-extended comp
+    auto s_plain = [&](u32 s) -> u32 { return DT == 0 ? s >> 1 : s & 0x7FFFFFFFu; };
+    auto s_neg = [&](u32 s) -> u32 { return DT == 0 ? s & 1u : s >> 31; };
+    auto s_cx = [&](u32 s, u32 bin) -> comp_t {
+        if (DT == 0) {
+            const u32 key = ((bin << sh) | ((s >> 1) >> w)) + t_lo;
+            const u32 idx = idxmask - ((s >> 1) & idxmask);
+            return ((comp_t)(key | ((s & 1u) ? 0u : 0x80000000u)) << kHiShift) | (comp_t)(u32)(~idx);
+        }
+        return (comp_t)(s ^ 0x80000000u);
+    };
 
     // ---- top-K cut and block boundaries: wavefront 0 ------------------------------------------------
     const int ntg = B2 - 2;
@@ -369,16 +416,20 @@ __global__ __launch_bounds__(NW * kWave) void enc_wg_kernel(SmallArgs a)
                 kp += (u32)__popcll(__ballot(in && !s_neg(me)));
                 kn += (u32)__popcll(__ballot(in && s_neg(me)));
                 const u64 hit = __ballot(i < cnt && gt == rem);
-                if (hit) thrK = (comp_t)bcast(s_plain(me), (int)__builtin_ctzll(hit));
+                if (hit) {
+                    const int hl = (int)__builtin_ctzll(hit);
+                    const comp_t cx = s_cx(me, (u32)lo) & ~kClsBit;
+                    if (DT == 0) thrK = ((comp_t)bcast((u32)((u64)cx >> kHiShift), hl) << kHiShift) | (comp_t)bcast((u32)cx, hl);
+                    else thrK = (comp_t)bcast((u32)cx, hl);
+                }
             }
             n_pos = pe + kp; n_neg = ne + kn;
         }
         const u32 Kc[2] = { n_pos / (u32)M, n_neg / (u32)Mn };
-        if (lane == 0) { misc[6] = thrK; misc[7] = n_pos; misc[8] = n_neg; }
+        if (lane == 0) { misc[6] = (u32)thrK; misc[11] = (u32)((u64)thrK >> kHiShift); misc[7] = n_pos; misc[8] = n_neg; }
         // boundaries: comps of class ranks j*K-1, one lane per boundary
         const int ntp = ntg > 0 ? ntg : 1;
         u32* tg_bin = L.tg; u32* tg_base = L.tg + ntp; u32* tg_cnt = L.tg + 2 * ntp; u32* tg_rem = L.tg + 3 * ntp; u32* tg_pre = L.tg + 4 * ntp;
-        (void)tg_bin;
         const bool mine = (int)lane < ntg;
         const int cls = (int)lane >= M - 1 ? 1 : 0;
         const int jb = (cls ? (int)lane - (M - 1) : (int)lane) + 1;
@@ -396,7 +447,7 @@ __global__ __launch_bounds__(NW * kWave) void enc_wg_kernel(SmallArgs a)
         const u32 cnt = act ? wd >> 22 : 0u;
         const u32 incl = wave_scan_dpp(cnt);
         if (mine) {
-            tg_base[lane] = pe + ne; tg_cnt[lane] = cnt;
+            tg_bin[lane] = (u32)lo; tg_base[lane] = pe + ne; tg_cnt[lane] = cnt;
             tg_rem[lane] = Rk - (cls ? ne : pe);
             tg_pre[lane] = incl - cnt;
             if (!act) thr[lane] = cls ? (comp_t)(kClsBit - 1) : ~(comp_t)0;
@@ -416,17 +467,23 @@ __global__ __launch_bounds__(NW * kWave) void enc_wg_kernel(SmallArgs a)
                 const u32 bs = tg_base[t], cn = tg_cnt[t];
                 const u32 me = L.S[bs + (pr - tg_pre[t])];
                 if (s_neg(me) == tc) {
-                    const u32 fm = tc ? 0u : 0x80000000u;     // same class and larger comp = plain unsigned "larger"
-                    const u32 mk = me ^ fm;
+                    // one compare per member: with the class bit moved to the top and set for the boundary's
+                    // class, "same class and larger comp" is a plain unsigned "larger"
+                    const u32 fm = DT == 0 ? (tc ^ 1u) : (tc ? 0u : 0x80000000u);
+                    auto key_of = [&](u32 sv) -> u32 {
+                        const u32 xv = sv ^ fm;
+                        return DT == 0 ? __builtin_amdgcn_alignbit(xv, xv, 1) : xv;     // fp32: rotate the class bit up
+                    };
+                    const u32 mk = key_of(me);
                     u32 gt = 0;
-                    for (u32 jj = 0; jj < cn; ++jj) gt += (L.S[bs + jj] ^ fm) > mk ? 1u : 0u;
-                    if (gt == tg_rem[t]) thr[t] = (comp_t)(me ^ 0x80000000u);
+                    for (u32 jj = 0; jj < cn; ++jj) gt += key_of(L.S[bs + jj]) > mk ? 1u : 0u;
+                    if (gt == tg_rem[t]) thr[t] = s_cx(me, tg_bin[t]);
                 }
             }
         }
     }
     __syncthreads();
-    const comp_t thrK = (comp_t)misc[6];
+    const comp_t thrK = DT == 0 ? (comp_t)(((u64)misc[11] << kHiShift) | (u64)misc[6]) : (comp_t)misc[6];
     n_pos = misc[7]; n_neg = misc[8];
     const u32 n = n_pos + n_neg;
     const u32 Kc[2] = { n_pos / (u32)M, n_neg / (u32)Mn };
@@ -446,7 +503,7 @@ __global__ __launch_bounds__(NW * kWave) void enc_wg_kernel(SmallArgs a)
     comp_t tx[kRegThr];
 #pragma unroll
     for (int j = 0; j < kRegThr; ++j) tx[j] = j < ntg ? thr[j] : (comp_t)0;
-    const bool tree8 = M == 8 && Mn == 8;
+    const bool tree8 = DT == 1 && M == 8 && Mn == 8;      // (one-word comps: a select is one instruction)
     __syncthreads();                                 // S, the fine bins and the boundaries have been read: their storage is reused
     u32 info[kWgSlots];                              // kept << 31 | block << 16 | entries of the same block before this one in the slot
 #pragma unroll
@@ -456,7 +513,8 @@ __global__ __launch_bounds__(NW * kWave) void enc_wg_kernel(SmallArgs a)
         bool kept = false;
         u32 b = 0;
         if (slot < nslots && p < nL) {
-            const comp_t cx = (comp_t)(ent[j] ^ 0x80000000u);
+            const comp_t cx = DT == 0 ? ((comp_t)(ent[j] ^ 0x80000000u) << kHiShift) | (comp_t)(u32)(~ent_idx(j))
+                                      : (comp_t)(ent[j] ^ 0x80000000u);
             if ((cx & ~kClsBit) >= thrK) {
                 kept = true;
                 u32 abv;
@@ -478,7 +536,7 @@ __global__ __launch_bounds__(NW * kWave) void enc_wg_kernel(SmallArgs a)
                     for (int t = kRegThr; t < ntg; ++t) abv += thr[t] > cx ? 1u : 0u;
                 }
                 b = abv;
-                const u32 key = ((u32)cx >> 16) & 0x7FFFu;
+                const u32 key = ent_key(j);
                 atomicMin(&L.vminb[b], key);
                 atomicMax(&L.vmaxb[b], key);
             }
@@ -515,9 +573,8 @@ __global__ __launch_bounds__(NW * kWave) void enc_wg_kernel(SmallArgs a)
         if (info[j] >> 31) {
             const u32 b = (info[j] >> 16) & 0x7FFFu, before = info[j] & 0xFFFFu;
             const u32 pos = L.blk_start[b] + (u32)stab[slot * B2 + (int)b] + before;
-            const u32 e = ent[j];
-            bo_val[pos] = ((e >> 16) & 0x7FFFu) << 16;           // |x| as fp32 bits (exact widening)
-            bo_idx[pos] = (uint16_t)(0xFFFFu - (e & 0xFFFFu));
+            bo_val[pos] = E::value_bits(ent_key(j));             // |x| as fp32 bits (bf16: exact widening)
+            bo_idx[pos] = (uint16_t)ent_idx(j);
         }
     }
     __syncthreads();
@@ -541,8 +598,8 @@ __global__ __launch_bounds__(NW * kWave) void enc_wg_kernel(SmallArgs a)
         r0 = bs0 + sub * perb; r0 = r0 < be ? r0 : be;
         r1 = r0 + perb < be ? r0 + perb : be;
         if (mycnt) {
-            vmaxbits = L.vmaxb[myb] << 16;
-            vmin = __uint_as_float(L.vminb[myb] << 16);
+            vmaxbits = E::value_bits(L.vmaxb[myb]);
+            vmin = __uint_as_float(E::value_bits(L.vminb[myb]));
             rng = __uint_as_float(vmaxbits) - vmin;
             dg = !(rng > 0.f);                       // only a range of exactly 0 is degenerate
             if (!dg) { er = range_exp(rng); rng1 = unit_range(rng, er); }
@@ -698,7 +755,8 @@ __global__ __launch_bounds__(NW * kWave) void enc_wg_kernel(SmallArgs a)
         a.mv.n_pos[r] = n_pos;
         a.mv.n_neg[r] = n_neg;
         a.fallback[r] = 0u;
-        if (k > 0) a.hint[hslot] = nL > (u32)k ? ((u32)thrK >> 16) & 0x7FFFu : t_lo;     // this row's cut key, for a later row
+        if (k > 0) a.hint[hslot] = nL > (u32)k ? (DT == 0 ? (u32)((u64)thrK >> kHiShift) & 0x7FFFFFFFu : ((u32)thrK >> 16) & 0x7FFFu)
+                                               : t_lo;           // this row's cut key, for a later row
     }
 }
 

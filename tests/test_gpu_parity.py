@@ -129,10 +129,12 @@ def _mixed_rows(rng, rows, N, dtype):
     return synth.f32_to_bf16_bits(x) if dtype == "bf16" else x
 
 
-@pytest.mark.parametrize("dtype,N", [("bf16", 256), ("bf16", 4096), ("bf16", 8192), ("f32", 768), ("f32", 2048), ("f32", 4096)])
+@pytest.mark.parametrize("dtype,N", [("bf16", 256), ("bf16", 4096), ("bf16", 8192), ("f32", 768), ("f32", 2048), ("f32", 4096),
+                                     ("f32", 8192), ("f32", 12288), ("bf16", 20480)])
 def test_row_resident_variants(oracle, dtype, N):
-    """Every variant of the one-wave-per-row encoder (list in registers or LDS, short or long
-    bitwidth ladders, up to 64 blocks) and both bit-field sources of the short-row decoder."""
+    """Every variant of the one-wave-per-row and of the workgroup-per-row encoder (list in registers or
+    LDS, short or long bitwidth ladders, up to 64 blocks, bf16 and fp32, 4 and 16 wavefronts per row) and
+    both bit-field sources of the short-row decoder."""
     rng = np.random.default_rng(N)
     x = _mixed_rows(rng, 24, N, dtype)
     for keep, M, bits, budget in ((0.02, 1, B28, 1e-3), (0.1, 8, B28, 1e-3), (0.15, 32, B28, 5e-4),
@@ -141,7 +143,7 @@ def test_row_resident_variants(oracle, dtype, N):
         check(oracle, x, dtype, keep, M, bits, budget)
 
 
-@pytest.mark.parametrize("dtype,N", [("bf16", 4096), ("f32", 768), ("f32", 4096), ("bf16", 8192)])
+@pytest.mark.parametrize("dtype,N", [("bf16", 4096), ("f32", 768), ("f32", 4096), ("bf16", 8192), ("f32", 8192)])
 def test_wide_dynamic_range_rows(oracle, dtype, N):
     """Magnitudes spread evenly over many octaves: the row kernel's histogram window covers 16
     octaves below the row's largest value, so these rows put rank k-1 inside the window, on its
