@@ -406,7 +406,7 @@ static int encode_impl(const void* x, slicer_dtype dt, int64_t rows, int64_t row
 
     // asymmetric thresholds need a second selection over a subset of the row: the generic kernel has it for
     // every shape, the row-resident kernel for bf16 rows (rows it flags are redone generically, same rule)
-    const bool use_wg = p.wg_ept && !asym && guard == 0 && ((uintptr_t)x & 15) == 0;
+    const bool use_wg = p.wg_ept && !asym && ((uintptr_t)x & 15) == 0;
     if (use_wg) {
         // one workgroup per row; rows it cannot hold are flagged and redone by the generic kernel
         SmallArgs sa;

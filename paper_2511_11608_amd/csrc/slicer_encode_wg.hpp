@@ -18,7 +18,7 @@
 // ...), scans run over the workgroup, the two short serial steps (cut, boundaries) run on
 // wavefront 0, and workgroup barriers separate the stages.
 //
-// Budget guard or fixed ladder; rows it cannot hold are flagged for the generic kernel.  bf16 entries
+// Either guard or a fixed ladder, lambda = 0; rows it cannot hold are flagged for the generic kernel.  bf16 entries
 // are one word (sign, key, inverted index); fp32 entries keep the raw word in the list and the index
 // beside it, and the members of a fine bin compare on "in-bin key bits, inverted index, class".
 #pragma once
@@ -616,7 +616,8 @@ __global__ __launch_bounds__(NW * kWave) void enc_wg_kernel(SmallArgs a)
         }
         if (sub == 0) {
             for (int t = 0; t <= nq; ++t) sums[myb * (nq + 1) + t] = 0;
-            L.run[myb] = (mycnt && !dg) ? (u32)nq : 0u;      // index of the chosen bitwidth, nq = none feasible yet
+            // budget guard: index of the chosen bitwidth, nq = none feasible yet; DS guard: mask of violations
+            L.run[myb] = (mycnt && !dg && a.guard == 0) ? (u32)nq : 0u;
         }
     }
     __syncthreads();
@@ -627,7 +628,43 @@ __global__ __launch_bounds__(NW * kWave) void enc_wg_kernel(SmallArgs a)
         inv[t] = (on && (NQ || t < nq)) ? invt[myb * (u32)nq + t] : 0.f;
         if ((NQ || t < nq) && a.qlist[t] > 8) small_q = false;
     }
-    if (!a.lad.on) {
+    if (!a.lad.on && a.guard == 1) {
+        // Eq. "DS": sum over the block of | (code at q_bit >> (q_bit - q)) - code at q | for every lower bitwidth
+        const int top = nq - 1, qtop = (int)L.qtab[top];
+        const float inv_top = on ? invt[myb * (u32)nq + (u32)top] : 0.f;
+        for (u32 i0 = 0; i0 < T; i0 += 8) {             // 8 differences below 2^16 each
+            u32 acc[QN];
+#pragma unroll
+            for (int t = 0; t < QN; ++t) acc[t] = 0;
+            const u32 i1 = i0 + 8 < T ? i0 + 8 : T;
+            for (u32 i = i0; i < i1; ++i) {
+                const u32 p = r0 + i;
+                if (p < r1) {
+                    const float d = to_unit(__uint_as_float(bo_val[p]) - vmin, er);
+                    const u32 c0 = (u32)rintf(d * inv_top);           // within [0, 2^q - 1]: no clamp needed
+#pragma unroll
+                    for (int t = 0; t < QN; ++t) {
+                        if ((NQ || t < nq) && t < top) {
+                            const u32 c = (u32)rintf(d * inv[t]);
+                            const u32 ref = c0 >> (u32)(qtop - a.qlist[t]);
+                            acc[t] += ref > c ? ref - c : c - ref;
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < QN; ++t) {
+                if ((NQ || t < nq) && t < top) {
+                    if (wave_one_block) {                            // 64 lane sums below 2^19 fit 32 bits
+                        const u32 tot = bcast(wave_scan_dpp(acc[t]), kWave - 1);
+                        if (lane == 0 && tot) atomicAdd(&sums[myb * (nq + 1) + t], (u64)tot);
+                    } else if (acc[t]) {
+                        atomicAdd(&sums[myb * (nq + 1) + t], (u64)acc[t]);
+                    }
+                }
+            }
+        }
+    } else if (!a.lad.on) {
         // residual on the 2^-15 grid: rint(y * 2^15) reduced to 15 signed bits; bitwidths up to 8 keep
         // y * 2^15 below 2^23, where adding 2^23 rounds to the integer grid with the same round-half-even
         float inv15[QN];
@@ -686,6 +723,17 @@ __global__ __launch_bounds__(NW * kWave) void enc_wg_kernel(SmallArgs a)
     __syncthreads();
     if (a.lad.on) {
         if (on && sub == 0) L.run[myb] = ladder_index(a.lad, (int)(myb >= (u32)M ? myb - (u32)M : myb));
+    } else if (a.guard == 1) {
+        // greedy descent: the chosen index is one above the highest violating candidate below q_bit
+        if (on && mycnt && !dg) {
+            for (u32 t = sub; t + 1 < (u32)nq; t += lpb)
+                if (!((double)sums[myb * (nq + 1) + t] <= a.beta * (double)mycnt)) atomicOr(&L.run[myb], 1u << t);
+        }
+        __syncthreads();
+        if (on && sub == 0) {
+            const u32 viol = L.run[myb];
+            L.run[myb] = viol ? 32u - (u32)__clz((int)viol) : 0u;
+        }
     } else if (on && mycnt && !dg) {
         const double rhs = a.beta * ldexp((double)sums[myb * (nq + 1) + nq], 2 * e - 40);
         for (u32 t = sub; t < (u32)nq; t += lpb) {

@@ -218,7 +218,8 @@ def test_ds_guard_workloads(oracle, name):
         check_ds(oracle, wl.x, wl.dtype, wl.keep_ratio, wl.n_blocks, wl.bit_set, delta)
 
 
-@pytest.mark.parametrize("dtype,N", [("bf16", 4096), ("f32", 768), ("bf16", 1000), ("f32", 40000)])
+@pytest.mark.parametrize("dtype,N", [("bf16", 4096), ("f32", 768), ("bf16", 1000), ("f32", 40000),
+                                     ("bf16", 8192), ("f32", 8192), ("bf16", 20480)])    # the last three: one workgroup per row
 def test_ds_guard_mixed_rows(oracle, dtype, N):
     rng = np.random.default_rng(N + 2)
     x = _mixed_rows(rng, 12, N, dtype)
