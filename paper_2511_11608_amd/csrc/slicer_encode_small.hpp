@@ -68,7 +68,7 @@ constexpr int kCoarseBins = 1 << kCoarseBits;
 constexpr int kFineBins = 1024;
 
 // LDS carve-up of one wave (word offsets); small_lds_words() on the host must match.
-// The coarse histogram (2048 words) overlays everything: nothing else is live before the
+// The coarse histogram (2048 16-bit counters) overlays everything: nothing else is live before the
 // compaction.  Region 0 is the fine histogram first; once the boundaries are known it holds
 // the block-ordered indices, the stream image, the ABQ sums and the quantiser scales.
 // MAXS > 0: the list is copied into registers after the compaction, so the bin-ordered
@@ -101,12 +101,14 @@ __host__ __device__ inline int small_region0_words(int64_t k, u64 cap_words, int
     return (int)((r0 + 1) & ~(int64_t)1);
 }
 
-__host__ __device__ inline int small_lds_words(int dt, int cap, int region0, int B2, int maxs)
+// floor: words of the coarse histogram, which overlays the carve-up (16-bit counters in the one-wavefront
+// kernel: kCoarseBins / 2; 32-bit counters in the workgroup-per-row kernel: kCoarseBins)
+__host__ __device__ inline int small_lds_words(int dt, int cap, int region0, int B2, int maxs, int floor = kCoarseBins / 2)
 {
     int wds = region0 + cap + (maxs ? 0 : cap) + ((dt == 0 && !maxs) ? cap / 2 : 0);
     wds += 2 * B2 + small_tg_words(B2) + 16;
     wds += (B2 + 1) + B2 * 3;
-    if (wds < kCoarseBins) wds = kCoarseBins;
+    if (wds < floor) wds = floor;
     return wds;
 }
 
@@ -148,8 +150,16 @@ __device__ inline void lds_inc(u32 byte_off, u32 v)
 // gives the last key taken, and the list is built from that rule; the equal keys at the end are cut
 // in index order.  Both selections need the exact key of their rank, i.e. one key per histogram bin:
 // rows whose ranks lie below the 2048-key window are flagged for the generic kernel.
+// Wavefronts per SIMD the register allocator must leave room for.  The bf16 variants for rows of up to 4096
+// elements with a short ladder come out three registers above the limit of five wavefronts (96 VGPRs);
+// asking for five costs a handful of spill moves outside every loop.
+constexpr int small_min_waves(int dt, int epl, int nq, int maxs, bool asym)
+{
+    return (dt == 1 && epl <= 64 && nq == 7 && maxs == 10 && !asym) ? 5 : 1;
+}
+
 template <int DT, int EPL, int NQ, int MAXS, bool ASYM = false>
-__global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
+__global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(small_min_waves(DT, EPL, NQ, MAXS, ASYM)))) void enc_small_kernel(SmallArgs a)
 {
     typedef Elem<DT> E;
     typedef typename std::conditional<DT == 0, u64, u32>::type comp_t;   // bf16: key + index fit 31 bits
@@ -249,10 +259,12 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
         constexpr bool kSkip0 = decltype(skip0)::value;
         constexpr bool kWindowed = decltype(windowed)::value;
         constexpr int SHB = SH >= 2 ? SH - 2 : 0;      // fp32: shift that leaves the bin number times 4
+        // two 16-bit counters per word (a row has fewer than 2^16 elements): bin b is half b & 1 of word b >> 1
+        auto bin_inc = [](u32 b4) { lds_inc((b4 >> 1) & ~3u, 1u << ((b4 & 4u) << 2)); };
         {
             uint4* h4 = (uint4*)smem;
 #pragma unroll
-            for (int i = 0; i < kCoarseBins / 4 / kWave; ++i) h4[i * kWave + lane] = make_uint4(0, 0, 0, 0);
+            for (int i = 0; i < kCoarseBins / 8 / kWave; ++i) h4[i * kWave + lane] = make_uint4(0, 0, 0, 0);
         }
         wave_sync();
         const u32 wt2 = wtop * 0x10001u;
@@ -268,17 +280,17 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
                         const u32 b4 = SH >= 2 ? min((df >> SHB) & ~3u, (u32)(4 * kCoarseBins - 4))
                                                : (min(df >> SH, (u32)(kCoarseBins - 1)) << 2);
                         if (kWindowed) {
-                            if ((!kSkip0 || key) && key <= wtop && (df >> SH) < (u32)kCoarseBins) lds_inc(b4, 1u);
+                            if ((!kSkip0 || key) && key <= wtop && (df >> SH) < (u32)kCoarseBins) bin_inc(b4);
                         } else if (!kSkip0 || key) {
-                            lds_inc(b4, 1u);
+                            bin_inc(b4);
                         }
                     } else {
                         const u32 kp = key_pair(wd);
                         u32 b = pk_sub_sat_u16(wt2, kp);
                         if (SH) b = pk_shr_u16(b, SH);
                         b = pk_shl_u16(pk_min_u16(b, (u32)(kCoarseBins - 1) * 0x10001u), 2);
-                        if (!kSkip0 || (kp & 0xFFFFu)) lds_inc(b & 0xFFFFu, 1u);
-                        if (!kSkip0 || (kp >> 16)) lds_inc(b >> 16, 1u);
+                        if (!kSkip0 || (kp & 0xFFFFu)) bin_inc(b & 0xFFFFu);
+                        if (!kSkip0 || (kp >> 16)) bin_inc(b >> 16);
                     }
                 }
             }
@@ -288,20 +300,22 @@ __global__ __launch_bounds__(kWave) void enc_small_kernel(SmallArgs a)
         wave_sync();
         // Scan from the top in two levels: every lane sums 32 bins, the lane that holds the rank
         // is then opened bin by bin.
-        constexpr int BPL = kCoarseBins / kWave;       // 32
-        const uint4* h4 = (const uint4*)(smem + (int)lane * BPL);
-        u32 local = 0;
+        constexpr int BPL = kCoarseBins / kWave;       // 32 bins = 16 words
+        const uint4* h4 = (const uint4*)(smem + (int)lane * (BPL / 2));
+        u32 both = 0;                                  // the halves add up separately: no sum reaches 2^16
 #pragma unroll
-        for (int j = 0; j < BPL / 4; ++j) {
+        for (int j = 0; j < BPL / 8; ++j) {
             const uint4 t = h4[j];
-            local += (t.x + t.y) + (t.z + t.w);
+            both += (t.x + t.y) + (t.z + t.w);
         }
+        const u32 local = (both & 0xFFFFu) + (both >> 16);
         const u32 incl = wave_scan_dpp(local), excl = incl - local;
         const u32 rem = rank_t - above;
         const u64 m_src = __ballot(local > 0 && excl <= rem && rem < incl);
         const int src = m_src ? (int)__builtin_ctzll(m_src) : 0;
         const u32 ex_src = bcast(excl, src);
-        const u32 c2 = lane < (u32)BPL ? smem[src * BPL + (int)lane] : 0u;
+        const u32 w2 = lane < (u32)BPL ? smem[src * (BPL / 2) + (int)(lane >> 1)] : 0u;
+        const u32 c2 = (lane & 1u) ? w2 >> 16 : w2 & 0xFFFFu;
         const u32 inc2 = wave_scan_dpp(c2);            // lanes 0..31: running count inside lane `src`
         const u64 m_b1 = __ballot(lane < (u32)BPL && ex_src + inc2 > rem);
         found = m_src && m_b1;

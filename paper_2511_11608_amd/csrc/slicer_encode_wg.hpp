@@ -33,7 +33,7 @@ constexpr int kWgMisc = 64;            // broadcast words (0..15), per-wavefront
 // words of LDS: the one-wavefront layout (list in LDS) followed by the workgroup's own tables
 __host__ __device__ inline int wg_main_words(int dt, int cap, int region0, int B2)
 {
-    return small_lds_words(dt, cap, region0, B2, 0);
+    return small_lds_words(dt, cap, region0, B2, 0, kCoarseBins);
 }
 __host__ __device__ inline int wg_lds_words(int dt, int cap, int region0, int B2)
 {
