@@ -151,6 +151,9 @@ Plan make_plan(int dt, int64_t rows, int64_t row_len, double keep_ratio, int n_b
         int64_t cap = std::min<int64_t>(1984, (p.k + margin + 63) / 64 * 64);   // ranks are 11-bit fields
         int epl = epc;
         while ((int64_t)epl * kWave < row_len) epl *= 2;
+        // fp32 rows of the common transformer widths 768 and 1280: three and five chunks per lane instead of four and eight
+        if (dt == SLICER_F32 && row_len > 512 && row_len <= 768) epl = 12;
+        if (dt == SLICER_F32 && row_len > 1024 && row_len <= 1280) epl = 20;
         const int maxs = cap <= 640 ? 10 : cap <= 1280 ? 20 : 0;             // list held in registers
         const int64_t region0 = small_region0_words(p.k, p.cap_words, B2_all, nq);
         const int64_t lds = 4 * (int64_t)small_lds_words(dt, (int)cap, (int)region0, B2_all, maxs);
@@ -247,6 +250,14 @@ int launch_small(const SmallArgs& sa, const Plan& p, hipStream_t st, bool asym)
 {
     constexpr int E0 = DT == 0 ? 4 : 16;      // smallest instantiated elements-per-lane
     const int lds = p.small_lds_bytes;
+    if constexpr (DT == 0) {
+        if (p.small_epl == 12 || p.small_epl == 20) {
+            if (p.small_epl == 12) launch_small_epl<0, 12>(sa, lds, p.small_maxs, st, asym);
+            else launch_small_epl<0, 20>(sa, lds, p.small_maxs, st, asym);
+            hipError_t e = hipGetLastError();
+            return e == hipSuccess ? SLICER_OK : hip_fail(e);
+        }
+    }
     if (p.small_epl <= E0) launch_small_epl<DT, E0>(sa, lds, p.small_maxs, st, asym);
     else if (p.small_epl == E0 * 2) launch_small_epl<DT, E0 * 2>(sa, lds, p.small_maxs, st, asym);
     else if (p.small_epl == E0 * 4) launch_small_epl<DT, E0 * 4>(sa, lds, p.small_maxs, st, asym);

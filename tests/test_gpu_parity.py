@@ -129,8 +129,8 @@ def _mixed_rows(rng, rows, N, dtype):
     return synth.f32_to_bf16_bits(x) if dtype == "bf16" else x
 
 
-@pytest.mark.parametrize("dtype,N", [("bf16", 256), ("bf16", 4096), ("bf16", 8192), ("f32", 768), ("f32", 2048), ("f32", 4096),
-                                     ("f32", 8192), ("f32", 12288), ("bf16", 20480)])
+@pytest.mark.parametrize("dtype,N", [("bf16", 256), ("bf16", 4096), ("bf16", 8192), ("f32", 768), ("f32", 1280), ("f32", 2048),
+                                     ("f32", 4096), ("f32", 8192), ("f32", 12288), ("bf16", 20480)])
 def test_row_resident_variants(oracle, dtype, N):
     """Every variant of the one-wave-per-row and of the workgroup-per-row encoder (list in registers or
     LDS, short or long bitwidth ladders, up to 64 blocks, bf16 and fp32, 4 and 16 wavefronts per row) and
