@@ -526,6 +526,12 @@ static int encode_impl(const void* x, slicer_dtype dt, int64_t rows, int64_t row
     fa.mv = ea.mv;
     const u64 grid = (u64)xcd_grid((int64_t)(((u64)rows * (u64)fa.chunks_per_row + 3) / 4));     // four wavefronts per workgroup
     if (grid >= (1ull << 31)) return SLICER_EINVAL;
+    if (rows <= kScanRows) {        // small batches: repair, offsets, header and gather in one launch
+        if (dt == SLICER_F32) hipLaunchKernelGGL((enc_finish_small_kernel<0>), dim3((unsigned)grid), dim3(kScanRows), 0, st, ea, fa);
+        else hipLaunchKernelGGL((enc_finish_small_kernel<1>), dim3((unsigned)grid), dim3(kScanRows), 0, st, ea, fa);
+        hipError_t e1 = hipGetLastError();
+        return e1 == hipSuccess ? SLICER_OK : hip_fail(e1);
+    }
     const dim3 gscan((unsigned)((rows + kScanRows - 1) / kScanRows));
     if (!ea.only_flagged)
         hipLaunchKernelGGL(enc_rowscan_kernel, gscan, dim3(kScanRows), 0, st, fa);

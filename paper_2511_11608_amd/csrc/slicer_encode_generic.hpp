@@ -622,7 +622,7 @@ __global__ __launch_bounds__(BLOCK) void enc_generic_kernel(EncArgs a)
 }
 
 // ---- row offsets (exclusive scan of the row word counts), header, gather ------------------
-// Two launches: (1) every workgroup scans the word counts of 256 consecutive rows and
+// Batches of more than kScanRows rows take two launches: (1) every workgroup scans the word counts of 256 consecutive rows and
 // leaves the rows' offsets relative to its chunk plus the chunk total; (2) the gather
 // kernel adds the totals of the preceding chunks, writes the final offsets and the header
 // and copies each row's slot to its place in the contiguous stream.
@@ -687,6 +687,34 @@ __global__ __launch_bounds__(kScanRows) void enc_fix_rowscan_kernel(EncArgs ea, 
     rowscan_chunk(a);
 }
 
+// one lane writes the header of the meta block (format v1) and zeroes the padding after the last array
+__device__ inline void write_header(const FinishArgs& a, u64 total)
+{
+    u32* h32 = (u32*)a.meta;
+    u64* h64 = (u64*)a.meta;
+    h32[0] = kMagic; h32[1] = kVersion; h32[2] = (u32)a.dt; h32[3] = (u32)a.M;
+    h64[2] = (u64)a.R; h64[3] = (u64)a.N; h64[4] = (u64)a.k;
+    h32[10] = a.bit_set; h32[11] = (u32)a.w;
+    h64[6] = total;
+    h32[14] = a.Mn != a.M ? (u32)a.Mn : 0u;        // 0: the negative class has M blocks too
+    h32[15] = 0;
+    uint8_t* m8 = (uint8_t*)a.meta;
+    for (size_t o = kHeaderBytes + 16 * (size_t)a.R + 9 * (size_t)a.R * (a.M + a.Mn); o < meta_bytes(a.R, a.M + a.Mn); ++o) m8[o] = 0;
+}
+
+// one wavefront copies words [c * kGatherWords, (c + 1) * kGatherWords) of row r's slot to the stream
+__device__ inline void gather_item(const FinishArgs& a, int64_t r, u64 c, u64 off)
+{
+    const u32 lane = lane_id();
+    const u64 nw = a.row_words[r];
+    const u64 j0 = c * (u64)kGatherWords;
+    if (j0 >= nw) return;
+    const u64 j1 = j0 + (u64)kGatherWords < nw ? j0 + (u64)kGatherWords : nw;
+    const u32* __restrict__ src = a.slots + (size_t)r * a.cap_words;
+    u32* __restrict__ dst = a.stream + off;
+    for (u64 j = j0 + lane; j < j1; j += kWave) dst[j] = src[j];
+}
+
 __global__ __launch_bounds__(256) void enc_gather_kernel(FinishArgs a)
 {
     // one wavefront per (row, kGatherWords-word chunk of its slot); no workgroup barrier
@@ -712,25 +740,62 @@ __global__ __launch_bounds__(256) void enc_gather_kernel(FinishArgs a)
 
     const u64 off = before + a.row_off_local[r];
     if (c == 0 && lane == 0) a.mv.row_off[r] = off;
-    if (want_total && lane == 0) {
-        u32* h32 = (u32*)a.meta;
-        u64* h64 = (u64*)a.meta;
-        h32[0] = kMagic; h32[1] = kVersion; h32[2] = (u32)a.dt; h32[3] = (u32)a.M;
-        h64[2] = (u64)a.R; h64[3] = (u64)a.N; h64[4] = (u64)a.k;
-        h32[10] = a.bit_set; h32[11] = (u32)a.w;
-        h64[6] = total;
-        h32[14] = a.Mn != a.M ? (u32)a.Mn : 0u;        // 0: the negative class has M blocks too
-        h32[15] = 0;
-        uint8_t* m8 = (uint8_t*)a.meta;     // zero the padding after the last array
-        for (size_t o = kHeaderBytes + 16 * (size_t)a.R + 9 * (size_t)a.R * (a.M + a.Mn); o < meta_bytes(a.R, a.M + a.Mn); ++o) m8[o] = 0;
+    if (want_total && lane == 0) write_header(a, total);
+    gather_item(a, r, c, off);
+}
+
+// Batches of up to kScanRows rows (one decode step, one feature map, a batch of long rows): repair, row
+// offsets, header and gather in ONE launch.  Every workgroup scans the (at most 256) word counts itself and
+// copies its share of the slots.  If a fast path flagged any row, which is rare, workgroup 0 alone redoes
+// those rows with the generic encoder and then copies every row; the others leave at once.
+template <int DT>
+__global__ __launch_bounds__(kScanRows) void enc_finish_small_kernel(EncArgs ea, FinishArgs a)
+{
+    __shared__ u64 s_off[kScanRows + 1];
+    __shared__ u64 s_wave[kScanRows / kWave];
+    const int tid = threadIdx.x, wid = tid / kWave;
+    const u32 lane = lane_id();
+    bool alone = false;
+    if (ea.only_flagged) {
+        const int any = tid < a.R ? (int)ea.only_flagged[tid] : 0;
+        if (__syncthreads_or(any)) {
+            if (blockIdx.x != 0) return;             // the whole workgroup
+            enc_generic_rows<DT, kScanRows>(ea, 0, a.R);
+            __syncthreads();
+            alone = true;
+        }
     }
-    const u64 nw = a.row_words[r];
-    const u64 j0 = c * (u64)kGatherWords;
-    if (j0 >= nw) return;
-    const u64 j1 = j0 + (u64)kGatherWords < nw ? j0 + (u64)kGatherWords : nw;
-    const u32* __restrict__ src = a.slots + (size_t)r * a.cap_words;
-    u32* __restrict__ dst = a.stream + off;
-    for (u64 j = j0 + lane; j < j1; j += kWave) dst[j] = src[j];
+    {   // exclusive scan of the word counts
+        const u64 v = tid < a.R ? a.row_words[tid] : 0ull;
+        u64 inc = v;
+#pragma unroll
+        for (int d = 1; d < kWave; d <<= 1) {
+            const u64 t = __shfl_up(inc, d);
+            if (lane >= (u32)d) inc += t;
+        }
+        if (lane == kWave - 1) s_wave[wid] = inc;
+        __syncthreads();
+        u64 wbase = 0, tot = 0;
+        for (int v2 = 0; v2 < kScanRows / kWave; ++v2) {
+            const u64 sp = s_wave[v2];
+            if (v2 < wid) wbase += sp;
+            tot += sp;
+        }
+        s_off[tid] = wbase + inc - v;
+        if (tid == 0) s_off[kScanRows] = tot;
+        __syncthreads();
+    }
+    const int64_t n_items = a.R * a.chunks_per_row;
+    const int64_t first = alone ? wid : xcd_row((int64_t)blockIdx.x, (n_items + 3) / 4) * (kScanRows / kWave) + wid;
+    const int64_t step = alone ? kScanRows / kWave : n_items;      // (not alone: one item per wavefront)
+    for (int64_t item = first; item < n_items; item += step) {
+        const int64_t r = item / a.chunks_per_row;
+        const u64 c = (u64)(item % a.chunks_per_row);
+        const u64 off = s_off[r];
+        if (c == 0 && lane == 0) a.mv.row_off[r] = off;
+        if (item == 0 && lane == 0) write_header(a, s_off[kScanRows]);
+        gather_item(a, r, c, off);
+    }
 }
 
 }  // namespace slicer
