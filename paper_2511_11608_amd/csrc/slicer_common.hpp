@@ -199,6 +199,17 @@ __device__ inline u32 wave_scan_dpp(u32 v)
     return r;
 }
 
+// Inclusive prefix sum inside each row of 16 lanes: lane 15 of a row ends up with the row's total.
+__device__ inline u32 row_scan_dpp(u32 v)
+{
+    u32 r = v + dpp_get<0x111, 0xf, 0xf>(v);     // row_shr:1
+    r += dpp_get<0x112, 0xf, 0xf>(v);            // row_shr:2
+    r += dpp_get<0x113, 0xf, 0xf>(v);            // row_shr:3
+    r += dpp_get<0x114, 0xf, 0xe>(r);            // row_shr:4, lanes 4..15 of a row
+    r += dpp_get<0x118, 0xf, 0xc>(r);            // row_shr:8, lanes 8..15 of a row
+    return r;
+}
+
 // Sum over the 64 lanes, in every lane (data-parallel-primitive moves: no LDS crossbar traffic).
 __device__ inline u32 wave_sum(u32 v) { return bcast(wave_scan_dpp(v), kWave - 1); }
 

@@ -583,7 +583,10 @@ __global__ __launch_bounds__(NW * kWave) void enc_wg_kernel(SmallArgs a)
     u64* sums = (u64*)(L.hist + ((((k + 1) / 2 + (int)a.cap_words) + 1) & ~1));
     float* invt = (float*)(sums + B2 * (nq + 1));
     const u32 lpb = (u32)kWgThreads / (u32)B2;
-    const bool wave_one_block = lpb % (u32)kWave == 0u;          // every wavefront then lies inside one block's threads
+    // every row of 16 lanes then lies inside one block's threads: the lanes' sums are added up across the row
+    // first (16 lanes meeting on one LDS address cost more than the whole loop), and lane 15 adds to the table
+    const bool row_one_block = lpb % 16u == 0u;
+    const bool row_last = (lane & 15u) == 15u;
     const u32 myb = udiv16(tid, lpb), sub = tid - myb * lpb;
     const bool on = myb < (u32)B2;
     u32 r0 = 0, r1 = 0, bs0 = 0, mycnt = 0;
@@ -655,9 +658,9 @@ __global__ __launch_bounds__(NW * kWave) void enc_wg_kernel(SmallArgs a)
 #pragma unroll
             for (int t = 0; t < QN; ++t) {
                 if ((NQ || t < nq) && t < top) {
-                    if (wave_one_block) {                            // 64 lane sums below 2^19 fit 32 bits
-                        const u32 tot = bcast(wave_scan_dpp(acc[t]), kWave - 1);
-                        if (lane == 0 && tot) atomicAdd(&sums[myb * (nq + 1) + t], (u64)tot);
+                    if (row_one_block) {                             // 16 lane sums below 2^19 fit 32 bits
+                        const u32 tot = row_scan_dpp(acc[t]);
+                        if (row_last && tot) atomicAdd(&sums[myb * (nq + 1) + t], (u64)tot);
                     } else if (acc[t]) {
                         atomicAdd(&sums[myb * (nq + 1) + t], (u64)acc[t]);
                     }
@@ -694,15 +697,14 @@ __global__ __launch_bounds__(NW * kWave) void enc_wg_kernel(SmallArgs a)
                     }
                 }
             }
-            if (wave_one_block) {
-                // the 64 lanes of this wavefront work on one block: add up across the wavefront first
-                // (16-bit pieces, so that the lane sums fit 32 bits), then one lane adds to the table
+            if (row_one_block) {
+                // 16-bit pieces, so that the sums over a row fit 32 bits
 #pragma unroll
                 for (int t = 0; t < QN; ++t) {
                     if (NQ || t < nq) {
-                        const u32 lo16 = bcast(wave_scan_dpp(acc[t] & 0xFFFFu), kWave - 1);
-                        const u32 hi16 = bcast(wave_scan_dpp(acc[t] >> 16), kWave - 1);
-                        if (lane == 0 && (lo16 | hi16)) atomicAdd(&sums[myb * (nq + 1) + t], (u64)lo16 + ((u64)hi16 << 16));
+                        const u32 lo16 = row_scan_dpp(acc[t] & 0xFFFFu);
+                        const u32 hi16 = row_scan_dpp(acc[t] >> 16);
+                        if (row_last && (lo16 | hi16)) atomicAdd(&sums[myb * (nq + 1) + t], (u64)lo16 + ((u64)hi16 << 16));
                     }
                 }
             } else {
@@ -711,11 +713,11 @@ __global__ __launch_bounds__(NW * kWave) void enc_wg_kernel(SmallArgs a)
                     if ((NQ || t < nq) && acc[t]) atomicAdd(&sums[myb * (nq + 1) + t], (u64)acc[t]);
             }
         }
-        if (wave_one_block) {
-            const u32 e0 = bcast(wave_scan_dpp((u32)accE & 0x3FFFFFu), kWave - 1);
-            const u32 e1 = bcast(wave_scan_dpp((u32)(accE >> 22) & 0x3FFFFFu), kWave - 1);
-            const u32 e2 = bcast(wave_scan_dpp((u32)(accE >> 44)), kWave - 1);
-            if (lane == 0 && (e0 | e1 | e2)) atomicAdd(&sums[myb * (nq + 1) + nq], (u64)e0 + ((u64)e1 << 22) + ((u64)e2 << 44));
+        if (row_one_block) {
+            const u32 e0 = row_scan_dpp((u32)accE & 0x3FFFFFu);
+            const u32 e1 = row_scan_dpp((u32)(accE >> 22) & 0x3FFFFFu);
+            const u32 e2 = row_scan_dpp((u32)(accE >> 44));
+            if (row_last && (e0 | e1 | e2)) atomicAdd(&sums[myb * (nq + 1) + nq], (u64)e0 + ((u64)e1 << 22) + ((u64)e2 << 44));
         } else if (accE) {
             atomicAdd(&sums[myb * (nq + 1) + nq], accE);
         }
