@@ -247,10 +247,9 @@ int slicer_bound(slicer_dtype dt, int64_t rows, int64_t row_len, double keep_rat
 /*
  * Which kernel family slicer_encode uses for a shape (for benchmarks and profiles, which
  * name the dominant kernel): 0 = generic (one workgroup per row, any shape), 1 = row-resident
- * (one wavefront per row, rows up to 8192 bf16 / 4096 fp32 elements), 2 = long-row stages
- * (rows of more than 4096 elements that the row-resident kernel does not take), 3 = one workgroup per row
- * (rows of 4097..32768 bf16 / 4097..16384 fp32 elements: all of them beyond one wavefront's reach, bf16 rows
- * of up to 8192 elements in batches of up to 1024 rows).
+ * (one wavefront per row, rows up to 4096 elements), 2 = long-row stages
+ * (rows of more than 4096 elements that the other two do not take), 3 = one workgroup per row
+ * (rows of 4097..32768 bf16 / 4097..16384 fp32 elements).
  * Assumes a 16-byte aligned x and the budget guard.  Negative: error code.
  */
 int slicer_encode_path(slicer_dtype dt, int64_t rows, int64_t row_len, double keep_ratio,

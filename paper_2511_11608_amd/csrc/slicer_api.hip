@@ -162,13 +162,14 @@ Plan make_plan(int dt, int64_t rows, int64_t row_len, double keep_ratio, int n_b
             p.small_maxs = maxs;
         }
     }
-    // One workgroup per row (the wavefronts of a workgroup share the row): rows too long for one wavefront
-    // (up to 32768 bf16 / 16384 fp32 elements), and bf16 rows of more than 4096 elements in batches too small
-    // to fill the chip with one wavefront each.
+    // One workgroup per row (the wavefronts of a workgroup share the row): every row of more than 4096 and up to
+    // 32768 bf16 / 16384 fp32 elements.  For bf16 rows of 4097..8192 elements, which one wavefront could hold,
+    // it is the faster kernel at every batch size (16384 rows of 8192: 238 against 293 us; 4096 rows of 6144:
+    // 68 against 74 us); at 4096 elements and below one wavefront per row wins (115 against 189 us).
     p.wg_ept = 0; p.wg_nw = 0; p.wg_cap = 0; p.wg_region0 = 0; p.wg_lds_bytes = 0;
     {
         const int64_t wg_max = dt == SLICER_F32 ? 16384 : 32768;
-        if (row_len % epc == 0 && row_len > 4096 && row_len <= wg_max && B2_all <= kWave && (row_len > max_n || rows <= 1024)) {
+        if (row_len % epc == 0 && row_len > 4096 && row_len <= wg_max && B2_all <= kWave) {
             const int64_t margin = std::max<int64_t>(64, row_len / (dt == SLICER_F32 ? 16 : 32));
             const int64_t cap = std::min<int64_t>(1984, (p.k + margin + 63) / 64 * 64);
             const int64_t region0 = small_region0_words(p.k, p.cap_words, B2_all, nq);

@@ -1,8 +1,9 @@
-// Row-resident encoder for rows of 4 K to 32 K bf16 (16 K fp32) elements and small batches: ONE WORKGROUP
-// (4, 8 or 16 wavefronts) PER ROW.  A single wavefront needs about 30 us for an 8192-element row,
-// nearly all of it dependent-instruction and LDS latency, and a batch of a few hundred rows
-// (one auto-regressive decode step of Sec. 2.1, one hidden state per client) leaves three
-// quarters of the SIMDs idle; here the wavefronts of a workgroup share the row (four when the batch
+// Row-resident encoder for rows of 4 K to 32 K bf16 (16 K fp32) elements: ONE WORKGROUP (4 or 16
+// wavefronts) PER ROW.  A single wavefront needs about 30 us for an 8192-element row,
+// nearly all of it dependent-instruction and LDS latency, and holds so much of the row per lane that
+// only two or three wavefronts fit a SIMD; a batch of a few hundred rows
+// (one auto-regressive decode step of Sec. 2.1, one hidden state per client) also leaves three
+// quarters of the SIMDs idle.  Here the wavefronts of a workgroup share the row (four when the batch
 // fills the chip anyway, sixteen for the smallest batches: more wavefronts per SIMD hide each other's
 // latencies).
 //

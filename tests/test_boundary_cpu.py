@@ -72,7 +72,7 @@ def test_encode_path_by_shape(lib):
     B = synth.BITS_2_TO_8
     assert binding.slicer_encode_path(binding.SLICER_BF16, 16384, 4096, 0.10, 8, B) == 1     # LLM prefill
     assert binding.slicer_encode_path(binding.SLICER_BF16, 256, 8192, 0.10, 8, B) == 3       # AR decode step: one workgroup per row
-    assert binding.slicer_encode_path(binding.SLICER_BF16, 16384, 8192, 0.10, 8, B) == 1     # the same rows in a large batch: one wavefront per row
+    assert binding.slicer_encode_path(binding.SLICER_BF16, 16384, 8192, 0.10, 8, B) == 3     # the same rows in a large batch
     assert binding.slicer_encode_path(binding.SLICER_BF16, 300, 12288, 0.10, 8, B) == 3      # beyond one wavefront's row length
     assert binding.slicer_encode_path(binding.SLICER_F32, 12608, 768, 0.15, 8, B) == 1       # ViT tokens
     assert binding.slicer_encode_path(binding.SLICER_F32, 32, 401408, 0.20, 16, B) == 2      # ResNet stage 3

@@ -62,6 +62,7 @@ CASES = {
     "llm_wide": lambda: synth.llm_prefill(seed=2, rows=300, width=12288),            # between the row-resident and the long-row home ranges
     "vit_wide": lambda: synth.vit_tokens(seed=2, rows=200, width=8192),
     "vit_4096": lambda: synth.vit_tokens(seed=3, rows=200, width=4096),              # widest fp32 row of the row-resident kernel
+    "llm_8192_batch": lambda: synth.llm_prefill(seed=4, rows=1500, width=8192),      # one workgroup per row in a batch that fills the chip
 }
 
 
