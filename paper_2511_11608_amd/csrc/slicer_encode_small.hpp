@@ -150,12 +150,14 @@ __device__ inline void lds_inc(u32 byte_off, u32 v)
 // gives the last key taken, and the list is built from that rule; the equal keys at the end are cut
 // in index order.  Both selections need the exact key of their rank, i.e. one key per histogram bin:
 // rows whose ranks lie below the 2048-key window are flagged for the generic kernel.
-// Wavefronts per SIMD the register allocator must leave room for.  The bf16 variants for rows of up to 4096
-// elements with a short ladder come out three registers above the limit of five wavefronts (96 VGPRs);
-// asking for five costs a handful of spill moves outside every loop.
+// Wavefronts per SIMD the register allocator must leave room for.  The variants that hold the row in at most
+// 32 registers come out at 84 to 101 VGPRs, a few of them just above the limit of five wavefronts (96 VGPRs):
+// asking for five costs those a handful of spill moves outside every loop.  fp32 rows of 4096 elements (64
+// registers for the row, 166 to 181 in all) are asked for three wavefronts (168) instead of two.
 constexpr int small_min_waves(int dt, int epl, int nq, int maxs, bool asym)
 {
-    return (dt == 1 && epl <= 64 && nq == 7 && maxs == 10 && !asym) ? 5 : 1;
+    const int row_regs = dt == 0 ? epl : epl / 2;
+    return row_regs <= 32 ? 5 : (dt == 0 && row_regs == 64) ? 3 : 1;
 }
 
 template <int DT, int EPL, int NQ, int MAXS, bool ASYM = false>
