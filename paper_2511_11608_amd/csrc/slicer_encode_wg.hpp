@@ -42,8 +42,17 @@ __host__ __device__ inline int wg_lds_words(int dt, int cap, int region0, int B2
     return wg_main_words(dt, cap, region0, B2) + kWgMisc + 128 + ((cap / kWave) * B2 + 1) / 2 + 2;
 }
 
+// wavefronts per SIMD the register allocator must leave room for (same rule as the one-wavefront kernel)
+constexpr int wg_min_waves(int dt, int nw, int ept)
+{
+    const int row_regs = dt == 0 ? ept : ept / 2;
+    const int per_wg = (nw + 3) / 4;                  // wavefronts of one workgroup on a SIMD
+    const int want = row_regs <= 32 ? 5 : row_regs == 64 ? 3 : 1;
+    return want > per_wg ? want : per_wg;
+}
+
 template <int DT, int NW, int EPT, int NQ>
-__global__ __launch_bounds__(NW * kWave) void enc_wg_kernel(SmallArgs a)
+__global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(wg_min_waves(DT, NW, EPT)))) void enc_wg_kernel(SmallArgs a)
 {
     typedef Elem<DT> E;
     constexpr int kWgThreads = NW * kWave, kWgWaves = NW;
